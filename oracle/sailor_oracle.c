@@ -1,0 +1,534 @@
+/*
+ * CPU oracle -- TEST INFRASTRUCTURE ONLY (see sailor_oracle.h).
+ *
+ * Every candidate is evaluated from scratch, stage by stage, in the natural order of
+ * the definitions: no tables of derived values, no blocking, no reordering.
+ * Floating point is fp64, byte counts are exact unsigned 64-bit integers.
+ */
+#include "sailor_oracle.h"
+
+#include <math.h>
+#include <pthread.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define SO_MAX_STAGES 512
+#define SO_MAX_POOLS 256
+#define SO_TIE_TOL 1e-5
+
+struct so_ctx {
+  so_problem p;
+  int32_t ZG;
+  uint64_t inner;          /* n_mb * n_tp * n_dp * ZG : candidates per (shape, outer pools) */
+  uint64_t *block_off;     /* [n_pp][3] : first index of block (pp_idx, s)                  */
+  uint64_t *block_size;    /* [n_pp][3]                                                     */
+  uint64_t *part_row;      /* [n_pp] : offset of the first partition row of pp_idx          */
+  uint64_t n_candidates;
+};
+
+/* ---- candidate space (plan tuple of Sec. 4.2, restricted to contiguous segments) ------ */
+
+static uint64_t n_cuts(int P, int s) {
+  if (s == 1) return 1;
+  if (s == 2) return (uint64_t)(P - 1);
+  return (uint64_t)(P - 1) * (uint64_t)(P - 2) / 2;
+}
+
+static int segments_allowed(const so_problem *p, int P, int s) {
+  if (s > p->max_segments) return 0;
+  if (s > P) return 0;
+  if (s == 3 && P > p->seg3_max_pp) return 0;
+  return 1;
+}
+
+so_ctx *so_create(const so_problem *p) {
+  if (!p || p->n_layers < 1 || p->n_types < 1 || p->n_zones < 1) return NULL;
+  if (p->n_types * p->n_zones > SO_MAX_POOLS) return NULL;
+  so_ctx *c = (so_ctx *)calloc(1, sizeof(so_ctx));
+  if (!c) return NULL;
+  c->p = *p;
+  c->ZG = p->n_zones * p->n_types;
+  c->inner = (uint64_t)p->n_mb * p->n_tp * p->n_dp * c->ZG;
+  c->block_off = (uint64_t *)calloc((size_t)p->n_pp * 3, sizeof(uint64_t));
+  c->block_size = (uint64_t *)calloc((size_t)p->n_pp * 3, sizeof(uint64_t));
+  c->part_row = (uint64_t *)calloc((size_t)p->n_pp, sizeof(uint64_t));
+  uint64_t off = 0, row = 0;
+  for (int ip = 0; ip < p->n_pp; ++ip) {
+    int P = p->pp_values[ip];
+    if (P < 1 || P > p->n_layers || P > SO_MAX_STAGES) { so_destroy(c); return NULL; }
+    c->part_row[ip] = row;
+    row += (uint64_t)p->n_partitions[ip] * P;
+    for (int s = 1; s <= 3; ++s) {
+      uint64_t size = 0;
+      if (segments_allowed(p, P, s)) {
+        size = c->inner * n_cuts(P, s) * (uint64_t)p->n_partitions[ip];
+        for (int j = 1; j < s; ++j) size *= (uint64_t)(c->ZG - 1);
+      }
+      c->block_off[ip * 3 + (s - 1)] = off;
+      c->block_size[ip * 3 + (s - 1)] = size;
+      off += size;
+    }
+  }
+  c->n_candidates = off;
+  return c;
+}
+
+void so_destroy(so_ctx *c) {
+  if (!c) return;
+  free(c->block_off);
+  free(c->block_size);
+  free(c->part_row);
+  free(c);
+}
+
+uint64_t so_num_candidates(const so_ctx *c) { return c->n_candidates; }
+
+static void fill_values(const so_ctx *c, so_config *g) {
+  g->pp = c->p.pp_values[g->pp_idx];
+  g->dp = c->p.dp_values[g->dp_idx];
+  g->tp = c->p.tp_values[g->tp_idx];
+  g->mb = c->p.mb_values[g->mb_idx];
+}
+
+/* index -> plan.  Digits, least significant first: mb, tp, dp, pool of segment 1,
+ * [relative pool of segment 2], [relative pool of segment 3], [cut], partition. */
+int so_decode(const so_ctx *c, uint64_t index, so_config *out) {
+  const so_problem *p = &c->p;
+  if (index >= c->n_candidates) return -1;
+  int ip = 0, s = 1;
+  for (int b = 0; b < p->n_pp * 3; ++b) {
+    if (c->block_size[b] > 0 && index >= c->block_off[b] &&
+        index < c->block_off[b] + c->block_size[b]) {
+      ip = b / 3;
+      s = b % 3 + 1;
+    }
+  }
+  uint64_t r = index - c->block_off[ip * 3 + (s - 1)];
+  so_config g;
+  memset(&g, 0, sizeof g);
+  g.pp_idx = ip;
+  g.n_segments = s;
+  int P = p->pp_values[ip];
+  g.mb_idx = (int32_t)(r % p->n_mb); r /= p->n_mb;
+  g.tp_idx = (int32_t)(r % p->n_tp); r /= p->n_tp;
+  g.dp_idx = (int32_t)(r % p->n_dp); r /= p->n_dp;
+  g.pool[0] = (int32_t)(r % c->ZG); r /= c->ZG;
+  g.pool[1] = g.pool[2] = -1;
+  g.cut[0] = g.cut[1] = P;
+  if (s >= 2) {
+    int rel = (int)(r % (c->ZG - 1)); r /= (c->ZG - 1);
+    g.pool[1] = (g.pool[0] + 1 + rel) % c->ZG;
+  }
+  if (s == 3) {
+    int rel = (int)(r % (c->ZG - 1)); r /= (c->ZG - 1);
+    g.pool[2] = (g.pool[1] + 1 + rel) % c->ZG;
+  }
+  if (s == 2) {
+    g.cut[0] = (int32_t)(r % (P - 1)) + 1; r /= (P - 1);
+  } else if (s == 3) {
+    uint64_t nc = n_cuts(P, 3);
+    uint64_t ci = r % nc; r /= nc;
+    /* pairs 1 <= k1 < k2 <= P-1 in lexicographic order */
+    uint64_t seen = 0;
+    for (int k1 = 1; k1 <= P - 2; ++k1)
+      for (int k2 = k1 + 1; k2 <= P - 1; ++k2) {
+        if (seen == ci) { g.cut[0] = k1; g.cut[1] = k2; }
+        ++seen;
+      }
+  }
+  g.partition = (int32_t)r;
+  fill_values(c, &g);
+  *out = g;
+  return 0;
+}
+
+int so_encode(const so_ctx *c, const so_config *g, uint64_t *out) {
+  const so_problem *p = &c->p;
+  int ip = g->pp_idx, s = g->n_segments;
+  if (ip < 0 || ip >= p->n_pp || s < 1 || s > 3) return -1;
+  int P = p->pp_values[ip];
+  if (c->block_size[ip * 3 + (s - 1)] == 0) return -1;
+  uint64_t r = (uint64_t)g->partition;
+  if (s == 2) {
+    r = r * (P - 1) + (uint64_t)(g->cut[0] - 1);
+  } else if (s == 3) {
+    uint64_t ci = 0, seen = 0;
+    for (int k1 = 1; k1 <= P - 2; ++k1)
+      for (int k2 = k1 + 1; k2 <= P - 1; ++k2) {
+        if (k1 == g->cut[0] && k2 == g->cut[1]) ci = seen;
+        ++seen;
+      }
+    r = r * n_cuts(P, 3) + ci;
+  }
+  if (s == 3) {
+    int rel = ((g->pool[2] - g->pool[1] - 1) % c->ZG + c->ZG) % c->ZG;
+    r = r * (c->ZG - 1) + (uint64_t)rel;
+  }
+  if (s >= 2) {
+    int rel = ((g->pool[1] - g->pool[0] - 1) % c->ZG + c->ZG) % c->ZG;
+    r = r * (c->ZG - 1) + (uint64_t)rel;
+  }
+  r = r * c->ZG + (uint64_t)g->pool[0];
+  r = r * p->n_dp + (uint64_t)g->dp_idx;
+  r = r * p->n_tp + (uint64_t)g->tp_idx;
+  r = r * p->n_mb + (uint64_t)g->mb_idx;
+  *out = c->block_off[ip * 3 + (s - 1)] + r;
+  return 0;
+}
+
+/* The same space as a loop nest (independent of so_decode): pp, then segment count,
+ * then partition, cut, pools from the last segment inwards, dp, tp, mb innermost. */
+uint64_t so_enumerate(const so_ctx *c, so_config *out, uint64_t max_out) {
+  const so_problem *p = &c->p;
+  uint64_t n = 0;
+  int ZG = c->ZG;
+  for (int ip = 0; ip < p->n_pp; ++ip) {
+    int P = p->pp_values[ip];
+    for (int s = 1; s <= 3; ++s) {
+      if (!segments_allowed(p, P, s)) continue;
+      for (int q = 0; q < p->n_partitions[ip]; ++q)
+        for (int k1 = (s >= 2 ? 1 : P); k1 <= (s >= 2 ? P - (s - 1) : P); ++k1)
+          for (int k2 = (s == 3 ? k1 + 1 : P); k2 <= (s == 3 ? P - 1 : P); ++k2)
+            for (int r3 = 0; r3 < (s == 3 ? ZG - 1 : 1); ++r3)
+              for (int r2 = 0; r2 < (s >= 2 ? ZG - 1 : 1); ++r2)
+                for (int a1 = 0; a1 < ZG; ++a1)
+                  for (int id = 0; id < p->n_dp; ++id)
+                    for (int it = 0; it < p->n_tp; ++it)
+                      for (int im = 0; im < p->n_mb; ++im) {
+                        if (n < max_out) {
+                          so_config g;
+                          memset(&g, 0, sizeof g);
+                          g.pp_idx = ip; g.n_segments = s; g.partition = q;
+                          g.cut[0] = k1; g.cut[1] = k2;
+                          g.pool[0] = a1;
+                          g.pool[1] = s >= 2 ? (a1 + 1 + r2) % ZG : -1;
+                          g.pool[2] = s == 3 ? (g.pool[1] + 1 + r3) % ZG : -1;
+                          g.dp_idx = id; g.tp_idx = it; g.mb_idx = im;
+                          fill_values(c, &g);
+                          out[n] = g;
+                        }
+                        ++n;
+                      }
+    }
+  }
+  return n;
+}
+
+/* ---- simulator for one plan (Sec. 4.3) ------------------------------------------------- */
+
+static const int32_t *partition_row(const so_ctx *c, const so_config *g) {
+  return c->p.partition_layers + c->part_row[g->pp_idx] + (uint64_t)g->partition * g->pp;
+}
+
+static double layer_time_sum(const so_problem *p, const double *tab, int g, int im, int it,
+                             int first_layer, int n) {
+  /* tab is [G][n_mb][n_tp][Lc] */
+  if (p->uniform_layers)
+    return (double)n * tab[(((size_t)g * p->n_mb + im) * p->n_tp + it)];
+  const double *row = tab + (((size_t)g * p->n_mb + im) * p->n_tp + it) * p->n_layers;
+  double s = 0.0;
+  for (int l = first_layer; l < first_layer + n; ++l) s += row[l];
+  return s;
+}
+
+static double upd_time_sum(const so_problem *p, int g, int it, int first_layer, int n) {
+  /* t_upd is [G][n_tp][Lc] */
+  if (p->uniform_layers) return (double)n * p->t_upd[(size_t)g * p->n_tp + it];
+  const double *row = p->t_upd + ((size_t)g * p->n_tp + it) * p->n_layers;
+  double s = 0.0;
+  for (int l = first_layer; l < first_layer + n; ++l) s += row[l];
+  return s;
+}
+
+static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int objective,
+                        int has_bound, double bound, so_eval *out) {
+  const so_problem *p = &c->p;
+  const int P = g->pp, G = p->n_types, Z = p->n_zones;
+  const int64_t D = g->dp, tp = g->tp, mb = g->mb;
+  const int32_t *nl = partition_row(c, g);
+  out->index = index;
+  out->mask = 0;
+  out->peak_mem = 0;
+
+  /* microbatches per pipeline: the global batch is never changed (Sec. 4.2) */
+  if (p->global_batch % (D * mb) != 0) {
+    out->mask = SO_BIT_BATCH;
+    out->iter_time = INFINITY;
+    out->cost = INFINITY;
+    return;
+  }
+  const int64_t Nb = p->global_batch / (D * mb);
+
+  int type_of[SO_MAX_STAGES], zone_of[SO_MAX_STAGES], first_layer[SO_MAX_STAGES];
+  int stages_on_pool[SO_MAX_POOLS];
+  memset(stages_on_pool, 0, sizeof stages_on_pool);
+  int layer = 0;
+  for (int i = 0; i < P; ++i) {
+    int seg = (i < g->cut[0]) ? 0 : (i < g->cut[1]) ? 1 : 2;
+    int pool = g->pool[seg];
+    type_of[i] = pool % G;
+    zone_of[i] = pool / G;
+    stages_on_pool[pool] += 1;
+    first_layer[i] = layer;
+    layer += nl[i];
+  }
+
+  /* H1: a tensor-parallel group stays inside one node (Sec. 4.2.1) */
+  for (int i = 0; i < P; ++i)
+    if (tp > p->gpus_per_node[type_of[i]]) out->mask |= SO_BIT_TP_NODE;
+
+  /* quota: D replicas of every stage, tp GPUs each, from the stage's (zone, type) pool */
+  for (int a = 0; a < Z * G; ++a)
+    if ((int64_t)stages_on_pool[a] * D * tp > (int64_t)p->avail[a]) out->mask |= SO_BIT_QUOTA;
+
+  /* memory per worker of each stage: M_model + M_activation (+ reserved), Sec. 4.3 */
+  uint64_t params_of[SO_MAX_STAGES];
+  uint64_t peak = 0;
+  for (int i = 0; i < P; ++i) {
+    uint64_t params = 0;
+    for (int l = first_layer[i]; l < first_layer[i] + nl[i]; ++l) params += p->layer_params[l];
+    if (i == 0) params += p->embed_params;
+    if (i == P - 1) params += p->head_params;
+    uint64_t shard = (params + (uint64_t)tp - 1) / (uint64_t)tp;
+    params_of[i] = shard;
+    uint64_t m_model = shard * (uint64_t)p->bytes_per_param;
+    int64_t inflight = (P - i) < Nb ? (P - i) : Nb; /* 1F1B: microbatches kept alive */
+    uint64_t m_act = (uint64_t)inflight * (uint64_t)nl[i] *
+                     p->act_store_bytes[(size_t)g->mb_idx * p->n_tp + g->tp_idx];
+    uint64_t m = m_model + m_act + p->mem_reserved[type_of[i]];
+    if (m > p->mem_capacity[type_of[i]]) out->mask |= SO_BIT_OOM;
+    if (m > peak) peak = m;
+  }
+  out->peak_mem = peak;
+
+  /* stage times: compute plus activation / gradient transfers to the neighbours */
+  const double p2p = (double)p->p2p_bytes[g->mb_idx];
+  double sum_t = 0.0, max_t = 0.0, t_sync = 0.0, t_upd = 0.0;
+  for (int i = 0; i < P; ++i) {
+    int gt = type_of[i], z = zone_of[i];
+    double f = layer_time_sum(p, p->t_fwd, gt, g->mb_idx, g->tp_idx, first_layer[i], nl[i]);
+    double b = layer_time_sum(p, p->t_bwd, gt, g->mb_idx, g->tp_idx, first_layer[i], nl[i]);
+    double x = 0.0;
+    if (i < P - 1) x += p2p / p->bandwidth[(size_t)z * Z + zone_of[i + 1]];
+    if (i > 0) x += p2p / p->bandwidth[(size_t)z * Z + zone_of[i - 1]];
+    double t = f + b + x;
+    sum_t += t;
+    if (t > max_t) max_t = t;
+    /* gradient all-reduce of the stage's D replicas inside their zone: ring */
+    double sync = 0.0;
+    if (D > 1)
+      sync = 2.0 * (double)(D - 1) / (double)D *
+             ((double)params_of[i] * (double)p->grad_bytes_per_param) /
+             p->bandwidth[(size_t)z * Z + z];
+    if (sync > t_sync) t_sync = sync;
+    double u = upd_time_sum(p, gt, g->tp_idx, first_layer[i], nl[i]);
+    if (u > t_upd) t_upd = u;
+  }
+  /* 1F1B: warm-up + cool-down pass every stage once, the steady phase repeats the
+   * straggler for the remaining microbatches */
+  const double t_pp = sum_t + (double)(Nb - 1) * max_t;
+  const double t_iter = t_pp + t_sync + t_upd;
+  out->iter_time = t_iter;
+
+  /* cost per iteration: rented GPUs for T_iter plus cross-zone traffic */
+  double gpu_dollars_per_hour = 0.0, c_comm = 0.0;
+  for (int i = 0; i < P; ++i)
+    gpu_dollars_per_hour += (double)(D * tp) * p->price_per_hour[type_of[i]];
+  if (p->egress_per_byte)
+    for (int i = 0; i + 1 < P; ++i) {
+      int z = zone_of[i], zn = zone_of[i + 1];
+      if (z != zn)
+        c_comm += (double)Nb * (double)D * p2p *
+                  (p->egress_per_byte[(size_t)z * Z + zn] + p->egress_per_byte[(size_t)zn * Z + z]);
+    }
+  out->cost = gpu_dollars_per_hour / 3600.0 * t_iter + c_comm;
+
+  if (has_bound) {
+    if (objective == SO_MAX_THROUGHPUT) {
+      if (out->cost > bound) out->mask |= SO_BIT_CONSTRAINT;
+    } else {
+      if (1.0 / t_iter < bound) out->mask |= SO_BIT_CONSTRAINT;
+    }
+  }
+}
+
+int so_eval_one(const so_ctx *c, uint64_t index, int objective, int has_bound, double bound,
+                so_eval *out) {
+  so_config g;
+  if (so_decode(c, index, &g) != 0) return -1;
+  eval_config(c, &g, index, objective, has_bound, bound, out);
+  return 0;
+}
+
+static double key_of(const so_eval *e, int objective) {
+  return objective == SO_MAX_THROUGHPUT ? e->iter_time : e->cost;
+}
+
+/* ---- plain thread sharding by contiguous index range ---------------------------------- */
+
+typedef struct {
+  const so_ctx *c;
+  uint64_t first, count;
+  const uint64_t *indices;
+  int objective, has_bound, k, mode; /* mode 0 batch, 1 min key, 2 first within tol, 3 top-k */
+  double bound, limit;
+  double *time, *cost;
+  uint64_t *mem;
+  uint32_t *mask;
+  /* results */
+  int found;
+  so_eval best;
+  so_eval *top;
+  int n_top;
+} so_job;
+
+static int lex_less(double ka, uint64_t ia, double kb, uint64_t ib) {
+  return ka < kb || (ka == kb && ia < ib);
+}
+
+static void *run_job(void *arg) {
+  so_job *j = (so_job *)arg;
+  j->found = 0;
+  j->n_top = 0;
+  for (uint64_t n = 0; n < j->count; ++n) {
+    uint64_t idx = j->indices ? j->indices[j->first + n] : j->first + n;
+    so_eval e;
+    if (so_eval_one(j->c, idx, j->objective, j->has_bound, j->bound, &e) != 0) continue;
+    if (j->mode == 0) {
+      uint64_t o = j->first + n;
+      if (j->time) j->time[o] = e.iter_time;
+      if (j->cost) j->cost[o] = e.cost;
+      if (j->mem) j->mem[o] = e.peak_mem;
+      if (j->mask) j->mask[o] = e.mask;
+      continue;
+    }
+    if (e.mask != 0) continue;
+    double key = key_of(&e, j->objective);
+    if (j->mode == 1) {
+      if (!j->found || key < key_of(&j->best, j->objective)) { j->best = e; j->found = 1; }
+    } else if (j->mode == 2) {
+      if (key <= j->limit) { j->best = e; j->found = 1; break; } /* lowest index in range */
+    } else {
+      /* insertion into the sorted list of the k best so far */
+      int pos = j->n_top;
+      while (pos > 0 && lex_less(key, e.index, key_of(&j->top[pos - 1], j->objective),
+                                 j->top[pos - 1].index))
+        --pos;
+      if (pos < j->k) {
+        int last = j->n_top < j->k ? j->n_top : j->k - 1;
+        for (int m = last; m > pos; --m) j->top[m] = j->top[m - 1];
+        j->top[pos] = e;
+        if (j->n_top < j->k) j->n_top += 1;
+      }
+    }
+  }
+  return NULL;
+}
+
+static void run_sharded(so_job *proto, int n_threads, so_job *jobs) {
+  if (n_threads < 1) n_threads = 1;
+  pthread_t th[256];
+  if (n_threads > 256) n_threads = 256;
+  uint64_t per = (proto->count + n_threads - 1) / n_threads;
+  for (int t = 0; t < n_threads; ++t) {
+    jobs[t] = *proto;
+    uint64_t lo = per * t;
+    if (lo > proto->count) lo = proto->count;
+    uint64_t hi = lo + per < proto->count ? lo + per : proto->count;
+    jobs[t].first = proto->first + lo;
+    jobs[t].count = hi - lo;
+    if (proto->mode == 3) jobs[t].top = (so_eval *)calloc((size_t)proto->k, sizeof(so_eval));
+  }
+  if (n_threads == 1) {
+    run_job(&jobs[0]);
+    return;
+  }
+  for (int t = 0; t < n_threads; ++t) pthread_create(&th[t], NULL, run_job, &jobs[t]);
+  for (int t = 0; t < n_threads; ++t) pthread_join(th[t], NULL);
+}
+
+int so_eval_batch(const so_ctx *c, uint64_t first, uint64_t count, const uint64_t *indices,
+                  int objective, int has_bound, double bound, double *time, double *cost,
+                  uint64_t *mem, uint32_t *mask, int n_threads) {
+  /* outputs are written at position first + n when a range is given, n when a list is */
+  so_job proto;
+  memset(&proto, 0, sizeof proto);
+  proto.c = c; proto.count = count; proto.indices = indices;
+  proto.objective = objective; proto.has_bound = has_bound; proto.bound = bound;
+  proto.mode = 0;
+  if (indices) {
+    proto.first = 0;
+    proto.time = time; proto.cost = cost; proto.mem = mem; proto.mask = mask;
+  } else {
+    if (first + count > c->n_candidates) return -1;
+    proto.first = first;
+    proto.time = time ? time - first : NULL;
+    proto.cost = cost ? cost - first : NULL;
+    proto.mem = mem ? mem - first : NULL;
+    proto.mask = mask ? mask - first : NULL;
+  }
+  so_job jobs[256];
+  run_sharded(&proto, n_threads, jobs);
+  return 0;
+}
+
+int so_best(const so_ctx *c, uint64_t first, uint64_t count, int objective, int has_bound,
+            double bound, int n_threads, so_eval *out) {
+  if (first + count > c->n_candidates) return 0;
+  if (n_threads < 1) n_threads = 1;
+  if (n_threads > 256) n_threads = 256;
+  so_job proto, jobs[256];
+  memset(&proto, 0, sizeof proto);
+  proto.c = c; proto.first = first; proto.count = count;
+  proto.objective = objective; proto.has_bound = has_bound; proto.bound = bound;
+  /* pass 1: the minimum key over feasible candidates */
+  proto.mode = 1;
+  run_sharded(&proto, n_threads, jobs);
+  int found = 0;
+  double vmin = 0.0;
+  for (int t = 0; t < n_threads; ++t)
+    if (jobs[t].found) {
+      double k = key_of(&jobs[t].best, objective);
+      if (!found || k < vmin) { vmin = k; found = 1; }
+    }
+  if (!found) return 0;
+  /* pass 2: the lowest index whose key lies within the tie tolerance of the minimum */
+  proto.mode = 2;
+  proto.limit = vmin * (1.0 + SO_TIE_TOL);
+  run_sharded(&proto, n_threads, jobs);
+  for (int t = 0; t < n_threads; ++t)
+    if (jobs[t].found) { *out = jobs[t].best; return 1; } /* shards are in index order */
+  return 0;
+}
+
+int so_topk(const so_ctx *c, uint64_t first, uint64_t count, int objective, int has_bound,
+            double bound, int k, int n_threads, so_eval *out) {
+  if (first + count > c->n_candidates || k < 1) return 0;
+  if (n_threads < 1) n_threads = 1;
+  if (n_threads > 256) n_threads = 256;
+  so_job proto, jobs[256];
+  memset(&proto, 0, sizeof proto);
+  proto.c = c; proto.first = first; proto.count = count;
+  proto.objective = objective; proto.has_bound = has_bound; proto.bound = bound;
+  proto.mode = 3; proto.k = k;
+  run_sharded(&proto, n_threads, jobs);
+  /* merge the per-shard lists: repeatedly take the lexicographically smallest head */
+  int head[256];
+  memset(head, 0, sizeof head);
+  int n = 0;
+  while (n < k) {
+    int bt = -1;
+    for (int t = 0; t < n_threads; ++t) {
+      if (head[t] >= jobs[t].n_top) continue;
+      so_eval *e = &jobs[t].top[head[t]];
+      if (bt < 0 || lex_less(key_of(e, objective), e->index,
+                             key_of(&jobs[bt].top[head[bt]], objective),
+                             jobs[bt].top[head[bt]].index))
+        bt = t;
+    }
+    if (bt < 0) break;
+    out[n++] = jobs[bt].top[head[bt]++];
+  }
+  for (int t = 0; t < n_threads; ++t) free(jobs[t].top);
+  return n;
+}

@@ -1,0 +1,109 @@
+/*
+ * CPU oracle for the batched plan evaluator -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, fp64 / exact-integer implementation of what the planner's hot path
+ * computes for every candidate plan, written from the paper (Sailor, SOSP '25):
+ *   - plan tuple: stages P, data-parallel degree D shared by all stages, a
+ *     (GPU type, TP, zone) choice per stage, one microbatch size      (Sec. 4.2)
+ *   - heuristics H1 (TP inside a node), H5 (a stage's replicas stay in one region),
+ *     H6 (zones of a region merged)                                   (Sec. 4.2.1)
+ *   - memory M_peak = M_model + M_activation per worker, per stage   (Sec. 4.3)
+ *   - T_iter = max(T_pp) + T_sync + T_update, 1F1B with the steady phase set by
+ *     the straggler; T_total composition                             (Sec. 4.3, 4.2.2)
+ *   - C_iter = C_comp + C_comm                                        (Sec. 4.3, 4.2.3)
+ *   - sort by objective, return the best valid plan                   (Sec. 4.2)
+ *
+ * It shares no code with the HIP library and is never called by it.  Only the tests,
+ * the smoke check and the benchmark's CPU-baseline leg may use it.
+ *
+ * Parity pins (tests/test_oracle_*.py): homogeneous 1F1B closed form, discrete-event
+ * 1F1B schedule, ring all-reduce limits, big-integer memory bytes, cost identities,
+ * feasibility monotonicity, brute-force selection, enumeration bijection.
+ * Against numeric outputs of the paper's own simulator: parity unpinned (the paper
+ * prints no worked input -> output example).
+ *
+ * Units: seconds, bytes, bytes/second, $/hour, $/byte.
+ */
+#ifndef SAILOR_ORACLE_H
+#define SAILOR_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+  int32_t n_layers, n_types, n_zones, n_mb, n_tp, n_dp, n_pp;
+  int32_t max_segments, seg3_max_pp, uniform_layers;
+  int64_t global_batch;
+  const int32_t *mb_values, *tp_values, *dp_values, *pp_values;
+  const int32_t *n_partitions;     /* [n_pp] */
+  const int32_t *partition_layers; /* rows of pp layer counts, pp-major then partition */
+  const uint64_t *layer_params;    /* [n_layers] */
+  uint64_t embed_params, head_params;
+  uint32_t bytes_per_param, grad_bytes_per_param;
+  const double *t_fwd, *t_bwd;     /* [G][n_mb][n_tp][Lc], Lc = uniform ? 1 : n_layers */
+  const double *t_upd;             /* [G][n_tp][Lc] */
+  const uint64_t *act_store_bytes; /* [n_mb][n_tp] */
+  const uint64_t *p2p_bytes;       /* [n_mb] */
+  const uint64_t *mem_capacity, *mem_reserved; /* [G] */
+  const int32_t *gpus_per_node;    /* [G] */
+  const double *price_per_hour;    /* [G] */
+  const int32_t *avail;            /* [Z][G] */
+  const double *bandwidth;         /* [Z][Z] */
+  const double *egress_per_byte;   /* [Z][Z] or NULL */
+} so_problem;
+
+/* a decoded candidate */
+typedef struct {
+  int32_t pp, pp_idx, n_segments, partition;
+  int32_t cut[2];  /* first stage of segment 2 / segment 3 (unused entries = pp) */
+  int32_t pool[3]; /* zone * n_types + type, -1 if the segment is absent */
+  int32_t dp, tp, mb, dp_idx, tp_idx, mb_idx;
+} so_config;
+
+typedef struct {
+  uint64_t index;
+  uint32_t mask;
+  uint64_t peak_mem;
+  double iter_time, cost;
+} so_eval;
+
+enum { SO_MAX_THROUGHPUT = 0, SO_MIN_COST = 1 };
+enum {
+  SO_BIT_OOM = 1u << 0, SO_BIT_QUOTA = 1u << 1, SO_BIT_BATCH = 1u << 2,
+  SO_BIT_TP_NODE = 1u << 3, SO_BIT_CONSTRAINT = 1u << 5
+};
+
+typedef struct so_ctx so_ctx;
+
+so_ctx *so_create(const so_problem *p); /* borrows the arrays; NULL on bad input */
+void so_destroy(so_ctx *c);
+uint64_t so_num_candidates(const so_ctx *c);
+
+int so_decode(const so_ctx *c, uint64_t index, so_config *out);     /* 0 ok, -1 range */
+int so_encode(const so_ctx *c, const so_config *cfg, uint64_t *out); /* 0 ok, -1 invalid */
+/* nested-loop enumeration in index order; fills at most max_out configs, returns total */
+uint64_t so_enumerate(const so_ctx *c, so_config *out, uint64_t max_out);
+
+/* one candidate; has_bound = 0 ignores bound */
+int so_eval_one(const so_ctx *c, uint64_t index, int objective, int has_bound, double bound,
+                so_eval *out);
+/* indices == NULL means first .. first+count-1 ; any output pointer may be NULL */
+int so_eval_batch(const so_ctx *c, uint64_t first, uint64_t count, const uint64_t *indices,
+                  int objective, int has_bound, double bound, double *time, double *cost,
+                  uint64_t *mem, uint32_t *mask, int n_threads);
+
+/* best plan over [first, first+count): min key over mask == 0, then the lowest index
+ * whose key <= min * (1 + 1e-5).  Returns 1 if found, 0 if nothing is feasible. */
+int so_best(const so_ctx *c, uint64_t first, uint64_t count, int objective, int has_bound,
+            double bound, int n_threads, so_eval *out);
+/* ascending (key, index) over mask == 0, first k; returns how many were found */
+int so_topk(const so_ctx *c, uint64_t first, uint64_t count, int objective, int has_bound,
+            double bound, int k, int n_threads, so_eval *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
