@@ -1,0 +1,196 @@
+/*
+ * sailor.h -- C ABI of the batched plan evaluator (HIP, gfx950).
+ *
+ * The library evaluates every candidate training-job plan of a planning problem
+ * through the runtime / memory / cost simulator of Sailor (SOSP '25, Sec. 4.3) and
+ * selects the best valid plans under an objective and an optional constraint
+ * (Sec. 4, Sec. 4.2).  All evaluation runs in GPU kernels; the host only validates,
+ * uploads tables, launches and decodes the winning indices into plan tuples.
+ *
+ * Conventions
+ *   - every call returns a sailor_status; out-parameters are untouched on error
+ *   - "host" / "device" says where a pointer must live; device pointers belong to the
+ *     HIP device that was current when the plan was created
+ *   - units: seconds, bytes, bytes/second, $/hour, $/byte
+ *   - a plan object is not thread-safe; different plans are independent
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream)
+ *
+ * Candidate space (plan tuple of Sec. 4.2: stages P, one data-parallel degree D for all
+ * stages, a (GPU type, TP, zone) choice per stage, one microbatch size).  A plan's P
+ * stages are cut into 1..3 contiguous segments; each segment runs on one pool
+ * a = zone * n_types + type; neighbouring segments use different pools; one TP degree
+ * per plan.  Candidates are numbered block by block, blocks ordered by pp index, then
+ * by segment count s (a block exists when s <= max_segments, s <= P and, for s = 3,
+ * P <= seg3_max_pp).  Inside a block the index is mixed radix, least significant digit
+ * first:
+ *     mb index, tp index, dp index, pool of segment 1,
+ *     [s >= 2: r2 in [0, ZG-1), pool2 = (pool1 + 1 + r2) mod ZG],
+ *     [s == 3: r3 in [0, ZG-1), pool3 = (pool2 + 1 + r3) mod ZG],
+ *     [s == 2: k - 1 in [0, P-1), segment 1 = stages [0, k)],
+ *     [s == 3: rank of (k1, k2), 1 <= k1 < k2 <= P-1, in lexicographic order],
+ *     partition index q in [0, n_partitions[pp index]).
+ * The numbering is part of the contract: the tie rule prefers the lowest index.
+ *
+ * Mask bits of an evaluated candidate (0 = valid plan)
+ *   bit 0 OOM               some stage's worker exceeds its GPU's memory (Sec. 4.3)
+ *   bit 1 OVER_QUOTA        a pool needs more GPUs than are available (Sec. 4)
+ *   bit 2 BATCH_INDIVISIBLE global batch not divisible by D * mb; then time = cost =
+ *                           +inf, mem = 0 and no other bit is set
+ *   bit 3 TP_EXCEEDS_NODE   heuristic H1 (Sec. 4.2.1)
+ *   bit 5 CONSTRAINT        the optional bound is violated (Sec. 4.2)
+ */
+#ifndef SAILOR_H
+#define SAILOR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sailor_plan sailor_plan; /* opaque, owned by the library */
+
+typedef enum {
+  SAILOR_OK = 0,
+  SAILOR_EINVAL = -1,      /* NULL pointer, malformed list or table, limit exceeded */
+  SAILOR_ENOMEM = -2,      /* host or device allocation failed, or an internal buffer overflowed */
+  SAILOR_EDEVICE = -3,     /* a HIP call failed */
+  SAILOR_ERANGE = -4,      /* candidate index or range outside [0, N) */
+  SAILOR_ENOFEASIBLE = -5  /* no candidate has mask == 0 */
+} sailor_status;
+
+typedef enum { SAILOR_MAX_THROUGHPUT = 0, SAILOR_MIN_COST = 1 } sailor_objective;
+
+enum {
+  SAILOR_MASK_OOM = 1u << 0,
+  SAILOR_MASK_OVER_QUOTA = 1u << 1,
+  SAILOR_MASK_BATCH_INDIVISIBLE = 1u << 2,
+  SAILOR_MASK_TP_EXCEEDS_NODE = 1u << 3,
+  SAILOR_MASK_CONSTRAINT = 1u << 5
+};
+
+/* Limits checked by sailor_plan_create. */
+enum {
+  SAILOR_MAX_POOLS = 64,  /* n_zones * n_types */
+  SAILOR_MAX_TYPES = 16,
+  SAILOR_MAX_ZONES = 16,
+  SAILOR_MAX_MB = 8,
+  SAILOR_MAX_TP = 8,
+  SAILOR_MAX_DP = 24,
+  SAILOR_MAX_STAGES = 256,
+  SAILOR_MAX_K = 4096     /* largest k of sailor_topk */
+};
+
+/*
+ * The planning problem: job profile, cluster, search lists (inputs of the planner,
+ * Sec. 4 and Sec. 4.1).  All arrays are host memory, row-major, caller-owned and copied
+ * during sailor_plan_create; the caller may free them when it returns.
+ * G = n_types, Z = n_zones, Lc = uniform_layers ? 1 : n_layers.
+ */
+typedef struct {
+  int32_t n_layers, n_types, n_zones, n_mb, n_tp, n_dp, n_pp;
+  int32_t max_segments;    /* 1, 2 or 3 */
+  int32_t seg3_max_pp;     /* a third segment only for pp <= this */
+  int32_t uniform_layers;  /* 1: time tables hold a single per-layer column */
+  int64_t global_batch;    /* never changed by the planner (Sec. 4.2) */
+  const int32_t *mb_values, *tp_values, *dp_values, *pp_values; /* positive, strictly ascending */
+  const int32_t *n_partitions;     /* [n_pp], >= 1 */
+  const int32_t *partition_layers; /* for each pp index, n_partitions rows of pp layer counts,
+                                      each >= 1, each row summing to n_layers */
+  const uint64_t *layer_params;    /* [n_layers] parameters per layer */
+  uint64_t embed_params, head_params; /* charged to the first / the last stage */
+  uint32_t bytes_per_param;        /* weights + gradients + optimizer state per parameter */
+  uint32_t grad_bytes_per_param;   /* bytes all-reduced per parameter */
+  const double *t_fwd, *t_bwd;     /* [G][n_mb][n_tp][Lc] seconds per layer */
+  const double *t_upd;             /* [G][n_tp][Lc] seconds per layer */
+  const uint64_t *act_store_bytes; /* [n_mb][n_tp] stored activations per layer per
+                                      in-flight microbatch */
+  const uint64_t *p2p_bytes;       /* [n_mb] activation bytes sent between two stages */
+  const uint64_t *mem_capacity;    /* [G] */
+  const uint64_t *mem_reserved;    /* [G] buffers / fragmentation, added to every worker */
+  const int32_t *gpus_per_node;    /* [G] */
+  const double *price_per_hour;    /* [G] */
+  const int32_t *avail;            /* [Z][G] GPUs available now, >= 0 */
+  const double *bandwidth;         /* [Z][Z] bytes/s from row zone to column zone, > 0;
+                                      the diagonal is the intra-zone link */
+  const double *egress_per_byte;   /* [Z][Z] $/byte, >= 0, or NULL for zeros */
+} sailor_problem;
+
+/* Optional bound: SAILOR_MAX_THROUGHPUT -> bound is the largest allowed $/iteration;
+ * SAILOR_MIN_COST -> bound is the smallest allowed iterations/second. */
+typedef struct {
+  double bound;
+  int32_t has_bound;
+} sailor_constraint;
+
+/* One decoded (and, where stated, evaluated) plan. */
+typedef struct {
+  uint64_t index;
+  uint64_t peak_mem_bytes;
+  double iter_time_s, cost_per_iter; /* evaluated in fp64 on the device */
+  uint32_t mask;
+  int32_t pp, tp, dp, mb;
+  int32_t pp_index, tp_index, dp_index, mb_index;
+  int32_t partition, n_segments;
+  int32_t cut[2];  /* first stage of segment 2 / 3; unused entries = pp */
+  int32_t pool[3]; /* zone * n_types + type; unused entries = -1 */
+} sailor_result;
+
+/* Build a plan: validate, copy the problem to the current HIP device, build the static
+ * per-stage and per-segment tables there.  *out receives the plan.
+ * Errors: SAILOR_EINVAL (see limits and field comments), SAILOR_ENOMEM, SAILOR_EDEVICE. */
+sailor_status sailor_plan_create(const sailor_problem *problem, sailor_plan **out);
+
+/* Free everything the plan owns (host and device).  NULL is accepted. */
+sailor_status sailor_plan_destroy(sailor_plan *plan);
+
+/* Replace the availability table ([Z][G], host) -- the only input that changes between
+ * re-plans when resources come and go (Sec. 4, Sec. 4.4).  Tables that do not depend on
+ * availability are kept (cf. the reuse noted under H2, Sec. 4.2.1). */
+sailor_status sailor_plan_set_avail(sailor_plan *plan, const int32_t *avail);
+
+/* Number of candidates N. */
+sailor_status sailor_plan_num_candidates(const sailor_plan *plan, uint64_t *out);
+
+/* Decode an index into the configuration fields of *out (host only, nothing is
+ * evaluated: peak_mem_bytes, times, cost and mask are set to 0).  SAILOR_ERANGE if
+ * index >= N. */
+sailor_status sailor_plan_decode(const sailor_plan *plan, uint64_t index, sailor_result *out);
+
+/* Evaluate candidates (Sec. 4.3: memory footprint, iteration time, cost per iteration,
+ * plus the validity mask).  d_indices == NULL evaluates first .. first+count-1, otherwise
+ * the count indices stored in device memory at d_indices (first is ignored).  Output
+ * arrays are device memory of count elements; any may be NULL.  fp32 time and cost,
+ * exact 64-bit bytes.  Asynchronous on hip_stream.  constraint may be NULL.
+ * Errors: SAILOR_ERANGE if the range leaves [0, N); an index >= N inside d_indices yields
+ * mask = 0xFFFFFFFF, time = cost = +inf, mem = 0. */
+sailor_status sailor_eval_batch(sailor_plan *plan, uint64_t first, uint64_t count,
+                                const uint64_t *d_indices, sailor_objective objective,
+                                const sailor_constraint *constraint, float *d_time,
+                                float *d_cost, uint64_t *d_mem, uint32_t *d_mask,
+                                void *hip_stream);
+
+/* Best valid plan over the whole space (Sec. 4.2: order by the objective, return the
+ * best): the minimum key (iteration time or cost) over mask == 0, then the lowest index
+ * whose key is within a relative 1e-5 of that minimum.  *out (host) is filled completely.
+ * Synchronises hip_stream.  SAILOR_ENOFEASIBLE when no candidate is valid. */
+sailor_status sailor_best_plan(sailor_plan *plan, sailor_objective objective,
+                               const sailor_constraint *constraint, sailor_result *out,
+                               void *hip_stream);
+
+/* The k best valid plans in ascending (key, index) order; out (host) has room for k
+ * entries, *n_found receives how many exist (<= k).  1 <= k <= SAILOR_MAX_K.
+ * Synchronises hip_stream.  SAILOR_ENOFEASIBLE (with *n_found = 0) when none is valid. */
+sailor_status sailor_topk(sailor_plan *plan, sailor_objective objective,
+                          const sailor_constraint *constraint, int32_t k, sailor_result *out,
+                          int32_t *n_found, void *hip_stream);
+
+/* Time, in milliseconds between HIP events on hip_stream, of the kernels launched by the
+ * last sailor_best_plan / sailor_topk / sailor_eval_batch call on this plan:
+ * total and the part spent in the full-space scan kernel.  For measurement only. */
+sailor_status sailor_plan_last_timing(sailor_plan *plan, float *total_ms, float *scan_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,38 @@
+"""Builds libsailor.so (HIP, gfx950) in-tree with hipcc."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+SOURCES = [os.path.join(_HERE, "csrc", "sailor.hip")]
+HEADERS = [os.path.join(_HERE, "csrc", "sailor_kernels.hip.h"),
+           os.path.join(_HERE, "csrc", "sailor_dev.h"),
+           os.path.join(os.path.dirname(_HERE), "include", "sailor.h")]
+LIB = os.path.join(_HERE, "libsailor.so")
+
+HIPCC_FLAGS = [
+    "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
+    "-ffp-contract=off",  # fused multiply-adds only where the source asks for them
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-function",
+]
+
+
+def is_stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
+
+
+def build(force: bool = True, extra_flags=()) -> str:
+    if force or is_stale():
+        hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+        cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-o", LIB, *SOURCES]
+        subprocess.check_call(cmd)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build())

@@ -1,0 +1,624 @@
+// Host side of the C ABI declared in include/sailor.h: validation, upload, launches,
+// decoding of winning indices.  No simulator arithmetic runs here.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/sailor.h"
+#include "sailor_kernels.hip.h"
+
+using namespace sailor;
+
+namespace {
+
+constexpr uint32_t kSurvCap = 1u << 22;  // 64 MiB of survivors
+constexpr uint32_t kRefCap = 1u << 18;
+constexpr uint32_t kUnitTarget = 16384;  // candidates per scan workgroup
+
+#define HIP_TRY(expr)                                                              \
+  do {                                                                             \
+    hipError_t e_ = (expr);                                                        \
+    if (e_ != hipSuccess) {                                                        \
+      std::fprintf(stderr, "sailor: %s failed: %s\n", #expr, hipGetErrorString(e_)); \
+      return SAILOR_EDEVICE;                                                       \
+    }                                                                              \
+  } while (0)
+
+struct DeviceArena {  // every device allocation of a plan, freed together
+  std::vector<void *> ptrs;
+  template <typename T>
+  hipError_t alloc(T **out, size_t n) {
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, std::max<size_t>(n, 1) * sizeof(T));
+    if (e == hipSuccess) ptrs.push_back(p);
+    *out = static_cast<T *>(p);
+    return e;
+  }
+  template <typename T>
+  hipError_t upload(const T **out, const T *src, size_t n) {
+    T *p = nullptr;
+    hipError_t e = alloc(&p, n);
+    if (e != hipSuccess) return e;
+    *out = p;
+    return n ? hipMemcpy(p, src, n * sizeof(T), hipMemcpyHostToDevice) : hipSuccess;
+  }
+  void release() {
+    for (void *p : ptrs) (void)hipFree(p);
+    ptrs.clear();
+  }
+};
+
+}  // namespace
+
+struct sailor_plan {
+  DevPlan dev{};
+  DeviceArena arena;
+  std::vector<ShapeRec> shapes;
+  std::vector<BlockRec> blocks;
+  std::vector<UnitRec> units;
+  std::vector<int32_t> mbv, tpv, dpv, ppv;
+  int device = 0;
+  size_t lds_bytes = 0;
+  int32_t *d_avail = nullptr;
+  // scratch of the selection pipeline
+  float *umin_s = nullptr, *umin_l = nullptr;
+  uint32_t *counters = nullptr;
+  SurvRec *surv = nullptr;
+  RefRec *ref = nullptr;
+  // host-mapped result area: header + SAILOR_MAX_K records
+  void *h_result = nullptr;
+  ResultHeader *d_hdr = nullptr;
+  RefRec *d_out = nullptr;
+  hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+  bool timing_valid = false, scan_timed = false;
+};
+
+namespace {
+
+bool ascending_positive(const int32_t *v, int n) {
+  if (!v || n < 1) return false;
+  for (int i = 0; i < n; ++i) {
+    if (v[i] < 1) return false;
+    if (i && v[i] <= v[i - 1]) return false;
+  }
+  return true;
+}
+
+bool finite_nonneg(const double *v, size_t n) {
+  for (size_t i = 0; i < n; ++i)
+    if (!(v[i] >= 0.0) || !std::isfinite(v[i])) return false;
+  return true;
+}
+
+sailor_status validate(const sailor_problem *p) {
+  if (!p) return SAILOR_EINVAL;
+  if (p->n_layers < 1 || p->n_types < 1 || p->n_zones < 1) return SAILOR_EINVAL;
+  if (p->n_types > SAILOR_MAX_TYPES || p->n_zones > SAILOR_MAX_ZONES) return SAILOR_EINVAL;
+  if (p->n_types * p->n_zones > SAILOR_MAX_POOLS) return SAILOR_EINVAL;
+  if (p->n_mb < 1 || p->n_mb > SAILOR_MAX_MB || p->n_tp < 1 || p->n_tp > SAILOR_MAX_TP ||
+      p->n_dp < 1 || p->n_dp > SAILOR_MAX_DP || p->n_pp < 1)
+    return SAILOR_EINVAL;
+  if (p->max_segments < 1 || p->max_segments > 3 || p->global_batch < 1) return SAILOR_EINVAL;
+  if (!ascending_positive(p->mb_values, p->n_mb) || !ascending_positive(p->tp_values, p->n_tp) ||
+      !ascending_positive(p->dp_values, p->n_dp) || !ascending_positive(p->pp_values, p->n_pp))
+    return SAILOR_EINVAL;
+  if (!p->n_partitions || !p->partition_layers || !p->layer_params || !p->t_fwd || !p->t_bwd ||
+      !p->t_upd || !p->act_store_bytes || !p->p2p_bytes || !p->mem_capacity || !p->mem_reserved ||
+      !p->gpus_per_node || !p->price_per_hour || !p->avail || !p->bandwidth)
+    return SAILOR_EINVAL;
+  const int G = p->n_types, Z = p->n_zones, L = p->n_layers;
+  size_t row = 0;
+  for (int ip = 0; ip < p->n_pp; ++ip) {
+    const int P = p->pp_values[ip];
+    if (P > L || P > SAILOR_MAX_STAGES || p->n_partitions[ip] < 1) return SAILOR_EINVAL;
+    for (int q = 0; q < p->n_partitions[ip]; ++q) {
+      int64_t sum = 0;
+      for (int i = 0; i < P; ++i) {
+        const int32_t n = p->partition_layers[row++];
+        if (n < 1) return SAILOR_EINVAL;
+        sum += n;
+      }
+      if (sum != L) return SAILOR_EINVAL;
+    }
+  }
+  const size_t Lc = p->uniform_layers ? 1 : (size_t)L;
+  if (!finite_nonneg(p->t_fwd, (size_t)G * p->n_mb * p->n_tp * Lc) ||
+      !finite_nonneg(p->t_bwd, (size_t)G * p->n_mb * p->n_tp * Lc) ||
+      !finite_nonneg(p->t_upd, (size_t)G * p->n_tp * Lc) ||
+      !finite_nonneg(p->price_per_hour, G))
+    return SAILOR_EINVAL;
+  for (int i = 0; i < Z * Z; ++i)
+    if (!(p->bandwidth[i] > 0.0) || !std::isfinite(p->bandwidth[i])) return SAILOR_EINVAL;
+  if (p->egress_per_byte && !finite_nonneg(p->egress_per_byte, (size_t)Z * Z)) return SAILOR_EINVAL;
+  for (int i = 0; i < Z * G; ++i)
+    if (p->avail[i] < 0) return SAILOR_EINVAL;
+  for (int g = 0; g < G; ++g)
+    if (p->gpus_per_node[g] < 1) return SAILOR_EINVAL;
+  // byte counts must stay far below 2^64: total parameters * bytes + the largest
+  // activation term + reserved
+  unsigned __int128 params = (unsigned __int128)p->embed_params + p->head_params;
+  for (int l = 0; l < L; ++l) params += p->layer_params[l];
+  uint64_t act_max = 0, res_max = 0;
+  for (int i = 0; i < p->n_mb * p->n_tp; ++i) act_max = std::max(act_max, p->act_store_bytes[i]);
+  for (int g = 0; g < G; ++g) res_max = std::max(res_max, p->mem_reserved[g]);
+  unsigned __int128 worst = params * p->bytes_per_param +
+                            (unsigned __int128)act_max * (unsigned)L * (unsigned)SAILOR_MAX_STAGES +
+                            res_max;
+  if (worst >> 62) return SAILOR_EINVAL;
+  for (int g = 0; g < G; ++g)
+    if (p->mem_capacity[g] >> 62) return SAILOR_EINVAL;
+  for (int m = 0; m < p->n_mb; ++m)
+    if (p->p2p_bytes[m] >> 53) return SAILOR_EINVAL;
+  return SAILOR_OK;
+}
+
+uint64_t n_cut_choices(int P, int s) {
+  if (s == 1) return 1;
+  if (s == 2) return (uint64_t)(P - 1);
+  return (uint64_t)(P - 1) * (uint64_t)(P - 2) / 2;
+}
+
+// Lays the candidate space out as blocks -> shapes -> scan units (host bookkeeping only).
+sailor_status build_space(const sailor_problem *p, sailor_plan *pl, std::vector<int32_t> &st_n,
+                          std::vector<int32_t> &st_first, std::vector<uint8_t> &st_flags) {
+  const int ZG = p->n_types * p->n_zones;
+  const uint64_t inner = (uint64_t)p->n_mb * p->n_tp * p->n_dp * ZG;
+  uint64_t off = 0;
+  uint32_t row_stage = 0;
+  size_t row = 0;
+  for (int ip = 0; ip < p->n_pp; ++ip) {
+    const int P = p->pp_values[ip];
+    const uint32_t row_stage0 = row_stage;
+    for (int q = 0; q < p->n_partitions[ip]; ++q) {
+      int first = 0;
+      for (int i = 0; i < P; ++i) {
+        const int32_t n = p->partition_layers[row++];
+        st_n.push_back(n);
+        st_first.push_back(first);
+        st_flags.push_back((uint8_t)((i == 0 ? 1 : 0) | (i == P - 1 ? 2 : 0)));
+        first += n;
+      }
+      row_stage += P;
+    }
+    for (int s = 1; s <= 3; ++s) {
+      if (s > p->max_segments || s > P || (s == 3 && P > p->seg3_max_pp)) continue;
+      uint64_t shape_size = inner;
+      for (int j = 1; j < s; ++j) shape_size *= (uint64_t)(ZG - 1);
+      if (shape_size == 0) continue;
+      if (shape_size >> 32) return SAILOR_EINVAL;
+      BlockRec b{};
+      b.off = off;
+      b.first_shape = (uint32_t)pl->shapes.size();
+      b.shape_size = (uint32_t)shape_size;
+      b.pp_idx = ip;
+      b.s = s;
+      b.P = P;
+      for (int q = 0; q < p->n_partitions[ip]; ++q)
+        for (int k1 = (s >= 2 ? 1 : P); k1 <= (s >= 2 ? P - (s - 1) : P); ++k1)
+          for (int k2 = (s == 3 ? k1 + 1 : P); k2 <= (s == 3 ? P - 1 : P); ++k2) {
+            ShapeRec sh{};
+            sh.base = off;
+            sh.row_stage = row_stage0 + (uint32_t)q * P;
+            sh.pp_idx = ip;
+            sh.q = q;
+            sh.P = (uint16_t)P;
+            sh.s = (uint16_t)s;
+            sh.k1 = (uint16_t)k1;
+            sh.k2 = (uint16_t)k2;
+            const int edges[4] = {0, k1, k2, P};
+            for (int j = 0; j < 3; ++j) {
+              sh.lo[j] = (uint16_t)(j < s ? edges[j] : 0);
+              sh.n[j] = (uint16_t)(j < s ? edges[j + 1] - edges[j] : 0);
+            }
+            if (s == 1) sh.n[0] = (uint16_t)P;
+            if (s == 2) sh.n[1] = (uint16_t)(P - k1);
+            pl->shapes.push_back(sh);
+            off += shape_size;
+          }
+      b.n_shapes = (uint32_t)pl->shapes.size() - b.first_shape;
+      b.size = off - b.off;
+      if (b.n_shapes != n_cut_choices(P, s) * (uint64_t)p->n_partitions[ip]) return SAILOR_EINVAL;
+      pl->blocks.push_back(b);
+    }
+  }
+  pl->dev.N = off;
+  pl->dev.inner = (uint32_t)inner;
+  pl->dev.n_row_stages = (int)row_stage;
+
+  // scan units: (shape, tp, range of the relative pool digit of segment 2)
+  const uint64_t innerp = (uint64_t)p->n_mb * p->n_dp * ZG;
+  for (uint32_t si = 0; si < pl->shapes.size(); ++si) {
+    const ShapeRec &sh = pl->shapes[si];
+    const int n_o = sh.s >= 2 ? ZG - 1 : 1;
+    const uint64_t per_o = sh.s == 3 ? innerp * (uint64_t)(ZG - 1) : innerp;
+    int chunk = (int)std::min<uint64_t>((uint64_t)n_o, std::max<uint64_t>(1, kUnitTarget / per_o));
+    const int n_chunks = (n_o + chunk - 1) / chunk;
+    for (int t = 0; t < p->n_tp; ++t)
+      for (int c = 0; c < n_chunks; ++c) {
+        const int lo = (int)((int64_t)n_o * c / n_chunks), hi = (int)((int64_t)n_o * (c + 1) / n_chunks);
+        UnitRec u{};
+        u.shape = si;
+        u.tp = (uint16_t)t;
+        u.s = sh.s;
+        u.o_lo = (uint16_t)lo;
+        u.o_cnt = (uint16_t)(hi - lo);
+        pl->units.push_back(u);
+      }
+  }
+  return SAILOR_OK;
+}
+
+sailor_status constraint_limits(sailor_objective obj, const sailor_constraint *c, int *has_bound,
+                                double *bound, float *lim_s, float *lim_l) {
+  *has_bound = (c && c->has_bound) ? 1 : 0;
+  *bound = 0.0;
+  *lim_s = *lim_l = kPosInf;
+  if (!*has_bound) return SAILOR_OK;
+  if (std::isnan(c->bound)) return SAILOR_EINVAL;
+  *bound = c->bound;
+  // the fp32 scan compares cost <= bound, or time <= 1 / bound (throughput floor)
+  double lim = obj == SAILOR_MAX_THROUGHPUT ? c->bound : 1.0 / c->bound;
+  if (obj == SAILOR_MIN_COST && c->bound <= 0.0) lim = HUGE_VAL;
+  if (lim < 0.0) {
+    *lim_s = *lim_l = -1.0f;  // nothing satisfies a negative cost bound
+    return SAILOR_OK;
+  }
+  *lim_s = std::nextafterf((float)(lim * (1.0 - (double)kEvalEps)), 0.0f);
+  *lim_l = std::nextafterf((float)(lim * (1.0 + (double)kEvalEps)), kPosInf);
+  return SAILOR_OK;
+}
+
+void fill_config(const sailor_plan *pl, const ShapeRec &sh, uint64_t index, sailor_result *out) {
+  const DevPlan &d = pl->dev;
+  std::memset(out, 0, sizeof *out);
+  out->index = index;
+  const BlockRec *blk = &pl->blocks[0];
+  for (const BlockRec &b : pl->blocks)
+    if (index >= b.off) blk = &b;
+  uint64_t rem = (index - blk->off) % blk->shape_size;
+  const uint32_t in = (uint32_t)(rem % d.inner);
+  uint32_t o = (uint32_t)(rem / d.inner);
+  out->mb_index = in % d.MB;
+  out->tp_index = (in / d.MB) % d.TP;
+  out->dp_index = (in / (d.MB * d.TP)) % d.DP;
+  out->pool[0] = in / (d.MB * d.TP * d.DP);
+  out->pool[1] = out->pool[2] = -1;
+  if (sh.s >= 2) {
+    out->pool[1] = (out->pool[0] + 1 + (int)(o % (d.ZG - 1))) % d.ZG;
+    o /= (d.ZG - 1);
+  }
+  if (sh.s == 3) out->pool[2] = (out->pool[1] + 1 + (int)o) % d.ZG;
+  out->pp_index = sh.pp_idx;
+  out->pp = sh.P;
+  out->mb = pl->mbv[out->mb_index];
+  out->tp = pl->tpv[out->tp_index];
+  out->dp = pl->dpv[out->dp_index];
+  out->partition = sh.q;
+  out->n_segments = sh.s;
+  out->cut[0] = sh.k1;
+  out->cut[1] = sh.k2;
+}
+
+const ShapeRec &shape_of(const sailor_plan *pl, uint64_t index) {
+  const BlockRec *blk = &pl->blocks[0];
+  for (const BlockRec &b : pl->blocks)
+    if (index >= b.off) blk = &b;
+  return pl->shapes[blk->first_shape + (index - blk->off) / blk->shape_size];
+}
+
+template <int MODE>
+void launch_units(sailor_plan *pl, sailor_objective obj, int has_bound, const ScanArgs &a,
+                  hipStream_t st) {
+  const dim3 grid((unsigned)pl->units.size()), block(kUnitThreads);
+  const size_t lds = pl->lds_bytes;
+  if (obj == SAILOR_MAX_THROUGHPUT) {
+    if (has_bound) k_units<MODE, 0, true><<<grid, block, lds, st>>>(pl->dev, a);
+    else k_units<MODE, 0, false><<<grid, block, lds, st>>>(pl->dev, a);
+  } else {
+    if (has_bound) k_units<MODE, 1, true><<<grid, block, lds, st>>>(pl->dev, a);
+    else k_units<MODE, 1, false><<<grid, block, lds, st>>>(pl->dev, a);
+  }
+}
+
+// Shared by best_plan (k = 0: tolerance rule) and topk.
+sailor_status run_selection(sailor_plan *pl, sailor_objective obj, const sailor_constraint *con,
+                            uint32_t k, hipStream_t st, ResultHeader *hdr_out) {
+  int has_bound;
+  double bound;
+  ScanArgs sa{};
+  sailor_status rc = constraint_limits(obj, con, &has_bound, &bound, &sa.lim_s, &sa.lim_l);
+  if (rc != SAILOR_OK) return rc;
+  HIP_TRY(hipSetDevice(pl->device));
+  sa.umin_s = pl->umin_s;
+  sa.umin_l = pl->umin_l;
+  sa.counters = pl->counters;
+  sa.surv = pl->surv;
+  sa.surv_cap = kSurvCap;
+  const bool best = (k == 0);
+  const uint32_t n_units = (uint32_t)pl->units.size();
+
+  HIP_TRY(hipEventRecord(pl->ev[0], st));
+  k_init_counters<<<1, 64, 0, st>>>(pl->counters);
+  launch_units<MODE_SCAN>(pl, obj, has_bound, sa, st);
+  HIP_TRY(hipEventRecord(pl->ev[1], st));
+  if (best) {
+    sa.tau_src = pl->counters + CNT_GMIN;
+    sa.band = (float)(1.0 + kTieTol) + 3.0f * kEvalEps;
+  } else {
+    // an upper bound of the k-th smallest key: the k-th smallest unit minimum
+    k_select_kth<<<1, 1024, 0, st>>>(pl->umin_s, 1, nullptr, n_units, k, pl->counters + CNT_TAU0);
+    sa.tau_src = pl->counters + CNT_TAU0;
+    sa.band = 1.0f + 3.0f * kEvalEps;
+  }
+  launch_units<MODE_COLLECT>(pl, obj, has_bound, sa, st);
+  RefineArgs ra{};
+  ra.surv = pl->surv;
+  ra.surv_cap = kSurvCap;
+  ra.counters = pl->counters;
+  ra.ref = pl->ref;
+  ra.ref_cap = kRefCap;
+  ra.objective = (int)obj;
+  ra.has_bound = has_bound;
+  ra.bound = bound;
+  ra.band = 1.0f + 3.0f * kEvalEps;
+  if (!best) {
+    // the exact k-th smallest fp32 key among the survivors, then only its neighbourhood
+    k_select_kth<<<1, 1024, 0, st>>>(&pl->surv[0].key, (int)(sizeof(SurvRec) / 4),
+                                     pl->counters + CNT_SURV, kSurvCap, k, pl->counters + CNT_TAU1);
+    ra.tau_src = pl->counters + CNT_TAU1;
+  }
+  k_refine<<<256, 256, 0, st>>>(pl->dev, ra);
+  if (best) {
+    k_pick_best<<<1, 1024, 0, st>>>(pl->ref, kRefCap, pl->counters, (int)obj, pl->d_hdr, pl->d_out);
+  } else {
+    k_rank_topk<<<kRefCap / 256, 256, 0, st>>>(pl->ref, kRefCap, pl->counters, (int)obj, k,
+                                               pl->d_hdr, pl->d_out);
+  }
+  HIP_TRY(hipEventRecord(pl->ev[2], st));
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipStreamSynchronize(st));
+  pl->timing_valid = true;
+  pl->scan_timed = true;
+  *hdr_out = *static_cast<ResultHeader *>(pl->h_result);
+  if (hdr_out->surv_count > kSurvCap || hdr_out->ref_count > kRefCap) return SAILOR_ENOMEM;
+  return SAILOR_OK;
+}
+
+void to_result(const sailor_plan *pl, const RefRec &r, sailor_result *out) {
+  fill_config(pl, shape_of(pl, r.idx), r.idx, out);
+  out->peak_mem_bytes = r.mem;
+  out->iter_time_s = r.T;
+  out->cost_per_iter = r.C;
+  out->mask = r.mask;
+}
+
+}  // namespace
+
+extern "C" {
+
+sailor_status sailor_plan_destroy(sailor_plan *pl) {
+  if (!pl) return SAILOR_OK;
+  (void)hipSetDevice(pl->device);
+  pl->arena.release();
+  if (pl->h_result) (void)hipHostFree(pl->h_result);
+  for (hipEvent_t e : pl->ev)
+    if (e) (void)hipEventDestroy(e);
+  delete pl;
+  return SAILOR_OK;
+}
+
+sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
+  if (!out) return SAILOR_EINVAL;
+  sailor_status rc = validate(p);
+  if (rc != SAILOR_OK) return rc;
+  sailor_plan *pl = new (std::nothrow) sailor_plan();
+  if (!pl) return SAILOR_ENOMEM;
+  std::vector<int32_t> st_n, st_first;
+  std::vector<uint8_t> st_flags;
+  rc = build_space(p, pl, st_n, st_first, st_flags);
+  if (rc != SAILOR_OK || pl->dev.N == 0) {
+    delete pl;
+    return rc != SAILOR_OK ? rc : SAILOR_EINVAL;
+  }
+  DevPlan &d = pl->dev;
+  d.G = p->n_types; d.Z = p->n_zones; d.ZG = d.G * d.Z;
+  d.MB = p->n_mb; d.TP = p->n_tp; d.DP = p->n_dp;
+  d.bpp = p->bytes_per_param; d.gb = p->grad_bytes_per_param; d.B = p->global_batch;
+  d.n_blocks = (int)pl->blocks.size();
+  d.n_shapes = (int)pl->shapes.size();
+  d.n_units = (int)pl->units.size();
+  for (int i = 0; i < d.MB; ++i) d.mbv[i] = p->mb_values[i];
+  for (int i = 0; i < d.TP; ++i) d.tpv[i] = p->tp_values[i];
+  for (int i = 0; i < d.DP; ++i) d.dpv[i] = p->dp_values[i];
+  pl->mbv.assign(p->mb_values, p->mb_values + d.MB);
+  pl->tpv.assign(p->tp_values, p->tp_values + d.TP);
+  pl->dpv.assign(p->dp_values, p->dp_values + d.DP);
+  pl->ppv.assign(p->pp_values, p->pp_values + p->n_pp);
+  pl->lds_bytes = (size_t)3 * d.ZG * d.MB * sizeof(Rec) + (size_t)d.Z * d.Z * sizeof(float4) +
+                  (size_t)4 * d.ZG * sizeof(uint32_t);
+
+#define CREATE_TRY(expr)                                                           \
+  do {                                                                             \
+    hipError_t e_ = (expr);                                                        \
+    if (e_ != hipSuccess) {                                                        \
+      std::fprintf(stderr, "sailor: %s failed: %s\n", #expr, hipGetErrorString(e_)); \
+      sailor_plan_destroy(pl);                                                     \
+      return e_ == hipErrorOutOfMemory ? SAILOR_ENOMEM : SAILOR_EDEVICE;           \
+    }                                                                              \
+  } while (0)
+
+  CREATE_TRY(hipGetDevice(&pl->device));
+  DeviceArena &ar = pl->arena;
+  const int G = d.G, Z = d.Z, ZG = d.ZG, MB = d.MB, TP = d.TP, DP = d.DP, L = p->n_layers;
+  const size_t Lc = p->uniform_layers ? 1 : (size_t)L;
+  const size_t RS = (size_t)d.n_row_stages, NS = pl->shapes.size();
+
+  // inputs, copied as they are
+  CREATE_TRY(ar.alloc(&pl->d_avail, ZG));
+  CREATE_TRY(hipMemcpy(pl->d_avail, p->avail, ZG * sizeof(int32_t), hipMemcpyHostToDevice));
+  d.avail = pl->d_avail;
+  CREATE_TRY(ar.upload(&d.cap, p->mem_capacity, G));
+  CREATE_TRY(ar.upload(&d.res, p->mem_reserved, G));
+  CREATE_TRY(ar.upload(&d.node, p->gpus_per_node, G));
+  CREATE_TRY(ar.upload(&d.price, p->price_per_hour, G));
+  CREATE_TRY(ar.upload(&d.bw, p->bandwidth, (size_t)Z * Z));
+  if (p->egress_per_byte) CREATE_TRY(ar.upload(&d.egress, p->egress_per_byte, (size_t)Z * Z));
+  CREATE_TRY(ar.upload(&d.act, p->act_store_bytes, (size_t)MB * TP));
+  CREATE_TRY(ar.upload(&d.p2p, p->p2p_bytes, MB));
+  StageArgs sa{};
+  CREATE_TRY(ar.upload(&sa.layer_params, p->layer_params, L));
+  CREATE_TRY(ar.upload(&sa.t_fwd, p->t_fwd, (size_t)G * MB * TP * Lc));
+  CREATE_TRY(ar.upload(&sa.t_bwd, p->t_bwd, (size_t)G * MB * TP * Lc));
+  CREATE_TRY(ar.upload(&sa.t_upd, p->t_upd, (size_t)G * TP * Lc));
+  CREATE_TRY(ar.upload(&sa.st_flags, st_flags.data(), RS));
+  sa.embed = p->embed_params; sa.head = p->head_params; sa.L = L; sa.uniform = p->uniform_layers ? 1 : 0;
+  CREATE_TRY(ar.upload(&d.st_n, st_n.data(), RS));
+  CREATE_TRY(ar.upload(&d.st_first, st_first.data(), RS));
+  CREATE_TRY(ar.upload(&d.shapes, pl->shapes.data(), NS));
+  CREATE_TRY(ar.upload(&d.blocks, pl->blocks.data(), pl->blocks.size()));
+  CREATE_TRY(ar.upload(&d.units, pl->units.data(), pl->units.size()));
+  // derived tables, filled by the set-up kernels
+  CREATE_TRY(ar.alloc(&d.ibw_f, (size_t)Z * Z));
+  CREATE_TRY(ar.alloc(&d.egs_f, (size_t)Z * Z));
+  CREATE_TRY(ar.alloc(&d.price_f, G));
+  CREATE_TRY(ar.alloc(&d.p2p_f, MB));
+  CREATE_TRY(ar.alloc(&d.xb_f, MB));
+  CREATE_TRY(ar.alloc(&d.cd_f, DP));
+  CREATE_TRY(ar.alloc(&d.nbm1_f, (size_t)MB * DP));
+  CREATE_TRY(ar.alloc(&d.dtp_f, (size_t)TP * DP));
+  CREATE_TRY(ar.alloc(&d.nb, (size_t)MB * DP));
+  CREATE_TRY(ar.alloc(&d.divis, MB));
+  CREATE_TRY(ar.alloc(&d.st_params, RS));
+  CREATE_TRY(ar.alloc(&d.st_c, RS * G * MB * TP));
+  CREATE_TRY(ar.alloc(&d.st_u, RS * G * TP));
+  const size_t slots = NS * TP * 3;
+  CREATE_TRY(ar.alloc(&d.ta, slots * G * MB));
+  CREATE_TRY(ar.alloc(&d.memok, slots * G * MB));
+  CREATE_TRY(ar.alloc(&d.need, slots * MB * DP));
+  CREATE_TRY(ar.alloc(&d.smax, slots));
+  CREATE_TRY(ar.alloc(&d.upd, slots * G));
+  // selection scratch
+  CREATE_TRY(ar.alloc(&pl->umin_s, pl->units.size()));
+  CREATE_TRY(ar.alloc(&pl->umin_l, pl->units.size()));
+  CREATE_TRY(ar.alloc(&pl->counters, (size_t)CNT_COUNT));
+  CREATE_TRY(ar.alloc(&pl->surv, (size_t)kSurvCap));
+  CREATE_TRY(ar.alloc(&pl->ref, (size_t)kRefCap));
+  const size_t res_bytes = sizeof(ResultHeader) + 8 + (size_t)SAILOR_MAX_K * sizeof(RefRec);
+  CREATE_TRY(hipHostMalloc(&pl->h_result, res_bytes, hipHostMallocMapped));
+  std::memset(pl->h_result, 0, res_bytes);
+  void *d_res = nullptr;
+  CREATE_TRY(hipHostGetDevicePointer(&d_res, pl->h_result, 0));
+  pl->d_hdr = static_cast<ResultHeader *>(d_res);
+  pl->d_out = reinterpret_cast<RefRec *>(static_cast<char *>(d_res) + sizeof(ResultHeader));
+  for (hipEvent_t &e : pl->ev) CREATE_TRY(hipEventCreate(&e));
+
+  k_small_tables<<<1, 256>>>(d);
+  k_stage_tables<<<(unsigned)RS, 128>>>(d, sa);
+  k_shape_agg<<<(unsigned)NS, 256>>>(d);
+  CREATE_TRY(hipGetLastError());
+  CREATE_TRY(hipDeviceSynchronize());
+#undef CREATE_TRY
+  *out = pl;
+  return SAILOR_OK;
+}
+
+sailor_status sailor_plan_set_avail(sailor_plan *pl, const int32_t *avail) {
+  if (!pl || !avail) return SAILOR_EINVAL;
+  for (int i = 0; i < pl->dev.ZG; ++i)
+    if (avail[i] < 0) return SAILOR_EINVAL;
+  HIP_TRY(hipSetDevice(pl->device));
+  HIP_TRY(hipMemcpy(pl->d_avail, avail, pl->dev.ZG * sizeof(int32_t), hipMemcpyHostToDevice));
+  return SAILOR_OK;
+}
+
+sailor_status sailor_plan_num_candidates(const sailor_plan *pl, uint64_t *out) {
+  if (!pl || !out) return SAILOR_EINVAL;
+  *out = pl->dev.N;
+  return SAILOR_OK;
+}
+
+sailor_status sailor_plan_decode(const sailor_plan *pl, uint64_t index, sailor_result *out) {
+  if (!pl || !out) return SAILOR_EINVAL;
+  if (index >= pl->dev.N) return SAILOR_ERANGE;
+  fill_config(pl, shape_of(pl, index), index, out);
+  return SAILOR_OK;
+}
+
+sailor_status sailor_eval_batch(sailor_plan *pl, uint64_t first, uint64_t count,
+                                const uint64_t *d_indices, sailor_objective objective,
+                                const sailor_constraint *constraint, float *d_time, float *d_cost,
+                                uint64_t *d_mem, uint32_t *d_mask, void *hip_stream) {
+  if (!pl || (objective != SAILOR_MAX_THROUGHPUT && objective != SAILOR_MIN_COST))
+    return SAILOR_EINVAL;
+  if (!d_indices && (first > pl->dev.N || count > pl->dev.N - first)) return SAILOR_ERANGE;
+  if (count > (uint64_t)0x7fffffff * 256) return SAILOR_ERANGE;
+  if (constraint && constraint->has_bound && std::isnan(constraint->bound)) return SAILOR_EINVAL;
+  if (count == 0) return SAILOR_OK;
+  HIP_TRY(hipSetDevice(pl->device));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  EvalArgs a{};
+  a.first = first; a.count = count; a.indices = d_indices;
+  a.time = d_time; a.cost = d_cost; a.mem = d_mem; a.mask = d_mask;
+  a.objective = (int)objective;
+  a.has_bound = (constraint && constraint->has_bound) ? 1 : 0;
+  a.bound = a.has_bound ? (float)constraint->bound : 0.f;
+  HIP_TRY(hipEventRecord(pl->ev[0], st));
+  k_eval_direct<<<(unsigned)((count + 255) / 256), 256, 0, st>>>(pl->dev, a);
+  HIP_TRY(hipEventRecord(pl->ev[2], st));
+  HIP_TRY(hipGetLastError());
+  pl->timing_valid = true;
+  pl->scan_timed = false;
+  return SAILOR_OK;
+}
+
+sailor_status sailor_best_plan(sailor_plan *pl, sailor_objective objective,
+                               const sailor_constraint *constraint, sailor_result *out,
+                               void *hip_stream) {
+  if (!pl || !out || (objective != SAILOR_MAX_THROUGHPUT && objective != SAILOR_MIN_COST))
+    return SAILOR_EINVAL;
+  ResultHeader hdr;
+  sailor_status rc = run_selection(pl, objective, constraint, 0,
+                                   static_cast<hipStream_t>(hip_stream), &hdr);
+  if (rc != SAILOR_OK) return rc;
+  if (hdr.n_found == 0) return SAILOR_ENOFEASIBLE;
+  const RefRec *rec = reinterpret_cast<const RefRec *>(static_cast<char *>(pl->h_result) +
+                                                       sizeof(ResultHeader));
+  to_result(pl, rec[0], out);
+  return SAILOR_OK;
+}
+
+sailor_status sailor_topk(sailor_plan *pl, sailor_objective objective,
+                          const sailor_constraint *constraint, int32_t k, sailor_result *out,
+                          int32_t *n_found, void *hip_stream) {
+  if (!pl || !out || !n_found || k < 1 || k > SAILOR_MAX_K ||
+      (objective != SAILOR_MAX_THROUGHPUT && objective != SAILOR_MIN_COST))
+    return SAILOR_EINVAL;
+  ResultHeader hdr;
+  sailor_status rc = run_selection(pl, objective, constraint, (uint32_t)k,
+                                   static_cast<hipStream_t>(hip_stream), &hdr);
+  if (rc != SAILOR_OK) return rc;
+  *n_found = (int32_t)hdr.n_found;
+  if (hdr.n_found == 0) return SAILOR_ENOFEASIBLE;
+  const RefRec *rec = reinterpret_cast<const RefRec *>(static_cast<char *>(pl->h_result) +
+                                                       sizeof(ResultHeader));
+  for (uint32_t i = 0; i < hdr.n_found; ++i) to_result(pl, rec[i], &out[i]);
+  return SAILOR_OK;
+}
+
+sailor_status sailor_plan_last_timing(sailor_plan *pl, float *total_ms, float *scan_ms) {
+  if (!pl || !pl->timing_valid) return SAILOR_EINVAL;
+  HIP_TRY(hipEventSynchronize(pl->ev[2]));
+  float t = 0.f, s = 0.f;
+  HIP_TRY(hipEventElapsedTime(&t, pl->ev[0], pl->ev[2]));
+  if (pl->scan_timed) HIP_TRY(hipEventElapsedTime(&s, pl->ev[0], pl->ev[1]));
+  if (total_ms) *total_ms = t;
+  if (scan_ms) *scan_ms = s;
+  return SAILOR_OK;
+}
+
+}  // extern "C"

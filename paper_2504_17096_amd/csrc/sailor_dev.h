@@ -1,0 +1,108 @@
+// Device-side data layout of a plan, shared by the host code and the kernels.
+//
+// A candidate plan (Sailor, Sec. 4.2) is a point of a flat index space; see
+// include/sailor.h for the numbering.  Candidates that share the pipeline depth, the
+// layer split and the cut points form a "shape": all per-stage work of the simulator
+// (Sec. 4.3) that does not depend on which pool a segment runs on is folded, once per
+// plan, into per-shape segment aggregates.  The scan kernel then evaluates a candidate
+// from a few aggregates instead of a loop over its stages.
+#pragma once
+
+#include <stdint.h>
+
+namespace sailor {
+
+constexpr int kMaxMB = 8, kMaxTP = 8, kMaxDP = 24, kMaxPools = 64, kMaxZones = 16,
+              kMaxTypes = 16, kMaxStages = 256;
+constexpr int kUnitThreads = 256;
+constexpr float kNegInf = -__builtin_huge_valf();
+constexpr float kPosInf = __builtin_huge_valf();
+
+// relative error budget of an fp32 key against its exact value, used to widen the
+// bands inside which candidates are re-evaluated in fp64
+constexpr float kEvalEps = 2.0e-6f;
+constexpr double kTieTol = 1.0e-5;
+
+struct ShapeRec {
+  uint64_t base;       // first candidate index of the shape
+  uint32_t row_stage;  // first entry of the shape's partition row in the stage tables
+  uint32_t pp_idx, q;
+  uint16_t P, s;
+  uint16_t n[3];       // stages per segment (0 = absent)
+  uint16_t lo[3];      // first stage of each segment
+  uint16_t k1, k2;     // cut points (P when unused)
+};
+
+struct BlockRec {       // all candidates with one (pp index, segment count)
+  uint64_t off, size;
+  uint32_t first_shape, n_shapes;
+  uint32_t shape_size;  // candidates per shape
+  uint32_t pp_idx, s, P;
+};
+
+struct UnitRec {        // work of one workgroup of the scan: one shape, one tp, a range of
+  uint32_t shape;       // the relative-pool digit of segment 2
+  uint16_t tp, s;
+  uint16_t o_lo, o_cnt;
+};
+
+struct SurvRec {        // candidate kept for the fp64 re-evaluation
+  uint64_t idx;
+  float key;            // fp32 key; +inf when only loosely inside the constraint
+  float key_loose;      // fp32 key
+};
+
+struct RefRec {         // fp64 re-evaluation of one candidate
+  uint64_t idx, mem;
+  double T, C;
+  uint32_t mask, pad;
+};
+
+struct ResultHeader {   // written by the final kernel into host-mapped memory
+  uint32_t n_found, surv_count, ref_count, feasible_count;
+};
+
+struct DevPlan {
+  int G, Z, ZG, MB, TP, DP;
+  int n_blocks, n_shapes, n_units, n_row_stages;
+  uint32_t inner;          // MB*TP*DP*ZG candidates per (shape, outer pool digits)
+  uint32_t bpp, gb;
+  int64_t B;
+  uint64_t N;
+  int mbv[kMaxMB], tpv[kMaxTP], dpv[kMaxDP];
+  // inputs
+  const int32_t *avail;        // [ZG]
+  const uint64_t *cap, *res;   // [G]
+  const int32_t *node;         // [G]
+  const double *price;         // [G]
+  const double *bw, *egress;   // [Z][Z]
+  const uint64_t *act;         // [MB][TP]
+  const uint64_t *p2p;         // [MB]
+  // derived small tables
+  float *ibw_f, *egs_f;        // [Z][Z] 1/bw ; egress both ways
+  float *price_f;              // [G]
+  float *p2p_f, *xb_f;         // [MB] p2p bytes ; (B/mb) * p2p bytes
+  float *cd_f;                 // [DP] 2 (D-1) / D
+  float *nbm1_f;               // [MB][DP] microbatches per pipeline - 1
+  float *dtp_f;                // [TP][DP] D * tp / 3600
+  int32_t *nb;                 // [MB][DP] microbatches per pipeline, 0 if B % (D mb) != 0
+  uint32_t *divis;             // [MB] bit d set when nb[mb][d] > 0
+  // per-stage tables, one entry per stage of every partition row
+  const int32_t *st_n;         // layers
+  const int32_t *st_first;     // first layer
+  uint64_t *st_params;         // parameters incl. embedding / head
+  double *st_c;                // [rs][G][MB][TP] sum of fwd + bwd layer times
+  double *st_u;                // [rs][G][TP] sum of update times
+  // candidate space
+  const ShapeRec *shapes;
+  const BlockRec *blocks;
+  const UnitRec *units;
+  // per-shape segment aggregates, [shape][TP][3]...
+  float4 *ta;                  // [..][G][MB] {sum, first, last, max interior} of stage compute
+  uint32_t *memok;             // [..][G][MB] bit d: no stage of the segment runs out of memory
+  uint64_t *need;              // [..][MB][DP] max over stages of model + activation bytes
+  float *smax;                 // [..] largest gradient shard of the segment, bytes
+  float *upd;                  // [..][G] slowest stage update
+};
+
+}  // namespace sailor

@@ -1,0 +1,767 @@
+// HIP kernels of the batched plan evaluator (gfx950, wave64).
+//
+// Set-up kernels (once per plan): k_small_tables, k_stage_tables, k_shape_agg.
+// Hot path:  k_units<SCAN>    full-space fp32 evaluation + per-unit minima
+//            k_select_kth     radix select of the k-th smallest fp32 key
+//            k_units<COLLECT> re-evaluates the few units that can hold a winner
+//            k_refine         fp64 / exact-integer stage-by-stage re-evaluation
+//            k_pick_best / k_rank_topk   final selection
+//            k_eval_direct    per-candidate outputs for sailor_eval_batch
+//
+// The simulator arithmetic follows Sailor, Sec. 4.3 (memory, iteration time, cost);
+// T_pp = sum of stage times + (N_b - 1) * straggler is the 1F1B composition of
+// Sec. 4.2.2 with the straggler counted N_b times in total.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "sailor_dev.h"
+
+namespace sailor {
+
+// ------------------------------------------------------------------ helpers
+
+__device__ __forceinline__ float wave_min(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v = fminf(v, __shfl_xor(v, off));
+  return v;
+}
+
+__device__ __forceinline__ size_t agg_slot(const DevPlan &pl, uint32_t shape, int tp, int seg) {
+  return ((size_t)shape * pl.TP + tp) * 3 + seg;
+}
+
+// ------------------------------------------------------------------ set-up kernels
+
+// Reciprocal bandwidths, two-way egress, and the per-(mb, dp, tp) scalars of a plan.
+__global__ void k_small_tables(DevPlan pl) {
+  const int t = threadIdx.x, nt = blockDim.x;
+  const int Z = pl.Z;
+  for (int i = t; i < Z * Z; i += nt) {
+    int a = i / Z, b = i % Z;
+    pl.ibw_f[i] = (float)(1.0 / pl.bw[i]);
+    double e = 0.0;
+    if (pl.egress && a != b) e = pl.egress[a * Z + b] + pl.egress[b * Z + a];
+    pl.egs_f[i] = (float)e;
+  }
+  for (int g = t; g < pl.G; g += nt) pl.price_f[g] = (float)pl.price[g];
+  for (int m = t; m < pl.MB; m += nt) {
+    pl.p2p_f[m] = (float)(double)pl.p2p[m];
+    // N_b * D = B / mb whenever the batch divides; the product is exact in fp64 for
+    // realistic sizes and is rounded once
+    pl.xb_f[m] = (float)((double)(pl.B / pl.mbv[m]) * (double)pl.p2p[m]);
+    uint32_t bits = 0;
+    for (int d = 0; d < pl.DP; ++d) {
+      int64_t per = (int64_t)pl.dpv[d] * pl.mbv[m];
+      int32_t nb = (pl.B % per == 0) ? (int32_t)(pl.B / per) : 0;
+      pl.nb[m * pl.DP + d] = nb;
+      pl.nbm1_f[m * pl.DP + d] = (float)(nb - 1);
+      if (nb > 0) bits |= 1u << d;
+    }
+    pl.divis[m] = bits;
+  }
+  for (int d = t; d < pl.DP; d += nt) {
+    double D = (double)pl.dpv[d];
+    pl.cd_f[d] = (float)(2.0 * (D - 1.0) / D);
+    for (int k = 0; k < pl.TP; ++k)
+      pl.dtp_f[k * pl.DP + d] = (float)((double)((int64_t)pl.dpv[d] * pl.tpv[k]) / 3600.0);
+  }
+}
+
+struct StageArgs {
+  const uint64_t *layer_params;  // [L]
+  const double *t_fwd, *t_bwd;   // [G][MB][TP][Lc]
+  const double *t_upd;           // [G][TP][Lc]
+  const uint8_t *st_flags;       // bit 0: first stage of its row, bit 1: last
+  uint64_t embed, head;
+  int L, uniform;
+};
+
+// Per stage of every partition row: parameters, summed layer times per (type, mb, tp).
+__global__ void k_stage_tables(DevPlan pl, StageArgs a) {
+  const int rs = blockIdx.x;
+  const int n = pl.st_n[rs], first = pl.st_first[rs];
+  const int G = pl.G, MB = pl.MB, TP = pl.TP;
+  if (threadIdx.x == 0) {
+    uint64_t p = 0;
+    for (int l = first; l < first + n; ++l) p += a.layer_params[l];
+    if (a.st_flags[rs] & 1) p += a.embed;
+    if (a.st_flags[rs] & 2) p += a.head;
+    pl.st_params[rs] = p;
+  }
+  const int Lc = a.uniform ? 1 : a.L;
+  for (int i = threadIdx.x; i < G * MB * TP; i += blockDim.x) {
+    double f = 0.0, b = 0.0;
+    if (a.uniform) {
+      f = (double)n * a.t_fwd[i];
+      b = (double)n * a.t_bwd[i];
+    } else {
+      const double *rf = a.t_fwd + (size_t)i * Lc, *rb = a.t_bwd + (size_t)i * Lc;
+      for (int l = first; l < first + n; ++l) { f += rf[l]; b += rb[l]; }
+    }
+    pl.st_c[(size_t)rs * G * MB * TP + i] = f + b;
+  }
+  for (int i = threadIdx.x; i < G * TP; i += blockDim.x) {
+    double u = 0.0;
+    if (a.uniform) {
+      u = (double)n * a.t_upd[i];
+    } else {
+      const double *ru = a.t_upd + (size_t)i * Lc;
+      for (int l = first; l < first + n; ++l) u += ru[l];
+    }
+    pl.st_u[(size_t)rs * G * TP + i] = u;
+  }
+}
+
+__device__ __forceinline__ uint64_t stage_bytes(const DevPlan &pl, uint32_t rs, int i, int P,
+                                                int tp, int64_t nb, uint64_t act) {
+  // model + activation bytes of a worker of stage i (Sec. 4.3); reserved bytes are added
+  // where the GPU type is known
+  uint64_t shard = (pl.st_params[rs + i] + (uint64_t)tp - 1) / (uint64_t)tp;
+  int64_t inflight = (int64_t)(P - i) < nb ? (int64_t)(P - i) : nb;
+  return shard * (uint64_t)pl.bpp + (uint64_t)inflight * (uint64_t)pl.st_n[rs + i] * act;
+}
+
+// Segment aggregates of one shape: everything of a segment that does not depend on
+// the pool it is placed on.
+__global__ void k_shape_agg(DevPlan pl) {
+  const uint32_t shp = blockIdx.x;
+  const ShapeRec sh = pl.shapes[shp];
+  const int G = pl.G, MB = pl.MB, TP = pl.TP, DP = pl.DP, P = sh.P;
+  const int t = threadIdx.x, nt = blockDim.x;
+  // need[tp][seg][mb][dp], smax, upd
+  for (int it = t; it < TP * 3 * MB * DP; it += nt) {
+    int d = it % DP, m = (it / DP) % MB, seg = (it / (DP * MB)) % 3, k = it / (DP * MB * 3);
+    uint64_t mx = 0;
+    int64_t nb = pl.nb[m * DP + d];
+    if (seg < sh.s && nb > 0) {
+      uint64_t act = pl.act[m * TP + k];
+      for (int i = sh.lo[seg]; i < sh.lo[seg] + sh.n[seg]; ++i) {
+        uint64_t b = stage_bytes(pl, sh.row_stage, i, P, pl.tpv[k], nb, act);
+        mx = b > mx ? b : mx;
+      }
+    }
+    pl.need[(agg_slot(pl, shp, k, seg) * MB + m) * DP + d] = mx;
+  }
+  for (int it = t; it < TP * 3; it += nt) {
+    int seg = it % 3, k = it / 3;
+    uint64_t mx = 0;
+    if (seg < sh.s)
+      for (int i = sh.lo[seg]; i < sh.lo[seg] + sh.n[seg]; ++i) {
+        uint64_t shard = (pl.st_params[sh.row_stage + i] + pl.tpv[k] - 1) / (uint64_t)pl.tpv[k];
+        mx = shard > mx ? shard : mx;
+      }
+    pl.smax[agg_slot(pl, shp, k, seg)] = (float)((double)mx * (double)pl.gb);
+  }
+  for (int it = t; it < TP * 3 * G; it += nt) {
+    int g = it % G, seg = (it / G) % 3, k = it / (G * 3);
+    double mx = 0.0;
+    if (seg < sh.s)
+      for (int i = sh.lo[seg]; i < sh.lo[seg] + sh.n[seg]; ++i)
+        mx = fmax(mx, pl.st_u[((size_t)(sh.row_stage + i) * G + g) * TP + k]);
+    pl.upd[agg_slot(pl, shp, k, seg) * G + g] = (float)mx;
+  }
+  for (int it = t; it < TP * 3 * G * MB; it += nt) {
+    int m = it % MB, g = (it / MB) % G, seg = (it / (MB * G)) % 3, k = it / (MB * G * 3);
+    float4 v = make_float4(0.f, 0.f, kNegInf, kNegInf);
+    if (seg < sh.s) {
+      const int lo = sh.lo[seg], n = sh.n[seg];
+      double sum = 0.0, mxi = -__builtin_huge_val(), fst = 0.0, lst = 0.0;
+      for (int i = lo; i < lo + n; ++i) {
+        double c = pl.st_c[(((size_t)(sh.row_stage + i) * G + g) * MB + m) * TP + k];
+        sum += c;
+        if (i == lo) fst = c;
+        if (i == lo + n - 1) lst = c;
+        if (i > lo && i < lo + n - 1) mxi = fmax(mxi, c);
+      }
+      v = make_float4((float)sum, (float)fst, (float)lst, (float)mxi);
+    }
+    pl.ta[(agg_slot(pl, shp, k, seg) * G + g) * MB + m] = v;
+  }
+  __syncthreads();
+  __threadfence();
+  // memok bit d: largest worker of the segment fits the type's memory
+  for (int it = t; it < TP * 3 * G * MB; it += nt) {
+    int m = it % MB, g = (it / MB) % G, seg = (it / (MB * G)) % 3, k = it / (MB * G * 3);
+    uint32_t bits = 0;
+    if (seg < sh.s)
+      for (int d = 0; d < DP; ++d) {
+        uint64_t need = pl.need[(agg_slot(pl, shp, k, seg) * MB + m) * DP + d];
+        if (pl.nb[m * DP + d] > 0 && need + pl.res[g] <= pl.cap[g]) bits |= 1u << d;
+      }
+    pl.memok[(agg_slot(pl, shp, k, seg) * G + g) * MB + m] = bits;
+  }
+}
+
+// ------------------------------------------------------------------ fp32 evaluation
+
+struct Rec {       // one segment placed on one pool, for one (mb, tp); 32 bytes
+  float sumT;      // sum of its stage times without the cross-segment transfers
+  float tF, tL;    // first / last stage time without the cross-segment transfers
+  float tI;        // slowest interior stage
+  float syncb;     // gradient bytes of the largest shard / intra-zone bandwidth
+  float upd;       // slowest update
+  float pricen;    // stages * $/h
+  uint32_t bits;   // bit d: valid for dp index d (memory, quota, batch, H1)
+};
+
+struct LaneC {     // scalars of a (mb, dp, tp) triple
+  float p2pf, nbm1, cd, dtp, xb;
+};
+
+__device__ __forceinline__ Rec make_rec(float4 ta, float smax, float upd, float price, float p2pf,
+                                        float ibw_zz, int n, uint32_t bits) {
+  Rec r;
+  const float w = p2pf * ibw_zz;  // one transfer inside the zone
+  r.sumT = fmaf((float)(2 * (n - 1)), w, ta.x);
+  r.tF = (n == 1) ? ta.y : ta.y + w;
+  r.tL = (n == 1) ? kNegInf : ta.z + w;
+  r.tI = (n >= 3) ? fmaf(2.0f, w, ta.w) : kNegInf;
+  r.syncb = smax * ibw_zz;
+  r.upd = upd;
+  r.pricen = (float)n * price;
+  r.bits = bits;
+  return r;
+}
+
+// Iteration time and cost of a plan from its segment records.  wf[j] / wb[j]: time of the
+// activation / gradient transfer across the boundary between segments j and j+1;
+// eg = sum over boundaries of the two-way egress price.
+template <int S>
+__device__ __forceinline__ void combine(const Rec *r, const float *wf, const float *wb, float eg,
+                                        const bool *single, const LaneC &lc, float &T, float &C) {
+  float tmax = kNegInf, sum = 0.f, syn = 0.f, up = 0.f, pr = 0.f;
+#pragma unroll
+  for (int j = 0; j < S; ++j) {
+    float tf = r[j].tF;
+    if (j > 0) tf += wb[j - 1];
+    if (j < S - 1 && single[j]) tf += wf[j];
+    float tl = r[j].tL;
+    if (j < S - 1) tl += wf[j];
+    tmax = fmaxf(tmax, fmaxf(fmaxf(tf, tl), r[j].tI));
+    sum += r[j].sumT;
+    syn = fmaxf(syn, r[j].syncb);
+    up = fmaxf(up, r[j].upd);
+    pr += r[j].pricen;
+  }
+#pragma unroll
+  for (int j = 0; j < S - 1; ++j) sum += wf[j] + wb[j];
+  const float tpp = fmaf(lc.nbm1, tmax, sum);
+  T = (tpp + lc.cd * syn) + up;
+  C = fmaf(pr * lc.dtp, T, lc.xb * eg);
+}
+
+// bit d set when n stages with D = dpv[d] replicas of tp GPUs fit into avail GPUs
+__device__ __forceinline__ uint32_t quota_bits(const DevPlan &pl, int n, int tp, int avail) {
+  uint32_t bits = 0;
+  for (int d = 0; d < pl.DP; ++d)
+    if ((int64_t)n * pl.dpv[d] * tp <= (int64_t)avail) bits |= 1u << d;
+  return bits;
+}
+
+enum { MODE_SCAN = 0, MODE_COLLECT = 1 };
+
+struct ScanArgs {
+  float *umin_s, *umin_l;   // [n_units] minima over strictly / loosely constrained candidates
+  uint32_t *counters;       // see Counter
+  const uint32_t *tau_src;  // COLLECT: fp32 bits of the threshold, scaled by band
+  float band;
+  float lim_s, lim_l;       // constraint limits (strict, loose) on cost or on time
+  SurvRec *surv;
+  uint32_t surv_cap;
+};
+
+enum Counter { CNT_SURV = 0, CNT_REF = 1, CNT_FEAS = 2, CNT_GMIN = 3, CNT_TAU0 = 4, CNT_TAU1 = 5,
+               CNT_COUNT = 8 };
+
+__global__ void k_init_counters(uint32_t *c) {
+  if (threadIdx.x < CNT_COUNT)
+    c[threadIdx.x] = (threadIdx.x >= CNT_GMIN) ? 0x7f800000u : 0u;
+}
+
+template <int S, int MODE, int OBJ, bool HASB>
+__device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, const UnitRec &u,
+                                          const ShapeRec &sh, const Rec *rec, const float4 *pair,
+                                          const uint32_t *q13, float &ms, float &ml) {
+  const int ZG = pl.ZG, G = pl.G, MB = pl.MB, DP = pl.DP, Z = pl.Z;
+  const int nin = MB * DP * ZG;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwave = blockDim.x >> 6;
+  const bool single[3] = {sh.n[0] == 1, sh.n[1] == 1, sh.n[2] == 1};
+  const int tp = u.tp;
+  for (int e0 = wave * 64; e0 < nin; e0 += nwave * 64) {
+    const int e = e0 + lane;
+    const bool active = e < nin;
+    const int ee = active ? e : 0;
+    const int mb = ee % MB, dp = (ee / MB) % DP, a1 = ee / (MB * DP);
+    LaneC lc;
+    lc.p2pf = pl.p2p_f[mb];
+    lc.nbm1 = pl.nbm1_f[mb * DP + dp];
+    lc.cd = pl.cd_f[dp];
+    lc.dtp = pl.dtp_f[tp * DP + dp];
+    lc.xb = pl.xb_f[mb];
+    const uint32_t dpbit = active ? (1u << dp) : 0u;
+    const int z1 = a1 / G;
+    Rec r[3];
+    float wf[2] = {0.f, 0.f}, wb[2] = {0.f, 0.f};
+    r[0] = rec[(0 * ZG + a1) * MB + mb];
+    // index of the candidate with outer digits 0
+    const uint64_t idx0 = sh.base + (uint64_t)(mb + MB * (tp + pl.TP * (dp + DP * a1)));
+    const int n_o = (S >= 2) ? u.o_cnt : 1;
+    for (int oi = 0; oi < n_o; ++oi) {
+      const int r2 = u.o_lo + oi;
+      int a2 = 0, z2 = 0;
+      float eg2 = 0.f;
+      if (S >= 2) {
+        a2 = a1 + 1 + r2;
+        if (a2 >= ZG) a2 -= ZG;
+        z2 = a2 / G;
+        r[1] = rec[(1 * ZG + a2) * MB + mb];
+        const float4 pr = pair[z1 * Z + z2];
+        wf[0] = lc.p2pf * pr.x;
+        wb[0] = lc.p2pf * pr.y;
+        eg2 = pr.z;
+      }
+      const int n_o3 = (S == 3) ? ZG - 1 : 1;
+      for (int r3 = 0; r3 < n_o3; ++r3) {
+        float eg = eg2;
+        uint32_t bits = r[0].bits & dpbit;
+        if (S >= 2) bits &= r[1].bits;
+        if (S == 3) {
+          int a3 = a2 + 1 + r3;
+          if (a3 >= ZG) a3 -= ZG;
+          const int z3 = a3 / G;
+          r[2] = rec[(2 * ZG + a3) * MB + mb];
+          const float4 pr = pair[z2 * Z + z3];
+          wf[1] = lc.p2pf * pr.x;
+          wb[1] = lc.p2pf * pr.y;
+          eg += pr.z;
+          bits &= r[2].bits;
+          if (a3 == a1) bits &= q13[a1];  // segments 1 and 3 share one pool's quota
+        }
+        float T, C;
+        combine<S>(r, wf, wb, eg, single, lc, T, C);
+        const float key = OBJ == 0 ? T : C;
+        const float con = OBJ == 0 ? C : T;
+        const bool feas = bits != 0;
+        const bool strict = feas && (!HASB || con <= a.lim_s);
+        const bool loose = feas && (!HASB || con <= a.lim_l);
+        if (MODE == MODE_SCAN) {
+          if (strict) ms = fminf(ms, key);
+          if (HASB && loose) ml = fminf(ml, key);
+        } else {
+          const float tau = __uint_as_float(*a.tau_src) * a.band;
+          if (loose && key <= tau) {
+            uint32_t slot = atomicAdd(&a.counters[CNT_SURV], 1u);
+            if (slot < a.surv_cap) {
+              SurvRec sv;
+              sv.idx = idx0 + (uint64_t)pl.inner * (uint64_t)(r2 + (S == 3 ? (ZG - 1) * r3 : 0));
+              sv.key = strict ? key : kPosInf;
+              sv.key_loose = key;
+              a.surv[slot] = sv;
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// One workgroup per unit: stage the unit's segment records in LDS, then every lane walks
+// its (mb, dp, pool 1) triple over the unit's outer pool digits.
+template <int MODE, int OBJ, bool HASB>
+__global__ __launch_bounds__(kUnitThreads) void k_units(DevPlan pl, ScanArgs a) {
+  extern __shared__ uint4 lds_raw[];
+  const UnitRec u = pl.units[blockIdx.x];
+  if (MODE == MODE_COLLECT) {
+    const float tau = __uint_as_float(*a.tau_src) * a.band;
+    if (!(a.umin_l[blockIdx.x] <= tau)) return;  // uniform over the workgroup
+  }
+  const ShapeRec sh = pl.shapes[u.shape];
+  const int ZG = pl.ZG, G = pl.G, MB = pl.MB, Z = pl.Z, S = sh.s;
+  Rec *rec = reinterpret_cast<Rec *>(lds_raw);                      // [S][ZG][MB]
+  float4 *pair = reinterpret_cast<float4 *>(rec + 3 * ZG * MB);     // [Z][Z]
+  uint32_t *qm = reinterpret_cast<uint32_t *>(pair + Z * Z);        // [3][ZG]
+  uint32_t *q13 = qm + 3 * ZG;                                      // [ZG]
+  __shared__ float red[2][kUnitThreads / 64];
+  const int t = threadIdx.x;
+  const int tpv = pl.tpv[u.tp];
+
+  for (int i = t; i < S * ZG; i += blockDim.x) {
+    const int seg = i / ZG, p = i % ZG, g = p % G;
+    uint32_t b = quota_bits(pl, sh.n[seg], tpv, pl.avail[p]);
+    if (tpv > pl.node[g]) b = 0;  // H1: tensor parallelism stays inside a node
+    qm[i] = b;
+  }
+  if (S == 3)
+    for (int p = t; p < ZG; p += blockDim.x)
+      q13[p] = quota_bits(pl, sh.n[0] + sh.n[2], tpv, pl.avail[p]);
+  for (int i = t; i < Z * Z; i += blockDim.x) {
+    const int za = i / Z, zb = i % Z;
+    pair[i] = make_float4(pl.ibw_f[za * Z + zb], pl.ibw_f[zb * Z + za], pl.egs_f[i], 0.f);
+  }
+  __syncthreads();
+  for (int i = t; i < S * ZG * MB; i += blockDim.x) {
+    const int mb = i % MB, p = (i / MB) % ZG, seg = i / (MB * ZG);
+    const int g = p % G, z = p / G;
+    const size_t sl = agg_slot(pl, u.shape, u.tp, seg);
+    const float4 ta = pl.ta[(sl * G + g) * MB + mb];
+    const uint32_t bits = pl.memok[(sl * G + g) * MB + mb] & qm[seg * ZG + p] & pl.divis[mb];
+    rec[(seg * ZG + p) * MB + mb] = make_rec(ta, pl.smax[sl], pl.upd[sl * G + g], pl.price_f[g],
+                                             pl.p2p_f[mb], pl.ibw_f[z * Z + z], sh.n[seg], bits);
+  }
+  __syncthreads();
+
+  float ms = kPosInf, ml = kPosInf;
+  if (S == 1) unit_body<1, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, ms, ml);
+  else if (S == 2) unit_body<2, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, ms, ml);
+  else unit_body<3, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, ms, ml);
+
+  if (MODE == MODE_SCAN) {
+    if (!HASB) ml = ms;
+    ms = wave_min(ms);
+    ml = wave_min(ml);
+    if ((t & 63) == 0) { red[0][t >> 6] = ms; red[1][t >> 6] = ml; }
+    __syncthreads();
+    if (t == 0) {
+      for (int w = 1; w < (int)(blockDim.x >> 6); ++w) {
+        ms = fminf(ms, red[0][w]);
+        ml = fminf(ml, red[1][w]);
+      }
+      a.umin_s[blockIdx.x] = ms;
+      a.umin_l[blockIdx.x] = ml;
+      // keys are non-negative, so their bit patterns order like unsigned integers
+      if (ms < kPosInf) atomicMin(&a.counters[CNT_GMIN], __float_as_uint(ms));
+    }
+  }
+}
+
+// ------------------------------------------------------------------ k-th smallest key
+
+// Radix select (11 + 11 + 10 bits) of the k-th smallest non-negative float among
+// n = min(*count, cap) values read with a stride; fewer than k values yield +inf.
+// One workgroup.  The result's bit pattern goes to *out.
+__global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stride_words,
+                                                     const uint32_t *count, uint32_t cap,
+                                                     uint32_t k, uint32_t *out) {
+  __shared__ uint32_t hist[2048];
+  __shared__ uint32_t s_prefix, s_k, s_done;
+  const uint32_t n = count ? min(*count, cap) : cap;
+  const int t = threadIdx.x;
+  if (t == 0) { s_prefix = 0; s_k = k; s_done = 0; }
+  const int shifts[3] = {21, 10, 0}, widths[3] = {11, 11, 10};
+  for (int pass = 0; pass < 3; ++pass) {
+    for (int i = t; i < 2048; i += blockDim.x) hist[i] = 0;
+    __syncthreads();
+    const int sh = shifts[pass], wd = widths[pass];
+    const uint32_t prefix = s_prefix;
+    if (!s_done)
+      for (uint32_t i = t; i < n; i += blockDim.x) {
+        uint32_t x = __float_as_uint(vals[(size_t)i * stride_words]);
+        bool match = pass == 0 || (x >> (sh + wd)) == prefix;
+        if (match) atomicAdd(&hist[(x >> sh) & ((1u << wd) - 1)], 1u);
+      }
+    __syncthreads();
+    if (t == 0 && !s_done) {
+      uint32_t cum = 0, kk = s_k, bin = 0;
+      bool found = false;
+      for (uint32_t b = 0; b < (1u << wd); ++b) {
+        if (cum + hist[b] >= kk) { bin = b; found = true; break; }
+        cum += hist[b];
+      }
+      if (!found) { s_done = 1; s_prefix = 0x7f800000u; }
+      else { s_prefix = (prefix << wd) | bin; s_k = kk - cum; }
+    }
+    __syncthreads();
+  }
+  if (t == 0) *out = s_prefix;
+}
+
+// ------------------------------------------------------------------ fp64 re-evaluation
+
+struct Cand {
+  uint32_t shape;
+  int P, s, mb, tp, dp;      // indices into the value lists
+  int a[3];
+  int k1, k2;
+};
+
+__device__ __forceinline__ bool decode_index(const DevPlan &pl, uint64_t idx, Cand &c) {
+  if (idx >= pl.N) return false;
+  int b = 0;
+  for (int i = 0; i < pl.n_blocks; ++i)
+    if (idx >= pl.blocks[i].off) b = i;  // blocks are ordered and non-empty
+  const BlockRec blk = pl.blocks[b];
+  const uint64_t r = idx - blk.off;
+  const uint32_t sl = (uint32_t)(r / blk.shape_size);
+  uint32_t rem = (uint32_t)(r % blk.shape_size);
+  c.shape = blk.first_shape + sl;
+  c.P = blk.P;
+  c.s = blk.s;
+  const uint32_t in = rem % pl.inner;
+  uint32_t o = rem / pl.inner;
+  c.mb = in % pl.MB;
+  c.tp = (in / pl.MB) % pl.TP;
+  c.dp = (in / (pl.MB * pl.TP)) % pl.DP;
+  c.a[0] = in / (pl.MB * pl.TP * pl.DP);
+  c.a[1] = c.a[2] = -1;
+  if (c.s >= 2) {
+    c.a[1] = (c.a[0] + 1 + (int)(o % (pl.ZG - 1))) % pl.ZG;
+    o /= (pl.ZG - 1);
+  }
+  if (c.s == 3) c.a[2] = (c.a[1] + 1 + (int)o) % pl.ZG;
+  const ShapeRec sh = pl.shapes[c.shape];
+  c.k1 = sh.k1;
+  c.k2 = sh.k2;
+  return true;
+}
+
+// Stage-by-stage evaluation of one plan in fp64 and exact integers (Sec. 4.3).
+__device__ void eval_exact(const DevPlan &pl, const Cand &c, int objective, int has_bound,
+                           double bound, double &T, double &C, uint64_t &peak, uint32_t &mask) {
+  const int G = pl.G, Z = pl.Z, MB = pl.MB, TP = pl.TP, DP = pl.DP, P = c.P;
+  const ShapeRec sh = pl.shapes[c.shape];
+  const uint32_t rs = sh.row_stage;
+  const int64_t D = pl.dpv[c.dp], tp = pl.tpv[c.tp];
+  mask = 0;
+  peak = 0;
+  const int64_t nb = pl.nb[c.mb * DP + c.dp];
+  if (nb == 0) {
+    mask = 4u;  // batch not divisible
+    T = C = __builtin_huge_val();
+    return;
+  }
+  const uint64_t act = pl.act[c.mb * TP + c.tp];
+  const double p2p = (double)pl.p2p[c.mb];
+  // quota per pool and H1
+  for (int j = 0; j < c.s; ++j) {
+    int64_t stages = sh.n[j];
+    for (int j2 = 0; j2 < c.s; ++j2)
+      if (j2 != j && c.a[j2] == c.a[j]) stages += sh.n[j2];
+    if (stages * D * tp > (int64_t)pl.avail[c.a[j]]) mask |= 2u;
+    if (tp > pl.node[c.a[j] % G]) mask |= 8u;
+  }
+  double sum_t = 0.0, max_t = 0.0, t_sync = 0.0, t_upd = 0.0, dollars = 0.0, comm = 0.0;
+  for (int i = 0; i < P; ++i) {
+    const int seg = i < c.k1 ? 0 : (i < c.k2 ? 1 : 2);
+    const int g = c.a[seg] % G, z = c.a[seg] / G;
+    const uint64_t m = stage_bytes(pl, rs, i, P, (int)tp, nb, act) + pl.res[g];
+    if (m > pl.cap[g]) mask |= 1u;
+    peak = m > peak ? m : peak;
+    double x = 0.0;
+    if (i < P - 1) {
+      const int sn = (i + 1) < c.k1 ? 0 : ((i + 1) < c.k2 ? 1 : 2);
+      const int zn = c.a[sn] / G;
+      x += p2p / pl.bw[z * Z + zn];
+      if (pl.egress && zn != z)
+        comm += (double)nb * (double)D * p2p * (pl.egress[z * Z + zn] + pl.egress[zn * Z + z]);
+    }
+    if (i > 0) {
+      const int sp = (i - 1) < c.k1 ? 0 : ((i - 1) < c.k2 ? 1 : 2);
+      x += p2p / pl.bw[z * Z + c.a[sp] / G];
+    }
+    const double t = pl.st_c[(((size_t)(rs + i) * G + g) * MB + c.mb) * TP + c.tp] + x;
+    sum_t += t;
+    max_t = fmax(max_t, t);
+    if (D > 1) {
+      const uint64_t shard = (pl.st_params[rs + i] + (uint64_t)tp - 1) / (uint64_t)tp;
+      const double sync = 2.0 * (double)(D - 1) / (double)D * ((double)shard * (double)pl.gb) /
+                          pl.bw[z * Z + z];
+      t_sync = fmax(t_sync, sync);
+    }
+    t_upd = fmax(t_upd, pl.st_u[((size_t)(rs + i) * G + g) * TP + c.tp]);
+    dollars += (double)(D * tp) * pl.price[g];
+  }
+  T = (sum_t + (double)(nb - 1) * max_t) + t_sync + t_upd;
+  C = dollars / 3600.0 * T + comm;
+  if (has_bound) {
+    if (objective == 0) { if (C > bound) mask |= 32u; }
+    else if (1.0 / T < bound) mask |= 32u;
+  }
+}
+
+struct RefineArgs {
+  const SurvRec *surv;
+  uint32_t surv_cap;
+  uint32_t *counters;
+  const uint32_t *tau_src;  // NULL: take every survivor
+  float band;
+  RefRec *ref;
+  uint32_t ref_cap;
+  int objective, has_bound;
+  double bound;
+};
+
+__global__ void k_refine(DevPlan pl, RefineArgs a) {
+  const uint32_t n = min(a.counters[CNT_SURV], a.surv_cap);
+  const float tau = a.tau_src ? __uint_as_float(*a.tau_src) * a.band : kPosInf;
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    const SurvRec sv = a.surv[i];
+    if (!(sv.key_loose <= tau)) continue;
+    Cand c;
+    if (!decode_index(pl, sv.idx, c)) continue;
+    RefRec r;
+    r.idx = sv.idx;
+    r.pad = 0;
+    eval_exact(pl, c, a.objective, a.has_bound, a.bound, r.T, r.C, r.mem, r.mask);
+    const uint32_t slot = atomicAdd(&a.counters[CNT_REF], 1u);
+    if (slot < a.ref_cap) a.ref[slot] = r;
+    if (r.mask == 0) atomicAdd(&a.counters[CNT_FEAS], 1u);
+  }
+}
+
+__device__ __forceinline__ bool lex_less(double ka, uint64_t ia, double kb, uint64_t ib) {
+  return ka < kb || (ka == kb && ia < ib);
+}
+
+// Best plan: minimum fp64 key over valid candidates, then the lowest index within the
+// tie tolerance of it.  One workgroup; results go to host-mapped memory.
+__global__ __launch_bounds__(1024) void k_pick_best(const RefRec *ref, uint32_t ref_cap,
+                                                    const uint32_t *counters, int objective,
+                                                    ResultHeader *hdr, RefRec *out) {
+  __shared__ double s_key[1024];
+  __shared__ unsigned long long s_idx[1024];
+  __shared__ uint32_t s_pos[1024];
+  const uint32_t n = min(counters[CNT_REF], ref_cap);
+  const int t = threadIdx.x;
+  double best = __builtin_huge_val();
+  for (uint32_t i = t; i < n; i += blockDim.x)
+    if (ref[i].mask == 0) best = fmin(best, objective == 0 ? ref[i].T : ref[i].C);
+  s_key[t] = best;
+  __syncthreads();
+  for (int w = 512; w >= 1; w >>= 1) {
+    if (t < w) s_key[t] = fmin(s_key[t], s_key[t + w]);
+    __syncthreads();
+  }
+  const double limit = s_key[0] * (1.0 + kTieTol);
+  __syncthreads();
+  unsigned long long bi = ~0ull;
+  uint32_t bp = 0;
+  for (uint32_t i = t; i < n; i += blockDim.x) {
+    const double key = objective == 0 ? ref[i].T : ref[i].C;
+    if (ref[i].mask == 0 && key <= limit && ref[i].idx < bi) { bi = ref[i].idx; bp = i; }
+  }
+  s_idx[t] = bi;
+  s_pos[t] = bp;
+  __syncthreads();
+  for (int w = 512; w >= 1; w >>= 1) {
+    if (t < w && s_idx[t + w] < s_idx[t]) { s_idx[t] = s_idx[t + w]; s_pos[t] = s_pos[t + w]; }
+    __syncthreads();
+  }
+  if (t == 0) {
+    const bool found = s_idx[0] != ~0ull;
+    if (found) out[0] = ref[s_pos[0]];
+    hdr->n_found = found ? 1u : 0u;
+    hdr->surv_count = counters[CNT_SURV];
+    hdr->ref_count = counters[CNT_REF];
+    hdr->feasible_count = counters[CNT_FEAS];
+  }
+}
+
+// Top-k: the rank of every valid re-evaluated candidate in ascending (key, index) order,
+// by counting; ranks below k are written to host-mapped memory.
+__global__ void k_rank_topk(const RefRec *ref, uint32_t ref_cap, const uint32_t *counters,
+                            int objective, uint32_t k, ResultHeader *hdr, RefRec *out) {
+  const uint32_t n = min(counters[CNT_REF], ref_cap);
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i == 0) {
+    const uint32_t f = counters[CNT_FEAS];
+    hdr->n_found = f < k ? f : k;
+    hdr->surv_count = counters[CNT_SURV];
+    hdr->ref_count = counters[CNT_REF];
+    hdr->feasible_count = f;
+  }
+  if (i >= n) return;
+  const RefRec me = ref[i];
+  if (me.mask != 0) return;
+  const double mk = objective == 0 ? me.T : me.C;
+  uint32_t rank = 0;
+  for (uint32_t j = 0; j < n; ++j) {
+    const double kj = objective == 0 ? ref[j].T : ref[j].C;
+    if (ref[j].mask == 0 && lex_less(kj, ref[j].idx, mk, me.idx)) ++rank;
+  }
+  if (rank < k) out[rank] = me;
+}
+
+// ------------------------------------------------------------------ eval_batch
+
+struct EvalArgs {
+  uint64_t first, count;
+  const uint64_t *indices;
+  float *time, *cost;
+  uint64_t *mem;
+  uint32_t *mask;
+  int objective, has_bound;
+  float bound;
+};
+
+template <int S>
+__device__ __forceinline__ void eval_direct_s(const DevPlan &pl, const Cand &c, const ShapeRec &sh,
+                                              const LaneC &lc, float &T, float &C, uint64_t &peak,
+                                              uint32_t &mask) {
+  const int G = pl.G, Z = pl.Z, MB = pl.MB, DP = pl.DP;
+  const int tpv = pl.tpv[c.tp];
+  const int64_t D = pl.dpv[c.dp];
+  Rec r[S];
+  float wf[2] = {0.f, 0.f}, wb[2] = {0.f, 0.f}, eg = 0.f;
+  bool single[3] = {sh.n[0] == 1, sh.n[1] == 1, sh.n[2] == 1};
+#pragma unroll
+  for (int j = 0; j < S; ++j) {
+    const int p = c.a[j], g = p % G, z = p / G;
+    const size_t sl = agg_slot(pl, c.shape, c.tp, j);
+    r[j] = make_rec(pl.ta[(sl * G + g) * MB + c.mb], pl.smax[sl], pl.upd[sl * G + g], pl.price_f[g],
+                    lc.p2pf, pl.ibw_f[z * Z + z], sh.n[j], 0u);
+    const uint64_t m = pl.need[(sl * MB + c.mb) * DP + c.dp] + pl.res[g];
+    if (m > pl.cap[g]) mask |= 1u;
+    peak = m > peak ? m : peak;
+    int64_t stages = sh.n[j];
+    if (S == 3 && (j == 0 || j == 2) && c.a[0] == c.a[2]) stages = sh.n[0] + sh.n[2];
+    if (stages * D * tpv > (int64_t)pl.avail[p]) mask |= 2u;
+    if (tpv > pl.node[g]) mask |= 8u;
+    if (j > 0) {
+      const int zp = c.a[j - 1] / G;
+      wf[j - 1] = lc.p2pf * pl.ibw_f[zp * Z + z];
+      wb[j - 1] = lc.p2pf * pl.ibw_f[z * Z + zp];
+      eg += pl.egs_f[zp * Z + z];
+    }
+  }
+  combine<S>(r, wf, wb, eg, single, lc, T, C);
+}
+
+// One lane per candidate; reads the segment aggregates straight from global memory.
+__global__ __launch_bounds__(256) void k_eval_direct(DevPlan pl, EvalArgs a) {
+  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= a.count) return;
+  const uint64_t idx = a.indices ? a.indices[i] : a.first + i;
+  float T = kPosInf, C = kPosInf;
+  uint64_t peak = 0;
+  uint32_t mask = 0xFFFFFFFFu;
+  Cand c;
+  if (decode_index(pl, idx, c)) {
+    mask = 0;
+    const int nb = pl.nb[c.mb * pl.DP + c.dp];
+    if (nb == 0) {
+      mask = 4u;
+    } else {
+      const ShapeRec sh = pl.shapes[c.shape];
+      LaneC lc;
+      lc.p2pf = pl.p2p_f[c.mb];
+      lc.nbm1 = pl.nbm1_f[c.mb * pl.DP + c.dp];
+      lc.cd = pl.cd_f[c.dp];
+      lc.dtp = pl.dtp_f[c.tp * pl.DP + c.dp];
+      lc.xb = pl.xb_f[c.mb];
+      if (c.s == 1) eval_direct_s<1>(pl, c, sh, lc, T, C, peak, mask);
+      else if (c.s == 2) eval_direct_s<2>(pl, c, sh, lc, T, C, peak, mask);
+      else eval_direct_s<3>(pl, c, sh, lc, T, C, peak, mask);
+      if (a.has_bound) {
+        if (a.objective == 0) { if (C > a.bound) mask |= 32u; }
+        else if (1.0f / T < a.bound) mask |= 32u;
+      }
+    }
+  }
+  if (a.time) a.time[i] = T;
+  if (a.cost) a.cost[i] = C;
+  if (a.mem) a.mem[i] = peak;
+  if (a.mask) a.mask[i] = mask;
+}
+
+}  // namespace sailor
