@@ -74,7 +74,7 @@ struct sailor_plan {
   void *h_result = nullptr;
   ResultHeader *d_hdr = nullptr;
   RefRec *d_out = nullptr;
-  hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};  // start, scan end, end, scan start
   bool timing_valid = false, scan_timed = false;
 };
 
@@ -230,11 +230,11 @@ sailor_status build_space(const sailor_problem *p, sailor_plan *pl, std::vector<
   pl->dev.inner = (uint32_t)inner;
   pl->dev.n_row_stages = (int)row_stage;
 
-  // scan units: (shape, tp, range of the relative pool digit of segment 2)
+  // scan units: (shape, tp, range of segment 2's pool)
   const uint64_t innerp = (uint64_t)p->n_mb * p->n_dp * ZG;
   for (uint32_t si = 0; si < pl->shapes.size(); ++si) {
     const ShapeRec &sh = pl->shapes[si];
-    const int n_o = sh.s >= 2 ? ZG - 1 : 1;
+    const int n_o = sh.s >= 2 ? ZG : 1;
     const uint64_t per_o = sh.s == 3 ? innerp * (uint64_t)(ZG - 1) : innerp;
     int chunk = (int)std::min<uint64_t>((uint64_t)n_o, std::max<uint64_t>(1, kUnitTarget / per_o));
     const int n_chunks = (n_o + chunk - 1) / chunk;
@@ -344,6 +344,7 @@ sailor_status run_selection(sailor_plan *pl, sailor_objective obj, const sailor_
 
   HIP_TRY(hipEventRecord(pl->ev[0], st));
   k_init_counters<<<1, 64, 0, st>>>(pl->counters);
+  HIP_TRY(hipEventRecord(pl->ev[3], st));
   launch_units<MODE_SCAN>(pl, obj, has_bound, sa, st);
   HIP_TRY(hipEventRecord(pl->ev[1], st));
   if (best) {
@@ -376,7 +377,7 @@ sailor_status run_selection(sailor_plan *pl, sailor_objective obj, const sailor_
   if (best) {
     k_pick_best<<<1, 1024, 0, st>>>(pl->ref, kRefCap, pl->counters, (int)obj, pl->d_hdr, pl->d_out);
   } else {
-    k_rank_topk<<<kRefCap / 256, 256, 0, st>>>(pl->ref, kRefCap, pl->counters, (int)obj, k,
+    k_rank_topk<<<64, 256, 0, st>>>(pl->ref, kRefCap, pl->counters, (int)obj, k,
                                                pl->d_hdr, pl->d_out);
   }
   HIP_TRY(hipEventRecord(pl->ev[2], st));
@@ -615,7 +616,7 @@ sailor_status sailor_plan_last_timing(sailor_plan *pl, float *total_ms, float *s
   HIP_TRY(hipEventSynchronize(pl->ev[2]));
   float t = 0.f, s = 0.f;
   HIP_TRY(hipEventElapsedTime(&t, pl->ev[0], pl->ev[2]));
-  if (pl->scan_timed) HIP_TRY(hipEventElapsedTime(&s, pl->ev[0], pl->ev[1]));
+  if (pl->scan_timed) HIP_TRY(hipEventElapsedTime(&s, pl->ev[3], pl->ev[1]));
   if (total_ms) *total_ms = t;
   if (scan_ms) *scan_ms = s;
   return SAILOR_OK;

@@ -40,8 +40,8 @@ struct BlockRec {       // all candidates with one (pp index, segment count)
   uint32_t pp_idx, s, P;
 };
 
-struct UnitRec {        // work of one workgroup of the scan: one shape, one tp, a range of
-  uint32_t shape;       // the relative-pool digit of segment 2
+struct UnitRec {        // work of one workgroup of the scan: one shape, one tp, a range
+  uint32_t shape;       // [o_lo, o_lo + o_cnt) of segment 2's pool
   uint16_t tp, s;
   uint16_t o_lo, o_cnt;
 };

@@ -224,31 +224,58 @@ __device__ __forceinline__ Rec make_rec(float4 ta, float smax, float upd, float 
   return r;
 }
 
-// Iteration time and cost of a plan from its segment records.  wf[j] / wb[j]: time of the
-// activation / gradient transfer across the boundary between segments j and j+1;
-// eg = sum over boundaries of the two-way egress price.
-template <int S>
-__device__ __forceinline__ void combine(const Rec *r, const float *wf, const float *wb, float eg,
-                                        const bool *single, const LaneC &lc, float &T, float &C) {
-  float tmax = kNegInf, sum = 0.f, syn = 0.f, up = 0.f, pr = 0.f;
-#pragma unroll
-  for (int j = 0; j < S; ++j) {
-    float tf = r[j].tF;
-    if (j > 0) tf += wb[j - 1];
-    if (j < S - 1 && single[j]) tf += wf[j];
-    float tl = r[j].tL;
-    if (j < S - 1) tl += wf[j];
-    tmax = fmaxf(tmax, fmaxf(fmaxf(tf, tl), r[j].tI));
-    sum += r[j].sumT;
-    syn = fmaxf(syn, r[j].syncb);
-    up = fmaxf(up, r[j].upd);
-    pr += r[j].pricen;
-  }
-#pragma unroll
-  for (int j = 0; j < S - 1; ++j) sum += wf[j] + wb[j];
-  const float tpp = fmaf(lc.nbm1, tmax, sum);
-  T = (tpp + lc.cd * syn) + up;
-  C = fmaf(pr * lc.dtp, T, lc.xb * eg);
+// Iteration time and cost of a plan, accumulated segment by segment.  Everything that
+// depends only on the leading segments is finished before the pool of the next segment
+// is known, so the scan hoists it out of its inner loops; the order of the floating
+// point additions is fixed here, and both evaluation kernels go through these steps, so
+// they return bit-identical values.
+struct Acc {
+  float tmax;  // slowest stage of the closed segments
+  float sum;   // sum of stage times incl. the transfers across closed boundaries
+  float syn, up, pr, egs;
+  float tf, tl, ti;  // open segment: first / last / slowest interior stage
+};
+
+// the first segment
+__device__ __forceinline__ Acc acc_begin(const Rec &r) {
+  Acc a;
+  a.tmax = kNegInf;
+  a.sum = r.sumT;
+  a.syn = r.syncb;
+  a.up = r.upd;
+  a.pr = r.pricen;
+  a.egs = 0.f;
+  a.tf = r.tF;
+  a.tl = r.tL;
+  a.ti = r.tI;
+  return a;
+}
+
+// Closes the open segment over a boundary with transfer times wf (activations, sent by the
+// open segment's last stage) and wb (gradients, sent by the next segment's first stage),
+// and opens segment r behind it.
+__device__ __forceinline__ Acc acc_cross(const Acc &p, const Rec &r, float wf, float wb, float eg,
+                                         bool open_is_single, bool first_boundary) {
+  Acc a;
+  const float tf = open_is_single ? p.tf + wf : p.tf;
+  a.tmax = fmaxf(p.tmax, fmaxf(fmaxf(tf, p.tl + wf), p.ti));
+  a.sum = (p.sum + r.sumT) + (wf + wb);
+  a.syn = fmaxf(p.syn, r.syncb);
+  a.up = fmaxf(p.up, r.upd);
+  a.pr = p.pr + r.pricen;
+  a.egs = first_boundary ? eg : p.egs + eg;
+  a.tf = r.tF + wb;
+  a.tl = r.tL;
+  a.ti = r.tI;
+  return a;
+}
+
+// Closes the last segment: T_iter = T_pp + T_sync + T_update, C_iter = C_comp + C_comm.
+__device__ __forceinline__ void acc_finish(const Acc &p, const LaneC &lc, float &T, float &C) {
+  const float tmax = fmaxf(p.tmax, fmaxf(fmaxf(p.tf, p.tl), p.ti));
+  const float tpp = fmaf(lc.nbm1, tmax, p.sum);
+  T = fmaf(lc.cd, p.syn, tpp) + p.up;
+  C = fmaf(p.pr * lc.dtp, T, lc.xb * p.egs);
 }
 
 // bit d set when n stages with D = dpv[d] replicas of tp GPUs fit into avail GPUs
@@ -279,14 +306,48 @@ __global__ void k_init_counters(uint32_t *c) {
     c[threadIdx.x] = (threadIdx.x >= CNT_GMIN) ? 0x7f800000u : 0u;
 }
 
+// One candidate of the scan: update the running minima, or append it to the survivors.
+template <int MODE, int OBJ, bool HASB>
+__device__ __forceinline__ void visit(const ScanArgs &a, float T, float C, bool feas, float tau,
+                                      uint64_t idx, float &ms, float &ml) {
+  const float key = OBJ == 0 ? T : C;
+  const float con = OBJ == 0 ? C : T;
+  if (MODE == MODE_SCAN) {
+    const float kf = feas ? key : kPosInf;
+    if (HASB) {
+      ms = fminf(ms, con <= a.lim_s ? kf : kPosInf);
+      ml = fminf(ml, con <= a.lim_l ? kf : kPosInf);
+    } else {
+      ms = fminf(ms, kf);
+    }
+  } else {
+    const bool loose = feas && (!HASB || con <= a.lim_l);
+    if (loose && key <= tau) {
+      const bool strict = !HASB || con <= a.lim_s;
+      const uint32_t slot = atomicAdd(&a.counters[CNT_SURV], 1u);
+      if (slot < a.surv_cap) {
+        SurvRec sv;
+        sv.idx = idx;
+        sv.key = strict ? key : kPosInf;
+        sv.key_loose = key;
+        a.surv[slot] = sv;
+      }
+    }
+  }
+}
+
+// The lanes of a workgroup own the (mb, dp, pool of segment 1) triples; the pools of the
+// later segments are walked in uniform loops, so their record addresses, zones and
+// transfer terms are the same for the whole wave.  A lane whose own pool equals the
+// uniform pool of segment 2 sits that iteration out.
 template <int S, int MODE, int OBJ, bool HASB>
 __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, const UnitRec &u,
                                           const ShapeRec &sh, const Rec *rec, const float4 *pair,
-                                          const uint32_t *q13, float &ms, float &ml) {
+                                          const uint32_t *q13, float tau, float &ms, float &ml) {
   const int ZG = pl.ZG, G = pl.G, MB = pl.MB, DP = pl.DP, Z = pl.Z;
   const int nin = MB * DP * ZG;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwave = blockDim.x >> 6;
-  const bool single[3] = {sh.n[0] == 1, sh.n[1] == 1, sh.n[2] == 1};
+  const bool single0 = sh.n[0] == 1, single1 = sh.n[1] == 1;
   const int tp = u.tp;
   for (int e0 = wave * 64; e0 < nin; e0 += nwave * 64) {
     const int e = e0 + lane;
@@ -301,67 +362,55 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
     lc.xb = pl.xb_f[mb];
     const uint32_t dpbit = active ? (1u << dp) : 0u;
     const int z1 = a1 / G;
-    Rec r[3];
-    float wf[2] = {0.f, 0.f}, wb[2] = {0.f, 0.f};
-    r[0] = rec[(0 * ZG + a1) * MB + mb];
-    // index of the candidate with outer digits 0
+    const Rec *recm = rec + mb;            // this lane's column of the record table
+    const float4 *pair1 = pair + z1 * Z;   // transfers out of this lane's first zone
+    const Rec r0 = recm[a1 * MB];
+    const Acc A0 = acc_begin(r0);
+    const uint32_t b0 = r0.bits & dpbit;
+    const uint32_t q13a = (S == 3) ? q13[a1] : 0xFFFFFFFFu;
+    // index of the candidate whose outer digits are all zero
     const uint64_t idx0 = sh.base + (uint64_t)(mb + MB * (tp + pl.TP * (dp + DP * a1)));
-    const int n_o = (S >= 2) ? u.o_cnt : 1;
-    for (int oi = 0; oi < n_o; ++oi) {
-      const int r2 = u.o_lo + oi;
-      int a2 = 0, z2 = 0;
-      float eg2 = 0.f;
-      if (S >= 2) {
-        a2 = a1 + 1 + r2;
-        if (a2 >= ZG) a2 -= ZG;
-        z2 = a2 / G;
-        r[1] = rec[(1 * ZG + a2) * MB + mb];
-        const float4 pr = pair[z1 * Z + z2];
-        wf[0] = lc.p2pf * pr.x;
-        wb[0] = lc.p2pf * pr.y;
-        eg2 = pr.z;
-      }
-      const int n_o3 = (S == 3) ? ZG - 1 : 1;
-      for (int r3 = 0; r3 < n_o3; ++r3) {
-        float eg = eg2;
-        uint32_t bits = r[0].bits & dpbit;
-        if (S >= 2) bits &= r[1].bits;
-        if (S == 3) {
-          int a3 = a2 + 1 + r3;
-          if (a3 >= ZG) a3 -= ZG;
-          const int z3 = a3 / G;
-          r[2] = rec[(2 * ZG + a3) * MB + mb];
-          const float4 pr = pair[z2 * Z + z3];
-          wf[1] = lc.p2pf * pr.x;
-          wb[1] = lc.p2pf * pr.y;
-          eg += pr.z;
-          bits &= r[2].bits;
-          if (a3 == a1) bits &= q13[a1];  // segments 1 and 3 share one pool's quota
-        }
+    if (S == 1) {
+      float T, C;
+      acc_finish(A0, lc, T, C);
+      visit<MODE, OBJ, HASB>(a, T, C, b0 != 0, tau, idx0, ms, ml);
+      continue;
+    }
+    int z2 = u.o_lo / G, g2 = u.o_lo % G;
+    for (int a2 = u.o_lo; a2 < u.o_lo + u.o_cnt; ++a2) {
+      const Rec r1 = recm[(ZG + a2) * MB];
+      const float4 p12 = pair1[z2];
+      const Acc A1 = acc_cross(A0, r1, lc.p2pf * p12.x, lc.p2pf * p12.y, p12.z, single0, true);
+      const uint32_t b1 = (a1 != a2) ? (b0 & r1.bits) : 0u;
+      int rel2 = a2 - a1 - 1;
+      if (rel2 < 0) rel2 += ZG;
+      if (S == 2) {
         float T, C;
-        combine<S>(r, wf, wb, eg, single, lc, T, C);
-        const float key = OBJ == 0 ? T : C;
-        const float con = OBJ == 0 ? C : T;
-        const bool feas = bits != 0;
-        const bool strict = feas && (!HASB || con <= a.lim_s);
-        const bool loose = feas && (!HASB || con <= a.lim_l);
-        if (MODE == MODE_SCAN) {
-          if (strict) ms = fminf(ms, key);
-          if (HASB && loose) ml = fminf(ml, key);
-        } else {
-          const float tau = __uint_as_float(*a.tau_src) * a.band;
-          if (loose && key <= tau) {
-            uint32_t slot = atomicAdd(&a.counters[CNT_SURV], 1u);
-            if (slot < a.surv_cap) {
-              SurvRec sv;
-              sv.idx = idx0 + (uint64_t)pl.inner * (uint64_t)(r2 + (S == 3 ? (ZG - 1) * r3 : 0));
-              sv.key = strict ? key : kPosInf;
-              sv.key_loose = key;
-              a.surv[slot] = sv;
-            }
+        acc_finish(A1, lc, T, C);
+        visit<MODE, OBJ, HASB>(a, T, C, b1 != 0, tau, idx0 + (uint64_t)pl.inner * (uint64_t)rel2,
+                               ms, ml);
+      } else {
+        int z3 = 0, g3 = 0;
+        for (int a3 = 0; a3 < ZG; ++a3) {
+          if (a3 != a2) {  // uniform
+            const Rec r2 = recm[(2 * ZG + a3) * MB];
+            const float4 p23 = pair[z2 * Z + z3];
+            const Acc A2 = acc_cross(A1, r2, lc.p2pf * p23.x, lc.p2pf * p23.y, p23.z, single1,
+                                     false);
+            uint32_t b2 = b1 & r2.bits;
+            if (a3 == a1) b2 &= q13a;  // segments 1 and 3 share one pool's quota
+            int rel3 = a3 - a2 - 1;
+            if (rel3 < 0) rel3 += ZG;
+            float T, C;
+            acc_finish(A2, lc, T, C);
+            visit<MODE, OBJ, HASB>(a, T, C, b2 != 0, tau,
+                                   idx0 + (uint64_t)pl.inner * (uint64_t)(rel2 + (ZG - 1) * rel3),
+                                   ms, ml);
           }
+          if (++g3 == G) { g3 = 0; ++z3; }
         }
       }
+      if (++g2 == G) { g2 = 0; ++z2; }
     }
   }
 }
@@ -372,9 +421,11 @@ template <int MODE, int OBJ, bool HASB>
 __global__ __launch_bounds__(kUnitThreads) void k_units(DevPlan pl, ScanArgs a) {
   extern __shared__ uint4 lds_raw[];
   const UnitRec u = pl.units[blockIdx.x];
+  float tau = kPosInf;
   if (MODE == MODE_COLLECT) {
-    const float tau = __uint_as_float(*a.tau_src) * a.band;
-    if (!(a.umin_l[blockIdx.x] <= tau)) return;  // uniform over the workgroup
+    tau = __uint_as_float(*a.tau_src) * a.band;
+    const float um = a.umin_l[blockIdx.x];
+    if (!(um < kPosInf && um <= tau)) return;  // uniform over the workgroup
   }
   const ShapeRec sh = pl.shapes[u.shape];
   const int ZG = pl.ZG, G = pl.G, MB = pl.MB, Z = pl.Z, S = sh.s;
@@ -412,9 +463,9 @@ __global__ __launch_bounds__(kUnitThreads) void k_units(DevPlan pl, ScanArgs a) 
   __syncthreads();
 
   float ms = kPosInf, ml = kPosInf;
-  if (S == 1) unit_body<1, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, ms, ml);
-  else if (S == 2) unit_body<2, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, ms, ml);
-  else unit_body<3, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, ms, ml);
+  if (S == 1) unit_body<1, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, tau, ms, ml);
+  else if (S == 2) unit_body<2, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, tau, ms, ml);
+  else unit_body<3, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, tau, ms, ml);
 
   if (MODE == MODE_SCAN) {
     if (!HASB) ml = ms;
@@ -438,39 +489,52 @@ __global__ __launch_bounds__(kUnitThreads) void k_units(DevPlan pl, ScanArgs a) 
 // ------------------------------------------------------------------ k-th smallest key
 
 // Radix select (11 + 11 + 10 bits) of the k-th smallest non-negative float among
-// n = min(*count, cap) values read with a stride; fewer than k values yield +inf.
-// One workgroup.  The result's bit pattern goes to *out.
+// n = min(*count, cap) values read with a stride; +inf entries are ignored and fewer than
+// k finite values yield +inf.  One workgroup of 1024 threads.  The result's bit pattern
+// goes to *out.
 __global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stride_words,
                                                      const uint32_t *count, uint32_t cap,
                                                      uint32_t k, uint32_t *out) {
   __shared__ uint32_t hist[2048];
+  __shared__ uint32_t wsum[16];
   __shared__ uint32_t s_prefix, s_k, s_done;
   const uint32_t n = count ? min(*count, cap) : cap;
-  const int t = threadIdx.x;
+  const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
   if (t == 0) { s_prefix = 0; s_k = k; s_done = 0; }
   const int shifts[3] = {21, 10, 0}, widths[3] = {11, 11, 10};
   for (int pass = 0; pass < 3; ++pass) {
-    for (int i = t; i < 2048; i += blockDim.x) hist[i] = 0;
+    hist[t] = 0;
+    hist[t + 1024] = 0;
     __syncthreads();
     const int sh = shifts[pass], wd = widths[pass];
-    const uint32_t prefix = s_prefix;
-    if (!s_done)
-      for (uint32_t i = t; i < n; i += blockDim.x) {
-        uint32_t x = __float_as_uint(vals[(size_t)i * stride_words]);
-        bool match = pass == 0 || (x >> (sh + wd)) == prefix;
-        if (match) atomicAdd(&hist[(x >> sh) & ((1u << wd) - 1)], 1u);
-      }
-    __syncthreads();
-    if (t == 0 && !s_done) {
-      uint32_t cum = 0, kk = s_k, bin = 0;
-      bool found = false;
-      for (uint32_t b = 0; b < (1u << wd); ++b) {
-        if (cum + hist[b] >= kk) { bin = b; found = true; break; }
-        cum += hist[b];
-      }
-      if (!found) { s_done = 1; s_prefix = 0x7f800000u; }
-      else { s_prefix = (prefix << wd) | bin; s_k = kk - cum; }
+    const uint32_t prefix = s_prefix, kk = s_k;
+    if (s_done) break;  // uniform
+    for (uint32_t i = t; i < n; i += blockDim.x) {
+      const uint32_t x = __float_as_uint(vals[(size_t)i * stride_words]);
+      const bool match = x < 0x7f800000u && (pass == 0 || (x >> (sh + wd)) == prefix);
+      if (match) atomicAdd(&hist[(x >> sh) & ((1u << wd) - 1)], 1u);
     }
+    __syncthreads();
+    // inclusive prefix sum over the bins, two bins per thread
+    const uint32_t h0 = hist[2 * t], h1 = hist[2 * t + 1];
+    uint32_t incl = h0 + h1;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t v = __shfl_up(incl, off);
+      if (lane >= off) incl += v;
+    }
+    if (lane == 63) wsum[wv] = incl;
+    __syncthreads();
+    uint32_t before = 0;
+    for (int w = 0; w < wv; ++w) before += wsum[w];
+    incl += before;
+    const uint32_t excl = incl - (h0 + h1);
+    if (excl < kk && kk <= incl) {  // exactly one thread: the k-th value lies in its bins
+      const uint32_t bin = (kk <= excl + h0) ? 2 * t : 2 * t + 1;
+      s_prefix = (prefix << wd) | bin;
+      s_k = kk - (bin == 2u * t ? excl : excl + h0);
+    }
+    if (t == 1023 && incl < kk) { s_done = 1; s_prefix = 0x7f800000u; }
     __syncthreads();
   }
   if (t == 0) *out = s_prefix;
@@ -662,24 +726,24 @@ __global__ __launch_bounds__(1024) void k_pick_best(const RefRec *ref, uint32_t 
 __global__ void k_rank_topk(const RefRec *ref, uint32_t ref_cap, const uint32_t *counters,
                             int objective, uint32_t k, ResultHeader *hdr, RefRec *out) {
   const uint32_t n = min(counters[CNT_REF], ref_cap);
-  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i == 0) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
     const uint32_t f = counters[CNT_FEAS];
     hdr->n_found = f < k ? f : k;
     hdr->surv_count = counters[CNT_SURV];
     hdr->ref_count = counters[CNT_REF];
     hdr->feasible_count = f;
   }
-  if (i >= n) return;
-  const RefRec me = ref[i];
-  if (me.mask != 0) return;
-  const double mk = objective == 0 ? me.T : me.C;
-  uint32_t rank = 0;
-  for (uint32_t j = 0; j < n; ++j) {
-    const double kj = objective == 0 ? ref[j].T : ref[j].C;
-    if (ref[j].mask == 0 && lex_less(kj, ref[j].idx, mk, me.idx)) ++rank;
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    const RefRec me = ref[i];
+    if (me.mask != 0) continue;
+    const double mk = objective == 0 ? me.T : me.C;
+    uint32_t rank = 0;
+    for (uint32_t j = 0; j < n; ++j) {
+      const double kj = objective == 0 ? ref[j].T : ref[j].C;
+      if (ref[j].mask == 0 && lex_less(kj, ref[j].idx, mk, me.idx)) ++rank;
+    }
+    if (rank < k) out[rank] = me;
   }
-  if (rank < k) out[rank] = me;
 }
 
 // ------------------------------------------------------------------ eval_batch
@@ -701,15 +765,13 @@ __device__ __forceinline__ void eval_direct_s(const DevPlan &pl, const Cand &c, 
   const int G = pl.G, Z = pl.Z, MB = pl.MB, DP = pl.DP;
   const int tpv = pl.tpv[c.tp];
   const int64_t D = pl.dpv[c.dp];
-  Rec r[S];
-  float wf[2] = {0.f, 0.f}, wb[2] = {0.f, 0.f}, eg = 0.f;
-  bool single[3] = {sh.n[0] == 1, sh.n[1] == 1, sh.n[2] == 1};
+  Acc acc;
 #pragma unroll
   for (int j = 0; j < S; ++j) {
     const int p = c.a[j], g = p % G, z = p / G;
     const size_t sl = agg_slot(pl, c.shape, c.tp, j);
-    r[j] = make_rec(pl.ta[(sl * G + g) * MB + c.mb], pl.smax[sl], pl.upd[sl * G + g], pl.price_f[g],
-                    lc.p2pf, pl.ibw_f[z * Z + z], sh.n[j], 0u);
+    const Rec r = make_rec(pl.ta[(sl * G + g) * MB + c.mb], pl.smax[sl], pl.upd[sl * G + g],
+                           pl.price_f[g], lc.p2pf, pl.ibw_f[z * Z + z], sh.n[j], 0u);
     const uint64_t m = pl.need[(sl * MB + c.mb) * DP + c.dp] + pl.res[g];
     if (m > pl.cap[g]) mask |= 1u;
     peak = m > peak ? m : peak;
@@ -717,14 +779,15 @@ __device__ __forceinline__ void eval_direct_s(const DevPlan &pl, const Cand &c, 
     if (S == 3 && (j == 0 || j == 2) && c.a[0] == c.a[2]) stages = sh.n[0] + sh.n[2];
     if (stages * D * tpv > (int64_t)pl.avail[p]) mask |= 2u;
     if (tpv > pl.node[g]) mask |= 8u;
-    if (j > 0) {
+    if (j == 0) {
+      acc = acc_begin(r);
+    } else {
       const int zp = c.a[j - 1] / G;
-      wf[j - 1] = lc.p2pf * pl.ibw_f[zp * Z + z];
-      wb[j - 1] = lc.p2pf * pl.ibw_f[z * Z + zp];
-      eg += pl.egs_f[zp * Z + z];
+      acc = acc_cross(acc, r, lc.p2pf * pl.ibw_f[zp * Z + z], lc.p2pf * pl.ibw_f[z * Z + zp],
+                      pl.egs_f[zp * Z + z], sh.n[j - 1] == 1, j == 1);
     }
   }
-  combine<S>(r, wf, wb, eg, single, lc, T, C);
+  acc_finish(acc, lc, T, C);
 }
 
 // One lane per candidate; reads the segment aggregates straight from global memory.
