@@ -64,6 +64,7 @@ struct sailor_plan {
   std::vector<int32_t> mbv, tpv, dpv, ppv;
   int device = 0;
   size_t lds_bytes = 0;
+  unsigned unit_threads = 256;
   int32_t *d_avail = nullptr;
   // scratch of the selection pipeline
   float *umin_s = nullptr, *umin_l = nullptr;
@@ -250,6 +251,23 @@ sailor_status build_space(const sailor_problem *p, sailor_plan *pl, std::vector<
         pl->units.push_back(u);
       }
   }
+  // Largest units first, so that the small ones fill the tail of the launch.
+  auto unit_cost = [&](const UnitRec &u) {  // candidates of the unit
+    return innerp * (uint64_t)u.o_cnt * (u.s == 3 ? (uint64_t)(ZG - 1) : 1u);
+  };
+  std::stable_sort(pl->units.begin(), pl->units.end(),
+                   [&](const UnitRec &a, const UnitRec &b) { return unit_cost(a) > unit_cost(b); });
+  // Waves per workgroup: the lanes of a unit cover MB*DP*ZG triples in chunks of 64; pick
+  // the wave count (2..8) that leaves the fewest idle wave slots in the last round.
+  const uint64_t chunks = (innerp + 63) / 64;
+  unsigned best_w = 4;
+  double best_eff = 0.0;
+  for (unsigned w = 2; w <= kMaxUnitThreads / 64; ++w) {
+    const uint64_t rounds = (chunks + w - 1) / w;
+    const double eff = (double)chunks / (double)(rounds * w);
+    if (eff > best_eff + 1e-9 || (eff > best_eff - 1e-9 && w == 4)) { best_eff = eff; best_w = w; }
+  }
+  pl->unit_threads = best_w * 64;
   return SAILOR_OK;
 }
 
@@ -314,7 +332,7 @@ const ShapeRec &shape_of(const sailor_plan *pl, uint64_t index) {
 template <int MODE>
 void launch_units(sailor_plan *pl, sailor_objective obj, int has_bound, const ScanArgs &a,
                   hipStream_t st) {
-  const dim3 grid((unsigned)pl->units.size()), block(kUnitThreads);
+  const dim3 grid((unsigned)pl->units.size()), block(pl->unit_threads);
   const size_t lds = pl->lds_bytes;
   if (obj == SAILOR_MAX_THROUGHPUT) {
     if (has_bound) k_units<MODE, 0, true><<<grid, block, lds, st>>>(pl->dev, a);

@@ -14,7 +14,7 @@ namespace sailor {
 
 constexpr int kMaxMB = 8, kMaxTP = 8, kMaxDP = 24, kMaxPools = 64, kMaxZones = 16,
               kMaxTypes = 16, kMaxStages = 256;
-constexpr int kUnitThreads = 256;
+constexpr int kMaxUnitThreads = 512;  // scan workgroups use 2..8 waves, chosen per plan
 constexpr float kNegInf = -__builtin_huge_valf();
 constexpr float kPosInf = __builtin_huge_valf();
 

@@ -418,7 +418,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
 // One workgroup per unit: stage the unit's segment records in LDS, then every lane walks
 // its (mb, dp, pool 1) triple over the unit's outer pool digits.
 template <int MODE, int OBJ, bool HASB>
-__global__ __launch_bounds__(kUnitThreads) void k_units(DevPlan pl, ScanArgs a) {
+__global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs a) {
   extern __shared__ uint4 lds_raw[];
   const UnitRec u = pl.units[blockIdx.x];
   float tau = kPosInf;
@@ -433,7 +433,7 @@ __global__ __launch_bounds__(kUnitThreads) void k_units(DevPlan pl, ScanArgs a) 
   float4 *pair = reinterpret_cast<float4 *>(rec + 3 * ZG * MB);     // [Z][Z]
   uint32_t *qm = reinterpret_cast<uint32_t *>(pair + Z * Z);        // [3][ZG]
   uint32_t *q13 = qm + 3 * ZG;                                      // [ZG]
-  __shared__ float red[2][kUnitThreads / 64];
+  __shared__ float red[2][kMaxUnitThreads / 64];
   const int t = threadIdx.x;
   const int tpv = pl.tpv[u.tp];
 
