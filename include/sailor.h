@@ -185,10 +185,16 @@ sailor_status sailor_topk(sailor_plan *plan, sailor_objective objective,
                           const sailor_constraint *constraint, int32_t k, sailor_result *out,
                           int32_t *n_found, void *hip_stream);
 
-/* Time, in milliseconds between HIP events on hip_stream, of the kernels launched by the
- * last sailor_best_plan / sailor_topk / sailor_eval_batch call on this plan:
- * total and the part spent in the full-space scan kernel.  For measurement only. */
-sailor_status sailor_plan_last_timing(sailor_plan *plan, float *total_ms, float *scan_ms);
+/* Measurement only.  mode 0 (default): no events are recorded.  mode 1: the dominant kernel
+ * of each call (the full-space scan of sailor_best_plan / sailor_topk, the evaluation kernel
+ * of sailor_eval_batch) is launched with start and stop events on its stream.  mode 2: in
+ * addition two events bracket all kernels of a sailor_best_plan / sailor_topk call. */
+sailor_status sailor_plan_set_timing(sailor_plan *plan, int32_t mode);
+
+/* Milliseconds measured by the last call on this plan under the timing mode above:
+ * *total_ms (mode 2, else 0) and *kernel_ms (mode >= 1).  Waits for the events.
+ * SAILOR_EINVAL if the last call recorded nothing. */
+sailor_status sailor_plan_last_timing(sailor_plan *plan, float *total_ms, float *kernel_ms);
 
 #ifdef __cplusplus
 }

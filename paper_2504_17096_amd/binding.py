@@ -26,7 +26,8 @@ MAX_K = 4096
 
 EXPORTS = ["sailor_plan_create", "sailor_plan_destroy", "sailor_plan_set_avail",
            "sailor_plan_num_candidates", "sailor_plan_decode", "sailor_eval_batch",
-           "sailor_best_plan", "sailor_topk", "sailor_plan_last_timing"]
+           "sailor_best_plan", "sailor_topk", "sailor_plan_set_timing",
+           "sailor_plan_last_timing"]
 
 
 class SailorError(RuntimeError):
@@ -121,6 +122,7 @@ def load_library() -> C.CDLL:
                                      C.POINTER(sailor_result), P]
     lib.sailor_topk.argtypes = [P, C.c_int, C.POINTER(sailor_constraint), C.c_int32,
                                 C.POINTER(sailor_result), C.POINTER(C.c_int32), P]
+    lib.sailor_plan_set_timing.argtypes = [P, C.c_int32]
     lib.sailor_plan_last_timing.argtypes = [P, C.POINTER(C.c_float), C.POINTER(C.c_float)]
     for name in EXPORTS:
         getattr(lib, name).restype = C.c_int
@@ -261,8 +263,22 @@ class Plan:
             raise SailorError(rc, "sailor_topk")
         return [_result(buf[i]) for i in range(n.value)]
 
+    def set_timing(self, mode: int) -> None:
+        rc = self._lib.sailor_plan_set_timing(self._h, mode)
+        if rc != SAILOR_OK:
+            raise SailorError(rc, "sailor_plan_set_timing")
+
+    def topk_raw(self, k: int, objective: int, bound: Optional[float], buf, stream: int = 0) -> int:
+        """sailor_topk into a caller-kept (sailor_result * k) array; returns n_found."""
+        n = C.c_int32(0)
+        rc = self._lib.sailor_topk(self._h, objective, _constraint(bound), k, buf, C.byref(n),
+                                   stream or None)
+        if rc not in (SAILOR_OK, SAILOR_ENOFEASIBLE):
+            raise SailorError(rc, "sailor_topk")
+        return n.value
+
     def last_timing(self) -> Tuple[float, float]:
-        """(total ms, scan-kernel ms) of the last call, between HIP events."""
+        """(total ms, dominant-kernel ms) of the last call, from HIP events (see set_timing)."""
         t, s = C.c_float(), C.c_float()
         rc = self._lib.sailor_plan_last_timing(self._h, C.byref(t), C.byref(s))
         if rc != SAILOR_OK:

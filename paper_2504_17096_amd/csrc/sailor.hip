@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/sailor.h: validation, upload, launches,
 // decoding of winning indices.  No simulator arithmetic runs here.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <cmath>
@@ -75,8 +76,11 @@ struct sailor_plan {
   void *h_result = nullptr;
   ResultHeader *d_hdr = nullptr;
   RefRec *d_out = nullptr;
+  uint32_t cnt_phase = 0;      // which of the two counter sets the next call uses
+  bool counters_dirty = false; // a failed call may have left either set in any state
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};  // start, scan end, end, scan start
-  bool timing_valid = false, scan_timed = false;
+  int timing_mode = 0;         // 0 none, 1 dominant kernel, 2 dominant kernel + whole call
+  bool total_timed = false, scan_timed = false;
 };
 
 namespace {
@@ -329,56 +333,72 @@ const ShapeRec &shape_of(const sailor_plan *pl, uint64_t index) {
   return pl->shapes[blk->first_shape + (index - blk->off) / blk->shape_size];
 }
 
+// Plain launch, or a launch whose own start / stop timestamps are recorded in two events.
+template <typename K, typename... A>
+void launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, hipEvent_t e0,
+            hipEvent_t e1, A... args) {
+  if (e0) hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, st, e0, e1, 0, args...);
+  else kernel<<<grid, block, lds, st>>>(args...);
+}
+
 template <int MODE>
 void launch_units(sailor_plan *pl, sailor_objective obj, int has_bound, const ScanArgs &a,
-                  hipStream_t st) {
+                  hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
   const dim3 grid((unsigned)pl->units.size()), block(pl->unit_threads);
   const size_t lds = pl->lds_bytes;
   if (obj == SAILOR_MAX_THROUGHPUT) {
-    if (has_bound) k_units<MODE, 0, true><<<grid, block, lds, st>>>(pl->dev, a);
-    else k_units<MODE, 0, false><<<grid, block, lds, st>>>(pl->dev, a);
+    if (has_bound) launch(k_units<MODE, 0, true>, grid, block, lds, st, e0, e1, pl->dev, a);
+    else launch(k_units<MODE, 0, false>, grid, block, lds, st, e0, e1, pl->dev, a);
   } else {
-    if (has_bound) k_units<MODE, 1, true><<<grid, block, lds, st>>>(pl->dev, a);
-    else k_units<MODE, 1, false><<<grid, block, lds, st>>>(pl->dev, a);
+    if (has_bound) launch(k_units<MODE, 1, true>, grid, block, lds, st, e0, e1, pl->dev, a);
+    else launch(k_units<MODE, 1, false>, grid, block, lds, st, e0, e1, pl->dev, a);
   }
 }
 
 // Shared by best_plan (k = 0: tolerance rule) and topk.
-sailor_status run_selection(sailor_plan *pl, sailor_objective obj, const sailor_constraint *con,
-                            uint32_t k, hipStream_t st, ResultHeader *hdr_out) {
+sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
+                                 const sailor_constraint *con, uint32_t k, hipStream_t st,
+                                 ResultHeader *hdr_out) {
   int has_bound;
   double bound;
   ScanArgs sa{};
   sailor_status rc = constraint_limits(obj, con, &has_bound, &bound, &sa.lim_s, &sa.lim_l);
   if (rc != SAILOR_OK) return rc;
   HIP_TRY(hipSetDevice(pl->device));
+  if (pl->counters_dirty) {
+    k_init_counters<<<1, 64, 0, st>>>(pl->counters, 2 * CNT_COUNT);
+    pl->counters_dirty = false;
+  }
+  // two counter sets: this call's set was reset by the final kernel of the previous call
+  uint32_t *cnt = pl->counters + pl->cnt_phase * CNT_COUNT;
+  uint32_t *cnt_next = pl->counters + (pl->cnt_phase ^ 1u) * CNT_COUNT;
+  pl->cnt_phase ^= 1u;
   sa.umin_s = pl->umin_s;
   sa.umin_l = pl->umin_l;
-  sa.counters = pl->counters;
+  sa.counters = cnt;
   sa.surv = pl->surv;
   sa.surv_cap = kSurvCap;
   const bool best = (k == 0);
   const uint32_t n_units = (uint32_t)pl->units.size();
+  const bool t_scan = pl->timing_mode >= 1, t_all = pl->timing_mode >= 2;
 
-  HIP_TRY(hipEventRecord(pl->ev[0], st));
-  k_init_counters<<<1, 64, 0, st>>>(pl->counters);
-  HIP_TRY(hipEventRecord(pl->ev[3], st));
-  launch_units<MODE_SCAN>(pl, obj, has_bound, sa, st);
-  HIP_TRY(hipEventRecord(pl->ev[1], st));
+  if (t_all) HIP_TRY(hipEventRecord(pl->ev[0], st));
+  launch_units<MODE_SCAN>(pl, obj, has_bound, sa, st, t_scan ? pl->ev[3] : nullptr,
+                          t_scan ? pl->ev[1] : nullptr);
   if (best) {
-    sa.tau_src = pl->counters + CNT_GMIN;
+    sa.tau_src = cnt + CNT_GMIN;
     sa.band = (float)(1.0 + kTieTol) + 3.0f * kEvalEps;
   } else {
     // an upper bound of the k-th smallest key: the k-th smallest unit minimum
-    k_select_kth<<<1, 1024, 0, st>>>(pl->umin_s, 1, nullptr, n_units, k, pl->counters + CNT_TAU0);
-    sa.tau_src = pl->counters + CNT_TAU0;
+    k_select_kth<<<1, 1024, 0, st>>>(pl->umin_s, 1, nullptr, n_units, k, cnt + CNT_TAU0);
+    sa.tau_src = cnt + CNT_TAU0;
     sa.band = 1.0f + 3.0f * kEvalEps;
   }
-  launch_units<MODE_COLLECT>(pl, obj, has_bound, sa, st);
+  launch_units<MODE_COLLECT>(pl, obj, has_bound, sa, st, nullptr, nullptr);
   RefineArgs ra{};
   ra.surv = pl->surv;
   ra.surv_cap = kSurvCap;
-  ra.counters = pl->counters;
+  ra.counters = cnt;
   ra.ref = pl->ref;
   ra.ref_cap = kRefCap;
   ra.objective = (int)obj;
@@ -387,25 +407,33 @@ sailor_status run_selection(sailor_plan *pl, sailor_objective obj, const sailor_
   ra.band = 1.0f + 3.0f * kEvalEps;
   if (!best) {
     // the exact k-th smallest fp32 key among the survivors, then only its neighbourhood
-    k_select_kth<<<1, 1024, 0, st>>>(&pl->surv[0].key, (int)(sizeof(SurvRec) / 4),
-                                     pl->counters + CNT_SURV, kSurvCap, k, pl->counters + CNT_TAU1);
-    ra.tau_src = pl->counters + CNT_TAU1;
+    k_select_kth<<<1, 1024, 0, st>>>(&pl->surv[0].key, (int)(sizeof(SurvRec) / 4), cnt + CNT_SURV,
+                                     kSurvCap, k, cnt + CNT_TAU1);
+    ra.tau_src = cnt + CNT_TAU1;
   }
-  k_refine<<<256, 256, 0, st>>>(pl->dev, ra);
+  k_refine<<<256, kRefineWaves * 64, 0, st>>>(pl->dev, ra);
   if (best) {
-    k_pick_best<<<1, 1024, 0, st>>>(pl->ref, kRefCap, pl->counters, (int)obj, pl->d_hdr, pl->d_out);
+    k_pick_best<<<1, 1024, 0, st>>>(pl->ref, kRefCap, cnt, cnt_next, (int)obj, pl->d_hdr,
+                                    pl->d_out);
   } else {
-    k_rank_topk<<<64, 256, 0, st>>>(pl->ref, kRefCap, pl->counters, (int)obj, k,
-                                               pl->d_hdr, pl->d_out);
+    k_rank_topk<<<64, 256, 0, st>>>(pl->ref, kRefCap, cnt, cnt_next, (int)obj, k, pl->d_hdr,
+                                    pl->d_out);
   }
-  HIP_TRY(hipEventRecord(pl->ev[2], st));
+  if (t_all) HIP_TRY(hipEventRecord(pl->ev[2], st));
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipStreamSynchronize(st));
-  pl->timing_valid = true;
-  pl->scan_timed = true;
+  pl->total_timed = t_all;
+  pl->scan_timed = t_scan;
   *hdr_out = *static_cast<ResultHeader *>(pl->h_result);
   if (hdr_out->surv_count > kSurvCap || hdr_out->ref_count > kRefCap) return SAILOR_ENOMEM;
   return SAILOR_OK;
+}
+
+sailor_status run_selection(sailor_plan *pl, sailor_objective obj, const sailor_constraint *con,
+                            uint32_t k, hipStream_t st, ResultHeader *hdr_out) {
+  const sailor_status rc = run_selection_impl(pl, obj, con, k, st, hdr_out);
+  if (rc == SAILOR_EDEVICE) pl->counters_dirty = true;
+  return rc;
 }
 
 void to_result(const sailor_plan *pl, const RefRec &r, sailor_result *out) {
@@ -458,6 +486,10 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   pl->tpv.assign(p->tp_values, p->tp_values + d.TP);
   pl->dpv.assign(p->dp_values, p->dp_values + d.DP);
   pl->ppv.assign(p->pp_values, p->pp_values + p->n_pp);
+  auto magic = [](uint32_t dv) { return dv == 1 ? 0u : (uint32_t)(((1ull << 32) + dv - 1) / dv); };
+  d.mg_mb = magic((uint32_t)d.MB);
+  d.mg_mbdp = magic((uint32_t)(d.MB * d.DP));
+  d.mg_g = magic((uint32_t)d.G);
   pl->lds_bytes = (size_t)3 * d.ZG * d.MB * sizeof(Rec) + (size_t)d.Z * d.Z * sizeof(float4) +
                   (size_t)4 * d.ZG * sizeof(uint32_t);
 
@@ -524,7 +556,7 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   // selection scratch
   CREATE_TRY(ar.alloc(&pl->umin_s, pl->units.size()));
   CREATE_TRY(ar.alloc(&pl->umin_l, pl->units.size()));
-  CREATE_TRY(ar.alloc(&pl->counters, (size_t)CNT_COUNT));
+  CREATE_TRY(ar.alloc(&pl->counters, (size_t)2 * CNT_COUNT));
   CREATE_TRY(ar.alloc(&pl->surv, (size_t)kSurvCap));
   CREATE_TRY(ar.alloc(&pl->ref, (size_t)kRefCap));
   const size_t res_bytes = sizeof(ResultHeader) + 8 + (size_t)SAILOR_MAX_K * sizeof(RefRec);
@@ -536,6 +568,7 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   pl->d_out = reinterpret_cast<RefRec *>(static_cast<char *>(d_res) + sizeof(ResultHeader));
   for (hipEvent_t &e : pl->ev) CREATE_TRY(hipEventCreate(&e));
 
+  k_init_counters<<<1, 64>>>(pl->counters, 2 * CNT_COUNT);
   k_small_tables<<<1, 256>>>(d);
   k_stage_tables<<<(unsigned)RS, 128>>>(d, sa);
   k_shape_agg<<<(unsigned)NS, 256>>>(d);
@@ -586,12 +619,12 @@ sailor_status sailor_eval_batch(sailor_plan *pl, uint64_t first, uint64_t count,
   a.objective = (int)objective;
   a.has_bound = (constraint && constraint->has_bound) ? 1 : 0;
   a.bound = a.has_bound ? (float)constraint->bound : 0.f;
-  HIP_TRY(hipEventRecord(pl->ev[0], st));
-  k_eval_direct<<<(unsigned)((count + 255) / 256), 256, 0, st>>>(pl->dev, a);
-  HIP_TRY(hipEventRecord(pl->ev[2], st));
+  const bool timed = pl->timing_mode >= 1;
+  launch(k_eval_direct, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st,
+         timed ? pl->ev[3] : nullptr, timed ? pl->ev[1] : nullptr, pl->dev, a);
   HIP_TRY(hipGetLastError());
-  pl->timing_valid = true;
-  pl->scan_timed = false;
+  pl->total_timed = false;
+  pl->scan_timed = timed;
   return SAILOR_OK;
 }
 
@@ -629,14 +662,26 @@ sailor_status sailor_topk(sailor_plan *pl, sailor_objective objective,
   return SAILOR_OK;
 }
 
-sailor_status sailor_plan_last_timing(sailor_plan *pl, float *total_ms, float *scan_ms) {
-  if (!pl || !pl->timing_valid) return SAILOR_EINVAL;
-  HIP_TRY(hipEventSynchronize(pl->ev[2]));
+sailor_status sailor_plan_set_timing(sailor_plan *pl, int32_t mode) {
+  if (!pl || mode < 0 || mode > 2) return SAILOR_EINVAL;
+  pl->timing_mode = mode;
+  pl->total_timed = pl->scan_timed = false;
+  return SAILOR_OK;
+}
+
+sailor_status sailor_plan_last_timing(sailor_plan *pl, float *total_ms, float *kernel_ms) {
+  if (!pl || (!pl->total_timed && !pl->scan_timed)) return SAILOR_EINVAL;
   float t = 0.f, s = 0.f;
-  HIP_TRY(hipEventElapsedTime(&t, pl->ev[0], pl->ev[2]));
-  if (pl->scan_timed) HIP_TRY(hipEventElapsedTime(&s, pl->ev[3], pl->ev[1]));
+  if (pl->scan_timed) {
+    HIP_TRY(hipEventSynchronize(pl->ev[1]));
+    HIP_TRY(hipEventElapsedTime(&s, pl->ev[3], pl->ev[1]));
+  }
+  if (pl->total_timed) {
+    HIP_TRY(hipEventSynchronize(pl->ev[2]));
+    HIP_TRY(hipEventElapsedTime(&t, pl->ev[0], pl->ev[2]));
+  }
   if (total_ms) *total_ms = t;
-  if (scan_ms) *scan_ms = s;
+  if (kernel_ms) *kernel_ms = s;
   return SAILOR_OK;
 }
 

@@ -67,6 +67,7 @@ struct DevPlan {
   int n_blocks, n_shapes, n_units, n_row_stages;
   uint32_t inner;          // MB*TP*DP*ZG candidates per (shape, outer pool digits)
   uint32_t bpp, gb;
+  uint32_t mg_mb, mg_mbdp, mg_g;  // ceil(2^32 / d) for d = MB, MB*DP, G (0 encodes d = 1)
   int64_t B;
   uint64_t N;
   int mbv[kMaxMB], tpv[kMaxTP], dpv[kMaxDP];

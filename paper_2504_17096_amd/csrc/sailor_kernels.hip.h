@@ -257,7 +257,9 @@ __device__ __forceinline__ Acc acc_begin(const Rec &r) {
 __device__ __forceinline__ Acc acc_cross(const Acc &p, const Rec &r, float wf, float wb, float eg,
                                          bool open_is_single, bool first_boundary) {
   Acc a;
-  const float tf = open_is_single ? p.tf + wf : p.tf;
+  // a one-stage segment's only stage also pays the outgoing transfer (fma with an exact
+  // 0 / 1 factor equals the plain sum)
+  const float tf = fmaf(open_is_single ? 1.0f : 0.0f, wf, p.tf);
   a.tmax = fmaxf(p.tmax, fmaxf(fmaxf(tf, p.tl + wf), p.ti));
   a.sum = (p.sum + r.sumT) + (wf + wb);
   a.syn = fmaxf(p.syn, r.syncb);
@@ -301,9 +303,12 @@ struct ScanArgs {
 enum Counter { CNT_SURV = 0, CNT_REF = 1, CNT_FEAS = 2, CNT_GMIN = 3, CNT_TAU0 = 4, CNT_TAU1 = 5,
                CNT_COUNT = 8 };
 
-__global__ void k_init_counters(uint32_t *c) {
-  if (threadIdx.x < CNT_COUNT)
-    c[threadIdx.x] = (threadIdx.x >= CNT_GMIN) ? 0x7f800000u : 0u;
+__device__ __forceinline__ uint32_t counter_reset_value(int i) {
+  return (i % CNT_COUNT >= CNT_GMIN) ? 0x7f800000u : 0u;  // thresholds start at +inf
+}
+
+__global__ void k_init_counters(uint32_t *c, int n) {
+  if ((int)threadIdx.x < n) c[threadIdx.x] = counter_reset_value(threadIdx.x);
 }
 
 // One candidate of the scan: update the running minima, or append it to the survivors.
@@ -336,76 +341,123 @@ __device__ __forceinline__ void visit(const ScanArgs &a, float T, float C, bool 
   }
 }
 
+// q = n / d for n * d < 2^32 with m = ceil(2^32 / d) (m = 0 encodes d = 1)
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t m) {
+  return m ? __umulhi(n, m) : n;
+}
+
+struct LaneItem {  // what a lane owns for one chunk of the lane space
+  int mb, dp, a1, z1;
+  bool active;
+  LaneC lc;
+  uint32_t dpbit;
+};
+
+// lane item e of a lane space laid out as mb + MB * (dp + DP * a1)
+__device__ __forceinline__ LaneItem lane_item(const DevPlan &pl, int e, int n_items, int tp) {
+  LaneItem it;
+  it.active = e < n_items;
+  const uint32_t ee = it.active ? (uint32_t)e : 0u;
+  const uint32_t mbdp = (uint32_t)(pl.MB * pl.DP);
+  const uint32_t a1 = fast_div(ee, pl.mg_mbdp), rem = ee - a1 * mbdp;
+  const uint32_t dp = fast_div(rem, pl.mg_mb);
+  it.a1 = (int)a1;
+  it.dp = (int)dp;
+  it.mb = (int)(rem - dp * (uint32_t)pl.MB);
+  it.lc.p2pf = pl.p2p_f[it.mb];
+  it.lc.nbm1 = pl.nbm1_f[it.mb * pl.DP + it.dp];
+  it.lc.cd = pl.cd_f[it.dp];
+  it.lc.dtp = pl.dtp_f[tp * pl.DP + it.dp];
+  it.lc.xb = pl.xb_f[it.mb];
+  it.dpbit = it.active ? (1u << it.dp) : 0u;
+  it.z1 = 0;
+  return it;
+}
+
 // The lanes of a workgroup own the (mb, dp, pool of segment 1) triples; the pools of the
 // later segments are walked in uniform loops, so their record addresses, zones and
-// transfer terms are the same for the whole wave.  A lane whose own pool equals the
-// uniform pool of segment 2 sits that iteration out.
+// transfer terms are the same for the whole wave.
+//   one or two segments: lanes cover every pool 1; in the loop over pool 2 a lane whose own
+//     pool equals it sits that iteration out;
+//   three segments: pool 2 is the outer uniform loop, lanes cover the ZG - 1 other pools,
+//     pool 3 is the inner uniform loop.
 template <int S, int MODE, int OBJ, bool HASB>
 __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, const UnitRec &u,
                                           const ShapeRec &sh, const Rec *rec, const float4 *pair,
                                           const uint32_t *q13, float tau, float &ms, float &ml) {
   const int ZG = pl.ZG, G = pl.G, MB = pl.MB, DP = pl.DP, Z = pl.Z;
-  const int nin = MB * DP * ZG;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwave = blockDim.x >> 6;
   const bool single0 = sh.n[0] == 1, single1 = sh.n[1] == 1;
   const int tp = u.tp;
-  for (int e0 = wave * 64; e0 < nin; e0 += nwave * 64) {
-    const int e = e0 + lane;
-    const bool active = e < nin;
-    const int ee = active ? e : 0;
-    const int mb = ee % MB, dp = (ee / MB) % DP, a1 = ee / (MB * DP);
-    LaneC lc;
-    lc.p2pf = pl.p2p_f[mb];
-    lc.nbm1 = pl.nbm1_f[mb * DP + dp];
-    lc.cd = pl.cd_f[dp];
-    lc.dtp = pl.dtp_f[tp * DP + dp];
-    lc.xb = pl.xb_f[mb];
-    const uint32_t dpbit = active ? (1u << dp) : 0u;
-    const int z1 = a1 / G;
-    const Rec *recm = rec + mb;            // this lane's column of the record table
-    const float4 *pair1 = pair + z1 * Z;   // transfers out of this lane's first zone
-    const Rec r0 = recm[a1 * MB];
-    const Acc A0 = acc_begin(r0);
-    const uint32_t b0 = r0.bits & dpbit;
-    const uint32_t q13a = (S == 3) ? q13[a1] : 0xFFFFFFFFu;
-    // index of the candidate whose outer digits are all zero
-    const uint64_t idx0 = sh.base + (uint64_t)(mb + MB * (tp + pl.TP * (dp + DP * a1)));
-    if (S == 1) {
-      float T, C;
-      acc_finish(A0, lc, T, C);
-      visit<MODE, OBJ, HASB>(a, T, C, b0 != 0, tau, idx0, ms, ml);
-      continue;
-    }
-    int z2 = u.o_lo / G, g2 = u.o_lo % G;
-    for (int a2 = u.o_lo; a2 < u.o_lo + u.o_cnt; ++a2) {
-      const Rec r1 = recm[(ZG + a2) * MB];
-      const float4 p12 = pair1[z2];
-      const Acc A1 = acc_cross(A0, r1, lc.p2pf * p12.x, lc.p2pf * p12.y, p12.z, single0, true);
-      const uint32_t b1 = (a1 != a2) ? (b0 & r1.bits) : 0u;
-      int rel2 = a2 - a1 - 1;
-      if (rel2 < 0) rel2 += ZG;
-      if (S == 2) {
+  if (S <= 2) {
+    const int nin = MB * DP * ZG;
+    for (int e0 = wave * 64; e0 < nin; e0 += nwave * 64) {
+      const LaneItem it = lane_item(pl, e0 + lane, nin, tp);
+      const int a1 = it.a1, z1 = (int)fast_div((uint32_t)a1, pl.mg_g);
+      const Rec *recm = rec + it.mb;         // this lane's column of the record table
+      const float4 *pair1 = pair + z1 * Z;   // transfers out of this lane's first zone
+      const Rec r0 = recm[a1 * MB];
+      const Acc A0 = acc_begin(r0);
+      const uint32_t b0 = r0.bits & it.dpbit;
+      // index of the candidate whose outer digits are all zero
+      const uint64_t idx0 = sh.base + (uint64_t)(it.mb + MB * (tp + pl.TP * (it.dp + DP * a1)));
+      if (S == 1) {
         float T, C;
-        acc_finish(A1, lc, T, C);
+        acc_finish(A0, it.lc, T, C);
+        visit<MODE, OBJ, HASB>(a, T, C, b0 != 0, tau, idx0, ms, ml);
+        continue;
+      }
+      int z2 = u.o_lo / G, g2 = u.o_lo % G;
+      for (int a2 = u.o_lo; a2 < u.o_lo + u.o_cnt; ++a2) {
+        const Rec r1 = recm[(ZG + a2) * MB];
+        const float4 p12 = pair1[z2];
+        const Acc A1 = acc_cross(A0, r1, it.lc.p2pf * p12.x, it.lc.p2pf * p12.y, p12.z, single0,
+                                 true);
+        const uint32_t b1 = (a1 != a2) ? (b0 & r1.bits) : 0u;
+        int rel2 = a2 - a1 - 1;
+        if (rel2 < 0) rel2 += ZG;
+        float T, C;
+        acc_finish(A1, it.lc, T, C);
         visit<MODE, OBJ, HASB>(a, T, C, b1 != 0, tau, idx0 + (uint64_t)pl.inner * (uint64_t)rel2,
                                ms, ml);
-      } else {
+        if (++g2 == G) { g2 = 0; ++z2; }
+      }
+    }
+  } else {
+    const int nin = MB * DP * (ZG - 1);
+    int z2 = u.o_lo / G, g2 = u.o_lo % G;
+    for (int a2 = u.o_lo; a2 < u.o_lo + u.o_cnt; ++a2) {
+      for (int e0 = wave * 64; e0 < nin; e0 += nwave * 64) {
+        const LaneItem it = lane_item(pl, e0 + lane, nin, tp);
+        const int a1 = it.a1 + (it.a1 >= a2 ? 1 : 0);  // skip the pool of segment 2
+        const int z1 = (int)fast_div((uint32_t)a1, pl.mg_g);
+        const Rec *recm = rec + it.mb;
+        const Rec r0 = recm[a1 * MB];
+        const Rec r1 = recm[(ZG + a2) * MB];
+        const float4 p12 = pair[z1 * Z + z2];
+        const Acc A1 = acc_cross(acc_begin(r0), r1, it.lc.p2pf * p12.x, it.lc.p2pf * p12.y, p12.z,
+                                 single0, true);
+        const uint32_t b1 = r0.bits & it.dpbit & r1.bits;
+        const uint32_t q13a = q13[a1];
+        int rel2 = a2 - a1 - 1;
+        if (rel2 < 0) rel2 += ZG;
+        const uint64_t idx0 = sh.base + (uint64_t)(it.mb + MB * (tp + pl.TP * (it.dp + DP * a1))) +
+                              (uint64_t)pl.inner * (uint64_t)rel2;
         int z3 = 0, g3 = 0;
         for (int a3 = 0; a3 < ZG; ++a3) {
           if (a3 != a2) {  // uniform
             const Rec r2 = recm[(2 * ZG + a3) * MB];
             const float4 p23 = pair[z2 * Z + z3];
-            const Acc A2 = acc_cross(A1, r2, lc.p2pf * p23.x, lc.p2pf * p23.y, p23.z, single1,
-                                     false);
+            const Acc A2 = acc_cross(A1, r2, it.lc.p2pf * p23.x, it.lc.p2pf * p23.y, p23.z,
+                                     single1, false);
             uint32_t b2 = b1 & r2.bits;
             if (a3 == a1) b2 &= q13a;  // segments 1 and 3 share one pool's quota
             int rel3 = a3 - a2 - 1;
             if (rel3 < 0) rel3 += ZG;
             float T, C;
-            acc_finish(A2, lc, T, C);
+            acc_finish(A2, it.lc, T, C);
             visit<MODE, OBJ, HASB>(a, T, C, b2 != 0, tau,
-                                   idx0 + (uint64_t)pl.inner * (uint64_t)(rel2 + (ZG - 1) * rel3),
-                                   ms, ml);
+                                   idx0 + (uint64_t)pl.inner * (uint64_t)((ZG - 1) * rel3), ms, ml);
           }
           if (++g3 == G) { g3 = 0; ++z3; }
         }
@@ -439,7 +491,7 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
 
   for (int i = t; i < S * ZG; i += blockDim.x) {
     const int seg = i / ZG, p = i % ZG, g = p % G;
-    uint32_t b = quota_bits(pl, sh.n[seg], tpv, pl.avail[p]);
+    uint32_t b = quota_bits(pl, seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]), tpv, pl.avail[p]);
     if (tpv > pl.node[g]) b = 0;  // H1: tensor parallelism stays inside a node
     qm[i] = b;
   }
@@ -458,7 +510,8 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
     const float4 ta = pl.ta[(sl * G + g) * MB + mb];
     const uint32_t bits = pl.memok[(sl * G + g) * MB + mb] & qm[seg * ZG + p] & pl.divis[mb];
     rec[(seg * ZG + p) * MB + mb] = make_rec(ta, pl.smax[sl], pl.upd[sl * G + g], pl.price_f[g],
-                                             pl.p2p_f[mb], pl.ibw_f[z * Z + z], sh.n[seg], bits);
+                                             pl.p2p_f[mb], pl.ibw_f[z * Z + z],
+                                             seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]), bits);
   }
   __syncthreads();
 
@@ -579,18 +632,36 @@ __device__ __forceinline__ bool decode_index(const DevPlan &pl, uint64_t idx, Ca
   return true;
 }
 
-// Stage-by-stage evaluation of one plan in fp64 and exact integers (Sec. 4.3).
-__device__ void eval_exact(const DevPlan &pl, const Cand &c, int objective, int has_bound,
-                           double bound, double &T, double &C, uint64_t &peak, uint32_t &mask) {
+constexpr int kRefineWaves = 4;  // waves per workgroup of k_refine
+
+struct RefineLds {  // per-wave staging of the per-stage terms that are summed in stage order
+  double t[kMaxStages], dol[kMaxStages], comm[kMaxStages];
+};
+
+__device__ __forceinline__ double wave_max_f64(double v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v = fmax(v, __shfl_xor(v, off));
+  return v;
+}
+
+// Stage-by-stage evaluation of one plan in fp64 and exact integers (Sec. 4.3) by one wave:
+// lane i takes stages i, i + 64, ...; maxima are reduced across the wave, sums are taken in
+// stage order (every lane adds the staged terms in the same order, so all lanes hold the
+// same results).
+__device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c, int objective,
+                                                int has_bound, double bound, RefineLds &lds,
+                                                double &T, double &C, uint64_t &peak,
+                                                uint32_t &mask) {
   const int G = pl.G, Z = pl.Z, MB = pl.MB, TP = pl.TP, DP = pl.DP, P = c.P;
+  const int lane = threadIdx.x & 63;
   const ShapeRec sh = pl.shapes[c.shape];
   const uint32_t rs = sh.row_stage;
   const int64_t D = pl.dpv[c.dp], tp = pl.tpv[c.tp];
   mask = 0;
   peak = 0;
   const int64_t nb = pl.nb[c.mb * DP + c.dp];
-  if (nb == 0) {
-    mask = 4u;  // batch not divisible
+  if (nb == 0) {  // uniform over the wave
+    mask = 4u;    // batch not divisible
     T = C = __builtin_huge_val();
     return;
   }
@@ -604,27 +675,27 @@ __device__ void eval_exact(const DevPlan &pl, const Cand &c, int objective, int 
     if (stages * D * tp > (int64_t)pl.avail[c.a[j]]) mask |= 2u;
     if (tp > pl.node[c.a[j] % G]) mask |= 8u;
   }
-  double sum_t = 0.0, max_t = 0.0, t_sync = 0.0, t_upd = 0.0, dollars = 0.0, comm = 0.0;
-  for (int i = 0; i < P; ++i) {
+  double max_t = 0.0, t_sync = 0.0, t_upd = 0.0;
+  uint32_t oom = 0;
+  for (int i = lane; i < P; i += 64) {
     const int seg = i < c.k1 ? 0 : (i < c.k2 ? 1 : 2);
     const int g = c.a[seg] % G, z = c.a[seg] / G;
     const uint64_t m = stage_bytes(pl, rs, i, P, (int)tp, nb, act) + pl.res[g];
-    if (m > pl.cap[g]) mask |= 1u;
+    if (m > pl.cap[g]) oom = 1u;
     peak = m > peak ? m : peak;
-    double x = 0.0;
+    double x = 0.0, comm = 0.0;
     if (i < P - 1) {
       const int sn = (i + 1) < c.k1 ? 0 : ((i + 1) < c.k2 ? 1 : 2);
       const int zn = c.a[sn] / G;
       x += p2p / pl.bw[z * Z + zn];
       if (pl.egress && zn != z)
-        comm += (double)nb * (double)D * p2p * (pl.egress[z * Z + zn] + pl.egress[zn * Z + z]);
+        comm = (double)nb * (double)D * p2p * (pl.egress[z * Z + zn] + pl.egress[zn * Z + z]);
     }
     if (i > 0) {
       const int sp = (i - 1) < c.k1 ? 0 : ((i - 1) < c.k2 ? 1 : 2);
       x += p2p / pl.bw[z * Z + c.a[sp] / G];
     }
     const double t = pl.st_c[(((size_t)(rs + i) * G + g) * MB + c.mb) * TP + c.tp] + x;
-    sum_t += t;
     max_t = fmax(max_t, t);
     if (D > 1) {
       const uint64_t shard = (pl.st_params[rs + i] + (uint64_t)tp - 1) / (uint64_t)tp;
@@ -633,7 +704,29 @@ __device__ void eval_exact(const DevPlan &pl, const Cand &c, int objective, int 
       t_sync = fmax(t_sync, sync);
     }
     t_upd = fmax(t_upd, pl.st_u[((size_t)(rs + i) * G + g) * TP + c.tp]);
-    dollars += (double)(D * tp) * pl.price[g];
+    lds.t[i] = t;
+    lds.dol[i] = (double)(D * tp) * pl.price[g];
+    lds.comm[i] = comm;
+  }
+  if (__builtin_amdgcn_ballot_w64(oom != 0) != 0) mask |= 1u;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const uint64_t o = __shfl_xor((unsigned long long)peak, off);
+    peak = o > peak ? o : peak;
+  }
+  max_t = wave_max_f64(max_t);
+  t_sync = wave_max_f64(t_sync);
+  t_upd = wave_max_f64(t_upd);
+  // LDS operations of one wave complete in order; the fence keeps the compiler from
+  // moving the reads above the writes
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  double sum_t = 0.0, dollars = 0.0, comm = 0.0;
+  for (int i = 0; i < P; ++i) {
+    sum_t += lds.t[i];
+    dollars += lds.dol[i];
+    comm += lds.comm[i];
   }
   T = (sum_t + (double)(nb - 1) * max_t) + t_sync + t_upd;
   C = dollars / 3600.0 * T + comm;
@@ -641,6 +734,7 @@ __device__ void eval_exact(const DevPlan &pl, const Cand &c, int objective, int 
     if (objective == 0) { if (C > bound) mask |= 32u; }
     else if (1.0 / T < bound) mask |= 32u;
   }
+  __builtin_amdgcn_wave_barrier();  // the staging arrays are reused by the next candidate
 }
 
 struct RefineArgs {
@@ -655,10 +749,14 @@ struct RefineArgs {
   double bound;
 };
 
-__global__ void k_refine(DevPlan pl, RefineArgs a) {
+// One wave per survivor.
+__global__ __launch_bounds__(kRefineWaves * 64) void k_refine(DevPlan pl, RefineArgs a) {
+  __shared__ RefineLds lds[kRefineWaves];
   const uint32_t n = min(a.counters[CNT_SURV], a.surv_cap);
   const float tau = a.tau_src ? __uint_as_float(*a.tau_src) * a.band : kPosInf;
-  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+  const uint32_t wave = blockIdx.x * kRefineWaves + (threadIdx.x >> 6);
+  const uint32_t n_waves = gridDim.x * kRefineWaves;
+  for (uint32_t i = wave; i < n; i += n_waves) {
     const SurvRec sv = a.surv[i];
     if (!(sv.key_loose <= tau)) continue;
     Cand c;
@@ -666,10 +764,13 @@ __global__ void k_refine(DevPlan pl, RefineArgs a) {
     RefRec r;
     r.idx = sv.idx;
     r.pad = 0;
-    eval_exact(pl, c, a.objective, a.has_bound, a.bound, r.T, r.C, r.mem, r.mask);
-    const uint32_t slot = atomicAdd(&a.counters[CNT_REF], 1u);
-    if (slot < a.ref_cap) a.ref[slot] = r;
-    if (r.mask == 0) atomicAdd(&a.counters[CNT_FEAS], 1u);
+    eval_exact_wave(pl, c, a.objective, a.has_bound, a.bound, lds[threadIdx.x >> 6], r.T, r.C,
+                    r.mem, r.mask);
+    if ((threadIdx.x & 63) == 0) {
+      const uint32_t slot = atomicAdd(&a.counters[CNT_REF], 1u);
+      if (slot < a.ref_cap) a.ref[slot] = r;
+      if (r.mask == 0) atomicAdd(&a.counters[CNT_FEAS], 1u);
+    }
   }
 }
 
@@ -680,13 +781,15 @@ __device__ __forceinline__ bool lex_less(double ka, uint64_t ia, double kb, uint
 // Best plan: minimum fp64 key over valid candidates, then the lowest index within the
 // tie tolerance of it.  One workgroup; results go to host-mapped memory.
 __global__ __launch_bounds__(1024) void k_pick_best(const RefRec *ref, uint32_t ref_cap,
-                                                    const uint32_t *counters, int objective,
+                                                    const uint32_t *counters,
+                                                    uint32_t *next_counters, int objective,
                                                     ResultHeader *hdr, RefRec *out) {
   __shared__ double s_key[1024];
   __shared__ unsigned long long s_idx[1024];
   __shared__ uint32_t s_pos[1024];
   const uint32_t n = min(counters[CNT_REF], ref_cap);
   const int t = threadIdx.x;
+  if (t < CNT_COUNT) next_counters[t] = counter_reset_value(t);  // for the next call
   double best = __builtin_huge_val();
   for (uint32_t i = t; i < n; i += blockDim.x)
     if (ref[i].mask == 0) best = fmin(best, objective == 0 ? ref[i].T : ref[i].C);
@@ -722,10 +825,19 @@ __global__ __launch_bounds__(1024) void k_pick_best(const RefRec *ref, uint32_t 
 }
 
 // Top-k: the rank of every valid re-evaluated candidate in ascending (key, index) order,
-// by counting; ranks below k are written to host-mapped memory.
-__global__ void k_rank_topk(const RefRec *ref, uint32_t ref_cap, const uint32_t *counters,
-                            int objective, uint32_t k, ResultHeader *hdr, RefRec *out) {
+// by counting against tiles of the list staged in LDS; ranks below k are written to
+// host-mapped memory.
+constexpr int kRankTile = 1024;
+
+__global__ __launch_bounds__(256) void k_rank_topk(const RefRec *ref, uint32_t ref_cap,
+                                                   const uint32_t *counters,
+                                                   uint32_t *next_counters, int objective,
+                                                   uint32_t k, ResultHeader *hdr, RefRec *out) {
+  __shared__ double t_key[kRankTile];
+  __shared__ unsigned long long t_idx[kRankTile];
   const uint32_t n = min(counters[CNT_REF], ref_cap);
+  if (blockIdx.x == 0 && threadIdx.x < CNT_COUNT)
+    next_counters[threadIdx.x] = counter_reset_value(threadIdx.x);  // for the next call
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     const uint32_t f = counters[CNT_FEAS];
     hdr->n_found = f < k ? f : k;
@@ -733,16 +845,28 @@ __global__ void k_rank_topk(const RefRec *ref, uint32_t ref_cap, const uint32_t 
     hdr->ref_count = counters[CNT_REF];
     hdr->feasible_count = f;
   }
-  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
-    const RefRec me = ref[i];
-    if (me.mask != 0) continue;
-    const double mk = objective == 0 ? me.T : me.C;
+  // uniform trip counts: every thread of a workgroup takes part in the tile barriers
+  for (uint32_t base = blockIdx.x * blockDim.x; base < n; base += gridDim.x * blockDim.x) {
+    const uint32_t i = base + threadIdx.x;
+    const bool mine = i < n && ref[i].mask == 0;
+    const double mk = mine ? (objective == 0 ? ref[i].T : ref[i].C) : 0.0;
+    const uint64_t mi = mine ? ref[i].idx : 0;
     uint32_t rank = 0;
-    for (uint32_t j = 0; j < n; ++j) {
-      const double kj = objective == 0 ? ref[j].T : ref[j].C;
-      if (ref[j].mask == 0 && lex_less(kj, ref[j].idx, mk, me.idx)) ++rank;
+    for (uint32_t t0 = 0; t0 < n; t0 += kRankTile) {
+      const uint32_t tn = min((uint32_t)kRankTile, n - t0);
+      __syncthreads();
+      for (uint32_t j = threadIdx.x; j < tn; j += blockDim.x) {
+        const RefRec &o = ref[t0 + j];
+        // an invalid entry never precedes anything
+        t_key[j] = o.mask == 0 ? (objective == 0 ? o.T : o.C) : __builtin_huge_val();
+        t_idx[j] = o.mask == 0 ? o.idx : ~0ull;
+      }
+      __syncthreads();
+      if (mine)
+        for (uint32_t j = 0; j < tn; ++j)
+          if (lex_less(t_key[j], t_idx[j], mk, mi)) ++rank;
     }
-    if (rank < k) out[rank] = me;
+    if (mine && rank < k) out[rank] = ref[i];
   }
 }
 
