@@ -155,6 +155,22 @@ def main() -> int:
             eval_ms += plan.last_timing()[1] / 5
     plan.set_timing(0)
 
+    # availability stream: 64 snapshots of the 4-zone x 3-type cluster, a full re-plan
+    # (6 791 040 candidates) at each: latency of set_avail + best_plan
+    import numpy as np
+    prob5 = workloads.config3()
+    plan5 = Plan(prob5)
+    lat = []
+    for snap in workloads.config5_snapshots(prob5):
+        t0 = time.perf_counter()
+        plan5.set_avail(snap)
+        plan5.best_plan(objective=MAX_THROUGHPUT, stream=stream)
+        lat.append((time.perf_counter() - t0) * 1e3)
+    n5 = plan5.num_candidates()
+    plan5.destroy()
+    replan = {"snapshots": len(lat), "candidates": n5, "p50_ms": float(np.percentile(lat, 50)),
+              "p99_ms": float(np.percentile(lat, 99))}
+
     if args.copy_probe:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").fill_(1.0)
         dst = torch.empty_like(src)
@@ -185,7 +201,7 @@ def main() -> int:
                   "eval_batch_ms": eval_ms,
                   "eval_batch_candidates_per_s": n / (eval_ms * 1e-3),
                   "eval_batch_output_GBps": 20.0 * n / (eval_ms * 1e-3) / 1e9,
-                  "plan_create_ms": create_ms, "best_index": best.index,
+                  "plan_create_ms": create_ms, "replan_stream": replan, "best_index": best.index,
                   "top1_index": top1_index},
     }
     if not args.no_cpu_baseline:

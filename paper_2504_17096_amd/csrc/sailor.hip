@@ -20,6 +20,9 @@ namespace {
 constexpr uint32_t kSurvCap = 1u << 22;  // 64 MiB of survivors
 constexpr uint32_t kRefCap = 1u << 18;
 constexpr uint32_t kUnitTarget = 16384;  // candidates per scan workgroup
+constexpr uint32_t kEvalUnitTarget = 16384;  // candidates per workgroup of the range evaluation
+constexpr unsigned kEvalRowsThreads = 512;
+constexpr size_t kEvalRowsMaxLds = 64 * 1024;  // above this the range form evaluates lane by lane
 
 #define HIP_TRY(expr)                                                              \
   do {                                                                             \
@@ -62,6 +65,9 @@ struct sailor_plan {
   std::vector<ShapeRec> shapes;
   std::vector<BlockRec> blocks;
   std::vector<UnitRec> units;
+  std::vector<EvalUnit> eunits;  // range evaluation, ascending idx_lo
+  const EvalUnit *d_eunits = nullptr;
+  size_t eval_lds_bytes = 0;
   std::vector<int32_t> mbv, tpv, dpv, ppv;
   int device = 0;
   size_t lds_bytes = 0;
@@ -254,6 +260,22 @@ sailor_status build_space(const sailor_problem *p, sailor_plan *pl, std::vector<
         u.o_cnt = (uint16_t)(hi - lo);
         pl->units.push_back(u);
       }
+  }
+  // units of the range evaluation: (shape, range of the outer pool digits), about 16 Ki
+  // candidates each, in index order
+  for (uint32_t si = 0; si < pl->shapes.size(); ++si) {
+    const ShapeRec &sh = pl->shapes[si];
+    uint64_t o_total = 1;
+    for (int j = 1; j < sh.s; ++j) o_total *= (uint64_t)(ZG - 1);
+    const uint64_t chunk = std::min<uint64_t>(o_total, std::max<uint64_t>(1, kEvalUnitTarget / inner));
+    for (uint64_t lo = 0; lo < o_total; lo += chunk) {
+      EvalUnit e{};
+      e.shape = si;
+      e.o_lo = (uint32_t)lo;
+      e.o_cnt = (uint32_t)std::min<uint64_t>(chunk, o_total - lo);
+      e.idx_lo = sh.base + lo * inner;
+      pl->eunits.push_back(e);
+    }
   }
   // Largest units first, so that the small ones fill the tail of the launch.
   auto unit_cost = [&](const UnitRec &u) {  // candidates of the unit
@@ -490,6 +512,13 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   d.mg_mb = magic((uint32_t)d.MB);
   d.mg_mbdp = magic((uint32_t)(d.MB * d.DP));
   d.mg_g = magic((uint32_t)d.G);
+  d.mg_mbtp = magic((uint32_t)(d.MB * d.TP));
+  d.mg_mbtpdp = magic((uint32_t)(d.MB * d.TP * d.DP));
+  pl->eval_lds_bytes = (size_t)3 * d.TP * d.ZG * d.MB * sizeof(Rec) +
+                       (size_t)d.Z * d.Z * sizeof(float4) +
+                       (size_t)3 * d.TP * d.MB * d.DP * sizeof(uint64_t) +
+                       (size_t)4 * d.TP * d.ZG * sizeof(uint32_t) +
+                       (size_t)d.ZG * (sizeof(PoolInfo) + sizeof(uint32_t));
   pl->lds_bytes = (size_t)3 * d.ZG * d.MB * sizeof(Rec) + (size_t)d.Z * d.Z * sizeof(float4) +
                   (size_t)4 * d.ZG * sizeof(uint32_t);
 
@@ -533,6 +562,7 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(ar.upload(&d.shapes, pl->shapes.data(), NS));
   CREATE_TRY(ar.upload(&d.blocks, pl->blocks.data(), pl->blocks.size()));
   CREATE_TRY(ar.upload(&d.units, pl->units.data(), pl->units.size()));
+  CREATE_TRY(ar.upload(&pl->d_eunits, pl->eunits.data(), pl->eunits.size()));
   // derived tables, filled by the set-up kernels
   CREATE_TRY(ar.alloc(&d.ibw_f, (size_t)Z * Z));
   CREATE_TRY(ar.alloc(&d.egs_f, (size_t)Z * Z));
@@ -620,6 +650,28 @@ sailor_status sailor_eval_batch(sailor_plan *pl, uint64_t first, uint64_t count,
   a.has_bound = (constraint && constraint->has_bound) ? 1 : 0;
   a.bound = a.has_bound ? (float)constraint->bound : 0.f;
   const bool timed = pl->timing_mode >= 1;
+  if (!d_indices && pl->eval_lds_bytes <= kEvalRowsMaxLds) {
+    // the units that intersect [first, first + count)
+    auto end_of = [&](const EvalUnit &e) { return e.idx_lo + (uint64_t)e.o_cnt * pl->dev.inner; };
+    size_t lo = 0, hi = pl->eunits.size();
+    while (lo < hi) {  // first unit that ends after `first`
+      const size_t mid = (lo + hi) / 2;
+      if (end_of(pl->eunits[mid]) <= first) lo = mid + 1; else hi = mid;
+    }
+    const size_t u0 = lo;
+    hi = pl->eunits.size();
+    while (lo < hi) {  // first unit that starts at or after the end of the range
+      const size_t mid = (lo + hi) / 2;
+      if (pl->eunits[mid].idx_lo < first + count) lo = mid + 1; else hi = mid;
+    }
+    launch(k_eval_rows, dim3((unsigned)(lo - u0)), dim3(kEvalRowsThreads), pl->eval_lds_bytes, st,
+           timed ? pl->ev[3] : nullptr, timed ? pl->ev[1] : nullptr, pl->dev, a, pl->d_eunits,
+           (uint32_t)u0);
+    HIP_TRY(hipGetLastError());
+    pl->total_timed = false;
+    pl->scan_timed = timed;
+    return SAILOR_OK;
+  }
   launch(k_eval_direct, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st,
          timed ? pl->ev[3] : nullptr, timed ? pl->ev[1] : nullptr, pl->dev, a);
   HIP_TRY(hipGetLastError());

@@ -46,6 +46,13 @@ struct UnitRec {        // work of one workgroup of the scan: one shape, one tp,
   uint16_t o_lo, o_cnt;
 };
 
+struct EvalUnit {       // work of one workgroup of the range evaluation: one shape, all tp,
+  uint64_t idx_lo;      // a contiguous index range = a range of the outer pool digits
+  uint32_t shape;
+  uint32_t o_lo, o_cnt;
+  uint32_t pad;
+};
+
 struct SurvRec {        // candidate kept for the fp64 re-evaluation
   uint64_t idx;
   float key;            // fp32 key; +inf when only loosely inside the constraint
@@ -67,7 +74,8 @@ struct DevPlan {
   int n_blocks, n_shapes, n_units, n_row_stages;
   uint32_t inner;          // MB*TP*DP*ZG candidates per (shape, outer pool digits)
   uint32_t bpp, gb;
-  uint32_t mg_mb, mg_mbdp, mg_g;  // ceil(2^32 / d) for d = MB, MB*DP, G (0 encodes d = 1)
+  // ceil(2^32 / d) for d = MB, MB*DP, G, MB*TP, MB*TP*DP (0 encodes d = 1)
+  uint32_t mg_mb, mg_mbdp, mg_g, mg_mbtp, mg_mbtpdp;
   int64_t B;
   uint64_t N;
   int mbv[kMaxMB], tpv[kMaxTP], dpv[kMaxDP];

@@ -951,4 +951,170 @@ __global__ __launch_bounds__(256) void k_eval_direct(DevPlan pl, EvalArgs a) {
   if (a.mask) a.mask[i] = mask;
 }
 
+// Range form of sailor_eval_batch.  One workgroup per EvalUnit: the records of the unit's
+// shape for every tp are staged in LDS.  A lane keeps its inner digits (mb, tp, dp, pool 1)
+// while the unit's outer pool digits advance, and consecutive lanes hold consecutive
+// candidate indices, so every store instruction writes 64 consecutive elements.
+struct PoolInfo {   // per pool, staged in LDS
+  uint64_t res, cap;
+};
+
+template <int S>
+__device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs &a,
+                                               const EvalUnit &u, const ShapeRec &sh,
+                                               const Rec *rec, const float4 *pair,
+                                               const uint32_t *qm, const uint32_t *q13,
+                                               const uint64_t *need, const PoolInfo *pinfo,
+                                               const uint32_t *pmeta) {
+  const int ZG = pl.ZG, MB = pl.MB, TP = pl.TP, DP = pl.DP, Z = pl.Z;
+  const uint32_t inner = pl.inner;
+  const uint64_t last = a.first + a.count;
+  const bool single0 = sh.n[0] == 1, single1 = sh.n[1] == 1;
+  for (uint32_t in = threadIdx.x; in < inner; in += blockDim.x) {
+    const uint32_t a1 = fast_div(in, pl.mg_mbtpdp), rem = in - a1 * (uint32_t)(MB * TP * DP);
+    const uint32_t dp = fast_div(rem, pl.mg_mbtp), rem2 = rem - dp * (uint32_t)(MB * TP);
+    const uint32_t tp = fast_div(rem2, pl.mg_mb), mb = rem2 - tp * (uint32_t)MB;
+    const bool divisible = pl.nb[mb * DP + dp] != 0;
+    LaneC lc;
+    lc.p2pf = pl.p2p_f[mb];
+    lc.nbm1 = pl.nbm1_f[mb * DP + dp];
+    lc.cd = pl.cd_f[dp];
+    lc.dtp = pl.dtp_f[tp * DP + dp];
+    lc.xb = pl.xb_f[mb];
+    const uint32_t tpbit = 1u << (8 + tp);
+    // this lane's slices of the staged tables
+    const Rec *recl = rec + (size_t)tp * ZG * MB + mb;          // + (seg * TP * ZG + pool) * MB
+    const uint64_t *needl = need + (tp * MB + mb) * DP + dp;    // + seg * TP * MB * DP
+    const uint32_t *qml = qm + tp * ZG;                         // + seg * TP * ZG + pool
+    // segment 1 does not change while the outer digits advance
+    const int p0 = (int)a1;
+    const Rec r0 = recl[p0 * MB];
+    const Acc A0 = acc_begin(r0);
+    const PoolInfo i0 = pinfo[p0];
+    const uint32_t m0 = pmeta[p0];
+    const uint64_t mem0 = needl[0] + i0.res;
+    uint32_t mask0 = 0;
+    if (mem0 > i0.cap) mask0 |= 1u;
+    if (m0 & tpbit) mask0 |= 8u;
+    const bool q0 = (qml[p0] >> dp) & 1u;
+    const bool q0_13 = S == 3 ? ((q13[tp * ZG + p0] >> dp) & 1u) : true;
+    const int z0 = (int)(m0 & 0xFFu);
+    for (uint32_t o = 0; o < u.o_cnt; ++o) {
+      const uint64_t idx = u.idx_lo + (uint64_t)o * inner + in;
+      if (idx < a.first || idx >= last) continue;
+      const uint32_t oa = u.o_lo + o;
+      float T = kPosInf, C = kPosInf;
+      uint64_t peak = 0;
+      uint32_t mask = 4u;
+      if (divisible) {
+        mask = mask0;
+        peak = mem0;
+        Acc acc = A0;
+        bool quota_ok = q0;
+        if (S >= 2) {
+          const int r2 = (int)(oa % (uint32_t)(ZG - 1));  // uniform
+          int p1 = p0 + 1 + r2;
+          if (p1 >= ZG) p1 -= ZG;
+          const Rec r1 = recl[(TP * ZG + p1) * MB];
+          const PoolInfo i1 = pinfo[p1];
+          const uint32_t m1 = pmeta[p1];
+          const int z1 = (int)(m1 & 0xFFu);
+          const uint64_t mem1 = needl[TP * MB * DP] + i1.res;
+          if (mem1 > i1.cap) mask |= 1u;
+          if (m1 & tpbit) mask |= 8u;
+          peak = mem1 > peak ? mem1 : peak;
+          quota_ok = quota_ok && ((qml[TP * ZG + p1] >> dp) & 1u);
+          const float4 pr = pair[z0 * Z + z1];
+          acc = acc_cross(acc, r1, lc.p2pf * pr.x, lc.p2pf * pr.y, pr.z, single0, true);
+          if (S == 3) {
+            const int r3 = (int)(oa / (uint32_t)(ZG - 1));  // uniform
+            int p2 = p1 + 1 + r3;
+            if (p2 >= ZG) p2 -= ZG;
+            const Rec r2r = recl[(2 * TP * ZG + p2) * MB];
+            const PoolInfo i2 = pinfo[p2];
+            const uint32_t m2 = pmeta[p2];
+            const uint64_t mem2 = needl[2 * TP * MB * DP] + i2.res;
+            if (mem2 > i2.cap) mask |= 1u;
+            if (m2 & tpbit) mask |= 8u;
+            peak = mem2 > peak ? mem2 : peak;
+            if (p2 == p0) {  // segments 1 and 3 share one pool's quota
+              quota_ok = q0_13 && ((qml[TP * ZG + p1] >> dp) & 1u);
+            } else {
+              quota_ok = quota_ok && ((qml[2 * TP * ZG + p2] >> dp) & 1u);
+            }
+            const float4 pr2 = pair[z1 * Z + (int)(m2 & 0xFFu)];
+            acc = acc_cross(acc, r2r, lc.p2pf * pr2.x, lc.p2pf * pr2.y, pr2.z, single1, false);
+          }
+        }
+        if (!quota_ok) mask |= 2u;
+        acc_finish(acc, lc, T, C);
+        if (a.has_bound) {
+          if (a.objective == 0) { if (C > a.bound) mask |= 32u; }
+          else if (1.0f / T < a.bound) mask |= 32u;
+        }
+      }
+      const uint64_t out = idx - a.first;
+      if (a.time) a.time[out] = T;
+      if (a.cost) a.cost[out] = C;
+      if (a.mem) a.mem[out] = peak;
+      if (a.mask) a.mask[out] = mask;
+    }
+  }
+}
+
+__global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const EvalUnit *units,
+                                                   uint32_t unit0) {
+  extern __shared__ uint4 lds_raw[];
+  const EvalUnit u = units[unit0 + blockIdx.x];
+  const ShapeRec sh = pl.shapes[u.shape];
+  const int ZG = pl.ZG, G = pl.G, MB = pl.MB, TP = pl.TP, DP = pl.DP, Z = pl.Z, S = sh.s;
+  Rec *rec = reinterpret_cast<Rec *>(lds_raw);                           // [3][TP][ZG][MB]
+  float4 *pair = reinterpret_cast<float4 *>(rec + 3 * TP * ZG * MB);     // [Z][Z]
+  PoolInfo *pinfo = reinterpret_cast<PoolInfo *>(pair + Z * Z);          // [ZG]
+  uint64_t *need = reinterpret_cast<uint64_t *>(pinfo + ZG);             // [3][TP][MB][DP]
+  uint32_t *qm = reinterpret_cast<uint32_t *>(need + 3 * TP * MB * DP);  // [3][TP][ZG]
+  uint32_t *q13 = qm + 3 * TP * ZG;                                      // [TP][ZG]
+  uint32_t *pmeta = q13 + TP * ZG;  // [ZG] zone | (bit 8 + k: tp k exceeds the node size) (H1)
+  const int t = threadIdx.x;
+  for (int i = t; i < S * TP * ZG; i += blockDim.x) {
+    const int p = i % ZG, k = (i / ZG) % TP, seg = i / (ZG * TP);
+    qm[i] = quota_bits(pl, seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]), pl.tpv[k],
+                       pl.avail[p]);
+  }
+  if (S == 3)
+    for (int i = t; i < TP * ZG; i += blockDim.x)
+      q13[i] = quota_bits(pl, sh.n[0] + sh.n[2], pl.tpv[i / ZG], pl.avail[i % ZG]);
+  for (int p = t; p < ZG; p += blockDim.x) {
+    const int g = p % G;
+    PoolInfo pi;
+    pi.res = pl.res[g];
+    pi.cap = pl.cap[g];
+    pinfo[p] = pi;
+    uint32_t m = (uint32_t)(p / G);
+    for (int k = 0; k < TP; ++k)
+      if (pl.tpv[k] > pl.node[g]) m |= 1u << (8 + k);
+    pmeta[p] = m;
+  }
+  for (int i = t; i < Z * Z; i += blockDim.x) {
+    const int za = i / Z, zb = i % Z;
+    pair[i] = make_float4(pl.ibw_f[za * Z + zb], pl.ibw_f[zb * Z + za], pl.egs_f[i], 0.f);
+  }
+  for (int i = t; i < S * TP * MB * DP; i += blockDim.x) {
+    const int md = i % (MB * DP), k = (i / (MB * DP)) % TP, seg = i / (MB * DP * TP);
+    need[i] = pl.need[agg_slot(pl, u.shape, k, seg) * MB * DP + md];
+  }
+  for (int i = t; i < S * TP * ZG * MB; i += blockDim.x) {
+    const int mb = i % MB, p = (i / MB) % ZG, k = (i / (MB * ZG)) % TP, seg = i / (MB * ZG * TP);
+    const int g = p % G, z = p / G;
+    const size_t sl = agg_slot(pl, u.shape, k, seg);
+    rec[i] = make_rec(pl.ta[(sl * G + g) * MB + mb], pl.smax[sl], pl.upd[sl * G + g],
+                      pl.price_f[g], pl.p2p_f[mb], pl.ibw_f[z * Z + z],
+                      seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]), 0u);
+  }
+  __syncthreads();
+  if (S == 1) eval_rows_body<1>(pl, a, u, sh, rec, pair, qm, q13, need, pinfo, pmeta);
+  else if (S == 2) eval_rows_body<2>(pl, a, u, sh, rec, pair, qm, q13, need, pinfo, pmeta);
+  else eval_rows_body<3>(pl, a, u, sh, rec, pair, qm, q13, need, pinfo, pmeta);
+}
+
 }  // namespace sailor

@@ -62,3 +62,24 @@ def find_index(orc, **want):
         if all(getattr(cfg, k) == v for k, v in want.items()):
             return c
     raise LookupError(want)
+
+
+def wide_problem(seed=0):
+    """Every list at its limit: 64 pools (16 zones x 4 types), 8 microbatch sizes, 8 TP
+    degrees, 24 DP degrees; a short model so that the space stays small."""
+    rng = np.random.default_rng(seed)
+    G, Z, L = 4, 16, 2
+    mb, tp, dp = tuple(range(1, 9)), tuple(range(1, 9)), tuple(range(1, 25))
+    bw = rng.uniform(0.5e9, 2e9, (Z, Z))
+    np.fill_diagonal(bw, 1e10)
+    eg = rng.uniform(1e-11, 5e-11, (Z, Z))
+    return make_problem(
+        n_layers=L, n_types=G, n_zones=Z, mb_list=mb, tp_list=tp, dp_list=dp, pp_list=[1, 2],
+        global_batch=840, max_segments=2,
+        t_fwd=rng.uniform(0.5e-3, 3e-3, (G, 8, 8, 1)), t_bwd=rng.uniform(1e-3, 5e-3, (G, 8, 8, 1)),
+        t_upd=rng.uniform(1e-4, 3e-4, (G, 8, 1)), layer_params=30_000_000, embed=7_000_001,
+        head=5_000_003, act=rng.integers(10_000_000, 400_000_000, (8, 8)).astype(np.uint64),
+        p2p=rng.integers(1_000_000, 9_000_000, 8).astype(np.uint64),
+        cap=np.array([4, 2, 1, 1], np.uint64) * np.uint64(GIB), reserved=100_000_000,
+        node=np.array([8, 4, 2, 1], np.int32), price=rng.uniform(0.5, 4.0, G),
+        avail=rng.integers(0, 40, (Z, G)), bw=bw, egress=eg)

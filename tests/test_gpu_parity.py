@@ -12,7 +12,7 @@ import pytest
 
 from oracle.oracle import MAX_THROUGHPUT, MIN_COST, Oracle
 from paper_2504_17096_amd import workloads as W
-from tests.helpers import make_problem
+from tests.helpers import make_problem, wide_problem
 
 pytestmark = pytest.mark.gpu
 
@@ -100,6 +100,7 @@ PROBLEMS = {
     "tiny5": lambda: W.tiny_problem(5, n_layers=12, max_segments=2, with_egress=False),
     "tiny6": lambda: W.tiny_problem(6, n_zones=1, n_types=1),
     "onepool": lambda: make_problem(n_layers=4, max_segments=3, seg3_max_pp=4),
+    "wide": wide_problem,
 }
 
 
