@@ -510,7 +510,8 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   pl->ppv.assign(p->pp_values, p->pp_values + p->n_pp);
   auto magic = [](uint32_t dv) { return dv == 1 ? 0u : (uint32_t)(((1ull << 32) + dv - 1) / dv); };
   d.mg_mb = magic((uint32_t)d.MB);
-  d.mg_mbdp = magic((uint32_t)(d.MB * d.DP));
+  d.mg_mbzg = magic((uint32_t)(d.MB * d.ZG));
+  d.mg_mbzg1 = d.ZG > 1 ? magic((uint32_t)(d.MB * (d.ZG - 1))) : 0u;
   d.mg_g = magic((uint32_t)d.G);
   d.mg_mbtp = magic((uint32_t)(d.MB * d.TP));
   d.mg_mbtpdp = magic((uint32_t)(d.MB * d.TP * d.DP));

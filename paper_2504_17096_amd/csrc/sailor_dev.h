@@ -74,8 +74,8 @@ struct DevPlan {
   int n_blocks, n_shapes, n_units, n_row_stages;
   uint32_t inner;          // MB*TP*DP*ZG candidates per (shape, outer pool digits)
   uint32_t bpp, gb;
-  // ceil(2^32 / d) for d = MB, MB*DP, G, MB*TP, MB*TP*DP (0 encodes d = 1)
-  uint32_t mg_mb, mg_mbdp, mg_g, mg_mbtp, mg_mbtpdp;
+  // ceil(2^32 / d) for d = MB, G, MB*TP, MB*TP*DP, MB*ZG, MB*(ZG-1) (0 encodes d = 1)
+  uint32_t mg_mb, mg_g, mg_mbtp, mg_mbtpdp, mg_mbzg, mg_mbzg1;
   int64_t B;
   uint64_t N;
   int mbv[kMaxMB], tpv[kMaxTP], dpv[kMaxDP];

@@ -353,17 +353,19 @@ struct LaneItem {  // what a lane owns for one chunk of the lane space
   uint32_t dpbit;
 };
 
-// lane item e of a lane space laid out as mb + MB * (dp + DP * a1)
-__device__ __forceinline__ LaneItem lane_item(const DevPlan &pl, int e, int n_items, int tp) {
+// Lane item e of a lane space laid out as mb + MB * (a1 + n_a1 * dp): the dp digit is the
+// slowest, so a wave holds one or two dp values and whole waves drop out together when
+// their data-parallel degree cannot be placed.  mg = ceil(2^32 / (MB * n_a1)).
+__device__ __forceinline__ LaneItem lane_item(const DevPlan &pl, int e, int n_items, int n_a1,
+                                              uint32_t mg, int tp) {
   LaneItem it;
   it.active = e < n_items;
   const uint32_t ee = it.active ? (uint32_t)e : 0u;
-  const uint32_t mbdp = (uint32_t)(pl.MB * pl.DP);
-  const uint32_t a1 = fast_div(ee, pl.mg_mbdp), rem = ee - a1 * mbdp;
-  const uint32_t dp = fast_div(rem, pl.mg_mb);
+  const uint32_t dp = fast_div(ee, mg), rem = ee - dp * (uint32_t)(pl.MB * n_a1);
+  const uint32_t a1 = fast_div(rem, pl.mg_mb);
   it.a1 = (int)a1;
   it.dp = (int)dp;
-  it.mb = (int)(rem - dp * (uint32_t)pl.MB);
+  it.mb = (int)(rem - a1 * (uint32_t)pl.MB);
   it.lc.p2pf = pl.p2p_f[it.mb];
   it.lc.nbm1 = pl.nbm1_f[it.mb * pl.DP + it.dp];
   it.lc.cd = pl.cd_f[it.dp];
@@ -374,13 +376,18 @@ __device__ __forceinline__ LaneItem lane_item(const DevPlan &pl, int e, int n_it
   return it;
 }
 
-// The lanes of a workgroup own the (mb, dp, pool of segment 1) triples; the pools of the
+__device__ __forceinline__ bool wave_any(bool p) { return __builtin_amdgcn_ballot_w64(p) != 0; }
+
+// The lanes of a workgroup own the (mb, pool of segment 1, dp) triples; the pools of the
 // later segments are walked in uniform loops, so their record addresses, zones and
 // transfer terms are the same for the whole wave.
 //   one or two segments: lanes cover every pool 1; in the loop over pool 2 a lane whose own
 //     pool equals it sits that iteration out;
 //   three segments: pool 2 is the outer uniform loop, lanes cover the ZG - 1 other pools,
 //     pool 3 is the inner uniform loop.
+// Invalid plans are pruned early (cf. H2, Sec. 4.2.1): as soon as the validity bits of the
+// segments placed so far are zero in every lane of a wave, the wave skips everything that
+// depends on the remaining segments.
 template <int S, int MODE, int OBJ, bool HASB>
 __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, const UnitRec &u,
                                           const ShapeRec &sh, const Rec *rec, const float4 *pair,
@@ -392,13 +399,15 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
   if (S <= 2) {
     const int nin = MB * DP * ZG;
     for (int e0 = wave * 64; e0 < nin; e0 += nwave * 64) {
-      const LaneItem it = lane_item(pl, e0 + lane, nin, tp);
-      const int a1 = it.a1, z1 = (int)fast_div((uint32_t)a1, pl.mg_g);
+      const LaneItem it = lane_item(pl, e0 + lane, nin, ZG, pl.mg_mbzg, tp);
+      const int a1 = it.a1;
       const Rec *recm = rec + it.mb;         // this lane's column of the record table
-      const float4 *pair1 = pair + z1 * Z;   // transfers out of this lane's first zone
       const Rec r0 = recm[a1 * MB];
-      const Acc A0 = acc_begin(r0);
       const uint32_t b0 = r0.bits & it.dpbit;
+      if (!wave_any(b0 != 0)) continue;
+      const int z1 = (int)fast_div((uint32_t)a1, pl.mg_g);
+      const float4 *pair1 = pair + z1 * Z;   // transfers out of this lane's first zone
+      const Acc A0 = acc_begin(r0);
       // index of the candidate whose outer digits are all zero
       const uint64_t idx0 = sh.base + (uint64_t)(it.mb + MB * (tp + pl.TP * (it.dp + DP * a1)));
       if (S == 1) {
@@ -409,17 +418,20 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
       }
       int z2 = u.o_lo / G, g2 = u.o_lo % G;
       for (int a2 = u.o_lo; a2 < u.o_lo + u.o_cnt; ++a2) {
-        const Rec r1 = recm[(ZG + a2) * MB];
-        const float4 p12 = pair1[z2];
-        const Acc A1 = acc_cross(A0, r1, it.lc.p2pf * p12.x, it.lc.p2pf * p12.y, p12.z, single0,
-                                 true);
-        const uint32_t b1 = (a1 != a2) ? (b0 & r1.bits) : 0u;
-        int rel2 = a2 - a1 - 1;
-        if (rel2 < 0) rel2 += ZG;
-        float T, C;
-        acc_finish(A1, it.lc, T, C);
-        visit<MODE, OBJ, HASB>(a, T, C, b1 != 0, tau, idx0 + (uint64_t)pl.inner * (uint64_t)rel2,
-                               ms, ml);
+        const Rec *rp1 = recm + (ZG + a2) * MB;
+        const uint32_t b1 = (a1 != a2) ? (b0 & rp1->bits) : 0u;
+        if (wave_any(b1 != 0)) {
+          const Rec r1 = *rp1;
+          const float4 p12 = pair1[z2];
+          const Acc A1 = acc_cross(A0, r1, it.lc.p2pf * p12.x, it.lc.p2pf * p12.y, p12.z,
+                                   single0, true);
+          int rel2 = a2 - a1 - 1;
+          if (rel2 < 0) rel2 += ZG;
+          float T, C;
+          acc_finish(A1, it.lc, T, C);
+          visit<MODE, OBJ, HASB>(a, T, C, b1 != 0, tau,
+                                 idx0 + (uint64_t)pl.inner * (uint64_t)rel2, ms, ml);
+        }
         if (++g2 == G) { g2 = 0; ++z2; }
       }
     }
@@ -428,16 +440,17 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
     int z2 = u.o_lo / G, g2 = u.o_lo % G;
     for (int a2 = u.o_lo; a2 < u.o_lo + u.o_cnt; ++a2) {
       for (int e0 = wave * 64; e0 < nin; e0 += nwave * 64) {
-        const LaneItem it = lane_item(pl, e0 + lane, nin, tp);
+        const LaneItem it = lane_item(pl, e0 + lane, nin, ZG - 1, pl.mg_mbzg1, tp);
         const int a1 = it.a1 + (it.a1 >= a2 ? 1 : 0);  // skip the pool of segment 2
-        const int z1 = (int)fast_div((uint32_t)a1, pl.mg_g);
         const Rec *recm = rec + it.mb;
         const Rec r0 = recm[a1 * MB];
         const Rec r1 = recm[(ZG + a2) * MB];
+        const uint32_t b1 = r0.bits & it.dpbit & r1.bits;
+        if (!wave_any(b1 != 0)) continue;
+        const int z1 = (int)fast_div((uint32_t)a1, pl.mg_g);
         const float4 p12 = pair[z1 * Z + z2];
         const Acc A1 = acc_cross(acc_begin(r0), r1, it.lc.p2pf * p12.x, it.lc.p2pf * p12.y, p12.z,
                                  single0, true);
-        const uint32_t b1 = r0.bits & it.dpbit & r1.bits;
         const uint32_t q13a = q13[a1];
         int rel2 = a2 - a1 - 1;
         if (rel2 < 0) rel2 += ZG;
@@ -446,18 +459,22 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
         int z3 = 0, g3 = 0;
         for (int a3 = 0; a3 < ZG; ++a3) {
           if (a3 != a2) {  // uniform
-            const Rec r2 = recm[(2 * ZG + a3) * MB];
-            const float4 p23 = pair[z2 * Z + z3];
-            const Acc A2 = acc_cross(A1, r2, it.lc.p2pf * p23.x, it.lc.p2pf * p23.y, p23.z,
-                                     single1, false);
-            uint32_t b2 = b1 & r2.bits;
+            const Rec *rp2 = recm + (2 * ZG + a3) * MB;
+            uint32_t b2 = b1 & rp2->bits;
             if (a3 == a1) b2 &= q13a;  // segments 1 and 3 share one pool's quota
-            int rel3 = a3 - a2 - 1;
-            if (rel3 < 0) rel3 += ZG;
-            float T, C;
-            acc_finish(A2, it.lc, T, C);
-            visit<MODE, OBJ, HASB>(a, T, C, b2 != 0, tau,
-                                   idx0 + (uint64_t)pl.inner * (uint64_t)((ZG - 1) * rel3), ms, ml);
+            if (wave_any(b2 != 0)) {
+              const Rec r2 = *rp2;
+              const float4 p23 = pair[z2 * Z + z3];
+              const Acc A2 = acc_cross(A1, r2, it.lc.p2pf * p23.x, it.lc.p2pf * p23.y, p23.z,
+                                       single1, false);
+              int rel3 = a3 - a2 - 1;
+              if (rel3 < 0) rel3 += ZG;
+              float T, C;
+              acc_finish(A2, it.lc, T, C);
+              visit<MODE, OBJ, HASB>(a, T, C, b2 != 0, tau,
+                                     idx0 + (uint64_t)pl.inner * (uint64_t)((ZG - 1) * rel3), ms,
+                                     ml);
+            }
           }
           if (++g3 == G) { g3 = 0; ++z3; }
         }
