@@ -185,6 +185,15 @@ sailor_status sailor_topk(sailor_plan *plan, sailor_objective objective,
                           const sailor_constraint *constraint, int32_t k, sailor_result *out,
                           int32_t *n_found, void *hip_stream);
 
+/* Resize the device scratch of the selection: the list of candidates that survive the fp32
+ * scan (16 B each, default 4 Mi entries) and the list re-evaluated in fp64 (40 B each,
+ * default 256 Ki entries).  sailor_topk searches for a tighter threshold when the first
+ * list would overflow; a call fails with SAILOR_ENOMEM only when more candidates than fit
+ * lie within the rounding band of the k-th key (or, for sailor_best_plan, within the tie
+ * tolerance of the minimum).  Waits for the device.  SAILOR_EINVAL for a zero size. */
+sailor_status sailor_plan_set_scratch(sailor_plan *plan, uint32_t max_survivors,
+                                      uint32_t max_refined);
+
 /* Measurement only.  mode 0 (default): no events are recorded.  mode 1: the dominant kernel
  * of each call (the full-space scan of sailor_best_plan / sailor_topk, the evaluation kernel
  * of sailor_eval_batch) is launched with start and stop events on its stream.  mode 2: in

@@ -26,7 +26,7 @@ MAX_K = 4096
 
 EXPORTS = ["sailor_plan_create", "sailor_plan_destroy", "sailor_plan_set_avail",
            "sailor_plan_num_candidates", "sailor_plan_decode", "sailor_eval_batch",
-           "sailor_best_plan", "sailor_topk", "sailor_plan_set_timing",
+           "sailor_best_plan", "sailor_topk", "sailor_plan_set_scratch", "sailor_plan_set_timing",
            "sailor_plan_last_timing"]
 
 
@@ -122,6 +122,7 @@ def load_library() -> C.CDLL:
                                      C.POINTER(sailor_result), P]
     lib.sailor_topk.argtypes = [P, C.c_int, C.POINTER(sailor_constraint), C.c_int32,
                                 C.POINTER(sailor_result), C.POINTER(C.c_int32), P]
+    lib.sailor_plan_set_scratch.argtypes = [P, C.c_uint32, C.c_uint32]
     lib.sailor_plan_set_timing.argtypes = [P, C.c_int32]
     lib.sailor_plan_last_timing.argtypes = [P, C.POINTER(C.c_float), C.POINTER(C.c_float)]
     for name in EXPORTS:
@@ -262,6 +263,11 @@ class Plan:
         if rc != SAILOR_OK:
             raise SailorError(rc, "sailor_topk")
         return [_result(buf[i]) for i in range(n.value)]
+
+    def set_scratch(self, max_survivors: int, max_refined: int) -> None:
+        rc = self._lib.sailor_plan_set_scratch(self._h, max_survivors, max_refined)
+        if rc != SAILOR_OK:
+            raise SailorError(rc, "sailor_plan_set_scratch")
 
     def set_timing(self, mode: int) -> None:
         rc = self._lib.sailor_plan_set_timing(self._h, mode)

@@ -17,8 +17,8 @@ using namespace sailor;
 
 namespace {
 
-constexpr uint32_t kSurvCap = 1u << 22;  // 64 MiB of survivors
-constexpr uint32_t kRefCap = 1u << 18;
+constexpr uint32_t kDefaultSurvCap = 1u << 22;  // 64 MiB of survivors
+constexpr uint32_t kDefaultRefCap = 1u << 18;
 constexpr uint32_t kUnitTarget = 16384;  // candidates per scan workgroup
 constexpr uint32_t kEvalUnitTarget = 16384;  // candidates per workgroup of the range evaluation
 constexpr unsigned kEvalRowsThreads = 512;
@@ -51,6 +51,14 @@ struct DeviceArena {  // every device allocation of a plan, freed together
     *out = p;
     return n ? hipMemcpy(p, src, n * sizeof(T), hipMemcpyHostToDevice) : hipSuccess;
   }
+  void free_one(void *p) {
+    for (size_t i = 0; i < ptrs.size(); ++i)
+      if (ptrs[i] == p) {
+        (void)hipFree(p);
+        ptrs.erase(ptrs.begin() + (long)i);
+        return;
+      }
+  }
   void release() {
     for (void *p : ptrs) (void)hipFree(p);
     ptrs.clear();
@@ -78,6 +86,7 @@ struct sailor_plan {
   uint32_t *counters = nullptr;
   SurvRec *surv = nullptr;
   RefRec *ref = nullptr;
+  uint32_t surv_cap = kDefaultSurvCap, ref_cap = kDefaultRefCap;
   // host-mapped result area: header + SAILOR_MAX_K records
   void *h_result = nullptr;
   ResultHeader *d_hdr = nullptr;
@@ -399,10 +408,44 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
   sa.umin_l = pl->umin_l;
   sa.counters = cnt;
   sa.surv = pl->surv;
-  sa.surv_cap = kSurvCap;
+  sa.surv_cap = pl->surv_cap;
   const bool best = (k == 0);
   const uint32_t n_units = (uint32_t)pl->units.size();
   const bool t_scan = pl->timing_mode >= 1, t_all = pl->timing_mode >= 2;
+
+  // collect -> [k-th smallest survivor key] -> fp64 refine -> final selection -> sync
+  auto run_tail = [&](ResultHeader *hdr) -> sailor_status {
+    launch_units<MODE_COLLECT>(pl, obj, has_bound, sa, st, nullptr, nullptr);
+    RefineArgs ra{};
+    ra.surv = pl->surv;
+    ra.surv_cap = pl->surv_cap;
+    ra.counters = cnt;
+    ra.ref = pl->ref;
+    ra.ref_cap = pl->ref_cap;
+    ra.objective = (int)obj;
+    ra.has_bound = has_bound;
+    ra.bound = bound;
+    ra.band = 1.0f + 3.0f * kEvalEps;
+    if (!best) {
+      // the exact k-th smallest fp32 key among the survivors, then only its neighbourhood
+      k_select_kth<<<1, 1024, 0, st>>>(&pl->surv[0].key, (int)(sizeof(SurvRec) / 4),
+                                       cnt + CNT_SURV, pl->surv_cap, k, cnt + CNT_TAU1);
+      ra.tau_src = cnt + CNT_TAU1;
+    }
+    k_refine<<<256, kRefineWaves * 64, 0, st>>>(pl->dev, ra);
+    if (best) {
+      k_pick_best<<<1, 1024, 0, st>>>(pl->ref, pl->ref_cap, cnt, cnt_next, (int)obj, pl->d_hdr,
+                                      pl->d_out);
+    } else {
+      k_rank_topk<<<64, 256, 0, st>>>(pl->ref, pl->ref_cap, cnt, cnt_next, (int)obj, k, pl->d_hdr,
+                                      pl->d_out);
+    }
+    if (t_all) HIP_TRY(hipEventRecord(pl->ev[2], st));
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(st));
+    *hdr = *static_cast<ResultHeader *>(pl->h_result);
+    return SAILOR_OK;
+  };
 
   if (t_all) HIP_TRY(hipEventRecord(pl->ev[0], st));
   launch_units<MODE_SCAN>(pl, obj, has_bound, sa, st, t_scan ? pl->ev[3] : nullptr,
@@ -416,38 +459,55 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
     sa.tau_src = cnt + CNT_TAU0;
     sa.band = 1.0f + 3.0f * kEvalEps;
   }
-  launch_units<MODE_COLLECT>(pl, obj, has_bound, sa, st, nullptr, nullptr);
-  RefineArgs ra{};
-  ra.surv = pl->surv;
-  ra.surv_cap = kSurvCap;
-  ra.counters = cnt;
-  ra.ref = pl->ref;
-  ra.ref_cap = kRefCap;
-  ra.objective = (int)obj;
-  ra.has_bound = has_bound;
-  ra.bound = bound;
-  ra.band = 1.0f + 3.0f * kEvalEps;
-  if (!best) {
-    // the exact k-th smallest fp32 key among the survivors, then only its neighbourhood
-    k_select_kth<<<1, 1024, 0, st>>>(&pl->surv[0].key, (int)(sizeof(SurvRec) / 4), cnt + CNT_SURV,
-                                     kSurvCap, k, cnt + CNT_TAU1);
-    ra.tau_src = cnt + CNT_TAU1;
-  }
-  k_refine<<<256, kRefineWaves * 64, 0, st>>>(pl->dev, ra);
-  if (best) {
-    k_pick_best<<<1, 1024, 0, st>>>(pl->ref, kRefCap, cnt, cnt_next, (int)obj, pl->d_hdr,
-                                    pl->d_out);
-  } else {
-    k_rank_topk<<<64, 256, 0, st>>>(pl->ref, kRefCap, cnt, cnt_next, (int)obj, k, pl->d_hdr,
-                                    pl->d_out);
-  }
-  if (t_all) HIP_TRY(hipEventRecord(pl->ev[2], st));
-  HIP_TRY(hipGetLastError());
-  HIP_TRY(hipStreamSynchronize(st));
+  rc = run_tail(hdr_out);
+  if (rc != SAILOR_OK) return rc;
   pl->total_timed = t_all;
   pl->scan_timed = t_scan;
-  *hdr_out = *static_cast<ResultHeader *>(pl->h_result);
-  if (hdr_out->surv_count > kSurvCap || hdr_out->ref_count > kRefCap) return SAILOR_ENOMEM;
+  if (!best && hdr_out->surv_count > pl->surv_cap) {
+    // The unit minima gave too loose a bound (few units hold valid plans, or none of them
+    // strictly inside the constraint).  Search for a threshold that keeps at least k strict
+    // candidates and fits the survivor buffer, with count-only collect passes: first
+    // doubling up from the smallest key, then bisecting.
+    const float gmin = __builtin_bit_cast(float, hdr_out->gmin_bits);
+    if (!(gmin < kPosInf)) return SAILOR_ENOMEM;  // nothing strictly valid to anchor on
+    sa.use_tau_host = 1;
+    sa.count_only = 1;
+    auto count_at = [&](float tau, uint32_t *n_loose, uint32_t *n_strict) -> sailor_status {
+      k_zero_counters<<<1, 64, 0, st>>>(cnt, (1u << CNT_NLOOSE) | (1u << CNT_NSTRICT));
+      sa.tau_host = tau;
+      launch_units<MODE_COLLECT>(pl, obj, has_bound, sa, st, nullptr, nullptr);
+      uint32_t two[2];
+      HIP_TRY(hipMemcpyAsync(two, cnt + CNT_NLOOSE, sizeof two, hipMemcpyDeviceToHost, st));
+      HIP_TRY(hipStreamSynchronize(st));
+      *n_loose = two[0];
+      *n_strict = two[1];
+      return SAILOR_OK;
+    };
+    double lo = (double)gmin, hi = 0.0;  // strict count < k at lo (or unknown), too many at hi
+    float tau = 0.f;
+    bool found = false;
+    uint32_t nl = 0, ns = 0;
+    for (int it = 0; it < 200 && !found; ++it) {
+      double t;
+      if (hi == 0.0) t = (it == 0) ? lo * (1.0 + 1e-6) : lo * 2.0 + 1e-300;  // doubling
+      else t = std::sqrt(lo * hi);                                            // bisecting
+      if (!(t < 3.0e38)) break;
+      tau = (float)t;
+      rc = count_at(tau, &nl, &ns);
+      if (rc != SAILOR_OK) return rc;
+      if (nl > pl->surv_cap) hi = t;
+      else if (ns >= k) found = true;
+      else lo = t;
+      if (hi != 0.0 && hi <= lo * (1.0 + 1e-7)) break;  // a wall of ties: give up
+    }
+    if (!found) return SAILOR_ENOMEM;
+    k_zero_counters<<<1, 64, 0, st>>>(cnt, (1u << CNT_SURV) | (1u << CNT_REF) | (1u << CNT_FEAS));
+    sa.count_only = 0;
+    sa.tau_host = tau;
+    rc = run_tail(hdr_out);
+    if (rc != SAILOR_OK) return rc;
+  }
+  if (hdr_out->surv_count > pl->surv_cap || hdr_out->ref_count > pl->ref_cap) return SAILOR_ENOMEM;
   return SAILOR_OK;
 }
 
@@ -588,8 +648,8 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(ar.alloc(&pl->umin_s, pl->units.size()));
   CREATE_TRY(ar.alloc(&pl->umin_l, pl->units.size()));
   CREATE_TRY(ar.alloc(&pl->counters, (size_t)2 * CNT_COUNT));
-  CREATE_TRY(ar.alloc(&pl->surv, (size_t)kSurvCap));
-  CREATE_TRY(ar.alloc(&pl->ref, (size_t)kRefCap));
+  CREATE_TRY(ar.alloc(&pl->surv, (size_t)pl->surv_cap));
+  CREATE_TRY(ar.alloc(&pl->ref, (size_t)pl->ref_cap));
   const size_t res_bytes = sizeof(ResultHeader) + 8 + (size_t)SAILOR_MAX_K * sizeof(RefRec);
   CREATE_TRY(hipHostMalloc(&pl->h_result, res_bytes, hipHostMallocMapped));
   std::memset(pl->h_result, 0, res_bytes);
@@ -712,6 +772,27 @@ sailor_status sailor_topk(sailor_plan *pl, sailor_objective objective,
   const RefRec *rec = reinterpret_cast<const RefRec *>(static_cast<char *>(pl->h_result) +
                                                        sizeof(ResultHeader));
   for (uint32_t i = 0; i < hdr.n_found; ++i) to_result(pl, rec[i], &out[i]);
+  return SAILOR_OK;
+}
+
+sailor_status sailor_plan_set_scratch(sailor_plan *pl, uint32_t max_survivors,
+                                      uint32_t max_refined) {
+  if (!pl || max_survivors < 1 || max_refined < 1) return SAILOR_EINVAL;
+  HIP_TRY(hipSetDevice(pl->device));
+  HIP_TRY(hipDeviceSynchronize());
+  SurvRec *surv = nullptr;
+  RefRec *ref = nullptr;
+  if (pl->arena.alloc(&surv, (size_t)max_survivors) != hipSuccess) return SAILOR_ENOMEM;
+  if (pl->arena.alloc(&ref, (size_t)max_refined) != hipSuccess) {
+    pl->arena.free_one(surv);
+    return SAILOR_ENOMEM;
+  }
+  pl->arena.free_one(pl->surv);
+  pl->arena.free_one(pl->ref);
+  pl->surv = surv;
+  pl->ref = ref;
+  pl->surv_cap = max_survivors;
+  pl->ref_cap = max_refined;
   return SAILOR_OK;
 }
 

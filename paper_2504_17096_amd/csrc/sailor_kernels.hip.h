@@ -293,18 +293,28 @@ enum { MODE_SCAN = 0, MODE_COLLECT = 1 };
 struct ScanArgs {
   float *umin_s, *umin_l;   // [n_units] minima over strictly / loosely constrained candidates
   uint32_t *counters;       // see Counter
-  const uint32_t *tau_src;  // COLLECT: fp32 bits of the threshold, scaled by band
+  const uint32_t *tau_src;  // COLLECT: fp32 bits of the threshold, scaled by band ...
   float band;
+  float tau_host;           // ... or, when use_tau_host is set, this threshold
+  int use_tau_host;
+  int count_only;           // COLLECT: count the candidates under the threshold, keep none
   float lim_s, lim_l;       // constraint limits (strict, loose) on cost or on time
   SurvRec *surv;
   uint32_t surv_cap;
 };
 
 enum Counter { CNT_SURV = 0, CNT_REF = 1, CNT_FEAS = 2, CNT_GMIN = 3, CNT_TAU0 = 4, CNT_TAU1 = 5,
+               CNT_NLOOSE = 6, CNT_NSTRICT = 7,  // count-only collect passes
                CNT_COUNT = 8 };
 
 __device__ __forceinline__ uint32_t counter_reset_value(int i) {
-  return (i % CNT_COUNT >= CNT_GMIN) ? 0x7f800000u : 0u;  // thresholds start at +inf
+  const int c = i % CNT_COUNT;
+  return (c >= CNT_GMIN && c <= CNT_TAU1) ? 0x7f800000u : 0u;  // thresholds start at +inf
+}
+
+// zeroes the counters selected by mask (a fill kernel, usable under stream capture)
+__global__ void k_zero_counters(uint32_t *c, uint32_t mask) {
+  if (threadIdx.x < CNT_COUNT && ((mask >> threadIdx.x) & 1u)) c[threadIdx.x] = 0u;
 }
 
 __global__ void k_init_counters(uint32_t *c, int n) {
@@ -327,7 +337,15 @@ __device__ __forceinline__ void visit(const ScanArgs &a, float T, float C, bool 
     }
   } else {
     const bool loose = feas && (!HASB || con <= a.lim_l);
-    if (loose && key <= tau) {
+    if (a.count_only) {  // uniform
+      const bool strict = !HASB || con <= a.lim_s;
+      const uint64_t m_loose = __builtin_amdgcn_ballot_w64(loose && key <= tau);
+      const uint64_t m_strict = __builtin_amdgcn_ballot_w64(loose && strict && key <= tau);
+      if (m_loose != 0 && (threadIdx.x & 63) == 0) {
+        atomicAdd(&a.counters[CNT_NLOOSE], (uint32_t)__popcll(m_loose));
+        if (m_strict != 0) atomicAdd(&a.counters[CNT_NSTRICT], (uint32_t)__popcll(m_strict));
+      }
+    } else if (loose && key <= tau) {
       const bool strict = !HASB || con <= a.lim_s;
       const uint32_t slot = atomicAdd(&a.counters[CNT_SURV], 1u);
       if (slot < a.surv_cap) {
@@ -492,7 +510,7 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
   const UnitRec u = pl.units[blockIdx.x];
   float tau = kPosInf;
   if (MODE == MODE_COLLECT) {
-    tau = __uint_as_float(*a.tau_src) * a.band;
+    tau = a.use_tau_host ? a.tau_host : __uint_as_float(*a.tau_src) * a.band;
     const float um = a.umin_l[blockIdx.x];
     if (!(um < kPosInf && um <= tau)) return;  // uniform over the workgroup
   }
@@ -838,6 +856,7 @@ __global__ __launch_bounds__(1024) void k_pick_best(const RefRec *ref, uint32_t 
     hdr->surv_count = counters[CNT_SURV];
     hdr->ref_count = counters[CNT_REF];
     hdr->feasible_count = counters[CNT_FEAS];
+    hdr->gmin_bits = counters[CNT_GMIN];
   }
 }
 
@@ -861,6 +880,7 @@ __global__ __launch_bounds__(256) void k_rank_topk(const RefRec *ref, uint32_t r
     hdr->surv_count = counters[CNT_SURV];
     hdr->ref_count = counters[CNT_REF];
     hdr->feasible_count = f;
+    hdr->gmin_bits = counters[CNT_GMIN];
   }
   // uniform trip counts: every thread of a workgroup takes part in the tile barriers
   for (uint32_t base = blockIdx.x * blockDim.x; base < n; base += gridDim.x * blockDim.x) {
