@@ -146,7 +146,10 @@ sailor_status sailor_plan_destroy(sailor_plan *plan);
 
 /* Replace the availability table ([Z][G], host) -- the only input that changes between
  * re-plans when resources come and go (Sec. 4, Sec. 4.4).  Tables that do not depend on
- * availability are kept (cf. the reuse noted under H2, Sec. 4.2.1). */
+ * availability are kept (cf. the reuse noted under H2, Sec. 4.2.1).  The table is copied
+ * before the call returns; it reaches the device, and the quota table derived from it is
+ * rebuilt there, at the start of the next evaluation or selection call, on that call's
+ * stream. */
 sailor_status sailor_plan_set_avail(sailor_plan *plan, const int32_t *avail);
 
 /* Number of candidates N. */

@@ -19,7 +19,10 @@ namespace {
 
 constexpr uint32_t kDefaultSurvCap = 1u << 22;  // 64 MiB of survivors
 constexpr uint32_t kDefaultRefCap = 1u << 18;
-constexpr uint32_t kUnitTarget = 16384;  // candidates per scan workgroup
+// candidates per scan workgroup: large enough to amortise the staging of a unit, small
+// enough to leave about ten workgroups per compute unit
+constexpr uint64_t kUnitTargetMin = 4096, kUnitTargetMax = 65536, kUnitsWanted = 2560;
+constexpr uint32_t kCollectSub = 4;      // workgroups that share one unit in the collect pass
 constexpr uint32_t kEvalUnitTarget = 16384;  // candidates per workgroup of the range evaluation
 constexpr unsigned kEvalRowsThreads = 512;
 constexpr size_t kEvalRowsMaxLds = 64 * 1024;  // above this the range form evaluates lane by lane
@@ -81,6 +84,10 @@ struct sailor_plan {
   size_t lds_bytes = 0;
   unsigned unit_threads = 256;
   int32_t *d_avail = nullptr;
+  int32_t *h_avail = nullptr;      // pinned staging of the availability table
+  bool avail_dirty = false;        // h_avail is newer than the device copy
+  bool upload_pending = false;     // an asynchronous upload from h_avail was enqueued
+  hipEvent_t ev_upload = nullptr;
   // scratch of the selection pipeline
   float *umin_s = nullptr, *umin_l = nullptr;
   uint32_t *counters = nullptr;
@@ -251,12 +258,14 @@ sailor_status build_space(const sailor_problem *p, sailor_plan *pl, std::vector<
   pl->dev.n_row_stages = (int)row_stage;
 
   // scan units: (shape, tp, range of segment 2's pool)
+  const uint64_t unit_target =
+      std::min(kUnitTargetMax, std::max(kUnitTargetMin, pl->dev.N / kUnitsWanted));
   const uint64_t innerp = (uint64_t)p->n_mb * p->n_dp * ZG;
   for (uint32_t si = 0; si < pl->shapes.size(); ++si) {
     const ShapeRec &sh = pl->shapes[si];
     const int n_o = sh.s >= 2 ? ZG : 1;
     const uint64_t per_o = sh.s == 3 ? innerp * (uint64_t)(ZG - 1) : innerp;
-    int chunk = (int)std::min<uint64_t>((uint64_t)n_o, std::max<uint64_t>(1, kUnitTarget / per_o));
+    int chunk = (int)std::min<uint64_t>((uint64_t)n_o, std::max<uint64_t>(1, unit_target / per_o));
     const int n_chunks = (n_o + chunk - 1) / chunk;
     for (int t = 0; t < p->n_tp; ++t)
       for (int c = 0; c < n_chunks; ++c) {
@@ -364,6 +373,19 @@ const ShapeRec &shape_of(const sailor_plan *pl, uint64_t index) {
   return pl->shapes[blk->first_shape + (index - blk->off) / blk->shape_size];
 }
 
+// Brings a changed availability table to the device on the caller's stream and rebuilds
+// the quota table from it.
+sailor_status refresh_avail(sailor_plan *pl, hipStream_t st) {
+  if (!pl->avail_dirty) return SAILOR_OK;
+  HIP_TRY(hipMemcpyAsync(pl->d_avail, pl->h_avail, pl->dev.ZG * sizeof(int32_t),
+                         hipMemcpyHostToDevice, st));
+  k_quota_table<<<pl->dev.P_max + 1, 256, 0, st>>>(pl->dev);
+  HIP_TRY(hipEventRecord(pl->ev_upload, st));
+  pl->upload_pending = true;
+  pl->avail_dirty = false;
+  return SAILOR_OK;
+}
+
 // Plain launch, or a launch whose own start / stop timestamps are recorded in two events.
 template <typename K, typename... A>
 void launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, hipEvent_t e0,
@@ -375,7 +397,8 @@ void launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, hipEven
 template <int MODE>
 void launch_units(sailor_plan *pl, sailor_objective obj, int has_bound, const ScanArgs &a,
                   hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
-  const dim3 grid((unsigned)pl->units.size()), block(pl->unit_threads);
+  const dim3 grid((unsigned)pl->units.size() * (MODE == MODE_COLLECT ? kCollectSub : 1u)),
+      block(pl->unit_threads);
   const size_t lds = pl->lds_bytes;
   if (obj == SAILOR_MAX_THROUGHPUT) {
     if (has_bound) launch(k_units<MODE, 0, true>, grid, block, lds, st, e0, e1, pl->dev, a);
@@ -396,6 +419,8 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
   sailor_status rc = constraint_limits(obj, con, &has_bound, &bound, &sa.lim_s, &sa.lim_l);
   if (rc != SAILOR_OK) return rc;
   HIP_TRY(hipSetDevice(pl->device));
+  rc = refresh_avail(pl, st);
+  if (rc != SAILOR_OK) return rc;
   if (pl->counters_dirty) {
     k_init_counters<<<1, 64, 0, st>>>(pl->counters, 2 * CNT_COUNT);
     pl->counters_dirty = false;
@@ -409,6 +434,7 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
   sa.counters = cnt;
   sa.surv = pl->surv;
   sa.surv_cap = pl->surv_cap;
+  sa.n_sub = kCollectSub;
   const bool best = (k == 0);
   const uint32_t n_units = (uint32_t)pl->units.size();
   const bool t_scan = pl->timing_mode >= 1, t_all = pl->timing_mode >= 2;
@@ -535,6 +561,8 @@ sailor_status sailor_plan_destroy(sailor_plan *pl) {
   (void)hipSetDevice(pl->device);
   pl->arena.release();
   if (pl->h_result) (void)hipHostFree(pl->h_result);
+  if (pl->h_avail) (void)hipHostFree(pl->h_avail);
+  if (pl->ev_upload) (void)hipEventDestroy(pl->ev_upload);
   for (hipEvent_t e : pl->ev)
     if (e) (void)hipEventDestroy(e);
   delete pl;
@@ -603,6 +631,11 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(ar.alloc(&pl->d_avail, ZG));
   CREATE_TRY(hipMemcpy(pl->d_avail, p->avail, ZG * sizeof(int32_t), hipMemcpyHostToDevice));
   d.avail = pl->d_avail;
+  CREATE_TRY(hipHostMalloc(reinterpret_cast<void **>(&pl->h_avail), ZG * sizeof(int32_t), 0));
+  CREATE_TRY(hipEventCreateWithFlags(&pl->ev_upload, hipEventDisableTiming));
+  d.P_max = 0;
+  for (int ip = 0; ip < p->n_pp; ++ip) d.P_max = std::max(d.P_max, (int)p->pp_values[ip]);
+  CREATE_TRY(ar.alloc(&d.qtab, (size_t)(d.P_max + 1) * TP * ZG));
   CREATE_TRY(ar.upload(&d.cap, p->mem_capacity, G));
   CREATE_TRY(ar.upload(&d.res, p->mem_reserved, G));
   CREATE_TRY(ar.upload(&d.node, p->gpus_per_node, G));
@@ -660,6 +693,7 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   for (hipEvent_t &e : pl->ev) CREATE_TRY(hipEventCreate(&e));
 
   k_init_counters<<<1, 64>>>(pl->counters, 2 * CNT_COUNT);
+  k_quota_table<<<d.P_max + 1, 256>>>(d);
   k_small_tables<<<1, 256>>>(d);
   k_stage_tables<<<(unsigned)RS, 128>>>(d, sa);
   k_shape_agg<<<(unsigned)NS, 256>>>(d);
@@ -675,7 +709,12 @@ sailor_status sailor_plan_set_avail(sailor_plan *pl, const int32_t *avail) {
   for (int i = 0; i < pl->dev.ZG; ++i)
     if (avail[i] < 0) return SAILOR_EINVAL;
   HIP_TRY(hipSetDevice(pl->device));
-  HIP_TRY(hipMemcpy(pl->d_avail, avail, pl->dev.ZG * sizeof(int32_t), hipMemcpyHostToDevice));
+  if (pl->upload_pending) {  // the staging buffer may still be read by an earlier upload
+    HIP_TRY(hipEventSynchronize(pl->ev_upload));
+    pl->upload_pending = false;
+  }
+  std::memcpy(pl->h_avail, avail, pl->dev.ZG * sizeof(int32_t));
+  pl->avail_dirty = true;  // uploaded, with the quota table, by the next call on its stream
   return SAILOR_OK;
 }
 
@@ -704,6 +743,10 @@ sailor_status sailor_eval_batch(sailor_plan *pl, uint64_t first, uint64_t count,
   if (count == 0) return SAILOR_OK;
   HIP_TRY(hipSetDevice(pl->device));
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  {
+    const sailor_status rc = refresh_avail(pl, st);
+    if (rc != SAILOR_OK) return rc;
+  }
   EvalArgs a{};
   a.first = first; a.count = count; a.indices = d_indices;
   a.time = d_time; a.cost = d_cost; a.mem = d_mem; a.mask = d_mask;

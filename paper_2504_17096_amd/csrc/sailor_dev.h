@@ -73,7 +73,7 @@ struct ResultHeader {   // written by the final kernel into host-mapped memory
 
 struct DevPlan {
   int G, Z, ZG, MB, TP, DP;
-  int n_blocks, n_shapes, n_units, n_row_stages;
+  int n_blocks, n_shapes, n_units, n_row_stages, P_max;
   uint32_t inner;          // MB*TP*DP*ZG candidates per (shape, outer pool digits)
   uint32_t bpp, gb;
   // ceil(2^32 / d) for d = MB, G, MB*TP, MB*TP*DP, MB*ZG, MB*(ZG-1) (0 encodes d = 1)
@@ -90,6 +90,8 @@ struct DevPlan {
   const uint64_t *act;         // [MB][TP]
   const uint64_t *p2p;         // [MB]
   // derived small tables
+  uint32_t *qtab;              // [P_max + 1][TP][ZG] bit d: n stages x dpv[d] x tp GPUs fit the
+                               // pool; bit 31: tp exceeds the pool's node size (H1)
   float *ibw_f, *egs_f;        // [Z][Z] 1/bw ; egress both ways
   float *price_f;              // [G]
   float *p2p_f, *xb_f;         // [MB] p2p bytes ; (B/mb) * p2p bytes

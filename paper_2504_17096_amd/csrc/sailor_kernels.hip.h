@@ -288,6 +288,21 @@ __device__ __forceinline__ uint32_t quota_bits(const DevPlan &pl, int n, int tp,
   return bits;
 }
 
+constexpr uint32_t kH1Bit = 1u << 31;
+
+// Quota table, rebuilt whenever the availability changes: for n stages on one pool with
+// tensor-parallel degree tp, which data-parallel degrees fit (Sec. 4: resource quotas),
+// plus the H1 flag of the pool's GPU type.
+__global__ void k_quota_table(DevPlan pl) {
+  const int n = blockIdx.x;
+  for (int i = threadIdx.x; i < pl.TP * pl.ZG; i += blockDim.x) {
+    const int p = i % pl.ZG, k = i / pl.ZG;
+    uint32_t b = quota_bits(pl, n, pl.tpv[k], pl.avail[p]);
+    if (pl.tpv[k] > pl.node[p % pl.G]) b |= kH1Bit;
+    pl.qtab[(size_t)n * pl.TP * pl.ZG + i] = b;
+  }
+}
+
 enum { MODE_SCAN = 0, MODE_COLLECT = 1 };
 
 struct ScanArgs {
@@ -298,6 +313,7 @@ struct ScanArgs {
   float tau_host;           // ... or, when use_tau_host is set, this threshold
   int use_tau_host;
   int count_only;           // COLLECT: count the candidates under the threshold, keep none
+  uint32_t n_sub;           // COLLECT: workgroups that share one unit
   float lim_s, lim_l;       // constraint limits (strict, loose) on cost or on time
   SurvRec *surv;
   uint32_t surv_cap;
@@ -409,9 +425,14 @@ __device__ __forceinline__ bool wave_any(bool p) { return __builtin_amdgcn_ballo
 template <int S, int MODE, int OBJ, bool HASB>
 __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, const UnitRec &u,
                                           const ShapeRec &sh, const Rec *rec, const float4 *pair,
-                                          const uint32_t *q13, float tau, float &ms, float &ml) {
+                                          const uint32_t *q13, float tau, int sub, int n_sub,
+                                          float &ms, float &ml) {
+  // the chunks of the lane space are dealt round-robin to the waves of the n_sub
+  // workgroups that share the unit
   const int ZG = pl.ZG, G = pl.G, MB = pl.MB, DP = pl.DP, Z = pl.Z;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwave = blockDim.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = (int)(threadIdx.x >> 6) + (int)(blockDim.x >> 6) * sub;
+  const int nwave = (int)(blockDim.x >> 6) * n_sub;
   const bool single0 = sh.n[0] == 1, single1 = sh.n[1] == 1;
   const int tp = u.tp;
   if (S <= 2) {
@@ -507,11 +528,15 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
 template <int MODE, int OBJ, bool HASB>
 __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs a) {
   extern __shared__ uint4 lds_raw[];
-  const UnitRec u = pl.units[blockIdx.x];
+  // SCAN: one workgroup per unit.  COLLECT: n_sub workgroups share a unit.
+  const uint32_t n_sub = MODE == MODE_COLLECT ? a.n_sub : 1u;
+  const uint32_t uidx = MODE == MODE_COLLECT ? blockIdx.x / n_sub : blockIdx.x;
+  const int sub = MODE == MODE_COLLECT ? (int)(blockIdx.x % n_sub) : 0;
+  const UnitRec u = pl.units[uidx];
   float tau = kPosInf;
   if (MODE == MODE_COLLECT) {
     tau = a.use_tau_host ? a.tau_host : __uint_as_float(*a.tau_src) * a.band;
-    const float um = a.umin_l[blockIdx.x];
+    const float um = a.umin_l[uidx];
     if (!(um < kPosInf && um <= tau)) return;  // uniform over the workgroup
   }
   const ShapeRec sh = pl.shapes[u.shape];
@@ -522,38 +547,56 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
   uint32_t *q13 = qm + 3 * ZG;                                      // [ZG]
   __shared__ float red[2][kMaxUnitThreads / 64];
   const int t = threadIdx.x;
-  const int tpv = pl.tpv[u.tp];
 
+  const int n0 = sh.n[0], n1 = sh.n[1], n2 = sh.n[2];
+  const uint32_t *qt = pl.qtab + (size_t)u.tp * ZG;  // + n * TP * ZG + pool
+  const size_t qstride = (size_t)pl.TP * ZG;
+  __shared__ uint32_t s_any;  // bit j: some pool can host segment j
+  if (t == 0) s_any = 0;
+  __syncthreads();
+  uint32_t any_here = 0;
   for (int i = t; i < S * ZG; i += blockDim.x) {
-    const int seg = i / ZG, p = i % ZG, g = p % G;
-    uint32_t b = quota_bits(pl, seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]), tpv, pl.avail[p]);
-    if (tpv > pl.node[g]) b = 0;  // H1: tensor parallelism stays inside a node
+    const int seg = i >= 2 * ZG ? 2 : (i >= ZG ? 1 : 0), p = i - seg * ZG;
+    const int n = seg == 0 ? n0 : (seg == 1 ? n1 : n2);
+    uint32_t b = qt[n * qstride + p];
+    if (b & kH1Bit) b = 0;  // H1: tensor parallelism stays inside a node
     qm[i] = b;
+    // a segment nobody can host rules the whole unit out
+    const bool counts = seg != 1 || (p >= (int)u.o_lo && p < (int)(u.o_lo + u.o_cnt));
+    if (b != 0 && counts) any_here |= 1u << seg;
   }
   if (S == 3)
-    for (int p = t; p < ZG; p += blockDim.x)
-      q13[p] = quota_bits(pl, sh.n[0] + sh.n[2], tpv, pl.avail[p]);
+    for (int p = t; p < ZG; p += blockDim.x) q13[p] = qt[(n0 + n2) * qstride + p];
   for (int i = t; i < Z * Z; i += blockDim.x) {
     const int za = i / Z, zb = i % Z;
     pair[i] = make_float4(pl.ibw_f[za * Z + zb], pl.ibw_f[zb * Z + za], pl.egs_f[i], 0.f);
   }
-  __syncthreads();
+  if (any_here) atomicOr(&s_any, any_here);
+  __syncthreads();  // (also orders the tables above before the records below)
+  if (s_any != (1u << S) - 1u) {
+    if (MODE == MODE_SCAN && t == 0) {
+      a.umin_s[uidx] = kPosInf;
+      a.umin_l[uidx] = kPosInf;
+    }
+    return;
+  }
   for (int i = t; i < S * ZG * MB; i += blockDim.x) {
-    const int mb = i % MB, p = (i / MB) % ZG, seg = i / (MB * ZG);
-    const int g = p % G, z = p / G;
-    const size_t sl = agg_slot(pl, u.shape, u.tp, seg);
-    const float4 ta = pl.ta[(sl * G + g) * MB + mb];
-    const uint32_t bits = pl.memok[(sl * G + g) * MB + mb] & qm[seg * ZG + p] & pl.divis[mb];
-    rec[(seg * ZG + p) * MB + mb] = make_rec(ta, pl.smax[sl], pl.upd[sl * G + g], pl.price_f[g],
-                                             pl.p2p_f[mb], pl.ibw_f[z * Z + z],
-                                             seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]), bits);
+    const uint32_t sp = fast_div((uint32_t)i, pl.mg_mb), mb = (uint32_t)i - sp * (uint32_t)MB;
+    const int seg = sp >= 2u * ZG ? 2 : (sp >= (uint32_t)ZG ? 1 : 0), p = (int)sp - seg * ZG;
+    const int z = (int)fast_div((uint32_t)p, pl.mg_g), g = p - z * G;
+    const uint32_t sl = (u.shape * (uint32_t)pl.TP + u.tp) * 3u + (uint32_t)seg;
+    const uint32_t gi = (sl * (uint32_t)G + (uint32_t)g) * (uint32_t)MB + mb;
+    const float4 ta = pl.ta[gi];
+    const uint32_t bits = pl.memok[gi] & qm[seg * ZG + p] & pl.divis[mb];
+    rec[i] = make_rec(ta, pl.smax[sl], pl.upd[sl * G + g], pl.price_f[g], pl.p2p_f[mb],
+                      pl.ibw_f[z * Z + z], seg == 0 ? n0 : (seg == 1 ? n1 : n2), bits);
   }
   __syncthreads();
 
   float ms = kPosInf, ml = kPosInf;
-  if (S == 1) unit_body<1, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, tau, ms, ml);
-  else if (S == 2) unit_body<2, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, tau, ms, ml);
-  else unit_body<3, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, tau, ms, ml);
+  if (S == 1) unit_body<1, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, tau, sub, (int)n_sub, ms, ml);
+  else if (S == 2) unit_body<2, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, tau, sub, (int)n_sub, ms, ml);
+  else unit_body<3, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, tau, sub, (int)n_sub, ms, ml);
 
   if (MODE == MODE_SCAN) {
     if (!HASB) ml = ms;
@@ -566,10 +609,13 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
         ms = fminf(ms, red[0][w]);
         ml = fminf(ml, red[1][w]);
       }
-      a.umin_s[blockIdx.x] = ms;
-      a.umin_l[blockIdx.x] = ml;
+      a.umin_s[uidx] = ms;
+      a.umin_l[uidx] = ml;
       // keys are non-negative, so their bit patterns order like unsigned integers
-      if (ms < kPosInf) atomicMin(&a.counters[CNT_GMIN], __float_as_uint(ms));
+      // (a stale read only costs a redundant atomic; most units lose and skip theirs)
+      const uint32_t seen = __hip_atomic_load(&a.counters[CNT_GMIN], __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
+      if (__float_as_uint(ms) < seen) atomicMin(&a.counters[CNT_GMIN], __float_as_uint(ms));
     }
   }
 }
@@ -1115,12 +1161,12 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
   const int t = threadIdx.x;
   for (int i = t; i < S * TP * ZG; i += blockDim.x) {
     const int p = i % ZG, k = (i / ZG) % TP, seg = i / (ZG * TP);
-    qm[i] = quota_bits(pl, seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]), pl.tpv[k],
-                       pl.avail[p]);
+    const int n = seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]);
+    qm[i] = pl.qtab[((size_t)n * TP + k) * ZG + p];
   }
   if (S == 3)
     for (int i = t; i < TP * ZG; i += blockDim.x)
-      q13[i] = quota_bits(pl, sh.n[0] + sh.n[2], pl.tpv[i / ZG], pl.avail[i % ZG]);
+      q13[i] = pl.qtab[(size_t)(sh.n[0] + sh.n[2]) * TP * ZG + i];
   for (int p = t; p < ZG; p += blockDim.x) {
     const int g = p % G;
     PoolInfo pi;
