@@ -285,3 +285,49 @@ def test_small_scratch_makes_topk_search_for_a_tighter_threshold(torch_cuda):
         check_topk(plan.topk(64, stream=stream), orc.topk(64), MAX_THROUGHPUT)
     finally:
         plan.destroy()
+
+
+@pytest.mark.parametrize("seed", range(100, 124))
+def test_random_small_problems(torch_cuda, seed):
+    # shapes drawn at random: odd pool counts, deep pipelines on few layers, batches that
+    # some (D, mb) pairs do not divide, empty pools
+    rng = np.random.default_rng(seed)
+    n_layers = int(rng.choice([3, 4, 5, 6, 8, 9, 12]))
+    prob = W.tiny_problem(seed, n_layers=n_layers, n_types=int(rng.integers(1, 4)),
+                          n_zones=int(rng.integers(1, 4)), max_segments=int(rng.integers(1, 4)),
+                          seg3_max_pp=int(rng.choice([3, 4, 6, 12])),
+                          uniform_layers=bool(rng.integers(0, 2)),
+                          partitions_per_pp=int(rng.integers(1, 4)),
+                          with_egress=bool(rng.integers(0, 2)))
+    prob.global_batch = int(rng.choice([8, 12, 16, 24]))
+    avail = prob.avail.copy()
+    avail[rng.random(avail.shape) < 0.25] = 0
+    prob = prob.with_avail(avail)
+    plan, orc = _plan(prob), Oracle(prob)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        n = orc.num_candidates
+        assert plan.num_candidates() == n
+        want = orc.eval_batch(n_threads=THREADS)
+        assert_eval_parity(gpu_eval(torch_cuda, plan, 0, n), want)
+        idx = rng.integers(0, n, 500).astype(np.uint64)
+        assert_eval_parity(gpu_eval(torch_cuda, plan, 0, len(idx), indices=idx),
+                           orc.eval_batch(indices=idx))
+        for objective in (MAX_THROUGHPUT, MIN_COST):
+            ok = want[3] == 0
+            bounds = [None]
+            if ok.any():
+                val = want[1] if objective == MAX_THROUGHPUT else 1.0 / want[0]
+                bounds.append(float(np.quantile(val[ok], 0.3)))
+            for bound in bounds:
+                w_best = orc.best(objective=objective, bound=bound, n_threads=THREADS)
+                g_best = plan.best_plan(objective=objective, bound=bound, stream=stream)
+                if w_best is None:
+                    assert g_best is None
+                else:
+                    check_result(g_best, w_best, orc)
+                check_topk(plan.topk(17, objective=objective, bound=bound, stream=stream),
+                           orc.topk(17, objective=objective, bound=bound, n_threads=THREADS),
+                           objective)
+    finally:
+        plan.destroy()
