@@ -27,6 +27,10 @@ if ROOT not in sys.path:
 # the epilogue, with P the mean pipeline depth over the candidate space
 FLOPS_PER_STAGE, FLOPS_EPILOGUE = 12.0, 15.0
 PEAK_FP32_VECTOR_TFLOPS = 157.3
+# HBM bytes per scan launch on this workload from rocprofv3 FETCH_SIZE / WRITE_SIZE, each
+# scaled by a 1 GiB copy of the same run (profiles/k_units_scan_cfg4_counters.md); set to
+# None whenever k_units changes after the counters were taken
+SCAN_TRAFFIC_BYTES = 7.52e6
 
 
 def mean_pipeline_depth(prob) -> float:
@@ -71,7 +75,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--cpu-sample", type=int, default=16_000_000)
+    ap.add_argument("--cpu-sample", type=int, default=48_000_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE)")
@@ -194,7 +198,7 @@ def main() -> int:
                    "top_k": K, "mean_pipeline_depth": pbar},
         "roofline": {"bound": "alu", "kernel": "k_units<SCAN>", "achieved": achieved,
                      "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_FP32_VECTOR_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_FP32_VECTOR_TFLOPS, "traffic": SCAN_TRAFFIC_BYTES,
                      "flops_per_candidate": flops_per_cand, "kernel_ms": scan_ms},
         "extra": {"time_to_top64_ms": ms_per_step, "time_to_best_plan_ms": best_ms,
                   "device_ms_per_step": tot_ms, "scan_kernel_ms": scan_ms,
