@@ -1,12 +1,14 @@
 // HIP kernels of the batched plan evaluator (gfx950, wave64).
 //
-// Set-up kernels (once per plan): k_small_tables, k_stage_tables, k_shape_agg.
-// Hot path:  k_units<SCAN>    full-space fp32 evaluation + per-unit minima
+// Set-up kernels (once per plan): k_small_tables, k_stage_tables, k_shape_agg;
+//            k_quota_table    again whenever the availability changes.
+// Hot path:  k_units<SCAN>    full-space fp32 evaluation + per-unit minima, early pruning
 //            k_select_kth     radix select of the k-th smallest fp32 key
 //            k_units<COLLECT> re-evaluates the few units that can hold a winner
 //            k_refine         fp64 / exact-integer stage-by-stage re-evaluation
 //            k_pick_best / k_rank_topk   final selection
-//            k_eval_direct    per-candidate outputs for sailor_eval_batch
+//            k_eval_rows / k_eval_direct   per-candidate outputs for sailor_eval_batch
+//                             (index ranges / index lists)
 //
 // The simulator arithmetic follows Sailor, Sec. 4.3 (memory, iteration time, cost);
 // T_pp = sum of stage times + (N_b - 1) * straggler is the 1F1B composition of
@@ -381,7 +383,7 @@ __device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t m) {
 }
 
 struct LaneItem {  // what a lane owns for one chunk of the lane space
-  int mb, dp, a1, z1;
+  int mb, dp, a1;
   bool active;
   LaneC lc;
   uint32_t dpbit;
@@ -406,7 +408,6 @@ __device__ __forceinline__ LaneItem lane_item(const DevPlan &pl, int e, int n_it
   it.lc.dtp = pl.dtp_f[tp * pl.DP + it.dp];
   it.lc.xb = pl.xb_f[it.mb];
   it.dpbit = it.active ? (1u << it.dp) : 0u;
-  it.z1 = 0;
   return it;
 }
 
