@@ -39,6 +39,7 @@ class _Problem(C.Structure):
         ("n_layers", C.c_int32), ("n_types", C.c_int32), ("n_zones", C.c_int32),
         ("n_mb", C.c_int32), ("n_tp", C.c_int32), ("n_dp", C.c_int32), ("n_pp", C.c_int32),
         ("max_segments", C.c_int32), ("seg3_max_pp", C.c_int32), ("uniform_layers", C.c_int32),
+        ("per_segment_tp", C.c_int32),
         ("global_batch", C.c_int64),
         ("mb_values", C.c_void_p), ("tp_values", C.c_void_p), ("dp_values", C.c_void_p),
         ("pp_values", C.c_void_p), ("n_partitions", C.c_void_p), ("partition_layers", C.c_void_p),
@@ -57,7 +58,8 @@ class _Config(C.Structure):
     _fields_ = [("pp", C.c_int32), ("pp_idx", C.c_int32), ("n_segments", C.c_int32),
                 ("partition", C.c_int32), ("cut", C.c_int32 * 2), ("pool", C.c_int32 * 3),
                 ("dp", C.c_int32), ("tp", C.c_int32), ("mb", C.c_int32),
-                ("dp_idx", C.c_int32), ("tp_idx", C.c_int32), ("mb_idx", C.c_int32)]
+                ("dp_idx", C.c_int32), ("tp_idx", C.c_int32), ("mb_idx", C.c_int32),
+                ("seg_tp", C.c_int32 * 3), ("seg_tp_idx", C.c_int32 * 3)]
 
 
 class _Eval(C.Structure):
@@ -79,6 +81,8 @@ class Config:
     dp_idx: int
     tp_idx: int
     mb_idx: int
+    seg_tp: tuple = (0, 0, 0)
+    seg_tp_idx: tuple = (-1, -1, -1)
 
 
 @dataclass
@@ -121,7 +125,7 @@ def _load():
 
 def _cfg(c: _Config) -> Config:
     return Config(c.pp, c.pp_idx, c.n_segments, c.partition, tuple(c.cut), tuple(c.pool),
-                  c.dp, c.tp, c.mb, c.dp_idx, c.tp_idx, c.mb_idx)
+                  c.dp, c.tp, c.mb, c.dp_idx, c.tp_idx, c.mb_idx, tuple(c.seg_tp), tuple(c.seg_tp_idx))
 
 
 def _ev(e: _Eval) -> Eval:
@@ -146,6 +150,7 @@ class Oracle:
                                           len(prob.dp_values), len(prob.pp_values))
         s.max_segments, s.seg3_max_pp = prob.max_segments, prob.seg3_max_pp
         s.uniform_layers = 1 if prob.uniform_layers else 0
+        s.per_segment_tp = 1 if getattr(prob, "per_segment_tp", False) else 0
         s.global_batch = prob.global_batch
         s.mb_values = arr(prob.mb_values, np.int32)
         s.tp_values = arr(prob.tp_values, np.int32)
@@ -204,6 +209,8 @@ class Oracle:
         c.pool[0], c.pool[1], c.pool[2] = cfg.pool
         c.dp, c.tp, c.mb = cfg.dp, cfg.tp, cfg.mb
         c.dp_idx, c.tp_idx, c.mb_idx = cfg.dp_idx, cfg.tp_idx, cfg.mb_idx
+        for j in range(3):
+            c.seg_tp[j], c.seg_tp_idx[j] = cfg.seg_tp[j], cfg.seg_tp_idx[j]
         out = C.c_uint64()
         if self._lib.so_encode(self._ctx, C.byref(c), C.byref(out)) != 0:
             raise ValueError("invalid config")

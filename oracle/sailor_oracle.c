@@ -62,7 +62,10 @@ so_ctx *so_create(const so_problem *p) {
       uint64_t size = 0;
       if (segments_allowed(p, P, s)) {
         size = c->inner * n_cuts(P, s) * (uint64_t)p->n_partitions[ip];
-        for (int j = 1; j < s; ++j) size *= (uint64_t)(c->ZG - 1);
+        for (int j = 1; j < s; ++j) {
+          size *= (uint64_t)(c->ZG - 1);
+          if (p->per_segment_tp) size *= (uint64_t)p->n_tp; /* the segment's own TP digit */
+        }
       }
       c->block_off[ip * 3 + (s - 1)] = off;
       c->block_size[ip * 3 + (s - 1)] = size;
@@ -87,11 +90,18 @@ static void fill_values(const so_ctx *c, so_config *g) {
   g->pp = c->p.pp_values[g->pp_idx];
   g->dp = c->p.dp_values[g->dp_idx];
   g->tp = c->p.tp_values[g->tp_idx];
+  for (int j = 0; j < 3; ++j) {
+    if (j >= g->n_segments) { g->seg_tp_idx[j] = -1; g->seg_tp[j] = 0; continue; }
+    if (!c->p.per_segment_tp || j == 0) g->seg_tp_idx[j] = g->tp_idx;
+    g->seg_tp[j] = c->p.tp_values[g->seg_tp_idx[j]];
+  }
   g->mb = c->p.mb_values[g->mb_idx];
 }
 
 /* index -> plan.  Digits, least significant first: mb, tp, dp, pool of segment 1,
- * [relative pool of segment 2], [relative pool of segment 3], [cut], partition. */
+ * [relative pool of segment 2], [relative pool of segment 3], [cut], partition.
+ * With per-segment TP, "tp" is segment 1's and each later segment's own TP digit
+ * follows that segment's relative pool. */
 int so_decode(const so_ctx *c, uint64_t index, so_config *out) {
   const so_problem *p = &c->p;
   if (index >= c->n_candidates) return -1;
@@ -118,10 +128,12 @@ int so_decode(const so_ctx *c, uint64_t index, so_config *out) {
   if (s >= 2) {
     int rel = (int)(r % (c->ZG - 1)); r /= (c->ZG - 1);
     g.pool[1] = (g.pool[0] + 1 + rel) % c->ZG;
+    if (p->per_segment_tp) { g.seg_tp_idx[1] = (int32_t)(r % p->n_tp); r /= p->n_tp; }
   }
   if (s == 3) {
     int rel = (int)(r % (c->ZG - 1)); r /= (c->ZG - 1);
     g.pool[2] = (g.pool[1] + 1 + rel) % c->ZG;
+    if (p->per_segment_tp) { g.seg_tp_idx[2] = (int32_t)(r % p->n_tp); r /= p->n_tp; }
   }
   if (s == 2) {
     g.cut[0] = (int32_t)(r % (P - 1)) + 1; r /= (P - 1);
@@ -162,10 +174,12 @@ int so_encode(const so_ctx *c, const so_config *g, uint64_t *out) {
   }
   if (s == 3) {
     int rel = ((g->pool[2] - g->pool[1] - 1) % c->ZG + c->ZG) % c->ZG;
+    if (p->per_segment_tp) r = r * p->n_tp + (uint64_t)g->seg_tp_idx[2];
     r = r * (c->ZG - 1) + (uint64_t)rel;
   }
   if (s >= 2) {
     int rel = ((g->pool[1] - g->pool[0] - 1) % c->ZG + c->ZG) % c->ZG;
+    if (p->per_segment_tp) r = r * p->n_tp + (uint64_t)g->seg_tp_idx[1];
     r = r * (c->ZG - 1) + (uint64_t)rel;
   }
   r = r * c->ZG + (uint64_t)g->pool[0];
@@ -189,7 +203,9 @@ uint64_t so_enumerate(const so_ctx *c, so_config *out, uint64_t max_out) {
       for (int q = 0; q < p->n_partitions[ip]; ++q)
         for (int k1 = (s >= 2 ? 1 : P); k1 <= (s >= 2 ? P - (s - 1) : P); ++k1)
           for (int k2 = (s == 3 ? k1 + 1 : P); k2 <= (s == 3 ? P - 1 : P); ++k2)
+            for (int t3 = 0; t3 < (s == 3 && p->per_segment_tp ? p->n_tp : 1); ++t3)
             for (int r3 = 0; r3 < (s == 3 ? ZG - 1 : 1); ++r3)
+              for (int t2 = 0; t2 < (s >= 2 && p->per_segment_tp ? p->n_tp : 1); ++t2)
               for (int r2 = 0; r2 < (s >= 2 ? ZG - 1 : 1); ++r2)
                 for (int a1 = 0; a1 < ZG; ++a1)
                   for (int id = 0; id < p->n_dp; ++id)
@@ -204,6 +220,7 @@ uint64_t so_enumerate(const so_ctx *c, so_config *out, uint64_t max_out) {
                           g.pool[1] = s >= 2 ? (a1 + 1 + r2) % ZG : -1;
                           g.pool[2] = s == 3 ? (g.pool[1] + 1 + r3) % ZG : -1;
                           g.dp_idx = id; g.tp_idx = it; g.mb_idx = im;
+                          g.seg_tp_idx[1] = t2; g.seg_tp_idx[2] = t3;
                           fill_values(c, &g);
                           out[n] = g;
                         }
@@ -244,7 +261,7 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
                         int has_bound, double bound, so_eval *out) {
   const so_problem *p = &c->p;
   const int P = g->pp, G = p->n_types, Z = p->n_zones;
-  const int64_t D = g->dp, tp = g->tp, mb = g->mb;
+  const int64_t D = g->dp, mb = g->mb;
   const int32_t *nl = partition_row(c, g);
   out->index = index;
   out->mask = 0;
@@ -260,26 +277,29 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
   const int64_t Nb = p->global_batch / (D * mb);
 
   int type_of[SO_MAX_STAGES], zone_of[SO_MAX_STAGES], first_layer[SO_MAX_STAGES];
-  int stages_on_pool[SO_MAX_POOLS];
-  memset(stages_on_pool, 0, sizeof stages_on_pool);
+  int tp_of[SO_MAX_STAGES], tpi_of[SO_MAX_STAGES]; /* TP degree of the stage and its list index */
+  int64_t gpus_per_replica_on_pool[SO_MAX_POOLS];
+  memset(gpus_per_replica_on_pool, 0, sizeof gpus_per_replica_on_pool);
   int layer = 0;
   for (int i = 0; i < P; ++i) {
     int seg = (i < g->cut[0]) ? 0 : (i < g->cut[1]) ? 1 : 2;
     int pool = g->pool[seg];
     type_of[i] = pool % G;
     zone_of[i] = pool / G;
-    stages_on_pool[pool] += 1;
+    tp_of[i] = g->seg_tp[seg];
+    tpi_of[i] = g->seg_tp_idx[seg];
+    gpus_per_replica_on_pool[pool] += tp_of[i];
     first_layer[i] = layer;
     layer += nl[i];
   }
 
   /* H1: a tensor-parallel group stays inside one node (Sec. 4.2.1) */
   for (int i = 0; i < P; ++i)
-    if (tp > p->gpus_per_node[type_of[i]]) out->mask |= SO_BIT_TP_NODE;
+    if (tp_of[i] > p->gpus_per_node[type_of[i]]) out->mask |= SO_BIT_TP_NODE;
 
   /* quota: D replicas of every stage, tp GPUs each, from the stage's (zone, type) pool */
   for (int a = 0; a < Z * G; ++a)
-    if ((int64_t)stages_on_pool[a] * D * tp > (int64_t)p->avail[a]) out->mask |= SO_BIT_QUOTA;
+    if (gpus_per_replica_on_pool[a] * D > (int64_t)p->avail[a]) out->mask |= SO_BIT_QUOTA;
 
   /* memory per worker of each stage: M_model + M_activation (+ reserved), Sec. 4.3 */
   uint64_t params_of[SO_MAX_STAGES];
@@ -289,12 +309,12 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
     for (int l = first_layer[i]; l < first_layer[i] + nl[i]; ++l) params += p->layer_params[l];
     if (i == 0) params += p->embed_params;
     if (i == P - 1) params += p->head_params;
-    uint64_t shard = (params + (uint64_t)tp - 1) / (uint64_t)tp;
+    uint64_t shard = (params + (uint64_t)tp_of[i] - 1) / (uint64_t)tp_of[i];
     params_of[i] = shard;
     uint64_t m_model = shard * (uint64_t)p->bytes_per_param;
     int64_t inflight = (P - i) < Nb ? (P - i) : Nb; /* 1F1B: microbatches kept alive */
     uint64_t m_act = (uint64_t)inflight * (uint64_t)nl[i] *
-                     p->act_store_bytes[(size_t)g->mb_idx * p->n_tp + g->tp_idx];
+                     p->act_store_bytes[(size_t)g->mb_idx * p->n_tp + tpi_of[i]];
     uint64_t m = m_model + m_act + p->mem_reserved[type_of[i]];
     if (m > p->mem_capacity[type_of[i]]) out->mask |= SO_BIT_OOM;
     if (m > peak) peak = m;
@@ -306,8 +326,8 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
   double sum_t = 0.0, max_t = 0.0, t_sync = 0.0, t_upd = 0.0;
   for (int i = 0; i < P; ++i) {
     int gt = type_of[i], z = zone_of[i];
-    double f = layer_time_sum(p, p->t_fwd, gt, g->mb_idx, g->tp_idx, first_layer[i], nl[i]);
-    double b = layer_time_sum(p, p->t_bwd, gt, g->mb_idx, g->tp_idx, first_layer[i], nl[i]);
+    double f = layer_time_sum(p, p->t_fwd, gt, g->mb_idx, tpi_of[i], first_layer[i], nl[i]);
+    double b = layer_time_sum(p, p->t_bwd, gt, g->mb_idx, tpi_of[i], first_layer[i], nl[i]);
     double x = 0.0;
     if (i < P - 1) x += p2p / p->bandwidth[(size_t)z * Z + zone_of[i + 1]];
     if (i > 0) x += p2p / p->bandwidth[(size_t)z * Z + zone_of[i - 1]];
@@ -321,7 +341,7 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
              ((double)params_of[i] * (double)p->grad_bytes_per_param) /
              p->bandwidth[(size_t)z * Z + z];
     if (sync > t_sync) t_sync = sync;
-    double u = upd_time_sum(p, gt, g->tp_idx, first_layer[i], nl[i]);
+    double u = upd_time_sum(p, gt, tpi_of[i], first_layer[i], nl[i]);
     if (u > t_upd) t_upd = u;
   }
   /* 1F1B: warm-up + cool-down pass every stage once, the steady phase repeats the
@@ -333,7 +353,7 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
   /* cost per iteration: rented GPUs for T_iter plus cross-zone traffic */
   double gpu_dollars_per_hour = 0.0, c_comm = 0.0;
   for (int i = 0; i < P; ++i)
-    gpu_dollars_per_hour += (double)(D * tp) * p->price_per_hour[type_of[i]];
+    gpu_dollars_per_hour += (double)(D * tp_of[i]) * p->price_per_hour[type_of[i]];
   if (p->egress_per_byte)
     for (int i = 0; i + 1 < P; ++i) {
       int z = zone_of[i], zn = zone_of[i + 1];

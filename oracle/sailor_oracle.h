@@ -16,9 +16,17 @@
  * It shares no code with the HIP library and is never called by it.  Only the tests,
  * the smoke check and the benchmark's CPU-baseline leg may use it.
  *
+ * Optional per-segment tensor parallelism (per_segment_tp = 1): every stage of the plan
+ * tuple may carry its own TP degree (Sec. 4.2); with H1 a TP group is made of one GPU
+ * type, so each contiguous segment (one pool) gets its own TP digit.  Memory shards,
+ * activation bytes, profiled times, the node-size check, the gradient all-reduce, the
+ * GPU count against the quota and the rent all use the degree of the stage's segment.
+ *
  * Parity pins (tests/test_oracle_*.py): homogeneous 1F1B closed form, discrete-event
  * 1F1B schedule, ring all-reduce limits, big-integer memory bytes, cost identities,
- * feasibility monotonicity, brute-force selection, enumeration bijection.
+ * feasibility monotonicity, brute-force selection, enumeration bijection; per-segment
+ * TP: agreement with the shared-TP mode on equal degrees, hand-computed time / sync /
+ * cost on mixed degrees, Python-integer memory and quota, count formula.
  * Against numeric outputs of the paper's own simulator: parity unpinned (the paper
  * prints no worked input -> output example).
  *
@@ -36,6 +44,7 @@ extern "C" {
 typedef struct {
   int32_t n_layers, n_types, n_zones, n_mb, n_tp, n_dp, n_pp;
   int32_t max_segments, seg3_max_pp, uniform_layers;
+  int32_t per_segment_tp;          /* 1: every segment has its own TP degree (digit) */
   int64_t global_batch;
   const int32_t *mb_values, *tp_values, *dp_values, *pp_values;
   const int32_t *n_partitions;     /* [n_pp] */
@@ -60,7 +69,8 @@ typedef struct {
   int32_t pp, pp_idx, n_segments, partition;
   int32_t cut[2];  /* first stage of segment 2 / segment 3 (unused entries = pp) */
   int32_t pool[3]; /* zone * n_types + type, -1 if the segment is absent */
-  int32_t dp, tp, mb, dp_idx, tp_idx, mb_idx;
+  int32_t dp, tp, mb, dp_idx, tp_idx, mb_idx; /* tp, tp_idx: those of segment 1 */
+  int32_t seg_tp[3], seg_tp_idx[3];           /* TP degree per segment (0 / -1 if absent) */
 } so_config;
 
 typedef struct {

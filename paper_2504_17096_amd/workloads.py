@@ -100,6 +100,7 @@ class Problem:
     avail: np.ndarray              # int32 [Z][G]
     bandwidth: np.ndarray          # float64 [Z][Z], bytes/s
     egress_per_byte: Optional[np.ndarray] = None  # float64 [Z][Z] or None (= zeros)
+    per_segment_tp: bool = False   # every segment carries its own TP digit
     name: str = ""
     notes: dict = field(default_factory=dict)
 
@@ -118,6 +119,9 @@ class Problem:
     @property
     def n_pp(self) -> int:
         return len(self.pp_values)
+
+    def with_per_segment_tp(self, on: bool = True) -> "Problem":
+        return replace(self, per_segment_tp=bool(on))
 
     def with_avail(self, avail: np.ndarray) -> "Problem":
         return replace(self, avail=np.ascontiguousarray(avail, dtype=np.int32))
