@@ -31,6 +31,13 @@
  *     partition index q in [0, n_partitions[pp index]).
  * The numbering is part of the contract: the tie rule prefers the lowest index.
  *
+ * per_segment_tp = 1 gives every segment its own TP degree, the (GPU type, TP, zone)
+ * choice per stage of Sec. 4.2 under H1 (a TP group consists of one GPU type, and a
+ * segment runs on one).  The "tp index" digit above is then segment 1's, and the digit
+ * "tp index of the segment" follows r2 (segment 2) and r3 (segment 3).  A stage's
+ * memory shard, activation bytes, profiled times, node-size check, gradient shard,
+ * GPU count and rent use the degree of its segment.
+ *
  * Mask bits of an evaluated candidate (0 = valid plan)
  *   bit 0 OOM               some stage's worker exceeds its GPU's memory (Sec. 4.3)
  *   bit 1 OVER_QUOTA        a pool needs more GPUs than are available (Sec. 4)
@@ -92,6 +99,7 @@ typedef struct {
   int32_t max_segments;    /* 1, 2 or 3 */
   int32_t seg3_max_pp;     /* a third segment only for pp <= this */
   int32_t uniform_layers;  /* 1: time tables hold a single per-layer column */
+  int32_t per_segment_tp;  /* 1: every segment has its own TP digit; 0: one TP per plan */
   int64_t global_batch;    /* never changed by the planner (Sec. 4.2) */
   const int32_t *mb_values, *tp_values, *dp_values, *pp_values; /* positive, strictly ascending */
   const int32_t *n_partitions;     /* [n_pp], >= 1 */
@@ -134,6 +142,9 @@ typedef struct {
   int32_t partition, n_segments;
   int32_t cut[2];  /* first stage of segment 2 / 3; unused entries = pp */
   int32_t pool[3]; /* zone * n_types + type; unused entries = -1 */
+  int32_t seg_tp[3];       /* TP degree of each segment; unused entries = 0 */
+  int32_t seg_tp_index[3]; /* its index in tp_values; unused entries = -1;
+                              tp / tp_index above are those of segment 1 */
 } sailor_result;
 
 /* Build a plan: validate, copy the problem to the current HIP device, build the static

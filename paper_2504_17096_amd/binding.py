@@ -41,6 +41,7 @@ class sailor_problem(C.Structure):
         ("n_layers", C.c_int32), ("n_types", C.c_int32), ("n_zones", C.c_int32),
         ("n_mb", C.c_int32), ("n_tp", C.c_int32), ("n_dp", C.c_int32), ("n_pp", C.c_int32),
         ("max_segments", C.c_int32), ("seg3_max_pp", C.c_int32), ("uniform_layers", C.c_int32),
+        ("per_segment_tp", C.c_int32),
         ("global_batch", C.c_int64),
         ("mb_values", C.c_void_p), ("tp_values", C.c_void_p), ("dp_values", C.c_void_p),
         ("pp_values", C.c_void_p), ("n_partitions", C.c_void_p), ("partition_layers", C.c_void_p),
@@ -68,6 +69,7 @@ class sailor_result(C.Structure):
         ("pp_index", C.c_int32), ("tp_index", C.c_int32), ("dp_index", C.c_int32),
         ("mb_index", C.c_int32), ("partition", C.c_int32), ("n_segments", C.c_int32),
         ("cut", C.c_int32 * 2), ("pool", C.c_int32 * 3),
+        ("seg_tp", C.c_int32 * 3), ("seg_tp_index", C.c_int32 * 3),
     ]
 
 
@@ -90,12 +92,14 @@ class Result:
     n_segments: int
     cut: Tuple[int, int]
     pool: Tuple[int, int, int]
+    seg_tp: Tuple[int, int, int] = (0, 0, 0)
+    seg_tp_index: Tuple[int, int, int] = (-1, -1, -1)
 
 
 def _result(r: sailor_result) -> Result:
     return Result(r.index, r.peak_mem_bytes, r.iter_time_s, r.cost_per_iter, r.mask, r.pp, r.tp,
                   r.dp, r.mb, r.pp_index, r.tp_index, r.dp_index, r.mb_index, r.partition,
-                  r.n_segments, tuple(r.cut), tuple(r.pool))
+                  r.n_segments, tuple(r.cut), tuple(r.pool), tuple(r.seg_tp), tuple(r.seg_tp_index))
 
 
 _lib = None
@@ -146,6 +150,7 @@ def marshal_problem(prob):
     s.n_dp, s.n_pp = len(prob.dp_values), len(prob.pp_values)
     s.max_segments, s.seg3_max_pp = prob.max_segments, prob.seg3_max_pp
     s.uniform_layers = 1 if prob.uniform_layers else 0
+    s.per_segment_tp = 1 if getattr(prob, "per_segment_tp", False) else 0
     s.global_batch = prob.global_batch
     s.mb_values = arr(prob.mb_values, np.int32)
     s.tp_values = arr(prob.tp_values, np.int32)

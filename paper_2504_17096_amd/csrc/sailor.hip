@@ -131,6 +131,7 @@ sailor_status validate(const sailor_problem *p) {
       p->n_dp < 1 || p->n_dp > SAILOR_MAX_DP || p->n_pp < 1)
     return SAILOR_EINVAL;
   if (p->max_segments < 1 || p->max_segments > 3 || p->global_batch < 1) return SAILOR_EINVAL;
+  if (p->per_segment_tp != 0 && p->per_segment_tp != 1) return SAILOR_EINVAL;
   if (!ascending_positive(p->mb_values, p->n_mb) || !ascending_positive(p->tp_values, p->n_tp) ||
       !ascending_positive(p->dp_values, p->n_dp) || !ascending_positive(p->pp_values, p->n_pp))
     return SAILOR_EINVAL;
@@ -153,6 +154,8 @@ sailor_status validate(const sailor_problem *p) {
       if (sum != L) return SAILOR_EINVAL;
     }
   }
+  // the quota table has one row per GPU count a replica can take from a pool
+  if ((int64_t)p->pp_values[p->n_pp - 1] * p->tp_values[p->n_tp - 1] > (1 << 20)) return SAILOR_EINVAL;
   const size_t Lc = p->uniform_layers ? 1 : (size_t)L;
   if (!finite_nonneg(p->t_fwd, (size_t)G * p->n_mb * p->n_tp * Lc) ||
       !finite_nonneg(p->t_bwd, (size_t)G * p->n_mb * p->n_tp * Lc) ||
@@ -195,6 +198,8 @@ sailor_status build_space(const sailor_problem *p, sailor_plan *pl, std::vector<
                           std::vector<int32_t> &st_first, std::vector<uint8_t> &st_flags) {
   const int ZG = p->n_types * p->n_zones;
   const uint64_t inner = (uint64_t)p->n_mb * p->n_tp * p->n_dp * ZG;
+  const int pst = p->per_segment_tp ? 1 : 0;
+  const uint64_t otp = pst ? (uint64_t)p->n_tp : 1u;  // radix of the tp digits of segments 2, 3
   uint64_t off = 0;
   uint32_t row_stage = 0;
   size_t row = 0;
@@ -215,13 +220,12 @@ sailor_status build_space(const sailor_problem *p, sailor_plan *pl, std::vector<
     for (int s = 1; s <= 3; ++s) {
       if (s > p->max_segments || s > P || (s == 3 && P > p->seg3_max_pp)) continue;
       uint64_t shape_size = inner;
-      for (int j = 1; j < s; ++j) shape_size *= (uint64_t)(ZG - 1);
+      for (int j = 1; j < s; ++j) shape_size *= (uint64_t)(ZG - 1) * otp;
       if (shape_size == 0) continue;
-      if (shape_size >> 32) return SAILOR_EINVAL;
       BlockRec b{};
       b.off = off;
       b.first_shape = (uint32_t)pl->shapes.size();
-      b.shape_size = (uint32_t)shape_size;
+      b.shape_size = shape_size;
       b.pp_idx = ip;
       b.s = s;
       b.P = P;
@@ -256,8 +260,11 @@ sailor_status build_space(const sailor_problem *p, sailor_plan *pl, std::vector<
   pl->dev.N = off;
   pl->dev.inner = (uint32_t)inner;
   pl->dev.n_row_stages = (int)row_stage;
+  pl->dev.pst = pst;
+  pl->dev.otp = (int)otp;
+  pl->dev.stride3 = inner * (uint64_t)(ZG - 1) * otp;
 
-  // scan units: (shape, tp, range of segment 2's pool)
+  // scan units: (shape, tp of every segment, range of segment 2's pool)
   const uint64_t unit_target =
       std::min(kUnitTargetMax, std::max(kUnitTargetMin, pl->dev.N / kUnitsWanted));
   const uint64_t innerp = (uint64_t)p->n_mb * p->n_dp * ZG;
@@ -267,25 +274,36 @@ sailor_status build_space(const sailor_problem *p, sailor_plan *pl, std::vector<
     const uint64_t per_o = sh.s == 3 ? innerp * (uint64_t)(ZG - 1) : innerp;
     int chunk = (int)std::min<uint64_t>((uint64_t)n_o, std::max<uint64_t>(1, unit_target / per_o));
     const int n_chunks = (n_o + chunk - 1) / chunk;
-    for (int t = 0; t < p->n_tp; ++t)
-      for (int c = 0; c < n_chunks; ++c) {
-        const int lo = (int)((int64_t)n_o * c / n_chunks), hi = (int)((int64_t)n_o * (c + 1) / n_chunks);
-        UnitRec u{};
-        u.shape = si;
-        u.tp = (uint16_t)t;
-        u.s = sh.s;
-        u.o_lo = (uint16_t)lo;
-        u.o_cnt = (uint16_t)(hi - lo);
-        pl->units.push_back(u);
-      }
+    const int n_t1 = (pst && sh.s >= 2) ? p->n_tp : 1, n_t2 = (pst && sh.s == 3) ? p->n_tp : 1;
+    for (int t2 = 0; t2 < n_t2; ++t2)
+      for (int t1 = 0; t1 < n_t1; ++t1)
+        for (int t = 0; t < p->n_tp; ++t)
+          for (int c = 0; c < n_chunks; ++c) {
+            const int lo = (int)((int64_t)n_o * c / n_chunks),
+                      hi = (int)((int64_t)n_o * (c + 1) / n_chunks);
+            UnitRec u{};
+            u.shape = si;
+            u.tp[0] = (uint8_t)t;
+            u.tp[1] = (uint8_t)(pst ? t1 : t);
+            u.tp[2] = (uint8_t)(pst ? t2 : t);
+            u.s = (uint8_t)sh.s;
+            u.o_lo = (uint16_t)lo;
+            u.o_cnt = (uint16_t)(hi - lo);
+            u.off = pst ? inner * (uint64_t)(ZG - 1) * (uint64_t)t1 +
+                              pl->dev.stride3 * (uint64_t)(ZG - 1) * (uint64_t)t2
+                        : 0u;
+            pl->units.push_back(u);
+          }
   }
-  // units of the range evaluation: (shape, range of the outer pool digits), about 16 Ki
+  if (pl->units.size() > (size_t)0x7fffffff / kCollectSub) return SAILOR_EINVAL;
+  // units of the range evaluation: (shape, range of the outer digits), about 16 Ki
   // candidates each, in index order
   for (uint32_t si = 0; si < pl->shapes.size(); ++si) {
     const ShapeRec &sh = pl->shapes[si];
     uint64_t o_total = 1;
-    for (int j = 1; j < sh.s; ++j) o_total *= (uint64_t)(ZG - 1);
-    const uint64_t chunk = std::min<uint64_t>(o_total, std::max<uint64_t>(1, kEvalUnitTarget / inner));
+    for (int j = 1; j < sh.s; ++j) o_total *= (uint64_t)(ZG - 1) * otp;
+    const uint64_t chunk = std::min<uint64_t>(
+        std::min<uint64_t>(o_total, kEvalUnitMaxOuter), std::max<uint64_t>(1, kEvalUnitTarget / inner));
     for (uint64_t lo = 0; lo < o_total; lo += chunk) {
       EvalUnit e{};
       e.shape = si;
@@ -350,11 +368,21 @@ void fill_config(const sailor_plan *pl, const ShapeRec &sh, uint64_t index, sail
   out->dp_index = (in / (d.MB * d.TP)) % d.DP;
   out->pool[0] = in / (d.MB * d.TP * d.DP);
   out->pool[1] = out->pool[2] = -1;
+  out->seg_tp_index[0] = out->tp_index;
+  out->seg_tp_index[1] = out->seg_tp_index[2] = -1;
   if (sh.s >= 2) {
     out->pool[1] = (out->pool[0] + 1 + (int)(o % (d.ZG - 1))) % d.ZG;
     o /= (d.ZG - 1);
+    out->seg_tp_index[1] = d.pst ? (int32_t)(o % d.TP) : out->tp_index;
+    if (d.pst) o /= d.TP;
   }
-  if (sh.s == 3) out->pool[2] = (out->pool[1] + 1 + (int)o) % d.ZG;
+  if (sh.s == 3) {
+    out->pool[2] = (out->pool[1] + 1 + (int)(o % (d.ZG - 1))) % d.ZG;
+    o /= (d.ZG - 1);
+    out->seg_tp_index[2] = d.pst ? (int32_t)o : out->tp_index;
+  }
+  for (int j = 0; j < 3; ++j)
+    out->seg_tp[j] = out->seg_tp_index[j] >= 0 ? pl->tpv[out->seg_tp_index[j]] : 0;
   out->pp_index = sh.pp_idx;
   out->pp = sh.P;
   out->mb = pl->mbv[out->mb_index];
@@ -373,13 +401,17 @@ const ShapeRec &shape_of(const sailor_plan *pl, uint64_t index) {
   return pl->shapes[blk->first_shape + (index - blk->off) / blk->shape_size];
 }
 
+unsigned quota_grid(const DevPlan &d) {
+  return (unsigned)std::min<size_t>(1024, ((size_t)(d.W_max + 1) * d.ZG + 255) / 256);
+}
+
 // Brings a changed availability table to the device on the caller's stream and rebuilds
 // the quota table from it.
 sailor_status refresh_avail(sailor_plan *pl, hipStream_t st) {
   if (!pl->avail_dirty) return SAILOR_OK;
   HIP_TRY(hipMemcpyAsync(pl->d_avail, pl->h_avail, pl->dev.ZG * sizeof(int32_t),
                          hipMemcpyHostToDevice, st));
-  k_quota_table<<<pl->dev.P_max + 1, 256, 0, st>>>(pl->dev);
+  k_quota_table<<<quota_grid(pl->dev), 256, 0, st>>>(pl->dev);
   HIP_TRY(hipEventRecord(pl->ev_upload, st));
   pl->upload_pending = true;
   pl->avail_dirty = false;
@@ -606,8 +638,8 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   pl->eval_lds_bytes = (size_t)3 * d.TP * d.ZG * d.MB * sizeof(Rec) +
                        (size_t)d.Z * d.Z * sizeof(float4) +
                        (size_t)3 * d.TP * d.MB * d.DP * sizeof(uint64_t) +
-                       (size_t)4 * d.TP * d.ZG * sizeof(uint32_t) +
-                       (size_t)d.ZG * (sizeof(PoolInfo) + sizeof(uint32_t));
+                       (size_t)3 * d.TP * d.ZG * sizeof(uint32_t) + (size_t)d.ZG * sizeof(PoolInfo) +
+                       (size_t)(kEvalUnitMaxOuter + d.DP + d.TP) * sizeof(uint32_t);
   pl->lds_bytes = (size_t)3 * d.ZG * d.MB * sizeof(Rec) + (size_t)d.Z * d.Z * sizeof(float4) +
                   (size_t)4 * d.ZG * sizeof(uint32_t);
 
@@ -635,7 +667,9 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(hipEventCreateWithFlags(&pl->ev_upload, hipEventDisableTiming));
   d.P_max = 0;
   for (int ip = 0; ip < p->n_pp; ++ip) d.P_max = std::max(d.P_max, (int)p->pp_values[ip]);
-  CREATE_TRY(ar.alloc(&d.qtab, (size_t)(d.P_max + 1) * TP * ZG));
+  d.W_max = d.P_max * p->tp_values[TP - 1];
+  CREATE_TRY(ar.alloc(&d.qw, (size_t)(d.W_max + 1) * ZG));
+  CREATE_TRY(ar.alloc(&d.h1m, ZG));
   CREATE_TRY(ar.upload(&d.cap, p->mem_capacity, G));
   CREATE_TRY(ar.upload(&d.res, p->mem_reserved, G));
   CREATE_TRY(ar.upload(&d.node, p->gpus_per_node, G));
@@ -665,7 +699,7 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(ar.alloc(&d.xb_f, MB));
   CREATE_TRY(ar.alloc(&d.cd_f, DP));
   CREATE_TRY(ar.alloc(&d.nbm1_f, (size_t)MB * DP));
-  CREATE_TRY(ar.alloc(&d.dtp_f, (size_t)TP * DP));
+  CREATE_TRY(ar.alloc(&d.dph_f, DP));
   CREATE_TRY(ar.alloc(&d.nb, (size_t)MB * DP));
   CREATE_TRY(ar.alloc(&d.divis, MB));
   CREATE_TRY(ar.alloc(&d.st_params, RS));
@@ -693,7 +727,7 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   for (hipEvent_t &e : pl->ev) CREATE_TRY(hipEventCreate(&e));
 
   k_init_counters<<<1, 64>>>(pl->counters, 2 * CNT_COUNT);
-  k_quota_table<<<d.P_max + 1, 256>>>(d);
+  k_quota_table<<<quota_grid(d), 256>>>(d);
   k_small_tables<<<1, 256>>>(d);
   k_stage_tables<<<(unsigned)RS, 128>>>(d, sa);
   k_shape_agg<<<(unsigned)NS, 256>>>(d);

@@ -14,6 +14,7 @@ namespace sailor {
 
 constexpr int kMaxMB = 8, kMaxTP = 8, kMaxDP = 24, kMaxPools = 64, kMaxZones = 16,
               kMaxTypes = 16, kMaxStages = 256;
+constexpr int kEvalUnitMaxOuter = 1024;  // most outer-digit values one range-evaluation unit spans
 constexpr int kMaxUnitThreads = 512;  // scan workgroups use 2..8 waves, chosen per plan
 constexpr float kNegInf = -__builtin_huge_valf();
 constexpr float kPosInf = __builtin_huge_valf();
@@ -35,15 +36,17 @@ struct ShapeRec {
 
 struct BlockRec {       // all candidates with one (pp index, segment count)
   uint64_t off, size;
+  uint64_t shape_size;  // candidates per shape
   uint32_t first_shape, n_shapes;
-  uint32_t shape_size;  // candidates per shape
-  uint32_t pp_idx, s, P;
+  uint32_t pp_idx, s, P, pad;
 };
 
-struct UnitRec {        // work of one workgroup of the scan: one shape, one tp, a range
-  uint32_t shape;       // [o_lo, o_lo + o_cnt) of segment 2's pool
-  uint16_t tp, s;
+struct UnitRec {        // work of one workgroup of the scan: one shape, one tp per segment
+  uint32_t shape;       // (all equal unless segments carry their own tp digit), a range
+  uint8_t tp[3], s;     // [o_lo, o_lo + o_cnt) of segment 2's pool
   uint16_t o_lo, o_cnt;
+  uint32_t pad;
+  uint64_t off;         // index offset of the unit's tp digits of segments 2 and 3
 };
 
 struct EvalUnit {       // work of one workgroup of the range evaluation: one shape, all tp,
@@ -74,7 +77,11 @@ struct ResultHeader {   // written by the final kernel into host-mapped memory
 struct DevPlan {
   int G, Z, ZG, MB, TP, DP;
   int n_blocks, n_shapes, n_units, n_row_stages, P_max;
-  uint32_t inner;          // MB*TP*DP*ZG candidates per (shape, outer pool digits)
+  int pst;                 // 1: segments 2 and 3 carry their own tp digit
+  int otp;                 // radix of those digits: TP, or 1 when all segments share one tp
+  int W_max;               // most GPUs one replica can take from a pool: P_max * largest tp
+  uint32_t inner;          // MB*TP*DP*ZG candidates per (shape, outer digits)
+  uint64_t stride3;        // index stride of segment 3's relative pool: inner*(ZG-1)*otp
   uint32_t bpp, gb;
   // ceil(2^32 / d) for d = MB, G, MB*TP, MB*TP*DP, MB*ZG, MB*(ZG-1) (0 encodes d = 1)
   uint32_t mg_mb, mg_g, mg_mbtp, mg_mbtpdp, mg_mbzg, mg_mbzg1;
@@ -90,14 +97,14 @@ struct DevPlan {
   const uint64_t *act;         // [MB][TP]
   const uint64_t *p2p;         // [MB]
   // derived small tables
-  uint32_t *qtab;              // [P_max + 1][TP][ZG] bit d: n stages x dpv[d] x tp GPUs fit the
-                               // pool; bit 31: tp exceeds the pool's node size (H1)
+  uint32_t *qw;                // [W_max + 1][ZG] bit d: dpv[d] replicas of w GPUs fit the pool
+  uint32_t *h1m;               // [ZG] bit k: tpv[k] exceeds the node size of the pool's type (H1)
   float *ibw_f, *egs_f;        // [Z][Z] 1/bw ; egress both ways
   float *price_f;              // [G]
   float *p2p_f, *xb_f;         // [MB] p2p bytes ; (B/mb) * p2p bytes
   float *cd_f;                 // [DP] 2 (D-1) / D
   float *nbm1_f;               // [MB][DP] microbatches per pipeline - 1
-  float *dtp_f;                // [TP][DP] D * tp / 3600
+  float *dph_f;                // [DP] D / 3600
   int32_t *nb;                 // [MB][DP] microbatches per pipeline, 0 if B % (D mb) != 0
   uint32_t *divis;             // [MB] bit d set when nb[mb][d] > 0
   // per-stage tables, one entry per stage of every partition row

@@ -47,6 +47,12 @@ __global__ void k_small_tables(DevPlan pl) {
     pl.egs_f[i] = (float)e;
   }
   for (int g = t; g < pl.G; g += nt) pl.price_f[g] = (float)pl.price[g];
+  for (int p = t; p < pl.ZG; p += nt) {  // H1: tensor parallelism stays inside a node
+    uint32_t m = 0;
+    for (int k = 0; k < pl.TP; ++k)
+      if (pl.tpv[k] > pl.node[p % pl.G]) m |= 1u << k;
+    pl.h1m[p] = m;
+  }
   for (int m = t; m < pl.MB; m += nt) {
     pl.p2p_f[m] = (float)(double)pl.p2p[m];
     // N_b * D = B / mb whenever the batch divides; the product is exact in fp64 for
@@ -65,8 +71,7 @@ __global__ void k_small_tables(DevPlan pl) {
   for (int d = t; d < pl.DP; d += nt) {
     double D = (double)pl.dpv[d];
     pl.cd_f[d] = (float)(2.0 * (D - 1.0) / D);
-    for (int k = 0; k < pl.TP; ++k)
-      pl.dtp_f[k * pl.DP + d] = (float)((double)((int64_t)pl.dpv[d] * pl.tpv[k]) / 3600.0);
+    pl.dph_f[d] = (float)(D / 3600.0);
   }
 }
 
@@ -203,16 +208,16 @@ struct Rec {       // one segment placed on one pool, for one (mb, tp); 32 bytes
   float tI;        // slowest interior stage
   float syncb;     // gradient bytes of the largest shard / intra-zone bandwidth
   float upd;       // slowest update
-  float pricen;    // stages * $/h
+  float pricen;    // stages * tp * $/h: rent of one replica of the segment
   uint32_t bits;   // bit d: valid for dp index d (memory, quota, batch, H1)
 };
 
-struct LaneC {     // scalars of a (mb, dp, tp) triple
-  float p2pf, nbm1, cd, dtp, xb;
+struct LaneC {     // scalars of a (mb, dp) pair
+  float p2pf, nbm1, cd, dph, xb;
 };
 
 __device__ __forceinline__ Rec make_rec(float4 ta, float smax, float upd, float price, float p2pf,
-                                        float ibw_zz, int n, uint32_t bits) {
+                                        float ibw_zz, int n, int tp, uint32_t bits) {
   Rec r;
   const float w = p2pf * ibw_zz;  // one transfer inside the zone
   r.sumT = fmaf((float)(2 * (n - 1)), w, ta.x);
@@ -221,7 +226,7 @@ __device__ __forceinline__ Rec make_rec(float4 ta, float smax, float upd, float 
   r.tI = (n >= 3) ? fmaf(2.0f, w, ta.w) : kNegInf;
   r.syncb = smax * ibw_zz;
   r.upd = upd;
-  r.pricen = (float)n * price;
+  r.pricen = (float)(n * tp) * price;
   r.bits = bits;
   return r;
 }
@@ -279,29 +284,21 @@ __device__ __forceinline__ void acc_finish(const Acc &p, const LaneC &lc, float 
   const float tmax = fmaxf(p.tmax, fmaxf(fmaxf(p.tf, p.tl), p.ti));
   const float tpp = fmaf(lc.nbm1, tmax, p.sum);
   T = fmaf(lc.cd, p.syn, tpp) + p.up;
-  C = fmaf(p.pr * lc.dtp, T, lc.xb * p.egs);
+  C = fmaf(p.pr * lc.dph, T, lc.xb * p.egs);
 }
 
-// bit d set when n stages with D = dpv[d] replicas of tp GPUs fit into avail GPUs
-__device__ __forceinline__ uint32_t quota_bits(const DevPlan &pl, int n, int tp, int avail) {
-  uint32_t bits = 0;
-  for (int d = 0; d < pl.DP; ++d)
-    if ((int64_t)n * pl.dpv[d] * tp <= (int64_t)avail) bits |= 1u << d;
-  return bits;
-}
-
-constexpr uint32_t kH1Bit = 1u << 31;
-
-// Quota table, rebuilt whenever the availability changes: for n stages on one pool with
-// tensor-parallel degree tp, which data-parallel degrees fit (Sec. 4: resource quotas),
-// plus the H1 flag of the pool's GPU type.
+// Quota table, rebuilt whenever the availability changes: a replica that takes w GPUs
+// from a pool (its stages there times their tensor-parallel degrees) can be placed for
+// the data-parallel degrees whose bit is set (Sec. 4: resource quotas).
 __global__ void k_quota_table(DevPlan pl) {
-  const int n = blockIdx.x;
-  for (int i = threadIdx.x; i < pl.TP * pl.ZG; i += blockDim.x) {
-    const int p = i % pl.ZG, k = i / pl.ZG;
-    uint32_t b = quota_bits(pl, n, pl.tpv[k], pl.avail[p]);
-    if (pl.tpv[k] > pl.node[p % pl.G]) b |= kH1Bit;
-    pl.qtab[(size_t)n * pl.TP * pl.ZG + i] = b;
+  const int n = (pl.W_max + 1) * pl.ZG;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    const int p = i % pl.ZG, w = i / pl.ZG;
+    const int64_t avail = pl.avail[p];
+    uint32_t bits = 0;
+    for (int d = 0; d < pl.DP; ++d)
+      if ((int64_t)w * pl.dpv[d] <= avail) bits |= 1u << d;
+    pl.qw[i] = bits;
   }
 }
 
@@ -393,7 +390,7 @@ struct LaneItem {  // what a lane owns for one chunk of the lane space
 // slowest, so a wave holds one or two dp values and whole waves drop out together when
 // their data-parallel degree cannot be placed.  mg = ceil(2^32 / (MB * n_a1)).
 __device__ __forceinline__ LaneItem lane_item(const DevPlan &pl, int e, int n_items, int n_a1,
-                                              uint32_t mg, int tp) {
+                                              uint32_t mg) {
   LaneItem it;
   it.active = e < n_items;
   const uint32_t ee = it.active ? (uint32_t)e : 0u;
@@ -405,7 +402,7 @@ __device__ __forceinline__ LaneItem lane_item(const DevPlan &pl, int e, int n_it
   it.lc.p2pf = pl.p2p_f[it.mb];
   it.lc.nbm1 = pl.nbm1_f[it.mb * pl.DP + it.dp];
   it.lc.cd = pl.cd_f[it.dp];
-  it.lc.dtp = pl.dtp_f[tp * pl.DP + it.dp];
+  it.lc.dph = pl.dph_f[it.dp];
   it.lc.xb = pl.xb_f[it.mb];
   it.dpbit = it.active ? (1u << it.dp) : 0u;
   return it;
@@ -435,11 +432,12 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
   const int wave = (int)(threadIdx.x >> 6) + (int)(blockDim.x >> 6) * sub;
   const int nwave = (int)(blockDim.x >> 6) * n_sub;
   const bool single0 = sh.n[0] == 1, single1 = sh.n[1] == 1;
-  const int tp = u.tp;
+  const int tp = u.tp[0];
+  const uint64_t ubase = sh.base + u.off;
   if (S <= 2) {
     const int nin = MB * DP * ZG;
     for (int e0 = wave * 64; e0 < nin; e0 += nwave * 64) {
-      const LaneItem it = lane_item(pl, e0 + lane, nin, ZG, pl.mg_mbzg, tp);
+      const LaneItem it = lane_item(pl, e0 + lane, nin, ZG, pl.mg_mbzg);
       const int a1 = it.a1;
       const Rec *recm = rec + it.mb;         // this lane's column of the record table
       const Rec r0 = recm[a1 * MB];
@@ -449,7 +447,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
       const float4 *pair1 = pair + z1 * Z;   // transfers out of this lane's first zone
       const Acc A0 = acc_begin(r0);
       // index of the candidate whose outer digits are all zero
-      const uint64_t idx0 = sh.base + (uint64_t)(it.mb + MB * (tp + pl.TP * (it.dp + DP * a1)));
+      const uint64_t idx0 = ubase + (uint64_t)(it.mb + MB * (tp + pl.TP * (it.dp + DP * a1)));
       if (S == 1) {
         float T, C;
         acc_finish(A0, it.lc, T, C);
@@ -480,7 +478,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
     int z2 = u.o_lo / G, g2 = u.o_lo % G;
     for (int a2 = u.o_lo; a2 < u.o_lo + u.o_cnt; ++a2) {
       for (int e0 = wave * 64; e0 < nin; e0 += nwave * 64) {
-        const LaneItem it = lane_item(pl, e0 + lane, nin, ZG - 1, pl.mg_mbzg1, tp);
+        const LaneItem it = lane_item(pl, e0 + lane, nin, ZG - 1, pl.mg_mbzg1);
         const int a1 = it.a1 + (it.a1 >= a2 ? 1 : 0);  // skip the pool of segment 2
         const Rec *recm = rec + it.mb;
         const Rec r0 = recm[a1 * MB];
@@ -494,7 +492,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
         const uint32_t q13a = q13[a1];
         int rel2 = a2 - a1 - 1;
         if (rel2 < 0) rel2 += ZG;
-        const uint64_t idx0 = sh.base + (uint64_t)(it.mb + MB * (tp + pl.TP * (it.dp + DP * a1))) +
+        const uint64_t idx0 = ubase + (uint64_t)(it.mb + MB * (tp + pl.TP * (it.dp + DP * a1))) +
                               (uint64_t)pl.inner * (uint64_t)rel2;
         int z3 = 0, g3 = 0;
         for (int a3 = 0; a3 < ZG; ++a3) {
@@ -512,8 +510,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
               float T, C;
               acc_finish(A2, it.lc, T, C);
               visit<MODE, OBJ, HASB>(a, T, C, b2 != 0, tau,
-                                     idx0 + (uint64_t)pl.inner * (uint64_t)((ZG - 1) * rel3), ms,
-                                     ml);
+                                     idx0 + pl.stride3 * (uint64_t)rel3, ms, ml);
             }
           }
           if (++g3 == G) { g3 = 0; ++z3; }
@@ -550,24 +547,25 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
   const int t = threadIdx.x;
 
   const int n0 = sh.n[0], n1 = sh.n[1], n2 = sh.n[2];
-  const uint32_t *qt = pl.qtab + (size_t)u.tp * ZG;  // + n * TP * ZG + pool
-  const size_t qstride = (size_t)pl.TP * ZG;
+  const int k0 = u.tp[0], k1 = u.tp[1], k2 = u.tp[2];            // tp index of each segment
+  const int tv0 = pl.tpv[k0], tv1 = pl.tpv[k1], tv2 = pl.tpv[k2];
+  const int w0 = n0 * tv0, w1 = n1 * tv1, w2 = n2 * tv2;        // GPUs of one replica
   __shared__ uint32_t s_any;  // bit j: some pool can host segment j
   if (t == 0) s_any = 0;
   __syncthreads();
   uint32_t any_here = 0;
   for (int i = t; i < S * ZG; i += blockDim.x) {
     const int seg = i >= 2 * ZG ? 2 : (i >= ZG ? 1 : 0), p = i - seg * ZG;
-    const int n = seg == 0 ? n0 : (seg == 1 ? n1 : n2);
-    uint32_t b = qt[n * qstride + p];
-    if (b & kH1Bit) b = 0;  // H1: tensor parallelism stays inside a node
+    const int w = seg == 0 ? w0 : (seg == 1 ? w1 : w2), k = seg == 0 ? k0 : (seg == 1 ? k1 : k2);
+    uint32_t b = pl.qw[w * ZG + p];
+    if ((pl.h1m[p] >> k) & 1u) b = 0;  // H1: tensor parallelism stays inside a node
     qm[i] = b;
     // a segment nobody can host rules the whole unit out
     const bool counts = seg != 1 || (p >= (int)u.o_lo && p < (int)(u.o_lo + u.o_cnt));
     if (b != 0 && counts) any_here |= 1u << seg;
   }
   if (S == 3)
-    for (int p = t; p < ZG; p += blockDim.x) q13[p] = qt[(n0 + n2) * qstride + p];
+    for (int p = t; p < ZG; p += blockDim.x) q13[p] = pl.qw[(w0 + w2) * ZG + p];
   for (int i = t; i < Z * Z; i += blockDim.x) {
     const int za = i / Z, zb = i % Z;
     pair[i] = make_float4(pl.ibw_f[za * Z + zb], pl.ibw_f[zb * Z + za], pl.egs_f[i], 0.f);
@@ -585,12 +583,14 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
     const uint32_t sp = fast_div((uint32_t)i, pl.mg_mb), mb = (uint32_t)i - sp * (uint32_t)MB;
     const int seg = sp >= 2u * ZG ? 2 : (sp >= (uint32_t)ZG ? 1 : 0), p = (int)sp - seg * ZG;
     const int z = (int)fast_div((uint32_t)p, pl.mg_g), g = p - z * G;
-    const uint32_t sl = (u.shape * (uint32_t)pl.TP + u.tp) * 3u + (uint32_t)seg;
+    const int k = seg == 0 ? k0 : (seg == 1 ? k1 : k2);
+    const uint32_t sl = (u.shape * (uint32_t)pl.TP + (uint32_t)k) * 3u + (uint32_t)seg;
     const uint32_t gi = (sl * (uint32_t)G + (uint32_t)g) * (uint32_t)MB + mb;
     const float4 ta = pl.ta[gi];
     const uint32_t bits = pl.memok[gi] & qm[seg * ZG + p] & pl.divis[mb];
     rec[i] = make_rec(ta, pl.smax[sl], pl.upd[sl * G + g], pl.price_f[g], pl.p2p_f[mb],
-                      pl.ibw_f[z * Z + z], seg == 0 ? n0 : (seg == 1 ? n1 : n2), bits);
+                      pl.ibw_f[z * Z + z], seg == 0 ? n0 : (seg == 1 ? n1 : n2),
+                      seg == 0 ? tv0 : (seg == 1 ? tv1 : tv2), bits);
   }
   __syncthreads();
 
@@ -679,7 +679,8 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stri
 
 struct Cand {
   uint32_t shape;
-  int P, s, mb, tp, dp;      // indices into the value lists
+  int P, s, mb, dp;          // indices into the value lists
+  int tp[3];                 // tp index of each segment
   int a[3];
   int k1, k2;
 };
@@ -692,22 +693,27 @@ __device__ __forceinline__ bool decode_index(const DevPlan &pl, uint64_t idx, Ca
   const BlockRec blk = pl.blocks[b];
   const uint64_t r = idx - blk.off;
   const uint32_t sl = (uint32_t)(r / blk.shape_size);
-  uint32_t rem = (uint32_t)(r % blk.shape_size);
+  const uint64_t rem = r % blk.shape_size;
   c.shape = blk.first_shape + sl;
   c.P = blk.P;
   c.s = blk.s;
-  const uint32_t in = rem % pl.inner;
-  uint32_t o = rem / pl.inner;
+  const uint32_t in = (uint32_t)(rem % pl.inner);
+  uint32_t o = (uint32_t)(rem / pl.inner);
   c.mb = in % pl.MB;
-  c.tp = (in / pl.MB) % pl.TP;
+  c.tp[0] = c.tp[1] = c.tp[2] = (in / pl.MB) % pl.TP;
   c.dp = (in / (pl.MB * pl.TP)) % pl.DP;
   c.a[0] = in / (pl.MB * pl.TP * pl.DP);
   c.a[1] = c.a[2] = -1;
   if (c.s >= 2) {
     c.a[1] = (c.a[0] + 1 + (int)(o % (pl.ZG - 1))) % pl.ZG;
     o /= (pl.ZG - 1);
+    if (pl.pst) { c.tp[1] = (int)(o % pl.TP); o /= pl.TP; }
   }
-  if (c.s == 3) c.a[2] = (c.a[1] + 1 + (int)o) % pl.ZG;
+  if (c.s == 3) {
+    c.a[2] = (c.a[1] + 1 + (int)(o % (pl.ZG - 1))) % pl.ZG;
+    o /= (pl.ZG - 1);
+    if (pl.pst) c.tp[2] = (int)o;
+  }
   const ShapeRec sh = pl.shapes[c.shape];
   c.k1 = sh.k1;
   c.k2 = sh.k2;
@@ -738,7 +744,7 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
   const int lane = threadIdx.x & 63;
   const ShapeRec sh = pl.shapes[c.shape];
   const uint32_t rs = sh.row_stage;
-  const int64_t D = pl.dpv[c.dp], tp = pl.tpv[c.tp];
+  const int64_t D = pl.dpv[c.dp];
   mask = 0;
   peak = 0;
   const int64_t nb = pl.nb[c.mb * DP + c.dp];
@@ -747,22 +753,23 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
     T = C = __builtin_huge_val();
     return;
   }
-  const uint64_t act = pl.act[c.mb * TP + c.tp];
   const double p2p = (double)pl.p2p[c.mb];
-  // quota per pool and H1
+  // quota per pool (GPUs of one replica there, times D) and H1
   for (int j = 0; j < c.s; ++j) {
-    int64_t stages = sh.n[j];
+    int64_t gpus = 0;
     for (int j2 = 0; j2 < c.s; ++j2)
-      if (j2 != j && c.a[j2] == c.a[j]) stages += sh.n[j2];
-    if (stages * D * tp > (int64_t)pl.avail[c.a[j]]) mask |= 2u;
-    if (tp > pl.node[c.a[j] % G]) mask |= 8u;
+      if (c.a[j2] == c.a[j]) gpus += (int64_t)sh.n[j2] * pl.tpv[c.tp[j2]];
+    if (gpus * D > (int64_t)pl.avail[c.a[j]]) mask |= 2u;
+    if (pl.tpv[c.tp[j]] > pl.node[c.a[j] % G]) mask |= 8u;
   }
   double max_t = 0.0, t_sync = 0.0, t_upd = 0.0;
   uint32_t oom = 0;
   for (int i = lane; i < P; i += 64) {
     const int seg = i < c.k1 ? 0 : (i < c.k2 ? 1 : 2);
     const int g = c.a[seg] % G, z = c.a[seg] / G;
-    const uint64_t m = stage_bytes(pl, rs, i, P, (int)tp, nb, act) + pl.res[g];
+    const int k = c.tp[seg];
+    const int64_t tp = pl.tpv[k];
+    const uint64_t m = stage_bytes(pl, rs, i, P, (int)tp, nb, pl.act[c.mb * TP + k]) + pl.res[g];
     if (m > pl.cap[g]) oom = 1u;
     peak = m > peak ? m : peak;
     double x = 0.0, comm = 0.0;
@@ -777,7 +784,7 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
       const int sp = (i - 1) < c.k1 ? 0 : ((i - 1) < c.k2 ? 1 : 2);
       x += p2p / pl.bw[z * Z + c.a[sp] / G];
     }
-    const double t = pl.st_c[(((size_t)(rs + i) * G + g) * MB + c.mb) * TP + c.tp] + x;
+    const double t = pl.st_c[(((size_t)(rs + i) * G + g) * MB + c.mb) * TP + k] + x;
     max_t = fmax(max_t, t);
     if (D > 1) {
       const uint64_t shard = (pl.st_params[rs + i] + (uint64_t)tp - 1) / (uint64_t)tp;
@@ -785,7 +792,7 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
                           pl.bw[z * Z + z];
       t_sync = fmax(t_sync, sync);
     }
-    t_upd = fmax(t_upd, pl.st_u[((size_t)(rs + i) * G + g) * TP + c.tp]);
+    t_upd = fmax(t_upd, pl.st_u[((size_t)(rs + i) * G + g) * TP + k]);
     lds.t[i] = t;
     lds.dol[i] = (double)(D * tp) * pl.price[g];
     lds.comm[i] = comm;
@@ -971,21 +978,22 @@ __device__ __forceinline__ void eval_direct_s(const DevPlan &pl, const Cand &c, 
                                               const LaneC &lc, float &T, float &C, uint64_t &peak,
                                               uint32_t &mask) {
   const int G = pl.G, Z = pl.Z, MB = pl.MB, DP = pl.DP;
-  const int tpv = pl.tpv[c.tp];
   const int64_t D = pl.dpv[c.dp];
   Acc acc;
 #pragma unroll
   for (int j = 0; j < S; ++j) {
     const int p = c.a[j], g = p % G, z = p / G;
-    const size_t sl = agg_slot(pl, c.shape, c.tp, j);
+    const int tpv = pl.tpv[c.tp[j]];
+    const size_t sl = agg_slot(pl, c.shape, c.tp[j], j);
     const Rec r = make_rec(pl.ta[(sl * G + g) * MB + c.mb], pl.smax[sl], pl.upd[sl * G + g],
-                           pl.price_f[g], lc.p2pf, pl.ibw_f[z * Z + z], sh.n[j], 0u);
+                           pl.price_f[g], lc.p2pf, pl.ibw_f[z * Z + z], sh.n[j], tpv, 0u);
     const uint64_t m = pl.need[(sl * MB + c.mb) * DP + c.dp] + pl.res[g];
     if (m > pl.cap[g]) mask |= 1u;
     peak = m > peak ? m : peak;
-    int64_t stages = sh.n[j];
-    if (S == 3 && (j == 0 || j == 2) && c.a[0] == c.a[2]) stages = sh.n[0] + sh.n[2];
-    if (stages * D * tpv > (int64_t)pl.avail[p]) mask |= 2u;
+    int64_t gpus = (int64_t)sh.n[j] * tpv;  // of one replica on this pool
+    if (S == 3 && (j == 0 || j == 2) && c.a[0] == c.a[2])
+      gpus = (int64_t)sh.n[0] * pl.tpv[c.tp[0]] + (int64_t)sh.n[2] * pl.tpv[c.tp[2]];
+    if (gpus * D > (int64_t)pl.avail[p]) mask |= 2u;
     if (tpv > pl.node[g]) mask |= 8u;
     if (j == 0) {
       acc = acc_begin(r);
@@ -1018,7 +1026,7 @@ __global__ __launch_bounds__(256) void k_eval_direct(DevPlan pl, EvalArgs a) {
       lc.p2pf = pl.p2p_f[c.mb];
       lc.nbm1 = pl.nbm1_f[c.mb * pl.DP + c.dp];
       lc.cd = pl.cd_f[c.dp];
-      lc.dtp = pl.dtp_f[c.tp * pl.DP + c.dp];
+      lc.dph = pl.dph_f[c.dp];
       lc.xb = pl.xb_f[c.mb];
       if (c.s == 1) eval_direct_s<1>(pl, c, sh, lc, T, C, peak, mask);
       else if (c.s == 2) eval_direct_s<2>(pl, c, sh, lc, T, C, peak, mask);
@@ -1037,19 +1045,21 @@ __global__ __launch_bounds__(256) void k_eval_direct(DevPlan pl, EvalArgs a) {
 
 // Range form of sailor_eval_batch.  One workgroup per EvalUnit: the records of the unit's
 // shape for every tp are staged in LDS.  A lane keeps its inner digits (mb, tp, dp, pool 1)
-// while the unit's outer pool digits advance, and consecutive lanes hold consecutive
+// while the unit's outer digits advance, and consecutive lanes hold consecutive
 // candidate indices, so every store instruction writes 64 consecutive elements.
 struct PoolInfo {   // per pool, staged in LDS
   uint64_t res, cap;
+  int32_t avail;
+  uint32_t meta;    // zone | (bit 8 + k: tp k exceeds the node size) (H1)
 };
 
 template <int S>
 __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs &a,
                                                const EvalUnit &u, const ShapeRec &sh,
                                                const Rec *rec, const float4 *pair,
-                                               const uint32_t *qm, const uint32_t *q13,
-                                               const uint64_t *need, const PoolInfo *pinfo,
-                                               const uint32_t *pmeta) {
+                                               const uint32_t *qm, const uint64_t *need,
+                                               const PoolInfo *pinfo, const uint32_t *odec,
+                                               const int32_t *vals) {
   const int ZG = pl.ZG, MB = pl.MB, TP = pl.TP, DP = pl.DP, Z = pl.Z;
   const uint32_t inner = pl.inner;
   const uint64_t last = a.first + a.count;
@@ -1063,30 +1073,28 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
     lc.p2pf = pl.p2p_f[mb];
     lc.nbm1 = pl.nbm1_f[mb * DP + dp];
     lc.cd = pl.cd_f[dp];
-    lc.dtp = pl.dtp_f[tp * DP + dp];
+    lc.dph = pl.dph_f[dp];
     lc.xb = pl.xb_f[mb];
-    const uint32_t tpbit = 1u << (8 + tp);
-    // this lane's slices of the staged tables
-    const Rec *recl = rec + (size_t)tp * ZG * MB + mb;          // + (seg * TP * ZG + pool) * MB
-    const uint64_t *needl = need + (tp * MB + mb) * DP + dp;    // + seg * TP * MB * DP
-    const uint32_t *qml = qm + tp * ZG;                         // + seg * TP * ZG + pool
+    // this lane's slices of the staged tables; segment j with tp index k on pool p:
+    const Rec *recl = rec + mb;                 // [((j * TP + k) * ZG + p) * MB]
+    const uint64_t *needl = need + mb * DP + dp;  // [(j * TP + k) * MB * DP]
     // segment 1 does not change while the outer digits advance
     const int p0 = (int)a1;
-    const Rec r0 = recl[p0 * MB];
+    const Rec r0 = recl[(tp * ZG + p0) * MB];
     const Acc A0 = acc_begin(r0);
     const PoolInfo i0 = pinfo[p0];
-    const uint32_t m0 = pmeta[p0];
-    const uint64_t mem0 = needl[0] + i0.res;
+    const uint64_t mem0 = needl[tp * MB * DP] + i0.res;
     uint32_t mask0 = 0;
     if (mem0 > i0.cap) mask0 |= 1u;
-    if (m0 & tpbit) mask0 |= 8u;
-    const bool q0 = (qml[p0] >> dp) & 1u;
-    const bool q0_13 = S == 3 ? ((q13[tp * ZG + p0] >> dp) & 1u) : true;
-    const int z0 = (int)(m0 & 0xFFu);
+    if (i0.meta & (1u << (8 + tp))) mask0 |= 8u;
+    const bool q0 = (qm[tp * ZG + p0] >> dp) & 1u;
+    const int z0 = (int)(i0.meta & 0xFFu);
+    const int64_t D = vals[dp];  // value lists staged in LDS: [DP] dp, then [TP] tp
+    const int64_t gpus0 = (int64_t)sh.n[0] * vals[DP + tp];
     for (uint32_t o = 0; o < u.o_cnt; ++o) {
       const uint64_t idx = u.idx_lo + (uint64_t)o * inner + in;
       if (idx < a.first || idx >= last) continue;
-      const uint32_t oa = u.o_lo + o;
+      const uint32_t od = odec[o];  // outer digits (uniform)
       float T = kPosInf, C = kPosInf;
       uint64_t peak = 0;
       uint32_t mask = 4u;
@@ -1096,37 +1104,39 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
         Acc acc = A0;
         bool quota_ok = q0;
         if (S >= 2) {
-          const int r2 = (int)(oa % (uint32_t)(ZG - 1));  // uniform
+          const int r2 = (int)(od & 63u);
+          const uint32_t t1 = pl.pst ? ((od >> 6) & 7u) : tp;
           int p1 = p0 + 1 + r2;
           if (p1 >= ZG) p1 -= ZG;
-          const Rec r1 = recl[(TP * ZG + p1) * MB];
+          const Rec r1 = recl[((TP + t1) * ZG + p1) * MB];
           const PoolInfo i1 = pinfo[p1];
-          const uint32_t m1 = pmeta[p1];
-          const int z1 = (int)(m1 & 0xFFu);
-          const uint64_t mem1 = needl[TP * MB * DP] + i1.res;
+          const int z1 = (int)(i1.meta & 0xFFu);
+          const uint64_t mem1 = needl[(TP + t1) * MB * DP] + i1.res;
           if (mem1 > i1.cap) mask |= 1u;
-          if (m1 & tpbit) mask |= 8u;
+          if (i1.meta & (1u << (8 + t1))) mask |= 8u;
           peak = mem1 > peak ? mem1 : peak;
-          quota_ok = quota_ok && ((qml[TP * ZG + p1] >> dp) & 1u);
+          const bool q1 = (qm[(TP + t1) * ZG + p1] >> dp) & 1u;
+          quota_ok = quota_ok && q1;
           const float4 pr = pair[z0 * Z + z1];
           acc = acc_cross(acc, r1, lc.p2pf * pr.x, lc.p2pf * pr.y, pr.z, single0, true);
           if (S == 3) {
-            const int r3 = (int)(oa / (uint32_t)(ZG - 1));  // uniform
+            const int r3 = (int)((od >> 9) & 63u);
+            const uint32_t t2 = pl.pst ? (od >> 15) : tp;
             int p2 = p1 + 1 + r3;
             if (p2 >= ZG) p2 -= ZG;
-            const Rec r2r = recl[(2 * TP * ZG + p2) * MB];
+            const Rec r2r = recl[((2 * TP + t2) * ZG + p2) * MB];
             const PoolInfo i2 = pinfo[p2];
-            const uint32_t m2 = pmeta[p2];
-            const uint64_t mem2 = needl[2 * TP * MB * DP] + i2.res;
+            const uint64_t mem2 = needl[(2 * TP + t2) * MB * DP] + i2.res;
             if (mem2 > i2.cap) mask |= 1u;
-            if (m2 & tpbit) mask |= 8u;
+            if (i2.meta & (1u << (8 + t2))) mask |= 8u;
             peak = mem2 > peak ? mem2 : peak;
             if (p2 == p0) {  // segments 1 and 3 share one pool's quota
-              quota_ok = q0_13 && ((qml[TP * ZG + p1] >> dp) & 1u);
+              const int64_t gpus = gpus0 + (int64_t)sh.n[2] * vals[DP + t2];
+              quota_ok = q1 && gpus * D <= (int64_t)i0.avail;
             } else {
-              quota_ok = quota_ok && ((qml[2 * TP * ZG + p2] >> dp) & 1u);
+              quota_ok = quota_ok && ((qm[(2 * TP + t2) * ZG + p2] >> dp) & 1u);
             }
-            const float4 pr2 = pair[z1 * Z + (int)(m2 & 0xFFu)];
+            const float4 pr2 = pair[z1 * Z + (int)(i2.meta & 0xFFu)];
             acc = acc_cross(acc, r2r, lc.p2pf * pr2.x, lc.p2pf * pr2.y, pr2.z, single1, false);
           }
         }
@@ -1157,27 +1167,40 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
   PoolInfo *pinfo = reinterpret_cast<PoolInfo *>(pair + Z * Z);          // [ZG]
   uint64_t *need = reinterpret_cast<uint64_t *>(pinfo + ZG);             // [3][TP][MB][DP]
   uint32_t *qm = reinterpret_cast<uint32_t *>(need + 3 * TP * MB * DP);  // [3][TP][ZG]
-  uint32_t *q13 = qm + 3 * TP * ZG;                                      // [TP][ZG]
-  uint32_t *pmeta = q13 + TP * ZG;  // [ZG] zone | (bit 8 + k: tp k exceeds the node size) (H1)
-  const int t = threadIdx.x;
+  uint32_t *odec = qm + 3 * TP * ZG;  // [o_cnt] the outer digits of the unit, unpacked:
+  int32_t *vals = reinterpret_cast<int32_t *>(odec + kEvalUnitMaxOuter);  // [DP] dp, [TP] tp
+  const int t = threadIdx.x;          // r2 | tp2 << 6 | r3 << 9 | tp3 << 15
+  if (t < DP) vals[t] = pl.dpv[t];
+  else if (t < DP + TP) vals[t] = pl.tpv[t - DP];
+  __syncthreads();
+  if (S >= 2)
+    for (uint32_t o = t; o < u.o_cnt; o += blockDim.x) {
+      uint32_t oa = u.o_lo + o;
+      uint32_t d = oa % (uint32_t)(ZG - 1);
+      oa /= (uint32_t)(ZG - 1);
+      if (pl.pst) { d |= (oa % (uint32_t)TP) << 6; oa /= (uint32_t)TP; }
+      if (S == 3) {
+        d |= (oa % (uint32_t)(ZG - 1)) << 9;
+        oa /= (uint32_t)(ZG - 1);
+        if (pl.pst) d |= oa << 15;
+      }
+      odec[o] = d;
+    }
+  else
+    for (uint32_t o = t; o < u.o_cnt; o += blockDim.x) odec[o] = 0;
   for (int i = t; i < S * TP * ZG; i += blockDim.x) {
     const int p = i % ZG, k = (i / ZG) % TP, seg = i / (ZG * TP);
     const int n = seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]);
-    qm[i] = pl.qtab[((size_t)n * TP + k) * ZG + p];
+    qm[i] = pl.qw[(size_t)(n * vals[DP + k]) * ZG + p];
   }
-  if (S == 3)
-    for (int i = t; i < TP * ZG; i += blockDim.x)
-      q13[i] = pl.qtab[(size_t)(sh.n[0] + sh.n[2]) * TP * ZG + i];
   for (int p = t; p < ZG; p += blockDim.x) {
     const int g = p % G;
     PoolInfo pi;
     pi.res = pl.res[g];
     pi.cap = pl.cap[g];
+    pi.avail = pl.avail[p];
+    pi.meta = (uint32_t)(p / G) | (pl.h1m[p] << 8);
     pinfo[p] = pi;
-    uint32_t m = (uint32_t)(p / G);
-    for (int k = 0; k < TP; ++k)
-      if (pl.tpv[k] > pl.node[g]) m |= 1u << (8 + k);
-    pmeta[p] = m;
   }
   for (int i = t; i < Z * Z; i += blockDim.x) {
     const int za = i / Z, zb = i % Z;
@@ -1193,12 +1216,12 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
     const size_t sl = agg_slot(pl, u.shape, k, seg);
     rec[i] = make_rec(pl.ta[(sl * G + g) * MB + mb], pl.smax[sl], pl.upd[sl * G + g],
                       pl.price_f[g], pl.p2p_f[mb], pl.ibw_f[z * Z + z],
-                      seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]), 0u);
+                      seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]), vals[DP + k], 0u);
   }
   __syncthreads();
-  if (S == 1) eval_rows_body<1>(pl, a, u, sh, rec, pair, qm, q13, need, pinfo, pmeta);
-  else if (S == 2) eval_rows_body<2>(pl, a, u, sh, rec, pair, qm, q13, need, pinfo, pmeta);
-  else eval_rows_body<3>(pl, a, u, sh, rec, pair, qm, q13, need, pinfo, pmeta);
+  if (S == 1) eval_rows_body<1>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
+  else if (S == 2) eval_rows_body<2>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
+  else eval_rows_body<3>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
 }
 
 }  // namespace sailor

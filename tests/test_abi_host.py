@@ -2,6 +2,7 @@
 and rejects malformed problems before touching a device."""
 import ctypes as C
 import os
+import subprocess
 import re
 from dataclasses import replace
 
@@ -29,11 +30,31 @@ def test_exports_every_declared_entry_point(lib):
         assert getattr(lib, name) is not None
 
 
-def test_result_struct_layout_matches_header():
-    assert C.sizeof(binding.sailor_result) == 96
-    assert binding.sailor_result.mask.offset == 32
-    assert binding.sailor_result.pool.offset == 84
-    assert C.sizeof(binding.sailor_constraint) == 16
+def test_struct_layouts_match_the_header(tmp_path):
+    """sizeof / offsetof as a C compiler sees the header against the ctypes mirrors."""
+    fields = {"sailor_problem": ["n_layers", "per_segment_tp", "global_batch", "mb_values",
+                                 "embed_params", "grad_bytes_per_param", "t_fwd", "egress_per_byte"],
+              "sailor_result": ["index", "iter_time_s", "mask", "pp", "mb_index", "cut", "pool",
+                                "seg_tp", "seg_tp_index"],
+              "sailor_constraint": ["bound", "has_bound"]}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "sailor.h"', 'int main(void) {']
+    for st, fl in fields.items():
+        lines.append(f'printf("{st} %zu\\n", sizeof({st}));')
+        for f in fl:
+            lines.append(f'printf("{st}.{f} %zu\\n", offsetof({st}, {f}));')
+    lines += ['return 0; }']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = dict(l.split() for l in subprocess.run([str(exe)], check=True, capture_output=True,
+                                                 text=True).stdout.splitlines())
+    for st, fl in fields.items():
+        cls = getattr(binding, st)
+        assert C.sizeof(cls) == int(out[st])
+        for f in fl:
+            assert getattr(cls, f).offset == int(out[f"{st}.{f}"]), (st, f)
+    assert C.sizeof(binding.sailor_result) == 120 and binding.sailor_result.mask.offset == 32
 
 
 def _create(lib, prob):

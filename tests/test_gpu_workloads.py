@@ -176,3 +176,53 @@ def test_fourth_workload_max_throughput_under_a_budget(cfg4, torch_cuda):
     check_result(plan.best_plan(objective=MAX_THROUGHPUT, bound=budget, stream=stream), best, orc)
     check_topk(plan.topk(64, objective=MAX_THROUGHPUT, bound=budget, stream=stream), top,
                MAX_THROUGHPUT)
+
+
+# ------------------------------------------------------------------ a TP digit per segment
+
+@pytest.mark.parametrize("objective", [MAX_THROUGHPUT, MIN_COST])
+def test_third_workload_with_per_segment_tp(torch_cuda, objective):
+    # 9.4e7 candidates; the oracle still covers the whole space
+    prob = W.config3().with_per_segment_tp()
+    plan, orc = _plan(prob), Oracle(prob)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        assert plan.num_candidates() == orc.num_candidates == 94037760
+        best, top = oracle_best_and_topk(orc, 64, objective)
+        check_result(plan.best_plan(objective=objective, stream=stream), best, orc)
+        check_topk(plan.topk(64, objective=objective, stream=stream), top, objective)
+        base = Oracle(W.config3()).best(objective=objective, n_threads=THREADS)
+        key = (lambda e: e.iter_time) if objective == MAX_THROUGHPUT else (lambda e: e.cost)
+        assert key(best) <= key(base) * (1 + 1e-12)  # a superset of the shared-TP plans
+        if objective == MAX_THROUGHPUT:
+            bound = 1.5 * Oracle(W.config3()).best(objective=MIN_COST, n_threads=THREADS).cost
+        else:
+            bound = 0.6 / Oracle(W.config3()).best(objective=MAX_THROUGHPUT, n_threads=THREADS).iter_time
+        best_b, top_b = oracle_best_and_topk(orc, 64, objective, bound)
+        check_result(plan.best_plan(objective=objective, bound=bound, stream=stream), best_b, orc)
+        check_topk(plan.topk(64, objective=objective, bound=bound, stream=stream), top_b, objective)
+    finally:
+        plan.destroy()
+
+
+def test_fourth_workload_with_per_segment_tp(torch_cuda):
+    # 9.2e8 candidates: sampled outputs, one full-space selection
+    prob = W.config4().with_per_segment_tp()
+    plan, orc = _plan(prob), Oracle(prob)
+    torch, stream = torch_cuda, torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        n = orc.num_candidates
+        assert plan.num_candidates() == n == 915206400
+        rng = np.random.default_rng(44)
+        idx = np.concatenate([rng.integers(0, n, 1_000_000), [0, n - 1]]).astype(np.uint64)
+        want = orc.eval_batch(indices=idx, n_threads=THREADS)
+        assert_eval_parity(gpu_eval(torch, plan, 0, len(idx), indices=idx), want)
+        # a ragged range that crosses block and shape boundaries, through the range form
+        first, count = n // 2 - 1_234_567, 4_000_003
+        assert_eval_parity(gpu_eval(torch, plan, first, count),
+                           orc.eval_batch(first, count, n_threads=THREADS))
+        best, top = oracle_best_and_topk(orc, 64, MAX_THROUGHPUT)
+        check_result(plan.best_plan(objective=MAX_THROUGHPUT, stream=stream), best, orc)
+        check_topk(plan.topk(64, objective=MAX_THROUGHPUT, stream=stream), top, MAX_THROUGHPUT)
+    finally:
+        plan.destroy()
