@@ -289,9 +289,10 @@ sailor_status build_space(const sailor_problem *p, sailor_plan *pl, std::vector<
             u.s = (uint8_t)sh.s;
             u.o_lo = (uint16_t)lo;
             u.o_cnt = (uint16_t)(hi - lo);
-            u.off = pst ? inner * (uint64_t)(ZG - 1) * (uint64_t)t1 +
-                              pl->dev.stride3 * (uint64_t)(ZG - 1) * (uint64_t)t2
-                        : 0u;
+            for (int j = 0; j < 3; ++j) u.n[j] = sh.n[j];
+            u.base = sh.base + (pst ? inner * (uint64_t)(ZG - 1) * (uint64_t)t1 +
+                                          pl->dev.stride3 * (uint64_t)(ZG - 1) * (uint64_t)t2
+                                    : 0u);
             pl->units.push_back(u);
           }
   }
@@ -313,7 +314,8 @@ sailor_status build_space(const sailor_problem *p, sailor_plan *pl, std::vector<
       pl->eunits.push_back(e);
     }
   }
-  // Largest units first, so that the small ones fill the tail of the launch.
+  // Largest units first, so that the small ones fill the tail of the launch (the order is
+  // refined by a timed pass once the tables are on the device).
   auto unit_cost = [&](const UnitRec &u) {  // candidates of the unit
     return innerp * (uint64_t)u.o_cnt * (u.s == 3 ? (uint64_t)(ZG - 1) : 1u);
   };
@@ -733,6 +735,36 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   k_shape_agg<<<(unsigned)NS, 256>>>(d);
   CREATE_TRY(hipGetLastError());
   CREATE_TRY(hipDeviceSynchronize());
+  {
+    // Units of equal size differ widely in cost, because invalid plans are pruned early.
+    // One unconstrained scan records how long each unit takes; the units are then launched
+    // longest first, which also deals them evenly to the hardware's dispatch queues.
+    const size_t NU = pl->units.size();
+    float *d_cost = nullptr;
+    CREATE_TRY(ar.alloc(&d_cost, NU));
+    ScanArgs ca{};
+    ca.umin_s = pl->umin_s;
+    ca.umin_l = pl->umin_l;
+    ca.counters = pl->counters;
+    ca.lim_s = ca.lim_l = kPosInf;
+    ca.ucost = d_cost;
+    k_units<MODE_SCAN, 0, false><<<(unsigned)NU, pl->unit_threads, pl->lds_bytes>>>(d, ca);
+    CREATE_TRY(hipGetLastError());
+    std::vector<float> cost(NU);
+    CREATE_TRY(hipMemcpy(cost.data(), d_cost, NU * sizeof(float), hipMemcpyDeviceToHost));
+    std::vector<uint32_t> order(NU);
+    for (size_t i = 0; i < NU; ++i) order[i] = (uint32_t)i;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](uint32_t x, uint32_t y) { return cost[x] > cost[y]; });
+    std::vector<UnitRec> sorted(NU);
+    for (size_t i = 0; i < NU; ++i) sorted[i] = pl->units[order[i]];
+    pl->units.swap(sorted);
+    CREATE_TRY(hipMemcpy(const_cast<UnitRec *>(d.units), pl->units.data(), NU * sizeof(UnitRec),
+                         hipMemcpyHostToDevice));
+    k_init_counters<<<1, 64>>>(pl->counters, 2 * CNT_COUNT);
+    CREATE_TRY(hipDeviceSynchronize());
+    ar.free_one(d_cost);
+  }
 #undef CREATE_TRY
   *out = pl;
   return SAILOR_OK;

@@ -42,12 +42,14 @@ struct BlockRec {       // all candidates with one (pp index, segment count)
 };
 
 struct UnitRec {        // work of one workgroup of the scan: one shape, one tp per segment
-  uint32_t shape;       // (all equal unless segments carry their own tp digit), a range
-  uint8_t tp[3], s;     // [o_lo, o_lo + o_cnt) of segment 2's pool
-  uint16_t o_lo, o_cnt;
-  uint32_t pad;
-  uint64_t off;         // index offset of the unit's tp digits of segments 2 and 3
+  uint64_t base;        // (all equal unless segments carry their own tp digit), a range
+  uint32_t shape;       // [o_lo, o_lo + o_cnt) of segment 2's pool.  base = first index of
+  uint8_t tp[3], s;     // the shape + the offset of the unit's tp digits of segments 2, 3;
+  uint16_t o_lo, o_cnt; // n = stages per segment (copied from the shape, so that a
+  uint16_t n[3], pad;   // workgroup needs one record to start)
+  uint32_t pad2;
 };
+static_assert(sizeof(UnitRec) == 32, "one unit record per 32 bytes");
 
 struct EvalUnit {       // work of one workgroup of the range evaluation: one shape, all tp,
   uint64_t idx_lo;      // a contiguous index range = a range of the outer pool digits

@@ -316,6 +316,7 @@ struct ScanArgs {
   float lim_s, lim_l;       // constraint limits (strict, loose) on cost or on time
   SurvRec *surv;
   uint32_t surv_cap;
+  float *ucost;             // SCAN, optional: ticks of the 100 MHz clock each unit took
 };
 
 enum Counter { CNT_SURV = 0, CNT_REF = 1, CNT_FEAS = 2, CNT_GMIN = 3, CNT_TAU0 = 4, CNT_TAU1 = 5,
@@ -422,7 +423,7 @@ __device__ __forceinline__ bool wave_any(bool p) { return __builtin_amdgcn_ballo
 // depends on the remaining segments.
 template <int S, int MODE, int OBJ, bool HASB>
 __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, const UnitRec &u,
-                                          const ShapeRec &sh, const Rec *rec, const float4 *pair,
+                                          const Rec *rec, const float4 *pair,
                                           const uint32_t *q13, float tau, int sub, int n_sub,
                                           float &ms, float &ml) {
   // the chunks of the lane space are dealt round-robin to the waves of the n_sub
@@ -431,9 +432,9 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
   const int lane = threadIdx.x & 63;
   const int wave = (int)(threadIdx.x >> 6) + (int)(blockDim.x >> 6) * sub;
   const int nwave = (int)(blockDim.x >> 6) * n_sub;
-  const bool single0 = sh.n[0] == 1, single1 = sh.n[1] == 1;
+  const bool single0 = u.n[0] == 1, single1 = u.n[1] == 1;
   const int tp = u.tp[0];
-  const uint64_t ubase = sh.base + u.off;
+  const uint64_t ubase = u.base;
   if (S <= 2) {
     const int nin = MB * DP * ZG;
     for (int e0 = wave * 64; e0 < nin; e0 += nwave * 64) {
@@ -522,7 +523,9 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
 }
 
 // One workgroup per unit: stage the unit's segment records in LDS, then every lane walks
-// its (mb, dp, pool 1) triple over the unit's outer pool digits.
+// its (mb, dp, pool 1) triple over the unit's outer pool digits.  Everything the staging
+// needs comes from the unit record and tables that do not depend on one another, so all of
+// its global loads are in flight together and one barrier ends it.
 template <int MODE, int OBJ, bool HASB>
 __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs a) {
   extern __shared__ uint4 lds_raw[];
@@ -530,6 +533,7 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
   const uint32_t n_sub = MODE == MODE_COLLECT ? a.n_sub : 1u;
   const uint32_t uidx = MODE == MODE_COLLECT ? blockIdx.x / n_sub : blockIdx.x;
   const int sub = MODE == MODE_COLLECT ? (int)(blockIdx.x % n_sub) : 0;
+  const unsigned long long t_begin = (MODE == MODE_SCAN && a.ucost) ? wall_clock64() : 0ull;
   const UnitRec u = pl.units[uidx];
   float tau = kPosInf;
   if (MODE == MODE_COLLECT) {
@@ -537,32 +541,37 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
     const float um = a.umin_l[uidx];
     if (!(um < kPosInf && um <= tau)) return;  // uniform over the workgroup
   }
-  const ShapeRec sh = pl.shapes[u.shape];
-  const int ZG = pl.ZG, G = pl.G, MB = pl.MB, Z = pl.Z, S = sh.s;
+  const int ZG = pl.ZG, G = pl.G, MB = pl.MB, Z = pl.Z, S = u.s;
   Rec *rec = reinterpret_cast<Rec *>(lds_raw);                      // [S][ZG][MB]
   float4 *pair = reinterpret_cast<float4 *>(rec + 3 * ZG * MB);     // [Z][Z]
-  uint32_t *qm = reinterpret_cast<uint32_t *>(pair + Z * Z);        // [3][ZG]
-  uint32_t *q13 = qm + 3 * ZG;                                      // [ZG]
+  uint32_t *q13 = reinterpret_cast<uint32_t *>(pair + Z * Z);       // [ZG]
   __shared__ float red[2][kMaxUnitThreads / 64];
+  __shared__ uint32_t s_any[kMaxUnitThreads / 64];  // per wave, bit j: a pool can host segment j
   const int t = threadIdx.x;
 
-  const int n0 = sh.n[0], n1 = sh.n[1], n2 = sh.n[2];
+  const int n0 = u.n[0], n1 = u.n[1], n2 = u.n[2];
   const int k0 = u.tp[0], k1 = u.tp[1], k2 = u.tp[2];            // tp index of each segment
   const int tv0 = pl.tpv[k0], tv1 = pl.tpv[k1], tv2 = pl.tpv[k2];
   const int w0 = n0 * tv0, w1 = n1 * tv1, w2 = n2 * tv2;        // GPUs of one replica
-  __shared__ uint32_t s_any;  // bit j: some pool can host segment j
-  if (t == 0) s_any = 0;
-  __syncthreads();
   uint32_t any_here = 0;
-  for (int i = t; i < S * ZG; i += blockDim.x) {
-    const int seg = i >= 2 * ZG ? 2 : (i >= ZG ? 1 : 0), p = i - seg * ZG;
-    const int w = seg == 0 ? w0 : (seg == 1 ? w1 : w2), k = seg == 0 ? k0 : (seg == 1 ? k1 : k2);
-    uint32_t b = pl.qw[w * ZG + p];
-    if ((pl.h1m[p] >> k) & 1u) b = 0;  // H1: tensor parallelism stays inside a node
-    qm[i] = b;
-    // a segment nobody can host rules the whole unit out
+  for (int i = t; i < S * ZG * MB; i += blockDim.x) {
+    const uint32_t sp = fast_div((uint32_t)i, pl.mg_mb), mb = (uint32_t)i - sp * (uint32_t)MB;
+    const int seg = sp >= 2u * ZG ? 2 : (sp >= (uint32_t)ZG ? 1 : 0), p = (int)sp - seg * ZG;
+    const int z = (int)fast_div((uint32_t)p, pl.mg_g), g = p - z * G;
+    const int k = seg == 0 ? k0 : (seg == 1 ? k1 : k2);
+    const int w = seg == 0 ? w0 : (seg == 1 ? w1 : w2);
+    const uint32_t sl = (u.shape * (uint32_t)pl.TP + (uint32_t)k) * 3u + (uint32_t)seg;
+    const uint32_t gi = (sl * (uint32_t)G + (uint32_t)g) * (uint32_t)MB + mb;
+    const float4 ta = pl.ta[gi];
+    uint32_t q = pl.qw[w * ZG + p];
+    if ((pl.h1m[p] >> k) & 1u) q = 0;  // H1: tensor parallelism stays inside a node
+    const uint32_t bits = pl.memok[gi] & q & pl.divis[mb];
+    rec[i] = make_rec(ta, pl.smax[sl], pl.upd[sl * G + g], pl.price_f[g], pl.p2p_f[mb],
+                      pl.ibw_f[z * Z + z], seg == 0 ? n0 : (seg == 1 ? n1 : n2),
+                      seg == 0 ? tv0 : (seg == 1 ? tv1 : tv2), bits);
+    // a segment that no pool can host validly rules the whole unit out
     const bool counts = seg != 1 || (p >= (int)u.o_lo && p < (int)(u.o_lo + u.o_cnt));
-    if (b != 0 && counts) any_here |= 1u << seg;
+    if (bits != 0 && counts) any_here |= 1u << seg;
   }
   if (S == 3)
     for (int p = t; p < ZG; p += blockDim.x) q13[p] = pl.qw[(w0 + w2) * ZG + p];
@@ -570,34 +579,29 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
     const int za = i / Z, zb = i % Z;
     pair[i] = make_float4(pl.ibw_f[za * Z + zb], pl.ibw_f[zb * Z + za], pl.egs_f[i], 0.f);
   }
-  if (any_here) atomicOr(&s_any, any_here);
-  __syncthreads();  // (also orders the tables above before the records below)
-  if (s_any != (1u << S) - 1u) {
+  {
+    uint32_t wv = 0;
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+      if (__builtin_amdgcn_ballot_w64((any_here >> j) & 1u) != 0) wv |= 1u << j;
+    if ((t & 63) == 0) s_any[t >> 6] = wv;
+  }
+  __syncthreads();
+  uint32_t any_all = 0;
+  for (int w = 0; w < (int)(blockDim.x >> 6); ++w) any_all |= s_any[w];
+  if (any_all != (1u << S) - 1u) {  // uniform over the workgroup
     if (MODE == MODE_SCAN && t == 0) {
       a.umin_s[uidx] = kPosInf;
       a.umin_l[uidx] = kPosInf;
+      if (a.ucost) a.ucost[uidx] = (float)(wall_clock64() - t_begin);
     }
     return;
   }
-  for (int i = t; i < S * ZG * MB; i += blockDim.x) {
-    const uint32_t sp = fast_div((uint32_t)i, pl.mg_mb), mb = (uint32_t)i - sp * (uint32_t)MB;
-    const int seg = sp >= 2u * ZG ? 2 : (sp >= (uint32_t)ZG ? 1 : 0), p = (int)sp - seg * ZG;
-    const int z = (int)fast_div((uint32_t)p, pl.mg_g), g = p - z * G;
-    const int k = seg == 0 ? k0 : (seg == 1 ? k1 : k2);
-    const uint32_t sl = (u.shape * (uint32_t)pl.TP + (uint32_t)k) * 3u + (uint32_t)seg;
-    const uint32_t gi = (sl * (uint32_t)G + (uint32_t)g) * (uint32_t)MB + mb;
-    const float4 ta = pl.ta[gi];
-    const uint32_t bits = pl.memok[gi] & qm[seg * ZG + p] & pl.divis[mb];
-    rec[i] = make_rec(ta, pl.smax[sl], pl.upd[sl * G + g], pl.price_f[g], pl.p2p_f[mb],
-                      pl.ibw_f[z * Z + z], seg == 0 ? n0 : (seg == 1 ? n1 : n2),
-                      seg == 0 ? tv0 : (seg == 1 ? tv1 : tv2), bits);
-  }
-  __syncthreads();
 
   float ms = kPosInf, ml = kPosInf;
-  if (S == 1) unit_body<1, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, tau, sub, (int)n_sub, ms, ml);
-  else if (S == 2) unit_body<2, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, tau, sub, (int)n_sub, ms, ml);
-  else unit_body<3, MODE, OBJ, HASB>(pl, a, u, sh, rec, pair, q13, tau, sub, (int)n_sub, ms, ml);
+  if (S == 1) unit_body<1, MODE, OBJ, HASB>(pl, a, u, rec, pair, q13, tau, sub, (int)n_sub, ms, ml);
+  else if (S == 2) unit_body<2, MODE, OBJ, HASB>(pl, a, u, rec, pair, q13, tau, sub, (int)n_sub, ms, ml);
+  else unit_body<3, MODE, OBJ, HASB>(pl, a, u, rec, pair, q13, tau, sub, (int)n_sub, ms, ml);
 
   if (MODE == MODE_SCAN) {
     if (!HASB) ml = ms;
@@ -617,6 +621,7 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
       const uint32_t seen = __hip_atomic_load(&a.counters[CNT_GMIN], __ATOMIC_RELAXED,
                                               __HIP_MEMORY_SCOPE_AGENT);
       if (__float_as_uint(ms) < seen) atomicMin(&a.counters[CNT_GMIN], __float_as_uint(ms));
+      if (a.ucost) a.ucost[uidx] = (float)(wall_clock64() - t_begin);
     }
   }
 }
