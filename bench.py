@@ -126,6 +126,7 @@ def main() -> int:
     scan_ms /= args.steps
     assert n_found == K, n_found
     top1_index = int(buf[0].index)
+    counts = plan.last_counts()
 
     # device time of all kernels of a step (events around the whole call), outside the
     # timed region
@@ -224,7 +225,7 @@ def main() -> int:
                   "eval_batch_candidates_per_s": n / (eval_ms * 1e-3),
                   "eval_batch_output_GBps": 20.0 * n / (eval_ms * 1e-3) / 1e9,
                   "plan_create_ms": create_ms, "replan_stream": replan,
-                  "per_segment_tp": segtp, "best_index": best.index,
+                  "per_segment_tp": segtp, "survivors_refined_valid": list(counts), "best_index": best.index,
                   "top1_index": top1_index},
     }
     if not args.no_cpu_baseline:

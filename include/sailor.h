@@ -219,6 +219,14 @@ sailor_status sailor_plan_set_timing(sailor_plan *plan, int32_t mode);
  * SAILOR_EINVAL if the last call recorded nothing. */
 sailor_status sailor_plan_last_timing(sailor_plan *plan, float *total_ms, float *kernel_ms);
 
+/* Sizes of the intermediate lists of the last successful sailor_best_plan / sailor_topk
+ * (the selection of Sec. 4.2 runs as fp32 scan -> survivors -> fp64 re-evaluation):
+ * candidates kept by the fp32 threshold, candidates re-evaluated in fp64, and how many of
+ * those were valid.  Host pointers, any may be NULL.  SAILOR_EINVAL before the first
+ * successful selection. */
+sailor_status sailor_plan_last_counts(const sailor_plan *plan, uint32_t *survivors,
+                                      uint32_t *refined, uint32_t *feasible);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,7 +27,7 @@ MAX_K = 4096
 EXPORTS = ["sailor_plan_create", "sailor_plan_destroy", "sailor_plan_set_avail",
            "sailor_plan_num_candidates", "sailor_plan_decode", "sailor_eval_batch",
            "sailor_best_plan", "sailor_topk", "sailor_plan_set_scratch", "sailor_plan_set_timing",
-           "sailor_plan_last_timing"]
+           "sailor_plan_last_timing", "sailor_plan_last_counts"]
 
 
 class SailorError(RuntimeError):
@@ -129,6 +129,8 @@ def load_library() -> C.CDLL:
     lib.sailor_plan_set_scratch.argtypes = [P, C.c_uint32, C.c_uint32]
     lib.sailor_plan_set_timing.argtypes = [P, C.c_int32]
     lib.sailor_plan_last_timing.argtypes = [P, C.POINTER(C.c_float), C.POINTER(C.c_float)]
+    lib.sailor_plan_last_counts.argtypes = [P, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
+                                            C.POINTER(C.c_uint32)]
     for name in EXPORTS:
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -295,3 +297,12 @@ class Plan:
         if rc != SAILOR_OK:
             raise SailorError(rc, "sailor_plan_last_timing")
         return t.value, s.value
+
+    def last_counts(self) -> Tuple[int, int, int]:
+        """(survivors of the fp32 threshold, candidates re-evaluated in fp64, valid ones
+        among them) of the last successful best_plan / topk."""
+        a, b, c = C.c_uint32(), C.c_uint32(), C.c_uint32()
+        rc = self._lib.sailor_plan_last_counts(self._h, C.byref(a), C.byref(b), C.byref(c))
+        if rc != SAILOR_OK:
+            raise SailorError(rc, "sailor_plan_last_counts")
+        return a.value, b.value, c.value

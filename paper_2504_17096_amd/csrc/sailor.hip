@@ -23,6 +23,8 @@ constexpr uint32_t kDefaultRefCap = 1u << 18;
 // enough to leave about ten workgroups per compute unit
 constexpr uint64_t kUnitTargetMin = 4096, kUnitTargetMax = 65536, kUnitsWanted = 2560;
 constexpr uint32_t kCollectSub = 4;      // workgroups that share one unit in the collect pass
+constexpr uint32_t kListSub = 8;         // the same when the pass walks a list of units,
+constexpr uint32_t kListUnits = 256;     // and the units it visits per round
 constexpr uint32_t kEvalUnitTarget = 16384;  // candidates per workgroup of the range evaluation
 constexpr unsigned kEvalRowsThreads = 512;
 constexpr size_t kEvalRowsMaxLds = 64 * 1024;  // above this the range form evaluates lane by lane
@@ -83,6 +85,8 @@ struct sailor_plan {
   int device = 0;
   size_t lds_bytes = 0;
   unsigned unit_threads = 256;
+  ResultHeader last_hdr{};         // of the last successful selection
+  bool have_hdr = false;
   int32_t *d_avail = nullptr;
   int32_t *h_avail = nullptr;      // pinned staging of the availability table
   bool avail_dirty = false;        // h_avail is newer than the device copy
@@ -91,6 +95,7 @@ struct sailor_plan {
   // scratch of the selection pipeline
   float *umin_s = nullptr, *umin_l = nullptr;
   uint32_t *counters = nullptr;
+  uint32_t *ulist = nullptr;   // units the collect pass has to visit
   SurvRec *surv = nullptr;
   RefRec *ref = nullptr;
   uint32_t surv_cap = kDefaultSurvCap, ref_cap = kDefaultRefCap;
@@ -431,7 +436,10 @@ void launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, hipEven
 template <int MODE>
 void launch_units(sailor_plan *pl, sailor_objective obj, int has_bound, const ScanArgs &a,
                   hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
-  const dim3 grid((unsigned)pl->units.size() * (MODE == MODE_COLLECT ? kCollectSub : 1u)),
+  const unsigned n_units = (unsigned)pl->units.size();
+  const dim3 grid(MODE == MODE_SCAN ? n_units
+                  : a.ulist         ? std::min(n_units, kListUnits) * a.n_sub
+                                    : n_units * a.n_sub),
       block(pl->unit_threads);
   const size_t lds = pl->lds_bytes;
   if (obj == SAILOR_MAX_THROUGHPUT) {
@@ -489,7 +497,8 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
     if (!best) {
       // the exact k-th smallest fp32 key among the survivors, then only its neighbourhood
       k_select_kth<<<1, 1024, 0, st>>>(&pl->surv[0].key, (int)(sizeof(SurvRec) / 4),
-                                       cnt + CNT_SURV, pl->surv_cap, k, cnt + CNT_TAU1);
+                                       cnt + CNT_SURV, pl->surv_cap, k, cnt + CNT_TAU1, nullptr,
+                                       0u, 0.f, nullptr, nullptr);
       ra.tau_src = cnt + CNT_TAU1;
     }
     k_refine<<<256, kRefineWaves * 64, 0, st>>>(pl->dev, ra);
@@ -515,9 +524,13 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
     sa.band = (float)(1.0 + kTieTol) + 3.0f * kEvalEps;
   } else {
     // an upper bound of the k-th smallest key: the k-th smallest unit minimum
-    k_select_kth<<<1, 1024, 0, st>>>(pl->umin_s, 1, nullptr, n_units, k, cnt + CNT_TAU0);
-    sa.tau_src = cnt + CNT_TAU0;
+    // (the same kernel lists the units whose loose minimum lies under it)
     sa.band = 1.0f + 3.0f * kEvalEps;
+    k_select_kth<<<1, 1024, 0, st>>>(pl->umin_s, 1, nullptr, n_units, k, cnt + CNT_TAU0,
+                                     pl->umin_l, n_units, sa.band, pl->ulist, cnt + CNT_NLIST);
+    sa.tau_src = cnt + CNT_TAU0;
+    sa.ulist = pl->ulist;
+    sa.n_sub = kListSub;
   }
   rc = run_tail(hdr_out);
   if (rc != SAILOR_OK) return rc;
@@ -532,6 +545,8 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
     if (!(gmin < kPosInf)) return SAILOR_ENOMEM;  // nothing strictly valid to anchor on
     sa.use_tau_host = 1;
     sa.count_only = 1;
+    sa.ulist = nullptr;  // the list belongs to the first threshold
+    sa.n_sub = kCollectSub;
     auto count_at = [&](float tau, uint32_t *n_loose, uint32_t *n_strict) -> sailor_status {
       k_zero_counters<<<1, 64, 0, st>>>(cnt, (1u << CNT_NLOOSE) | (1u << CNT_NSTRICT));
       sa.tau_host = tau;
@@ -575,6 +590,7 @@ sailor_status run_selection(sailor_plan *pl, sailor_objective obj, const sailor_
                             uint32_t k, hipStream_t st, ResultHeader *hdr_out) {
   const sailor_status rc = run_selection_impl(pl, obj, con, k, st, hdr_out);
   if (rc == SAILOR_EDEVICE) pl->counters_dirty = true;
+  if (rc == SAILOR_OK) { pl->last_hdr = *hdr_out; pl->have_hdr = true; }
   return rc;
 }
 
@@ -717,6 +733,7 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(ar.alloc(&pl->umin_s, pl->units.size()));
   CREATE_TRY(ar.alloc(&pl->umin_l, pl->units.size()));
   CREATE_TRY(ar.alloc(&pl->counters, (size_t)2 * CNT_COUNT));
+  CREATE_TRY(ar.alloc(&pl->ulist, pl->units.size()));
   CREATE_TRY(ar.alloc(&pl->surv, (size_t)pl->surv_cap));
   CREATE_TRY(ar.alloc(&pl->ref, (size_t)pl->ref_cap));
   const size_t res_bytes = sizeof(ResultHeader) + 8 + (size_t)SAILOR_MAX_K * sizeof(RefRec);
@@ -736,10 +753,13 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(hipGetLastError());
   CREATE_TRY(hipDeviceSynchronize());
   {
-    // Units of equal size differ widely in cost, because invalid plans are pruned early.
-    // One unconstrained scan records how long each unit takes; the units are then launched
-    // longest first, which also deals them evenly to the hardware's dispatch queues.
-    const size_t NU = pl->units.size();
+    // Two passes over the space order the scan.  With availability ignored, a unit whose
+    // minimum is +inf holds no plan that memory, node size and batch divisibility allow,
+    // whatever the availability becomes: it is dropped for good.  Units of equal size still
+    // differ widely in cost, because invalid plans are pruned early, so a second pass
+    // records how long each remaining unit takes; they are then launched longest first,
+    // which also deals them evenly to the hardware's dispatch queues.
+    size_t NU = pl->units.size();
     float *d_cost = nullptr;
     CREATE_TRY(ar.alloc(&d_cost, NU));
     ScanArgs ca{};
@@ -747,20 +767,33 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
     ca.umin_l = pl->umin_l;
     ca.counters = pl->counters;
     ca.lim_s = ca.lim_l = kPosInf;
+    ca.ignore_quota = 1;
+    k_units<MODE_SCAN, 0, false><<<(unsigned)NU, pl->unit_threads, pl->lds_bytes>>>(d, ca);
+    CREATE_TRY(hipGetLastError());
+    std::vector<float> val(NU);
+    CREATE_TRY(hipMemcpy(val.data(), pl->umin_s, NU * sizeof(float), hipMemcpyDeviceToHost));
+    std::vector<UnitRec> kept;
+    for (size_t i = 0; i < NU; ++i)
+      if (val[i] < kPosInf) kept.push_back(pl->units[i]);
+    if (kept.empty()) kept.push_back(pl->units[0]);  // launches need a non-empty grid
+    pl->units.swap(kept);
+    NU = pl->units.size();
+    d.n_units = (int)NU;
+    UnitRec *d_units = const_cast<UnitRec *>(d.units);
+    CREATE_TRY(hipMemcpy(d_units, pl->units.data(), NU * sizeof(UnitRec), hipMemcpyHostToDevice));
+    ca.ignore_quota = 0;
     ca.ucost = d_cost;
     k_units<MODE_SCAN, 0, false><<<(unsigned)NU, pl->unit_threads, pl->lds_bytes>>>(d, ca);
     CREATE_TRY(hipGetLastError());
-    std::vector<float> cost(NU);
-    CREATE_TRY(hipMemcpy(cost.data(), d_cost, NU * sizeof(float), hipMemcpyDeviceToHost));
+    CREATE_TRY(hipMemcpy(val.data(), d_cost, NU * sizeof(float), hipMemcpyDeviceToHost));
     std::vector<uint32_t> order(NU);
     for (size_t i = 0; i < NU; ++i) order[i] = (uint32_t)i;
     std::stable_sort(order.begin(), order.end(),
-                     [&](uint32_t x, uint32_t y) { return cost[x] > cost[y]; });
+                     [&](uint32_t x, uint32_t y) { return val[x] > val[y]; });
     std::vector<UnitRec> sorted(NU);
     for (size_t i = 0; i < NU; ++i) sorted[i] = pl->units[order[i]];
     pl->units.swap(sorted);
-    CREATE_TRY(hipMemcpy(const_cast<UnitRec *>(d.units), pl->units.data(), NU * sizeof(UnitRec),
-                         hipMemcpyHostToDevice));
+    CREATE_TRY(hipMemcpy(d_units, pl->units.data(), NU * sizeof(UnitRec), hipMemcpyHostToDevice));
     k_init_counters<<<1, 64>>>(pl->counters, 2 * CNT_COUNT);
     CREATE_TRY(hipDeviceSynchronize());
     ar.free_one(d_cost);
@@ -925,6 +958,15 @@ sailor_status sailor_plan_last_timing(sailor_plan *pl, float *total_ms, float *k
   }
   if (total_ms) *total_ms = t;
   if (kernel_ms) *kernel_ms = s;
+  return SAILOR_OK;
+}
+
+sailor_status sailor_plan_last_counts(const sailor_plan *pl, uint32_t *survivors,
+                                      uint32_t *refined, uint32_t *feasible) {
+  if (!pl || !pl->have_hdr) return SAILOR_EINVAL;
+  if (survivors) *survivors = pl->last_hdr.surv_count;
+  if (refined) *refined = pl->last_hdr.ref_count;
+  if (feasible) *feasible = pl->last_hdr.feasible_count;
   return SAILOR_OK;
 }
 

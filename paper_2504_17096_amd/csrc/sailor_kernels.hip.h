@@ -317,11 +317,15 @@ struct ScanArgs {
   SurvRec *surv;
   uint32_t surv_cap;
   float *ucost;             // SCAN, optional: ticks of the 100 MHz clock each unit took
+  int ignore_quota;         // SCAN at plan creation: treat every pool as large enough
+  const uint32_t *ulist;    // COLLECT, optional: the units to visit and, in counters[CNT_NLIST],
+                            // how many; the grid then strides over the list
 };
 
 enum Counter { CNT_SURV = 0, CNT_REF = 1, CNT_FEAS = 2, CNT_GMIN = 3, CNT_TAU0 = 4, CNT_TAU1 = 5,
                CNT_NLOOSE = 6, CNT_NSTRICT = 7,  // count-only collect passes
-               CNT_COUNT = 8 };
+               CNT_NLIST = 8,                    // length of the collect pass's unit list
+               CNT_COUNT = 16 };
 
 __device__ __forceinline__ uint32_t counter_reset_value(int i) {
   const int c = i % CNT_COUNT;
@@ -527,12 +531,8 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
 // needs comes from the unit record and tables that do not depend on one another, so all of
 // its global loads are in flight together and one barrier ends it.
 template <int MODE, int OBJ, bool HASB>
-__global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs a) {
-  extern __shared__ uint4 lds_raw[];
-  // SCAN: one workgroup per unit.  COLLECT: n_sub workgroups share a unit.
-  const uint32_t n_sub = MODE == MODE_COLLECT ? a.n_sub : 1u;
-  const uint32_t uidx = MODE == MODE_COLLECT ? blockIdx.x / n_sub : blockIdx.x;
-  const int sub = MODE == MODE_COLLECT ? (int)(blockIdx.x % n_sub) : 0;
+__device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, uint32_t uidx,
+                                          int sub, uint32_t n_sub, uint4 *lds_raw) {
   const unsigned long long t_begin = (MODE == MODE_SCAN && a.ucost) ? wall_clock64() : 0ull;
   const UnitRec u = pl.units[uidx];
   float tau = kPosInf;
@@ -563,7 +563,7 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
     const uint32_t sl = (u.shape * (uint32_t)pl.TP + (uint32_t)k) * 3u + (uint32_t)seg;
     const uint32_t gi = (sl * (uint32_t)G + (uint32_t)g) * (uint32_t)MB + mb;
     const float4 ta = pl.ta[gi];
-    uint32_t q = pl.qw[w * ZG + p];
+    uint32_t q = a.ignore_quota ? 0xFFFFFFFFu : pl.qw[w * ZG + p];
     if ((pl.h1m[p] >> k) & 1u) q = 0;  // H1: tensor parallelism stays inside a node
     const uint32_t bits = pl.memok[gi] & q & pl.divis[mb];
     rec[i] = make_rec(ta, pl.smax[sl], pl.upd[sl * G + g], pl.price_f[g], pl.p2p_f[mb],
@@ -574,7 +574,8 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
     if (bits != 0 && counts) any_here |= 1u << seg;
   }
   if (S == 3)
-    for (int p = t; p < ZG; p += blockDim.x) q13[p] = pl.qw[(w0 + w2) * ZG + p];
+    for (int p = t; p < ZG; p += blockDim.x)
+      q13[p] = a.ignore_quota ? 0xFFFFFFFFu : pl.qw[(w0 + w2) * ZG + p];
   for (int i = t; i < Z * Z; i += blockDim.x) {
     const int za = i / Z, zb = i % Z;
     pair[i] = make_float4(pl.ibw_f[za * Z + zb], pl.ibw_f[zb * Z + za], pl.egs_f[i], 0.f);
@@ -626,21 +627,46 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
   }
 }
 
+// SCAN: one workgroup per unit.  COLLECT: n_sub workgroups share a unit; with a unit list
+// the grid strides over the list instead of covering every unit.
+template <int MODE, int OBJ, bool HASB>
+__global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs a) {
+  extern __shared__ uint4 lds_raw[];
+  if (MODE == MODE_SCAN) {
+    unit_work<MODE, OBJ, HASB>(pl, a, blockIdx.x, 0, 1u, lds_raw);
+  } else if (!a.ulist) {
+    unit_work<MODE, OBJ, HASB>(pl, a, blockIdx.x / a.n_sub, (int)(blockIdx.x % a.n_sub), a.n_sub,
+                               lds_raw);
+  } else {
+    const uint32_t n_list = a.counters[CNT_NLIST], per_round = gridDim.x / a.n_sub;
+    const int sub = (int)(blockIdx.x % a.n_sub);
+    for (uint32_t e = blockIdx.x / a.n_sub; e < n_list; e += per_round) {  // uniform
+      unit_work<MODE, OBJ, HASB>(pl, a, a.ulist[e], sub, a.n_sub, lds_raw);
+      __syncthreads();  // the staging area is reused
+    }
+  }
+}
+
 // ------------------------------------------------------------------ k-th smallest key
 
 // Radix select (11 + 11 + 10 bits) of the k-th smallest non-negative float among
 // n = min(*count, cap) values read with a stride; +inf entries are ignored and fewer than
 // k finite values yield +inf.  One workgroup of 1024 threads.  The result's bit pattern
 // goes to *out.
+// With a list: also writes the positions i < n_list_src whose list_src[i] is finite and at
+// most result * band to list, and their number to *list_count (in no particular order).
 __global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stride_words,
                                                      const uint32_t *count, uint32_t cap,
-                                                     uint32_t k, uint32_t *out) {
+                                                     uint32_t k, uint32_t *out,
+                                                     const float *list_src, uint32_t n_list_src,
+                                                     float band, uint32_t *list,
+                                                     uint32_t *list_count) {
   __shared__ uint32_t hist[2048];
   __shared__ uint32_t wsum[16];
-  __shared__ uint32_t s_prefix, s_k, s_done;
+  __shared__ uint32_t s_prefix, s_k, s_done, s_nlist;
   const uint32_t n = count ? min(*count, cap) : cap;
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
-  if (t == 0) { s_prefix = 0; s_k = k; s_done = 0; }
+  if (t == 0) { s_prefix = 0; s_k = k; s_done = 0; s_nlist = 0; }
   const int shifts[3] = {21, 10, 0}, widths[3] = {11, 11, 10};
   for (int pass = 0; pass < 3; ++pass) {
     hist[t] = 0;
@@ -678,6 +704,16 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stri
     __syncthreads();
   }
   if (t == 0) *out = s_prefix;
+  if (list) {
+    __syncthreads();
+    const float tau = __uint_as_float(s_prefix) * band;
+    for (uint32_t i = t; i < n_list_src; i += blockDim.x) {
+      const float v = list_src[i];
+      if (v < kPosInf && v <= tau) list[atomicAdd(&s_nlist, 1u)] = i;
+    }
+    __syncthreads();
+    if (t == 0) *list_count = s_nlist;
+  }
 }
 
 // ------------------------------------------------------------------ fp64 re-evaluation
@@ -919,17 +955,13 @@ __global__ __launch_bounds__(1024) void k_pick_best(const RefRec *ref, uint32_t 
   }
 }
 
-// Top-k: the rank of every valid re-evaluated candidate in ascending (key, index) order,
-// by counting against tiles of the list staged in LDS; ranks below k are written to
-// host-mapped memory.
-constexpr int kRankTile = 1024;
-
+// Top-k: the rank of every valid re-evaluated candidate in ascending (key, index) order.
+// One wave per candidate: its lanes count, in strides over the list, the entries that
+// precede it; ranks below k are written to host-mapped memory.
 __global__ __launch_bounds__(256) void k_rank_topk(const RefRec *ref, uint32_t ref_cap,
                                                    const uint32_t *counters,
                                                    uint32_t *next_counters, int objective,
                                                    uint32_t k, ResultHeader *hdr, RefRec *out) {
-  __shared__ double t_key[kRankTile];
-  __shared__ unsigned long long t_idx[kRankTile];
   const uint32_t n = min(counters[CNT_REF], ref_cap);
   if (blockIdx.x == 0 && threadIdx.x < CNT_COUNT)
     next_counters[threadIdx.x] = counter_reset_value(threadIdx.x);  // for the next call
@@ -941,28 +973,21 @@ __global__ __launch_bounds__(256) void k_rank_topk(const RefRec *ref, uint32_t r
     hdr->feasible_count = f;
     hdr->gmin_bits = counters[CNT_GMIN];
   }
-  // uniform trip counts: every thread of a workgroup takes part in the tile barriers
-  for (uint32_t base = blockIdx.x * blockDim.x; base < n; base += gridDim.x * blockDim.x) {
-    const uint32_t i = base + threadIdx.x;
-    const bool mine = i < n && ref[i].mask == 0;
-    const double mk = mine ? (objective == 0 ? ref[i].T : ref[i].C) : 0.0;
-    const uint64_t mi = mine ? ref[i].idx : 0;
-    uint32_t rank = 0;
-    for (uint32_t t0 = 0; t0 < n; t0 += kRankTile) {
-      const uint32_t tn = min((uint32_t)kRankTile, n - t0);
-      __syncthreads();
-      for (uint32_t j = threadIdx.x; j < tn; j += blockDim.x) {
-        const RefRec &o = ref[t0 + j];
-        // an invalid entry never precedes anything
-        t_key[j] = o.mask == 0 ? (objective == 0 ? o.T : o.C) : __builtin_huge_val();
-        t_idx[j] = o.mask == 0 ? o.idx : ~0ull;
-      }
-      __syncthreads();
-      if (mine)
-        for (uint32_t j = 0; j < tn; ++j)
-          if (lex_less(t_key[j], t_idx[j], mk, mi)) ++rank;
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const uint32_t n_waves = gridDim.x * (blockDim.x >> 6);
+  for (uint32_t i = wave; i < n; i += n_waves) {
+    const RefRec r = ref[i];
+    if (r.mask != 0) continue;  // uniform over the wave
+    const double mk = objective == 0 ? r.T : r.C;
+    uint32_t before = 0;
+    for (uint32_t j = lane; j < n; j += 64) {
+      const RefRec &o = ref[j];
+      if (o.mask == 0 && lex_less(objective == 0 ? o.T : o.C, o.idx, mk, r.idx)) ++before;
     }
-    if (mine && rank < k) out[rank] = ref[i];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) before += __shfl_xor(before, off);
+    if (lane == 0 && before < k) out[before] = r;
   }
 }
 
