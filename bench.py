@@ -30,7 +30,11 @@ PEAK_FP32_VECTOR_TFLOPS = 157.3
 # HBM bytes per scan launch on this workload from rocprofv3 FETCH_SIZE / WRITE_SIZE, each
 # scaled by a 1 GiB copy of the same run (profiles/k_units_scan_cfg4_counters.md); set to
 # None whenever k_units changes after the counters were taken
-SCAN_TRAFFIC_BYTES = 7.52e6
+SCAN_TRAFFIC_BYTES = 5.25e6
+# VALU wave-instructions the scan executes per launch on this workload (SQ_INSTS_VALU, same
+# file and same rule); each occupies one of the 1 024 SIMDs for 4 cycles at 2.4 GHz
+SCAN_VALU_WAVE_INSTS = 1.059e7
+SIMDS, CLOCK_HZ, CYCLES_PER_WAVE_INST = 1024, 2.4e9, 4
 
 
 def mean_pipeline_depth(prob) -> float:
@@ -205,6 +209,11 @@ def main() -> int:
     pbar = mean_pipeline_depth(prob)
     flops_per_cand = FLOPS_PER_STAGE * pbar + FLOPS_EPILOGUE
     achieved = flops_per_cand * n / (scan_ms * 1e-3) / 1e12
+    valu = None
+    if SCAN_VALU_WAVE_INSTS is not None:
+        issue_ms = SCAN_VALU_WAVE_INSTS * CYCLES_PER_WAVE_INST / SIMDS / CLOCK_HZ * 1e3
+        valu = {"wave_insts_per_launch": SCAN_VALU_WAVE_INSTS, "issue_ms": issue_ms,
+                "frac_of_kernel_time": issue_ms / scan_ms}
     out = {
         "metric": "candidate plans evaluated/sec (full hot path incl. top-64 selection)",
         "value": n / (ms_per_step * 1e-3), "unit": "candidates/s",
@@ -218,7 +227,8 @@ def main() -> int:
         "roofline": {"bound": "alu", "kernel": "k_units<SCAN>", "achieved": achieved,
                      "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP32_VECTOR_TFLOPS, "traffic": SCAN_TRAFFIC_BYTES,
-                     "flops_per_candidate": flops_per_cand, "kernel_ms": scan_ms},
+                     "flops_per_candidate": flops_per_cand, "kernel_ms": scan_ms,
+                     "valu_issue": valu},
         "extra": {"time_to_top64_ms": ms_per_step, "time_to_best_plan_ms": best_ms,
                   "device_ms_per_step": tot_ms, "scan_kernel_ms": scan_ms,
                   "eval_batch_ms": eval_ms,

@@ -39,7 +39,7 @@ class _Problem(C.Structure):
         ("n_layers", C.c_int32), ("n_types", C.c_int32), ("n_zones", C.c_int32),
         ("n_mb", C.c_int32), ("n_tp", C.c_int32), ("n_dp", C.c_int32), ("n_pp", C.c_int32),
         ("max_segments", C.c_int32), ("seg3_max_pp", C.c_int32), ("uniform_layers", C.c_int32),
-        ("per_segment_tp", C.c_int32),
+        ("per_segment_tp", C.c_int32), ("n_bw_coef", C.c_int32),
         ("global_batch", C.c_int64),
         ("mb_values", C.c_void_p), ("tp_values", C.c_void_p), ("dp_values", C.c_void_p),
         ("pp_values", C.c_void_p), ("n_partitions", C.c_void_p), ("partition_layers", C.c_void_p),
@@ -51,6 +51,7 @@ class _Problem(C.Structure):
         ("mem_capacity", C.c_void_p), ("mem_reserved", C.c_void_p),
         ("gpus_per_node", C.c_void_p), ("price_per_hour", C.c_void_p),
         ("avail", C.c_void_p), ("bandwidth", C.c_void_p), ("egress_per_byte", C.c_void_p),
+        ("bw_poly", C.c_void_p),
     ]
 
 
@@ -175,6 +176,9 @@ class Oracle:
         s.bandwidth = arr(prob.bandwidth, np.float64)
         s.egress_per_byte = (arr(prob.egress_per_byte, np.float64)
                              if prob.egress_per_byte is not None else None)
+        poly = getattr(prob, "bw_poly", None)
+        s.n_bw_coef = 0 if poly is None else int(np.asarray(poly).shape[-1])
+        s.bw_poly = arr(poly, np.float64) if poly is not None else None
         self._struct = s
         self._lib = lib
         self._ctx = lib.so_create(C.byref(s))

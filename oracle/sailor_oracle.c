@@ -257,6 +257,24 @@ static double upd_time_sum(const so_problem *p, int g, int it, int first_layer, 
   return s;
 }
 
+/* Bandwidth a message of `bytes` sees from zone a to zone b: the link's fitted polynomial
+ * in log2(bytes) (Sec. 4.1), kept inside [peak / 1000, peak]; the constant peak when no
+ * polynomial is given. */
+static double link_bandwidth(const so_problem *p, int a, int b, double bytes) {
+  const double peak = p->bandwidth[(size_t)a * p->n_zones + b];
+  if (p->n_bw_coef <= 0 || !p->bw_poly || bytes < 1.0) return peak;
+  const double *c = p->bw_poly + ((size_t)a * p->n_zones + b) * p->n_bw_coef;
+  const double x = log2(bytes);
+  double v = 0.0, xk = 1.0;
+  for (int k = 0; k < p->n_bw_coef; ++k) {
+    v += c[k] * xk;
+    xk *= x;
+  }
+  if (!(v < peak)) v = peak;
+  if (v < peak * 1e-3) v = peak * 1e-3;
+  return v;
+}
+
 static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int objective,
                         int has_bound, double bound, so_eval *out) {
   const so_problem *p = &c->p;
@@ -329,17 +347,17 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
     double f = layer_time_sum(p, p->t_fwd, gt, g->mb_idx, tpi_of[i], first_layer[i], nl[i]);
     double b = layer_time_sum(p, p->t_bwd, gt, g->mb_idx, tpi_of[i], first_layer[i], nl[i]);
     double x = 0.0;
-    if (i < P - 1) x += p2p / p->bandwidth[(size_t)z * Z + zone_of[i + 1]];
-    if (i > 0) x += p2p / p->bandwidth[(size_t)z * Z + zone_of[i - 1]];
+    if (i < P - 1) x += p2p / link_bandwidth(p, z, zone_of[i + 1], p2p);
+    if (i > 0) x += p2p / link_bandwidth(p, z, zone_of[i - 1], p2p);
     double t = f + b + x;
     sum_t += t;
     if (t > max_t) max_t = t;
     /* gradient all-reduce of the stage's D replicas inside their zone: ring */
     double sync = 0.0;
-    if (D > 1)
-      sync = 2.0 * (double)(D - 1) / (double)D *
-             ((double)params_of[i] * (double)p->grad_bytes_per_param) /
-             p->bandwidth[(size_t)z * Z + z];
+    if (D > 1) {
+      const double grad_bytes = (double)params_of[i] * (double)p->grad_bytes_per_param;
+      sync = 2.0 * (double)(D - 1) / (double)D * grad_bytes / link_bandwidth(p, z, z, grad_bytes);
+    }
     if (sync > t_sync) t_sync = sync;
     double u = upd_time_sum(p, gt, tpi_of[i], first_layer[i], nl[i]);
     if (u > t_upd) t_upd = u;

@@ -22,11 +22,20 @@
  * activation bytes, profiled times, the node-size check, the gradient all-reduce, the
  * GPU count against the quota and the rent all use the degree of the stage's segment.
  *
+ * Optional message-size dependent bandwidth (n_bw_coef > 0): the profiler fits, per link,
+ * a polynomial of the bandwidth over the message size (Sec. 4.1) and the simulator uses
+ * it for peer-to-peer transfers and collectives (Sec. 4.3).  Here the polynomial is in
+ * x = log2(bytes); its value is limited to [peak / 1000, peak] with peak = bandwidth[a][b].
+ * A transfer of S bytes takes S / bw(S); the all-reduce of a stage uses its gradient
+ * buffer as the message size, and T_sync is the maximum over the stages.
+ *
  * Parity pins (tests/test_oracle_*.py): homogeneous 1F1B closed form, discrete-event
  * 1F1B schedule, ring all-reduce limits, big-integer memory bytes, cost identities,
  * feasibility monotonicity, brute-force selection, enumeration bijection; per-segment
  * TP: agreement with the shared-TP mode on equal degrees, hand-computed time / sync /
- * cost on mixed degrees, Python-integer memory and quota, count formula.
+ * cost on mixed degrees, Python-integer memory and quota, count formula; bandwidth
+ * polynomial: reduction to the constant model, hand-computed transfers and all-reduce
+ * with numpy's polynomial evaluation, both limits, per-stage maximum of T_sync.
  * Against numeric outputs of the paper's own simulator: parity unpinned (the paper
  * prints no worked input -> output example).
  *
@@ -45,6 +54,7 @@ typedef struct {
   int32_t n_layers, n_types, n_zones, n_mb, n_tp, n_dp, n_pp;
   int32_t max_segments, seg3_max_pp, uniform_layers;
   int32_t per_segment_tp;          /* 1: every segment has its own TP degree (digit) */
+  int32_t n_bw_coef;               /* 0: constant bandwidth; else coefficients per zone pair */
   int64_t global_batch;
   const int32_t *mb_values, *tp_values, *dp_values, *pp_values;
   const int32_t *n_partitions;     /* [n_pp] */
@@ -62,6 +72,7 @@ typedef struct {
   const int32_t *avail;            /* [Z][G] */
   const double *bandwidth;         /* [Z][Z] */
   const double *egress_per_byte;   /* [Z][Z] or NULL */
+  const double *bw_poly;           /* [Z][Z][n_bw_coef], lowest power first, or NULL */
 } so_problem;
 
 /* a decoded candidate */

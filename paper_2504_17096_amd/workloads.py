@@ -101,6 +101,8 @@ class Problem:
     bandwidth: np.ndarray          # float64 [Z][Z], bytes/s
     egress_per_byte: Optional[np.ndarray] = None  # float64 [Z][Z] or None (= zeros)
     per_segment_tp: bool = False   # every segment carries its own TP digit
+    bw_poly: Optional[np.ndarray] = None  # float64 [Z][Z][n_coef]: bandwidth over log2(message
+                                          # bytes), lowest power first; None = constant
     name: str = ""
     notes: dict = field(default_factory=dict)
 
@@ -122,6 +124,10 @@ class Problem:
 
     def with_per_segment_tp(self, on: bool = True) -> "Problem":
         return replace(self, per_segment_tp=bool(on))
+
+    def with_bw_poly(self, poly: Optional[np.ndarray]) -> "Problem":
+        return replace(self, bw_poly=None if poly is None
+                       else np.ascontiguousarray(poly, dtype=np.float64))
 
     def with_avail(self, avail: np.ndarray) -> "Problem":
         return replace(self, avail=np.ascontiguousarray(avail, dtype=np.int32))
@@ -323,6 +329,23 @@ def config5_snapshots(base: Problem, n_snapshots: int = 64, seed: int = 5) -> Li
             if rng.uniform() < 0.05:
                 snap[z, :] = 0
         out.append(snap.astype(np.int32))
+    return out
+
+
+def bandwidth_poly(prob: Problem, seed: int = 6) -> np.ndarray:
+    """Seeded message-size profile of every link: a quadratic in log2(bytes) through
+    (1 KiB, 2-8 % of the peak), (1 MiB, 40-70 %) and (128 MiB, the peak), the shape
+    of a measured collective-bandwidth curve.  Returns [Z][Z][3], lowest power first."""
+    rng = SplitMix64(seed)
+    Z = prob.n_zones
+    out = np.zeros((Z, Z, 3))
+    xs = np.array([10.0, 20.0, 27.0])
+    vand = np.stack([xs ** 0, xs, xs ** 2], axis=1)
+    for a in range(Z):
+        for b in range(Z):
+            peak = float(prob.bandwidth[a, b])
+            ys = np.array([rng.uniform_range(0.02, 0.08), rng.uniform_range(0.4, 0.7), 1.0]) * peak
+            out[a, b] = np.linalg.solve(vand, ys)
     return out
 
 
