@@ -85,6 +85,7 @@ enum {
   SAILOR_MAX_TP = 8,
   SAILOR_MAX_DP = 24,
   SAILOR_MAX_STAGES = 256,
+  SAILOR_MAX_BW_COEF = 8, /* coefficients of a link's bandwidth polynomial */
   SAILOR_MAX_K = 4096     /* largest k of sailor_topk */
 };
 
@@ -100,6 +101,8 @@ typedef struct {
   int32_t seg3_max_pp;     /* a third segment only for pp <= this */
   int32_t uniform_layers;  /* 1: time tables hold a single per-layer column */
   int32_t per_segment_tp;  /* 1: every segment has its own TP digit; 0: one TP per plan */
+  int32_t n_bw_coef;       /* coefficients per link in bw_poly, 0..SAILOR_MAX_BW_COEF; 0: every
+                              message sees bandwidth[a][b] */
   int64_t global_batch;    /* never changed by the planner (Sec. 4.2) */
   const int32_t *mb_values, *tp_values, *dp_values, *pp_values; /* positive, strictly ascending */
   const int32_t *n_partitions;     /* [n_pp], >= 1 */
@@ -122,6 +125,14 @@ typedef struct {
   const double *bandwidth;         /* [Z][Z] bytes/s from row zone to column zone, > 0;
                                       the diagonal is the intra-zone link */
   const double *egress_per_byte;   /* [Z][Z] $/byte, >= 0, or NULL for zeros */
+  const double *bw_poly;           /* [Z][Z][n_bw_coef], lowest power first, finite; NULL when
+                                      n_bw_coef = 0.  Message-size profile of a link (cluster
+                                      profiling, Sec. 4.1): a message of S >= 1 bytes from zone a
+                                      to zone b sees the polynomial's value at x = log2(S),
+                                      limited to [bandwidth[a][b] / 1000, bandwidth[a][b]], and
+                                      takes S / that.  Used for activation / gradient transfers
+                                      between stages (S = p2p_bytes[mb]) and for the gradient
+                                      all-reduce of a stage (S = its gradient buffer), Sec. 4.3 */
 } sailor_problem;
 
 /* Optional bound: SAILOR_MAX_THROUGHPUT -> bound is the largest allowed $/iteration;

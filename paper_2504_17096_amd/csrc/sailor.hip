@@ -137,6 +137,8 @@ sailor_status validate(const sailor_problem *p) {
     return SAILOR_EINVAL;
   if (p->max_segments < 1 || p->max_segments > 3 || p->global_batch < 1) return SAILOR_EINVAL;
   if (p->per_segment_tp != 0 && p->per_segment_tp != 1) return SAILOR_EINVAL;
+  if (p->n_bw_coef < 0 || p->n_bw_coef > SAILOR_MAX_BW_COEF || (p->n_bw_coef > 0 && !p->bw_poly))
+    return SAILOR_EINVAL;
   if (!ascending_positive(p->mb_values, p->n_mb) || !ascending_positive(p->tp_values, p->n_tp) ||
       !ascending_positive(p->dp_values, p->n_dp) || !ascending_positive(p->pp_values, p->n_pp))
     return SAILOR_EINVAL;
@@ -170,6 +172,8 @@ sailor_status validate(const sailor_problem *p) {
   for (int i = 0; i < Z * Z; ++i)
     if (!(p->bandwidth[i] > 0.0) || !std::isfinite(p->bandwidth[i])) return SAILOR_EINVAL;
   if (p->egress_per_byte && !finite_nonneg(p->egress_per_byte, (size_t)Z * Z)) return SAILOR_EINVAL;
+  for (size_t i = 0; i < (size_t)Z * Z * p->n_bw_coef; ++i)
+    if (!std::isfinite(p->bw_poly[i])) return SAILOR_EINVAL;
   for (int i = 0; i < Z * G; ++i)
     if (p->avail[i] < 0) return SAILOR_EINVAL;
   for (int g = 0; g < G; ++g)
@@ -654,11 +658,12 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   d.mg_mbtp = magic((uint32_t)(d.MB * d.TP));
   d.mg_mbtpdp = magic((uint32_t)(d.MB * d.TP * d.DP));
   pl->eval_lds_bytes = (size_t)3 * d.TP * d.ZG * d.MB * sizeof(Rec) +
-                       (size_t)d.Z * d.Z * sizeof(float4) +
+                       (size_t)d.MB * d.Z * d.Z * sizeof(float4) +
                        (size_t)3 * d.TP * d.MB * d.DP * sizeof(uint64_t) +
                        (size_t)3 * d.TP * d.ZG * sizeof(uint32_t) + (size_t)d.ZG * sizeof(PoolInfo) +
                        (size_t)(kEvalUnitMaxOuter + d.DP + d.TP) * sizeof(uint32_t);
-  pl->lds_bytes = (size_t)3 * d.ZG * d.MB * sizeof(Rec) + (size_t)d.Z * d.Z * sizeof(float4) +
+  pl->lds_bytes = (size_t)3 * d.ZG * d.MB * sizeof(Rec) +
+                  (size_t)d.MB * d.Z * d.Z * sizeof(float4) +
                   (size_t)4 * d.ZG * sizeof(uint32_t);
 
 #define CREATE_TRY(expr)                                                           \
@@ -710,10 +715,12 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(ar.upload(&d.units, pl->units.data(), pl->units.size()));
   CREATE_TRY(ar.upload(&pl->d_eunits, pl->eunits.data(), pl->eunits.size()));
   // derived tables, filled by the set-up kernels
-  CREATE_TRY(ar.alloc(&d.ibw_f, (size_t)Z * Z));
+  d.n_bw_coef = p->n_bw_coef;
+  if (p->n_bw_coef > 0) CREATE_TRY(ar.upload(&d.bw_poly, p->bw_poly, (size_t)Z * Z * p->n_bw_coef));
+  CREATE_TRY(ar.alloc(&d.bwp, (size_t)MB * Z * Z));
+  CREATE_TRY(ar.alloc(&d.tsec_f, (size_t)MB * Z * Z));
   CREATE_TRY(ar.alloc(&d.egs_f, (size_t)Z * Z));
   CREATE_TRY(ar.alloc(&d.price_f, G));
-  CREATE_TRY(ar.alloc(&d.p2p_f, MB));
   CREATE_TRY(ar.alloc(&d.xb_f, MB));
   CREATE_TRY(ar.alloc(&d.cd_f, DP));
   CREATE_TRY(ar.alloc(&d.nbm1_f, (size_t)MB * DP));
@@ -727,7 +734,7 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(ar.alloc(&d.ta, slots * G * MB));
   CREATE_TRY(ar.alloc(&d.memok, slots * G * MB));
   CREATE_TRY(ar.alloc(&d.need, slots * MB * DP));
-  CREATE_TRY(ar.alloc(&d.smax, slots));
+  CREATE_TRY(ar.alloc(&d.syncz, slots * Z));
   CREATE_TRY(ar.alloc(&d.upd, slots * G));
   // selection scratch
   CREATE_TRY(ar.alloc(&pl->umin_s, pl->units.size()));

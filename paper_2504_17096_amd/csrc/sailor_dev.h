@@ -101,9 +101,13 @@ struct DevPlan {
   // derived small tables
   uint32_t *qw;                // [W_max + 1][ZG] bit d: dpv[d] replicas of w GPUs fit the pool
   uint32_t *h1m;               // [ZG] bit k: tpv[k] exceeds the node size of the pool's type (H1)
-  float *ibw_f, *egs_f;        // [Z][Z] 1/bw ; egress both ways
+  int n_bw_coef;               // 0: constant link bandwidth
+  const double *bw_poly;       // [Z][Z][n_bw_coef] bandwidth over log2(message bytes)
+  double *bwp;                 // [MB][Z][Z] bandwidth seen by one activation transfer
+  float *tsec_f;               // [MB][Z][Z] seconds of one activation transfer a -> b
+  float *egs_f;                // [Z][Z] egress both ways
   float *price_f;              // [G]
-  float *p2p_f, *xb_f;         // [MB] p2p bytes ; (B/mb) * p2p bytes
+  float *xb_f;                 // [MB] (B/mb) * p2p bytes
   float *cd_f;                 // [DP] 2 (D-1) / D
   float *nbm1_f;               // [MB][DP] microbatches per pipeline - 1
   float *dph_f;                // [DP] D / 3600
@@ -123,7 +127,7 @@ struct DevPlan {
   float4 *ta;                  // [..][G][MB] {sum, first, last, max interior} of stage compute
   uint32_t *memok;             // [..][G][MB] bit d: no stage of the segment runs out of memory
   uint64_t *need;              // [..][MB][DP] max over stages of model + activation bytes
-  float *smax;                 // [..] largest gradient shard of the segment, bytes
+  float *syncz;                // [..][Z] slowest stage: gradient bytes / intra-zone bandwidth
   float *upd;                  // [..][G] slowest stage update
 };
 

@@ -33,6 +33,21 @@ __device__ __forceinline__ size_t agg_slot(const DevPlan &pl, uint32_t shape, in
   return ((size_t)shape * pl.TP + tp) * 3 + seg;
 }
 
+// Bandwidth a message of `bytes` sees from zone a to zone b: the link's fitted polynomial
+// in log2(bytes) (cluster profiling, Sec. 4.1), kept inside [peak / 1000, peak]; the
+// constant peak when the problem carries no polynomial.
+__device__ __forceinline__ double link_bw(const DevPlan &pl, int a, int b, double bytes) {
+  const double peak = pl.bw[a * pl.Z + b];
+  if (pl.n_bw_coef <= 0 || bytes < 1.0) return peak;
+  const double *c = pl.bw_poly + (size_t)(a * pl.Z + b) * pl.n_bw_coef;
+  const double x = log2(bytes);
+  double v = c[pl.n_bw_coef - 1];
+  for (int k = pl.n_bw_coef - 2; k >= 0; --k) v = v * x + c[k];  // Horner
+  if (!(v < peak)) v = peak;
+  if (v < peak * 1e-3) v = peak * 1e-3;
+  return v;
+}
+
 // ------------------------------------------------------------------ set-up kernels
 
 // Reciprocal bandwidths, two-way egress, and the per-(mb, dp, tp) scalars of a plan.
@@ -41,7 +56,11 @@ __global__ void k_small_tables(DevPlan pl) {
   const int Z = pl.Z;
   for (int i = t; i < Z * Z; i += nt) {
     int a = i / Z, b = i % Z;
-    pl.ibw_f[i] = (float)(1.0 / pl.bw[i]);
+    for (int m = 0; m < pl.MB; ++m) {
+      const double bytes = (double)pl.p2p[m], bwv = link_bw(pl, a, b, bytes);
+      pl.bwp[m * Z * Z + i] = bwv;
+      pl.tsec_f[m * Z * Z + i] = (float)(bytes / bwv);
+    }
     double e = 0.0;
     if (pl.egress && a != b) e = pl.egress[a * Z + b] + pl.egress[b * Z + a];
     pl.egs_f[i] = (float)e;
@@ -54,7 +73,6 @@ __global__ void k_small_tables(DevPlan pl) {
     pl.h1m[p] = m;
   }
   for (int m = t; m < pl.MB; m += nt) {
-    pl.p2p_f[m] = (float)(double)pl.p2p[m];
     // N_b * D = B / mb whenever the batch divides; the product is exact in fp64 for
     // realistic sizes and is rounded once
     pl.xb_f[m] = (float)((double)(pl.B / pl.mbv[m]) * (double)pl.p2p[m]);
@@ -136,7 +154,7 @@ __global__ void k_shape_agg(DevPlan pl) {
   const ShapeRec sh = pl.shapes[shp];
   const int G = pl.G, MB = pl.MB, TP = pl.TP, DP = pl.DP, P = sh.P;
   const int t = threadIdx.x, nt = blockDim.x;
-  // need[tp][seg][mb][dp], smax, upd
+  // need[tp][seg][mb][dp], syncz, upd
   for (int it = t; it < TP * 3 * MB * DP; it += nt) {
     int d = it % DP, m = (it / DP) % MB, seg = (it / (DP * MB)) % 3, k = it / (DP * MB * 3);
     uint64_t mx = 0;
@@ -150,15 +168,16 @@ __global__ void k_shape_agg(DevPlan pl) {
     }
     pl.need[(agg_slot(pl, shp, k, seg) * MB + m) * DP + d] = mx;
   }
-  for (int it = t; it < TP * 3; it += nt) {
-    int seg = it % 3, k = it / 3;
-    uint64_t mx = 0;
+  for (int it = t; it < TP * 3 * pl.Z; it += nt) {
+    int z = it % pl.Z, seg = (it / pl.Z) % 3, k = it / (pl.Z * 3);
+    double mx = 0.0;  // seconds of the slowest stage's gradient buffer over the zone's link
     if (seg < sh.s)
       for (int i = sh.lo[seg]; i < sh.lo[seg] + sh.n[seg]; ++i) {
         uint64_t shard = (pl.st_params[sh.row_stage + i] + pl.tpv[k] - 1) / (uint64_t)pl.tpv[k];
-        mx = shard > mx ? shard : mx;
+        const double bytes = (double)shard * (double)pl.gb;
+        mx = fmax(mx, bytes / link_bw(pl, z, z, bytes));
       }
-    pl.smax[agg_slot(pl, shp, k, seg)] = (float)((double)mx * (double)pl.gb);
+    pl.syncz[agg_slot(pl, shp, k, seg) * pl.Z + z] = (float)mx;
   }
   for (int it = t; it < TP * 3 * G; it += nt) {
     int g = it % G, seg = (it / G) % 3, k = it / (G * 3);
@@ -206,25 +225,24 @@ struct Rec {       // one segment placed on one pool, for one (mb, tp); 32 bytes
   float sumT;      // sum of its stage times without the cross-segment transfers
   float tF, tL;    // first / last stage time without the cross-segment transfers
   float tI;        // slowest interior stage
-  float syncb;     // gradient bytes of the largest shard / intra-zone bandwidth
+  float syncb;     // slowest stage: gradient bytes / intra-zone bandwidth
   float upd;       // slowest update
   float pricen;    // stages * tp * $/h: rent of one replica of the segment
   uint32_t bits;   // bit d: valid for dp index d (memory, quota, batch, H1)
 };
 
 struct LaneC {     // scalars of a (mb, dp) pair
-  float p2pf, nbm1, cd, dph, xb;
+  float nbm1, cd, dph, xb;
 };
 
-__device__ __forceinline__ Rec make_rec(float4 ta, float smax, float upd, float price, float p2pf,
-                                        float ibw_zz, int n, int tp, uint32_t bits) {
-  Rec r;
-  const float w = p2pf * ibw_zz;  // one transfer inside the zone
+__device__ __forceinline__ Rec make_rec(float4 ta, float sync, float upd, float price, float w,
+                                        int n, int tp, uint32_t bits) {
+  Rec r;  // w: seconds of one transfer inside the zone
   r.sumT = fmaf((float)(2 * (n - 1)), w, ta.x);
   r.tF = (n == 1) ? ta.y : ta.y + w;
   r.tL = (n == 1) ? kNegInf : ta.z + w;
   r.tI = (n >= 3) ? fmaf(2.0f, w, ta.w) : kNegInf;
-  r.syncb = smax * ibw_zz;
+  r.syncb = sync;
   r.upd = upd;
   r.pricen = (float)(n * tp) * price;
   r.bits = bits;
@@ -404,7 +422,6 @@ __device__ __forceinline__ LaneItem lane_item(const DevPlan &pl, int e, int n_it
   it.a1 = (int)a1;
   it.dp = (int)dp;
   it.mb = (int)(rem - a1 * (uint32_t)pl.MB);
-  it.lc.p2pf = pl.p2p_f[it.mb];
   it.lc.nbm1 = pl.nbm1_f[it.mb * pl.DP + it.dp];
   it.lc.cd = pl.cd_f[it.dp];
   it.lc.dph = pl.dph_f[it.dp];
@@ -449,7 +466,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
       const uint32_t b0 = r0.bits & it.dpbit;
       if (!wave_any(b0 != 0)) continue;
       const int z1 = (int)fast_div((uint32_t)a1, pl.mg_g);
-      const float4 *pair1 = pair + z1 * Z;   // transfers out of this lane's first zone
+      const float4 *pair1 = pair + (it.mb * Z + z1) * Z;  // transfers out of this lane's first zone
       const Acc A0 = acc_begin(r0);
       // index of the candidate whose outer digits are all zero
       const uint64_t idx0 = ubase + (uint64_t)(it.mb + MB * (tp + pl.TP * (it.dp + DP * a1)));
@@ -466,8 +483,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
         if (wave_any(b1 != 0)) {
           const Rec r1 = *rp1;
           const float4 p12 = pair1[z2];
-          const Acc A1 = acc_cross(A0, r1, it.lc.p2pf * p12.x, it.lc.p2pf * p12.y, p12.z,
-                                   single0, true);
+          const Acc A1 = acc_cross(A0, r1, p12.x, p12.y, p12.z, single0, true);
           int rel2 = a2 - a1 - 1;
           if (rel2 < 0) rel2 += ZG;
           float T, C;
@@ -491,9 +507,9 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
         const uint32_t b1 = r0.bits & it.dpbit & r1.bits;
         if (!wave_any(b1 != 0)) continue;
         const int z1 = (int)fast_div((uint32_t)a1, pl.mg_g);
-        const float4 p12 = pair[z1 * Z + z2];
-        const Acc A1 = acc_cross(acc_begin(r0), r1, it.lc.p2pf * p12.x, it.lc.p2pf * p12.y, p12.z,
-                                 single0, true);
+        const float4 *pairm = pair + it.mb * Z * Z;
+        const float4 p12 = pairm[z1 * Z + z2];
+        const Acc A1 = acc_cross(acc_begin(r0), r1, p12.x, p12.y, p12.z, single0, true);
         const uint32_t q13a = q13[a1];
         int rel2 = a2 - a1 - 1;
         if (rel2 < 0) rel2 += ZG;
@@ -507,9 +523,8 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
             if (a3 == a1) b2 &= q13a;  // segments 1 and 3 share one pool's quota
             if (wave_any(b2 != 0)) {
               const Rec r2 = *rp2;
-              const float4 p23 = pair[z2 * Z + z3];
-              const Acc A2 = acc_cross(A1, r2, it.lc.p2pf * p23.x, it.lc.p2pf * p23.y, p23.z,
-                                       single1, false);
+              const float4 p23 = pairm[z2 * Z + z3];
+              const Acc A2 = acc_cross(A1, r2, p23.x, p23.y, p23.z, single1, false);
               int rel3 = a3 - a2 - 1;
               if (rel3 < 0) rel3 += ZG;
               float T, C;
@@ -543,8 +558,8 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
   }
   const int ZG = pl.ZG, G = pl.G, MB = pl.MB, Z = pl.Z, S = u.s;
   Rec *rec = reinterpret_cast<Rec *>(lds_raw);                      // [S][ZG][MB]
-  float4 *pair = reinterpret_cast<float4 *>(rec + 3 * ZG * MB);     // [Z][Z]
-  uint32_t *q13 = reinterpret_cast<uint32_t *>(pair + Z * Z);       // [ZG]
+  float4 *pair = reinterpret_cast<float4 *>(rec + 3 * ZG * MB);     // [MB][Z][Z]
+  uint32_t *q13 = reinterpret_cast<uint32_t *>(pair + MB * Z * Z);  // [ZG]
   __shared__ float red[2][kMaxUnitThreads / 64];
   __shared__ uint32_t s_any[kMaxUnitThreads / 64];  // per wave, bit j: a pool can host segment j
   const int t = threadIdx.x;
@@ -566,8 +581,8 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
     uint32_t q = a.ignore_quota ? 0xFFFFFFFFu : pl.qw[w * ZG + p];
     if ((pl.h1m[p] >> k) & 1u) q = 0;  // H1: tensor parallelism stays inside a node
     const uint32_t bits = pl.memok[gi] & q & pl.divis[mb];
-    rec[i] = make_rec(ta, pl.smax[sl], pl.upd[sl * G + g], pl.price_f[g], pl.p2p_f[mb],
-                      pl.ibw_f[z * Z + z], seg == 0 ? n0 : (seg == 1 ? n1 : n2),
+    rec[i] = make_rec(ta, pl.syncz[sl * Z + z], pl.upd[sl * G + g], pl.price_f[g],
+                      pl.tsec_f[(mb * Z + z) * Z + z], seg == 0 ? n0 : (seg == 1 ? n1 : n2),
                       seg == 0 ? tv0 : (seg == 1 ? tv1 : tv2), bits);
     // a segment that no pool can host validly rules the whole unit out
     const bool counts = seg != 1 || (p >= (int)u.o_lo && p < (int)(u.o_lo + u.o_cnt));
@@ -576,9 +591,9 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
   if (S == 3)
     for (int p = t; p < ZG; p += blockDim.x)
       q13[p] = a.ignore_quota ? 0xFFFFFFFFu : pl.qw[(w0 + w2) * ZG + p];
-  for (int i = t; i < Z * Z; i += blockDim.x) {
-    const int za = i / Z, zb = i % Z;
-    pair[i] = make_float4(pl.ibw_f[za * Z + zb], pl.ibw_f[zb * Z + za], pl.egs_f[i], 0.f);
+  for (int i = t; i < MB * Z * Z; i += blockDim.x) {  // per mb: transfer a -> b, b -> a, egress
+    const int m = i / (Z * Z), ab = i - m * Z * Z, za = ab / Z, zb = ab % Z;
+    pair[i] = make_float4(pl.tsec_f[i], pl.tsec_f[(m * Z + zb) * Z + za], pl.egs_f[ab], 0.f);
   }
   {
     uint32_t wv = 0;
@@ -795,6 +810,7 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
     return;
   }
   const double p2p = (double)pl.p2p[c.mb];
+  const double *bwp = pl.bwp + c.mb * Z * Z;  // bandwidth seen by a transfer of p2p bytes
   // quota per pool (GPUs of one replica there, times D) and H1
   for (int j = 0; j < c.s; ++j) {
     int64_t gpus = 0;
@@ -817,20 +833,20 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
     if (i < P - 1) {
       const int sn = (i + 1) < c.k1 ? 0 : ((i + 1) < c.k2 ? 1 : 2);
       const int zn = c.a[sn] / G;
-      x += p2p / pl.bw[z * Z + zn];
+      x += p2p / bwp[z * Z + zn];
       if (pl.egress && zn != z)
         comm = (double)nb * (double)D * p2p * (pl.egress[z * Z + zn] + pl.egress[zn * Z + z]);
     }
     if (i > 0) {
       const int sp = (i - 1) < c.k1 ? 0 : ((i - 1) < c.k2 ? 1 : 2);
-      x += p2p / pl.bw[z * Z + c.a[sp] / G];
+      x += p2p / bwp[z * Z + c.a[sp] / G];
     }
     const double t = pl.st_c[(((size_t)(rs + i) * G + g) * MB + c.mb) * TP + k] + x;
     max_t = fmax(max_t, t);
     if (D > 1) {
       const uint64_t shard = (pl.st_params[rs + i] + (uint64_t)tp - 1) / (uint64_t)tp;
-      const double sync = 2.0 * (double)(D - 1) / (double)D * ((double)shard * (double)pl.gb) /
-                          pl.bw[z * Z + z];
+      const double bytes = (double)shard * (double)pl.gb;
+      const double sync = 2.0 * (double)(D - 1) / (double)D * bytes / link_bw(pl, z, z, bytes);
       t_sync = fmax(t_sync, sync);
     }
     t_upd = fmax(t_upd, pl.st_u[((size_t)(rs + i) * G + g) * TP + k]);
@@ -1015,8 +1031,9 @@ __device__ __forceinline__ void eval_direct_s(const DevPlan &pl, const Cand &c, 
     const int p = c.a[j], g = p % G, z = p / G;
     const int tpv = pl.tpv[c.tp[j]];
     const size_t sl = agg_slot(pl, c.shape, c.tp[j], j);
-    const Rec r = make_rec(pl.ta[(sl * G + g) * MB + c.mb], pl.smax[sl], pl.upd[sl * G + g],
-                           pl.price_f[g], lc.p2pf, pl.ibw_f[z * Z + z], sh.n[j], tpv, 0u);
+    const float *ts = pl.tsec_f + c.mb * Z * Z;  // transfer seconds of this microbatch size
+    const Rec r = make_rec(pl.ta[(sl * G + g) * MB + c.mb], pl.syncz[sl * Z + z], pl.upd[sl * G + g],
+                           pl.price_f[g], ts[z * Z + z], sh.n[j], tpv, 0u);
     const uint64_t m = pl.need[(sl * MB + c.mb) * DP + c.dp] + pl.res[g];
     if (m > pl.cap[g]) mask |= 1u;
     peak = m > peak ? m : peak;
@@ -1029,7 +1046,7 @@ __device__ __forceinline__ void eval_direct_s(const DevPlan &pl, const Cand &c, 
       acc = acc_begin(r);
     } else {
       const int zp = c.a[j - 1] / G;
-      acc = acc_cross(acc, r, lc.p2pf * pl.ibw_f[zp * Z + z], lc.p2pf * pl.ibw_f[z * Z + zp],
+      acc = acc_cross(acc, r, ts[zp * Z + z], ts[z * Z + zp],
                       pl.egs_f[zp * Z + z], sh.n[j - 1] == 1, j == 1);
     }
   }
@@ -1053,7 +1070,6 @@ __global__ __launch_bounds__(256) void k_eval_direct(DevPlan pl, EvalArgs a) {
     } else {
       const ShapeRec sh = pl.shapes[c.shape];
       LaneC lc;
-      lc.p2pf = pl.p2p_f[c.mb];
       lc.nbm1 = pl.nbm1_f[c.mb * pl.DP + c.dp];
       lc.cd = pl.cd_f[c.dp];
       lc.dph = pl.dph_f[c.dp];
@@ -1100,13 +1116,13 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
     const uint32_t tp = fast_div(rem2, pl.mg_mb), mb = rem2 - tp * (uint32_t)MB;
     const bool divisible = pl.nb[mb * DP + dp] != 0;
     LaneC lc;
-    lc.p2pf = pl.p2p_f[mb];
     lc.nbm1 = pl.nbm1_f[mb * DP + dp];
     lc.cd = pl.cd_f[dp];
     lc.dph = pl.dph_f[dp];
     lc.xb = pl.xb_f[mb];
     // this lane's slices of the staged tables; segment j with tp index k on pool p:
     const Rec *recl = rec + mb;                 // [((j * TP + k) * ZG + p) * MB]
+    const float4 *pairm = pair + mb * Z * Z;    // transfers of this microbatch size
     const uint64_t *needl = need + mb * DP + dp;  // [(j * TP + k) * MB * DP]
     // segment 1 does not change while the outer digits advance
     const int p0 = (int)a1;
@@ -1147,8 +1163,8 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
           peak = mem1 > peak ? mem1 : peak;
           const bool q1 = (qm[(TP + t1) * ZG + p1] >> dp) & 1u;
           quota_ok = quota_ok && q1;
-          const float4 pr = pair[z0 * Z + z1];
-          acc = acc_cross(acc, r1, lc.p2pf * pr.x, lc.p2pf * pr.y, pr.z, single0, true);
+          const float4 pr = pairm[z0 * Z + z1];
+          acc = acc_cross(acc, r1, pr.x, pr.y, pr.z, single0, true);
           if (S == 3) {
             const int r3 = (int)((od >> 9) & 63u);
             const uint32_t t2 = pl.pst ? (od >> 15) : tp;
@@ -1166,8 +1182,8 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
             } else {
               quota_ok = quota_ok && ((qm[(2 * TP + t2) * ZG + p2] >> dp) & 1u);
             }
-            const float4 pr2 = pair[z1 * Z + (int)(i2.meta & 0xFFu)];
-            acc = acc_cross(acc, r2r, lc.p2pf * pr2.x, lc.p2pf * pr2.y, pr2.z, single1, false);
+            const float4 pr2 = pairm[z1 * Z + (int)(i2.meta & 0xFFu)];
+            acc = acc_cross(acc, r2r, pr2.x, pr2.y, pr2.z, single1, false);
           }
         }
         if (!quota_ok) mask |= 2u;
@@ -1193,8 +1209,8 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
   const ShapeRec sh = pl.shapes[u.shape];
   const int ZG = pl.ZG, G = pl.G, MB = pl.MB, TP = pl.TP, DP = pl.DP, Z = pl.Z, S = sh.s;
   Rec *rec = reinterpret_cast<Rec *>(lds_raw);                           // [3][TP][ZG][MB]
-  float4 *pair = reinterpret_cast<float4 *>(rec + 3 * TP * ZG * MB);     // [Z][Z]
-  PoolInfo *pinfo = reinterpret_cast<PoolInfo *>(pair + Z * Z);          // [ZG]
+  float4 *pair = reinterpret_cast<float4 *>(rec + 3 * TP * ZG * MB);     // [MB][Z][Z]
+  PoolInfo *pinfo = reinterpret_cast<PoolInfo *>(pair + MB * Z * Z);     // [ZG]
   uint64_t *need = reinterpret_cast<uint64_t *>(pinfo + ZG);             // [3][TP][MB][DP]
   uint32_t *qm = reinterpret_cast<uint32_t *>(need + 3 * TP * MB * DP);  // [3][TP][ZG]
   uint32_t *odec = qm + 3 * TP * ZG;  // [o_cnt] the outer digits of the unit, unpacked:
@@ -1232,9 +1248,9 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
     pi.meta = (uint32_t)(p / G) | (pl.h1m[p] << 8);
     pinfo[p] = pi;
   }
-  for (int i = t; i < Z * Z; i += blockDim.x) {
-    const int za = i / Z, zb = i % Z;
-    pair[i] = make_float4(pl.ibw_f[za * Z + zb], pl.ibw_f[zb * Z + za], pl.egs_f[i], 0.f);
+  for (int i = t; i < MB * Z * Z; i += blockDim.x) {  // per mb: transfer a -> b, b -> a, egress
+    const int m = i / (Z * Z), ab = i - m * Z * Z, za = ab / Z, zb = ab % Z;
+    pair[i] = make_float4(pl.tsec_f[i], pl.tsec_f[(m * Z + zb) * Z + za], pl.egs_f[ab], 0.f);
   }
   for (int i = t; i < S * TP * MB * DP; i += blockDim.x) {
     const int md = i % (MB * DP), k = (i / (MB * DP)) % TP, seg = i / (MB * DP * TP);
@@ -1244,8 +1260,8 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
     const int mb = i % MB, p = (i / MB) % ZG, k = (i / (MB * ZG)) % TP, seg = i / (MB * ZG * TP);
     const int g = p % G, z = p / G;
     const size_t sl = agg_slot(pl, u.shape, k, seg);
-    rec[i] = make_rec(pl.ta[(sl * G + g) * MB + mb], pl.smax[sl], pl.upd[sl * G + g],
-                      pl.price_f[g], pl.p2p_f[mb], pl.ibw_f[z * Z + z],
+    rec[i] = make_rec(pl.ta[(sl * G + g) * MB + mb], pl.syncz[sl * Z + z], pl.upd[sl * G + g],
+                      pl.price_f[g], pl.tsec_f[(mb * Z + z) * Z + z],
                       seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]), vals[DP + k], 0u);
   }
   __syncthreads();

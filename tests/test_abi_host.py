@@ -32,8 +32,9 @@ def test_exports_every_declared_entry_point(lib):
 
 def test_struct_layouts_match_the_header(tmp_path):
     """sizeof / offsetof as a C compiler sees the header against the ctypes mirrors."""
-    fields = {"sailor_problem": ["n_layers", "per_segment_tp", "global_batch", "mb_values",
-                                 "embed_params", "grad_bytes_per_param", "t_fwd", "egress_per_byte"],
+    fields = {"sailor_problem": ["n_layers", "per_segment_tp", "n_bw_coef", "global_batch", "mb_values",
+                                 "embed_params", "grad_bytes_per_param", "t_fwd", "egress_per_byte",
+                                 "bw_poly"],
               "sailor_result": ["index", "iter_time_s", "mask", "pp", "mb_index", "cut", "pool",
                                 "seg_tp", "seg_tp_index"],
               "sailor_constraint": ["bound", "has_bound"]}
@@ -75,6 +76,8 @@ def _create(lib, prob):
     lambda p: replace(p, dp_values=np.arange(1, 40, dtype=np.int32)),          # too many degrees
     lambda p: replace(p, mem_capacity=np.full_like(p.mem_capacity, 2 ** 63)),  # would overflow
     lambda p: replace(p, price_per_hour=p.price_per_hour * np.nan),
+    lambda p: replace(p, bw_poly=np.full((p.n_zones, p.n_zones, 2), np.inf)),  # not finite
+    lambda p: replace(p, bw_poly=np.ones((p.n_zones, p.n_zones, 9))),          # too many coefficients
 ])
 def test_malformed_problems_are_rejected(lib, mutate):
     rc, h = _create(lib, mutate(W.config1()))

@@ -109,7 +109,16 @@ PROBLEMS = {
     "tiny2_segtp": lambda: W.tiny_problem(2, n_zones=3).with_per_segment_tp(),
     "tiny4_segtp": lambda: W.tiny_problem(4, n_layers=8, n_types=3, seg3_max_pp=8).with_per_segment_tp(),
     "onepool_segtp": lambda: make_problem(n_layers=4, max_segments=3, seg3_max_pp=4).with_per_segment_tp(),
+    # message-size dependent link bandwidth
+    "cfg2_bwpoly": lambda: _with_profile(W.config2()),
+    "tiny2_bwpoly": lambda: _with_profile(W.tiny_problem(2, n_zones=3)),
+    "tiny4_segtp_bwpoly": lambda: _with_profile(
+        W.tiny_problem(4, n_layers=8, n_types=3, seg3_max_pp=8).with_per_segment_tp()),
 }
+
+
+def _with_profile(prob, seed=6):
+    return prob.with_bw_poly(W.bandwidth_poly(prob, seed))
 
 
 @pytest.fixture(scope="module", params=sorted(PROBLEMS))
@@ -310,6 +319,8 @@ def test_random_small_problems(torch_cuda, seed):
                           with_egress=bool(rng.integers(0, 2)))
     prob.global_batch = int(rng.choice([8, 12, 16, 24]))
     prob.per_segment_tp = bool(seed % 2)
+    if seed % 3 == 0:
+        prob = prob.with_bw_poly(W.bandwidth_poly(prob, seed))
     avail = prob.avail.copy()
     avail[rng.random(avail.shape) < 0.25] = 0
     prob = prob.with_avail(avail)

@@ -226,3 +226,25 @@ def test_fourth_workload_with_per_segment_tp(torch_cuda):
         check_topk(plan.topk(64, objective=MAX_THROUGHPUT, stream=stream), top, MAX_THROUGHPUT)
     finally:
         plan.destroy()
+
+
+# ------------------------------------------------------------------ message-size dependent links
+
+def test_third_workload_with_link_profiles(torch_cuda):
+    base = W.config3()
+    prob = base.with_bw_poly(W.bandwidth_poly(base))
+    plan, orc = _plan(prob), Oracle(prob)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        n = orc.num_candidates
+        want = orc.eval_batch(n_threads=THREADS)
+        worst = assert_eval_parity(gpu_eval(torch_cuda, plan, 0, n), want)
+        assert worst < 2e-6  # the error budget the selection relies on
+        for objective in (MAX_THROUGHPUT, MIN_COST):
+            best, top = oracle_best_and_topk(orc, 64, objective)
+            check_result(plan.best_plan(objective=objective, stream=stream), best, orc)
+            check_topk(plan.topk(64, objective=objective, stream=stream), top, objective)
+        slower = orc.best(objective=MAX_THROUGHPUT, n_threads=THREADS).iter_time
+        assert slower >= Oracle(base).best(objective=MAX_THROUGHPUT, n_threads=THREADS).iter_time
+    finally:
+        plan.destroy()
