@@ -11,7 +11,7 @@ import ctypes as C
 import os
 import subprocess
 from dataclasses import dataclass
-from typing import List, Optional
+from typing import List, Optional, Tuple
 
 import numpy as np
 
@@ -111,6 +111,8 @@ def _load():
         lib.so_encode.argtypes = [C.c_void_p, C.POINTER(_Config), C.POINTER(C.c_uint64)]
         lib.so_enumerate.restype = C.c_uint64
         lib.so_enumerate.argtypes = [C.c_void_p, C.POINTER(_Config), C.c_uint64]
+        lib.so_simulate_1f1b.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_double),
+                                         C.POINTER(C.c_double)]
         lib.so_eval_one.argtypes = [C.c_void_p, C.c_uint64, C.c_int, C.c_int, C.c_double,
                                     C.POINTER(_Eval)]
         lib.so_eval_batch.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_int,
@@ -237,6 +239,13 @@ class Oracle:
         if rc != 0:
             raise IndexError(index)
         return _ev(e)
+
+    def simulate_1f1b(self, index: int) -> Tuple[float, float]:
+        """(event-by-event makespan, closed-form T_pp) of one pipeline of the plan."""
+        a, b = C.c_double(), C.c_double()
+        if self._lib.so_simulate_1f1b(self._ctx, index, C.byref(a), C.byref(b)) < 0:
+            raise IndexError(index)
+        return a.value, b.value
 
     def eval_batch(self, first: int = 0, count: Optional[int] = None, indices=None,
                    objective: int = MAX_THROUGHPUT, bound: Optional[float] = None,

@@ -398,6 +398,106 @@ int so_eval_one(const so_ctx *c, uint64_t index, int objective, int has_bound, d
   return 0;
 }
 
+/* ---- discrete-event 1F1B schedule of one pipeline -------------------------------------- */
+
+/* The op a stage runs at position pos of its 1F1B order (warm-up forwards, one forward /
+ * one backward in turn, the remaining backwards): kind 0 = forward, 1 = backward. */
+static void op_at(int P, int64_t M, int i, int64_t pos, int *kind, int64_t *m) {
+  int64_t w = (P - 1 - i) < M ? (P - 1 - i) : M;
+  if (pos < w) { *kind = 0; *m = pos; return; }
+  int64_t q = pos - w;
+  if (q < 2 * (M - w)) {
+    if (q % 2 == 0) { *kind = 0; *m = w + q / 2; }
+    else { *kind = 1; *m = q / 2; }
+    return;
+  }
+  *kind = 1;
+  *m = (M - w) + (q - 2 * (M - w));
+}
+
+/* Makespan of the 1F1B schedule of one pipeline of the plan, event by event (Sec. 4.3 names
+ * the warm-up, steady and cool-down phases; the closed form of Sec. 4.2.2 summarises them).
+ * A forward of stage i takes its layers' forward time plus the transfer of the activations
+ * to stage i + 1, a backward its layers' backward time plus the transfer of the gradients to
+ * stage i - 1 (transfers are not overlapped, as in the closed form).  A forward starts when
+ * the stage is free and the previous stage's forward of that microbatch has ended, a backward
+ * when the next stage's backward has ended (the last stage: its own forward).
+ * t_closed receives sum_i t_i + (N_b - 1) max_i t_i of the same stage times.
+ * Returns 0, -1 for a bad index, 1 when the batch does not divide (outputs +inf). */
+int so_simulate_1f1b(const so_ctx *c, uint64_t index, double *t_event, double *t_closed) {
+  const so_problem *p = &c->p;
+  so_config g;
+  if (so_decode(c, index, &g) != 0) return -1;
+  const int P = g.pp, G = p->n_types;
+  const int32_t *nl = partition_row(c, &g);
+  if (p->global_batch % ((int64_t)g.dp * g.mb) != 0) {
+    *t_event = INFINITY;
+    *t_closed = INFINITY;
+    return 1;
+  }
+  const int64_t M = p->global_batch / ((int64_t)g.dp * g.mb);
+  const double p2p = (double)p->p2p_bytes[g.mb_idx];
+  double fdur[SO_MAX_STAGES], bdur[SO_MAX_STAGES];
+  int zone_of[SO_MAX_STAGES], type_of[SO_MAX_STAGES], tpi_of[SO_MAX_STAGES];
+  for (int i = 0; i < P; ++i) {
+    int seg = (i < g.cut[0]) ? 0 : (i < g.cut[1]) ? 1 : 2;
+    type_of[i] = g.pool[seg] % G;
+    zone_of[i] = g.pool[seg] / G;
+    tpi_of[i] = g.seg_tp_idx[seg];
+  }
+  int layer = 0;
+  double sum_t = 0.0, max_t = 0.0;
+  for (int i = 0; i < P; ++i) {
+    double f = layer_time_sum(p, p->t_fwd, type_of[i], g.mb_idx, tpi_of[i], layer, nl[i]);
+    double b = layer_time_sum(p, p->t_bwd, type_of[i], g.mb_idx, tpi_of[i], layer, nl[i]);
+    double send_f = (i < P - 1) ? p2p / link_bandwidth(p, zone_of[i], zone_of[i + 1], p2p) : 0.0;
+    double send_b = (i > 0) ? p2p / link_bandwidth(p, zone_of[i], zone_of[i - 1], p2p) : 0.0;
+    fdur[i] = f + send_f;
+    bdur[i] = b + send_b;
+    double t = f + b + (send_f + send_b);
+    sum_t += t;
+    if (t > max_t) max_t = t;
+    layer += nl[i];
+  }
+  *t_closed = sum_t + (double)(M - 1) * max_t;
+
+  double *fdone = (double *)malloc(sizeof(double) * (size_t)P * (size_t)M * 2);
+  if (!fdone) return -1;
+  double *bdone = fdone + (size_t)P * (size_t)M;
+  for (size_t k = 0; k < (size_t)P * (size_t)M * 2; ++k) fdone[k] = -1.0; /* not yet run */
+  int64_t pos[SO_MAX_STAGES];
+  double free_at[SO_MAX_STAGES];
+  for (int i = 0; i < P; ++i) { pos[i] = 0; free_at[i] = 0.0; }
+  int progressed = 1;
+  while (progressed) {
+    progressed = 0;
+    for (int i = 0; i < P; ++i) {
+      while (pos[i] < 2 * M) {
+        int kind;
+        int64_t m;
+        op_at(P, M, i, pos[i], &kind, &m);
+        double dep;
+        if (kind == 0) dep = (i == 0) ? 0.0 : fdone[(size_t)(i - 1) * M + m];
+        else dep = (i == P - 1) ? fdone[(size_t)i * M + m] : bdone[(size_t)(i + 1) * M + m];
+        if (dep < 0.0) break; /* the neighbour has not produced it yet */
+        double start = free_at[i] > dep ? free_at[i] : dep;
+        free_at[i] = start + (kind == 0 ? fdur[i] : bdur[i]);
+        (kind == 0 ? fdone : bdone)[(size_t)i * M + m] = free_at[i];
+        pos[i] += 1;
+        progressed = 1;
+      }
+    }
+  }
+  double end = 0.0;
+  for (int i = 0; i < P; ++i) {
+    if (pos[i] != 2 * M) { free(fdone); return -1; } /* cannot happen: the order is deadlock-free */
+    if (free_at[i] > end) end = free_at[i];
+  }
+  free(fdone);
+  *t_event = end;
+  return 0;
+}
+
 static double key_of(const so_eval *e, int objective) {
   return objective == SO_MAX_THROUGHPUT ? e->iter_time : e->cost;
 }

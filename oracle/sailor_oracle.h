@@ -111,6 +111,11 @@ uint64_t so_enumerate(const so_ctx *c, so_config *out, uint64_t max_out);
 /* one candidate; has_bound = 0 ignores bound */
 int so_eval_one(const so_ctx *c, uint64_t index, int objective, int has_bound, double bound,
                 so_eval *out);
+/* Discrete-event 1F1B schedule of one pipeline of the plan (the three phases Sec. 4.3 names,
+ * op by op) beside the closed form sum_i t_i + (N_b - 1) max_i t_i on the same stage times.
+ * 0 ok, -1 bad index, 1 batch not divisible (both outputs +inf). */
+int so_simulate_1f1b(const so_ctx *c, uint64_t index, double *t_event, double *t_closed);
+
 /* indices == NULL means first .. first+count-1 ; any output pointer may be NULL */
 int so_eval_batch(const so_ctx *c, uint64_t first, uint64_t count, const uint64_t *indices,
                   int objective, int has_bound, double bound, double *time, double *cost,
