@@ -132,6 +132,24 @@ def main() -> int:
     top1_index = int(buf[0].index)
     counts = plan.last_counts()
 
+    # the selected plans' 1F1B schedules event by event, against the closed form the
+    # evaluator uses for T_pp (outside the timed region)
+    import numpy as np
+    top_idx = np.array([int(buf[j].index) for j in range(K)], dtype=np.uint64)
+    d_idx = torch.from_numpy(top_idx.view(np.int64)).to("cuda:0")
+    d_ev = torch.empty(K, dtype=torch.float64, device="cuda:0")
+    d_cl = torch.empty(K, dtype=torch.float64, device="cuda:0")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(3):
+        e0.record()
+        plan.simulate_1f1b(K, d_idx, d_ev, d_cl, stream)
+        e1.record()
+        torch.cuda.synchronize()
+    gap = (d_cl / d_ev - 1.0).cpu().numpy()
+    event_sched = {"plans": K, "ms": e0.elapsed_time(e1),
+                   "closed_over_event_minus_1": {"min": float(gap.min()), "mean": float(gap.mean()),
+                                                 "max": float(gap.max())}}
+
     # device time of all kernels of a step (events around the whole call), outside the
     # timed region
     plan.set_timing(2)
@@ -166,7 +184,6 @@ def main() -> int:
 
     # availability stream: 64 snapshots of the 4-zone x 3-type cluster, a full re-plan
     # (6 791 040 candidates) at each: latency of set_avail + best_plan
-    import numpy as np
     prob5 = workloads.config3()
     plan5 = Plan(prob5)
     lat = []
@@ -235,7 +252,7 @@ def main() -> int:
                   "eval_batch_candidates_per_s": n / (eval_ms * 1e-3),
                   "eval_batch_output_GBps": 20.0 * n / (eval_ms * 1e-3) / 1e9,
                   "plan_create_ms": create_ms, "replan_stream": replan,
-                  "per_segment_tp": segtp, "survivors_refined_valid": list(counts), "best_index": best.index,
+                  "per_segment_tp": segtp, "event_schedule_top64": event_sched, "survivors_refined_valid": list(counts), "best_index": best.index,
                   "top1_index": top1_index},
     }
     if not args.no_cpu_baseline:

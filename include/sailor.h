@@ -230,6 +230,24 @@ sailor_status sailor_plan_set_timing(sailor_plan *plan, int32_t mode);
  * SAILOR_EINVAL if the last call recorded nothing. */
 sailor_status sailor_plan_last_timing(sailor_plan *plan, float *total_ms, float *kernel_ms);
 
+/* The 1F1B schedule of one pipeline of each listed plan, op by op (warm-up, steady and
+ * cool-down phases, Sec. 4.3), beside the closed form sum_i t_i + (N_b - 1) max_i t_i that the
+ * evaluator uses for T_pp (Sec. 4.2.2), on the same stage times.  A forward of stage i takes
+ * its layers' forward time plus the transfer to stage i + 1, a backward its backward time plus
+ * the transfer to stage i - 1; a forward waits for the previous stage's forward of the same
+ * microbatch, a backward for the next stage's backward.  Quantifies the closed form's error
+ * for plans that a selection returned.
+ *   d_indices  device, [count] candidate indices
+ *   d_event    device, [count] fp64 makespan of the schedule, or NULL
+ *   d_closed   device, [count] fp64 closed form, or NULL (not both NULL)
+ * A plan whose batch does not divide yields +inf, an index outside [0, N) NaN.  Work per plan
+ * is about 2 (N_b + P) dependent steps of one workgroup.  Asynchronous on hip_stream, except
+ * for pipelines deeper than about 60 stages, whose working set is allocated, used and freed
+ * inside the call (it then synchronises the stream).
+ * SAILOR_ERANGE: count > 2^31 - 1, or more than 2^24 microbatches per pipeline. */
+sailor_status sailor_simulate_1f1b(sailor_plan *plan, uint64_t count, const uint64_t *d_indices,
+                                   double *d_event, double *d_closed, void *hip_stream);
+
 /* Sizes of the intermediate lists of the last successful sailor_best_plan / sailor_topk
  * (the selection of Sec. 4.2 runs as fp32 scan -> survivors -> fp64 re-evaluation):
  * candidates kept by the fp32 threshold, candidates re-evaluated in fp64, and how many of

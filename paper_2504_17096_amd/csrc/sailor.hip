@@ -28,6 +28,8 @@ constexpr uint32_t kListUnits = 256;     // and the units it visits per round
 constexpr uint32_t kEvalUnitTarget = 16384;  // candidates per workgroup of the range evaluation
 constexpr unsigned kEvalRowsThreads = 512;
 constexpr size_t kEvalRowsMaxLds = 64 * 1024;  // above this the range form evaluates lane by lane
+constexpr size_t kSimMaxLds = 56 * 1024;       // rings of the event-by-event schedule beyond this
+constexpr uint64_t kSimBatch = 64;             // live in device memory, for so many candidates at once
 
 #define HIP_TRY(expr)                                                              \
   do {                                                                             \
@@ -729,6 +731,8 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(ar.alloc(&d.divis, MB));
   CREATE_TRY(ar.alloc(&d.st_params, RS));
   CREATE_TRY(ar.alloc(&d.st_c, RS * G * MB * TP));
+  CREATE_TRY(ar.alloc(&d.st_f, RS * G * MB * TP));
+  CREATE_TRY(ar.alloc(&d.st_b, RS * G * MB * TP));
   CREATE_TRY(ar.alloc(&d.st_u, RS * G * TP));
   const size_t slots = NS * TP * 3;
   CREATE_TRY(ar.alloc(&d.ta, slots * G * MB));
@@ -965,6 +969,57 @@ sailor_status sailor_plan_last_timing(sailor_plan *pl, float *total_ms, float *k
   }
   if (total_ms) *total_ms = t;
   if (kernel_ms) *kernel_ms = s;
+  return SAILOR_OK;
+}
+
+sailor_status sailor_simulate_1f1b(sailor_plan *pl, uint64_t count, const uint64_t *d_indices,
+                                   double *d_event, double *d_closed, void *hip_stream) {
+  if (!pl) return SAILOR_EINVAL;
+  if (count == 0) return SAILOR_OK;
+  if (!d_indices || (!d_event && !d_closed)) return SAILOR_EINVAL;
+  if (count > 0x7fffffffu) return SAILOR_ERANGE;
+  // microbatches per pipeline are counted in 32-bit integers
+  if (pl->dev.B / ((int64_t)pl->dpv[0] * pl->mbv[0]) > (1 << 24)) return SAILOR_ERANGE;
+  HIP_TRY(hipSetDevice(pl->device));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int p_max = pl->dev.P_max;
+  int ring = 2;
+  while (ring <= p_max) ring *= 2;
+  const size_t ring_bytes = (size_t)2 * p_max * ring * sizeof(double);  // per candidate
+  const unsigned threads = 64u * (unsigned)((p_max + 63) / 64);
+  SimArgs a{};
+  a.ring = ring;
+  a.p_max = p_max;
+  if (ring_bytes <= kSimMaxLds) {
+    a.count = count;
+    a.indices = d_indices;
+    a.t_event = d_event;
+    a.t_closed = d_closed;
+    k_sim_1f1b<<<(unsigned)count, threads, ring_bytes, st>>>(pl->dev, a);
+    HIP_TRY(hipGetLastError());
+    return SAILOR_OK;
+  }
+  // deep pipelines: the rings do not fit LDS and live in device memory, a batch at a time
+  const uint64_t batch = std::min<uint64_t>(count, kSimBatch);
+  double *rings = nullptr;
+  if (hipMalloc(reinterpret_cast<void **>(&rings), batch * ring_bytes) != hipSuccess)
+    return SAILOR_ENOMEM;
+  a.rings = rings;
+  hipError_t err = hipSuccess;
+  for (uint64_t off = 0; off < count && err == hipSuccess; off += batch) {
+    a.count = std::min<uint64_t>(batch, count - off);
+    a.indices = d_indices + off;
+    a.t_event = d_event ? d_event + off : nullptr;
+    a.t_closed = d_closed ? d_closed + off : nullptr;
+    k_sim_1f1b<<<(unsigned)a.count, threads, 0, st>>>(pl->dev, a);
+    err = hipGetLastError();
+  }
+  if (err == hipSuccess) err = hipStreamSynchronize(st);  // the rings are freed below
+  (void)hipFree(rings);
+  if (err != hipSuccess) {
+    std::fprintf(stderr, "sailor: event schedule failed: %s\n", hipGetErrorString(err));
+    return SAILOR_EDEVICE;
+  }
   return SAILOR_OK;
 }
 

@@ -118,6 +118,7 @@ struct DevPlan {
   const int32_t *st_first;     // first layer
   uint64_t *st_params;         // parameters incl. embedding / head
   double *st_c;                // [rs][G][MB][TP] sum of fwd + bwd layer times
+  double *st_f, *st_b;         // [rs][G][MB][TP] the two sums apart (event-by-event schedule)
   double *st_u;                // [rs][G][TP] sum of update times
   // candidate space
   const ShapeRec *shapes;

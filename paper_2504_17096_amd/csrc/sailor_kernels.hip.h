@@ -9,6 +9,7 @@
 //            k_pick_best / k_rank_topk   final selection
 //            k_eval_rows / k_eval_direct   per-candidate outputs for sailor_eval_batch
 //                             (index ranges / index lists)
+// Beside it: k_sim_1f1b       event-by-event 1F1B schedule of listed plans
 //
 // The simulator arithmetic follows Sailor, Sec. 4.3 (memory, iteration time, cost);
 // T_pp = sum of stage times + (N_b - 1) * straggler is the 1F1B composition of
@@ -125,6 +126,8 @@ __global__ void k_stage_tables(DevPlan pl, StageArgs a) {
       for (int l = first; l < first + n; ++l) { f += rf[l]; b += rb[l]; }
     }
     pl.st_c[(size_t)rs * G * MB * TP + i] = f + b;
+    pl.st_f[(size_t)rs * G * MB * TP + i] = f;
+    pl.st_b[(size_t)rs * G * MB * TP + i] = b;
   }
   for (int i = threadIdx.x; i < G * TP; i += blockDim.x) {
     double u = 0.0;
@@ -1004,6 +1007,140 @@ __global__ __launch_bounds__(256) void k_rank_topk(const RefRec *ref, uint32_t r
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) before += __shfl_xor(before, off);
     if (lane == 0 && before < k) out[before] = r;
+  }
+}
+
+// ------------------------------------------------------------------ event-by-event 1F1B
+
+struct SimArgs {
+  uint64_t count;
+  const uint64_t *indices;
+  double *t_event, *t_closed;  // either may be NULL
+  double *rings;               // NULL: the rings live in LDS; else [count][2][P_max][ring] doubles
+  int ring;                    // slots per stage, a power of two > P_max
+  int p_max;
+};
+
+// The op a stage runs at position pos of its 1F1B order: warm-up forwards, then one forward
+// and one backward in turn, then the remaining backwards.  Returns true for a backward.
+__device__ __forceinline__ bool sim_op_at(int P, int M, int i, int pos, int &m) {
+  const int w = min(P - 1 - i, M);
+  if (pos < w) { m = pos; return false; }
+  const int q = pos - w;
+  if (q < 2 * (M - w)) {
+    m = (q & 1) ? (q >> 1) : w + (q >> 1);
+    return (q & 1) != 0;
+  }
+  m = (M - w) + (q - 2 * (M - w));
+  return true;
+}
+
+// The 1F1B schedule of one pipeline of a plan, op by op (warm-up, steady and cool-down phases,
+// Sec. 4.3), beside the closed form of Sec. 4.2.2 on the same stage times.  One workgroup per
+// candidate, one thread per stage.  A forward of stage i takes its layers' forward time plus the
+// transfer to stage i + 1, a backward its backward time plus the transfer to stage i - 1; a
+// forward waits for the previous stage's forward of the same microbatch, a backward for the next
+// stage's backward.  The schedule advances in rounds: in a round every stage runs its next op if
+// what it waits for was finished in an earlier round.  End times travel between neighbouring
+// stages through rings indexed by microbatch; a producer is never more than P ops ahead of its
+// consumer, so `ring` > P slots per stage suffice.  At most 2 (N_b + P) rounds are needed.
+__global__ __launch_bounds__(256) void k_sim_1f1b(DevPlan pl, SimArgs a) {
+  extern __shared__ double sim_lds[];
+  __shared__ double s_t[kMaxStages];
+  __shared__ int s_fc[kMaxStages], s_bc[kMaxStages];  // forwards / backwards a stage has finished
+  __shared__ double s_red[4];
+  const uint64_t ci = blockIdx.x;
+  if (ci >= a.count) return;
+  const int i = threadIdx.x;
+  const uint64_t idx = a.indices[ci];
+  Cand c;
+  if (!decode_index(pl, idx, c)) {  // uniform over the workgroup
+    if (i == 0) {
+      if (a.t_event) a.t_event[ci] = __builtin_nan("");
+      if (a.t_closed) a.t_closed[ci] = __builtin_nan("");
+    }
+    return;
+  }
+  const int P = c.P, G = pl.G, Z = pl.Z, MB = pl.MB, TP = pl.TP;
+  const int M = pl.nb[c.mb * pl.DP + c.dp];
+  if (M == 0) {  // the batch does not divide
+    if (i == 0) {
+      if (a.t_event) a.t_event[ci] = __builtin_huge_val();
+      if (a.t_closed) a.t_closed[ci] = __builtin_huge_val();
+    }
+    return;
+  }
+  const ShapeRec sh = pl.shapes[c.shape];
+  const bool mine = i < P;
+  double fdur = 0.0, bdur = 0.0;
+  if (mine) {
+    const int seg = i < c.k1 ? 0 : (i < c.k2 ? 1 : 2);
+    const int g = c.a[seg] % G, z = c.a[seg] / G, k = c.tp[seg];
+    const size_t at = (((size_t)(sh.row_stage + i) * G + g) * MB + c.mb) * TP + k;
+    const double p2p = (double)pl.p2p[c.mb];
+    const double *bwp = pl.bwp + c.mb * Z * Z;
+    double send_f = 0.0, send_b = 0.0;
+    if (i < P - 1) {
+      const int sn = (i + 1) < c.k1 ? 0 : ((i + 1) < c.k2 ? 1 : 2);
+      send_f = p2p / bwp[z * Z + c.a[sn] / G];
+    }
+    if (i > 0) {
+      const int sp = (i - 1) < c.k1 ? 0 : ((i - 1) < c.k2 ? 1 : 2);
+      send_b = p2p / bwp[z * Z + c.a[sp] / G];
+    }
+    const double f = pl.st_f[at], b = pl.st_b[at];
+    fdur = f + send_f;
+    bdur = b + send_b;
+    s_t[i] = f + b + (send_f + send_b);
+    s_fc[i] = 0;
+    s_bc[i] = 0;
+  }
+  __syncthreads();
+  if (i == 0 && a.t_closed) {  // sums in stage order
+    double sum_t = 0.0, max_t = 0.0;
+    for (int j = 0; j < P; ++j) {
+      sum_t += s_t[j];
+      max_t = fmax(max_t, s_t[j]);
+    }
+    a.t_closed[ci] = sum_t + (double)(M - 1) * max_t;
+  }
+  double *ring_f = a.rings ? a.rings + ci * 2 * (size_t)a.p_max * a.ring : sim_lds;
+  double *ring_b = ring_f + (size_t)a.p_max * a.ring;
+  const int rmask = a.ring - 1;
+  int pos = 0;
+  double free_at = 0.0;
+  for (int round = 0; round < 2 * (M + P) + 4; ++round) {  // the bound is never reached
+    bool ready = false, bwd = false;
+    int m = 0;
+    double dep = 0.0;
+    if (mine && pos < 2 * M) {
+      bwd = sim_op_at(P, M, i, pos, m);
+      if (!bwd) {
+        if (i == 0) ready = true;
+        else if (s_fc[i - 1] > m) { ready = true; dep = ring_f[(size_t)(i - 1) * a.ring + (m & rmask)]; }
+      } else {
+        if (i == P - 1) { ready = true; dep = ring_f[(size_t)i * a.ring + (m & rmask)]; }
+        else if (s_bc[i + 1] > m) { ready = true; dep = ring_b[(size_t)(i + 1) * a.ring + (m & rmask)]; }
+      }
+    }
+    __syncthreads();  // every stage has read before any stage writes
+    if (ready) {
+      const double start = fmax(free_at, dep);
+      free_at = start + (bwd ? bdur : fdur);
+      if (bwd) { ring_b[(size_t)i * a.ring + (m & rmask)] = free_at; s_bc[i] += 1; }
+      else { ring_f[(size_t)i * a.ring + (m & rmask)] = free_at; s_fc[i] += 1; }
+      pos += 1;
+    }
+    if (!__syncthreads_or(ready ? 1 : 0)) break;  // nothing moved: every stage is done
+  }
+  // makespan: the latest stage
+  double end = mine ? free_at : 0.0;
+  end = wave_max_f64(end);
+  if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = end;
+  __syncthreads();
+  if (i == 0 && a.t_event) {
+    for (int w = 1; w < (int)(blockDim.x >> 6); ++w) end = fmax(end, s_red[w]);
+    a.t_event[ci] = end;
   }
 }
 

@@ -1,0 +1,107 @@
+"""Parity of the event-by-event 1F1B schedule on the device (sailor_simulate_1f1b) with the
+oracle's: fp64 on both sides, the same sequence of max / add per op, so the bar is 1e-12."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle.oracle import MAX_THROUGHPUT, Oracle
+from paper_2504_17096_amd import workloads as W
+from tests.helpers import make_problem
+
+pytestmark = pytest.mark.gpu
+REL = 1e-12
+
+
+def _plan(prob):
+    from paper_2504_17096_amd.binding import Plan
+    return Plan(prob)
+
+
+def gpu_sim(torch, plan, idx):
+    d_idx = torch.from_numpy(np.asarray(idx, dtype=np.uint64).view(np.int64)).to("cuda:0")
+    ev = torch.empty(len(idx), dtype=torch.float64, device="cuda:0")
+    cl = torch.empty(len(idx), dtype=torch.float64, device="cuda:0")
+    plan.simulate_1f1b(len(idx), d_idx, ev, cl, stream=torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    return ev.cpu().numpy(), cl.cpu().numpy()
+
+
+def check(torch, plan, orc, idx):
+    ev, cl = gpu_sim(torch, plan, idx)
+    for j, c in enumerate(idx):
+        we, wc = orc.simulate_1f1b(int(c))
+        if math.isinf(we):
+            assert math.isinf(ev[j]) and math.isinf(cl[j])
+        else:
+            assert ev[j] == pytest.approx(we, rel=REL), (int(c), ev[j], we)
+            assert cl[j] == pytest.approx(wc, rel=REL), (int(c), cl[j], wc)
+    return ev, cl
+
+
+@pytest.mark.parametrize("make", [
+    lambda: W.tiny_problem(1),
+    lambda: W.tiny_problem(3, uniform_layers=True),
+    lambda: W.tiny_problem(4, n_layers=8, n_types=3, seg3_max_pp=8).with_per_segment_tp(),
+    lambda: (lambda p: p.with_bw_poly(W.bandwidth_poly(p)))(W.tiny_problem(2, n_zones=3)),
+])
+def test_small_spaces(torch_cuda, make):
+    prob = make()
+    plan, orc = _plan(prob), Oracle(prob)
+    try:
+        n = orc.num_candidates
+        idx = np.arange(n) if n <= 6000 else np.random.default_rng(1).integers(0, n, 6000)
+        check(torch_cuda, plan, orc, idx)
+    finally:
+        plan.destroy()
+
+
+def test_second_workload_samples_and_bad_indices(torch_cuda):
+    prob = W.config2()
+    plan, orc = _plan(prob), Oracle(prob)
+    try:
+        n = orc.num_candidates
+        idx = np.random.default_rng(2).integers(0, n, 3000)
+        check(torch_cuda, plan, orc, idx)
+        ev, cl = gpu_sim(torch_cuda, plan, [0, n, n - 1, 2 ** 40])
+        assert np.isnan(ev[1]) and np.isnan(cl[1]) and np.isnan(ev[3])
+        assert ev[0] == pytest.approx(orc.simulate_1f1b(0)[0], rel=REL)
+        plan.simulate_1f1b(0, None)  # nothing to do
+    finally:
+        plan.destroy()
+
+
+def test_fourth_workload_selected_plans(torch_cuda):
+    # up to 2 048 microbatches on 48 stages; the plans a selection returns plus random ones
+    prob = W.config4()
+    plan, orc = _plan(prob), Oracle(prob)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        top = plan.topk(64, objective=MAX_THROUGHPUT, stream=stream)
+        idx = [r.index for r in top] + np.random.default_rng(3).integers(0, orc.num_candidates, 300).tolist()
+        ev, cl = check(torch_cuda, plan, orc, idx)
+        fin = np.isfinite(ev)
+        assert np.all(cl[fin] / ev[fin] < 1.5) and np.all(cl[fin] / ev[fin] > 0.5)
+        # the closed form is what the evaluator reports as T_pp: T_iter of a selected plan is
+        # at least as large
+        for r, c in zip(top, cl[:64]):
+            assert r.iter_time_s >= c * (1 - 1e-12)
+    finally:
+        plan.destroy()
+
+
+def test_deep_pipelines_keep_their_rings_in_device_memory(torch_cuda):
+    # 96 stages: the per-stage rings exceed LDS, the call allocates them (and synchronises)
+    rng = np.random.default_rng(4)
+    L = 96
+    prob = make_problem(n_layers=L, n_types=2, n_zones=2, mb_list=(1, 2), tp_list=(1,), dp_list=(1, 2),
+                        pp_list=[1, 32, 96], global_batch=48, max_segments=2, uniform_layers=False,
+                        t_fwd=rng.uniform(0.5e-3, 2e-3, (2, 2, 1, L)), t_bwd=rng.uniform(1e-3, 4e-3, (2, 2, 1, L)),
+                        p2p=3_000_000, bw=np.array([[1e10, 1e9], [2e9, 1e10]]), layer_params=1000)
+    plan, orc = _plan(prob), Oracle(prob)
+    try:
+        n = orc.num_candidates
+        idx = np.random.default_rng(5).integers(0, n, 150)  # more than one batch of 64
+        check(torch_cuda, plan, orc, idx)
+    finally:
+        plan.destroy()
