@@ -62,6 +62,8 @@ struct SurvRec {        // candidate kept for the fp64 re-evaluation
   uint64_t idx;
   float key;            // fp32 key; +inf when only loosely inside the constraint
   float key_loose;      // fp32 key
+  uint32_t shape;       // the candidate's shape, known to the pass that kept it
+  uint32_t pad;
 };
 
 struct RefRec {         // fp64 re-evaluation of one candidate

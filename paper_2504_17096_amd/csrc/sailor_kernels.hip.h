@@ -365,7 +365,7 @@ __global__ void k_init_counters(uint32_t *c, int n) {
 // One candidate of the scan: update the running minima, or append it to the survivors.
 template <int MODE, int OBJ, bool HASB>
 __device__ __forceinline__ void visit(const ScanArgs &a, float T, float C, bool feas, float tau,
-                                      uint64_t idx, float &ms, float &ml) {
+                                      uint64_t idx, uint32_t shape, float &ms, float &ml) {
   const float key = OBJ == 0 ? T : C;
   const float con = OBJ == 0 ? C : T;
   if (MODE == MODE_SCAN) {
@@ -394,6 +394,8 @@ __device__ __forceinline__ void visit(const ScanArgs &a, float T, float C, bool 
         sv.idx = idx;
         sv.key = strict ? key : kPosInf;
         sv.key_loose = key;
+        sv.shape = shape;
+        sv.pad = 0;
         a.surv[slot] = sv;
       }
     }
@@ -476,7 +478,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
       if (S == 1) {
         float T, C;
         acc_finish(A0, it.lc, T, C);
-        visit<MODE, OBJ, HASB>(a, T, C, b0 != 0, tau, idx0, ms, ml);
+        visit<MODE, OBJ, HASB>(a, T, C, b0 != 0, tau, idx0, u.shape, ms, ml);
         continue;
       }
       int z2 = u.o_lo / G, g2 = u.o_lo % G;
@@ -492,7 +494,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
           float T, C;
           acc_finish(A1, it.lc, T, C);
           visit<MODE, OBJ, HASB>(a, T, C, b1 != 0, tau,
-                                 idx0 + (uint64_t)pl.inner * (uint64_t)rel2, ms, ml);
+                                 idx0 + (uint64_t)pl.inner * (uint64_t)rel2, u.shape, ms, ml);
         }
         if (++g2 == G) { g2 = 0; ++z2; }
       }
@@ -533,7 +535,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
               float T, C;
               acc_finish(A2, it.lc, T, C);
               visit<MODE, OBJ, HASB>(a, T, C, b2 != 0, tau,
-                                     idx0 + pl.stride3 * (uint64_t)rel3, ms, ml);
+                                     idx0 + pl.stride3 * (uint64_t)rel3, u.shape, ms, ml);
             }
           }
           if (++g3 == G) { g3 = 0; ++z3; }
@@ -744,18 +746,16 @@ struct Cand {
   int k1, k2;
 };
 
-__device__ __forceinline__ bool decode_index(const DevPlan &pl, uint64_t idx, Cand &c) {
-  if (idx >= pl.N) return false;
-  int b = 0;
-  for (int i = 0; i < pl.n_blocks; ++i)
-    if (idx >= pl.blocks[i].off) b = i;  // blocks are ordered and non-empty
-  const BlockRec blk = pl.blocks[b];
-  const uint64_t r = idx - blk.off;
-  const uint32_t sl = (uint32_t)(r / blk.shape_size);
-  const uint64_t rem = r % blk.shape_size;
-  c.shape = blk.first_shape + sl;
-  c.P = blk.P;
-  c.s = blk.s;
+// The digits of candidate idx, which lies in the given shape.
+__device__ __forceinline__ void decode_in_shape(const DevPlan &pl, uint32_t shape, uint64_t idx,
+                                                Cand &c) {
+  const ShapeRec sh = pl.shapes[shape];
+  const uint64_t rem = idx - sh.base;
+  c.shape = shape;
+  c.P = sh.P;
+  c.s = sh.s;
+  c.k1 = sh.k1;
+  c.k2 = sh.k2;
   const uint32_t in = (uint32_t)(rem % pl.inner);
   uint32_t o = (uint32_t)(rem / pl.inner);
   c.mb = in % pl.MB;
@@ -773,9 +773,16 @@ __device__ __forceinline__ bool decode_index(const DevPlan &pl, uint64_t idx, Ca
     o /= (pl.ZG - 1);
     if (pl.pst) c.tp[2] = (int)o;
   }
-  const ShapeRec sh = pl.shapes[c.shape];
-  c.k1 = sh.k1;
-  c.k2 = sh.k2;
+}
+
+// Any index: find its block, then its shape.
+__device__ __forceinline__ bool decode_index(const DevPlan &pl, uint64_t idx, Cand &c) {
+  if (idx >= pl.N) return false;
+  int b = 0;
+  for (int i = 0; i < pl.n_blocks; ++i)
+    if (idx >= pl.blocks[i].off) b = i;  // blocks are ordered and non-empty
+  const BlockRec blk = pl.blocks[b];
+  decode_in_shape(pl, blk.first_shape + (uint32_t)((idx - blk.off) / blk.shape_size), idx, c);
   return true;
 }
 
@@ -909,7 +916,7 @@ __global__ __launch_bounds__(kRefineWaves * 64) void k_refine(DevPlan pl, Refine
     const SurvRec sv = a.surv[i];
     if (!(sv.key_loose <= tau)) continue;
     Cand c;
-    if (!decode_index(pl, sv.idx, c)) continue;
+    decode_in_shape(pl, sv.shape, sv.idx, c);
     RefRec r;
     r.idx = sv.idx;
     r.pad = 0;

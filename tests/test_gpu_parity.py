@@ -376,3 +376,48 @@ def test_widest_lists_with_a_tp_digit_per_segment(torch_cuda):
                        orc.topk(64, objective=objective, n_threads=THREADS), objective)
     finally:
         plan.destroy()
+
+
+def test_eval_batch_replays_from_a_captured_graph(torch_cuda):
+    # sailor_eval_batch only enqueues kernels on the caller's stream (no host synchronisation,
+    # no memset), so it can be captured; every replay must reproduce the eager outputs
+    torch = torch_cuda
+    prob = W.config2()
+    plan, orc = _plan(prob), Oracle(prob)
+    try:
+        n = orc.num_candidates
+        want = orc.eval_batch()
+        eager = gpu_eval(torch, plan, 0, n)
+        dev = "cuda:0"
+        t = torch.zeros(n, dtype=torch.float32, device=dev)
+        c = torch.zeros(n, dtype=torch.float32, device=dev)
+        m = torch.zeros(n, dtype=torch.int64, device=dev)
+        k = torch.zeros(n, dtype=torch.int32, device=dev)
+        idx = torch.from_numpy(np.random.default_rng(1).integers(0, n, 4096).astype(np.int64)).to(dev)
+        ti = torch.zeros(4096, dtype=torch.float32, device=dev)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            plan.eval_batch(0, n, d_time=t, d_cost=c, d_mem=m, d_mask=k, stream=side.cuda_stream)  # warm
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                plan.eval_batch(0, n, d_time=t, d_cost=c, d_mem=m, d_mask=k, stream=side.cuda_stream)
+                plan.eval_batch(0, 4096, d_indices=idx, d_time=ti, stream=side.cuda_stream)
+        torch.cuda.current_stream().wait_stream(side)
+        for rep in range(3):
+            for x in (t, c, m, k, ti):
+                x.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            got = (t.cpu().numpy(), c.cpu().numpy(), m.cpu().numpy().view(np.uint64),
+                   k.cpu().numpy().view(np.uint32))
+            for a, b in zip(got, eager):
+                assert np.array_equal(a, b), rep
+            assert np.array_equal(ti.cpu().numpy(), eager[0][idx.cpu().numpy()])
+            assert_eval_parity(got, want)
+            # eager work of the program between the replays
+            assert plan.best_plan().index == orc.best().index
+    finally:
+        plan.destroy()
