@@ -1153,6 +1153,11 @@ __global__ __launch_bounds__(256) void k_sim_1f1b(DevPlan pl, SimArgs a) {
 
 // ------------------------------------------------------------------ eval_batch
 
+// "iterations per second below the floor", decided the same way by both evaluation kernels
+// (a product instead of a division; the two differ only for values within rounding of the
+// floor)
+__device__ __forceinline__ bool throughput_below(float T, float floor_) { return T * floor_ > 1.0f; }
+
 struct EvalArgs {
   uint64_t first, count;
   const uint64_t *indices;
@@ -1223,7 +1228,7 @@ __global__ __launch_bounds__(256) void k_eval_direct(DevPlan pl, EvalArgs a) {
       else eval_direct_s<3>(pl, c, sh, lc, T, C, peak, mask);
       if (a.has_bound) {
         if (a.objective == 0) { if (C > a.bound) mask |= 32u; }
-        else if (1.0f / T < a.bound) mask |= 32u;
+        else if (throughput_below(T, a.bound)) mask |= 32u;
       }
     }
   }
@@ -1243,21 +1248,34 @@ struct PoolInfo {   // per pool, staged in LDS
   uint32_t meta;    // zone | (bit 8 + k: tp k exceeds the node size) (H1)
 };
 
-template <int S>
+// 24-bit multiply (full rate, unlike the 32-bit one): every product below is a table offset
+__device__ __forceinline__ uint32_t mul24(uint32_t a, uint32_t b) { return __umul24(a, b); }
+
+template <int S, bool PST>
 __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs &a,
                                                const EvalUnit &u, const ShapeRec &sh,
                                                const Rec *rec, const float4 *pair,
                                                const uint32_t *qm, const uint64_t *need,
                                                const PoolInfo *pinfo, const uint32_t *odec,
                                                const int32_t *vals) {
-  const int ZG = pl.ZG, MB = pl.MB, TP = pl.TP, DP = pl.DP, Z = pl.Z;
+  const uint32_t ZG = pl.ZG, MB = pl.MB, TP = pl.TP, DP = pl.DP, Z = pl.Z;
   const uint32_t inner = pl.inner;
   const uint64_t last = a.first + a.count;
   const bool single0 = sh.n[0] == 1, single1 = sh.n[1] == 1;
+  // the unit's outputs start here; lanes add a 32-bit offset (a unit that begins before the
+  // range only stores where idx >= first, so the wrapped pointer is never used below it)
+  const int64_t ubase = (int64_t)(u.idx_lo - a.first);
+  float *const o_time = a.time ? a.time + ubase : nullptr;
+  float *const o_cost = a.cost ? a.cost + ubase : nullptr;
+  uint64_t *const o_mem = a.mem ? a.mem + ubase : nullptr;
+  uint32_t *const o_mask = a.mask ? a.mask + ubase : nullptr;
+  const bool whole = u.idx_lo >= a.first && u.idx_lo + (uint64_t)u.o_cnt * inner <= last;  // uniform
+  const uint32_t seg_rec = mul24(mul24(TP, ZG), MB), seg_need = mul24(mul24(TP, MB), DP),
+                 seg_qm = mul24(TP, ZG);
   for (uint32_t in = threadIdx.x; in < inner; in += blockDim.x) {
-    const uint32_t a1 = fast_div(in, pl.mg_mbtpdp), rem = in - a1 * (uint32_t)(MB * TP * DP);
-    const uint32_t dp = fast_div(rem, pl.mg_mbtp), rem2 = rem - dp * (uint32_t)(MB * TP);
-    const uint32_t tp = fast_div(rem2, pl.mg_mb), mb = rem2 - tp * (uint32_t)MB;
+    const uint32_t a1 = fast_div(in, pl.mg_mbtpdp), rem = in - mul24(a1, MB * TP * DP);
+    const uint32_t dp = fast_div(rem, pl.mg_mbtp), rem2 = rem - mul24(dp, MB * TP);
+    const uint32_t tp = fast_div(rem2, pl.mg_mb), mb = rem2 - mul24(tp, MB);
     const bool divisible = pl.nb[mb * DP + dp] != 0;
     LaneC lc;
     lc.nbm1 = pl.nbm1_f[mb * DP + dp];
@@ -1265,25 +1283,31 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
     lc.dph = pl.dph_f[dp];
     lc.xb = pl.xb_f[mb];
     // this lane's slices of the staged tables; segment j with tp index k on pool p:
-    const Rec *recl = rec + mb;                 // [((j * TP + k) * ZG + p) * MB]
-    const float4 *pairm = pair + mb * Z * Z;    // transfers of this microbatch size
-    const uint64_t *needl = need + mb * DP + dp;  // [(j * TP + k) * MB * DP]
+    const Rec *recl = rec + mb;                      // [((j * TP + k) * ZG + p) * MB]
+    const uint64_t *needl = need + mul24(mb, DP) + dp;  // [(j * TP + k) * MB * DP]
+    const float4 *pairm = pair + mul24(mb, Z * Z);   // transfers of this microbatch size
+    // with one tp per plan the later segments use this lane's tp: their slices are fixed
+    const uint32_t tpo_rec = mul24(mul24(tp, ZG), MB), tpo_need = mul24(mul24(tp, MB), DP),
+                   tpo_qm = mul24(tp, ZG);
     // segment 1 does not change while the outer digits advance
-    const int p0 = (int)a1;
-    const Rec r0 = recl[(tp * ZG + p0) * MB];
+    const uint32_t p0 = a1;
+    const Rec r0 = recl[tpo_rec + mul24(p0, MB)];
     const Acc A0 = acc_begin(r0);
     const PoolInfo i0 = pinfo[p0];
-    const uint64_t mem0 = needl[tp * MB * DP] + i0.res;
+    const uint64_t mem0 = needl[tpo_need] + i0.res;
     uint32_t mask0 = 0;
     if (mem0 > i0.cap) mask0 |= 1u;
     if (i0.meta & (1u << (8 + tp))) mask0 |= 8u;
-    const bool q0 = (qm[tp * ZG + p0] >> dp) & 1u;
-    const int z0 = (int)(i0.meta & 0xFFu);
+    const bool q0 = (qm[tpo_qm + p0] >> dp) & 1u;
+    const uint32_t z0 = i0.meta & 0xFFu;
     const int64_t D = vals[dp];  // value lists staged in LDS: [DP] dp, then [TP] tp
     const int64_t gpus0 = (int64_t)sh.n[0] * vals[DP + tp];
-    for (uint32_t o = 0; o < u.o_cnt; ++o) {
-      const uint64_t idx = u.idx_lo + (uint64_t)o * inner + in;
-      if (idx < a.first || idx >= last) continue;
+    uint32_t off = in;           // o * inner + in
+    for (uint32_t o = 0; o < u.o_cnt; ++o, off += inner) {
+      if (!whole) {
+        const uint64_t idx = u.idx_lo + off;
+        if (idx < a.first || idx >= last) continue;
+      }
       const uint32_t od = odec[o];  // outer digits (uniform)
       float T = kPosInf, C = kPosInf;
       uint64_t peak = 0;
@@ -1294,29 +1318,36 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
         Acc acc = A0;
         bool quota_ok = q0;
         if (S >= 2) {
-          const int r2 = (int)(od & 63u);
-          const uint32_t t1 = pl.pst ? ((od >> 6) & 7u) : tp;
-          int p1 = p0 + 1 + r2;
+          const uint32_t r2 = od & 63u;
+          const uint32_t t1 = PST ? ((od >> 6) & 7u) : tp;
+          uint32_t p1 = p0 + 1 + r2;
           if (p1 >= ZG) p1 -= ZG;
-          const Rec r1 = recl[((TP + t1) * ZG + p1) * MB];
+          // uniform offsets when the segment has its own tp digit, this lane's otherwise
+          const uint32_t o_rec = seg_rec + (PST ? mul24(mul24(t1, ZG), MB) : tpo_rec);
+          const uint32_t o_need = seg_need + (PST ? mul24(mul24(t1, MB), DP) : tpo_need);
+          const uint32_t o_qm = seg_qm + (PST ? mul24(t1, ZG) : tpo_qm);
+          const Rec r1 = recl[o_rec + mul24(p1, MB)];
           const PoolInfo i1 = pinfo[p1];
-          const int z1 = (int)(i1.meta & 0xFFu);
-          const uint64_t mem1 = needl[(TP + t1) * MB * DP] + i1.res;
+          const uint32_t z1 = i1.meta & 0xFFu;
+          const uint64_t mem1 = needl[o_need] + i1.res;
           if (mem1 > i1.cap) mask |= 1u;
           if (i1.meta & (1u << (8 + t1))) mask |= 8u;
           peak = mem1 > peak ? mem1 : peak;
-          const bool q1 = (qm[(TP + t1) * ZG + p1] >> dp) & 1u;
+          const bool q1 = (qm[o_qm + p1] >> dp) & 1u;
           quota_ok = quota_ok && q1;
-          const float4 pr = pairm[z0 * Z + z1];
+          const float4 pr = pairm[mul24(z0, Z) + z1];
           acc = acc_cross(acc, r1, pr.x, pr.y, pr.z, single0, true);
           if (S == 3) {
-            const int r3 = (int)((od >> 9) & 63u);
-            const uint32_t t2 = pl.pst ? (od >> 15) : tp;
-            int p2 = p1 + 1 + r3;
+            const uint32_t r3 = (od >> 9) & 63u;
+            const uint32_t t2 = PST ? (od >> 15) : tp;
+            uint32_t p2 = p1 + 1 + r3;
             if (p2 >= ZG) p2 -= ZG;
-            const Rec r2r = recl[((2 * TP + t2) * ZG + p2) * MB];
+            const uint32_t o_rec2 = 2 * seg_rec + (PST ? mul24(mul24(t2, ZG), MB) : tpo_rec);
+            const uint32_t o_need2 = 2 * seg_need + (PST ? mul24(mul24(t2, MB), DP) : tpo_need);
+            const uint32_t o_qm2 = 2 * seg_qm + (PST ? mul24(t2, ZG) : tpo_qm);
+            const Rec r2r = recl[o_rec2 + mul24(p2, MB)];
             const PoolInfo i2 = pinfo[p2];
-            const uint64_t mem2 = needl[(2 * TP + t2) * MB * DP] + i2.res;
+            const uint64_t mem2 = needl[o_need2] + i2.res;
             if (mem2 > i2.cap) mask |= 1u;
             if (i2.meta & (1u << (8 + t2))) mask |= 8u;
             peak = mem2 > peak ? mem2 : peak;
@@ -1324,9 +1355,9 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
               const int64_t gpus = gpus0 + (int64_t)sh.n[2] * vals[DP + t2];
               quota_ok = q1 && gpus * D <= (int64_t)i0.avail;
             } else {
-              quota_ok = quota_ok && ((qm[(2 * TP + t2) * ZG + p2] >> dp) & 1u);
+              quota_ok = quota_ok && ((qm[o_qm2 + p2] >> dp) & 1u);
             }
-            const float4 pr2 = pairm[z1 * Z + (int)(i2.meta & 0xFFu)];
+            const float4 pr2 = pairm[mul24(z1, Z) + (i2.meta & 0xFFu)];
             acc = acc_cross(acc, r2r, pr2.x, pr2.y, pr2.z, single1, false);
           }
         }
@@ -1334,14 +1365,13 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
         acc_finish(acc, lc, T, C);
         if (a.has_bound) {
           if (a.objective == 0) { if (C > a.bound) mask |= 32u; }
-          else if (1.0f / T < a.bound) mask |= 32u;
+          else if (throughput_below(T, a.bound)) mask |= 32u;
         }
       }
-      const uint64_t out = idx - a.first;
-      if (a.time) a.time[out] = T;
-      if (a.cost) a.cost[out] = C;
-      if (a.mem) a.mem[out] = peak;
-      if (a.mask) a.mask[out] = mask;
+      if (o_time) o_time[off] = T;
+      if (o_cost) o_cost[off] = C;
+      if (o_mem) o_mem[off] = peak;
+      if (o_mask) o_mask[off] = mask;
     }
   }
 }
@@ -1409,9 +1439,14 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
                       seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]), vals[DP + k], 0u);
   }
   __syncthreads();
-  if (S == 1) eval_rows_body<1>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
-  else if (S == 2) eval_rows_body<2>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
-  else eval_rows_body<3>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
+  if (S == 1) eval_rows_body<1, false>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
+  else if (!pl.pst) {
+    if (S == 2) eval_rows_body<2, false>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
+    else eval_rows_body<3, false>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
+  } else {
+    if (S == 2) eval_rows_body<2, true>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
+    else eval_rows_body<3, true>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
+  }
 }
 
 }  // namespace sailor
