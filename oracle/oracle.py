@@ -40,6 +40,7 @@ class _Problem(C.Structure):
         ("n_mb", C.c_int32), ("n_tp", C.c_int32), ("n_dp", C.c_int32), ("n_pp", C.c_int32),
         ("max_segments", C.c_int32), ("seg3_max_pp", C.c_int32), ("uniform_layers", C.c_int32),
         ("per_segment_tp", C.c_int32), ("n_bw_coef", C.c_int32),
+        ("mixed_types", C.c_int32),
         ("global_batch", C.c_int64),
         ("mb_values", C.c_void_p), ("tp_values", C.c_void_p), ("dp_values", C.c_void_p),
         ("pp_values", C.c_void_p), ("n_partitions", C.c_void_p), ("partition_layers", C.c_void_p),
@@ -154,6 +155,7 @@ class Oracle:
         s.max_segments, s.seg3_max_pp = prob.max_segments, prob.seg3_max_pp
         s.uniform_layers = 1 if prob.uniform_layers else 0
         s.per_segment_tp = 1 if getattr(prob, "per_segment_tp", False) else 0
+        s.mixed_types = 1 if getattr(prob, "mixed_types", False) else 0
         s.global_batch = prob.global_batch
         s.mb_values = arr(prob.mb_values, np.int32)
         s.tp_values = arr(prob.tp_values, np.int32)

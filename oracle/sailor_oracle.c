@@ -18,7 +18,10 @@
 
 struct so_ctx {
   so_problem p;
-  int32_t ZG;
+  int32_t GX;              /* types a segment can choose: G, or G + G (G - 1) / 2 with pairs */
+  int32_t xa[SO_MAX_POOLS], xb[SO_MAX_POOLS]; /* the two real types of an extended type (equal
+                                                 for a plain one)                             */
+  int32_t ZG;              /* pools: n_zones * GX                                           */
   uint64_t inner;          /* n_mb * n_tp * n_dp * ZG : candidates per (shape, outer pools) */
   uint64_t *block_off;     /* [n_pp][3] : first index of block (pp_idx, s)                  */
   uint64_t *block_size;    /* [n_pp][3]                                                     */
@@ -43,11 +46,20 @@ static int segments_allowed(const so_problem *p, int P, int s) {
 
 so_ctx *so_create(const so_problem *p) {
   if (!p || p->n_layers < 1 || p->n_types < 1 || p->n_zones < 1) return NULL;
-  if (p->n_types * p->n_zones > SO_MAX_POOLS) return NULL;
   so_ctx *c = (so_ctx *)calloc(1, sizeof(so_ctx));
   if (!c) return NULL;
   c->p = *p;
-  c->ZG = p->n_zones * p->n_types;
+  c->GX = 0;
+  for (int a = 0; a < p->n_types && c->GX < SO_MAX_POOLS; ++a) { c->xa[c->GX] = a; c->xb[c->GX] = a; c->GX += 1; }
+  if (p->mixed_types)
+    for (int a = 0; a < p->n_types; ++a)
+      for (int b = a + 1; b < p->n_types && c->GX < SO_MAX_POOLS; ++b) {
+        c->xa[c->GX] = a;
+        c->xb[c->GX] = b;
+        c->GX += 1;
+      }
+  if (c->GX * p->n_zones > SO_MAX_POOLS) { free(c); return NULL; }
+  c->ZG = p->n_zones * c->GX;
   c->inner = (uint64_t)p->n_mb * p->n_tp * p->n_dp * c->ZG;
   c->block_off = (uint64_t *)calloc((size_t)p->n_pp * 3, sizeof(uint64_t));
   c->block_size = (uint64_t *)calloc((size_t)p->n_pp * 3, sizeof(uint64_t));
@@ -294,30 +306,41 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
   }
   const int64_t Nb = p->global_batch / (D * mb);
 
-  int type_of[SO_MAX_STAGES], zone_of[SO_MAX_STAGES], first_layer[SO_MAX_STAGES];
+  /* the stage's replicas are of type type_of[i], or half of them of type type_b[i] */
+  int type_of[SO_MAX_STAGES], type_b[SO_MAX_STAGES], zone_of[SO_MAX_STAGES], first_layer[SO_MAX_STAGES];
   int tp_of[SO_MAX_STAGES], tpi_of[SO_MAX_STAGES]; /* TP degree of the stage and its list index */
-  int64_t gpus_per_replica_on_pool[SO_MAX_POOLS];
-  memset(gpus_per_replica_on_pool, 0, sizeof gpus_per_replica_on_pool);
+  /* GPUs that one replica of the plan takes from every real (zone, type) pool, counted in
+   * halves: a stage whose replicas are split over two types takes half a replica from each */
+  int64_t half_gpus_on_pool[SO_MAX_POOLS];
+  memset(half_gpus_on_pool, 0, sizeof half_gpus_on_pool);
   int layer = 0;
   for (int i = 0; i < P; ++i) {
     int seg = (i < g->cut[0]) ? 0 : (i < g->cut[1]) ? 1 : 2;
     int pool = g->pool[seg];
-    type_of[i] = pool % G;
-    zone_of[i] = pool / G;
+    type_of[i] = c->xa[pool % c->GX];
+    type_b[i] = c->xb[pool % c->GX];
+    zone_of[i] = pool / c->GX;
     tp_of[i] = g->seg_tp[seg];
     tpi_of[i] = g->seg_tp_idx[seg];
-    gpus_per_replica_on_pool[pool] += tp_of[i];
+    if (type_b[i] == type_of[i]) {
+      half_gpus_on_pool[zone_of[i] * G + type_of[i]] += 2 * tp_of[i];
+    } else {
+      half_gpus_on_pool[zone_of[i] * G + type_of[i]] += tp_of[i];
+      half_gpus_on_pool[zone_of[i] * G + type_b[i]] += tp_of[i];
+      if (D % 2 != 0) out->mask |= SO_BIT_QUOTA; /* D replicas cannot be halved */
+    }
     first_layer[i] = layer;
     layer += nl[i];
   }
 
   /* H1: a tensor-parallel group stays inside one node (Sec. 4.2.1) */
   for (int i = 0; i < P; ++i)
-    if (tp_of[i] > p->gpus_per_node[type_of[i]]) out->mask |= SO_BIT_TP_NODE;
+    if (tp_of[i] > p->gpus_per_node[type_of[i]] || tp_of[i] > p->gpus_per_node[type_b[i]])
+      out->mask |= SO_BIT_TP_NODE;
 
-  /* quota: D replicas of every stage, tp GPUs each, from the stage's (zone, type) pool */
+  /* quota: D replicas of every stage, tp GPUs each, from the stage's (zone, type) pool(s) */
   for (int a = 0; a < Z * G; ++a)
-    if (gpus_per_replica_on_pool[a] * D > (int64_t)p->avail[a]) out->mask |= SO_BIT_QUOTA;
+    if (half_gpus_on_pool[a] * D > 2 * (int64_t)p->avail[a]) out->mask |= SO_BIT_QUOTA;
 
   /* memory per worker of each stage: M_model + M_activation (+ reserved), Sec. 4.3 */
   uint64_t params_of[SO_MAX_STAGES];
@@ -336,6 +359,11 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
     uint64_t m = m_model + m_act + p->mem_reserved[type_of[i]];
     if (m > p->mem_capacity[type_of[i]]) out->mask |= SO_BIT_OOM;
     if (m > peak) peak = m;
+    if (type_b[i] != type_of[i]) { /* the other half of the replicas */
+      uint64_t m2 = m_model + m_act + p->mem_reserved[type_b[i]];
+      if (m2 > p->mem_capacity[type_b[i]]) out->mask |= SO_BIT_OOM;
+      if (m2 > peak) peak = m2;
+    }
   }
   out->peak_mem = peak;
 
@@ -346,6 +374,11 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
     int gt = type_of[i], z = zone_of[i];
     double f = layer_time_sum(p, p->t_fwd, gt, g->mb_idx, tpi_of[i], first_layer[i], nl[i]);
     double b = layer_time_sum(p, p->t_bwd, gt, g->mb_idx, tpi_of[i], first_layer[i], nl[i]);
+    if (type_b[i] != gt) { /* the slower replica type sets the stage's pace (straggler, Sec. 4.3) */
+      double f2 = layer_time_sum(p, p->t_fwd, type_b[i], g->mb_idx, tpi_of[i], first_layer[i], nl[i]);
+      double b2 = layer_time_sum(p, p->t_bwd, type_b[i], g->mb_idx, tpi_of[i], first_layer[i], nl[i]);
+      if (f2 + b2 > f + b) { f = f2; b = b2; }
+    }
     double x = 0.0;
     if (i < P - 1) x += p2p / link_bandwidth(p, z, zone_of[i + 1], p2p);
     if (i > 0) x += p2p / link_bandwidth(p, z, zone_of[i - 1], p2p);
@@ -361,6 +394,10 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
     if (sync > t_sync) t_sync = sync;
     double u = upd_time_sum(p, gt, tpi_of[i], first_layer[i], nl[i]);
     if (u > t_upd) t_upd = u;
+    if (type_b[i] != gt) {
+      double u2 = upd_time_sum(p, type_b[i], tpi_of[i], first_layer[i], nl[i]);
+      if (u2 > t_upd) t_upd = u2;
+    }
   }
   /* 1F1B: warm-up + cool-down pass every stage once, the steady phase repeats the
    * straggler for the remaining microbatches */
@@ -371,7 +408,10 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
   /* cost per iteration: rented GPUs for T_iter plus cross-zone traffic */
   double gpu_dollars_per_hour = 0.0, c_comm = 0.0;
   for (int i = 0; i < P; ++i)
-    gpu_dollars_per_hour += (double)(D * tp_of[i]) * p->price_per_hour[type_of[i]];
+    gpu_dollars_per_hour +=
+        type_b[i] == type_of[i]
+            ? (double)(D * tp_of[i]) * p->price_per_hour[type_of[i]]
+            : (double)(D * tp_of[i]) * (0.5 * (p->price_per_hour[type_of[i]] + p->price_per_hour[type_b[i]]));
   if (p->egress_per_byte)
     for (int i = 0; i + 1 < P; ++i) {
       int z = zone_of[i], zn = zone_of[i + 1];
@@ -428,7 +468,7 @@ int so_simulate_1f1b(const so_ctx *c, uint64_t index, double *t_event, double *t
   const so_problem *p = &c->p;
   so_config g;
   if (so_decode(c, index, &g) != 0) return -1;
-  const int P = g.pp, G = p->n_types;
+  const int P = g.pp;
   const int32_t *nl = partition_row(c, &g);
   if (p->global_batch % ((int64_t)g.dp * g.mb) != 0) {
     *t_event = INFINITY;
@@ -438,11 +478,12 @@ int so_simulate_1f1b(const so_ctx *c, uint64_t index, double *t_event, double *t
   const int64_t M = p->global_batch / ((int64_t)g.dp * g.mb);
   const double p2p = (double)p->p2p_bytes[g.mb_idx];
   double fdur[SO_MAX_STAGES], bdur[SO_MAX_STAGES];
-  int zone_of[SO_MAX_STAGES], type_of[SO_MAX_STAGES], tpi_of[SO_MAX_STAGES];
+  int zone_of[SO_MAX_STAGES], type_of[SO_MAX_STAGES], type_b[SO_MAX_STAGES], tpi_of[SO_MAX_STAGES];
   for (int i = 0; i < P; ++i) {
     int seg = (i < g.cut[0]) ? 0 : (i < g.cut[1]) ? 1 : 2;
-    type_of[i] = g.pool[seg] % G;
-    zone_of[i] = g.pool[seg] / G;
+    type_of[i] = c->xa[g.pool[seg] % c->GX];
+    type_b[i] = c->xb[g.pool[seg] % c->GX];
+    zone_of[i] = g.pool[seg] / c->GX;
     tpi_of[i] = g.seg_tp_idx[seg];
   }
   int layer = 0;
@@ -450,6 +491,11 @@ int so_simulate_1f1b(const so_ctx *c, uint64_t index, double *t_event, double *t
   for (int i = 0; i < P; ++i) {
     double f = layer_time_sum(p, p->t_fwd, type_of[i], g.mb_idx, tpi_of[i], layer, nl[i]);
     double b = layer_time_sum(p, p->t_bwd, type_of[i], g.mb_idx, tpi_of[i], layer, nl[i]);
+    if (type_b[i] != type_of[i]) { /* the pipeline through the slower replica type */
+      double f2 = layer_time_sum(p, p->t_fwd, type_b[i], g.mb_idx, tpi_of[i], layer, nl[i]);
+      double b2 = layer_time_sum(p, p->t_bwd, type_b[i], g.mb_idx, tpi_of[i], layer, nl[i]);
+      if (f2 + b2 > f + b) { f = f2; b = b2; }
+    }
     double send_f = (i < P - 1) ? p2p / link_bandwidth(p, zone_of[i], zone_of[i + 1], p2p) : 0.0;
     double send_b = (i > 0) ? p2p / link_bandwidth(p, zone_of[i], zone_of[i - 1], p2p) : 0.0;
     fdur[i] = f + send_f;

@@ -29,6 +29,15 @@
  * A transfer of S bytes takes S / bw(S); the all-reduce of a stage uses its gradient
  * buffer as the message size, and T_sync is the maximum over the stages.
  *
+ * Optional mixed replicas (mixed_types = 1): the D replicas of a stage need not be of one GPU
+ * type (the D tuples of Sec. 4.2); H5 / H6 keep them in one zone.  Here a segment may use an
+ * extended type: a pair of GPU types a < b of its zone, half of the replicas on each (D must
+ * be even).  Extended types are numbered after the G plain ones, pairs in lexicographic
+ * order, and a pool is zone * G' + extended type with G' = G + G (G - 1) / 2.  A stage's time,
+ * and its update time, are those of its slower replica type (the straggler, Sec. 4.3); both
+ * types must fit their memory and node size; every real pool must hold what all segments
+ * together take from it; rent is the mean of the two prices.
+ *
  * Parity pins (tests/test_oracle_*.py): homogeneous 1F1B closed form, discrete-event
  * 1F1B schedule, ring all-reduce limits, big-integer memory bytes, cost identities,
  * feasibility monotonicity, brute-force selection, enumeration bijection; per-segment
@@ -55,6 +64,7 @@ typedef struct {
   int32_t max_segments, seg3_max_pp, uniform_layers;
   int32_t per_segment_tp;          /* 1: every segment has its own TP degree (digit) */
   int32_t n_bw_coef;               /* 0: constant bandwidth; else coefficients per zone pair */
+  int32_t mixed_types;             /* 1: a segment's replicas may be split over two GPU types */
   int64_t global_batch;
   const int32_t *mb_values, *tp_values, *dp_values, *pp_values;
   const int32_t *n_partitions;     /* [n_pp] */
@@ -79,7 +89,7 @@ typedef struct {
 typedef struct {
   int32_t pp, pp_idx, n_segments, partition;
   int32_t cut[2];  /* first stage of segment 2 / segment 3 (unused entries = pp) */
-  int32_t pool[3]; /* zone * n_types + type, -1 if the segment is absent */
+  int32_t pool[3]; /* zone * G' + (extended) type, -1 if the segment is absent */
   int32_t dp, tp, mb, dp_idx, tp_idx, mb_idx; /* tp, tp_idx: those of segment 1 */
   int32_t seg_tp[3], seg_tp_idx[3];           /* TP degree per segment (0 / -1 if absent) */
 } so_config;

@@ -101,6 +101,7 @@ class Problem:
     bandwidth: np.ndarray          # float64 [Z][Z], bytes/s
     egress_per_byte: Optional[np.ndarray] = None  # float64 [Z][Z] or None (= zeros)
     per_segment_tp: bool = False   # every segment carries its own TP digit
+    mixed_types: bool = False      # a segment's replicas may be split over two GPU types
     bw_poly: Optional[np.ndarray] = None  # float64 [Z][Z][n_coef]: bandwidth over log2(message
                                           # bytes), lowest power first; None = constant
     name: str = ""
@@ -124,6 +125,9 @@ class Problem:
 
     def with_per_segment_tp(self, on: bool = True) -> "Problem":
         return replace(self, per_segment_tp=bool(on))
+
+    def with_mixed_types(self, on: bool = True) -> "Problem":
+        return replace(self, mixed_types=bool(on))
 
     def with_bw_poly(self, poly: Optional[np.ndarray]) -> "Problem":
         return replace(self, bw_poly=None if poly is None
