@@ -38,6 +38,16 @@
  * memory shard, activation bytes, profiled times, node-size check, gradient shard,
  * GPU count and rent use the degree of its segment.
  *
+ * mixed_types = 1 lets the D replicas of a stage be of two GPU types (the D tuples of the plan,
+ * Sec. 4.2; H5 / H6 keep them in one zone).  A segment then chooses among G' = G + G (G - 1) / 2
+ * extended types: the G plain ones, then every pair a < b in lexicographic order, half of the
+ * replicas on each (D must be even).  Wherever the numbering above says "pool" it is
+ * zone * G' + extended type, and ZG = n_zones * G' (at most SAILOR_MAX_POOLS).  A stage of a
+ * pair runs, and updates, at the pace of its slower type (the straggler of Sec. 4.3); both
+ * types must fit their memory and node size; every real (zone, type) pool must hold what all
+ * segments of the plan together take from it, else OVER_QUOTA; the rent is the mean of the
+ * two prices.
+ *
  * Mask bits of an evaluated candidate (0 = valid plan)
  *   bit 0 OOM               some stage's worker exceeds its GPU's memory (Sec. 4.3)
  *   bit 1 OVER_QUOTA        a pool needs more GPUs than are available (Sec. 4)
@@ -103,6 +113,7 @@ typedef struct {
   int32_t per_segment_tp;  /* 1: every segment has its own TP digit; 0: one TP per plan */
   int32_t n_bw_coef;       /* coefficients per link in bw_poly, 0..SAILOR_MAX_BW_COEF; 0: every
                               message sees bandwidth[a][b] */
+  int32_t mixed_types;     /* 1: a segment's replicas may be split over two GPU types */
   int64_t global_batch;    /* never changed by the planner (Sec. 4.2) */
   const int32_t *mb_values, *tp_values, *dp_values, *pp_values; /* positive, strictly ascending */
   const int32_t *n_partitions;     /* [n_pp], >= 1 */
@@ -152,10 +163,14 @@ typedef struct {
   int32_t pp_index, tp_index, dp_index, mb_index;
   int32_t partition, n_segments;
   int32_t cut[2];  /* first stage of segment 2 / 3; unused entries = pp */
-  int32_t pool[3]; /* zone * n_types + type; unused entries = -1 */
+  int32_t pool[3]; /* zone * G' + (extended) type, G' = n_types unless mixed_types;
+                      unused entries = -1 */
   int32_t seg_tp[3];       /* TP degree of each segment; unused entries = 0 */
   int32_t seg_tp_index[3]; /* its index in tp_values; unused entries = -1;
                               tp / tp_index above are those of segment 1 */
+  int32_t zone[3];         /* zone of each segment; unused entries = -1 */
+  int32_t type_a[3];       /* GPU type of each segment's replicas ... */
+  int32_t type_b[3];       /* ... and of the other half of them (= type_a unless mixed) */
 } sailor_result;
 
 /* Build a plan: validate, copy the problem to the current HIP device, build the static

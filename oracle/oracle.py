@@ -184,6 +184,7 @@ class Oracle:
         s.n_bw_coef = 0 if poly is None else int(np.asarray(poly).shape[-1])
         s.bw_poly = arr(poly, np.float64) if poly is not None else None
         self._struct = s
+        self._prob = prob
         self._lib = lib
         self._ctx = lib.so_create(C.byref(s))
         if not self._ctx:

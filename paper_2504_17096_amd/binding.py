@@ -42,6 +42,7 @@ class sailor_problem(C.Structure):
         ("n_mb", C.c_int32), ("n_tp", C.c_int32), ("n_dp", C.c_int32), ("n_pp", C.c_int32),
         ("max_segments", C.c_int32), ("seg3_max_pp", C.c_int32), ("uniform_layers", C.c_int32),
         ("per_segment_tp", C.c_int32), ("n_bw_coef", C.c_int32),
+        ("mixed_types", C.c_int32),
         ("global_batch", C.c_int64),
         ("mb_values", C.c_void_p), ("tp_values", C.c_void_p), ("dp_values", C.c_void_p),
         ("pp_values", C.c_void_p), ("n_partitions", C.c_void_p), ("partition_layers", C.c_void_p),
@@ -71,6 +72,7 @@ class sailor_result(C.Structure):
         ("mb_index", C.c_int32), ("partition", C.c_int32), ("n_segments", C.c_int32),
         ("cut", C.c_int32 * 2), ("pool", C.c_int32 * 3),
         ("seg_tp", C.c_int32 * 3), ("seg_tp_index", C.c_int32 * 3),
+        ("zone", C.c_int32 * 3), ("type_a", C.c_int32 * 3), ("type_b", C.c_int32 * 3),
     ]
 
 
@@ -95,12 +97,16 @@ class Result:
     pool: Tuple[int, int, int]
     seg_tp: Tuple[int, int, int] = (0, 0, 0)
     seg_tp_index: Tuple[int, int, int] = (-1, -1, -1)
+    zone: Tuple[int, int, int] = (-1, -1, -1)
+    type_a: Tuple[int, int, int] = (-1, -1, -1)
+    type_b: Tuple[int, int, int] = (-1, -1, -1)
 
 
 def _result(r: sailor_result) -> Result:
     return Result(r.index, r.peak_mem_bytes, r.iter_time_s, r.cost_per_iter, r.mask, r.pp, r.tp,
                   r.dp, r.mb, r.pp_index, r.tp_index, r.dp_index, r.mb_index, r.partition,
-                  r.n_segments, tuple(r.cut), tuple(r.pool), tuple(r.seg_tp), tuple(r.seg_tp_index))
+                  r.n_segments, tuple(r.cut), tuple(r.pool), tuple(r.seg_tp), tuple(r.seg_tp_index), tuple(r.zone), tuple(r.type_a),
+                  tuple(r.type_b))
 
 
 _lib = None
@@ -155,6 +161,7 @@ def marshal_problem(prob):
     s.max_segments, s.seg3_max_pp = prob.max_segments, prob.seg3_max_pp
     s.uniform_layers = 1 if prob.uniform_layers else 0
     s.per_segment_tp = 1 if getattr(prob, "per_segment_tp", False) else 0
+    s.mixed_types = 1 if getattr(prob, "mixed_types", False) else 0
     s.global_batch = prob.global_batch
     s.mb_values = arr(prob.mb_values, np.int32)
     s.tp_values = arr(prob.tp_values, np.int32)

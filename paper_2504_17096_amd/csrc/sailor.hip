@@ -84,6 +84,7 @@ struct sailor_plan {
   const EvalUnit *d_eunits = nullptr;
   size_t eval_lds_bytes = 0;
   std::vector<int32_t> mbv, tpv, dpv, ppv;
+  std::vector<uint16_t> xt;        // real types a | b << 8 of every extended type
   int device = 0;
   size_t lds_bytes = 0;
   unsigned unit_threads = 256;
@@ -129,6 +130,11 @@ bool finite_nonneg(const double *v, size_t n) {
   return true;
 }
 
+// types a segment can choose: the plain ones and, with mixed replicas, every pair of them
+int extended_types(const sailor_problem *p) {
+  return p->mixed_types ? p->n_types + p->n_types * (p->n_types - 1) / 2 : p->n_types;
+}
+
 sailor_status validate(const sailor_problem *p) {
   if (!p) return SAILOR_EINVAL;
   if (p->n_layers < 1 || p->n_types < 1 || p->n_zones < 1) return SAILOR_EINVAL;
@@ -139,6 +145,8 @@ sailor_status validate(const sailor_problem *p) {
     return SAILOR_EINVAL;
   if (p->max_segments < 1 || p->max_segments > 3 || p->global_batch < 1) return SAILOR_EINVAL;
   if (p->per_segment_tp != 0 && p->per_segment_tp != 1) return SAILOR_EINVAL;
+  if (p->mixed_types != 0 && p->mixed_types != 1) return SAILOR_EINVAL;
+  if (p->n_zones * extended_types(p) > SAILOR_MAX_POOLS) return SAILOR_EINVAL;
   if (p->n_bw_coef < 0 || p->n_bw_coef > SAILOR_MAX_BW_COEF || (p->n_bw_coef > 0 && !p->bw_poly))
     return SAILOR_EINVAL;
   if (!ascending_positive(p->mb_values, p->n_mb) || !ascending_positive(p->tp_values, p->n_tp) ||
@@ -207,7 +215,7 @@ uint64_t n_cut_choices(int P, int s) {
 // Lays the candidate space out as blocks -> shapes -> scan units (host bookkeeping only).
 sailor_status build_space(const sailor_problem *p, sailor_plan *pl, std::vector<int32_t> &st_n,
                           std::vector<int32_t> &st_first, std::vector<uint8_t> &st_flags) {
-  const int ZG = p->n_types * p->n_zones;
+  const int ZG = extended_types(p) * p->n_zones;
   const uint64_t inner = (uint64_t)p->n_mb * p->n_tp * p->n_dp * ZG;
   const int pst = p->per_segment_tp ? 1 : 0;
   const uint64_t otp = pst ? (uint64_t)p->n_tp : 1u;  // radix of the tp digits of segments 2, 3
@@ -394,8 +402,13 @@ void fill_config(const sailor_plan *pl, const ShapeRec &sh, uint64_t index, sail
     o /= (d.ZG - 1);
     out->seg_tp_index[2] = d.pst ? (int32_t)o : out->tp_index;
   }
-  for (int j = 0; j < 3; ++j)
+  for (int j = 0; j < 3; ++j) {
     out->seg_tp[j] = out->seg_tp_index[j] >= 0 ? pl->tpv[out->seg_tp_index[j]] : 0;
+    const bool used = out->pool[j] >= 0;
+    out->zone[j] = used ? out->pool[j] / d.GX : -1;
+    out->type_a[j] = used ? (pl->xt[out->pool[j] % d.GX] & 255) : -1;
+    out->type_b[j] = used ? (pl->xt[out->pool[j] % d.GX] >> 8) : -1;
+  }
   out->pp_index = sh.pp_idx;
   out->pp = sh.P;
   out->mb = pl->mbv[out->mb_index];
@@ -415,14 +428,15 @@ const ShapeRec &shape_of(const sailor_plan *pl, uint64_t index) {
 }
 
 unsigned quota_grid(const DevPlan &d) {
-  return (unsigned)std::min<size_t>(1024, ((size_t)(d.W_max + 1) * d.ZG + 255) / 256);
+  const size_t n = std::max((size_t)(d.W_max + 1) * d.ZG, d.mixed ? (size_t)(2 * d.W_max + 1) * d.ZGr : 0);
+  return (unsigned)std::min<size_t>(1024, (n + 255) / 256);
 }
 
 // Brings a changed availability table to the device on the caller's stream and rebuilds
 // the quota table from it.
 sailor_status refresh_avail(sailor_plan *pl, hipStream_t st) {
   if (!pl->avail_dirty) return SAILOR_OK;
-  HIP_TRY(hipMemcpyAsync(pl->d_avail, pl->h_avail, pl->dev.ZG * sizeof(int32_t),
+  HIP_TRY(hipMemcpyAsync(pl->d_avail, pl->h_avail, pl->dev.ZGr * sizeof(int32_t),
                          hipMemcpyHostToDevice, st));
   k_quota_table<<<quota_grid(pl->dev), 256, 0, st>>>(pl->dev);
   HIP_TRY(hipEventRecord(pl->ev_upload, st));
@@ -439,6 +453,18 @@ void launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, hipEven
   else kernel<<<grid, block, lds, st>>>(args...);
 }
 
+template <int MODE, bool MIXED>
+void launch_units_m(sailor_plan *pl, sailor_objective obj, int has_bound, const ScanArgs &a,
+                    dim3 grid, dim3 block, size_t lds, hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
+  if (obj == SAILOR_MAX_THROUGHPUT) {
+    if (has_bound) launch(k_units<MODE, 0, true, MIXED>, grid, block, lds, st, e0, e1, pl->dev, a);
+    else launch(k_units<MODE, 0, false, MIXED>, grid, block, lds, st, e0, e1, pl->dev, a);
+  } else {
+    if (has_bound) launch(k_units<MODE, 1, true, MIXED>, grid, block, lds, st, e0, e1, pl->dev, a);
+    else launch(k_units<MODE, 1, false, MIXED>, grid, block, lds, st, e0, e1, pl->dev, a);
+  }
+}
+
 template <int MODE>
 void launch_units(sailor_plan *pl, sailor_objective obj, int has_bound, const ScanArgs &a,
                   hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
@@ -448,13 +474,8 @@ void launch_units(sailor_plan *pl, sailor_objective obj, int has_bound, const Sc
                                     : n_units * a.n_sub),
       block(pl->unit_threads);
   const size_t lds = pl->lds_bytes;
-  if (obj == SAILOR_MAX_THROUGHPUT) {
-    if (has_bound) launch(k_units<MODE, 0, true>, grid, block, lds, st, e0, e1, pl->dev, a);
-    else launch(k_units<MODE, 0, false>, grid, block, lds, st, e0, e1, pl->dev, a);
-  } else {
-    if (has_bound) launch(k_units<MODE, 1, true>, grid, block, lds, st, e0, e1, pl->dev, a);
-    else launch(k_units<MODE, 1, false>, grid, block, lds, st, e0, e1, pl->dev, a);
-  }
+  if (pl->dev.mixed) launch_units_m<MODE, true>(pl, obj, has_bound, a, grid, block, lds, st, e0, e1);
+  else launch_units_m<MODE, false>(pl, obj, has_bound, a, grid, block, lds, st, e0, e1);
 }
 
 // Shared by best_plan (k = 0: tolerance rule) and topk.
@@ -639,7 +660,11 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
     return rc != SAILOR_OK ? rc : SAILOR_EINVAL;
   }
   DevPlan &d = pl->dev;
-  d.G = p->n_types; d.Z = p->n_zones; d.ZG = d.G * d.Z;
+  d.G = p->n_types; d.Z = p->n_zones;
+  d.mixed = p->mixed_types ? 1 : 0;
+  d.GX = extended_types(p);
+  d.ZG = d.GX * d.Z;
+  d.ZGr = d.G * d.Z;
   d.MB = p->n_mb; d.TP = p->n_tp; d.DP = p->n_dp;
   d.bpp = p->bytes_per_param; d.gb = p->grad_bytes_per_param; d.B = p->global_batch;
   d.n_blocks = (int)pl->blocks.size();
@@ -656,17 +681,18 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   d.mg_mb = magic((uint32_t)d.MB);
   d.mg_mbzg = magic((uint32_t)(d.MB * d.ZG));
   d.mg_mbzg1 = d.ZG > 1 ? magic((uint32_t)(d.MB * (d.ZG - 1))) : 0u;
-  d.mg_g = magic((uint32_t)d.G);
+  d.mg_g = magic((uint32_t)d.GX);
   d.mg_mbtp = magic((uint32_t)(d.MB * d.TP));
   d.mg_mbtpdp = magic((uint32_t)(d.MB * d.TP * d.DP));
   pl->eval_lds_bytes = (size_t)3 * d.TP * d.ZG * d.MB * sizeof(Rec) +
                        (size_t)d.MB * d.Z * d.Z * sizeof(float4) +
                        (size_t)3 * d.TP * d.MB * d.DP * sizeof(uint64_t) +
-                       (size_t)3 * d.TP * d.ZG * sizeof(uint32_t) + (size_t)d.ZG * sizeof(PoolInfo) +
+                       (size_t)3 * d.TP * d.ZG * sizeof(uint32_t) +
+                       (size_t)d.ZG * (sizeof(PoolInfo) + sizeof(uint64_t)) +
                        (size_t)(kEvalUnitMaxOuter + d.DP + d.TP) * sizeof(uint32_t);
   pl->lds_bytes = (size_t)3 * d.ZG * d.MB * sizeof(Rec) +
                   (size_t)d.MB * d.Z * d.Z * sizeof(float4) +
-                  (size_t)4 * d.ZG * sizeof(uint32_t);
+                  (size_t)d.ZG * (sizeof(uint64_t) + sizeof(uint32_t));
 
 #define CREATE_TRY(expr)                                                           \
   do {                                                                             \
@@ -680,21 +706,33 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
 
   CREATE_TRY(hipGetDevice(&pl->device));
   DeviceArena &ar = pl->arena;
-  const int G = d.G, Z = d.Z, ZG = d.ZG, MB = d.MB, TP = d.TP, DP = d.DP, L = p->n_layers;
+  const int G = d.G, GX = d.GX, Z = d.Z, ZG = d.ZG, ZGr = d.ZGr, MB = d.MB, TP = d.TP, DP = d.DP,
+            L = p->n_layers;
   const size_t Lc = p->uniform_layers ? 1 : (size_t)L;
   const size_t RS = (size_t)d.n_row_stages, NS = pl->shapes.size();
 
   // inputs, copied as they are
-  CREATE_TRY(ar.alloc(&pl->d_avail, ZG));
-  CREATE_TRY(hipMemcpy(pl->d_avail, p->avail, ZG * sizeof(int32_t), hipMemcpyHostToDevice));
+  CREATE_TRY(ar.alloc(&pl->d_avail, ZGr));
+  CREATE_TRY(hipMemcpy(pl->d_avail, p->avail, ZGr * sizeof(int32_t), hipMemcpyHostToDevice));
   d.avail = pl->d_avail;
-  CREATE_TRY(hipHostMalloc(reinterpret_cast<void **>(&pl->h_avail), ZG * sizeof(int32_t), 0));
+  CREATE_TRY(hipHostMalloc(reinterpret_cast<void **>(&pl->h_avail), ZGr * sizeof(int32_t), 0));
   CREATE_TRY(hipEventCreateWithFlags(&pl->ev_upload, hipEventDisableTiming));
   d.P_max = 0;
   for (int ip = 0; ip < p->n_pp; ++ip) d.P_max = std::max(d.P_max, (int)p->pp_values[ip]);
   d.W_max = d.P_max * p->tp_values[TP - 1];
   CREATE_TRY(ar.alloc(&d.qw, (size_t)(d.W_max + 1) * ZG));
+  if (d.mixed) CREATE_TRY(ar.alloc(&d.qh, (size_t)(2 * d.W_max + 1) * ZGr));
   CREATE_TRY(ar.alloc(&d.h1m, ZG));
+  CREATE_TRY(ar.alloc(&d.isect, ZG));
+  {
+    std::vector<uint16_t> xt;
+    for (int a = 0; a < G; ++a) xt.push_back((uint16_t)(a | (a << 8)));
+    if (d.mixed)
+      for (int a = 0; a < G; ++a)
+        for (int b = a + 1; b < G; ++b) xt.push_back((uint16_t)(a | (b << 8)));
+    pl->xt = xt;
+    CREATE_TRY(ar.upload(&d.xt, xt.data(), xt.size()));
+  }
   CREATE_TRY(ar.upload(&d.cap, p->mem_capacity, G));
   CREATE_TRY(ar.upload(&d.res, p->mem_reserved, G));
   CREATE_TRY(ar.upload(&d.node, p->gpus_per_node, G));
@@ -722,7 +760,7 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(ar.alloc(&d.bwp, (size_t)MB * Z * Z));
   CREATE_TRY(ar.alloc(&d.tsec_f, (size_t)MB * Z * Z));
   CREATE_TRY(ar.alloc(&d.egs_f, (size_t)Z * Z));
-  CREATE_TRY(ar.alloc(&d.price_f, G));
+  CREATE_TRY(ar.alloc(&d.price_f, GX));
   CREATE_TRY(ar.alloc(&d.xb_f, MB));
   CREATE_TRY(ar.alloc(&d.cd_f, DP));
   CREATE_TRY(ar.alloc(&d.nbm1_f, (size_t)MB * DP));
@@ -735,11 +773,11 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(ar.alloc(&d.st_b, RS * G * MB * TP));
   CREATE_TRY(ar.alloc(&d.st_u, RS * G * TP));
   const size_t slots = NS * TP * 3;
-  CREATE_TRY(ar.alloc(&d.ta, slots * G * MB));
-  CREATE_TRY(ar.alloc(&d.memok, slots * G * MB));
+  CREATE_TRY(ar.alloc(&d.ta, slots * GX * MB));
+  CREATE_TRY(ar.alloc(&d.memok, slots * GX * MB));
   CREATE_TRY(ar.alloc(&d.need, slots * MB * DP));
   CREATE_TRY(ar.alloc(&d.syncz, slots * Z));
-  CREATE_TRY(ar.alloc(&d.upd, slots * G));
+  CREATE_TRY(ar.alloc(&d.upd, slots * GX));
   // selection scratch
   CREATE_TRY(ar.alloc(&pl->umin_s, pl->units.size()));
   CREATE_TRY(ar.alloc(&pl->umin_l, pl->units.size()));
@@ -779,7 +817,7 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
     ca.counters = pl->counters;
     ca.lim_s = ca.lim_l = kPosInf;
     ca.ignore_quota = 1;
-    k_units<MODE_SCAN, 0, false><<<(unsigned)NU, pl->unit_threads, pl->lds_bytes>>>(d, ca);
+    launch_units<MODE_SCAN>(pl, SAILOR_MAX_THROUGHPUT, 0, ca, nullptr, nullptr, nullptr);
     CREATE_TRY(hipGetLastError());
     std::vector<float> val(NU);
     CREATE_TRY(hipMemcpy(val.data(), pl->umin_s, NU * sizeof(float), hipMemcpyDeviceToHost));
@@ -794,7 +832,7 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
     CREATE_TRY(hipMemcpy(d_units, pl->units.data(), NU * sizeof(UnitRec), hipMemcpyHostToDevice));
     ca.ignore_quota = 0;
     ca.ucost = d_cost;
-    k_units<MODE_SCAN, 0, false><<<(unsigned)NU, pl->unit_threads, pl->lds_bytes>>>(d, ca);
+    launch_units<MODE_SCAN>(pl, SAILOR_MAX_THROUGHPUT, 0, ca, nullptr, nullptr, nullptr);
     CREATE_TRY(hipGetLastError());
     CREATE_TRY(hipMemcpy(val.data(), d_cost, NU * sizeof(float), hipMemcpyDeviceToHost));
     std::vector<uint32_t> order(NU);
@@ -816,14 +854,14 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
 
 sailor_status sailor_plan_set_avail(sailor_plan *pl, const int32_t *avail) {
   if (!pl || !avail) return SAILOR_EINVAL;
-  for (int i = 0; i < pl->dev.ZG; ++i)
+  for (int i = 0; i < pl->dev.ZGr; ++i)
     if (avail[i] < 0) return SAILOR_EINVAL;
   HIP_TRY(hipSetDevice(pl->device));
   if (pl->upload_pending) {  // the staging buffer may still be read by an earlier upload
     HIP_TRY(hipEventSynchronize(pl->ev_upload));
     pl->upload_pending = false;
   }
-  std::memcpy(pl->h_avail, avail, pl->dev.ZG * sizeof(int32_t));
+  std::memcpy(pl->h_avail, avail, pl->dev.ZGr * sizeof(int32_t));
   pl->avail_dirty = true;  // uploaded, with the quota table, by the next call on its stream
   return SAILOR_OK;
 }

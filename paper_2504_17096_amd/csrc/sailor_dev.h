@@ -79,7 +79,10 @@ struct ResultHeader {   // written by the final kernel into host-mapped memory
 };
 
 struct DevPlan {
-  int G, Z, ZG, MB, TP, DP;
+  // G real GPU types; GX types a segment can choose (G, or G + G (G - 1) / 2 with the pairs
+  // of mixed replicas); ZG = Z * GX pools of the candidate space; ZGr = Z * G real pools
+  int G, GX, Z, ZG, ZGr, MB, TP, DP;
+  int mixed;               // 1: pairs of types exist
   int n_blocks, n_shapes, n_units, n_row_stages, P_max;
   int pst;                 // 1: segments 2 and 3 carry their own tp digit
   int otp;                 // radix of those digits: TP, or 1 when all segments share one tp
@@ -87,7 +90,7 @@ struct DevPlan {
   uint32_t inner;          // MB*TP*DP*ZG candidates per (shape, outer digits)
   uint64_t stride3;        // index stride of segment 3's relative pool: inner*(ZG-1)*otp
   uint32_t bpp, gb;
-  // ceil(2^32 / d) for d = MB, G, MB*TP, MB*TP*DP, MB*ZG, MB*(ZG-1) (0 encodes d = 1)
+  // ceil(2^32 / d) for d = MB, GX, MB*TP, MB*TP*DP, MB*ZG, MB*(ZG-1) (0 encodes d = 1)
   uint32_t mg_mb, mg_g, mg_mbtp, mg_mbtpdp, mg_mbzg, mg_mbzg1;
   int64_t B;
   uint64_t N;
@@ -102,13 +105,17 @@ struct DevPlan {
   const uint64_t *p2p;         // [MB]
   // derived small tables
   uint32_t *qw;                // [W_max + 1][ZG] bit d: dpv[d] replicas of w GPUs fit the pool
-  uint32_t *h1m;               // [ZG] bit k: tpv[k] exceeds the node size of the pool's type (H1)
+                               // (a pair: half of them on each type, dpv[d] even)
+  uint32_t *qh;                // [2 W_max + 1][ZGr] bit d: dpv[d] * x half-GPUs fit the real pool
+  uint32_t *h1m;               // [ZG] bit k: tpv[k] exceeds the node size of the pool's type(s) (H1)
+  const uint16_t *xt;          // [GX] the two real types of an extended type: a | b << 8
+  uint64_t *isect;             // [ZG] bit q: pools p and q draw on a common real pool
   int n_bw_coef;               // 0: constant link bandwidth
   const double *bw_poly;       // [Z][Z][n_bw_coef] bandwidth over log2(message bytes)
   double *bwp;                 // [MB][Z][Z] bandwidth seen by one activation transfer
   float *tsec_f;               // [MB][Z][Z] seconds of one activation transfer a -> b
   float *egs_f;                // [Z][Z] egress both ways
-  float *price_f;              // [G]
+  float *price_f;              // [GX] (a pair: the mean)
   float *xb_f;                 // [MB] (B/mb) * p2p bytes
   float *cd_f;                 // [DP] 2 (D-1) / D
   float *nbm1_f;               // [MB][DP] microbatches per pipeline - 1
@@ -126,12 +133,13 @@ struct DevPlan {
   const ShapeRec *shapes;
   const BlockRec *blocks;
   const UnitRec *units;
-  // per-shape segment aggregates, [shape][TP][3]...
-  float4 *ta;                  // [..][G][MB] {sum, first, last, max interior} of stage compute
-  uint32_t *memok;             // [..][G][MB] bit d: no stage of the segment runs out of memory
+  // per-shape segment aggregates, [shape][TP][3]...  (a pair of types: every stage at the
+  // pace of its slower type, memory on both)
+  float4 *ta;                  // [..][GX][MB] {sum, first, last, max interior} of stage compute
+  uint32_t *memok;             // [..][GX][MB] bit d: no stage of the segment runs out of memory
   uint64_t *need;              // [..][MB][DP] max over stages of model + activation bytes
   float *syncz;                // [..][Z] slowest stage: gradient bytes / intra-zone bandwidth
-  float *upd;                  // [..][G] slowest stage update
+  float *upd;                  // [..][GX] slowest stage update
 };
 
 }  // namespace sailor

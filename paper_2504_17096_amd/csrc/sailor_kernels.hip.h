@@ -66,12 +66,22 @@ __global__ void k_small_tables(DevPlan pl) {
     if (pl.egress && a != b) e = pl.egress[a * Z + b] + pl.egress[b * Z + a];
     pl.egs_f[i] = (float)e;
   }
-  for (int g = t; g < pl.G; g += nt) pl.price_f[g] = (float)pl.price[g];
-  for (int p = t; p < pl.ZG; p += nt) {  // H1: tensor parallelism stays inside a node
-    uint32_t m = 0;
+  for (int g = t; g < pl.GX; g += nt) {
+    const int ga = pl.xt[g] & 255, gb = pl.xt[g] >> 8;
+    pl.price_f[g] = (float)(ga == gb ? pl.price[ga] : 0.5 * (pl.price[ga] + pl.price[gb]));
+  }
+  for (int p = t; p < pl.ZG; p += nt) {
+    const int x = pl.xt[p % pl.GX], ga = x & 255, gb = x >> 8, z = p / pl.GX;
+    uint32_t m = 0;  // H1: tensor parallelism stays inside a node
     for (int k = 0; k < pl.TP; ++k)
-      if (pl.tpv[k] > pl.node[p % pl.G]) m |= 1u << k;
+      if (pl.tpv[k] > pl.node[ga] || pl.tpv[k] > pl.node[gb]) m |= 1u << k;
     pl.h1m[p] = m;
+    uint64_t im = 0;  // pools of the same zone with a real type in common (itself included)
+    for (int q = 0; q < pl.ZG; ++q) {
+      const int y = pl.xt[q % pl.GX], qa = y & 255, qb = y >> 8;
+      if (q / pl.GX == z && (qa == ga || qa == gb || qb == ga || qb == gb)) im |= 1ull << q;
+    }
+    pl.isect[p] = im;
   }
   for (int m = t; m < pl.MB; m += nt) {
     // N_b * D = B / mb whenever the batch divides; the product is exact in fp64 for
@@ -155,7 +165,7 @@ __device__ __forceinline__ uint64_t stage_bytes(const DevPlan &pl, uint32_t rs, 
 __global__ void k_shape_agg(DevPlan pl) {
   const uint32_t shp = blockIdx.x;
   const ShapeRec sh = pl.shapes[shp];
-  const int G = pl.G, MB = pl.MB, TP = pl.TP, DP = pl.DP, P = sh.P;
+  const int G = pl.G, GX = pl.GX, MB = pl.MB, TP = pl.TP, DP = pl.DP, P = sh.P;
   const int t = threadIdx.x, nt = blockDim.x;
   // need[tp][seg][mb][dp], syncz, upd
   for (int it = t; it < TP * 3 * MB * DP; it += nt) {
@@ -182,22 +192,28 @@ __global__ void k_shape_agg(DevPlan pl) {
       }
     pl.syncz[agg_slot(pl, shp, k, seg) * pl.Z + z] = (float)mx;
   }
-  for (int it = t; it < TP * 3 * G; it += nt) {
-    int g = it % G, seg = (it / G) % 3, k = it / (G * 3);
+  for (int it = t; it < TP * 3 * GX; it += nt) {
+    int g = it % GX, seg = (it / GX) % 3, k = it / (GX * 3);
+    const int ga = pl.xt[g] & 255, gb = pl.xt[g] >> 8;
     double mx = 0.0;
     if (seg < sh.s)
-      for (int i = sh.lo[seg]; i < sh.lo[seg] + sh.n[seg]; ++i)
-        mx = fmax(mx, pl.st_u[((size_t)(sh.row_stage + i) * G + g) * TP + k]);
-    pl.upd[agg_slot(pl, shp, k, seg) * G + g] = (float)mx;
+      for (int i = sh.lo[seg]; i < sh.lo[seg] + sh.n[seg]; ++i) {
+        mx = fmax(mx, pl.st_u[((size_t)(sh.row_stage + i) * G + ga) * TP + k]);
+        mx = fmax(mx, pl.st_u[((size_t)(sh.row_stage + i) * G + gb) * TP + k]);
+      }
+    pl.upd[agg_slot(pl, shp, k, seg) * GX + g] = (float)mx;
   }
-  for (int it = t; it < TP * 3 * G * MB; it += nt) {
-    int m = it % MB, g = (it / MB) % G, seg = (it / (MB * G)) % 3, k = it / (MB * G * 3);
+  for (int it = t; it < TP * 3 * GX * MB; it += nt) {
+    int m = it % MB, g = (it / MB) % GX, seg = (it / (MB * GX)) % 3, k = it / (MB * GX * 3);
+    const int ga = pl.xt[g] & 255, gb = pl.xt[g] >> 8;
     float4 v = make_float4(0.f, 0.f, kNegInf, kNegInf);
     if (seg < sh.s) {
       const int lo = sh.lo[seg], n = sh.n[seg];
       double sum = 0.0, mxi = -__builtin_huge_val(), fst = 0.0, lst = 0.0;
       for (int i = lo; i < lo + n; ++i) {
-        double c = pl.st_c[(((size_t)(sh.row_stage + i) * G + g) * MB + m) * TP + k];
+        // replicas of two types: the slower one sets the stage's pace (straggler, Sec. 4.3)
+        double c = fmax(pl.st_c[(((size_t)(sh.row_stage + i) * G + ga) * MB + m) * TP + k],
+                        pl.st_c[(((size_t)(sh.row_stage + i) * G + gb) * MB + m) * TP + k]);
         sum += c;
         if (i == lo) fst = c;
         if (i == lo + n - 1) lst = c;
@@ -205,20 +221,22 @@ __global__ void k_shape_agg(DevPlan pl) {
       }
       v = make_float4((float)sum, (float)fst, (float)lst, (float)mxi);
     }
-    pl.ta[(agg_slot(pl, shp, k, seg) * G + g) * MB + m] = v;
+    pl.ta[(agg_slot(pl, shp, k, seg) * GX + g) * MB + m] = v;
   }
   __syncthreads();
   __threadfence();
   // memok bit d: largest worker of the segment fits the type's memory
-  for (int it = t; it < TP * 3 * G * MB; it += nt) {
-    int m = it % MB, g = (it / MB) % G, seg = (it / (MB * G)) % 3, k = it / (MB * G * 3);
+  for (int it = t; it < TP * 3 * GX * MB; it += nt) {
+    int m = it % MB, g = (it / MB) % GX, seg = (it / (MB * GX)) % 3, k = it / (MB * GX * 3);
+    const int ga = pl.xt[g] & 255, gb = pl.xt[g] >> 8;
     uint32_t bits = 0;
     if (seg < sh.s)
       for (int d = 0; d < DP; ++d) {
         uint64_t need = pl.need[(agg_slot(pl, shp, k, seg) * MB + m) * DP + d];
-        if (pl.nb[m * DP + d] > 0 && need + pl.res[g] <= pl.cap[g]) bits |= 1u << d;
+        if (pl.nb[m * DP + d] > 0 && need + pl.res[ga] <= pl.cap[ga] && need + pl.res[gb] <= pl.cap[gb])
+          bits |= 1u << d;
       }
-    pl.memok[(agg_slot(pl, shp, k, seg) * G + g) * MB + m] = bits;
+    pl.memok[(agg_slot(pl, shp, k, seg) * GX + g) * MB + m] = bits;
   }
 }
 
@@ -311,16 +329,64 @@ __device__ __forceinline__ void acc_finish(const Acc &p, const LaneC &lc, float 
 // Quota table, rebuilt whenever the availability changes: a replica that takes w GPUs
 // from a pool (its stages there times their tensor-parallel degrees) can be placed for
 // the data-parallel degrees whose bit is set (Sec. 4: resource quotas).
+// A pool that is a pair of types gives half of the replicas from each (an even number of
+// them); qh serves plans whose segments draw on one real pool together: x half-GPUs per
+// replica of the plan fit the real pool for the degrees whose bit is set.
 __global__ void k_quota_table(DevPlan pl) {
   const int n = (pl.W_max + 1) * pl.ZG;
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
     const int p = i % pl.ZG, w = i / pl.ZG;
-    const int64_t avail = pl.avail[p];
+    const int x = pl.xt[p % pl.GX], ga = x & 255, gb = x >> 8, z = p / pl.GX;
+    const int64_t avail_a = pl.avail[z * pl.G + ga], avail_b = pl.avail[z * pl.G + gb];
     uint32_t bits = 0;
-    for (int d = 0; d < pl.DP; ++d)
-      if ((int64_t)w * pl.dpv[d] <= avail) bits |= 1u << d;
+    for (int d = 0; d < pl.DP; ++d) {
+      const int64_t D = pl.dpv[d];
+      if (ga == gb ? (int64_t)w * D <= avail_a
+                   : (D % 2 == 0 && (int64_t)w * D <= 2 * avail_a && (int64_t)w * D <= 2 * avail_b))
+        bits |= 1u << d;
+    }
     pl.qw[i] = bits;
   }
+  if (!pl.mixed) return;
+  const int nh = (2 * pl.W_max + 1) * pl.ZGr;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < nh; i += gridDim.x * blockDim.x) {
+    const int r = i % pl.ZGr, x = i / pl.ZGr;
+    const int64_t avail2 = 2 * (int64_t)pl.avail[r];
+    uint32_t bits = 0;
+    for (int d = 0; d < pl.DP; ++d)
+      if ((int64_t)x * pl.dpv[d] <= avail2) bits |= 1u << d;
+    pl.qh[i] = bits;
+  }
+}
+
+// Plans whose segments draw on one real pool together (possible once pairs of types exist):
+// bit d is set when dpv[d] replicas of all segments fit every real pool.  p[j], w[j]: pool and
+// GPUs per replica of segment j.
+__device__ __forceinline__ uint32_t joint_quota_bits(const DevPlan &pl, int n_seg, int p0, int p1,
+                                                     int p2, int w0, int w1, int w2) {
+  // six slots (two per segment) of (real pool, half-GPUs per replica); constant trip counts,
+  // so that everything stays in registers
+  int r[6], h[6];
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    const int p = j == 0 ? p0 : (j == 1 ? p1 : p2), w = j == 0 ? w0 : (j == 1 ? w1 : w2);
+    const bool used = j < n_seg;
+    const int x = pl.xt[used ? p % pl.GX : 0], ga = x & 255, gb = x >> 8, z = used ? p / pl.GX : 0;
+    r[2 * j] = z * pl.G + ga;
+    r[2 * j + 1] = z * pl.G + gb;
+    h[2 * j] = !used ? 0 : (ga == gb ? 2 * w : w);
+    h[2 * j + 1] = (!used || ga == gb) ? 0 : w;
+  }
+  uint32_t bits = 0xFFFFFFFFu;
+#pragma unroll
+  for (int i = 0; i < 6; ++i) {
+    int total = 0;
+#pragma unroll
+    for (int k = 0; k < 6; ++k) total += (r[k] == r[i]) ? h[k] : 0;
+    // (a pool that several slots name is checked several times against the same total)
+    if (h[i] != 0) bits &= pl.qh[(size_t)total * pl.ZGr + r[i]];
+  }
+  return bits;
 }
 
 enum { MODE_SCAN = 0, MODE_COLLECT = 1 };
@@ -447,14 +513,17 @@ __device__ __forceinline__ bool wave_any(bool p) { return __builtin_amdgcn_ballo
 // Invalid plans are pruned early (cf. H2, Sec. 4.2.1): as soon as the validity bits of the
 // segments placed so far are zero in every lane of a wave, the wave skips everything that
 // depends on the remaining segments.
-template <int S, int MODE, int OBJ, bool HASB>
+// With pairs of types (MIXED) different pools can draw on one real pool; the plans concerned
+// (isect) get the joint quota check, the others keep the per-segment bits.
+template <int S, int MODE, int OBJ, bool HASB, bool MIXED>
 __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, const UnitRec &u,
                                           const Rec *rec, const float4 *pair,
-                                          const uint32_t *q13, float tau, int sub, int n_sub,
+                                          const uint32_t *q13, const uint64_t *isect, int w0,
+                                          int w1, int w2, float tau, int sub, int n_sub,
                                           float &ms, float &ml) {
   // the chunks of the lane space are dealt round-robin to the waves of the n_sub
   // workgroups that share the unit
-  const int ZG = pl.ZG, G = pl.G, MB = pl.MB, DP = pl.DP, Z = pl.Z;
+  const int ZG = pl.ZG, G = pl.GX, MB = pl.MB, DP = pl.DP, Z = pl.Z;
   const int lane = threadIdx.x & 63;
   const int wave = (int)(threadIdx.x >> 6) + (int)(blockDim.x >> 6) * sub;
   const int nwave = (int)(blockDim.x >> 6) * n_sub;
@@ -484,7 +553,9 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
       int z2 = u.o_lo / G, g2 = u.o_lo % G;
       for (int a2 = u.o_lo; a2 < u.o_lo + u.o_cnt; ++a2) {
         const Rec *rp1 = recm + (ZG + a2) * MB;
-        const uint32_t b1 = (a1 != a2) ? (b0 & rp1->bits) : 0u;
+        uint32_t b1 = (a1 != a2) ? (b0 & rp1->bits) : 0u;
+        if (MIXED && b1 != 0 && ((isect[a2] >> a1) & 1ull))
+          b1 &= joint_quota_bits(pl, 2, a1, a2, 0, w0, w1, 0);
         if (wave_any(b1 != 0)) {
           const Rec r1 = *rp1;
           const float4 p12 = pair1[z2];
@@ -503,6 +574,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
     const int nin = MB * DP * (ZG - 1);
     int z2 = u.o_lo / G, g2 = u.o_lo % G;
     for (int a2 = u.o_lo; a2 < u.o_lo + u.o_cnt; ++a2) {
+      const uint64_t is2 = MIXED ? isect[a2] : 0ull;
       for (int e0 = wave * 64; e0 < nin; e0 += nwave * 64) {
         const LaneItem it = lane_item(pl, e0 + lane, nin, ZG - 1, pl.mg_mbzg1);
         const int a1 = it.a1 + (it.a1 >= a2 ? 1 : 0);  // skip the pool of segment 2
@@ -515,7 +587,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
         const float4 *pairm = pair + it.mb * Z * Z;
         const float4 p12 = pairm[z1 * Z + z2];
         const Acc A1 = acc_cross(acc_begin(r0), r1, p12.x, p12.y, p12.z, single0, true);
-        const uint32_t q13a = q13[a1];
+        const uint32_t q13a = MIXED ? 0u : q13[a1];
         int rel2 = a2 - a1 - 1;
         if (rel2 < 0) rel2 += ZG;
         const uint64_t idx0 = ubase + (uint64_t)(it.mb + MB * (tp + pl.TP * (it.dp + DP * a1))) +
@@ -525,7 +597,12 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
           if (a3 != a2) {  // uniform
             const Rec *rp2 = recm + (2 * ZG + a3) * MB;
             uint32_t b2 = b1 & rp2->bits;
-            if (a3 == a1) b2 &= q13a;  // segments 1 and 3 share one pool's quota
+            if (MIXED) {
+              if (b2 != 0 && (((is2 >> a1) | (is2 >> a3) | (isect[a3] >> a1)) & 1ull))
+                b2 &= joint_quota_bits(pl, 3, a1, a2, a3, w0, w1, w2);
+            } else if (a3 == a1) {
+              b2 &= q13a;  // segments 1 and 3 share one pool's quota
+            }
             if (wave_any(b2 != 0)) {
               const Rec r2 = *rp2;
               const float4 p23 = pairm[z2 * Z + z3];
@@ -550,7 +627,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
 // its (mb, dp, pool 1) triple over the unit's outer pool digits.  Everything the staging
 // needs comes from the unit record and tables that do not depend on one another, so all of
 // its global loads are in flight together and one barrier ends it.
-template <int MODE, int OBJ, bool HASB>
+template <int MODE, int OBJ, bool HASB, bool MIXED>
 __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, uint32_t uidx,
                                           int sub, uint32_t n_sub, uint4 *lds_raw) {
   const unsigned long long t_begin = (MODE == MODE_SCAN && a.ucost) ? wall_clock64() : 0ull;
@@ -561,10 +638,11 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
     const float um = a.umin_l[uidx];
     if (!(um < kPosInf && um <= tau)) return;  // uniform over the workgroup
   }
-  const int ZG = pl.ZG, G = pl.G, MB = pl.MB, Z = pl.Z, S = u.s;
-  Rec *rec = reinterpret_cast<Rec *>(lds_raw);                      // [S][ZG][MB]
-  float4 *pair = reinterpret_cast<float4 *>(rec + 3 * ZG * MB);     // [MB][Z][Z]
-  uint32_t *q13 = reinterpret_cast<uint32_t *>(pair + MB * Z * Z);  // [ZG]
+  const int ZG = pl.ZG, G = pl.GX, MB = pl.MB, Z = pl.Z, S = u.s;
+  Rec *rec = reinterpret_cast<Rec *>(lds_raw);                        // [S][ZG][MB]
+  float4 *pair = reinterpret_cast<float4 *>(rec + 3 * ZG * MB);       // [MB][Z][Z]
+  uint64_t *isect = reinterpret_cast<uint64_t *>(pair + MB * Z * Z);  // [ZG]
+  uint32_t *q13 = reinterpret_cast<uint32_t *>(isect + ZG);           // [ZG]
   __shared__ float red[2][kMaxUnitThreads / 64];
   __shared__ uint32_t s_any[kMaxUnitThreads / 64];  // per wave, bit j: a pool can host segment j
   const int t = threadIdx.x;
@@ -593,9 +671,11 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
     const bool counts = seg != 1 || (p >= (int)u.o_lo && p < (int)(u.o_lo + u.o_cnt));
     if (bits != 0 && counts) any_here |= 1u << seg;
   }
-  if (S == 3)
+  if (S == 3 && !MIXED)
     for (int p = t; p < ZG; p += blockDim.x)
       q13[p] = a.ignore_quota ? 0xFFFFFFFFu : pl.qw[(w0 + w2) * ZG + p];
+  if (MIXED)  // under ignore_quota no pool counts as shared
+    for (int p = t; p < ZG; p += blockDim.x) isect[p] = a.ignore_quota ? 0ull : pl.isect[p];
   for (int i = t; i < MB * Z * Z; i += blockDim.x) {  // per mb: transfer a -> b, b -> a, egress
     const int m = i / (Z * Z), ab = i - m * Z * Z, za = ab / Z, zb = ab % Z;
     pair[i] = make_float4(pl.tsec_f[i], pl.tsec_f[(m * Z + zb) * Z + za], pl.egs_f[ab], 0.f);
@@ -620,9 +700,9 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
   }
 
   float ms = kPosInf, ml = kPosInf;
-  if (S == 1) unit_body<1, MODE, OBJ, HASB>(pl, a, u, rec, pair, q13, tau, sub, (int)n_sub, ms, ml);
-  else if (S == 2) unit_body<2, MODE, OBJ, HASB>(pl, a, u, rec, pair, q13, tau, sub, (int)n_sub, ms, ml);
-  else unit_body<3, MODE, OBJ, HASB>(pl, a, u, rec, pair, q13, tau, sub, (int)n_sub, ms, ml);
+  if (S == 1) unit_body<1, MODE, OBJ, HASB, MIXED>(pl, a, u, rec, pair, q13, isect, w0, w1, w2, tau, sub, (int)n_sub, ms, ml);
+  else if (S == 2) unit_body<2, MODE, OBJ, HASB, MIXED>(pl, a, u, rec, pair, q13, isect, w0, w1, w2, tau, sub, (int)n_sub, ms, ml);
+  else unit_body<3, MODE, OBJ, HASB, MIXED>(pl, a, u, rec, pair, q13, isect, w0, w1, w2, tau, sub, (int)n_sub, ms, ml);
 
   if (MODE == MODE_SCAN) {
     if (!HASB) ml = ms;
@@ -649,19 +729,19 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
 
 // SCAN: one workgroup per unit.  COLLECT: n_sub workgroups share a unit; with a unit list
 // the grid strides over the list instead of covering every unit.
-template <int MODE, int OBJ, bool HASB>
+template <int MODE, int OBJ, bool HASB, bool MIXED>
 __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs a) {
   extern __shared__ uint4 lds_raw[];
   if (MODE == MODE_SCAN) {
-    unit_work<MODE, OBJ, HASB>(pl, a, blockIdx.x, 0, 1u, lds_raw);
+    unit_work<MODE, OBJ, HASB, MIXED>(pl, a, blockIdx.x, 0, 1u, lds_raw);
   } else if (!a.ulist) {
-    unit_work<MODE, OBJ, HASB>(pl, a, blockIdx.x / a.n_sub, (int)(blockIdx.x % a.n_sub), a.n_sub,
+    unit_work<MODE, OBJ, HASB, MIXED>(pl, a, blockIdx.x / a.n_sub, (int)(blockIdx.x % a.n_sub), a.n_sub,
                                lds_raw);
   } else {
     const uint32_t n_list = a.counters[CNT_NLIST], per_round = gridDim.x / a.n_sub;
     const int sub = (int)(blockIdx.x % a.n_sub);
     for (uint32_t e = blockIdx.x / a.n_sub; e < n_list; e += per_round) {  // uniform
-      unit_work<MODE, OBJ, HASB>(pl, a, a.ulist[e], sub, a.n_sub, lds_raw);
+      unit_work<MODE, OBJ, HASB, MIXED>(pl, a, a.ulist[e], sub, a.n_sub, lds_raw);
       __syncthreads();  // the staging area is reused
     }
   }
@@ -806,7 +886,7 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
                                                 int has_bound, double bound, RefineLds &lds,
                                                 double &T, double &C, uint64_t &peak,
                                                 uint32_t &mask) {
-  const int G = pl.G, Z = pl.Z, MB = pl.MB, TP = pl.TP, DP = pl.DP, P = c.P;
+  const int G = pl.G, GX = pl.GX, Z = pl.Z, MB = pl.MB, TP = pl.TP, DP = pl.DP, P = c.P;
   const int lane = threadIdx.x & 63;
   const ShapeRec sh = pl.shapes[c.shape];
   const uint32_t rs = sh.row_stage;
@@ -822,36 +902,51 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
   const double p2p = (double)pl.p2p[c.mb];
   const double *bwp = pl.bwp + c.mb * Z * Z;  // bandwidth seen by a transfer of p2p bytes
   // quota per pool (GPUs of one replica there, times D) and H1
+  // (counted in halves: a segment on a pair of types takes half of its replicas from each)
   for (int j = 0; j < c.s; ++j) {
-    int64_t gpus = 0;
-    for (int j2 = 0; j2 < c.s; ++j2)
-      if (c.a[j2] == c.a[j]) gpus += (int64_t)sh.n[j2] * pl.tpv[c.tp[j2]];
-    if (gpus * D > (int64_t)pl.avail[c.a[j]]) mask |= 2u;
-    if (pl.tpv[c.tp[j]] > pl.node[c.a[j] % G]) mask |= 8u;
+    const int x = pl.xt[c.a[j] % GX], ga = x & 255, gb = x >> 8, z = c.a[j] / GX;
+    for (int slot = 0; slot < (ga == gb ? 1 : 2); ++slot) {
+      const int g = slot == 0 ? ga : gb;
+      int64_t halves = 0;
+      for (int j2 = 0; j2 < c.s; ++j2) {
+        const int x2 = pl.xt[c.a[j2] % GX], a2 = x2 & 255, b2 = x2 >> 8;
+        if (c.a[j2] / GX != z) continue;
+        const int64_t w = (int64_t)sh.n[j2] * pl.tpv[c.tp[j2]];
+        if (a2 == b2) halves += a2 == g ? 2 * w : 0;
+        else halves += (a2 == g || b2 == g) ? w : 0;
+      }
+      if (halves * D > 2 * (int64_t)pl.avail[z * G + g]) mask |= 2u;
+    }
+    if (ga != gb && D % 2 != 0) mask |= 2u;  // D replicas cannot be halved
+    if (pl.tpv[c.tp[j]] > pl.node[ga] || pl.tpv[c.tp[j]] > pl.node[gb]) mask |= 8u;
   }
   double max_t = 0.0, t_sync = 0.0, t_upd = 0.0;
   uint32_t oom = 0;
   for (int i = lane; i < P; i += 64) {
     const int seg = i < c.k1 ? 0 : (i < c.k2 ? 1 : 2);
-    const int g = c.a[seg] % G, z = c.a[seg] / G;
+    const int xg = pl.xt[c.a[seg] % GX], g = xg & 255, g2 = xg >> 8, z = c.a[seg] / GX;
     const int k = c.tp[seg];
     const int64_t tp = pl.tpv[k];
-    const uint64_t m = stage_bytes(pl, rs, i, P, (int)tp, nb, pl.act[c.mb * TP + k]) + pl.res[g];
-    if (m > pl.cap[g]) oom = 1u;
+    const uint64_t bytes_i = stage_bytes(pl, rs, i, P, (int)tp, nb, pl.act[c.mb * TP + k]);
+    const uint64_t m = bytes_i + pl.res[g], m2 = bytes_i + pl.res[g2];  // both replica types
+    if (m > pl.cap[g] || m2 > pl.cap[g2]) oom = 1u;
     peak = m > peak ? m : peak;
+    peak = m2 > peak ? m2 : peak;
     double x = 0.0, comm = 0.0;
     if (i < P - 1) {
       const int sn = (i + 1) < c.k1 ? 0 : ((i + 1) < c.k2 ? 1 : 2);
-      const int zn = c.a[sn] / G;
+      const int zn = c.a[sn] / GX;
       x += p2p / bwp[z * Z + zn];
       if (pl.egress && zn != z)
         comm = (double)nb * (double)D * p2p * (pl.egress[z * Z + zn] + pl.egress[zn * Z + z]);
     }
     if (i > 0) {
       const int sp = (i - 1) < c.k1 ? 0 : ((i - 1) < c.k2 ? 1 : 2);
-      x += p2p / bwp[z * Z + c.a[sp] / G];
+      x += p2p / bwp[z * Z + c.a[sp] / GX];
     }
-    const double t = pl.st_c[(((size_t)(rs + i) * G + g) * MB + c.mb) * TP + k] + x;
+    // the slower replica type sets the stage's pace (straggler, Sec. 4.3)
+    const double t = fmax(pl.st_c[(((size_t)(rs + i) * G + g) * MB + c.mb) * TP + k],
+                          pl.st_c[(((size_t)(rs + i) * G + g2) * MB + c.mb) * TP + k]) + x;
     max_t = fmax(max_t, t);
     if (D > 1) {
       const uint64_t shard = (pl.st_params[rs + i] + (uint64_t)tp - 1) / (uint64_t)tp;
@@ -860,8 +955,10 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
       t_sync = fmax(t_sync, sync);
     }
     t_upd = fmax(t_upd, pl.st_u[((size_t)(rs + i) * G + g) * TP + k]);
+    t_upd = fmax(t_upd, pl.st_u[((size_t)(rs + i) * G + g2) * TP + k]);
     lds.t[i] = t;
-    lds.dol[i] = (double)(D * tp) * pl.price[g];
+    lds.dol[i] = g == g2 ? (double)(D * tp) * pl.price[g]
+                         : (double)(D * tp) * (0.5 * (pl.price[g] + pl.price[g2]));
     lds.comm[i] = comm;
   }
   if (__builtin_amdgcn_ballot_w64(oom != 0) != 0) mask |= 1u;
@@ -1068,7 +1165,7 @@ __global__ __launch_bounds__(256) void k_sim_1f1b(DevPlan pl, SimArgs a) {
     }
     return;
   }
-  const int P = c.P, G = pl.G, Z = pl.Z, MB = pl.MB, TP = pl.TP;
+  const int P = c.P, G = pl.G, GX = pl.GX, Z = pl.Z, MB = pl.MB, TP = pl.TP;
   const int M = pl.nb[c.mb * pl.DP + c.dp];
   if (M == 0) {  // the batch does not divide
     if (i == 0) {
@@ -1082,20 +1179,25 @@ __global__ __launch_bounds__(256) void k_sim_1f1b(DevPlan pl, SimArgs a) {
   double fdur = 0.0, bdur = 0.0;
   if (mine) {
     const int seg = i < c.k1 ? 0 : (i < c.k2 ? 1 : 2);
-    const int g = c.a[seg] % G, z = c.a[seg] / G, k = c.tp[seg];
+    const int xg = pl.xt[c.a[seg] % GX], g = xg & 255, g2 = xg >> 8, z = c.a[seg] / GX, k = c.tp[seg];
     const size_t at = (((size_t)(sh.row_stage + i) * G + g) * MB + c.mb) * TP + k;
+    const size_t at2 = (((size_t)(sh.row_stage + i) * G + g2) * MB + c.mb) * TP + k;
     const double p2p = (double)pl.p2p[c.mb];
     const double *bwp = pl.bwp + c.mb * Z * Z;
     double send_f = 0.0, send_b = 0.0;
     if (i < P - 1) {
       const int sn = (i + 1) < c.k1 ? 0 : ((i + 1) < c.k2 ? 1 : 2);
-      send_f = p2p / bwp[z * Z + c.a[sn] / G];
+      send_f = p2p / bwp[z * Z + c.a[sn] / GX];
     }
     if (i > 0) {
       const int sp = (i - 1) < c.k1 ? 0 : ((i - 1) < c.k2 ? 1 : 2);
-      send_b = p2p / bwp[z * Z + c.a[sp] / G];
+      send_b = p2p / bwp[z * Z + c.a[sp] / GX];
     }
-    const double f = pl.st_f[at], b = pl.st_b[at];
+    double f = pl.st_f[at], b = pl.st_b[at];
+    if (g2 != g && pl.st_f[at2] + pl.st_b[at2] > f + b) {  // the pipeline through the slower type
+      f = pl.st_f[at2];
+      b = pl.st_b[at2];
+    }
     fdur = f + send_f;
     bdur = b + send_b;
     s_t[i] = f + b + (send_f + send_b);
@@ -1172,32 +1274,41 @@ template <int S>
 __device__ __forceinline__ void eval_direct_s(const DevPlan &pl, const Cand &c, const ShapeRec &sh,
                                               const LaneC &lc, float &T, float &C, uint64_t &peak,
                                               uint32_t &mask) {
-  const int G = pl.G, Z = pl.Z, MB = pl.MB, DP = pl.DP;
+  const int GX = pl.GX, Z = pl.Z, MB = pl.MB, DP = pl.DP;
   const int64_t D = pl.dpv[c.dp];
+  const float *ts = pl.tsec_f + c.mb * Z * Z;  // transfer seconds of this microbatch size
   Acc acc;
+  int w[3] = {0, 0, 0};
 #pragma unroll
   for (int j = 0; j < S; ++j) {
-    const int p = c.a[j], g = p % G, z = p / G;
+    const int p = c.a[j], gx = p % GX, z = p / GX;
+    const int ga = pl.xt[gx] & 255, gb = pl.xt[gx] >> 8;
     const int tpv = pl.tpv[c.tp[j]];
     const size_t sl = agg_slot(pl, c.shape, c.tp[j], j);
-    const float *ts = pl.tsec_f + c.mb * Z * Z;  // transfer seconds of this microbatch size
-    const Rec r = make_rec(pl.ta[(sl * G + g) * MB + c.mb], pl.syncz[sl * Z + z], pl.upd[sl * G + g],
-                           pl.price_f[g], ts[z * Z + z], sh.n[j], tpv, 0u);
-    const uint64_t m = pl.need[(sl * MB + c.mb) * DP + c.dp] + pl.res[g];
-    if (m > pl.cap[g]) mask |= 1u;
+    const Rec r = make_rec(pl.ta[(sl * GX + gx) * MB + c.mb], pl.syncz[sl * Z + z], pl.upd[sl * GX + gx],
+                           pl.price_f[gx], ts[z * Z + z], sh.n[j], tpv, 0u);
+    const uint64_t need = pl.need[(sl * MB + c.mb) * DP + c.dp];
+    const uint64_t m = need + pl.res[ga], m2 = need + pl.res[gb];
+    if (m > pl.cap[ga] || m2 > pl.cap[gb]) mask |= 1u;
     peak = m > peak ? m : peak;
-    int64_t gpus = (int64_t)sh.n[j] * tpv;  // of one replica on this pool
-    if (S == 3 && (j == 0 || j == 2) && c.a[0] == c.a[2])
-      gpus = (int64_t)sh.n[0] * pl.tpv[c.tp[0]] + (int64_t)sh.n[2] * pl.tpv[c.tp[2]];
-    if (gpus * D > (int64_t)pl.avail[p]) mask |= 2u;
-    if (tpv > pl.node[g]) mask |= 8u;
+    peak = m2 > peak ? m2 : peak;
+    w[j] = sh.n[j] * tpv;  // GPUs of one replica on this pool
+    if (!((pl.qw[(size_t)w[j] * pl.ZG + p] >> c.dp) & 1u)) mask |= 2u;
+    if (tpv > pl.node[ga] || tpv > pl.node[gb]) mask |= 8u;
     if (j == 0) {
       acc = acc_begin(r);
     } else {
-      const int zp = c.a[j - 1] / G;
+      const int zp = c.a[j - 1] / GX;
       acc = acc_cross(acc, r, ts[zp * Z + z], ts[z * Z + zp],
                       pl.egs_f[zp * Z + z], sh.n[j - 1] == 1, j == 1);
     }
+  }
+  // segments that draw on one real pool together
+  if (pl.mixed) {
+    if (S >= 2 && !((joint_quota_bits(pl, S, c.a[0], c.a[1], c.a[2], w[0], w[1], w[2]) >> c.dp) & 1u))
+      mask |= 2u;
+  } else if (S == 3 && c.a[0] == c.a[2]) {
+    if ((int64_t)(w[0] + w[2]) * D > (int64_t)pl.avail[c.a[0]]) mask |= 2u;
   }
   acc_finish(acc, lc, T, C);
 }
@@ -1242,9 +1353,10 @@ __global__ __launch_bounds__(256) void k_eval_direct(DevPlan pl, EvalArgs a) {
 // shape for every tp are staged in LDS.  A lane keeps its inner digits (mb, tp, dp, pool 1)
 // while the unit's outer digits advance, and consecutive lanes hold consecutive
 // candidate indices, so every store instruction writes 64 consecutive elements.
-struct PoolInfo {   // per pool, staged in LDS
-  uint64_t res, cap;
-  int32_t avail;
+struct PoolInfo {   // per pool, staged in LDS (a pair of types: the tighter of the two)
+  uint64_t res;     // reserved bytes (the larger)
+  int64_t room;     // capacity - reserved (the smaller; negative when nothing fits)
+  int32_t avail;    // GPUs available (plain types only)
   uint32_t meta;    // zone | (bit 8 + k: tp k exceeds the node size) (H1)
 };
 
@@ -1257,7 +1369,7 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
                                                const Rec *rec, const float4 *pair,
                                                const uint32_t *qm, const uint64_t *need,
                                                const PoolInfo *pinfo, const uint32_t *odec,
-                                               const int32_t *vals) {
+                                               const int32_t *vals, const uint64_t *isect) {
   const uint32_t ZG = pl.ZG, MB = pl.MB, TP = pl.TP, DP = pl.DP, Z = pl.Z;
   const uint32_t inner = pl.inner;
   const uint64_t last = a.first + a.count;
@@ -1294,9 +1406,9 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
     const Rec r0 = recl[tpo_rec + mul24(p0, MB)];
     const Acc A0 = acc_begin(r0);
     const PoolInfo i0 = pinfo[p0];
-    const uint64_t mem0 = needl[tpo_need] + i0.res;
+    const uint64_t need0 = needl[tpo_need], mem0 = need0 + i0.res;
     uint32_t mask0 = 0;
-    if (mem0 > i0.cap) mask0 |= 1u;
+    if ((int64_t)need0 > i0.room) mask0 |= 1u;
     if (i0.meta & (1u << (8 + tp))) mask0 |= 8u;
     const bool q0 = (qm[tpo_qm + p0] >> dp) & 1u;
     const uint32_t z0 = i0.meta & 0xFFu;
@@ -1329,12 +1441,15 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
           const Rec r1 = recl[o_rec + mul24(p1, MB)];
           const PoolInfo i1 = pinfo[p1];
           const uint32_t z1 = i1.meta & 0xFFu;
-          const uint64_t mem1 = needl[o_need] + i1.res;
-          if (mem1 > i1.cap) mask |= 1u;
+          const uint64_t need1 = needl[o_need], mem1 = need1 + i1.res;
+          if ((int64_t)need1 > i1.room) mask |= 1u;
           if (i1.meta & (1u << (8 + t1))) mask |= 8u;
           peak = mem1 > peak ? mem1 : peak;
           const bool q1 = (qm[o_qm + p1] >> dp) & 1u;
           quota_ok = quota_ok && q1;
+          if (S == 2 && pl.mixed && quota_ok && ((isect[p0] >> p1) & 1ull))
+            quota_ok = (joint_quota_bits(pl, 2, (int)p0, (int)p1, 0, (int)gpus0,
+                                         sh.n[1] * vals[DP + t1], 0) >> dp) & 1u;
           const float4 pr = pairm[mul24(z0, Z) + z1];
           acc = acc_cross(acc, r1, pr.x, pr.y, pr.z, single0, true);
           if (S == 3) {
@@ -1347,11 +1462,16 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
             const uint32_t o_qm2 = 2 * seg_qm + (PST ? mul24(t2, ZG) : tpo_qm);
             const Rec r2r = recl[o_rec2 + mul24(p2, MB)];
             const PoolInfo i2 = pinfo[p2];
-            const uint64_t mem2 = needl[o_need2] + i2.res;
-            if (mem2 > i2.cap) mask |= 1u;
+            const uint64_t need2 = needl[o_need2], mem2 = need2 + i2.res;
+            if ((int64_t)need2 > i2.room) mask |= 1u;
             if (i2.meta & (1u << (8 + t2))) mask |= 8u;
             peak = mem2 > peak ? mem2 : peak;
-            if (p2 == p0) {  // segments 1 and 3 share one pool's quota
+            if (pl.mixed) {  // pools that draw on one real pool together get the joint check
+              quota_ok = quota_ok && ((qm[o_qm2 + p2] >> dp) & 1u);
+              if (quota_ok && (((isect[p0] >> p1) | (isect[p1] >> p2) | (isect[p0] >> p2)) & 1ull))
+                quota_ok = (joint_quota_bits(pl, 3, (int)p0, (int)p1, (int)p2, (int)gpus0,
+                                             sh.n[1] * vals[DP + t1], sh.n[2] * vals[DP + t2]) >> dp) & 1u;
+            } else if (p2 == p0) {  // segments 1 and 3 share one pool's quota
               const int64_t gpus = gpus0 + (int64_t)sh.n[2] * vals[DP + t2];
               quota_ok = q1 && gpus * D <= (int64_t)i0.avail;
             } else {
@@ -1381,12 +1501,13 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
   extern __shared__ uint4 lds_raw[];
   const EvalUnit u = units[unit0 + blockIdx.x];
   const ShapeRec sh = pl.shapes[u.shape];
-  const int ZG = pl.ZG, G = pl.G, MB = pl.MB, TP = pl.TP, DP = pl.DP, Z = pl.Z, S = sh.s;
+  const int ZG = pl.ZG, G = pl.GX, MB = pl.MB, TP = pl.TP, DP = pl.DP, Z = pl.Z, S = sh.s;
   Rec *rec = reinterpret_cast<Rec *>(lds_raw);                           // [3][TP][ZG][MB]
   float4 *pair = reinterpret_cast<float4 *>(rec + 3 * TP * ZG * MB);     // [MB][Z][Z]
   PoolInfo *pinfo = reinterpret_cast<PoolInfo *>(pair + MB * Z * Z);     // [ZG]
   uint64_t *need = reinterpret_cast<uint64_t *>(pinfo + ZG);             // [3][TP][MB][DP]
-  uint32_t *qm = reinterpret_cast<uint32_t *>(need + 3 * TP * MB * DP);  // [3][TP][ZG]
+  uint64_t *isect = need + 3 * TP * MB * DP;                             // [ZG]
+  uint32_t *qm = reinterpret_cast<uint32_t *>(isect + ZG);               // [3][TP][ZG]
   uint32_t *odec = qm + 3 * TP * ZG;  // [o_cnt] the outer digits of the unit, unpacked:
   int32_t *vals = reinterpret_cast<int32_t *>(odec + kEvalUnitMaxOuter);  // [DP] dp, [TP] tp
   const int t = threadIdx.x;          // r2 | tp2 << 6 | r3 << 9 | tp3 << 15
@@ -1414,13 +1535,14 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
     qm[i] = pl.qw[(size_t)(n * vals[DP + k]) * ZG + p];
   }
   for (int p = t; p < ZG; p += blockDim.x) {
-    const int g = p % G;
+    const int x = pl.xt[p % G], ga = x & 255, gb = x >> 8;
     PoolInfo pi;
-    pi.res = pl.res[g];
-    pi.cap = pl.cap[g];
-    pi.avail = pl.avail[p];
+    pi.res = max(pl.res[ga], pl.res[gb]);
+    pi.room = min((int64_t)pl.cap[ga] - (int64_t)pl.res[ga], (int64_t)pl.cap[gb] - (int64_t)pl.res[gb]);
+    pi.avail = pl.mixed ? 0 : pl.avail[p];
     pi.meta = (uint32_t)(p / G) | (pl.h1m[p] << 8);
     pinfo[p] = pi;
+    isect[p] = pl.isect[p];
   }
   for (int i = t; i < MB * Z * Z; i += blockDim.x) {  // per mb: transfer a -> b, b -> a, egress
     const int m = i / (Z * Z), ab = i - m * Z * Z, za = ab / Z, zb = ab % Z;
@@ -1439,13 +1561,13 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
                       seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]), vals[DP + k], 0u);
   }
   __syncthreads();
-  if (S == 1) eval_rows_body<1, false>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
+  if (S == 1) eval_rows_body<1, false>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals, isect);
   else if (!pl.pst) {
-    if (S == 2) eval_rows_body<2, false>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
-    else eval_rows_body<3, false>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
+    if (S == 2) eval_rows_body<2, false>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals, isect);
+    else eval_rows_body<3, false>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals, isect);
   } else {
-    if (S == 2) eval_rows_body<2, true>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
-    else eval_rows_body<3, true>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals);
+    if (S == 2) eval_rows_body<2, true>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals, isect);
+    else eval_rows_body<3, true>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals, isect);
   }
 }
 

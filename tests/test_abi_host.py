@@ -32,11 +32,11 @@ def test_exports_every_declared_entry_point(lib):
 
 def test_struct_layouts_match_the_header(tmp_path):
     """sizeof / offsetof as a C compiler sees the header against the ctypes mirrors."""
-    fields = {"sailor_problem": ["n_layers", "per_segment_tp", "n_bw_coef", "global_batch", "mb_values",
+    fields = {"sailor_problem": ["n_layers", "per_segment_tp", "n_bw_coef", "mixed_types", "global_batch", "mb_values",
                                  "embed_params", "grad_bytes_per_param", "t_fwd", "egress_per_byte",
                                  "bw_poly"],
               "sailor_result": ["index", "iter_time_s", "mask", "pp", "mb_index", "cut", "pool",
-                                "seg_tp", "seg_tp_index"],
+                                "seg_tp", "seg_tp_index", "zone", "type_a", "type_b"],
               "sailor_constraint": ["bound", "has_bound"]}
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "sailor.h"', 'int main(void) {']
     for st, fl in fields.items():
@@ -55,7 +55,7 @@ def test_struct_layouts_match_the_header(tmp_path):
         assert C.sizeof(cls) == int(out[st])
         for f in fl:
             assert getattr(cls, f).offset == int(out[f"{st}.{f}"]), (st, f)
-    assert C.sizeof(binding.sailor_result) == 120 and binding.sailor_result.mask.offset == 32
+    assert C.sizeof(binding.sailor_result) == 160 and binding.sailor_result.mask.offset == 32
 
 
 def _create(lib, prob):

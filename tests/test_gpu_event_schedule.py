@@ -44,6 +44,7 @@ def check(torch, plan, orc, idx):
     lambda: W.tiny_problem(3, uniform_layers=True),
     lambda: W.tiny_problem(4, n_layers=8, n_types=3, seg3_max_pp=8).with_per_segment_tp(),
     lambda: (lambda p: p.with_bw_poly(W.bandwidth_poly(p)))(W.tiny_problem(2, n_zones=3)),
+    lambda: W.tiny_problem(7, n_types=3).with_mixed_types(),
 ])
 def test_small_spaces(torch_cuda, make):
     prob = make()

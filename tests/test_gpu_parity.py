@@ -76,6 +76,17 @@ def check_result(res, want, orc):
     assert (res.partition, res.n_segments, res.cut, res.pool) == (
         cfg.partition, cfg.n_segments, cfg.cut, cfg.pool)
     assert (res.seg_tp, res.seg_tp_index) == (cfg.seg_tp, cfg.seg_tp_idx)
+    # zone and the two replica types of every segment, from the documented pool numbering
+    import itertools
+    G = orc._prob.n_types
+    xt = [(a, a) for a in range(G)] + (list(itertools.combinations(range(G), 2))
+                                        if getattr(orc._prob, "mixed_types", False) else [])
+    for j in range(3):
+        if cfg.pool[j] < 0:
+            assert (res.zone[j], res.type_a[j], res.type_b[j]) == (-1, -1, -1)
+        else:
+            z, (a, b) = cfg.pool[j] // len(xt), xt[cfg.pool[j] % len(xt)]
+            assert (res.zone[j], res.type_a[j], res.type_b[j]) == (z, a, b)
 
 
 def check_topk(got, want, objective):
@@ -114,7 +125,19 @@ PROBLEMS = {
     "tiny2_bwpoly": lambda: _with_profile(W.tiny_problem(2, n_zones=3)),
     "tiny4_segtp_bwpoly": lambda: _with_profile(
         W.tiny_problem(4, n_layers=8, n_types=3, seg3_max_pp=8).with_per_segment_tp()),
+    # replicas of a stage split over two GPU types
+    "cfg2_mixed": lambda: W.config2().with_mixed_types(),
+    "tiny1_mixed": lambda: W.tiny_problem(1).with_mixed_types(),
+    "tiny4_mixed": lambda: W.tiny_problem(4, n_layers=8, n_types=3, seg3_max_pp=8).with_mixed_types(),
+    "tiny2_mixed_segtp_bwpoly": lambda: _with_profile(
+        W.tiny_problem(2, n_zones=3).with_mixed_types().with_per_segment_tp()),
+    "scarce_mixed": lambda: _scarce(W.tiny_problem(8, n_types=3, n_zones=2).with_mixed_types()),
 }
+
+
+def _scarce(prob):
+    """Few GPUs everywhere, so that segments compete for the real pools they share."""
+    return prob.with_avail(np.random.default_rng(8).integers(1, 12, prob.avail.shape))
 
 
 def _with_profile(prob, seed=6):
@@ -321,6 +344,8 @@ def test_random_small_problems(torch_cuda, seed):
     prob.per_segment_tp = bool(seed % 2)
     if seed % 3 == 0:
         prob = prob.with_bw_poly(W.bandwidth_poly(prob, seed))
+    if seed % 4 == 1:
+        prob = prob.with_mixed_types()
     avail = prob.avail.copy()
     avail[rng.random(avail.shape) < 0.25] = 0
     prob = prob.with_avail(avail)

@@ -248,3 +248,31 @@ def test_third_workload_with_link_profiles(torch_cuda):
         assert slower >= Oracle(base).best(objective=MAX_THROUGHPUT, n_threads=THREADS).iter_time
     finally:
         plan.destroy()
+
+
+# ------------------------------------------------------------------ mixed replica types
+
+def test_third_workload_with_mixed_replica_types(torch_cuda):
+    # 4 zones x (3 types + 3 pairs): about 1e8 candidates, scarce availability
+    base = W.config3()
+    prob = base.with_mixed_types()
+    plan, orc = _plan(prob), Oracle(prob)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        n = orc.num_candidates
+        assert plan.num_candidates() == n
+        rng = np.random.default_rng(33)
+        idx = rng.integers(0, n, 1_000_000).astype(np.uint64)
+        want = orc.eval_batch(indices=idx, n_threads=THREADS)
+        assert_eval_parity(gpu_eval(torch_cuda, plan, 0, len(idx), indices=idx), want)
+        first, count = n // 3, 5_000_001
+        assert_eval_parity(gpu_eval(torch_cuda, plan, first, count),
+                           orc.eval_batch(first, count, n_threads=THREADS))
+        for objective in (MAX_THROUGHPUT, MIN_COST):
+            best, top = oracle_best_and_topk(orc, 64, objective)
+            check_result(plan.best_plan(objective=objective, stream=stream), best, orc)
+            check_topk(plan.topk(64, objective=objective, stream=stream), top, objective)
+        base_best = Oracle(base).best(objective=MAX_THROUGHPUT, n_threads=THREADS)
+        assert orc.best(objective=MAX_THROUGHPUT, n_threads=THREADS).iter_time <= base_best.iter_time * (1 + 1e-12)
+    finally:
+        plan.destroy()
