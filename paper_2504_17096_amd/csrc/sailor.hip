@@ -916,9 +916,14 @@ sailor_status sailor_eval_batch(sailor_plan *pl, uint64_t first, uint64_t count,
       const size_t mid = (lo + hi) / 2;
       if (pl->eunits[mid].idx_lo < first + count) lo = mid + 1; else hi = mid;
     }
-    launch(k_eval_rows, dim3((unsigned)(lo - u0)), dim3(kEvalRowsThreads), pl->eval_lds_bytes, st,
-           timed ? pl->ev[3] : nullptr, timed ? pl->ev[1] : nullptr, pl->dev, a, pl->d_eunits,
-           (uint32_t)u0);
+    if (pl->dev.mixed)
+      launch(k_eval_rows<true>, dim3((unsigned)(lo - u0)), dim3(kEvalRowsThreads), pl->eval_lds_bytes,
+             st, timed ? pl->ev[3] : nullptr, timed ? pl->ev[1] : nullptr, pl->dev, a, pl->d_eunits,
+             (uint32_t)u0);
+    else
+      launch(k_eval_rows<false>, dim3((unsigned)(lo - u0)), dim3(kEvalRowsThreads), pl->eval_lds_bytes,
+             st, timed ? pl->ev[3] : nullptr, timed ? pl->ev[1] : nullptr, pl->dev, a, pl->d_eunits,
+             (uint32_t)u0);
     HIP_TRY(hipGetLastError());
     pl->total_timed = false;
     pl->scan_timed = timed;

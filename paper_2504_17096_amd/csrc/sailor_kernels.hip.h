@@ -1363,7 +1363,7 @@ struct PoolInfo {   // per pool, staged in LDS (a pair of types: the tighter of 
 // 24-bit multiply (full rate, unlike the 32-bit one): every product below is a table offset
 __device__ __forceinline__ uint32_t mul24(uint32_t a, uint32_t b) { return __umul24(a, b); }
 
-template <int S, bool PST>
+template <int S, bool PST, bool MIXED>
 __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs &a,
                                                const EvalUnit &u, const ShapeRec &sh,
                                                const Rec *rec, const float4 *pair,
@@ -1447,7 +1447,7 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
           peak = mem1 > peak ? mem1 : peak;
           const bool q1 = (qm[o_qm + p1] >> dp) & 1u;
           quota_ok = quota_ok && q1;
-          if (S == 2 && pl.mixed && quota_ok && ((isect[p0] >> p1) & 1ull))
+          if (S == 2 && MIXED && quota_ok && ((isect[p0] >> p1) & 1ull))
             quota_ok = (joint_quota_bits(pl, 2, (int)p0, (int)p1, 0, (int)gpus0,
                                          sh.n[1] * vals[DP + t1], 0) >> dp) & 1u;
           const float4 pr = pairm[mul24(z0, Z) + z1];
@@ -1466,7 +1466,7 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
             if ((int64_t)need2 > i2.room) mask |= 1u;
             if (i2.meta & (1u << (8 + t2))) mask |= 8u;
             peak = mem2 > peak ? mem2 : peak;
-            if (pl.mixed) {  // pools that draw on one real pool together get the joint check
+            if (MIXED) {  // pools that draw on one real pool together get the joint check
               quota_ok = quota_ok && ((qm[o_qm2 + p2] >> dp) & 1u);
               if (quota_ok && (((isect[p0] >> p1) | (isect[p1] >> p2) | (isect[p0] >> p2)) & 1ull))
                 quota_ok = (joint_quota_bits(pl, 3, (int)p0, (int)p1, (int)p2, (int)gpus0,
@@ -1496,6 +1496,7 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
   }
 }
 
+template <bool MIXED>
 __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const EvalUnit *units,
                                                    uint32_t unit0) {
   extern __shared__ uint4 lds_raw[];
@@ -1561,14 +1562,12 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
                       seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]), vals[DP + k], 0u);
   }
   __syncthreads();
-  if (S == 1) eval_rows_body<1, false>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals, isect);
-  else if (!pl.pst) {
-    if (S == 2) eval_rows_body<2, false>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals, isect);
-    else eval_rows_body<3, false>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals, isect);
-  } else {
-    if (S == 2) eval_rows_body<2, true>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals, isect);
-    else eval_rows_body<3, true>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals, isect);
-  }
+#define SAILOR_ROWS(S_, PST_) \
+  eval_rows_body<S_, PST_, MIXED>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals, isect)
+  if (S == 1) SAILOR_ROWS(1, false);
+  else if (!pl.pst) { if (S == 2) SAILOR_ROWS(2, false); else SAILOR_ROWS(3, false); }
+  else { if (S == 2) SAILOR_ROWS(2, true); else SAILOR_ROWS(3, true); }
+#undef SAILOR_ROWS
 }
 
 }  // namespace sailor
