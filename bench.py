@@ -197,23 +197,28 @@ def main() -> int:
     replan = {"snapshots": len(lat), "candidates": n5, "p50_ms": float(np.percentile(lat, 50)),
               "p99_ms": float(np.percentile(lat, 99))}
 
-    # the same query when every segment carries its own TP digit (915 206 400 candidates)
-    plan_s = Plan(prob.with_per_segment_tp())
-    n_s = plan_s.num_candidates()
-    budget_s = 1.2 * plan_s.best_plan(objective=MIN_COST, stream=stream).cost_per_iter
-    plan_s.set_timing(1)
-    for _ in range(2):
-        plan_s.topk_raw(K, MAX_THROUGHPUT, budget_s, buf, stream)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    reps_s, scan_s = 10, 0.0
-    for _ in range(reps_s):
-        plan_s.topk_raw(K, MAX_THROUGHPUT, budget_s, buf, stream)
-        scan_s += plan_s.last_timing()[1] / reps_s
-    seg_ms = (time.perf_counter() - t0) / reps_s * 1e3
-    plan_s.destroy()
-    segtp = {"candidates": n_s, "time_to_top64_ms": seg_ms, "scan_kernel_ms": scan_s,
-             "candidates_per_s": n_s / (seg_ms * 1e-3)}
+    # the same query on the widened spaces: a TP digit per segment (915 206 400 candidates),
+    # replicas of a stage split over two GPU types (5 zones x 10 extended types)
+    def widened(problem, reps):
+        p = Plan(problem)
+        t0 = time.perf_counter()
+        b = 1.2 * p.best_plan(objective=MIN_COST, stream=stream).cost_per_iter
+        p.set_timing(1)
+        for _ in range(2):
+            p.topk_raw(K, MAX_THROUGHPUT, b, buf, stream)
+        torch.cuda.synchronize()
+        t0, scan = time.perf_counter(), 0.0
+        for _ in range(reps):
+            p.topk_raw(K, MAX_THROUGHPUT, b, buf, stream)
+            scan += p.last_timing()[1] / reps
+        ms = (time.perf_counter() - t0) / reps * 1e3
+        out = {"candidates": p.num_candidates(), "time_to_top64_ms": ms, "scan_kernel_ms": scan,
+               "candidates_per_s": p.num_candidates() / (ms * 1e-3)}
+        p.destroy()
+        return out
+
+    segtp = widened(prob.with_per_segment_tp(), 10)
+    mixed = widened(prob.with_mixed_types(), 10)
 
     if args.copy_probe:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").fill_(1.0)
@@ -252,7 +257,7 @@ def main() -> int:
                   "eval_batch_candidates_per_s": n / (eval_ms * 1e-3),
                   "eval_batch_output_GBps": 20.0 * n / (eval_ms * 1e-3) / 1e9,
                   "plan_create_ms": create_ms, "replan_stream": replan,
-                  "per_segment_tp": segtp, "event_schedule_top64": event_sched, "survivors_refined_valid": list(counts), "best_index": best.index,
+                  "per_segment_tp": segtp, "mixed_types": mixed, "event_schedule_top64": event_sched, "survivors_refined_valid": list(counts), "best_index": best.index,
                   "top1_index": top1_index},
     }
     if not args.no_cpu_baseline:

@@ -276,3 +276,24 @@ def test_third_workload_with_mixed_replica_types(torch_cuda):
         assert orc.best(objective=MAX_THROUGHPUT, n_threads=THREADS).iter_time <= base_best.iter_time * (1 + 1e-12)
     finally:
         plan.destroy()
+
+
+def test_fourth_workload_with_mixed_replica_types(torch_cuda):
+    # 5 zones x (4 types + 6 pairs): 1.09e9 candidates; sampled outputs, one full-space selection
+    prob = W.config4().with_mixed_types()
+    plan, orc = _plan(prob), Oracle(prob)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        n = orc.num_candidates
+        assert plan.num_candidates() == n == 1094400000
+        idx = np.random.default_rng(45).integers(0, n, 1_000_000).astype(np.uint64)
+        assert_eval_parity(gpu_eval(torch_cuda, plan, 0, len(idx), indices=idx),
+                           orc.eval_batch(indices=idx, n_threads=THREADS))
+        first, count = n - 4_000_003, 4_000_003
+        assert_eval_parity(gpu_eval(torch_cuda, plan, first, count),
+                           orc.eval_batch(first, count, n_threads=THREADS))
+        best, top = oracle_best_and_topk(orc, 64, MAX_THROUGHPUT)
+        check_result(plan.best_plan(objective=MAX_THROUGHPUT, stream=stream), best, orc)
+        check_topk(plan.topk(64, objective=MAX_THROUGHPUT, stream=stream), top, MAX_THROUGHPUT)
+    finally:
+        plan.destroy()
