@@ -88,6 +88,7 @@ struct sailor_plan {
   int device = 0;
   size_t lds_bytes = 0;
   unsigned unit_threads = 256;
+  uint32_t seq = 0;                // sequence number of the last selection's final kernel
   ResultHeader last_hdr{};         // of the last successful selection
   bool have_hdr = false;
   int32_t *d_avail = nullptr;
@@ -531,14 +532,24 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
     k_refine<<<256, kRefineWaves * 64, 0, st>>>(pl->dev, ra);
     if (best) {
       k_pick_best<<<1, 1024, 0, st>>>(pl->ref, pl->ref_cap, cnt, cnt_next, (int)obj, pl->d_hdr,
-                                      pl->d_out);
+                                      pl->d_out, ++pl->seq);
     } else {
       k_rank_topk<<<64, 256, 0, st>>>(pl->ref, pl->ref_cap, cnt, cnt_next, (int)obj, k, pl->d_hdr,
-                                      pl->d_out);
+                                      pl->d_out, cnt + CNT_DONE, ++pl->seq);
     }
     if (t_all) HIP_TRY(hipEventRecord(pl->ev[2], st));
     HIP_TRY(hipGetLastError());
-    HIP_TRY(hipStreamSynchronize(st));
+    // Wait for the sequence number in host-mapped memory rather than for the dispatch to
+    // retire; the stream is asked now and then, so that a failed launch cannot hang the wait.
+    const volatile uint32_t *flag = &static_cast<ResultHeader *>(pl->h_result)->seq;
+    for (uint32_t spins = 1; *flag != pl->seq; ++spins) {
+      if ((spins & 0x3FFu) != 0) continue;
+      const hipError_t q = hipStreamQuery(st);
+      if (q == hipErrorNotReady) continue;
+      HIP_TRY(q);
+      if (*flag != pl->seq) return SAILOR_EDEVICE;  // the stream drained without a result
+    }
+    __atomic_thread_fence(__ATOMIC_ACQUIRE);
     *hdr = *static_cast<ResultHeader *>(pl->h_result);
     return SAILOR_OK;
   };
@@ -603,7 +614,8 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
       if (hi != 0.0 && hi <= lo * (1.0 + 1e-7)) break;  // a wall of ties: give up
     }
     if (!found) return SAILOR_ENOMEM;
-    k_zero_counters<<<1, 64, 0, st>>>(cnt, (1u << CNT_SURV) | (1u << CNT_REF) | (1u << CNT_FEAS));
+    k_zero_counters<<<1, 64, 0, st>>>(
+        cnt, (1u << CNT_SURV) | (1u << CNT_REF) | (1u << CNT_FEAS) | (1u << CNT_DONE));
     sa.count_only = 0;
     sa.tau_host = tau;
     rc = run_tail(hdr_out);

@@ -75,7 +75,8 @@ struct RefRec {         // fp64 re-evaluation of one candidate
 struct ResultHeader {   // written by the final kernel into host-mapped memory
   uint32_t n_found, surv_count, ref_count, feasible_count;
   uint32_t gmin_bits;  // smallest strict fp32 key of the scan
-  uint32_t pad[3];
+  uint32_t seq;        // the call's sequence number, written last: the results are complete
+  uint32_t pad[2];
 };
 
 struct DevPlan {

@@ -412,6 +412,7 @@ struct ScanArgs {
 enum Counter { CNT_SURV = 0, CNT_REF = 1, CNT_FEAS = 2, CNT_GMIN = 3, CNT_TAU0 = 4, CNT_TAU1 = 5,
                CNT_NLOOSE = 6, CNT_NSTRICT = 7,  // count-only collect passes
                CNT_NLIST = 8,                    // length of the collect pass's unit list
+               CNT_DONE = 9,                     // workgroups of the final kernel that have finished
                CNT_COUNT = 16 };
 
 __device__ __forceinline__ uint32_t counter_reset_value(int i) {
@@ -1031,12 +1032,20 @@ __device__ __forceinline__ bool lex_less(double ka, uint64_t ia, double kb, uint
   return ka < kb || (ka == kb && ia < ib);
 }
 
+// The host waits for the results by polling hdr->seq in host-mapped memory, which saves the
+// few microseconds between a kernel's last store and the completion of its dispatch; the
+// sequence number is therefore stored last, behind a system-scope fence.
+__device__ __forceinline__ void publish(ResultHeader *hdr, uint32_t seq) {
+  __threadfence_system();
+  __hip_atomic_store(&hdr->seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 // Best plan: minimum fp64 key over valid candidates, then the lowest index within the
 // tie tolerance of it.  One workgroup; results go to host-mapped memory.
 __global__ __launch_bounds__(1024) void k_pick_best(const RefRec *ref, uint32_t ref_cap,
                                                     const uint32_t *counters,
                                                     uint32_t *next_counters, int objective,
-                                                    ResultHeader *hdr, RefRec *out) {
+                                                    ResultHeader *hdr, RefRec *out, uint32_t seq) {
   __shared__ double s_key[1024];
   __shared__ unsigned long long s_idx[1024];
   __shared__ uint32_t s_pos[1024];
@@ -1075,6 +1084,7 @@ __global__ __launch_bounds__(1024) void k_pick_best(const RefRec *ref, uint32_t 
     hdr->ref_count = counters[CNT_REF];
     hdr->feasible_count = counters[CNT_FEAS];
     hdr->gmin_bits = counters[CNT_GMIN];
+    publish(hdr, seq);
   }
 }
 
@@ -1084,7 +1094,8 @@ __global__ __launch_bounds__(1024) void k_pick_best(const RefRec *ref, uint32_t 
 __global__ __launch_bounds__(256) void k_rank_topk(const RefRec *ref, uint32_t ref_cap,
                                                    const uint32_t *counters,
                                                    uint32_t *next_counters, int objective,
-                                                   uint32_t k, ResultHeader *hdr, RefRec *out) {
+                                                   uint32_t k, ResultHeader *hdr, RefRec *out,
+                                                   uint32_t *done, uint32_t seq) {
   const uint32_t n = min(counters[CNT_REF], ref_cap);
   if (blockIdx.x == 0 && threadIdx.x < CNT_COUNT)
     next_counters[threadIdx.x] = counter_reset_value(threadIdx.x);  // for the next call
@@ -1110,7 +1121,16 @@ __global__ __launch_bounds__(256) void k_rank_topk(const RefRec *ref, uint32_t r
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) before += __shfl_xor(before, off);
-    if (lane == 0 && before < k) out[before] = r;
+    if (lane == 0 && before < k) {
+      out[before] = r;
+      __threadfence_system();  // the record has reached host memory before this wave goes on
+    }
+  }
+  // the workgroup that finishes last publishes
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __threadfence_system();
+    if (atomicAdd(done, 1u) == gridDim.x - 1) publish(hdr, seq);
   }
 }
 
