@@ -213,20 +213,22 @@ sailor_status sailor_eval_batch(sailor_plan *plan, uint64_t first, uint64_t coun
 /* Best valid plan over the whole space (Sec. 4.2: order by the objective, return the
  * best): the minimum key (iteration time or cost) over mask == 0, then the lowest index
  * whose key is within a relative 1e-5 of that minimum.  *out (host) is filled completely.
- * Synchronises hip_stream.  SAILOR_ENOFEASIBLE when no candidate is valid. */
+ * Returns when the result has arrived in host memory: everything enqueued on hip_stream
+ * before the call has finished by then, the call's last dispatch may still be retiring.
+ * SAILOR_ENOFEASIBLE when no candidate is valid. */
 sailor_status sailor_best_plan(sailor_plan *plan, sailor_objective objective,
                                const sailor_constraint *constraint, sailor_result *out,
                                void *hip_stream);
 
 /* The k best valid plans in ascending (key, index) order; out (host) has room for k
  * entries, *n_found receives how many exist (<= k).  1 <= k <= SAILOR_MAX_K.
- * Synchronises hip_stream.  SAILOR_ENOFEASIBLE (with *n_found = 0) when none is valid. */
+ * Waits like sailor_best_plan.  SAILOR_ENOFEASIBLE (with *n_found = 0) when none is valid. */
 sailor_status sailor_topk(sailor_plan *plan, sailor_objective objective,
                           const sailor_constraint *constraint, int32_t k, sailor_result *out,
                           int32_t *n_found, void *hip_stream);
 
 /* Resize the device scratch of the selection: the list of candidates that survive the fp32
- * scan (16 B each, default 4 Mi entries) and the list re-evaluated in fp64 (40 B each,
+ * scan (24 B each, default 4 Mi entries) and the list re-evaluated in fp64 (40 B each,
  * default 256 Ki entries).  sailor_topk searches for a tighter threshold when the first
  * list would overflow; a call fails with SAILOR_ENOMEM only when more candidates than fit
  * lie within the rounding band of the k-th key (or, for sailor_best_plan, within the tie

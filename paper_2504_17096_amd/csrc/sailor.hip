@@ -17,7 +17,7 @@ using namespace sailor;
 
 namespace {
 
-constexpr uint32_t kDefaultSurvCap = 1u << 22;  // 64 MiB of survivors
+constexpr uint32_t kDefaultSurvCap = 1u << 22;  // 96 MiB of survivors
 constexpr uint32_t kDefaultRefCap = 1u << 18;
 // candidates per scan workgroup: large enough to amortise the staging of a unit, small
 // enough to leave about ten workgroups per compute unit
