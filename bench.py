@@ -33,7 +33,7 @@ PEAK_FP32_VECTOR_TFLOPS = 157.3
 SCAN_TRAFFIC_BYTES = 5.51e6
 # VALU wave-instructions the scan executes per launch on this workload (SQ_INSTS_VALU, same
 # file and same rule); each occupies one of the 1 024 SIMDs for 4 cycles at 2.4 GHz
-SCAN_VALU_WAVE_INSTS = 1.060e7
+SCAN_VALU_WAVE_INSTS = 1.064e7
 SIMDS, CLOCK_HZ, CYCLES_PER_WAVE_INST = 1024, 2.4e9, 4
 
 
