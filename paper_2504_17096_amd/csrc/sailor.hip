@@ -107,6 +107,7 @@ struct sailor_plan {
   void *h_result = nullptr;
   ResultHeader *d_hdr = nullptr;
   RefRec *d_out = nullptr;
+  RefRec *staged = nullptr;    // device-side copy of the top-k records before they go to the host
   uint32_t cnt_phase = 0;      // which of the two counter sets the next call uses
   bool counters_dirty = false; // a failed call may have left either set in any state
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};  // start, scan end, end, scan start
@@ -535,7 +536,7 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
                                       pl->d_out, ++pl->seq);
     } else {
       k_rank_topk<<<64, 256, 0, st>>>(pl->ref, pl->ref_cap, cnt, cnt_next, (int)obj, k, pl->d_hdr,
-                                      pl->d_out, cnt + CNT_DONE, ++pl->seq);
+                                      pl->d_out, pl->staged, cnt + CNT_DONE, ++pl->seq);
     }
     if (t_all) HIP_TRY(hipEventRecord(pl->ev[2], st));
     HIP_TRY(hipGetLastError());
@@ -797,6 +798,7 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(ar.alloc(&pl->ulist, pl->units.size()));
   CREATE_TRY(ar.alloc(&pl->surv, (size_t)pl->surv_cap));
   CREATE_TRY(ar.alloc(&pl->ref, (size_t)pl->ref_cap));
+  CREATE_TRY(ar.alloc(&pl->staged, (size_t)SAILOR_MAX_K));
   const size_t res_bytes = sizeof(ResultHeader) + 8 + (size_t)SAILOR_MAX_K * sizeof(RefRec);
   CREATE_TRY(hipHostMalloc(&pl->h_result, res_bytes, hipHostMallocMapped));
   std::memset(pl->h_result, 0, res_bytes);
