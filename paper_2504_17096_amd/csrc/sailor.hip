@@ -746,6 +746,11 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
     pl->xt = xt;
     CREATE_TRY(ar.upload(&d.xt, xt.data(), xt.size()));
   }
+  {
+    std::vector<int32_t> vals(p->dp_values, p->dp_values + DP);
+    vals.insert(vals.end(), p->tp_values, p->tp_values + TP);
+    CREATE_TRY(ar.upload(&d.vals, vals.data(), vals.size()));
+  }
   CREATE_TRY(ar.upload(&d.cap, p->mem_capacity, G));
   CREATE_TRY(ar.upload(&d.res, p->mem_reserved, G));
   CREATE_TRY(ar.upload(&d.node, p->gpus_per_node, G));

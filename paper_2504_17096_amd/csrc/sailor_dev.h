@@ -96,6 +96,8 @@ struct DevPlan {
   int64_t B;
   uint64_t N;
   int mbv[kMaxMB], tpv[kMaxTP], dpv[kMaxDP];
+  const int32_t *vals;         // the same lists in device memory, for lane-dependent indices:
+                               // [DP] dp, then [TP] tp
   // inputs
   const int32_t *avail;        // [ZG]
   const uint64_t *cap, *res;   // [G]

@@ -827,6 +827,13 @@ struct Cand {
   int k1, k2;
 };
 
+// Element j of a three-element array by selects (a lane-dependent subscript would move the
+// array to scratch memory).
+template <typename T>
+__device__ __forceinline__ int at3(const T *v, int j) {
+  return j == 0 ? (int)v[0] : (j == 1 ? (int)v[1] : (int)v[2]);
+}
+
 // The digits of candidate idx, which lies in the given shape.
 __device__ __forceinline__ void decode_in_shape(const DevPlan &pl, uint32_t shape, uint64_t idx,
                                                 Cand &c) {
@@ -891,7 +898,7 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
   const int lane = threadIdx.x & 63;
   const ShapeRec sh = pl.shapes[c.shape];
   const uint32_t rs = sh.row_stage;
-  const int64_t D = pl.dpv[c.dp];
+  const int64_t D = pl.vals[c.dp];
   mask = 0;
   peak = 0;
   const int64_t nb = pl.nb[c.mb * DP + c.dp];
@@ -905,29 +912,29 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
   // quota per pool (GPUs of one replica there, times D) and H1
   // (counted in halves: a segment on a pair of types takes half of its replicas from each)
   for (int j = 0; j < c.s; ++j) {
-    const int x = pl.xt[c.a[j] % GX], ga = x & 255, gb = x >> 8, z = c.a[j] / GX;
+    const int x = pl.xt[at3(c.a, j) % GX], ga = x & 255, gb = x >> 8, z = at3(c.a, j) / GX;
     for (int slot = 0; slot < (ga == gb ? 1 : 2); ++slot) {
       const int g = slot == 0 ? ga : gb;
       int64_t halves = 0;
       for (int j2 = 0; j2 < c.s; ++j2) {
-        const int x2 = pl.xt[c.a[j2] % GX], a2 = x2 & 255, b2 = x2 >> 8;
-        if (c.a[j2] / GX != z) continue;
-        const int64_t w = (int64_t)sh.n[j2] * pl.tpv[c.tp[j2]];
+        const int x2 = pl.xt[at3(c.a, j2) % GX], a2 = x2 & 255, b2 = x2 >> 8;
+        if (at3(c.a, j2) / GX != z) continue;
+        const int64_t w = (int64_t)at3(sh.n, j2) * pl.vals[pl.DP + at3(c.tp, j2)];
         if (a2 == b2) halves += a2 == g ? 2 * w : 0;
         else halves += (a2 == g || b2 == g) ? w : 0;
       }
       if (halves * D > 2 * (int64_t)pl.avail[z * G + g]) mask |= 2u;
     }
     if (ga != gb && D % 2 != 0) mask |= 2u;  // D replicas cannot be halved
-    if (pl.tpv[c.tp[j]] > pl.node[ga] || pl.tpv[c.tp[j]] > pl.node[gb]) mask |= 8u;
+    if (pl.vals[pl.DP + at3(c.tp, j)] > pl.node[ga] || pl.vals[pl.DP + at3(c.tp, j)] > pl.node[gb]) mask |= 8u;
   }
   double max_t = 0.0, t_sync = 0.0, t_upd = 0.0;
   uint32_t oom = 0;
   for (int i = lane; i < P; i += 64) {
     const int seg = i < c.k1 ? 0 : (i < c.k2 ? 1 : 2);
-    const int xg = pl.xt[c.a[seg] % GX], g = xg & 255, g2 = xg >> 8, z = c.a[seg] / GX;
-    const int k = c.tp[seg];
-    const int64_t tp = pl.tpv[k];
+    const int xg = pl.xt[at3(c.a, seg) % GX], g = xg & 255, g2 = xg >> 8, z = at3(c.a, seg) / GX;
+    const int k = at3(c.tp, seg);
+    const int64_t tp = pl.vals[pl.DP + k];
     const uint64_t bytes_i = stage_bytes(pl, rs, i, P, (int)tp, nb, pl.act[c.mb * TP + k]);
     const uint64_t m = bytes_i + pl.res[g], m2 = bytes_i + pl.res[g2];  // both replica types
     if (m > pl.cap[g] || m2 > pl.cap[g2]) oom = 1u;
@@ -936,14 +943,14 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
     double x = 0.0, comm = 0.0;
     if (i < P - 1) {
       const int sn = (i + 1) < c.k1 ? 0 : ((i + 1) < c.k2 ? 1 : 2);
-      const int zn = c.a[sn] / GX;
+      const int zn = at3(c.a, sn) / GX;
       x += p2p / bwp[z * Z + zn];
       if (pl.egress && zn != z)
         comm = (double)nb * (double)D * p2p * (pl.egress[z * Z + zn] + pl.egress[zn * Z + z]);
     }
     if (i > 0) {
       const int sp = (i - 1) < c.k1 ? 0 : ((i - 1) < c.k2 ? 1 : 2);
-      x += p2p / bwp[z * Z + c.a[sp] / GX];
+      x += p2p / bwp[z * Z + at3(c.a, sp) / GX];
     }
     // the slower replica type sets the stage's pace (straggler, Sec. 4.3)
     const double t = fmax(pl.st_c[(((size_t)(rs + i) * G + g) * MB + c.mb) * TP + k],
@@ -1214,7 +1221,7 @@ __global__ __launch_bounds__(256) void k_sim_1f1b(DevPlan pl, SimArgs a) {
   double fdur = 0.0, bdur = 0.0;
   if (mine) {
     const int seg = i < c.k1 ? 0 : (i < c.k2 ? 1 : 2);
-    const int xg = pl.xt[c.a[seg] % GX], g = xg & 255, g2 = xg >> 8, z = c.a[seg] / GX, k = c.tp[seg];
+    const int xg = pl.xt[at3(c.a, seg) % GX], g = xg & 255, g2 = xg >> 8, z = at3(c.a, seg) / GX, k = at3(c.tp, seg);
     const size_t at = (((size_t)(sh.row_stage + i) * G + g) * MB + c.mb) * TP + k;
     const size_t at2 = (((size_t)(sh.row_stage + i) * G + g2) * MB + c.mb) * TP + k;
     const double p2p = (double)pl.p2p[c.mb];
@@ -1222,11 +1229,11 @@ __global__ __launch_bounds__(256) void k_sim_1f1b(DevPlan pl, SimArgs a) {
     double send_f = 0.0, send_b = 0.0;
     if (i < P - 1) {
       const int sn = (i + 1) < c.k1 ? 0 : ((i + 1) < c.k2 ? 1 : 2);
-      send_f = p2p / bwp[z * Z + c.a[sn] / GX];
+      send_f = p2p / bwp[z * Z + at3(c.a, sn) / GX];
     }
     if (i > 0) {
       const int sp = (i - 1) < c.k1 ? 0 : ((i - 1) < c.k2 ? 1 : 2);
-      send_b = p2p / bwp[z * Z + c.a[sp] / GX];
+      send_b = p2p / bwp[z * Z + at3(c.a, sp) / GX];
     }
     double f = pl.st_f[at], b = pl.st_b[at];
     if (g2 != g && pl.st_f[at2] + pl.st_b[at2] > f + b) {  // the pipeline through the slower type
@@ -1310,7 +1317,7 @@ __device__ __forceinline__ void eval_direct_s(const DevPlan &pl, const Cand &c, 
                                               const LaneC &lc, float &T, float &C, uint64_t &peak,
                                               uint32_t &mask) {
   const int GX = pl.GX, Z = pl.Z, MB = pl.MB, DP = pl.DP;
-  const int64_t D = pl.dpv[c.dp];
+  const int64_t D = pl.vals[c.dp];
   const float *ts = pl.tsec_f + c.mb * Z * Z;  // transfer seconds of this microbatch size
   Acc acc;
   int w[3] = {0, 0, 0};
@@ -1318,7 +1325,7 @@ __device__ __forceinline__ void eval_direct_s(const DevPlan &pl, const Cand &c, 
   for (int j = 0; j < S; ++j) {
     const int p = c.a[j], gx = p % GX, z = p / GX;
     const int ga = pl.xt[gx] & 255, gb = pl.xt[gx] >> 8;
-    const int tpv = pl.tpv[c.tp[j]];
+    const int tpv = pl.vals[pl.DP + c.tp[j]];
     const size_t sl = agg_slot(pl, c.shape, c.tp[j], j);
     const Rec r = make_rec(pl.ta[(sl * GX + gx) * MB + c.mb], pl.syncz[sl * Z + z], pl.upd[sl * GX + gx],
                            pl.price_f[gx], ts[z * Z + z], sh.n[j], tpv, 0u);
