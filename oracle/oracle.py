@@ -16,8 +16,10 @@ from typing import List, Optional, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "sailor_oracle.c")
-_LIB = os.path.join(_HERE, "libsailor_oracle.so")
+# the mutation tests point this at a copy of the sources with a planted mistake
+_DIR = os.environ.get("SAILOR_ORACLE_DIR", _HERE)
+_SRC = os.path.join(_DIR, "sailor_oracle.c")
+_LIB = os.path.join(_DIR, "libsailor_oracle.so")
 
 MAX_THROUGHPUT, MIN_COST = 0, 1
 BIT_OOM, BIT_QUOTA, BIT_BATCH, BIT_TP_NODE, BIT_CONSTRAINT = 1, 2, 4, 8, 32
@@ -27,7 +29,7 @@ def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, no intrinsics)."""
     stale = (not os.path.exists(_LIB)
              or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
-             or os.path.getmtime(_LIB) < os.path.getmtime(os.path.join(_HERE, "sailor_oracle.h")))
+             or os.path.getmtime(_LIB) < os.path.getmtime(os.path.join(_DIR, "sailor_oracle.h")))
     if force or stale:
         subprocess.check_call(["gcc", "-O2", "-std=c99", "-Wall", "-shared", "-fPIC", "-o", _LIB,
                                _SRC, "-lpthread", "-lm"])

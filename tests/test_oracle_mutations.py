@@ -1,0 +1,57 @@
+"""The pins must notice a plausible mistake in the oracle: each case plants one in a copy of
+the oracle's sources (on the CPU, in a temporary directory), builds the copy and runs the pin
+file that covers the spot in a child process, which has to fail."""
+import os
+import shutil
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+MUTANTS = [
+    # (pin file, text in oracle/sailor_oracle.c, replacement)
+    ("test_oracle_simulator.py", "(double)(Nb - 1) * max_t", "(double)(Nb) * max_t"),
+    ("test_oracle_simulator.py", "2.0 * (double)(D - 1) / (double)D * grad_bytes",
+     "2.0 * (double)(D) / (double)D * grad_bytes"),
+    ("test_oracle_simulator.py", "if (i == P - 1) params += p->head_params;", ""),
+    ("test_oracle_simulator.py", "int64_t inflight = (P - i) < Nb ? (P - i) : Nb;", "int64_t inflight = (P - i);"),
+    ("test_oracle_simulator.py", "(p->egress_per_byte[(size_t)z * Z + zn] + p->egress_per_byte[(size_t)zn * Z + z])",
+     "(p->egress_per_byte[(size_t)z * Z + zn])"),
+    ("test_oracle_space.py", "g.pool[1] = (g.pool[0] + 1 + rel) % c->ZG;\n    if",
+     "g.pool[1] = (g.pool[0] + rel) % c->ZG;\n    if"),
+    ("test_oracle_selection.py", "vmin * (1.0 + SO_TIE_TOL)", "vmin"),
+    ("test_oracle_per_segment_tp.py", "tp_of[i] = g->seg_tp[seg];", "tp_of[i] = g->seg_tp[0];"),
+    ("test_oracle_bandwidth.py", "const double x = log2(bytes);", "const double x = log(bytes);"),
+    ("test_oracle_event_schedule.py", "double start = free_at[i] > dep ? free_at[i] : dep;", "double start = dep;"),
+    ("test_oracle_event_schedule.py", "int64_t w = (P - 1 - i) < M ? (P - 1 - i) : M;\n  if (pos < w)",
+     "int64_t w = (P - i) < M ? (P - i) : M;\n  if (pos < w)"),
+    ("test_oracle_mixed_types.py", "half_gpus_on_pool[zone_of[i] * G + type_b[i]] += tp_of[i];", ""),
+    ("test_oracle_mixed_types.py", "if (f2 + b2 > f + b) { f = f2; b = b2; }\n    }\n    double x = 0.0;",
+     "if (f2 + b2 < f + b) { f = f2; b = b2; }\n    }\n    double x = 0.0;"),
+]
+
+
+@pytest.mark.parametrize("pins,old,new", MUTANTS, ids=[f"{m[0][12:-3]}-{i}" for i, m in enumerate(MUTANTS)])
+def test_a_planted_mistake_fails_its_pins(tmp_path, pins, old, new):
+    for f in ("sailor_oracle.c", "sailor_oracle.h"):
+        shutil.copy(os.path.join(ROOT, "oracle", f), tmp_path / f)
+    src = (tmp_path / "sailor_oracle.c").read_text()
+    assert src.count(old) == 1, "the mutation no longer matches the oracle's source"
+    (tmp_path / "sailor_oracle.c").write_text(src.replace(old, new))
+    env = dict(os.environ, SAILOR_ORACLE_DIR=str(tmp_path))
+    run = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", pins), "-x", "-q",
+                          "-p", "no:cacheprovider"], cwd=ROOT, env=env, capture_output=True, text=True)
+    assert run.returncode == 1, "the pins passed on a broken oracle:\n" + run.stdout[-2000:]
+    assert " failed" in run.stdout
+
+
+def test_the_unmodified_copy_passes(tmp_path):
+    # the harness itself: the same route with nothing planted is green
+    for f in ("sailor_oracle.c", "sailor_oracle.h"):
+        shutil.copy(os.path.join(ROOT, "oracle", f), tmp_path / f)
+    env = dict(os.environ, SAILOR_ORACLE_DIR=str(tmp_path))
+    run = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_bandwidth.py"),
+                          "-x", "-q", "-p", "no:cacheprovider"], cwd=ROOT, env=env, capture_output=True, text=True)
+    assert run.returncode == 0, run.stdout[-2000:]
