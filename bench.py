@@ -74,6 +74,47 @@ def cpu_baseline(prob, n_sample: int) -> dict:
             "all_cores": {"value": n_sample / dt_mt, "threads": threads, "host_cores": cores}}
 
 
+def sweep(torch, workloads, Plan, MAX_THROUGHPUT, MIN_COST) -> int:
+    """Time to the 64 best plans (max throughput under 1.2 x the cheapest plan's cost) and to
+    the best plan, per workload; inputs resident, 30 repetitions after 5 warm-up calls."""
+    from paper_2504_17096_amd.binding import sailor_result
+    stream = torch.cuda.current_stream().cuda_stream
+    base = {"cfg1": workloads.config1(), "cfg2": workloads.config2(), "cfg3": workloads.config3(),
+            "cfg4": workloads.config4()}
+    cases = []
+    for name, p in base.items():
+        cases += [(name, p), (name + "+segment_tp", p.with_per_segment_tp()),
+                  (name + "+mixed_types", p.with_mixed_types())]
+    cases.append(("cfg3+link_profiles", base["cfg3"].with_bw_poly(workloads.bandwidth_poly(base["cfg3"]))))
+    cases.append(("cfg4+segment_tp+mixed_types", base["cfg4"].with_per_segment_tp().with_mixed_types()))
+    buf = (sailor_result * 64)()
+    for name, p in cases:
+        t0 = time.perf_counter()
+        plan = Plan(p)
+        create_ms = (time.perf_counter() - t0) * 1e3
+        budget = 1.2 * plan.best_plan(objective=MIN_COST, stream=stream).cost_per_iter
+        plan.set_timing(1)
+        for _ in range(5):
+            plan.topk_raw(64, MAX_THROUGHPUT, budget, buf, stream)
+        t0, scan = time.perf_counter(), 0.0
+        for _ in range(30):
+            found = plan.topk_raw(64, MAX_THROUGHPUT, budget, buf, stream)
+            scan += plan.last_timing()[1] / 30
+        top_ms = (time.perf_counter() - t0) / 30 * 1e3
+        plan.set_timing(0)
+        t0 = time.perf_counter()
+        for _ in range(30):
+            plan.best_plan(objective=MAX_THROUGHPUT, bound=budget, stream=stream)
+        best_ms = (time.perf_counter() - t0) / 30 * 1e3
+        n = plan.num_candidates()
+        print(json.dumps({"workload": name, "candidates": n, "found": found, "plan_create_ms": create_ms,
+                          "time_to_top64_ms": top_ms, "scan_kernel_ms": scan,
+                          "time_to_best_plan_ms": best_ms, "candidates_per_s": n / (top_ms * 1e-3)}),
+              flush=True)
+        plan.destroy()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -81,6 +122,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--cpu-sample", type=int, default=48_000_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line: the top-64 query on every synthetic "
+                         "workload and its widened variants, one JSON object per line")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -97,6 +141,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
     torch.cuda.set_device(0)
+    if args.sweep:
+        return sweep(torch, workloads, Plan, MAX_THROUGHPUT, MIN_COST)
     prob = workloads.config4()
     t0 = time.perf_counter()
     plan = Plan(prob)
