@@ -313,3 +313,44 @@ def test_fourth_workload_with_mixed_replica_types(torch_cuda):
         assert best.index == min(i for t, i in keys if t <= lim) or keys[-1][0] <= lim
     finally:
         plan.destroy()
+
+
+def test_fourth_workload_with_both_widenings_has_indices_beyond_32_bits(torch_cuda):
+    # TP per segment and pairs of types together: 1.27e10 candidates, so indices need more than
+    # 32 bits everywhere.  Sampled outputs (lists and a range above 2^33) and the selected plans
+    # one by one, as for the mixed-type space above.
+    prob = W.config4().with_per_segment_tp().with_mixed_types()
+    plan, orc = _plan(prob), Oracle(prob)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        n = orc.num_candidates
+        assert plan.num_candidates() == n == 12673296000
+        rng = np.random.default_rng(46)
+        idx = np.concatenate([rng.integers(0, n, 2_000_000), [0, n - 1, 2 ** 32 - 1, 2 ** 32, 2 ** 33 + 1]]).astype(np.uint64)
+        want = orc.eval_batch(indices=idx, n_threads=THREADS)
+        assert_eval_parity(gpu_eval(torch_cuda, plan, 0, len(idx), indices=idx), want)
+        first, count = 2 ** 33 + 12_345, 3_000_001
+        assert_eval_parity(gpu_eval(torch_cuda, plan, first, count),
+                           orc.eval_batch(first, count, n_threads=THREADS))
+        for c in rng.integers(0, n, 200).tolist() + [n - 1, 2 ** 32]:
+            r, cfg = plan.decode(int(c)), orc.decode(int(c))
+            assert (r.pp, r.dp, r.mb, r.partition, r.n_segments, r.cut, r.pool, r.seg_tp) == (
+                cfg.pp, cfg.dp, cfg.mb, cfg.partition, cfg.n_segments, cfg.cut, cfg.pool, cfg.seg_tp)
+        top = plan.topk(64, objective=MAX_THROUGHPUT, stream=stream)
+        assert len(top) == 64
+        keys = []
+        for r in top:
+            e = orc.eval_one(r.index)
+            assert e.mask == 0 and r.peak_mem_bytes == e.peak_mem
+            assert r.iter_time_s == pytest.approx(e.iter_time, rel=1e-9)
+            assert r.cost_per_iter == pytest.approx(e.cost, rel=1e-9)
+            keys.append((e.iter_time, r.index))
+        assert keys == sorted(keys) and len({i for _, i in keys}) == 64
+        ok = want[3] == 0
+        better = idx[ok][want[0][ok] < keys[-1][0] * (1 - 1e-12)]
+        assert set(int(c) for c in better) <= {i for _, i in keys}
+        # the widened space contains the plain one: its optimum cannot be worse
+        plain = Oracle(W.config4())
+        assert keys[0][0] <= _cfg4_unconstrained(plain, MAX_THROUGHPUT)[0].iter_time * (1 + 1e-12)
+    finally:
+        plan.destroy()
