@@ -106,3 +106,15 @@ def test_deep_pipelines_keep_their_rings_in_device_memory(torch_cuda):
         check(torch_cuda, plan, orc, idx)
     finally:
         plan.destroy()
+
+
+def test_deepest_pipeline(torch_cuda):
+    # 256 stages: one thread per stage fills the workgroup, the rings live in device memory
+    from tests.test_gpu_parity import _deep
+    prob = _deep()
+    plan, orc = _plan(prob), Oracle(prob)
+    try:
+        idx = np.random.default_rng(6).integers(0, orc.num_candidates, 120)
+        check(torch_cuda, plan, orc, idx)
+    finally:
+        plan.destroy()

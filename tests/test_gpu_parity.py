@@ -132,7 +132,24 @@ PROBLEMS = {
     "tiny2_mixed_segtp_bwpoly": lambda: _with_profile(
         W.tiny_problem(2, n_zones=3).with_mixed_types().with_per_segment_tp()),
     "scarce_mixed": lambda: _scarce(W.tiny_problem(8, n_types=3, n_zones=2).with_mixed_types()),
+    # the deepest pipeline the library accepts: 256 stages of one layer each
+    "deep256": lambda: _deep(),
 }
+
+
+def _deep():
+    rng = np.random.default_rng(256)
+    L = 256
+    return make_problem(n_layers=L, n_types=2, n_zones=2, mb_list=(1, 2), tp_list=(1, 2), dp_list=(1, 2, 4),
+                        pp_list=[64, 255, 256], global_batch=64, max_segments=2, uniform_layers=False,
+                        partitions={255: [[2] + [1] * 254, [1] * 127 + [2] + [1] * 127]},
+                        t_fwd=rng.uniform(0.5e-3, 2e-3, (2, 2, 2, L)), t_bwd=rng.uniform(1e-3, 4e-3, (2, 2, 2, L)),
+                        t_upd=rng.uniform(1e-5, 3e-5, (2, 2, L)),
+                        layer_params=rng.integers(1_000_000, 3_000_000, L).astype(np.uint64),
+                        act=rng.integers(1_000_000, 9_000_000, (2, 2)).astype(np.uint64), p2p=2_000_000,
+                        cap=np.array([2, 1], np.uint64) * np.uint64(1 << 30), avail=np.array([[600, 300], [400, 500]]),
+                        bw=np.array([[1e10, 1e9], [2e9, 1e10]]), egress=np.array([[0, 2e-11], [3e-11, 0]]),
+                        price=np.array([3.0, 1.5]))
 
 
 def _scarce(prob):
