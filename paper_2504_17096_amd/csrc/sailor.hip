@@ -25,6 +25,7 @@ constexpr uint64_t kUnitTargetMin = 4096, kUnitTargetMax = 65536, kUnitsWanted =
 constexpr uint32_t kCollectSub = 4;      // workgroups that share one unit in the collect pass
 constexpr uint32_t kListSub = 8;         // the same when the pass walks a list of units,
 constexpr uint32_t kListUnits = 256;     // and the units it visits per round
+constexpr uint32_t kRankOneWorkgroup = 128;  // largest k whose final ranking runs as one workgroup
 constexpr uint32_t kEvalUnitTarget = 16384;  // candidates per workgroup of the range evaluation
 constexpr unsigned kEvalRowsThreads = 512;
 constexpr size_t kEvalRowsMaxLds = 64 * 1024;  // above this the range form evaluates lane by lane
@@ -535,8 +536,11 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
       k_pick_best<<<1, 1024, 0, st>>>(pl->ref, pl->ref_cap, cnt, cnt_next, (int)obj, pl->d_hdr,
                                       pl->d_out, ++pl->seq);
     } else {
-      k_rank_topk<<<64, 256, 0, st>>>(pl->ref, pl->ref_cap, cnt, cnt_next, (int)obj, k, pl->d_hdr,
-                                      pl->d_out, pl->staged, cnt + CNT_DONE, ++pl->seq);
+      // few records expected (about k, plus ties): one workgroup ranks them from LDS
+      const bool one = k <= kRankOneWorkgroup;
+      k_rank_topk<<<one ? 1 : 64, one ? kRankLds : 256, 0, st>>>(
+          pl->ref, pl->ref_cap, cnt, cnt_next, (int)obj, k, pl->d_hdr, pl->d_out, pl->staged,
+          cnt + CNT_DONE, ++pl->seq);
     }
     if (t_all) HIP_TRY(hipEventRecord(pl->ev[2], st));
     HIP_TRY(hipGetLastError());

@@ -765,8 +765,32 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stri
   __shared__ uint32_t hist[2048];
   __shared__ uint32_t wsum[16];
   __shared__ uint32_t s_prefix, s_k, s_done, s_nlist;
-  const uint32_t n = count ? min(*count, cap) : cap;
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+  // The first kSelectKeep values of every thread stay in registers for all three passes.
+  // Their loads (and those of the list's source) do not wait for a count that comes from
+  // memory: the buffers hold cap values, so the first value of every thread is requested
+  // together with the count and taken as +inf afterwards if it lies beyond it (requesting
+  // all kKept that way cost more than it saved when the list was short).
+  constexpr int kSelectKeep = 4;
+  constexpr uint32_t kKept = kSelectKeep * 1024;
+  uint32_t xr[kSelectKeep];
+  float lr[kSelectKeep];
+  const uint32_t n_early = count ? min(cap, 1024u) : cap;
+#pragma unroll
+  for (int q = 0; q < kSelectKeep; ++q) {
+    const uint32_t i = t + q * 1024u;
+    xr[q] = i < n_early ? __float_as_uint(vals[(size_t)i * stride_words]) : 0x7f800000u;
+    lr[q] = (list && i < n_list_src) ? list_src[i] : kPosInf;
+  }
+  const uint32_t n = count ? min(*count, cap) : cap;
+  if (t >= n) xr[0] = 0x7f800000u;
+  if (count) {
+#pragma unroll
+    for (int q = 1; q < kSelectKeep; ++q) {
+      const uint32_t i = t + q * 1024u;
+      if (i < n) xr[q] = __float_as_uint(vals[(size_t)i * stride_words]);
+    }
+  }
   if (t == 0) { s_prefix = 0; s_k = k; s_done = 0; s_nlist = 0; }
   const int shifts[3] = {21, 10, 0}, widths[3] = {11, 11, 10};
   for (int pass = 0; pass < 3; ++pass) {
@@ -776,7 +800,23 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stri
     const int sh = shifts[pass], wd = widths[pass];
     const uint32_t prefix = s_prefix, kk = s_k;
     if (s_done) break;  // uniform
-    for (uint32_t i = t; i < n; i += blockDim.x) {
+#pragma unroll
+    for (int q = 0; q < kSelectKeep; ++q) {
+      const uint32_t x = xr[q];
+      const bool match = x < 0x7f800000u && (pass == 0 || (x >> (sh + wd)) == prefix);
+      const uint32_t bin = (x >> sh) & ((1u << wd) - 1);
+      // Keys of a survivor list lie close together and share their leading digits: the
+      // lanes that agree with the wave's first matching lane add to its bin once (hundreds
+      // of atomics on one LDS word took 1 us per pass).
+      const unsigned long long m = __builtin_amdgcn_ballot_w64(match);
+      if (m == 0) continue;  // uniform over the wave
+      const uint32_t bin0 = (uint32_t)__shfl((int)bin, __ffsll((long long)m) - 1);
+      const bool same = match && bin == bin0;
+      const unsigned long long ms = __builtin_amdgcn_ballot_w64(same);
+      if (lane == __ffsll((long long)m) - 1) atomicAdd(&hist[bin0], (uint32_t)__popcll(ms));
+      if (match && !same) atomicAdd(&hist[bin], 1u);
+    }
+    for (uint32_t i = t + kKept; i < n; i += blockDim.x) {
       const uint32_t x = __float_as_uint(vals[(size_t)i * stride_words]);
       const bool match = x < 0x7f800000u && (pass == 0 || (x >> (sh + wd)) == prefix);
       if (match) atomicAdd(&hist[(x >> sh) & ((1u << wd) - 1)], 1u);
@@ -808,7 +848,12 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stri
   if (list) {
     __syncthreads();
     const float tau = __uint_as_float(s_prefix) * band;
-    for (uint32_t i = t; i < n_list_src; i += blockDim.x) {
+#pragma unroll
+    for (int q = 0; q < kSelectKeep; ++q) {
+      const uint32_t i = t + q * 1024u;
+      if (lr[q] < kPosInf && lr[q] <= tau) list[atomicAdd(&s_nlist, 1u)] = i;
+    }
+    for (uint32_t i = t + kKept; i < n_list_src; i += blockDim.x) {
       const float v = list_src[i];
       if (v < kPosInf && v <= tau) list[atomicAdd(&s_nlist, 1u)] = i;
     }
@@ -886,6 +931,16 @@ __device__ __forceinline__ double wave_max_f64(double v) {
   return v;
 }
 
+// The two real types a | b << 8 of extended type x (the plain ones, then the pairs a < b in
+// lexicographic order), by arithmetic: what DevPlan::xt holds, without the trip to memory
+// in front of the loads that depend on it.
+__device__ __forceinline__ int type_pair(int x, int G) {
+  if (x < G) return x | (x << 8);
+  int r = x - G, a = 0;
+  while (a < G - 2 && r >= G - 1 - a) { r -= G - 1 - a; ++a; }
+  return a | ((a + 1 + r) << 8);
+}
+
 // Stage-by-stage evaluation of one plan in fp64 and exact integers (Sec. 4.3) by one wave:
 // lane i takes stages i, i + 64, ...; maxima are reduced across the wave, sums are taken in
 // stage order (every lane adds the staged terms in the same order, so all lanes hold the
@@ -899,6 +954,9 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
   const ShapeRec sh = pl.shapes[c.shape];
   const uint32_t rs = sh.row_stage;
   const int64_t D = pl.vals[c.dp];
+  int xs[3];  // real types of each segment's pool
+#pragma unroll
+  for (int j = 0; j < 3; ++j) xs[j] = j < c.s ? type_pair(c.a[j] % GX, G) : 0;
   mask = 0;
   peak = 0;
   const int64_t nb = pl.nb[c.mb * DP + c.dp];
@@ -912,12 +970,12 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
   // quota per pool (GPUs of one replica there, times D) and H1
   // (counted in halves: a segment on a pair of types takes half of its replicas from each)
   for (int j = 0; j < c.s; ++j) {
-    const int x = pl.xt[at3(c.a, j) % GX], ga = x & 255, gb = x >> 8, z = at3(c.a, j) / GX;
+    const int x = at3(xs, j), ga = x & 255, gb = x >> 8, z = at3(c.a, j) / GX;
     for (int slot = 0; slot < (ga == gb ? 1 : 2); ++slot) {
       const int g = slot == 0 ? ga : gb;
       int64_t halves = 0;
       for (int j2 = 0; j2 < c.s; ++j2) {
-        const int x2 = pl.xt[at3(c.a, j2) % GX], a2 = x2 & 255, b2 = x2 >> 8;
+        const int x2 = at3(xs, j2), a2 = x2 & 255, b2 = x2 >> 8;
         if (at3(c.a, j2) / GX != z) continue;
         const int64_t w = (int64_t)at3(sh.n, j2) * pl.vals[pl.DP + at3(c.tp, j2)];
         if (a2 == b2) halves += a2 == g ? 2 * w : 0;
@@ -932,7 +990,7 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
   uint32_t oom = 0;
   for (int i = lane; i < P; i += 64) {
     const int seg = i < c.k1 ? 0 : (i < c.k2 ? 1 : 2);
-    const int xg = pl.xt[at3(c.a, seg) % GX], g = xg & 255, g2 = xg >> 8, z = at3(c.a, seg) / GX;
+    const int xg = at3(xs, seg), g = xg & 255, g2 = xg >> 8, z = at3(c.a, seg) / GX;
     const int k = at3(c.tp, seg);
     const int64_t tp = pl.vals[pl.DP + k];
     const uint64_t bytes_i = stage_bytes(pl, rs, i, P, (int)tp, nb, pl.act[c.mb * TP + k]);
@@ -984,7 +1042,8 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   double sum_t = 0.0, dollars = 0.0, comm = 0.0;
-  for (int i = 0; i < P; ++i) {
+#pragma unroll 8
+  for (int i = 0; i < P; ++i) {  // (unrolled so that the LDS reads run ahead of the additions)
     sum_t += lds.t[i];
     dollars += lds.dol[i];
     comm += lds.comm[i];
@@ -1013,12 +1072,16 @@ struct RefineArgs {
 // One wave per survivor.
 __global__ __launch_bounds__(kRefineWaves * 64) void k_refine(DevPlan pl, RefineArgs a) {
   __shared__ RefineLds lds[kRefineWaves];
-  const uint32_t n = min(a.counters[CNT_SURV], a.surv_cap);
-  const float tau = a.tau_src ? __uint_as_float(*a.tau_src) * a.band : kPosInf;
   const uint32_t wave = blockIdx.x * kRefineWaves + (threadIdx.x >> 6);
   const uint32_t n_waves = gridDim.x * kRefineWaves;
+  // the wave's first record is requested together with the count (the buffer holds surv_cap
+  // records, so the address is valid whatever the count turns out to be)
+  SurvRec first{};
+  if (wave < a.surv_cap) first = a.surv[wave];
+  const uint32_t n = min(a.counters[CNT_SURV], a.surv_cap);
+  const float tau = a.tau_src ? __uint_as_float(*a.tau_src) * a.band : kPosInf;
   for (uint32_t i = wave; i < n; i += n_waves) {
-    const SurvRec sv = a.surv[i];
+    const SurvRec sv = i == wave ? first : a.surv[i];
     if (!(sv.key_loose <= tau)) continue;
     Cand c;
     decode_in_shape(pl, sv.shape, sv.idx, c);
@@ -1095,17 +1158,32 @@ __global__ __launch_bounds__(1024) void k_pick_best(const RefRec *ref, uint32_t 
   }
 }
 
+constexpr uint32_t kRankLds = 1024;  // records the one-workgroup form of k_rank_topk takes
+
 // Top-k: the rank of every valid re-evaluated candidate in ascending (key, index) order.
-// One wave per candidate: its lanes count, in strides over the list, the entries that
-// precede it; ranks below k go to a device-side list, which the workgroup that finishes last
-// copies to host-mapped memory in one coalesced pass (scattered 40-byte stores over the bus,
-// each behind its own fence, cost 20 us for 500 records).
-__global__ __launch_bounds__(256) void k_rank_topk(const RefRec *ref, uint32_t ref_cap,
-                                                   const uint32_t *counters,
-                                                   uint32_t *next_counters, int objective,
-                                                   uint32_t k, ResultHeader *hdr, RefRec *out,
-                                                   RefRec *staged, uint32_t *done, uint32_t seq) {
+// Launched as one workgroup of kRankLds threads when few records are expected (small k):
+// keys and indices go to LDS, every thread counts the predecessors of one record, and the
+// k first are copied to host-mapped memory in rank order.  Otherwise (several workgroups,
+// or more than kRankLds records) one wave per candidate: its lanes count, in strides over
+// the list, the entries that precede it; ranks below k go to a device-side list, which the
+// workgroup that finishes last copies to host-mapped memory in one coalesced pass
+// (scattered 40-byte stores over the bus, each behind its own fence, cost 20 us for 500
+// records).
+__global__ __launch_bounds__(kRankLds) void k_rank_topk(const RefRec *ref, uint32_t ref_cap,
+                                                        const uint32_t *counters,
+                                                        uint32_t *next_counters, int objective,
+                                                        uint32_t k, ResultHeader *hdr, RefRec *out,
+                                                        RefRec *staged, uint32_t *done,
+                                                        uint32_t seq) {
   __shared__ uint32_t s_last;
+  __shared__ double s_key[kRankLds];
+  __shared__ unsigned long long s_idx[kRankLds];
+  __shared__ uint16_t s_opos[kRankLds];
+  __shared__ uint32_t s_before[kRankLds];
+  // (one-workgroup form) a thread's record is requested together with the count: the
+  // buffer holds ref_cap records, so the address is valid whatever the count turns out to be
+  RefRec mine{};
+  if (gridDim.x == 1 && threadIdx.x < ref_cap) mine = ref[threadIdx.x];
   const uint32_t n = min(counters[CNT_REF], ref_cap);
   if (blockIdx.x == 0 && threadIdx.x < CNT_COUNT)
     next_counters[threadIdx.x] = counter_reset_value(threadIdx.x);  // for the next call
@@ -1116,6 +1194,44 @@ __global__ __launch_bounds__(256) void k_rank_topk(const RefRec *ref, uint32_t r
     hdr->ref_count = counters[CNT_REF];
     hdr->feasible_count = f;
     hdr->gmin_bits = counters[CNT_GMIN];
+  }
+  if (gridDim.x == 1 && n <= kRankLds) {  // uniform
+    const uint32_t t = threadIdx.x;
+    if (t < n) {
+      const bool ok = mine.mask == 0;
+      s_key[t] = ok ? (objective == 0 ? mine.T : mine.C) : __builtin_huge_val();
+      s_idx[t] = ok ? mine.idx : ~0ull;
+    }
+    s_before[t] = 0;
+    __syncthreads();
+    // the workgroup's threads form rows of np >= n threads (a power of two); row r counts,
+    // for record q, the predecessors among records r, r + rows, ...
+    uint32_t np = 64;
+    while (np < n) np <<= 1;
+    const uint32_t q = t & (np - 1), row = t / np, rows = kRankLds / np;
+    if (q < n && s_idx[q] != ~0ull) {
+      const double mk = s_key[q];
+      const unsigned long long mi = s_idx[q];
+      uint32_t before = 0;
+#pragma unroll 4
+      for (uint32_t j = row; j < n; j += rows) before += lex_less(s_key[j], s_idx[j], mk, mi) ? 1u : 0u;
+      if (before) atomicAdd(&s_before[q], before);
+    }
+    __syncthreads();
+    if (t < n && s_idx[t] != ~0ull && s_before[t] < k) s_opos[s_before[t]] = (uint16_t)t;
+    __syncthreads();
+    const uint32_t f = counters[CNT_FEAS], n_out = f < k ? f : k;  // n_out <= n
+    constexpr uint32_t kWords = sizeof(RefRec) / 8;
+    for (uint32_t w = threadIdx.x; w < n_out * kWords; w += blockDim.x)
+      reinterpret_cast<unsigned long long *>(out)[w] =
+          reinterpret_cast<const unsigned long long *>(ref + s_opos[w / kWords])[w % kWords];
+    // One system-scope fence for the workgroup (each costs a fraction of a microsecond per
+    // wave that executes it): the stores above are ordered before thread 0's fence by a
+    // workgroup-scope release and the barrier.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (threadIdx.x == 0) publish(hdr, seq);
+    return;
   }
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);

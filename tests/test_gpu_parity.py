@@ -463,3 +463,39 @@ def test_eval_batch_replays_from_a_captured_graph(torch_cuda):
             assert plan.best_plan().index == orc.best().index
     finally:
         plan.destroy()
+
+
+def test_independent_plans_serve_two_host_threads(torch_cuda):
+    # one plan per thread, each on a stream of its own: the calls overlap in time (ctypes
+    # releases the interpreter lock) and every one must return what the oracle selects
+    import threading
+    torch = torch_cuda
+    probs = [W.config2(), W.config1().with_per_segment_tp()]
+    orcs = [Oracle(p) for p in probs]
+    want = [(o.best(MAX_THROUGHPUT), o.topk(16, MIN_COST)) for o in orcs]
+    plans = [_plan(p) for p in probs]
+    streams = [torch.cuda.Stream() for _ in probs]
+    errors = []
+
+    def serve(i):
+        try:
+            for rep in range(40):
+                best = plans[i].best_plan(MAX_THROUGHPUT, stream=streams[i].cuda_stream)
+                assert best.index == want[i][0].index, (i, rep)
+                top = plans[i].topk(16, MIN_COST, stream=streams[i].cuda_stream)
+                assert [r.index for r in top] == [e.index for e in want[i][1]], (i, rep)
+        except BaseException as e:  # reported by the main thread
+            errors.append(e)
+
+    try:
+        workers = [threading.Thread(target=serve, args=(i,)) for i in range(len(probs))]
+        for w in workers:
+            w.start()
+        for w in workers:
+            w.join(timeout=100)
+        assert not any(w.is_alive() for w in workers)
+        assert not errors, errors
+        torch.cuda.synchronize()
+    finally:
+        for p in plans:
+            p.destroy()
