@@ -39,6 +39,28 @@ SIMDS, CLOCK_HZ, CYCLES_PER_WAVE_INST = 1024, 2.4e9, 4
 EVENT_EVERY = 8
 
 
+def timed_steps(plan, step, steps, sync):
+    """Wall time per step (ms) over `steps` calls of step(), and the mean duration (ms) of the
+    scan kernel over the calls whose dispatch carried start / stop events: every
+    EVENT_EVERY-th one.  A dispatch with events costs the step about 15 us (the runtime
+    completes and timestamps it apart from its neighbours), so events on every launch would
+    measure mostly that; the steps with events are part of the timed region."""
+    scan_ms, n_timed, out = 0.0, 0, None
+    sync()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        timed = i % EVENT_EVERY == 0
+        plan.set_timing(1 if timed else 0)
+        out = step()
+        if timed:
+            scan_ms += plan.last_timing()[1]
+            n_timed += 1
+    sync()
+    wall = time.perf_counter() - t0
+    plan.set_timing(0)
+    return wall / steps * 1e3, scan_ms / n_timed, out
+
+
 def mean_pipeline_depth(prob) -> float:
     """Block-size weighted mean of P over the candidate space (bookkeeping only)."""
     zg = prob.n_zones * prob.n_types
@@ -78,7 +100,8 @@ def cpu_baseline(prob, n_sample: int) -> dict:
 
 def sweep(torch, workloads, Plan, MAX_THROUGHPUT, MIN_COST) -> int:
     """Time to the 64 best plans (max throughput under 1.2 x the cheapest plan's cost) and to
-    the best plan, per workload; inputs resident, 30 repetitions after 5 warm-up calls."""
+    the best plan, per workload; inputs resident, 32 (top-64) and 30 (best plan) repetitions
+    after 5 warm-up calls."""
     from paper_2504_17096_amd.binding import sailor_result
     stream = torch.cuda.current_stream().cuda_stream
     base = {"cfg1": workloads.config1(), "cfg2": workloads.config2(), "cfg3": workloads.config3(),
@@ -98,12 +121,9 @@ def sweep(torch, workloads, Plan, MAX_THROUGHPUT, MIN_COST) -> int:
         plan.set_timing(1)
         for _ in range(5):
             plan.topk_raw(64, MAX_THROUGHPUT, budget, buf, stream)
-        t0, scan = time.perf_counter(), 0.0
-        for _ in range(30):
-            found = plan.topk_raw(64, MAX_THROUGHPUT, budget, buf, stream)
-            scan += plan.last_timing()[1] / 30
-        top_ms = (time.perf_counter() - t0) / 30 * 1e3
-        plan.set_timing(0)
+        top_ms, scan, found = timed_steps(
+            plan, lambda: plan.topk_raw(64, MAX_THROUGHPUT, budget, buf, stream), 32,
+            torch.cuda.synchronize)
         t0 = time.perf_counter()
         for _ in range(30):
             plan.best_plan(objective=MAX_THROUGHPUT, bound=budget, stream=stream)
@@ -163,28 +183,12 @@ def main() -> int:
     def step():
         return plan.topk_raw(K, MAX_THROUGHPUT, budget, buf, stream)
 
-    # Start / stop events ride on the scan kernel's own dispatch in every EVENT_EVERY-th step
-    # of the timed region: a dispatch that carries events costs the step about 15 us (the
-    # runtime completes and timestamps it apart from its neighbours), so timing every launch
-    # would measure mostly that.  The steps with events are part of the timed region and of
-    # `value`; the kernel's duration is the mean over them.
+    # start / stop events ride on the scan kernel's own dispatch in every EVENT_EVERY-th step
+    # of the timed region (see timed_steps); those steps are part of `value`
     plan.set_timing(1)
     for _ in range(args.warmup):
         step()
-    torch.cuda.synchronize()
-    scan_ms, n_timed = 0.0, 0
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        timed = i % EVENT_EVERY == 0
-        plan.set_timing(1 if timed else 0)
-        n_found = step()
-        if timed:
-            scan_ms += plan.last_timing()[1]
-            n_timed += 1
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall / args.steps * 1e3
-    scan_ms /= n_timed
+    ms_per_step, scan_ms, n_found = timed_steps(plan, step, args.steps, torch.cuda.synchronize)
     assert n_found == K, n_found
     top1_index = int(buf[0].index)
     counts = plan.last_counts()
@@ -263,19 +267,15 @@ def main() -> int:
         p.set_timing(1)
         for _ in range(2):
             p.topk_raw(K, MAX_THROUGHPUT, b, buf, stream)
-        torch.cuda.synchronize()
-        t0, scan = time.perf_counter(), 0.0
-        for _ in range(reps):
-            p.topk_raw(K, MAX_THROUGHPUT, b, buf, stream)
-            scan += p.last_timing()[1] / reps
-        ms = (time.perf_counter() - t0) / reps * 1e3
+        ms, scan, _ = timed_steps(p, lambda: p.topk_raw(K, MAX_THROUGHPUT, b, buf, stream), reps,
+                                  torch.cuda.synchronize)
         out = {"candidates": p.num_candidates(), "time_to_top64_ms": ms, "scan_kernel_ms": scan,
                "candidates_per_s": p.num_candidates() / (ms * 1e-3)}
         p.destroy()
         return out
 
-    segtp = widened(prob.with_per_segment_tp(), 10)
-    mixed = widened(prob.with_mixed_types(), 10)
+    segtp = widened(prob.with_per_segment_tp(), 16)
+    mixed = widened(prob.with_mixed_types(), 16)
 
     if args.copy_probe:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").fill_(1.0)
