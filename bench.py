@@ -150,6 +150,9 @@ def main() -> int:
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
+    if args.steps < 1 or args.warmup < 0:
+        print("bench.py: --steps must be at least 1 and --warmup at least 0", file=sys.stderr)
+        return 2
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding across GPUs); "
               "use --gpus 1", file=sys.stderr)

@@ -243,7 +243,7 @@ def test_best_plan_and_topk(case, torch_cuda, objective):
             assert got is None
         else:
             check_result(got, want, orc)
-        for k in (1, 7, 64):
+        for k in (1, 7, 64, 300):  # (above 128 the final ranking runs on several workgroups)
             want_k = orc.topk(k, objective=objective, bound=bound, n_threads=THREADS)
             got_k = plan.topk(k, objective=objective, bound=bound, stream=stream)
             check_topk(got_k, want_k, objective)
