@@ -151,13 +151,18 @@ __global__ void k_stage_tables(DevPlan pl, StageArgs a) {
   }
 }
 
+// model + activation bytes of a worker of stage i of P (Sec. 4.3) from the stage's parameter
+// and layer counts; reserved bytes are added where the GPU type is known
+__device__ __forceinline__ uint64_t stage_bytes_of(uint64_t params, int32_t layers, uint32_t bpp,
+                                                   int i, int P, int tp, int64_t nb, uint64_t act) {
+  const uint64_t shard = (params + (uint64_t)tp - 1) / (uint64_t)tp;
+  const int64_t inflight = (int64_t)(P - i) < nb ? (int64_t)(P - i) : nb;
+  return shard * (uint64_t)bpp + (uint64_t)inflight * (uint64_t)layers * act;
+}
+
 __device__ __forceinline__ uint64_t stage_bytes(const DevPlan &pl, uint32_t rs, int i, int P,
                                                 int tp, int64_t nb, uint64_t act) {
-  // model + activation bytes of a worker of stage i (Sec. 4.3); reserved bytes are added
-  // where the GPU type is known
-  uint64_t shard = (pl.st_params[rs + i] + (uint64_t)tp - 1) / (uint64_t)tp;
-  int64_t inflight = (int64_t)(P - i) < nb ? (int64_t)(P - i) : nb;
-  return shard * (uint64_t)pl.bpp + (uint64_t)inflight * (uint64_t)pl.st_n[rs + i] * act;
+  return stage_bytes_of(pl.st_params[rs + i], pl.st_n[rs + i], pl.bpp, i, P, tp, nb, act);
 }
 
 // Segment aggregates of one shape: everything of a segment that does not depend on
@@ -960,71 +965,100 @@ __device__ __forceinline__ void eval_exact_wave(const DevPlan &pl, const Cand &c
   mask = 0;
   peak = 0;
   const int64_t nb = pl.nb[c.mb * DP + c.dp];
-  if (nb == 0) {  // uniform over the wave
+  const double p2p = (double)pl.p2p[c.mb];
+  const double *bwp = pl.bwp + c.mb * Z * Z;  // bandwidth seen by a transfer of p2p bytes
+  // quota per pool (GPUs of one replica there, times D) and H1
+  // (counted in halves: a segment on a pair of types takes half of its replicas from each).
+  // Everything read from memory is requested first, for all three segments at once: the
+  // loads do not depend on one another, and a loop that fetched them as it went paid a trip
+  // to memory for each.
+  int zj[3], ga[3], gb[3];
+  int64_t tpj[3], wj[3], av_a[3], av_b[3], nd_a[3], nd_b[3];
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    const bool used = j < c.s;
+    ga[j] = xs[j] & 255;
+    gb[j] = xs[j] >> 8;
+    zj[j] = used ? c.a[j] / GX : 0;
+    tpj[j] = used ? (int64_t)pl.vals[pl.DP + c.tp[j]] : 0;
+    av_a[j] = used ? (int64_t)pl.avail[zj[j] * G + ga[j]] : 0;
+    av_b[j] = used ? (int64_t)pl.avail[zj[j] * G + gb[j]] : 0;
+    nd_a[j] = used ? (int64_t)pl.node[ga[j]] : 0;
+    nd_b[j] = used ? (int64_t)pl.node[gb[j]] : 0;
+  }
+  if (nb == 0) {  // uniform over the wave (tested only now: the loads above need not wait for it)
     mask = 4u;    // batch not divisible
     T = C = __builtin_huge_val();
     return;
   }
-  const double p2p = (double)pl.p2p[c.mb];
-  const double *bwp = pl.bwp + c.mb * Z * Z;  // bandwidth seen by a transfer of p2p bytes
-  // quota per pool (GPUs of one replica there, times D) and H1
-  // (counted in halves: a segment on a pair of types takes half of its replicas from each)
-  for (int j = 0; j < c.s; ++j) {
-    const int x = at3(xs, j), ga = x & 255, gb = x >> 8, z = at3(c.a, j) / GX;
-    for (int slot = 0; slot < (ga == gb ? 1 : 2); ++slot) {
-      const int g = slot == 0 ? ga : gb;
+#pragma unroll
+  for (int j = 0; j < 3; ++j) wj[j] = (int64_t)sh.n[j] * tpj[j];
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    if (j >= c.s) continue;
+#pragma unroll
+    for (int slot = 0; slot < 2; ++slot) {
+      if (slot == 1 && ga[j] == gb[j]) continue;
+      const int g = slot == 0 ? ga[j] : gb[j];
       int64_t halves = 0;
-      for (int j2 = 0; j2 < c.s; ++j2) {
-        const int x2 = at3(xs, j2), a2 = x2 & 255, b2 = x2 >> 8;
-        if (at3(c.a, j2) / GX != z) continue;
-        const int64_t w = (int64_t)at3(sh.n, j2) * pl.vals[pl.DP + at3(c.tp, j2)];
-        if (a2 == b2) halves += a2 == g ? 2 * w : 0;
-        else halves += (a2 == g || b2 == g) ? w : 0;
+#pragma unroll
+      for (int j2 = 0; j2 < 3; ++j2) {
+        if (j2 >= c.s || zj[j2] != zj[j]) continue;
+        if (ga[j2] == gb[j2]) halves += ga[j2] == g ? 2 * wj[j2] : 0;
+        else halves += (ga[j2] == g || gb[j2] == g) ? wj[j2] : 0;
       }
-      if (halves * D > 2 * (int64_t)pl.avail[z * G + g]) mask |= 2u;
+      if (halves * D > 2 * (slot == 0 ? av_a[j] : av_b[j])) mask |= 2u;
     }
-    if (ga != gb && D % 2 != 0) mask |= 2u;  // D replicas cannot be halved
-    if (pl.vals[pl.DP + at3(c.tp, j)] > pl.node[ga] || pl.vals[pl.DP + at3(c.tp, j)] > pl.node[gb]) mask |= 8u;
+    if (ga[j] != gb[j] && D % 2 != 0) mask |= 2u;  // D replicas cannot be halved
+    if (tpj[j] > nd_a[j] || tpj[j] > nd_b[j]) mask |= 8u;
   }
   double max_t = 0.0, t_sync = 0.0, t_upd = 0.0;
   uint32_t oom = 0;
   for (int i = lane; i < P; i += 64) {
     const int seg = i < c.k1 ? 0 : (i < c.k2 ? 1 : 2);
-    const int xg = at3(xs, seg), g = xg & 255, g2 = xg >> 8, z = at3(c.a, seg) / GX;
+    const int xg = at3(xs, seg), g = xg & 255, g2 = xg >> 8, z = at3(zj, seg);
     const int k = at3(c.tp, seg);
-    const int64_t tp = pl.vals[pl.DP + k];
-    const uint64_t bytes_i = stage_bytes(pl, rs, i, P, (int)tp, nb, pl.act[c.mb * TP + k]);
-    const uint64_t m = bytes_i + pl.res[g], m2 = bytes_i + pl.res[g2];  // both replica types
-    if (m > pl.cap[g] || m2 > pl.cap[g2]) oom = 1u;
+    const int64_t tp = at3(tpj, seg);
+    // the zones of the neighbouring stages (the stage's own where there is none)
+    const int sn = (i + 1) < c.k1 ? 0 : ((i + 1) < c.k2 ? 1 : 2);
+    const int sp = (i - 1) < c.k1 ? 0 : ((i - 1) < c.k2 ? 1 : 2);
+    const int zn = i < P - 1 ? at3(zj, sn) : z, zp = i > 0 ? at3(zj, sp) : z;
+    // everything the stage reads from memory, requested together
+    const size_t si = (size_t)rs + i;
+    const uint64_t params = pl.st_params[si];
+    const int32_t layers = pl.st_n[si];
+    const uint64_t act = pl.act[c.mb * TP + k];
+    const uint64_t res1 = pl.res[g], res2 = pl.res[g2], cap1 = pl.cap[g], cap2 = pl.cap[g2];
+    const double c1 = pl.st_c[((si * G + g) * MB + c.mb) * TP + k];
+    const double c2 = pl.st_c[((si * G + g2) * MB + c.mb) * TP + k];
+    const double u1 = pl.st_u[(si * G + g) * TP + k], u2 = pl.st_u[(si * G + g2) * TP + k];
+    const double price1 = pl.price[g], price2 = pl.price[g2];
+    const double bw_n = bwp[z * Z + zn], bw_p = bwp[z * Z + zp];
+    const double eg = pl.egress ? pl.egress[z * Z + zn] + pl.egress[zn * Z + z] : 0.0;
+    const uint64_t bytes_i = stage_bytes_of(params, layers, pl.bpp, i, P, (int)tp, nb, act);
+    const uint64_t m = bytes_i + res1, m2 = bytes_i + res2;  // both replica types
+    if (m > cap1 || m2 > cap2) oom = 1u;
     peak = m > peak ? m : peak;
     peak = m2 > peak ? m2 : peak;
     double x = 0.0, comm = 0.0;
     if (i < P - 1) {
-      const int sn = (i + 1) < c.k1 ? 0 : ((i + 1) < c.k2 ? 1 : 2);
-      const int zn = at3(c.a, sn) / GX;
-      x += p2p / bwp[z * Z + zn];
-      if (pl.egress && zn != z)
-        comm = (double)nb * (double)D * p2p * (pl.egress[z * Z + zn] + pl.egress[zn * Z + z]);
+      x += p2p / bw_n;
+      if (pl.egress && zn != z) comm = (double)nb * (double)D * p2p * eg;
     }
-    if (i > 0) {
-      const int sp = (i - 1) < c.k1 ? 0 : ((i - 1) < c.k2 ? 1 : 2);
-      x += p2p / bwp[z * Z + at3(c.a, sp) / GX];
-    }
+    if (i > 0) x += p2p / bw_p;
     // the slower replica type sets the stage's pace (straggler, Sec. 4.3)
-    const double t = fmax(pl.st_c[(((size_t)(rs + i) * G + g) * MB + c.mb) * TP + k],
-                          pl.st_c[(((size_t)(rs + i) * G + g2) * MB + c.mb) * TP + k]) + x;
+    const double t = fmax(c1, c2) + x;
     max_t = fmax(max_t, t);
     if (D > 1) {
-      const uint64_t shard = (pl.st_params[rs + i] + (uint64_t)tp - 1) / (uint64_t)tp;
+      const uint64_t shard = (params + (uint64_t)tp - 1) / (uint64_t)tp;
       const double bytes = (double)shard * (double)pl.gb;
       const double sync = 2.0 * (double)(D - 1) / (double)D * bytes / link_bw(pl, z, z, bytes);
       t_sync = fmax(t_sync, sync);
     }
-    t_upd = fmax(t_upd, pl.st_u[((size_t)(rs + i) * G + g) * TP + k]);
-    t_upd = fmax(t_upd, pl.st_u[((size_t)(rs + i) * G + g2) * TP + k]);
+    t_upd = fmax(t_upd, u1);
+    t_upd = fmax(t_upd, u2);
     lds.t[i] = t;
-    lds.dol[i] = g == g2 ? (double)(D * tp) * pl.price[g]
-                         : (double)(D * tp) * (0.5 * (pl.price[g] + pl.price[g2]));
+    lds.dol[i] = g == g2 ? (double)(D * tp) * price1 : (double)(D * tp) * (0.5 * (price1 + price2));
     lds.comm[i] = comm;
   }
   if (__builtin_amdgcn_ballot_w64(oom != 0) != 0) mask |= 1u;
