@@ -1150,44 +1150,61 @@ __global__ __launch_bounds__(1024) void k_pick_best(const RefRec *ref, uint32_t 
                                                     const uint32_t *counters,
                                                     uint32_t *next_counters, int objective,
                                                     ResultHeader *hdr, RefRec *out, uint32_t seq) {
-  __shared__ double s_key[1024];
-  __shared__ unsigned long long s_idx[1024];
-  __shared__ uint32_t s_pos[1024];
-  const uint32_t n = min(counters[CNT_REF], ref_cap);
-  const int t = threadIdx.x;
+  __shared__ double s_key[16];
+  __shared__ unsigned long long s_idx[16];
+  __shared__ uint32_t s_pos[16];
+  const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+  // a thread's first record is requested together with the counters (the buffer holds
+  // ref_cap records, so the address is valid whatever the count turns out to be)
+  RefRec mine{};
+  if ((uint32_t)t < ref_cap) mine = ref[t];
+  const uint32_t n_ref = counters[CNT_REF], n_surv = counters[CNT_SURV],
+                 n_feas = counters[CNT_FEAS], gmin = counters[CNT_GMIN];
+  const uint32_t n = min(n_ref, ref_cap);
   if (t < CNT_COUNT) next_counters[t] = counter_reset_value(t);  // for the next call
   double best = __builtin_huge_val();
-  for (uint32_t i = t; i < n; i += blockDim.x)
+  if ((uint32_t)t < n && mine.mask == 0) best = objective == 0 ? mine.T : mine.C;
+  for (uint32_t i = t + blockDim.x; i < n; i += blockDim.x)
     if (ref[i].mask == 0) best = fmin(best, objective == 0 ? ref[i].T : ref[i].C);
-  s_key[t] = best;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) best = fmin(best, __shfl_xor(best, off));
+  if (lane == 0) s_key[wv] = best;
   __syncthreads();
-  for (int w = 512; w >= 1; w >>= 1) {
-    if (t < w) s_key[t] = fmin(s_key[t], s_key[t + w]);
-    __syncthreads();
-  }
-  const double limit = s_key[0] * (1.0 + kTieTol);
-  __syncthreads();
+  best = s_key[0];
+#pragma unroll
+  for (int w = 1; w < 16; ++w) best = fmin(best, s_key[w]);
+  const double limit = best * (1.0 + kTieTol);
   unsigned long long bi = ~0ull;
   uint32_t bp = 0;
-  for (uint32_t i = t; i < n; i += blockDim.x) {
+  if ((uint32_t)t < n && mine.mask == 0 && (objective == 0 ? mine.T : mine.C) <= limit) {
+    bi = mine.idx;
+    bp = t;
+  }
+  for (uint32_t i = t + blockDim.x; i < n; i += blockDim.x) {
     const double key = objective == 0 ? ref[i].T : ref[i].C;
     if (ref[i].mask == 0 && key <= limit && ref[i].idx < bi) { bi = ref[i].idx; bp = i; }
   }
-  s_idx[t] = bi;
-  s_pos[t] = bp;
-  __syncthreads();
-  for (int w = 512; w >= 1; w >>= 1) {
-    if (t < w && s_idx[t + w] < s_idx[t]) { s_idx[t] = s_idx[t + w]; s_pos[t] = s_pos[t + w]; }
-    __syncthreads();
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const unsigned long long oi = __shfl_xor(bi, off);
+    const uint32_t op = __shfl_xor(bp, off);
+    if (oi < bi) { bi = oi; bp = op; }
   }
+  if (lane == 0) { s_idx[wv] = bi; s_pos[wv] = bp; }
+  __syncthreads();
   if (t == 0) {
-    const bool found = s_idx[0] != ~0ull;
-    if (found) out[0] = ref[s_pos[0]];
+    for (int w = 1; w < 16; ++w)
+      if (s_idx[w] < bi) { bi = s_idx[w]; bp = s_pos[w]; }
+    const bool found = bi != ~0ull;
+    if (found) {
+      if (bp == 0) out[0] = mine;  // (thread 0 holds record 0)
+      else out[0] = ref[bp];
+    }
     hdr->n_found = found ? 1u : 0u;
-    hdr->surv_count = counters[CNT_SURV];
-    hdr->ref_count = counters[CNT_REF];
-    hdr->feasible_count = counters[CNT_FEAS];
-    hdr->gmin_bits = counters[CNT_GMIN];
+    hdr->surv_count = n_surv;
+    hdr->ref_count = n_ref;
+    hdr->feasible_count = n_feas;
+    hdr->gmin_bits = gmin;
     publish(hdr, seq);
   }
 }
@@ -1219,10 +1236,10 @@ __global__ __launch_bounds__(kRankLds) void k_rank_topk(const RefRec *ref, uint3
   RefRec mine{};
   if (gridDim.x == 1 && threadIdx.x < ref_cap) mine = ref[threadIdx.x];
   const uint32_t n = min(counters[CNT_REF], ref_cap);
+  const uint32_t f = counters[CNT_FEAS];  // valid records (requested with the count)
   if (blockIdx.x == 0 && threadIdx.x < CNT_COUNT)
     next_counters[threadIdx.x] = counter_reset_value(threadIdx.x);  // for the next call
   if (blockIdx.x == 0 && threadIdx.x == 0) {
-    const uint32_t f = counters[CNT_FEAS];
     hdr->n_found = f < k ? f : k;
     hdr->surv_count = counters[CNT_SURV];
     hdr->ref_count = counters[CNT_REF];
@@ -1254,7 +1271,7 @@ __global__ __launch_bounds__(kRankLds) void k_rank_topk(const RefRec *ref, uint3
     __syncthreads();
     if (t < n && s_idx[t] != ~0ull && s_before[t] < k) s_opos[s_before[t]] = (uint16_t)t;
     __syncthreads();
-    const uint32_t f = counters[CNT_FEAS], n_out = f < k ? f : k;  // n_out <= n
+    const uint32_t n_out = f < k ? f : k;  // n_out <= n
     constexpr uint32_t kWords = sizeof(RefRec) / 8;
     for (uint32_t w = threadIdx.x; w < n_out * kWords; w += blockDim.x)
       reinterpret_cast<unsigned long long *>(out)[w] =
@@ -1296,7 +1313,7 @@ __global__ __launch_bounds__(kRankLds) void k_rank_topk(const RefRec *ref, uint3
   __syncthreads();
   if (!s_last) return;  // uniform
   __threadfence();      // the last workgroup: see what the others staged
-  const uint32_t f = counters[CNT_FEAS], n_out = f < k ? f : k;
+  const uint32_t n_out = f < k ? f : k;
   const unsigned long long *src = reinterpret_cast<const unsigned long long *>(staged);
   unsigned long long *dst = reinterpret_cast<unsigned long long *>(out);
   for (uint32_t i = threadIdx.x; i < n_out * (uint32_t)(sizeof(RefRec) / 8); i += blockDim.x)
