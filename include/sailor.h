@@ -239,7 +239,9 @@ sailor_status sailor_plan_set_scratch(sailor_plan *plan, uint32_t max_survivors,
 /* Measurement only.  mode 0 (default): no events are recorded.  mode 1: the dominant kernel
  * of each call (the full-space scan of sailor_best_plan / sailor_topk, the evaluation kernel
  * of sailor_eval_batch) is launched with start and stop events on its stream.  mode 2: in
- * addition two events bracket all kernels of a sailor_best_plan / sailor_topk call. */
+ * addition two events bracket all kernels of a sailor_best_plan / sailor_topk call.  A
+ * dispatch that carries events is completed and timestamped apart from its neighbours, which
+ * lengthens the call by some 15 us: time a sample of the calls, not every one. */
 sailor_status sailor_plan_set_timing(sailor_plan *plan, int32_t mode);
 
 /* Milliseconds measured by the last call on this plan under the timing mode above:

@@ -499,3 +499,35 @@ def test_independent_plans_serve_two_host_threads(torch_cuda):
     finally:
         for p in plans:
             p.destroy()
+
+
+def test_timing_modes_report_the_scan_and_the_whole_call(torch_cuda):
+    from paper_2504_17096_amd.binding import SAILOR_EINVAL, SailorError
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    prob = W.config2()
+    plan = _plan(prob)
+    try:
+        want = plan.best_plan(stream=stream).index
+        with pytest.raises(SailorError) as ei:   # nothing was recorded in mode 0
+            plan.last_timing()
+        assert ei.value.status == SAILOR_EINVAL
+        plan.set_timing(1)
+        assert plan.best_plan(stream=stream).index == want
+        total, scan = plan.last_timing()
+        assert total == 0.0 and 0.0 < scan < 50.0
+        plan.set_timing(2)
+        assert [r.index for r in plan.topk(3, stream=stream)][0] == want
+        total, scan2 = plan.last_timing()
+        assert 0.0 < scan2 <= total < 50.0
+        n = plan.num_candidates()
+        t = torch_cuda.empty(n, dtype=torch_cuda.float32, device="cuda:0")
+        plan.eval_batch(0, n, d_time=t, stream=stream)
+        assert 0.0 < plan.last_timing()[1] < 50.0
+        plan.set_timing(0)
+        assert plan.best_plan(stream=stream).index == want
+        with pytest.raises(SailorError):
+            plan.last_timing()
+        with pytest.raises(SailorError):
+            plan.set_timing(3)
+    finally:
+        plan.destroy()
