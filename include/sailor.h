@@ -174,7 +174,11 @@ typedef struct {
 } sailor_result;
 
 /* Build a plan: validate, copy the problem to the current HIP device, build the static
- * per-stage and per-segment tables there.  *out receives the plan.
+ * per-stage and per-segment tables there, and run three to four passes over the space that
+ * decide how later scans are launched (which pieces of the space can never hold a valid plan,
+ * how long the others take); results do not depend on that.  *out receives the plan.
+ * Test hook: with SAILOR_UNIT_PARTS=n (2..255) in the environment every piece is cut into n
+ * parts, which measured times otherwise decide.
  * Errors: SAILOR_EINVAL (see limits and field comments), SAILOR_ENOMEM, SAILOR_EDEVICE. */
 sailor_status sailor_plan_create(const sailor_problem *problem, sailor_plan **out);
 

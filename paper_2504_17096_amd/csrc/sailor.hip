@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -25,6 +26,9 @@ constexpr uint64_t kUnitTargetMin = 4096, kUnitTargetMax = 65536, kUnitsWanted =
 constexpr uint32_t kCollectSub = 4;      // workgroups that share one unit in the collect pass
 constexpr uint32_t kListSub = 8;         // the same when the pass walks a list of units,
 constexpr uint32_t kListUnits = 256;     // and the units it visits per round
+// a scan unit that takes more than kSplitAbove x the average load of a workgroup slot (and
+// kSplitAboveMean x the mean unit) is cut into parts of about kSplitTo x that load
+constexpr double kSplitAbove = 0.9, kSplitAboveMean = 1.5, kSplitTo = 0.7, kSplitToMean = 1.1;
 constexpr uint32_t kRankOneWorkgroup = 128;  // largest k whose final ranking runs as one workgroup
 constexpr uint32_t kEvalUnitTarget = 16384;  // candidates per workgroup of the range evaluation
 constexpr unsigned kEvalRowsThreads = 512;
@@ -312,6 +316,8 @@ sailor_status build_space(const sailor_problem *p, sailor_plan *pl, std::vector<
             u.o_lo = (uint16_t)lo;
             u.o_cnt = (uint16_t)(hi - lo);
             for (int j = 0; j < 3; ++j) u.n[j] = sh.n[j];
+            u.part = 0;
+            u.n_parts = 1;
             u.base = sh.base + (pst ? inner * (uint64_t)(ZG - 1) * (uint64_t)t1 +
                                           pl->dev.stride3 * (uint64_t)(ZG - 1) * (uint64_t)t2
                                     : 0u);
@@ -774,7 +780,19 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(ar.upload(&d.st_first, st_first.data(), RS));
   CREATE_TRY(ar.upload(&d.shapes, pl->shapes.data(), NS));
   CREATE_TRY(ar.upload(&d.blocks, pl->blocks.data(), pl->blocks.size()));
-  CREATE_TRY(ar.upload(&d.units, pl->units.data(), pl->units.size()));
+  // per-unit tables: one entry per unit as laid out (units dropped later leave room for the
+  // parts of units that are cut); the test hook SAILOR_UNIT_PARTS=n cuts every unit into n
+  // parts whatever the timing says and needs n times the room
+  const char *parts_env = std::getenv("SAILOR_UNIT_PARTS");
+  const long forced_parts = parts_env ? std::min(255L, std::strtol(parts_env, nullptr, 10)) : 0;
+  const size_t unit_cap = pl->units.size() * (size_t)std::max(1L, forced_parts);
+  {
+    UnitRec *d_units_new = nullptr;
+    CREATE_TRY(ar.alloc(&d_units_new, unit_cap));
+    CREATE_TRY(hipMemcpy(d_units_new, pl->units.data(), pl->units.size() * sizeof(UnitRec),
+                         hipMemcpyHostToDevice));
+    d.units = d_units_new;
+  }
   CREATE_TRY(ar.upload(&pl->d_eunits, pl->eunits.data(), pl->eunits.size()));
   // derived tables, filled by the set-up kernels
   d.n_bw_coef = p->n_bw_coef;
@@ -801,10 +819,10 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(ar.alloc(&d.syncz, slots * Z));
   CREATE_TRY(ar.alloc(&d.upd, slots * GX));
   // selection scratch
-  CREATE_TRY(ar.alloc(&pl->umin_s, pl->units.size()));
-  CREATE_TRY(ar.alloc(&pl->umin_l, pl->units.size()));
+  CREATE_TRY(ar.alloc(&pl->umin_s, unit_cap));
+  CREATE_TRY(ar.alloc(&pl->umin_l, unit_cap));
   CREATE_TRY(ar.alloc(&pl->counters, (size_t)2 * CNT_COUNT));
-  CREATE_TRY(ar.alloc(&pl->ulist, pl->units.size()));
+  CREATE_TRY(ar.alloc(&pl->ulist, unit_cap));
   CREATE_TRY(ar.alloc(&pl->surv, (size_t)pl->surv_cap));
   CREATE_TRY(ar.alloc(&pl->ref, (size_t)pl->ref_cap));
   CREATE_TRY(ar.alloc(&pl->staged, (size_t)SAILOR_MAX_K));
@@ -832,8 +850,9 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
     // records how long each remaining unit takes; they are then launched longest first,
     // which also deals them evenly to the hardware's dispatch queues.
     size_t NU = pl->units.size();
+    const size_t n_units_alloc = unit_cap;  // entries of the per-unit tables on the device
     float *d_cost = nullptr;
-    CREATE_TRY(ar.alloc(&d_cost, NU));
+    CREATE_TRY(ar.alloc(&d_cost, unit_cap));
     ScanArgs ca{};
     ca.umin_s = pl->umin_s;
     ca.umin_l = pl->umin_l;
@@ -858,6 +877,57 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
     launch_units<MODE_SCAN>(pl, SAILOR_MAX_THROUGHPUT, 0, ca, nullptr, nullptr, nullptr);
     CREATE_TRY(hipGetLastError());
     CREATE_TRY(hipMemcpy(val.data(), d_cost, NU * sizeof(float), hipMemcpyDeviceToHost));
+    // With the longest units first the launch ends about when the average load of a
+    // workgroup slot is done, unless a unit on its own takes longer than that: such a unit is
+    // cut into parts -- every part keeps the unit's records and takes a share of its lane
+    // space -- within the room the dropped units left in the tables, and the pass is timed
+    // again.  (Cutting units that are merely above the mean costs more in staging than it
+    // gains: spaces with far more units than slots ran 4 % slower that way.)
+    {
+      double total = 0.0;
+      for (size_t i = 0; i < NU; ++i) total += val[i];
+      const double mean = total / (double)NU;
+      int per_cu = 0, cus = 0;
+      const void *scan_kernel = d.mixed ? (const void *)k_units<MODE_SCAN, 0, true, true>
+                                        : (const void *)k_units<MODE_SCAN, 0, true, false>;
+      CREATE_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, scan_kernel,
+                                                              (int)pl->unit_threads, pl->lds_bytes));
+      CREATE_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, pl->device));
+      const double slots = (double)std::max(1, per_cu) * (double)std::max(1, cus);
+      const double load = total / std::min((double)NU, slots);  // average load of a slot
+      const double above = std::max(kSplitAbove * load, kSplitAboveMean * mean);
+      const double target = std::max(kSplitTo * load, kSplitToMean * mean);
+      const size_t waves = pl->unit_threads / 64;
+      // 64-lane chunks of a unit's lane space (three segments: pool 1 skips segment 2's pool)
+      const size_t chunks_of_unit = ((size_t)d.MB * d.DP * (size_t)std::max(1, d.ZG - 1) + 63) / 64;
+      const size_t most = std::max<size_t>(1, std::min<size_t>(255, chunks_of_unit / waves));
+      size_t room = n_units_alloc - NU;
+      std::vector<UnitRec> cut;
+      cut.reserve(n_units_alloc);
+      for (size_t i = 0; i < NU; ++i) {
+        UnitRec u = pl->units[i];
+        size_t parts = 1;
+        if (forced_parts > 0) parts = std::min<size_t>((size_t)forced_parts, room + 1);
+        else if (val[i] > above)
+          parts = std::min<size_t>({most, (size_t)std::ceil(val[i] / target), room + 1});
+        u.n_parts = (uint8_t)parts;
+        for (size_t c = 0; c < parts; ++c) {
+          u.part = (uint8_t)c;
+          cut.push_back(u);
+        }
+        room -= parts - 1;
+      }
+      if (cut.size() != NU) {
+        pl->units.swap(cut);
+        NU = pl->units.size();
+        d.n_units = (int)NU;
+        val.resize(NU);
+        CREATE_TRY(hipMemcpy(d_units, pl->units.data(), NU * sizeof(UnitRec), hipMemcpyHostToDevice));
+        launch_units<MODE_SCAN>(pl, SAILOR_MAX_THROUGHPUT, 0, ca, nullptr, nullptr, nullptr);
+        CREATE_TRY(hipGetLastError());
+        CREATE_TRY(hipMemcpy(val.data(), d_cost, NU * sizeof(float), hipMemcpyDeviceToHost));
+      }
+    }
     std::vector<uint32_t> order(NU);
     for (size_t i = 0; i < NU; ++i) order[i] = (uint32_t)i;
     std::stable_sort(order.begin(), order.end(),

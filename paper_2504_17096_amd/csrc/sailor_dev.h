@@ -46,8 +46,9 @@ struct UnitRec {        // work of one workgroup of the scan: one shape, one tp 
   uint32_t shape;       // [o_lo, o_lo + o_cnt) of segment 2's pool.  base = first index of
   uint8_t tp[3], s;     // the shape + the offset of the unit's tp digits of segments 2, 3;
   uint16_t o_lo, o_cnt; // n = stages per segment (copied from the shape, so that a
-  uint16_t n[3], pad;   // workgroup needs one record to start)
-  uint32_t pad2;
+  uint16_t n[3];        // workgroup needs one record to start).  A unit found to run long is
+  uint8_t part, n_parts;  // cut into n_parts records: record `part` takes every n_parts-th
+  uint32_t pad2;          // share of the lane space (the (mb, dp, pool 1) triples)
 };
 static_assert(sizeof(UnitRec) == 32, "one unit record per 32 bytes");
 

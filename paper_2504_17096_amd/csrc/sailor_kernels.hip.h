@@ -706,9 +706,14 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
   }
 
   float ms = kPosInf, ml = kPosInf;
-  if (S == 1) unit_body<1, MODE, OBJ, HASB, MIXED>(pl, a, u, rec, pair, q13, isect, w0, w1, w2, tau, sub, (int)n_sub, ms, ml);
-  else if (S == 2) unit_body<2, MODE, OBJ, HASB, MIXED>(pl, a, u, rec, pair, q13, isect, w0, w1, w2, tau, sub, (int)n_sub, ms, ml);
-  else unit_body<3, MODE, OBJ, HASB, MIXED>(pl, a, u, rec, pair, q13, isect, w0, w1, w2, tau, sub, (int)n_sub, ms, ml);
+  // The unit's own share of the lane space, divided further among the n_sub workgroups.
+  // Chunk c of the lane space goes to wave c mod (waves * n_shares), so with the part as the
+  // fast digit of the share a part keeps the same chunks ((c / waves) mod n_parts == part)
+  // whatever n_sub is: the collect pass must visit exactly what the scan saw.
+  const int share = sub * (int)u.n_parts + (int)u.part, n_shares = (int)u.n_parts * (int)n_sub;
+  if (S == 1) unit_body<1, MODE, OBJ, HASB, MIXED>(pl, a, u, rec, pair, q13, isect, w0, w1, w2, tau, share, n_shares, ms, ml);
+  else if (S == 2) unit_body<2, MODE, OBJ, HASB, MIXED>(pl, a, u, rec, pair, q13, isect, w0, w1, w2, tau, share, n_shares, ms, ml);
+  else unit_body<3, MODE, OBJ, HASB, MIXED>(pl, a, u, rec, pair, q13, isect, w0, w1, w2, tau, share, n_shares, ms, ml);
 
   if (MODE == MODE_SCAN) {
     if (!HASB) ml = ms;

@@ -531,3 +531,27 @@ def test_timing_modes_report_the_scan_and_the_whole_call(torch_cuda):
             plan.set_timing(3)
     finally:
         plan.destroy()
+
+
+@pytest.mark.parametrize("parts", [2, 5])
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg2_mixed", "tiny4_segtp", "wide"])
+def test_selection_with_every_scan_unit_cut_into_parts(torch_cuda, monkeypatch, name, parts):
+    # units that run long are cut by measured time at plan creation, which small problems
+    # never trigger: the library's test hook cuts every unit, and the selections (scan,
+    # unit list, collect pass over the listed parts) must not change
+    monkeypatch.setenv("SAILOR_UNIT_PARTS", str(parts))
+    prob = PROBLEMS[name]()
+    plan, orc = _plan(prob), Oracle(prob)
+    monkeypatch.delenv("SAILOR_UNIT_PARTS")
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        cheapest = orc.best(objective=MIN_COST, n_threads=THREADS)
+        for objective, bound in ((MAX_THROUGHPUT, None), (MIN_COST, None),
+                                 (MAX_THROUGHPUT, 1.3 * cheapest.cost)):
+            check_result(plan.best_plan(objective=objective, bound=bound, stream=stream),
+                         orc.best(objective=objective, bound=bound, n_threads=THREADS), orc)
+            for k in (5, 64, 300):
+                check_topk(plan.topk(k, objective=objective, bound=bound, stream=stream),
+                           orc.topk(k, objective=objective, bound=bound, n_threads=THREADS), objective)
+    finally:
+        plan.destroy()
