@@ -98,6 +98,7 @@ struct sailor_plan {
   bool have_hdr = false;
   int32_t *d_avail = nullptr;
   int32_t *h_avail = nullptr;      // pinned staging of the availability table
+  const int32_t *h_avail_dev = nullptr;  // the same memory as the device addresses it
   bool avail_dirty = false;        // h_avail is newer than the device copy
   bool upload_pending = false;     // an asynchronous upload from h_avail was enqueued
   hipEvent_t ev_upload = nullptr;
@@ -445,9 +446,9 @@ unsigned quota_grid(const DevPlan &d) {
 // the quota table from it.
 sailor_status refresh_avail(sailor_plan *pl, hipStream_t st) {
   if (!pl->avail_dirty) return SAILOR_OK;
-  HIP_TRY(hipMemcpyAsync(pl->d_avail, pl->h_avail, pl->dev.ZGr * sizeof(int32_t),
-                         hipMemcpyHostToDevice, st));
-  k_quota_table<<<quota_grid(pl->dev), 256, 0, st>>>(pl->dev);
+  // the kernel reads the new table from the pinned staging buffer and leaves a copy on the
+  // device (no separate upload in front of it)
+  k_quota_table<<<quota_grid(pl->dev), 256, 0, st>>>(pl->dev, pl->h_avail_dev, pl->d_avail);
   HIP_TRY(hipEventRecord(pl->ev_upload, st));
   pl->upload_pending = true;
   pl->avail_dirty = false;
@@ -739,6 +740,11 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   CREATE_TRY(hipMemcpy(pl->d_avail, p->avail, ZGr * sizeof(int32_t), hipMemcpyHostToDevice));
   d.avail = pl->d_avail;
   CREATE_TRY(hipHostMalloc(reinterpret_cast<void **>(&pl->h_avail), ZGr * sizeof(int32_t), 0));
+  {
+    void *dev_view = nullptr;
+    CREATE_TRY(hipHostGetDevicePointer(&dev_view, pl->h_avail, 0));
+    pl->h_avail_dev = static_cast<const int32_t *>(dev_view);
+  }
   CREATE_TRY(hipEventCreateWithFlags(&pl->ev_upload, hipEventDisableTiming));
   d.P_max = 0;
   for (int ip = 0; ip < p->n_pp; ++ip) d.P_max = std::max(d.P_max, (int)p->pp_values[ip]);
@@ -836,7 +842,7 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   for (hipEvent_t &e : pl->ev) CREATE_TRY(hipEventCreate(&e));
 
   k_init_counters<<<1, 64>>>(pl->counters, 2 * CNT_COUNT);
-  k_quota_table<<<quota_grid(d), 256>>>(d);
+  k_quota_table<<<quota_grid(d), 256>>>(d, d.avail, nullptr);
   k_small_tables<<<1, 256>>>(d);
   k_stage_tables<<<(unsigned)RS, 128>>>(d, sa);
   k_shape_agg<<<(unsigned)NS, 256>>>(d);

@@ -337,12 +337,17 @@ __device__ __forceinline__ void acc_finish(const Acc &p, const LaneC &lc, float 
 // A pool that is a pair of types gives half of the replicas from each (an even number of
 // them); qh serves plans whose segments draw on one real pool together: x half-GPUs per
 // replica of the plan fit the real pool for the degrees whose bit is set.
-__global__ void k_quota_table(DevPlan pl) {
+__global__ void k_quota_table(DevPlan pl, const int32_t *avail, int32_t *avail_copy) {
+  // avail: the table to build from -- pl.avail, or a newer one in host-mapped memory, which
+  // is then also copied to avail_copy (= pl.avail) for the kernels that read it later; that
+  // saves a separate upload in front of this kernel
+  if (avail_copy && blockIdx.x == 0)
+    for (int r = threadIdx.x; r < pl.ZGr; r += blockDim.x) avail_copy[r] = avail[r];
   const int n = (pl.W_max + 1) * pl.ZG;
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
     const int p = i % pl.ZG, w = i / pl.ZG;
     const int x = pl.xt[p % pl.GX], ga = x & 255, gb = x >> 8, z = p / pl.GX;
-    const int64_t avail_a = pl.avail[z * pl.G + ga], avail_b = pl.avail[z * pl.G + gb];
+    const int64_t avail_a = avail[z * pl.G + ga], avail_b = avail[z * pl.G + gb];
     uint32_t bits = 0;
     for (int d = 0; d < pl.DP; ++d) {
       const int64_t D = pl.dpv[d];
@@ -356,7 +361,7 @@ __global__ void k_quota_table(DevPlan pl) {
   const int nh = (2 * pl.W_max + 1) * pl.ZGr;
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < nh; i += gridDim.x * blockDim.x) {
     const int r = i % pl.ZGr, x = i / pl.ZGr;
-    const int64_t avail2 = 2 * (int64_t)pl.avail[r];
+    const int64_t avail2 = 2 * (int64_t)avail[r];
     uint32_t bits = 0;
     for (int d = 0; d < pl.DP; ++d)
       if ((int64_t)x * pl.dpv[d] <= avail2) bits |= 1u << d;
