@@ -567,11 +567,21 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
   };
 
   if (t_all) HIP_TRY(hipEventRecord(pl->ev[0], st));
+  if (best) {
+    // the scan itself lists the units that can hold a plan within the tie band of the
+    // minimum (a superset: see ScanArgs), so the collect pass visits a handful of units
+    // instead of asking every unit's workgroups
+    sa.band = (float)(1.0 + kTieTol) + 3.0f * kEvalEps;
+    sa.near_list = pl->ulist;
+    sa.near_band = sa.band;
+  }
   launch_units<MODE_SCAN>(pl, obj, has_bound, sa, st, t_scan ? pl->ev[3] : nullptr,
                           t_scan ? pl->ev[1] : nullptr);
+  sa.near_list = nullptr;
   if (best) {
     sa.tau_src = cnt + CNT_GMIN;
-    sa.band = (float)(1.0 + kTieTol) + 3.0f * kEvalEps;
+    sa.ulist = pl->ulist;
+    sa.n_sub = kListSub;
   } else {
     // an upper bound of the k-th smallest key: the k-th smallest unit minimum
     // (the same kernel lists the units whose loose minimum lies under it)

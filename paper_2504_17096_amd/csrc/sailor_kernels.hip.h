@@ -417,6 +417,10 @@ struct ScanArgs {
   int ignore_quota;         // SCAN at plan creation: treat every pool as large enough
   const uint32_t *ulist;    // COLLECT, optional: the units to visit and, in counters[CNT_NLIST],
                             // how many; the grid then strides over the list
+  uint32_t *near_list;      // SCAN, optional (best plan): units whose loose minimum lies within
+  float near_band;          // near_band of the smallest strict key seen so far are appended
+                            // here (count in counters[CNT_NLIST]); the running minimum only
+                            // falls, so the list holds every unit within the band of the final one
 };
 
 enum Counter { CNT_SURV = 0, CNT_REF = 1, CNT_FEAS = 2, CNT_GMIN = 3, CNT_TAU0 = 4, CNT_TAU1 = 5,
@@ -738,6 +742,11 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
       const uint32_t seen = __hip_atomic_load(&a.counters[CNT_GMIN], __ATOMIC_RELAXED,
                                               __HIP_MEMORY_SCOPE_AGENT);
       if (__float_as_uint(ms) < seen) atomicMin(&a.counters[CNT_GMIN], __float_as_uint(ms));
+      if (a.near_list && ml < kPosInf) {
+        // (a stale `seen` is larger than the true running minimum and only lengthens the list)
+        const float running = fminf(__uint_as_float(seen), ms);
+        if (ml <= running * a.near_band) a.near_list[atomicAdd(&a.counters[CNT_NLIST], 1u)] = uidx;
+      }
       if (a.ucost) a.ucost[uidx] = (float)(wall_clock64() - t_begin);
     }
   }
