@@ -29,11 +29,13 @@ FLOPS_PER_STAGE, FLOPS_EPILOGUE = 12.0, 15.0
 PEAK_FP32_VECTOR_TFLOPS = 157.3
 # HBM bytes per scan launch on this workload from rocprofv3 FETCH_SIZE / WRITE_SIZE, each
 # scaled by a 1 GiB copy of the same run (profiles/k_units_scan_cfg4_counters.md); set to
-# None whenever k_units changes after the counters were taken
-SCAN_TRAFFIC_BYTES = 5.51e6
+# None whenever k_units changes after the counters were taken (how many scan units are cut
+# into parts depends on times measured at plan creation, so the figures move by a percent or
+# two between runs)
+SCAN_TRAFFIC_BYTES = 5.79e6
 # VALU wave-instructions the scan executes per launch on this workload (SQ_INSTS_VALU, same
 # file and same rule); each occupies one of the 1 024 SIMDs for 4 cycles at 2.4 GHz
-SCAN_VALU_WAVE_INSTS = 1.064e7
+SCAN_VALU_WAVE_INSTS = 1.081e7
 SIMDS, CLOCK_HZ, CYCLES_PER_WAVE_INST = 1024, 2.4e9, 4
 # steps of the timed region between two whose scan dispatch carries start / stop events
 EVENT_EVERY = 8
