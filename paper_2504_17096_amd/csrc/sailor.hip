@@ -718,7 +718,7 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
   d.mg_g = magic((uint32_t)d.GX);
   d.mg_mbtp = magic((uint32_t)(d.MB * d.TP));
   d.mg_mbtpdp = magic((uint32_t)(d.MB * d.TP * d.DP));
-  pl->eval_lds_bytes = (size_t)3 * d.TP * d.ZG * d.MB * sizeof(Rec) +
+  pl->eval_lds_bytes = (size_t)3 * d.TP * ((size_t)d.ZG * d.MB + 1) * sizeof(Rec) +
                        (size_t)d.MB * d.Z * d.Z * sizeof(float4) +
                        (size_t)3 * d.TP * d.MB * d.DP * sizeof(uint64_t) +
                        (size_t)3 * d.TP * d.ZG * sizeof(uint32_t) +

@@ -1591,13 +1591,26 @@ struct PoolInfo {   // per pool, staged in LDS (a pair of types: the tighter of 
 // 24-bit multiply (full rate, unlike the 32-bit one): every product below is a table offset
 __device__ __forceinline__ uint32_t mul24(uint32_t a, uint32_t b) { return __umul24(a, b); }
 
+// A segment record of the range evaluation, kept in LDS as two 16-byte halves in arrays of
+// their own: the records a wave reads together then lie 16 bytes apart, not 32, and collide
+// on half as many banks.
+__device__ __forceinline__ Rec rec_of(const float4 *lo, const float4 *hi, uint32_t i) {
+  const float4 a = lo[i], b = hi[i];
+  Rec r;
+  r.sumT = a.x; r.tF = a.y; r.tL = a.z; r.tI = a.w;
+  r.syncb = b.x; r.upd = b.y; r.pricen = b.z;
+  r.bits = 0u;  // validity comes from the masks here
+  return r;
+}
+
 template <int S, bool PST, bool MIXED>
 __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs &a,
                                                const EvalUnit &u, const ShapeRec &sh,
-                                               const Rec *rec, const float4 *pair,
-                                               const uint32_t *qm, const uint64_t *need,
-                                               const PoolInfo *pinfo, const uint32_t *odec,
-                                               const int32_t *vals, const uint64_t *isect) {
+                                               const float4 *rec_lo, const float4 *rec_hi,
+                                               const float4 *pair, const uint32_t *qm,
+                                               const uint64_t *need, const PoolInfo *pinfo,
+                                               const uint32_t *odec, const int32_t *vals,
+                                               const uint64_t *isect) {
   const uint32_t ZG = pl.ZG, MB = pl.MB, TP = pl.TP, DP = pl.DP, Z = pl.Z;
   const uint32_t inner = pl.inner;
   const uint64_t last = a.first + a.count;
@@ -1610,7 +1623,8 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
   uint64_t *const o_mem = a.mem ? a.mem + ubase : nullptr;
   uint32_t *const o_mask = a.mask ? a.mask + ubase : nullptr;
   const bool whole = u.idx_lo >= a.first && u.idx_lo + (uint64_t)u.o_cnt * inner <= last;  // uniform
-  const uint32_t seg_rec = mul24(mul24(TP, ZG), MB), seg_need = mul24(mul24(TP, MB), DP),
+  const uint32_t tp_rec = mul24(ZG, MB) + 1u;  // records per (segment, tp) slice, one unused
+  const uint32_t seg_rec = mul24(TP, tp_rec), seg_need = mul24(mul24(TP, MB), DP),
                  seg_qm = mul24(TP, ZG);
   for (uint32_t in = threadIdx.x; in < inner; in += blockDim.x) {
     const uint32_t a1 = fast_div(in, pl.mg_mbtpdp), rem = in - mul24(a1, MB * TP * DP);
@@ -1623,15 +1637,15 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
     lc.dph = pl.dph_f[dp];
     lc.xb = pl.xb_f[mb];
     // this lane's slices of the staged tables; segment j with tp index k on pool p:
-    const Rec *recl = rec + mb;                      // [((j * TP + k) * ZG + p) * MB]
+    const float4 *recl_lo = rec_lo + mb, *recl_hi = rec_hi + mb;  // [(j * TP + k) * tp_rec + p * MB]
     const uint64_t *needl = need + mul24(mb, DP) + dp;  // [(j * TP + k) * MB * DP]
     const float4 *pairm = pair + mul24(mb, Z * Z);   // transfers of this microbatch size
     // with one tp per plan the later segments use this lane's tp: their slices are fixed
-    const uint32_t tpo_rec = mul24(mul24(tp, ZG), MB), tpo_need = mul24(mul24(tp, MB), DP),
+    const uint32_t tpo_rec = mul24(tp, tp_rec), tpo_need = mul24(mul24(tp, MB), DP),
                    tpo_qm = mul24(tp, ZG);
     // segment 1 does not change while the outer digits advance
     const uint32_t p0 = a1;
-    const Rec r0 = recl[tpo_rec + mul24(p0, MB)];
+    const Rec r0 = rec_of(recl_lo, recl_hi, tpo_rec + mul24(p0, MB));
     const Acc A0 = acc_begin(r0);
     const PoolInfo i0 = pinfo[p0];
     const uint64_t need0 = needl[tpo_need], mem0 = need0 + i0.res;
@@ -1663,10 +1677,10 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
           uint32_t p1 = p0 + 1 + r2;
           if (p1 >= ZG) p1 -= ZG;
           // uniform offsets when the segment has its own tp digit, this lane's otherwise
-          const uint32_t o_rec = seg_rec + (PST ? mul24(mul24(t1, ZG), MB) : tpo_rec);
+          const uint32_t o_rec = seg_rec + (PST ? mul24(t1, tp_rec) : tpo_rec);
           const uint32_t o_need = seg_need + (PST ? mul24(mul24(t1, MB), DP) : tpo_need);
           const uint32_t o_qm = seg_qm + (PST ? mul24(t1, ZG) : tpo_qm);
-          const Rec r1 = recl[o_rec + mul24(p1, MB)];
+          const Rec r1 = rec_of(recl_lo, recl_hi, o_rec + mul24(p1, MB));
           const PoolInfo i1 = pinfo[p1];
           const uint32_t z1 = i1.meta & 0xFFu;
           const uint64_t need1 = needl[o_need], mem1 = need1 + i1.res;
@@ -1685,10 +1699,10 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
             const uint32_t t2 = PST ? (od >> 15) : tp;
             uint32_t p2 = p1 + 1 + r3;
             if (p2 >= ZG) p2 -= ZG;
-            const uint32_t o_rec2 = 2 * seg_rec + (PST ? mul24(mul24(t2, ZG), MB) : tpo_rec);
+            const uint32_t o_rec2 = 2 * seg_rec + (PST ? mul24(t2, tp_rec) : tpo_rec);
             const uint32_t o_need2 = 2 * seg_need + (PST ? mul24(mul24(t2, MB), DP) : tpo_need);
             const uint32_t o_qm2 = 2 * seg_qm + (PST ? mul24(t2, ZG) : tpo_qm);
-            const Rec r2r = recl[o_rec2 + mul24(p2, MB)];
+            const Rec r2r = rec_of(recl_lo, recl_hi, o_rec2 + mul24(p2, MB));
             const PoolInfo i2 = pinfo[p2];
             const uint64_t need2 = needl[o_need2], mem2 = need2 + i2.res;
             if ((int64_t)need2 > i2.room) mask |= 1u;
@@ -1731,8 +1745,11 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
   const EvalUnit u = units[unit0 + blockIdx.x];
   const ShapeRec sh = pl.shapes[u.shape];
   const int ZG = pl.ZG, G = pl.GX, MB = pl.MB, TP = pl.TP, DP = pl.DP, Z = pl.Z, S = sh.s;
-  Rec *rec = reinterpret_cast<Rec *>(lds_raw);                           // [3][TP][ZG][MB]
-  float4 *pair = reinterpret_cast<float4 *>(rec + 3 * TP * ZG * MB);     // [MB][Z][Z]
+  // [3][TP][ZG * MB + 1]: a (segment, tp) slice is one record longer than its contents, so
+  // that the slices of the tp values a wave reads together do not start on the same LDS banks
+  float4 *rec_lo = reinterpret_cast<float4 *>(lds_raw);  // the records' two halves (see rec_of)
+  float4 *rec_hi = rec_lo + 3 * TP * (ZG * MB + 1);
+  float4 *pair = rec_hi + 3 * TP * (ZG * MB + 1);         // [MB][Z][Z]
   PoolInfo *pinfo = reinterpret_cast<PoolInfo *>(pair + MB * Z * Z);     // [ZG]
   uint64_t *need = reinterpret_cast<uint64_t *>(pinfo + ZG);             // [3][TP][MB][DP]
   uint64_t *isect = need + 3 * TP * MB * DP;                             // [ZG]
@@ -1785,13 +1802,17 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
     const int mb = i % MB, p = (i / MB) % ZG, k = (i / (MB * ZG)) % TP, seg = i / (MB * ZG * TP);
     const int g = p % G, z = p / G;
     const size_t sl = agg_slot(pl, u.shape, k, seg);
-    rec[i] = make_rec(pl.ta[(sl * G + g) * MB + mb], pl.syncz[sl * Z + z], pl.upd[sl * G + g],
-                      pl.price_f[g], pl.tsec_f[(mb * Z + z) * Z + z],
-                      seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]), vals[DP + k], 0u);
+    const Rec r =
+        make_rec(pl.ta[(sl * G + g) * MB + mb], pl.syncz[sl * Z + z], pl.upd[sl * G + g],
+                 pl.price_f[g], pl.tsec_f[(mb * Z + z) * Z + z],
+                 seg == 0 ? sh.n[0] : (seg == 1 ? sh.n[1] : sh.n[2]), vals[DP + k], 0u);
+    const int at = i + seg * TP + k;  // (one unused record behind every slice)
+    rec_lo[at] = make_float4(r.sumT, r.tF, r.tL, r.tI);
+    rec_hi[at] = make_float4(r.syncb, r.upd, r.pricen, 0.f);
   }
   __syncthreads();
 #define SAILOR_ROWS(S_, PST_) \
-  eval_rows_body<S_, PST_, MIXED>(pl, a, u, sh, rec, pair, qm, need, pinfo, odec, vals, isect)
+  eval_rows_body<S_, PST_, MIXED>(pl, a, u, sh, rec_lo, rec_hi, pair, qm, need, pinfo, odec, vals, isect)
   if (S == 1) SAILOR_ROWS(1, false);
   else if (!pl.pst) { if (S == 2) SAILOR_ROWS(2, false); else SAILOR_ROWS(3, false); }
   else { if (S == 2) SAILOR_ROWS(2, true); else SAILOR_ROWS(3, true); }
