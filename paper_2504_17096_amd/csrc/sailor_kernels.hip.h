@@ -1656,6 +1656,9 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
     const uint32_t z0 = i0.meta & 0xFFu;
     const int64_t D = vals[dp];  // value lists staged in LDS: [DP] dp, then [TP] tp
     const int64_t gpus0 = (int64_t)sh.n[0] * vals[DP + tp];
+    // with one tp per plan the bytes segments 2 and 3 need do not change with the outer digits
+    const uint64_t need1_lane = (!PST && S >= 2) ? needl[seg_need + tpo_need] : 0;
+    const uint64_t need2_lane = (!PST && S == 3) ? needl[2 * seg_need + tpo_need] : 0;
     uint32_t off = in;           // o * inner + in
     for (uint32_t o = 0; o < u.o_cnt; ++o, off += inner) {
       if (!whole) {
@@ -1683,7 +1686,7 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
           const Rec r1 = rec_of(recl_lo, recl_hi, o_rec + mul24(p1, MB));
           const PoolInfo i1 = pinfo[p1];
           const uint32_t z1 = i1.meta & 0xFFu;
-          const uint64_t need1 = needl[o_need], mem1 = need1 + i1.res;
+          const uint64_t need1 = PST ? needl[o_need] : need1_lane, mem1 = need1 + i1.res;
           if ((int64_t)need1 > i1.room) mask |= 1u;
           if (i1.meta & (1u << (8 + t1))) mask |= 8u;
           peak = mem1 > peak ? mem1 : peak;
@@ -1704,7 +1707,7 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
             const uint32_t o_qm2 = 2 * seg_qm + (PST ? mul24(t2, ZG) : tpo_qm);
             const Rec r2r = rec_of(recl_lo, recl_hi, o_rec2 + mul24(p2, MB));
             const PoolInfo i2 = pinfo[p2];
-            const uint64_t need2 = needl[o_need2], mem2 = need2 + i2.res;
+            const uint64_t need2 = PST ? needl[o_need2] : need2_lane, mem2 = need2 + i2.res;
             if ((int64_t)need2 > i2.room) mask |= 1u;
             if (i2.meta & (1u << (8 + t2))) mask |= 8u;
             peak = mem2 > peak ? mem2 : peak;
