@@ -795,7 +795,7 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stri
   // memory: the buffers hold cap values, so the first value of every thread is requested
   // together with the count and taken as +inf afterwards if it lies beyond it (requesting
   // all kKept that way cost more than it saved when the list was short).
-  constexpr int kSelectKeep = 4;
+  constexpr int kSelectKeep = 8;
   constexpr uint32_t kKept = kSelectKeep * 1024;
   uint32_t xr[kSelectKeep];
   float lr[kSelectKeep];
@@ -826,6 +826,7 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stri
     if (s_done) break;  // uniform
 #pragma unroll
     for (int q = 0; q < kSelectKeep; ++q) {
+      if ((uint32_t)q * 1024u >= n) break;  // uniform: nothing is kept beyond the count
       const uint32_t x = xr[q];
       const bool match = x < 0x7f800000u && (pass == 0 || (x >> (sh + wd)) == prefix);
       const uint32_t bin = (x >> sh) & ((1u << wd) - 1);
@@ -840,10 +841,19 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stri
       if (lane == __ffsll((long long)m) - 1) atomicAdd(&hist[bin0], (uint32_t)__popcll(ms));
       if (match && !same) atomicAdd(&hist[bin], 1u);
     }
-    for (uint32_t i = t + kKept; i < n; i += blockDim.x) {
-      const uint32_t x = __float_as_uint(vals[(size_t)i * stride_words]);
-      const bool match = x < 0x7f800000u && (pass == 0 || (x >> (sh + wd)) == prefix);
-      if (match) atomicAdd(&hist[(x >> sh) & ((1u << wd) - 1)], 1u);
+    for (uint32_t i0 = t + kKept; i0 < n; i0 += 4u * blockDim.x) {  // four loads in flight
+      uint32_t x4[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t i = i0 + q * blockDim.x;
+        x4[q] = i < n ? __float_as_uint(vals[(size_t)i * stride_words]) : 0x7f800000u;
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t x = x4[q];
+        const bool match = x < 0x7f800000u && (pass == 0 || (x >> (sh + wd)) == prefix);
+        if (match) atomicAdd(&hist[(x >> sh) & ((1u << wd) - 1)], 1u);
+      }
     }
     __syncthreads();
     // inclusive prefix sum over the bins, two bins per thread
