@@ -1242,8 +1242,8 @@ constexpr uint32_t kRankLds = 1024;  // records the one-workgroup form of k_rank
 
 // Top-k: the rank of every valid re-evaluated candidate in ascending (key, index) order.
 // Launched as one workgroup of kRankLds threads when few records are expected (small k):
-// keys and indices go to LDS, every thread counts the predecessors of one record, and the
-// k first are copied to host-mapped memory in rank order.  Otherwise (several workgroups,
+// keys and indices go to LDS, the threads share out the counting of each record's
+// predecessors, and the k first are copied to host-mapped memory in rank order.  Otherwise (several workgroups,
 // or more than kRankLds records) one wave per candidate: its lanes count, in strides over
 // the list, the entries that precede it; ranks below k go to a device-side list, which the
 // workgroup that finishes last copies to host-mapped memory in one coalesced pass
