@@ -97,3 +97,22 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libsailor.so")
     with pytest.raises(ImportError):
         binding.load_library()
+
+
+def test_product_sources_do_not_reach_into_the_oracle():
+    # the checker and the product share nothing but the seeded input generators
+    import pathlib
+    import re
+    root = pathlib.Path(__file__).resolve().parent.parent
+    pkg = root / "paper_2504_17096_amd"
+    sources = list(pkg.glob("*.py")) + [f for f in (pkg / "csrc").iterdir() if f.is_file()]
+    sources.append(root / "include" / "sailor.h")
+    assert len(sources) >= 7
+    for f in sources:
+        text = f.read_text()
+        assert not re.search(r"^\s*(from|import)\s+oracle\b", text, re.M), f
+        assert "sailor_oracle" not in text and "oracle/" not in text, f
+    for f in (root / "oracle").iterdir():
+        if f.suffix in (".py", ".c", ".h"):
+            text = f.read_text()
+            assert "paper_2504_17096_amd" not in text and "sailor.h" not in text, f
