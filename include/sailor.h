@@ -226,6 +226,9 @@ sailor_status sailor_best_plan(sailor_plan *plan, sailor_objective objective,
 
 /* The k best valid plans in ascending (key, index) order; out (host) has room for k
  * entries, *n_found receives how many exist (<= k).  1 <= k <= SAILOR_MAX_K.
+ * Keys, and the constrained quantity against the bound, are the fp64 values reported in out:
+ * plans whose values agree to the last few bits (or a value that equals the bound to the
+ * last bit) are ordered (decided) by those bits, which depend on the order of the additions.
  * Waits like sailor_best_plan.  SAILOR_ENOFEASIBLE (with *n_found = 0) when none is valid. */
 sailor_status sailor_topk(sailor_plan *plan, sailor_objective objective,
                           const sailor_constraint *constraint, int32_t k, sailor_result *out,
