@@ -533,7 +533,7 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
     ra.band = 1.0f + 3.0f * kEvalEps;
     if (!best) {
       // the exact k-th smallest fp32 key among the survivors, then only its neighbourhood
-      k_select_kth<<<1, 1024, 0, st>>>(&pl->surv[0].key, (int)(sizeof(SurvRec) / 4),
+      k_select_kth<256><<<1, 256, 0, st>>>(&pl->surv[0].key, (int)(sizeof(SurvRec) / 4),
                                        cnt + CNT_SURV, pl->surv_cap, k, cnt + CNT_TAU1, nullptr,
                                        0u, 0.f, nullptr, nullptr);
       ra.tau_src = cnt + CNT_TAU1;
@@ -586,7 +586,7 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
     // an upper bound of the k-th smallest key: the k-th smallest unit minimum
     // (the same kernel lists the units whose loose minimum lies under it)
     sa.band = 1.0f + 3.0f * kEvalEps;
-    k_select_kth<<<1, 1024, 0, st>>>(pl->umin_s, 1, nullptr, n_units, k, cnt + CNT_TAU0,
+    k_select_kth<1024><<<1, 1024, 0, st>>>(pl->umin_s, 1, nullptr, n_units, k, cnt + CNT_TAU0,
                                      pl->umin_l, n_units, sa.band, pl->ulist, cnt + CNT_NLIST);
     sa.tau_src = cnt + CNT_TAU0;
     sa.ulist = pl->ulist;

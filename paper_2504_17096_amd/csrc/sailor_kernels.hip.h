@@ -776,18 +776,21 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
 
 // Radix select (11 + 11 + 10 bits) of the k-th smallest non-negative float among
 // n = min(*count, cap) values read with a stride; +inf entries are ignored and fewer than
-// k finite values yield +inf.  One workgroup of 1024 threads.  The result's bit pattern
+// k finite values yield +inf.  One workgroup of THREADS threads (1024 for thousands of values,
+// 256 for a short list: fewer waves make the passes' barriers cheaper).  The result's bit pattern
 // goes to *out.
 // With a list: also writes the positions i < n_list_src whose list_src[i] is finite and at
 // most result * band to list, and their number to *list_count (in no particular order).
-__global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stride_words,
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void k_select_kth(const float *vals, int stride_words,
                                                      const uint32_t *count, uint32_t cap,
                                                      uint32_t k, uint32_t *out,
                                                      const float *list_src, uint32_t n_list_src,
                                                      float band, uint32_t *list,
                                                      uint32_t *list_count) {
+  constexpr int kBinsPerThread = 2048 / THREADS, kWaves = THREADS / 64;
   __shared__ uint32_t hist[2048];
-  __shared__ uint32_t wsum[16];
+  __shared__ uint32_t wsum[kWaves];
   __shared__ uint32_t s_prefix, s_k, s_done, s_nlist;
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
   // The first kSelectKeep values of every thread stay in registers for all three passes.
@@ -796,13 +799,13 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stri
   // together with the count and taken as +inf afterwards if it lies beyond it (requesting
   // all kKept that way cost more than it saved when the list was short).
   constexpr int kSelectKeep = 8;
-  constexpr uint32_t kKept = kSelectKeep * 1024;
+  constexpr uint32_t kKept = kSelectKeep * THREADS;
   uint32_t xr[kSelectKeep];
   float lr[kSelectKeep];
-  const uint32_t n_early = count ? min(cap, 1024u) : cap;
+  const uint32_t n_early = count ? min(cap, (uint32_t)THREADS) : cap;
 #pragma unroll
   for (int q = 0; q < kSelectKeep; ++q) {
-    const uint32_t i = t + q * 1024u;
+    const uint32_t i = t + q * (uint32_t)THREADS;
     xr[q] = i < n_early ? __float_as_uint(vals[(size_t)i * stride_words]) : 0x7f800000u;
     lr[q] = (list && i < n_list_src) ? list_src[i] : kPosInf;
   }
@@ -811,22 +814,22 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stri
   if (count) {
 #pragma unroll
     for (int q = 1; q < kSelectKeep; ++q) {
-      const uint32_t i = t + q * 1024u;
+      const uint32_t i = t + q * (uint32_t)THREADS;
       if (i < n) xr[q] = __float_as_uint(vals[(size_t)i * stride_words]);
     }
   }
   if (t == 0) { s_prefix = 0; s_k = k; s_done = 0; s_nlist = 0; }
   const int shifts[3] = {21, 10, 0}, widths[3] = {11, 11, 10};
   for (int pass = 0; pass < 3; ++pass) {
-    hist[t] = 0;
-    hist[t + 1024] = 0;
+#pragma unroll
+    for (int b = 0; b < kBinsPerThread; ++b) hist[t + b * THREADS] = 0;
     __syncthreads();
     const int sh = shifts[pass], wd = widths[pass];
     const uint32_t prefix = s_prefix, kk = s_k;
     if (s_done) break;  // uniform
 #pragma unroll
     for (int q = 0; q < kSelectKeep; ++q) {
-      if ((uint32_t)q * 1024u >= n) break;  // uniform: nothing is kept beyond the count
+      if ((uint32_t)q * (uint32_t)THREADS >= n) break;  // uniform: nothing is kept beyond the count
       const uint32_t x = xr[q];
       const bool match = x < 0x7f800000u && (pass == 0 || (x >> (sh + wd)) == prefix);
       const uint32_t bin = (x >> sh) & ((1u << wd) - 1);
@@ -856,9 +859,14 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stri
       }
     }
     __syncthreads();
-    // inclusive prefix sum over the bins, two bins per thread
-    const uint32_t h0 = hist[2 * t], h1 = hist[2 * t + 1];
-    uint32_t incl = h0 + h1;
+    // inclusive prefix sum over the bins, kBinsPerThread consecutive bins per thread
+    uint32_t h[kBinsPerThread], mine = 0;
+#pragma unroll
+    for (int b = 0; b < kBinsPerThread; ++b) {
+      h[b] = hist[kBinsPerThread * t + b];
+      mine += h[b];
+    }
+    uint32_t incl = mine;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
       const uint32_t v = __shfl_up(incl, off);
@@ -869,13 +877,16 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stri
     uint32_t before = 0;
     for (int w = 0; w < wv; ++w) before += wsum[w];
     incl += before;
-    const uint32_t excl = incl - (h0 + h1);
+    uint32_t excl = incl - mine;
     if (excl < kk && kk <= incl) {  // exactly one thread: the k-th value lies in its bins
-      const uint32_t bin = (kk <= excl + h0) ? 2 * t : 2 * t + 1;
-      s_prefix = (prefix << wd) | bin;
-      s_k = kk - (bin == 2u * t ? excl : excl + h0);
+      int bin = 0;
+#pragma unroll
+      for (int b = 0; b < kBinsPerThread - 1; ++b)  // (constant subscripts: h stays in registers)
+        if (bin == b && excl + h[b] < kk) { excl += h[b]; bin = b + 1; }
+      s_prefix = (prefix << wd) | (uint32_t)(kBinsPerThread * t + bin);
+      s_k = kk - excl;
     }
-    if (t == 1023 && incl < kk) { s_done = 1; s_prefix = 0x7f800000u; }
+    if (t == THREADS - 1 && incl < kk) { s_done = 1; s_prefix = 0x7f800000u; }
     __syncthreads();
   }
   if (t == 0) *out = s_prefix;
@@ -884,7 +895,7 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float *vals, int stri
     const float tau = __uint_as_float(s_prefix) * band;
 #pragma unroll
     for (int q = 0; q < kSelectKeep; ++q) {
-      const uint32_t i = t + q * 1024u;
+      const uint32_t i = t + q * (uint32_t)THREADS;
       if (lr[q] < kPosInf && lr[q] <= tau) list[atomicAdd(&s_nlist, 1u)] = i;
     }
     for (uint32_t i = t + kKept; i < n_list_src; i += blockDim.x) {
