@@ -95,6 +95,7 @@ enum {
   SAILOR_MAX_TP = 8,
   SAILOR_MAX_DP = 24,
   SAILOR_MAX_STAGES = 256,
+  SAILOR_MAX_SHAPES = 1 << 20, /* (layer split, cut points) combinations over all pp */
   SAILOR_MAX_BW_COEF = 8, /* coefficients of a link's bandwidth polynomial */
   SAILOR_MAX_K = 4096     /* largest k of sailor_topk */
 };

@@ -143,6 +143,8 @@ int extended_types(const sailor_problem *p) {
   return p->mixed_types ? p->n_types + p->n_types * (p->n_types - 1) / 2 : p->n_types;
 }
 
+uint64_t n_cut_choices(int P, int s);
+
 sailor_status validate(const sailor_problem *p) {
   if (!p) return SAILOR_EINVAL;
   if (p->n_layers < 1 || p->n_types < 1 || p->n_zones < 1) return SAILOR_EINVAL;
@@ -178,6 +180,16 @@ sailor_status validate(const sailor_problem *p) {
       }
       if (sum != L) return SAILOR_EINVAL;
     }
+  }
+  {  // shapes (layer split x cut points) carry per-shape tables: keep their number bounded
+    uint64_t n_shapes = 0;
+    for (int ip = 0; ip < p->n_pp; ++ip)
+      for (int s = 1; s <= p->max_segments; ++s) {
+        const int P = p->pp_values[ip];
+        if (s > P || (s == 3 && P > p->seg3_max_pp)) continue;
+        n_shapes += n_cut_choices(P, s) * (uint64_t)p->n_partitions[ip];
+        if (n_shapes > (uint64_t)SAILOR_MAX_SHAPES) return SAILOR_EINVAL;
+      }
   }
   // the quota table has one row per GPU count a replica can take from a pool
   if ((int64_t)p->pp_values[p->n_pp - 1] * p->tp_values[p->n_tp - 1] > (1 << 20)) return SAILOR_EINVAL;
@@ -624,7 +636,8 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
     uint32_t nl = 0, ns = 0;
     for (int it = 0; it < 200 && !found; ++it) {
       double t;
-      if (hi == 0.0) t = (it == 0) ? lo * (1.0 + 1e-6) : lo * 2.0 + 1e-300;  // doubling
+      // doubling (from the smallest normal float when the minimum key is zero)
+      if (hi == 0.0) t = (it == 0) ? lo * (1.0 + 1e-6) : std::max(lo * 2.0, 1.17549435e-38);
       else t = std::sqrt(lo * hi);                                            // bisecting
       if (!(t < 3.0e38)) break;
       tau = (float)t;
@@ -680,16 +693,20 @@ sailor_status sailor_plan_destroy(sailor_plan *pl) {
   return SAILOR_OK;
 }
 
-sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
+// The body of sailor_plan_create.  *track holds the plan while this function owns it, so that
+// the caller can release it when a container throws half-way.
+static sailor_status create_impl(const sailor_problem *p, sailor_plan **out, sailor_plan **track) {
   if (!out) return SAILOR_EINVAL;
   sailor_status rc = validate(p);
   if (rc != SAILOR_OK) return rc;
   sailor_plan *pl = new (std::nothrow) sailor_plan();
   if (!pl) return SAILOR_ENOMEM;
+  *track = pl;
   std::vector<int32_t> st_n, st_first;
   std::vector<uint8_t> st_flags;
   rc = build_space(p, pl, st_n, st_first, st_flags);
   if (rc != SAILOR_OK || pl->dev.N == 0) {
+    *track = nullptr;
     delete pl;
     return rc != SAILOR_OK ? rc : SAILOR_EINVAL;
   }
@@ -733,6 +750,7 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
     hipError_t e_ = (expr);                                                        \
     if (e_ != hipSuccess) {                                                        \
       std::fprintf(stderr, "sailor: %s failed: %s\n", #expr, hipGetErrorString(e_)); \
+      *track = nullptr;                                                            \
       sailor_plan_destroy(pl);                                                     \
       return e_ == hipErrorOutOfMemory ? SAILOR_ENOMEM : SAILOR_EDEVICE;           \
     }                                                                              \
@@ -957,8 +975,22 @@ sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
     ar.free_one(d_cost);
   }
 #undef CREATE_TRY
+  *track = nullptr;
   *out = pl;
   return SAILOR_OK;
+}
+
+sailor_status sailor_plan_create(const sailor_problem *p, sailor_plan **out) {
+  sailor_plan *half_built = nullptr;
+  try {  // no C++ exception crosses the C boundary
+    return create_impl(p, out, &half_built);
+  } catch (const std::bad_alloc &) {
+    if (half_built) sailor_plan_destroy(half_built);
+    return SAILOR_ENOMEM;
+  } catch (...) {
+    if (half_built) sailor_plan_destroy(half_built);
+    return SAILOR_EINVAL;
+  }
 }
 
 sailor_status sailor_plan_set_avail(sailor_plan *pl, const int32_t *avail) {

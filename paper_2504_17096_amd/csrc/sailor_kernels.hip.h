@@ -44,8 +44,10 @@ __device__ __forceinline__ double link_bw(const DevPlan &pl, int a, int b, doubl
   const double x = log2(bytes);
   double v = c[pl.n_bw_coef - 1];
   for (int k = pl.n_bw_coef - 2; k >= 0; --k) v = v * x + c[k];  // Horner
-  if (!(v < peak)) v = peak;
-  if (v < peak * 1e-3) v = peak * 1e-3;
+  // (ordered comparisons: the coefficients are validated finite and the device code is built
+  // without NaN support, so the limits must not lean on how a NaN compares)
+  if (v >= peak) v = peak;
+  if (v <= peak * 1e-3) v = peak * 1e-3;
   return v;
 }
 
@@ -1166,8 +1168,10 @@ __global__ __launch_bounds__(kRefineWaves * 64) void k_refine(DevPlan pl, Refine
                     r.mem, r.mask);
     if ((threadIdx.x & 63) == 0) {
       const uint32_t slot = atomicAdd(&a.counters[CNT_REF], 1u);
-      if (slot < a.ref_cap) a.ref[slot] = r;
-      if (r.mask == 0) atomicAdd(&a.counters[CNT_FEAS], 1u);
+      if (slot < a.ref_cap) {  // (a record that does not fit is counted in CNT_REF only: the
+        a.ref[slot] = r;       // host reports the overflow, the ranking sees what was stored)
+        if (r.mask == 0) atomicAdd(&a.counters[CNT_FEAS], 1u);
+      }
     }
   }
 }
@@ -1275,16 +1279,31 @@ __global__ __launch_bounds__(kRankLds) void k_rank_topk(const RefRec *ref, uint3
   // buffer holds ref_cap records, so the address is valid whatever the count turns out to be
   RefRec mine{};
   if (gridDim.x == 1 && threadIdx.x < ref_cap) mine = ref[threadIdx.x];
-  const uint32_t n = min(counters[CNT_REF], ref_cap);
-  const uint32_t f = counters[CNT_FEAS];  // valid records (requested with the count)
+  const uint32_t n_ref = counters[CNT_REF];
+  const uint32_t n = min(n_ref, ref_cap);
+  const uint32_t f = counters[CNT_FEAS];  // valid stored records (requested with the count)
+  const bool overflow = n_ref > ref_cap;  // uniform: the list is incomplete, nothing is ranked
   if (blockIdx.x == 0 && threadIdx.x < CNT_COUNT)
     next_counters[threadIdx.x] = counter_reset_value(threadIdx.x);  // for the next call
   if (blockIdx.x == 0 && threadIdx.x == 0) {
-    hdr->n_found = f < k ? f : k;
+    hdr->n_found = overflow ? 0u : (f < k ? f : k);
     hdr->surv_count = counters[CNT_SURV];
-    hdr->ref_count = counters[CNT_REF];
+    hdr->ref_count = n_ref;
     hdr->feasible_count = f;
     hdr->gmin_bits = counters[CNT_GMIN];
+  }
+  if (overflow) {  // the host turns ref_count > ref_cap into SAILOR_ENOMEM
+    if (gridDim.x == 1) {
+      if (threadIdx.x == 0) publish(hdr, seq);
+      return;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      __threadfence_system();
+      s_last = atomicAdd(done, 1u) == gridDim.x - 1 ? 1u : 0u;
+      if (s_last) publish(hdr, seq);
+    }
+    return;
   }
   if (gridDim.x == 1 && n <= kRankLds) {  // uniform
     const uint32_t t = threadIdx.x;

@@ -368,6 +368,32 @@ def test_small_scratch_makes_topk_search_for_a_tighter_threshold(torch_cuda):
         plan.destroy()
 
 
+def test_ties_that_overflow_the_re_evaluated_list_give_a_clean_error(torch_cuda):
+    # thousands of exact ties lie inside the rounding band of the k-th key; with room for only
+    # 40 re-evaluated records the call must report SAILOR_ENOMEM (and rank nothing), and work
+    # again once the room is back
+    from paper_2504_17096_amd.binding import SAILOR_ENOMEM, SailorError
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    p = make_problem(n_layers=4, n_types=1, n_zones=16, pp_list=[4], max_segments=3,
+                     seg3_max_pp=4, mb_list=(1,), tp_list=(1,), dp_list=(1, 2), global_batch=8,
+                     p2p=1_000_000, bw=1e9, avail=64)
+    plan, orc = _plan(p), Oracle(p)
+    try:
+        plan.set_scratch(1 << 16, 40)
+        for k in (64, 200):  # ranked by one workgroup / by several
+            with pytest.raises(SailorError) as ei:
+                plan.topk(k, stream=stream)
+            assert ei.value.status == SAILOR_ENOMEM
+        with pytest.raises(SailorError) as ei:
+            plan.best_plan(stream=stream)
+        assert ei.value.status == SAILOR_ENOMEM
+        plan.set_scratch(1 << 16, 1 << 15)
+        assert [r.index for r in plan.topk(64, stream=stream)] == [e.index for e in orc.topk(64)]
+        check_result(plan.best_plan(stream=stream), orc.best(), orc)
+    finally:
+        plan.destroy()
+
+
 @pytest.mark.parametrize("seed", range(100, 124))
 def test_random_small_problems(torch_cuda, seed):
     # shapes drawn at random: odd pool counts, deep pipelines on few layers, batches that
