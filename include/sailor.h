@@ -97,7 +97,9 @@ enum {
   SAILOR_MAX_STAGES = 256,
   SAILOR_MAX_SHAPES = 1 << 20, /* (layer split, cut points) combinations over all pp */
   SAILOR_MAX_BW_COEF = 8, /* coefficients of a link's bandwidth polynomial */
-  SAILOR_MAX_K = 4096     /* largest k of sailor_topk */
+  SAILOR_MAX_K = 4096,    /* largest k of sailor_topk */
+  SAILOR_STATIC_SCRATCH_BYTES = 8 << 20, /* device array behind sailor_simulate_1f1b_static */
+  SAILOR_STATIC_MAX_PLANS = 4096         /* most plans one call of it takes */
 };
 
 /*
@@ -274,6 +276,24 @@ sailor_status sailor_plan_last_timing(sailor_plan *plan, float *total_ms, float 
  * SAILOR_ERANGE: count > 2^31 - 1, or more than 2^24 microbatches per pipeline. */
 sailor_status sailor_simulate_1f1b(sailor_plan *plan, uint64_t count, const uint64_t *d_indices,
                                    double *d_event, double *d_closed, void *hip_stream);
+
+/* sailor_simulate_1f1b for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  (sailor_simulate_1f1b itself
+ * allocates, synchronises and frees inside the call when a pipeline is deeper than about 60
+ * stages.)  Same arguments, same results bit for bit; the schedule's working set -- per plan two
+ * rings of end times per stage -- always lives in one file-scope device array of
+ * SAILOR_STATIC_SCRATCH_BYTES that every GPU the library runs on holds from load to exit.  The
+ * call allocates and frees nothing, never synchronises, and only enqueues kernels on
+ * hip_stream; plans are processed in batches of as many as fit the array, one launch per batch.
+ * Nothing in the array has to start at zero (a slot is read only after the stage that produces
+ * it has written it in the same launch), so nothing is cleared.  All calls on one GPU share the
+ * array: calls that overlap on one GPU (different streams or host threads) race and must be
+ * serialised by the caller.
+ * SAILOR_ERANGE (with a message on stderr): count > SAILOR_STATIC_MAX_PLANS, the rings of one
+ * plan of the deepest pipeline exceed the array, or more than 2^24 microbatches per pipeline. */
+sailor_status sailor_simulate_1f1b_static(sailor_plan *plan, uint64_t count,
+                                          const uint64_t *d_indices, double *d_event,
+                                          double *d_closed, void *hip_stream);
 
 /* Sizes of the intermediate lists of the last successful sailor_best_plan / sailor_topk
  * (the selection of Sec. 4.2 runs as fp32 scan -> survivors -> fp64 re-evaluation):

@@ -27,7 +27,8 @@ MAX_K = 4096
 EXPORTS = ["sailor_plan_create", "sailor_plan_destroy", "sailor_plan_set_avail",
            "sailor_plan_num_candidates", "sailor_plan_decode", "sailor_eval_batch",
            "sailor_best_plan", "sailor_topk", "sailor_plan_set_scratch", "sailor_plan_set_timing",
-           "sailor_plan_last_timing", "sailor_plan_last_counts", "sailor_simulate_1f1b"]
+           "sailor_plan_last_timing", "sailor_plan_last_counts", "sailor_simulate_1f1b",
+           "sailor_simulate_1f1b_static"]
 
 
 class SailorError(RuntimeError):
@@ -137,6 +138,7 @@ def load_library() -> C.CDLL:
     lib.sailor_plan_set_timing.argtypes = [P, C.c_int32]
     lib.sailor_plan_last_timing.argtypes = [P, C.POINTER(C.c_float), C.POINTER(C.c_float)]
     lib.sailor_simulate_1f1b.argtypes = [P, C.c_uint64, P, P, P, P]
+    lib.sailor_simulate_1f1b_static.argtypes = [P, C.c_uint64, P, P, P, P]
     lib.sailor_plan_last_counts.argtypes = [P, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                             C.POINTER(C.c_uint32)]
     for name in EXPORTS:
@@ -325,3 +327,12 @@ class Plan:
                                             _ptr(d_closed), stream or None)
         if rc != SAILOR_OK:
             raise SailorError(rc, "sailor_simulate_1f1b")
+
+    def simulate_1f1b_static(self, count: int, d_indices, d_event=None, d_closed=None,
+                             stream: int = 0) -> None:
+        """sailor_simulate_1f1b_static: the same schedule with its working set in the library's
+        static device array (no allocation inside the call)."""
+        rc = self._lib.sailor_simulate_1f1b_static(self._h, count, _ptr(d_indices), _ptr(d_event),
+                                                   _ptr(d_closed), stream or None)
+        if rc != SAILOR_OK:
+            raise SailorError(rc, "sailor_simulate_1f1b_static")

@@ -4,6 +4,7 @@
 #include <hip/hip_ext.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -15,6 +16,11 @@
 #include "sailor_kernels.hip.h"
 
 using namespace sailor;
+
+// Rings of sailor_simulate_1f1b_static: device memory that exists without any allocation call.
+// Every GPU the library runs on holds its own copy at its own address until the process ends;
+// in host code the array's name is only a handle for hipGetSymbolAddress, never an address.
+static __device__ __align__(256) unsigned char scratch[SAILOR_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -36,6 +42,8 @@ constexpr size_t kEvalRowsMaxLds = 64 * 1024;  // above this the range form eval
 constexpr size_t kSimMaxLds = 56 * 1024;       // rings of the event-by-event schedule beyond this
 constexpr uint64_t kSimBatch = 64;             // live in device memory, for so many candidates at once
 
+constexpr int kMaxDevices = 64;                // devices whose static scratch address is kept
+
 #define HIP_TRY(expr)                                                              \
   do {                                                                             \
     hipError_t e_ = (expr);                                                        \
@@ -44,6 +52,21 @@ constexpr uint64_t kSimBatch = 64;             // live in device memory, for so 
       return SAILOR_EDEVICE;                                                       \
     }                                                                              \
   } while (0)
+
+std::atomic<void *> g_scratch_ptr[kMaxDevices];  // per device, looked up once
+
+// The current device's copy of `scratch` (the device must be current).
+sailor_status static_scratch(int device, double **out) {
+  if (device < 0 || device >= kMaxDevices) return SAILOR_EINVAL;
+  void *p = g_scratch_ptr[device].load(std::memory_order_acquire);
+  if (!p) {
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return SAILOR_EDEVICE;
+    g_scratch_ptr[device].store(p, std::memory_order_release);  // (racing threads store the same)
+  }
+  *out = static_cast<double *>(p);
+  return SAILOR_OK;
+}
 
 struct DeviceArena {  // every device allocation of a plan, freed together
   std::vector<void *> ptrs;
@@ -1203,6 +1226,48 @@ sailor_status sailor_simulate_1f1b(sailor_plan *pl, uint64_t count, const uint64
   if (err != hipSuccess) {
     std::fprintf(stderr, "sailor: event schedule failed: %s\n", hipGetErrorString(err));
     return SAILOR_EDEVICE;
+  }
+  return SAILOR_OK;
+}
+
+sailor_status sailor_simulate_1f1b_static(sailor_plan *pl, uint64_t count, const uint64_t *d_indices,
+                                          double *d_event, double *d_closed, void *hip_stream) {
+  if (!pl) return SAILOR_EINVAL;
+  if (count == 0) return SAILOR_OK;
+  if (!d_indices || (!d_event && !d_closed)) return SAILOR_EINVAL;
+  if (count > SAILOR_STATIC_MAX_PLANS) {
+    std::fprintf(stderr, "sailor: sailor_simulate_1f1b_static takes at most %d plans per call (%llu given)\n",
+                 (int)SAILOR_STATIC_MAX_PLANS, (unsigned long long)count);
+    return SAILOR_ERANGE;
+  }
+  if (pl->dev.B / ((int64_t)pl->dpv[0] * pl->mbv[0]) > (1 << 24)) return SAILOR_ERANGE;
+  const int p_max = pl->dev.P_max;
+  int ring = 2;
+  while (ring <= p_max) ring *= 2;
+  const size_t ring_bytes = (size_t)2 * p_max * ring * sizeof(double);  // per plan
+  if (ring_bytes > (size_t)SAILOR_STATIC_SCRATCH_BYTES) {
+    std::fprintf(stderr, "sailor: the rings of one %d-stage pipeline (%zu bytes) exceed the static scratch\n",
+                 p_max, ring_bytes);
+    return SAILOR_ERANGE;
+  }
+  HIP_TRY(hipSetDevice(pl->device));
+  double *rings = nullptr;
+  const sailor_status rc = static_scratch(pl->device, &rings);
+  if (rc != SAILOR_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const unsigned threads = 64u * (unsigned)((p_max + 63) / 64);
+  const uint64_t batch = std::min<uint64_t>(count, (uint64_t)SAILOR_STATIC_SCRATCH_BYTES / ring_bytes);
+  SimArgs a{};
+  a.ring = ring;
+  a.p_max = p_max;
+  a.rings = rings;  // the batches follow one another on the stream and reuse the rings
+  for (uint64_t off = 0; off < count; off += batch) {
+    a.count = std::min<uint64_t>(batch, count - off);
+    a.indices = d_indices + off;
+    a.t_event = d_event ? d_event + off : nullptr;
+    a.t_closed = d_closed ? d_closed + off : nullptr;
+    k_sim_1f1b<<<(unsigned)a.count, threads, 0, st>>>(pl->dev, a);
+    HIP_TRY(hipGetLastError());
   }
   return SAILOR_OK;
 }
