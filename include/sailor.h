@@ -176,7 +176,9 @@ typedef struct {
   int32_t type_b[3];       /* ... and of the other half of them (= type_a unless mixed) */
 } sailor_result;
 
-/* Build a plan: validate, copy the problem to the current HIP device, build the static
+/* The planner's inputs (Sec. 4: job profile, quotas and current availability, prices; Sec. 4.1:
+ * per-layer times and memory per GPU type, link bandwidths) become a plan object.
+ * Build a plan: validate, copy the problem to the current HIP device, build the static
  * per-stage and per-segment tables there, and run three to four passes over the space that
  * decide how later scans are launched (which pieces of the space can never hold a valid plan,
  * how long the others take); results do not depend on that.  *out receives the plan.
@@ -195,6 +197,24 @@ sailor_status sailor_plan_destroy(sailor_plan *plan);
  * rebuilt there, at the start of the next evaluation or selection call, on that call's
  * stream. */
 sailor_status sailor_plan_set_avail(sailor_plan *plan, const int32_t *avail);
+
+/* Re-planning (Sec. 4.4: the planner is invoked again whenever the availability changes;
+ * H2, Sec. 4.2.1: what does not depend on the availability is reused).  The library keeps, for
+ * every piece of the space (one layer split and cut, one TP degree per segment, a range of
+ * pools), the best key of its last full evaluation.  While the query (objective and bound) stays
+ * the same, sailor_best_plan / sailor_topk evaluate again only the pieces whose quota checks
+ * can have changed: those that read a row of the quota table (GPUs one replica takes from a
+ * pool -> data-parallel degrees that fit) in which some pool's entry differs from the table of
+ * their last evaluation -- an integer-only comparison made while the new table is built.  The
+ * other pieces contribute their kept minima.  Results are identical to a full evaluation.
+ * on = 1 (default) / 0: off, every call evaluates the whole space. */
+sailor_status sailor_plan_set_incremental(sailor_plan *plan, int32_t on);
+
+/* Pieces of the space the last successful sailor_best_plan / sailor_topk evaluated, and how
+ * many there are.  Host pointers, either may be NULL.  SAILOR_EINVAL before the first
+ * successful selection. */
+sailor_status sailor_plan_last_scan(const sailor_plan *plan, uint32_t *units_evaluated,
+                                    uint32_t *units_total);
 
 /* Number of candidates N. */
 sailor_status sailor_plan_num_candidates(const sailor_plan *plan, uint64_t *out);
@@ -227,7 +247,9 @@ sailor_status sailor_best_plan(sailor_plan *plan, sailor_objective objective,
                                const sailor_constraint *constraint, sailor_result *out,
                                void *hip_stream);
 
-/* The k best valid plans in ascending (key, index) order; out (host) has room for k
+/* Sec. 4.2: the planner "sorts the configurations according to the objective"; this returns the
+ * head of that order.
+ * The k best valid plans in ascending (key, index) order; out (host) has room for k
  * entries, *n_found receives how many exist (<= k).  1 <= k <= SAILOR_MAX_K.
  * Keys, and the constrained quantity against the bound, are the fp64 values reported in out:
  * plans whose values agree to the last few bits (or a value that equals the bound to the

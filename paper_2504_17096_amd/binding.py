@@ -28,7 +28,7 @@ EXPORTS = ["sailor_plan_create", "sailor_plan_destroy", "sailor_plan_set_avail",
            "sailor_plan_num_candidates", "sailor_plan_decode", "sailor_eval_batch",
            "sailor_best_plan", "sailor_topk", "sailor_plan_set_scratch", "sailor_plan_set_timing",
            "sailor_plan_last_timing", "sailor_plan_last_counts", "sailor_simulate_1f1b",
-           "sailor_simulate_1f1b_static"]
+           "sailor_simulate_1f1b_static", "sailor_plan_set_incremental", "sailor_plan_last_scan"]
 
 
 class SailorError(RuntimeError):
@@ -139,6 +139,8 @@ def load_library() -> C.CDLL:
     lib.sailor_plan_last_timing.argtypes = [P, C.POINTER(C.c_float), C.POINTER(C.c_float)]
     lib.sailor_simulate_1f1b.argtypes = [P, C.c_uint64, P, P, P, P]
     lib.sailor_simulate_1f1b_static.argtypes = [P, C.c_uint64, P, P, P, P]
+    lib.sailor_plan_set_incremental.argtypes = [P, C.c_int32]
+    lib.sailor_plan_last_scan.argtypes = [P, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
     lib.sailor_plan_last_counts.argtypes = [P, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                             C.POINTER(C.c_uint32)]
     for name in EXPORTS:
@@ -320,6 +322,19 @@ class Plan:
         if rc != SAILOR_OK:
             raise SailorError(rc, "sailor_plan_last_counts")
         return a.value, b.value, c.value
+
+    def set_incremental(self, on: bool) -> None:
+        rc = self._lib.sailor_plan_set_incremental(self._h, 1 if on else 0)
+        if rc != SAILOR_OK:
+            raise SailorError(rc, "sailor_plan_set_incremental")
+
+    def last_scan(self) -> Tuple[int, int]:
+        """(pieces of the space the last selection evaluated, pieces in total)."""
+        a, b = C.c_uint32(), C.c_uint32()
+        rc = self._lib.sailor_plan_last_scan(self._h, C.byref(a), C.byref(b))
+        if rc != SAILOR_OK:
+            raise SailorError(rc, "sailor_plan_last_scan")
+        return a.value, b.value
 
     def simulate_1f1b(self, count: int, d_indices, d_event=None, d_closed=None, stream: int = 0) -> None:
         """sailor_simulate_1f1b; the arrays are device tensors (uint64 / int64 indices, float64)."""

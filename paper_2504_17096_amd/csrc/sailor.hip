@@ -137,6 +137,16 @@ struct sailor_plan {
   ResultHeader *d_hdr = nullptr;
   RefRec *d_out = nullptr;
   RefRec *staged = nullptr;    // device-side copy of the top-k records before they go to the host
+  // re-planning: per-unit minima of the last scan are kept while the query stays the same
+  uint32_t *unit_gen = nullptr;   // device, per unit: availability generation of its minima
+  uint32_t *ubits = nullptr;      // device, per unit: validity words as last staged
+  uint32_t ubits_stride = 0;
+  uint32_t avail_gen = 1;         // bumped whenever a new availability table reaches the device
+  bool incremental = true;        // sailor_plan_set_incremental
+  bool cache_ok = false;          // the minima on the device belong to the query below
+  int cache_obj = 0, cache_hasb = 0;
+  float cache_lim_s = 0.f, cache_lim_l = 0.f;
+  bool last_incremental = false;  // the last successful selection reused minima
   uint32_t cnt_phase = 0;      // which of the two counter sets the next call uses
   bool counters_dirty = false; // a failed call may have left either set in any state
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};  // start, scan end, end, scan start
@@ -483,7 +493,9 @@ sailor_status refresh_avail(sailor_plan *pl, hipStream_t st) {
   if (!pl->avail_dirty) return SAILOR_OK;
   // the kernel reads the new table from the pinned staging buffer and leaves a copy on the
   // device (no separate upload in front of it)
-  k_quota_table<<<quota_grid(pl->dev), 256, 0, st>>>(pl->dev, pl->h_avail_dev, pl->d_avail);
+  pl->avail_gen += 1;
+  k_quota_table<<<quota_grid(pl->dev), 256, 0, st>>>(pl->dev, pl->h_avail_dev, pl->d_avail,
+                                                      pl->avail_gen);
   HIP_TRY(hipEventRecord(pl->ev_upload, st));
   pl->upload_pending = true;
   pl->avail_dirty = false;
@@ -549,6 +561,21 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
   sa.surv = pl->surv;
   sa.surv_cap = pl->surv_cap;
   sa.n_sub = kCollectSub;
+  // a unit's minima of the last scan are reused when the query is the same and no quota row
+  // the unit reads has changed since (the kernels compare generations per unit)
+  sa.unit_gen = pl->unit_gen;
+  sa.cur_gen = pl->avail_gen;
+  sa.ubits = pl->incremental ? pl->ubits : nullptr;
+  sa.ubits_stride = pl->ubits_stride;
+  sa.incremental = (pl->incremental && pl->cache_ok && pl->cache_obj == (int)obj &&
+                    pl->cache_hasb == has_bound && pl->cache_lim_s == sa.lim_s &&
+                    pl->cache_lim_l == sa.lim_l) ? 1 : 0;
+  const bool was_incremental = sa.incremental != 0;
+  pl->cache_ok = false;  // until this call has succeeded
+  pl->cache_obj = (int)obj;
+  pl->cache_hasb = has_bound;
+  pl->cache_lim_s = sa.lim_s;
+  pl->cache_lim_l = sa.lim_l;
   const bool best = (k == 0);
   const uint32_t n_units = (uint32_t)pl->units.size();
   const bool t_scan = pl->timing_mode >= 1, t_all = pl->timing_mode >= 2;
@@ -679,6 +706,8 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
     rc = run_tail(hdr_out);
     if (rc != SAILOR_OK) return rc;
   }
+  pl->cache_ok = true;  // the scan completed: every unit's minima and stamp are in place
+  pl->last_incremental = was_incremental;
   if (hdr_out->surv_count > pl->surv_cap || hdr_out->ref_count > pl->ref_cap) return SAILOR_ENOMEM;
   return SAILOR_OK;
 }
@@ -764,7 +793,7 @@ static sailor_status create_impl(const sailor_problem *p, sailor_plan **out, sai
                        (size_t)3 * d.TP * d.ZG * sizeof(uint32_t) +
                        (size_t)d.ZG * (sizeof(PoolInfo) + sizeof(uint64_t)) +
                        (size_t)(kEvalUnitMaxOuter + d.DP + d.TP) * sizeof(uint32_t);
-  pl->lds_bytes = (size_t)3 * d.ZG * d.MB * sizeof(Rec) +
+  pl->lds_bytes = unit_lds_records(d.ZG, d.MB) * (2 * sizeof(float4) + sizeof(uint32_t)) +
                   (size_t)d.MB * d.Z * d.Z * sizeof(float4) +
                   (size_t)d.ZG * (sizeof(uint64_t) + sizeof(uint32_t));
 
@@ -802,6 +831,8 @@ static sailor_status create_impl(const sailor_problem *p, sailor_plan **out, sai
   d.W_max = d.P_max * p->tp_values[TP - 1];
   CREATE_TRY(ar.alloc(&d.qw, (size_t)(d.W_max + 1) * ZG));
   if (d.mixed) CREATE_TRY(ar.alloc(&d.qh, (size_t)(2 * d.W_max + 1) * ZGr));
+  CREATE_TRY(ar.alloc(&d.row_gen, (size_t)d.W_max + 2));
+  CREATE_TRY(hipMemset(d.row_gen, 0, ((size_t)d.W_max + 2) * sizeof(uint32_t)));
   CREATE_TRY(ar.alloc(&d.h1m, ZG));
   CREATE_TRY(ar.alloc(&d.isect, ZG));
   {
@@ -880,6 +911,10 @@ static sailor_status create_impl(const sailor_problem *p, sailor_plan **out, sai
   CREATE_TRY(ar.alloc(&pl->umin_l, unit_cap));
   CREATE_TRY(ar.alloc(&pl->counters, (size_t)2 * CNT_COUNT));
   CREATE_TRY(ar.alloc(&pl->ulist, unit_cap));
+  CREATE_TRY(ar.alloc(&pl->unit_gen, unit_cap));
+  CREATE_TRY(hipMemset(pl->unit_gen, 0, unit_cap * sizeof(uint32_t)));
+  pl->ubits_stride = (uint32_t)(unit_lds_records(ZG, MB) + (size_t)ZG);
+  CREATE_TRY(ar.alloc(&pl->ubits, unit_cap * (size_t)pl->ubits_stride));
   CREATE_TRY(ar.alloc(&pl->surv, (size_t)pl->surv_cap));
   CREATE_TRY(ar.alloc(&pl->ref, (size_t)pl->ref_cap));
   CREATE_TRY(ar.alloc(&pl->staged, (size_t)SAILOR_MAX_K));
@@ -893,7 +928,7 @@ static sailor_status create_impl(const sailor_problem *p, sailor_plan **out, sai
   for (hipEvent_t &e : pl->ev) CREATE_TRY(hipEventCreate(&e));
 
   k_init_counters<<<1, 64>>>(pl->counters, 2 * CNT_COUNT);
-  k_quota_table<<<quota_grid(d), 256>>>(d, d.avail, nullptr);
+  k_quota_table<<<quota_grid(d), 256>>>(d, d.avail, nullptr, 0u);
   k_small_tables<<<1, 256>>>(d);
   k_stage_tables<<<(unsigned)RS, 128>>>(d, sa);
   k_shape_agg<<<(unsigned)NS, 256>>>(d);
@@ -1269,6 +1304,22 @@ sailor_status sailor_simulate_1f1b_static(sailor_plan *pl, uint64_t count, const
     k_sim_1f1b<<<(unsigned)a.count, threads, 0, st>>>(pl->dev, a);
     HIP_TRY(hipGetLastError());
   }
+  return SAILOR_OK;
+}
+
+sailor_status sailor_plan_set_incremental(sailor_plan *pl, int32_t on) {
+  if (!pl || (on != 0 && on != 1)) return SAILOR_EINVAL;
+  if (pl->incremental != (on != 0)) pl->cache_ok = false;  // what a scan keeps depends on it
+  pl->incremental = on != 0;
+  return SAILOR_OK;
+}
+
+sailor_status sailor_plan_last_scan(const sailor_plan *pl, uint32_t *units_evaluated,
+                                    uint32_t *units_total) {
+  if (!pl || !pl->have_hdr) return SAILOR_EINVAL;
+  const uint32_t total = (uint32_t)pl->units.size();
+  if (units_evaluated) *units_evaluated = pl->last_incremental ? pl->last_hdr.rescanned : total;
+  if (units_total) *units_total = total;
   return SAILOR_OK;
 }
 

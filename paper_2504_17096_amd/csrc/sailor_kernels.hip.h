@@ -277,6 +277,25 @@ __device__ __forceinline__ Rec make_rec(float4 ta, float sync, float upd, float 
   return r;
 }
 
+// A segment record in LDS: two 16-byte halves in arrays of their own (the records a wave reads
+// together then lie 16 bytes apart and spread over all banks; 32-byte records leave half of
+// them idle) and the validity bits once more in a dense array for the tests that need
+// nothing else.
+__device__ __forceinline__ void rec_store(float4 *lo, float4 *hi, uint32_t *bits, int i, const Rec &r) {
+  lo[i] = make_float4(r.sumT, r.tF, r.tL, r.tI);
+  hi[i] = make_float4(r.syncb, r.upd, r.pricen, __uint_as_float(r.bits));
+  bits[i] = r.bits;
+}
+
+__device__ __forceinline__ Rec rec_load(const float4 *lo, const float4 *hi, int i) {
+  const float4 a = lo[i], b = hi[i];
+  Rec r;
+  r.sumT = a.x; r.tF = a.y; r.tL = a.z; r.tI = a.w;
+  r.syncb = b.x; r.upd = b.y; r.pricen = b.z;
+  r.bits = __float_as_uint(b.w);
+  return r;
+}
+
 // Iteration time and cost of a plan, accumulated segment by segment.  Everything that
 // depends only on the leading segments is finished before the pool of the next segment
 // is known, so the scan hoists it out of its inner loops; the order of the floating
@@ -339,7 +358,11 @@ __device__ __forceinline__ void acc_finish(const Acc &p, const LaneC &lc, float 
 // A pool that is a pair of types gives half of the replicas from each (an even number of
 // them); qh serves plans whose segments draw on one real pool together: x half-GPUs per
 // replica of the plan fit the real pool for the degrees whose bit is set.
-__global__ void k_quota_table(DevPlan pl, const int32_t *avail, int32_t *avail_copy) {
+// gen: the availability generation (0 while the plan is built).  A row of qw (GPUs per
+// replica) that changes in any pool is stamped with gen in row_gen, so that a scan can tell
+// which units' validity bits are still those of their last evaluation; row_gen[W_max + 1]
+// stands for the whole of qh.
+__global__ void k_quota_table(DevPlan pl, const int32_t *avail, int32_t *avail_copy, uint32_t gen) {
   // avail: the table to build from -- pl.avail, or a newer one in host-mapped memory, which
   // is then also copied to avail_copy (= pl.avail) for the kernels that read it later; that
   // saves a separate upload in front of this kernel
@@ -357,7 +380,12 @@ __global__ void k_quota_table(DevPlan pl, const int32_t *avail, int32_t *avail_c
                    : (D % 2 == 0 && (int64_t)w * D <= 2 * avail_a && (int64_t)w * D <= 2 * avail_b))
         bits |= 1u << d;
     }
-    pl.qw[i] = bits;
+    if (gen == 0u) {
+      pl.qw[i] = bits;
+    } else if (pl.qw[i] != bits) {
+      pl.qw[i] = bits;
+      atomicMax(&pl.row_gen[w], gen);
+    }
   }
   if (!pl.mixed) return;
   const int nh = (2 * pl.W_max + 1) * pl.ZGr;
@@ -367,7 +395,12 @@ __global__ void k_quota_table(DevPlan pl, const int32_t *avail, int32_t *avail_c
     uint32_t bits = 0;
     for (int d = 0; d < pl.DP; ++d)
       if ((int64_t)x * pl.dpv[d] <= avail2) bits |= 1u << d;
-    pl.qh[i] = bits;
+    if (gen == 0u) {
+      pl.qh[i] = bits;
+    } else if (pl.qh[i] != bits) {
+      pl.qh[i] = bits;
+      atomicMax(&pl.row_gen[pl.W_max + 1], gen);
+    }
   }
 }
 
@@ -419,6 +452,13 @@ struct ScanArgs {
   int ignore_quota;         // SCAN at plan creation: treat every pool as large enough
   const uint32_t *ulist;    // COLLECT, optional: the units to visit and, in counters[CNT_NLIST],
                             // how many; the grid then strides over the list
+  uint32_t *unit_gen;       // SCAN, optional: per unit, the availability generation its minima
+  uint32_t cur_gen;         // were computed at; a scan stamps what it computes with cur_gen
+  int incremental;          // SCAN: units whose quota rows have not changed since their stamp,
+                            // or whose validity bits come out as they were, keep their minima
+                            // and are not evaluated again
+  uint32_t *ubits;          // SCAN, with unit_gen: per unit, the validity bits of its records
+  uint32_t ubits_stride;    // (and the shared-pool quota words) as last staged; words per unit
   uint32_t *near_list;      // SCAN, optional (best plan): units whose loose minimum lies within
   float near_band;          // near_band of the smallest strict key seen so far are appended
                             // here (count in counters[CNT_NLIST]); the running minimum only
@@ -429,6 +469,7 @@ enum Counter { CNT_SURV = 0, CNT_REF = 1, CNT_FEAS = 2, CNT_GMIN = 3, CNT_TAU0 =
                CNT_NLOOSE = 6, CNT_NSTRICT = 7,  // count-only collect passes
                CNT_NLIST = 8,                    // length of the collect pass's unit list
                CNT_DONE = 9,                     // workgroups of the final kernel that have finished
+               CNT_RESCAN = 10,                  // units an incremental scan evaluated again
                CNT_COUNT = 16 };
 
 __device__ __forceinline__ uint32_t counter_reset_value(int i) {
@@ -534,7 +575,8 @@ __device__ __forceinline__ bool wave_any(bool p) { return __builtin_amdgcn_ballo
 // (isect) get the joint quota check, the others keep the per-segment bits.
 template <int S, int MODE, int OBJ, bool HASB, bool MIXED>
 __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, const UnitRec &u,
-                                          const Rec *rec, const float4 *pair,
+                                          const float4 *rec_lo, const float4 *rec_hi,
+                                          const uint32_t *rbits, const float4 *pair,
                                           const uint32_t *q13, const uint64_t *isect, int w0,
                                           int w1, int w2, float tau, int sub, int n_sub,
                                           float &ms, float &ml) {
@@ -552,10 +594,9 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
     for (int e0 = wave * 64; e0 < nin; e0 += nwave * 64) {
       const LaneItem it = lane_item(pl, e0 + lane, nin, ZG, pl.mg_mbzg);
       const int a1 = it.a1;
-      const Rec *recm = rec + it.mb;         // this lane's column of the record table
-      const Rec r0 = recm[a1 * MB];
-      const uint32_t b0 = r0.bits & it.dpbit;
+      const uint32_t b0 = rbits[a1 * MB + it.mb] & it.dpbit;
       if (!wave_any(b0 != 0)) continue;
+      const Rec r0 = rec_load(rec_lo, rec_hi, a1 * MB + it.mb);
       const int z1 = (int)fast_div((uint32_t)a1, pl.mg_g);
       const float4 *pair1 = pair + (it.mb * Z + z1) * Z;  // transfers out of this lane's first zone
       const Acc A0 = acc_begin(r0);
@@ -569,12 +610,12 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
       }
       int z2 = u.o_lo / G, g2 = u.o_lo % G;
       for (int a2 = u.o_lo; a2 < u.o_lo + u.o_cnt; ++a2) {
-        const Rec *rp1 = recm + (ZG + a2) * MB;
-        uint32_t b1 = (a1 != a2) ? (b0 & rp1->bits) : 0u;
+        const int i1 = (ZG + a2) * MB + it.mb;
+        uint32_t b1 = (a1 != a2) ? (b0 & rbits[i1]) : 0u;
         if (MIXED && b1 != 0 && ((isect[a2] >> a1) & 1ull))
           b1 &= joint_quota_bits(pl, 2, a1, a2, 0, w0, w1, 0);
         if (wave_any(b1 != 0)) {
-          const Rec r1 = *rp1;
+          const Rec r1 = rec_load(rec_lo, rec_hi, i1);
           const float4 p12 = pair1[z2];
           const Acc A1 = acc_cross(A0, r1, p12.x, p12.y, p12.z, single0, true);
           int rel2 = a2 - a1 - 1;
@@ -595,11 +636,11 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
       for (int e0 = wave * 64; e0 < nin; e0 += nwave * 64) {
         const LaneItem it = lane_item(pl, e0 + lane, nin, ZG - 1, pl.mg_mbzg1);
         const int a1 = it.a1 + (it.a1 >= a2 ? 1 : 0);  // skip the pool of segment 2
-        const Rec *recm = rec + it.mb;
-        const Rec r0 = recm[a1 * MB];
-        const Rec r1 = recm[(ZG + a2) * MB];
-        const uint32_t b1 = r0.bits & it.dpbit & r1.bits;
+        const int i0 = a1 * MB + it.mb, i1 = (ZG + a2) * MB + it.mb;
+        const uint32_t b1 = rbits[i0] & it.dpbit & rbits[i1];
         if (!wave_any(b1 != 0)) continue;
+        const Rec r0 = rec_load(rec_lo, rec_hi, i0);
+        const Rec r1 = rec_load(rec_lo, rec_hi, i1);
         const int z1 = (int)fast_div((uint32_t)a1, pl.mg_g);
         const float4 *pairm = pair + it.mb * Z * Z;
         const float4 p12 = pairm[z1 * Z + z2];
@@ -612,8 +653,8 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
         int z3 = 0, g3 = 0;
         for (int a3 = 0; a3 < ZG; ++a3) {
           if (a3 != a2) {  // uniform
-            const Rec *rp2 = recm + (2 * ZG + a3) * MB;
-            uint32_t b2 = b1 & rp2->bits;
+            const int i2 = (2 * ZG + a3) * MB + it.mb;
+            uint32_t b2 = b1 & rbits[i2];
             if (MIXED) {
               if (b2 != 0 && (((is2 >> a1) | (is2 >> a3) | (isect[a3] >> a1)) & 1ull))
                 b2 &= joint_quota_bits(pl, 3, a1, a2, a3, w0, w1, w2);
@@ -621,7 +662,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
               b2 &= q13a;  // segments 1 and 3 share one pool's quota
             }
             if (wave_any(b2 != 0)) {
-              const Rec r2 = *rp2;
+              const Rec r2 = rec_load(rec_lo, rec_hi, i2);
               const float4 p23 = pairm[z2 * Z + z3];
               const Acc A2 = acc_cross(A1, r2, p23.x, p23.y, p23.z, single1, false);
               int rel3 = a3 - a2 - 1;
@@ -640,6 +681,27 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
   }
 }
 
+// Records a scanned unit's minima and folds them into the global minimum (and, for the best
+// plan, the list of units near it).  One thread.
+__device__ __forceinline__ void unit_publish(const ScanArgs &a, uint32_t uidx, float ms, float ml) {
+  // keys are non-negative, so their bit patterns order like unsigned integers
+  // (a stale read only costs a redundant atomic; most units lose and skip theirs)
+  const uint32_t seen = __hip_atomic_load(&a.counters[CNT_GMIN], __ATOMIC_RELAXED,
+                                          __HIP_MEMORY_SCOPE_AGENT);
+  if (__float_as_uint(ms) < seen) atomicMin(&a.counters[CNT_GMIN], __float_as_uint(ms));
+  if (a.near_list && ml < kPosInf) {
+    // (a stale `seen` is larger than the true running minimum and only lengthens the list)
+    const float running = fminf(__uint_as_float(seen), ms);
+    if (ml <= running * a.near_band) a.near_list[atomicAdd(&a.counters[CNT_NLIST], 1u)] = uidx;
+  }
+}
+
+// LDS of a scan workgroup: the records of [3][ZG][MB] (segment, pool, mb) as two float4 arrays
+// and a dense array of their validity bits, the transfer table, the shared-pool masks.
+__host__ __device__ inline size_t unit_lds_records(int ZG, int MB) {
+  return ((size_t)3 * ZG * MB + 3) & ~(size_t)3;  // a multiple of 4, so that what follows stays 16-byte aligned
+}
+
 // One workgroup per unit: stage the unit's segment records in LDS, then every lane walks
 // its (mb, dp, pool 1) triple over the unit's outer pool digits.  Everything the staging
 // needs comes from the unit record and tables that do not depend on one another, so all of
@@ -656,8 +718,11 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
     if (!(um < kPosInf && um <= tau)) return;  // uniform over the workgroup
   }
   const int ZG = pl.ZG, G = pl.GX, MB = pl.MB, Z = pl.Z, S = u.s;
-  Rec *rec = reinterpret_cast<Rec *>(lds_raw);                        // [S][ZG][MB]
-  float4 *pair = reinterpret_cast<float4 *>(rec + 3 * ZG * MB);       // [MB][Z][Z]
+  const size_t n_rec = unit_lds_records(ZG, MB);
+  float4 *rec_lo = reinterpret_cast<float4 *>(lds_raw);               // [S][ZG][MB], first halves
+  float4 *rec_hi = rec_lo + n_rec;                                    // second halves
+  uint32_t *rbits = reinterpret_cast<uint32_t *>(rec_hi + n_rec);     // validity bits alone
+  float4 *pair = reinterpret_cast<float4 *>(rbits + n_rec);           // [MB][Z][Z]
   uint64_t *isect = reinterpret_cast<uint64_t *>(pair + MB * Z * Z);  // [ZG]
   uint32_t *q13 = reinterpret_cast<uint32_t *>(isect + ZG);           // [ZG]
   __shared__ float red[2][kMaxUnitThreads / 64];
@@ -668,6 +733,27 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
   const int k0 = u.tp[0], k1 = u.tp[1], k2 = u.tp[2];            // tp index of each segment
   const int tv0 = pl.tpv[k0], tv1 = pl.tpv[k1], tv2 = pl.tpv[k2];
   const int w0 = n0 * tv0, w1 = n1 * tv1, w2 = n2 * tv2;        // GPUs of one replica
+  bool joint_changed = false;  // (MIXED) the shared-pool table changed: no cheaper test exists
+  if (MODE == MODE_SCAN && a.incremental) {
+    // Re-planning after an availability change: the unit's minima of the last scan still hold
+    // if no quota row it reads (GPUs per replica of its segments; segments 1 and 3 on one pool)
+    // has changed since.  Uniform over the workgroup.  A unit that fails this test is staged
+    // and its validity bits are compared with those of its last evaluation.
+    const uint32_t stamp = a.unit_gen[uidx];
+    uint32_t changed = pl.row_gen[w0];
+    if (S >= 2) changed = max(changed, pl.row_gen[w1]);
+    if (S == 3) changed = max(changed, max(pl.row_gen[w2], pl.row_gen[w0 + w2]));
+    if (MIXED && S >= 2) {
+      joint_changed = pl.row_gen[pl.W_max + 1] > stamp;
+      changed = max(changed, pl.row_gen[pl.W_max + 1]);
+    }
+    if (changed <= stamp) {
+      if (t == 0) unit_publish(a, uidx, a.umin_s[uidx], a.umin_l[uidx]);
+      return;
+    }
+  }
+  const bool keep_bits = MODE == MODE_SCAN && a.ubits != nullptr;
+  uint32_t *const ub = keep_bits ? a.ubits + (size_t)uidx * a.ubits_stride : nullptr;
   uint32_t any_here = 0;
   for (int i = t; i < S * ZG * MB; i += blockDim.x) {
     const uint32_t sp = fast_div((uint32_t)i, pl.mg_mb), mb = (uint32_t)i - sp * (uint32_t)MB;
@@ -681,16 +767,28 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
     uint32_t q = a.ignore_quota ? 0xFFFFFFFFu : pl.qw[w * ZG + p];
     if ((pl.h1m[p] >> k) & 1u) q = 0;  // H1: tensor parallelism stays inside a node
     const uint32_t bits = pl.memok[gi] & q & pl.divis[mb];
-    rec[i] = make_rec(ta, pl.syncz[sl * Z + z], pl.upd[sl * G + g], pl.price_f[g],
-                      pl.tsec_f[(mb * Z + z) * Z + z], seg == 0 ? n0 : (seg == 1 ? n1 : n2),
-                      seg == 0 ? tv0 : (seg == 1 ? tv1 : tv2), bits);
+    rec_store(rec_lo, rec_hi, rbits, i,
+              make_rec(ta, pl.syncz[sl * Z + z], pl.upd[sl * G + g], pl.price_f[g],
+                       pl.tsec_f[(mb * Z + z) * Z + z], seg == 0 ? n0 : (seg == 1 ? n1 : n2),
+                       seg == 0 ? tv0 : (seg == 1 ? tv1 : tv2), bits));
     // a segment that no pool can host validly rules the whole unit out
     const bool counts = seg != 1 || (p >= (int)u.o_lo && p < (int)(u.o_lo + u.o_cnt));
     if (bits != 0 && counts) any_here |= 1u << seg;
+    if (keep_bits && counts) {  // (segment 2's pools outside the unit's range do not concern it)
+      if (!a.incremental) ub[i] = bits;
+      else if (ub[i] != bits) { ub[i] = bits; any_here |= 8u; }
+    }
   }
   if (S == 3 && !MIXED)
-    for (int p = t; p < ZG; p += blockDim.x)
-      q13[p] = a.ignore_quota ? 0xFFFFFFFFu : pl.qw[(w0 + w2) * ZG + p];
+    for (int p = t; p < ZG; p += blockDim.x) {
+      const uint32_t q = a.ignore_quota ? 0xFFFFFFFFu : pl.qw[(w0 + w2) * ZG + p];
+      q13[p] = q;
+      if (keep_bits) {
+        uint32_t *const uq = ub + a.ubits_stride - ZG;  // behind the records' bits
+        if (!a.incremental) uq[p] = q;
+        else if (uq[p] != q) { uq[p] = q; any_here |= 8u; }
+      }
+    }
   if (MIXED)  // under ignore_quota no pool counts as shared
     for (int p = t; p < ZG; p += blockDim.x) isect[p] = a.ignore_quota ? 0ull : pl.isect[p];
   for (int i = t; i < MB * Z * Z; i += blockDim.x) {  // per mb: transfer a -> b, b -> a, egress
@@ -700,17 +798,30 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
   {
     uint32_t wv = 0;
 #pragma unroll
-    for (int j = 0; j < 3; ++j)
+    for (int j = 0; j < 4; ++j)  // (bit 3: a validity word differs from the last evaluation's)
       if (__builtin_amdgcn_ballot_w64((any_here >> j) & 1u) != 0) wv |= 1u << j;
     if ((t & 63) == 0) s_any[t >> 6] = wv;
   }
   __syncthreads();
   uint32_t any_all = 0;
   for (int w = 0; w < (int)(blockDim.x >> 6); ++w) any_all |= s_any[w];
+  if (MODE == MODE_SCAN && a.incremental && !(any_all & 8u) && !joint_changed) {
+    // every validity bit is what it was: the minima still hold (uniform over the workgroup)
+    if (t == 0) {
+      a.unit_gen[uidx] = a.cur_gen;
+      unit_publish(a, uidx, a.umin_s[uidx], a.umin_l[uidx]);
+    }
+    return;
+  }
+  any_all &= 7u;
   if (any_all != (1u << S) - 1u) {  // uniform over the workgroup
     if (MODE == MODE_SCAN && t == 0) {
       a.umin_s[uidx] = kPosInf;
       a.umin_l[uidx] = kPosInf;
+      if (a.unit_gen) {
+        a.unit_gen[uidx] = a.cur_gen;
+        if (a.incremental) atomicAdd(&a.counters[CNT_RESCAN], 1u);
+      }
       if (a.ucost) a.ucost[uidx] = (float)(wall_clock64() - t_begin);
     }
     return;
@@ -722,9 +833,9 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
   // fast digit of the share a part keeps the same chunks ((c / waves) mod n_parts == part)
   // whatever n_sub is: the collect pass must visit exactly what the scan saw.
   const int share = sub * (int)u.n_parts + (int)u.part, n_shares = (int)u.n_parts * (int)n_sub;
-  if (S == 1) unit_body<1, MODE, OBJ, HASB, MIXED>(pl, a, u, rec, pair, q13, isect, w0, w1, w2, tau, share, n_shares, ms, ml);
-  else if (S == 2) unit_body<2, MODE, OBJ, HASB, MIXED>(pl, a, u, rec, pair, q13, isect, w0, w1, w2, tau, share, n_shares, ms, ml);
-  else unit_body<3, MODE, OBJ, HASB, MIXED>(pl, a, u, rec, pair, q13, isect, w0, w1, w2, tau, share, n_shares, ms, ml);
+  if (S == 1) unit_body<1, MODE, OBJ, HASB, MIXED>(pl, a, u, rec_lo, rec_hi, rbits, pair, q13, isect, w0, w1, w2, tau, share, n_shares, ms, ml);
+  else if (S == 2) unit_body<2, MODE, OBJ, HASB, MIXED>(pl, a, u, rec_lo, rec_hi, rbits, pair, q13, isect, w0, w1, w2, tau, share, n_shares, ms, ml);
+  else unit_body<3, MODE, OBJ, HASB, MIXED>(pl, a, u, rec_lo, rec_hi, rbits, pair, q13, isect, w0, w1, w2, tau, share, n_shares, ms, ml);
 
   if (MODE == MODE_SCAN) {
     if (!HASB) ml = ms;
@@ -739,16 +850,11 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
       }
       a.umin_s[uidx] = ms;
       a.umin_l[uidx] = ml;
-      // keys are non-negative, so their bit patterns order like unsigned integers
-      // (a stale read only costs a redundant atomic; most units lose and skip theirs)
-      const uint32_t seen = __hip_atomic_load(&a.counters[CNT_GMIN], __ATOMIC_RELAXED,
-                                              __HIP_MEMORY_SCOPE_AGENT);
-      if (__float_as_uint(ms) < seen) atomicMin(&a.counters[CNT_GMIN], __float_as_uint(ms));
-      if (a.near_list && ml < kPosInf) {
-        // (a stale `seen` is larger than the true running minimum and only lengthens the list)
-        const float running = fminf(__uint_as_float(seen), ms);
-        if (ml <= running * a.near_band) a.near_list[atomicAdd(&a.counters[CNT_NLIST], 1u)] = uidx;
+      if (a.unit_gen) {
+        a.unit_gen[uidx] = a.cur_gen;
+        if (a.incremental) atomicAdd(&a.counters[CNT_RESCAN], 1u);
       }
+      unit_publish(a, uidx, ms, ml);
       if (a.ucost) a.ucost[uidx] = (float)(wall_clock64() - t_begin);
     }
   }
@@ -1249,6 +1355,7 @@ __global__ __launch_bounds__(1024) void k_pick_best(const RefRec *ref, uint32_t 
     hdr->ref_count = n_ref;
     hdr->feasible_count = n_feas;
     hdr->gmin_bits = gmin;
+    hdr->rescanned = counters[CNT_RESCAN];
     publish(hdr, seq);
   }
 }
@@ -1291,6 +1398,7 @@ __global__ __launch_bounds__(kRankLds) void k_rank_topk(const RefRec *ref, uint3
     hdr->ref_count = n_ref;
     hdr->feasible_count = f;
     hdr->gmin_bits = counters[CNT_GMIN];
+    hdr->rescanned = counters[CNT_RESCAN];
   }
   if (overflow) {  // the host turns ref_count > ref_cap into SAILOR_ENOMEM
     if (gridDim.x == 1) {

@@ -336,6 +336,24 @@ def config5_snapshots(base: Problem, n_snapshots: int = 64, seed: int = 5) -> Li
     return out
 
 
+def node_events(base: Problem, n_snapshots: int = 64, seed: int = 7) -> List[np.ndarray]:
+    """Availability stream in which one (zone, type) pool changes per snapshot: a few nodes of
+    one type join or leave one zone (the 16 -> 20 GPU reconfiguration of Sec. 5.5 is of this
+    kind), 4 to 16 GPUs at a time, clamped to [0, 256]."""
+    rng = SplitMix64(seed)
+    Z, G = base.n_zones, base.n_types
+    state = base.avail.astype(np.int64).copy()
+    out = []
+    for _ in range(n_snapshots):
+        z, g = rng.randint(0, Z - 1), rng.randint(0, G - 1)
+        step = 4 * rng.randint(1, 4)
+        if rng.uniform() < 0.5:
+            step = -step
+        state[z, g] = min(256, max(0, int(state[z, g]) + step))
+        out.append(state.astype(np.int32).copy())
+    return out
+
+
 def bandwidth_poly(prob: Problem, seed: int = 6) -> np.ndarray:
     """Seeded message-size profile of every link: a quadratic in log2(bytes) through
     (1 KiB, 2-8 % of the peak), (1 MiB, 40-70 %) and (128 MiB, the peak), the shape
