@@ -4,15 +4,20 @@ A step is one pass of the whole hot path over the largest synthetic workload (th
 OPT-30B-like cluster with 104 256 000 candidate plans): index decode, table gathers,
 per-stage memory check, 1F1B makespan with transfers and gradient all-reduce, cost,
 validity mask, and the selection of the 64 best plans for "max throughput under a
-budget of 1.2 x the cheapest plan".  Inputs are resident on the device before timing.
+budget of 1.2 x the cheapest plan".  Inputs are resident on the device before timing;
+every step evaluates the whole space (nothing is kept from one step to the next).
 
-Prints one JSON line: candidates/s over the timed steps, the roofline of the dominant
-kernel (the full-space scan, timed with HIP events on its own stream inside the
-library) and the CPU oracle timed on this host on a bounded sample.
+Prints one JSON line: candidates/s over the timed steps; the roofline of the dominant
+kernel (the full-space scan: its duration from HIP events on its own dispatch, its
+instruction counts from the committed rocprofv3 counter summary, which is used only while
+the kernel sources still hash to what the counters were taken on); the same for a variant of
+the workload in which nearly every candidate is valid; measured FMA and write ceilings; and
+the CPU oracle timed on this host for the same calls.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -26,19 +31,69 @@ if ROOT not in sys.path:
 # (stage time, two transfers, sum, max, all-reduce, update, price, egress) plus 15 for
 # the epilogue, with P the mean pipeline depth over the candidate space
 FLOPS_PER_STAGE, FLOPS_EPILOGUE = 12.0, 15.0
-PEAK_FP32_VECTOR_TFLOPS = 157.3
-# HBM bytes per scan launch on this workload from rocprofv3 FETCH_SIZE / WRITE_SIZE, each
-# scaled by a 1 GiB copy of the same run (profiles/k_units_scan_cfg4_counters.md); set to
-# None whenever k_units changes after the counters were taken (how many scan units are cut
-# into parts depends on times measured at plan creation, so the figures move by a percent or
-# two between runs)
-SCAN_TRAFFIC_BYTES = 5.79e6
-# VALU wave-instructions the scan executes per launch on this workload (SQ_INSTS_VALU, same
-# file and same rule); each occupies one of the 1 024 SIMDs for 4 cycles at 2.4 GHz
-SCAN_VALU_WAVE_INSTS = 1.081e7
-SIMDS, CLOCK_HZ, CYCLES_PER_WAVE_INST = 1024, 2.4e9, 4
+# vector ALU of the part: 256 compute units x 4 SIMDs x 16 lanes at 2.4 GHz issue 39.3 T
+# lane-operations/s; an FMA counts two flops (78.6 TFLOP/s), the published 157.3 TFLOP/s
+# needs packed FP32 instructions, which this build switches off
+CUS, SIMDS_PER_CU, LANES_PER_SIMD, CLOCK_HZ = 256, 4, 16, 2.4e9
+PEAK_LANE_OPS = CUS * SIMDS_PER_CU * LANES_PER_SIMD * CLOCK_HZ / 1e12   # T lane-ops/s
+PEAK_FP32_FMA_TFLOPS, PEAK_FP32_PACKED_TFLOPS = 78.6, 157.3
+PEAK_HBM_GBPS = 8000.0
+# rocprofv3 counter summary of the kernels below, with the hash of the sources it was taken on
+COUNTERS_JSON = os.path.join(ROOT, "profiles", "kernel_counters.json")
+HASHED_SOURCES = ["paper_2504_17096_amd/csrc/sailor_kernels.hip.h",
+                  "paper_2504_17096_amd/csrc/sailor_dev.h",
+                  "paper_2504_17096_amd/csrc/sailor.hip"]
 # steps of the timed region between two whose scan dispatch carries start / stop events
 EVENT_EVERY = 8
+
+
+def source_hash() -> str:
+    h = hashlib.sha256()
+    for rel in HASHED_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def load_counters():
+    """(entries by name, note): the committed counter summary, or ({}, why not) when it is
+    missing or was taken on other kernel sources than the ones built now."""
+    if not os.path.exists(COUNTERS_JSON):
+        return {}, "no counter summary committed"
+    with open(COUNTERS_JSON) as f:
+        doc = json.load(f)
+    if doc.get("source_sha256") != source_hash():
+        return {}, "kernel sources changed since the counters were taken"
+    return doc.get("kernels", {}), "profiles/kernel_counters.json, sources unchanged"
+
+
+def alu_roofline(entry, kernel_ms, nominal_flops):
+    """Flat roofline keys of an ALU-bound kernel from its counters (per launch) and its
+    duration in this run.  `achieved` counts every vector instruction as 64 lane-operations."""
+    out = {"bound": "alu", "unit": "T lane-ops/s", "peak": PEAK_LANE_OPS, "kernel_ms": kernel_ms,
+           "achieved": None, "frac": None, "traffic": None}
+    if nominal_flops is not None:
+        nominal = nominal_flops / (kernel_ms * 1e-3) / 1e12
+        out["nominal_tflops"] = nominal  # per-stage definition's work / time: NOT a utilisation
+        out["nominal_work_ratio"] = nominal / PEAK_FP32_PACKED_TFLOPS
+    if not entry:
+        return out
+    c = entry["counters"]
+    valu = c["SQ_INSTS_VALU"]
+    out["achieved"] = valu * 64 / (kernel_ms * 1e-3) / 1e12
+    out["frac"] = out["achieved"] / PEAK_LANE_OPS
+    fp32_flops = (c["SQ_INSTS_VALU_ADD_F32"] + c["SQ_INSTS_VALU_MUL_F32"]
+                  + 2 * c["SQ_INSTS_VALU_FMA_F32"]) * 64
+    out["fp32_op_rate_tflops"] = fp32_flops / (kernel_ms * 1e-3) / 1e12
+    out["fp32_frac_of_78_6"] = out["fp32_op_rate_tflops"] / PEAK_FP32_FMA_TFLOPS
+    out["fp32_frac_of_157_3"] = out["fp32_op_rate_tflops"] / PEAK_FP32_PACKED_TFLOPS
+    out["valu_insts_per_launch"] = valu
+    out["int32_share_of_valu"] = c["SQ_INSTS_VALU_INT32"] / valu
+    out["salu_per_valu"] = c["SQ_INSTS_SALU"] / valu
+    out["lds_conflict_cycles_per_lds_inst"] = c["SQ_LDS_BANK_CONFLICT"] / max(1.0, c["SQ_INSTS_LDS"])
+    out["traffic"] = entry.get("hbm_bytes")
+    out["kernel_us_rocprof"] = entry.get("avg_duration_us")
+    return out
 
 
 def timed_steps(plan, step, steps, sync):
@@ -79,31 +134,68 @@ def mean_pipeline_depth(prob) -> float:
     return wsum / tot
 
 
-def cpu_baseline(prob, n_sample: int) -> dict:
-    """The oracle as it stands, single thread, on uniformly drawn candidates."""
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(prob, prob5, budget, k, n_sample: int, n_snapshots: int) -> dict:
+    """The oracle as it stands on this host: the calls the GPU is timed on (the 64 best plans,
+    the best plan and every candidate's outputs over the whole space; re-plans of an
+    availability stream), sharded over the host's cores by index range, and its
+    single-thread rate on a sample."""
     import numpy as np
-    from oracle.oracle import Oracle
+    from oracle.oracle import MAX_THROUGHPUT, Oracle
+    from paper_2504_17096_amd import workloads
+    cores = os.cpu_count() or 1
+    threads = min(cores, 16)
     orc = Oracle(prob)
     n = orc.num_candidates
+    t0 = time.perf_counter()
+    top = orc.topk(k, MAX_THROUGHPUT, budget, n_threads=threads)
+    t_top = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    best = orc.best(MAX_THROUGHPUT, budget, n_threads=threads)
+    t_best = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    outs = orc.eval_batch(objective=MAX_THROUGHPUT, bound=budget, n_threads=threads)
+    t_eval = time.perf_counter() - t0
+    del outs
+    lat = []
+    for snap in workloads.config5_snapshots(prob5)[:n_snapshots]:
+        t0 = time.perf_counter()
+        Oracle(prob5.with_avail(snap)).best(MAX_THROUGHPUT, n_threads=threads)
+        lat.append(time.perf_counter() - t0)
     idx = np.random.default_rng(12345).integers(0, n, n_sample).astype(np.uint64)
     t0 = time.perf_counter()
     orc.eval_batch(indices=idx, n_threads=1)
-    dt = time.perf_counter() - t0
-    cores = os.cpu_count() or 1
-    threads = min(cores, 16)
-    t0 = time.perf_counter()
-    orc.eval_batch(indices=idx, n_threads=threads)
-    dt_mt = time.perf_counter() - t0
-    return {"value": n_sample / dt, "unit": "candidates/s", "cores": 1, "kind": "oracle",
-            "sample": f"{n_sample} uniformly drawn candidates of the same workload, fp64 C -O2, "
-                      f"evaluation only ({dt:.1f} s)",
-            "all_cores": {"value": n_sample / dt_mt, "threads": threads, "host_cores": cores}}
+    t_one = time.perf_counter() - t0
+    return {"value": n / t_top, "unit": "candidates/s", "cores": threads, "kind": "oracle",
+            "sample": f"the benchmark's own query (the {k} best plans, max throughput under the "
+                      f"budget) over all {n} candidates, fp64 C -O2, {threads} threads by index "
+                      f"range: {t_top:.2f} s",
+            "cpu_model": cpu_model(), "host_cores": cores,
+            "top64_s": t_top, "best_plan_s": t_best, "eval_batch_s": t_eval,
+            "top1_index": top[0].index if top else None,
+            "best_index": best.index if best else None,
+            "replan_stream": {"snapshots": len(lat), "candidates": Oracle(prob5).num_candidates,
+                              "p50_s": float(np.percentile(lat, 50)),
+                              "p99_s": float(np.percentile(lat, 99))},
+            "single_thread": {"candidates_per_s": n_sample / t_one,
+                              "sample": f"{n_sample} uniformly drawn candidates, evaluation only "
+                                        f"({t_one:.1f} s)"}}
 
 
 def sweep(torch, workloads, Plan, MAX_THROUGHPUT, MIN_COST) -> int:
     """Time to the 64 best plans (max throughput under 1.2 x the cheapest plan's cost) and to
-    the best plan, per workload; inputs resident, 32 (top-64) and 30 (best plan) repetitions
-    after 5 warm-up calls."""
+    the best plan, per workload; inputs resident, every call evaluates the whole space; 32
+    (top-64) and 30 (best plan) repetitions after 5 warm-up calls."""
     from paper_2504_17096_amd.binding import sailor_result
     stream = torch.cuda.current_stream().cuda_stream
     base = {"cfg1": workloads.config1(), "cfg2": workloads.config2(), "cfg3": workloads.config3(),
@@ -113,12 +205,14 @@ def sweep(torch, workloads, Plan, MAX_THROUGHPUT, MIN_COST) -> int:
         cases += [(name, p), (name + "+segment_tp", p.with_per_segment_tp()),
                   (name + "+mixed_types", p.with_mixed_types())]
     cases.append(("cfg3+link_profiles", base["cfg3"].with_bw_poly(workloads.bandwidth_poly(base["cfg3"]))))
+    cases.append(("cfg4_dense", workloads.config4_dense()))
     cases.append(("cfg4+segment_tp+mixed_types", base["cfg4"].with_per_segment_tp().with_mixed_types()))
     buf = (sailor_result * 64)()
     for name, p in cases:
         t0 = time.perf_counter()
         plan = Plan(p)
         create_ms = (time.perf_counter() - t0) * 1e3
+        plan.set_incremental(False)
         budget = 1.2 * plan.best_plan(objective=MIN_COST, stream=stream).cost_per_iter
         plan.set_timing(1)
         for _ in range(5):
@@ -139,16 +233,40 @@ def sweep(torch, workloads, Plan, MAX_THROUGHPUT, MIN_COST) -> int:
     return 0
 
 
+def replan_stream(np, Plan, prob, snapshots, stream, incremental):
+    """Latency of set_avail + best_plan over an availability stream, and how many pieces of the
+    space each re-plan evaluated again."""
+    plan = Plan(prob)
+    plan.set_incremental(incremental)
+    plan.best_plan(stream=stream)  # the plan in force before the stream starts
+    lat, evaluated = [], []
+    for snap in snapshots:
+        t0 = time.perf_counter()
+        plan.set_avail(snap)
+        plan.best_plan(stream=stream)
+        lat.append((time.perf_counter() - t0) * 1e3)
+        evaluated.append(plan.last_scan()[0])
+    total = plan.last_scan()[1]
+    plan.destroy()
+    return {"p50_ms": float(np.percentile(lat, 50)), "p99_ms": float(np.percentile(lat, 99)),
+            "units_total": total, "units_evaluated_mean": float(np.mean(evaluated)),
+            "units_evaluated_per_snapshot": evaluated}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--cpu-sample", type=int, default=48_000_000)
+    ap.add_argument("--cpu-sample", type=int, default=16_000_000)
+    ap.add_argument("--cpu-snapshots", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: the top-64 query on every synthetic "
                          "workload and its widened variants, one JSON object per line")
+    ap.add_argument("--only-kernels", action="store_true",
+                    help="profiling runs: only the timed query, the whole-space evaluation and the "
+                         "dense variant (the three kernels the counter summary covers)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -160,9 +278,10 @@ def main() -> int:
               "use --gpus 1", file=sys.stderr)
         return 2
 
+    import numpy as np
     import torch
-    from paper_2504_17096_amd import workloads
-    from paper_2504_17096_amd.binding import MAX_THROUGHPUT, MIN_COST, Plan
+    from paper_2504_17096_amd import microbench, workloads
+    from paper_2504_17096_amd.binding import MAX_THROUGHPUT, MIN_COST, Plan, sailor_result
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -173,7 +292,11 @@ def main() -> int:
     prob = workloads.config4()
     t0 = time.perf_counter()
     plan = Plan(prob)
-    create_ms = (time.perf_counter() - t0) * 1e3
+    create_ms = (time.perf_counter() - t0) * 1e3      # includes the start of the HIP runtime
+    t0 = time.perf_counter()
+    Plan(prob).destroy()
+    create_warm_ms = (time.perf_counter() - t0) * 1e3  # the same problem once more
+    plan.set_incremental(False)  # every timed call evaluates the whole space
     n = plan.num_candidates()
     stream = torch.cuda.current_stream().cuda_stream
     K = 64
@@ -181,8 +304,6 @@ def main() -> int:
     # the budget of the timed query comes from a first pass on the device
     cheapest = plan.best_plan(objective=MIN_COST, stream=stream)
     budget = 1.2 * cheapest.cost_per_iter
-
-    from paper_2504_17096_amd.binding import sailor_result
     buf = (sailor_result * K)()   # results are decoded by the library into this array
 
     def step():
@@ -200,13 +321,12 @@ def main() -> int:
 
     # the selected plans' 1F1B schedules event by event, against the closed form the
     # evaluator uses for T_pp (outside the timed region)
-    import numpy as np
     top_idx = np.array([int(buf[j].index) for j in range(K)], dtype=np.uint64)
     d_idx = torch.from_numpy(top_idx.view(np.int64)).to("cuda:0")
     d_ev = torch.empty(K, dtype=torch.float64, device="cuda:0")
     d_cl = torch.empty(K, dtype=torch.float64, device="cuda:0")
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for i in range(3):
+    for i in range(1 if args.only_kernels else 3):
         e0.record()
         plan.simulate_1f1b(K, d_idx, d_ev, d_cl, stream)
         e1.record()
@@ -219,7 +339,7 @@ def main() -> int:
     # time-to-best-plan (single best plan, tolerance tie rule), outside the timed region
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    reps = 20
+    reps = 1 if args.only_kernels else 20
     for _ in range(reps):
         best = plan.best_plan(objective=MAX_THROUGHPUT, bound=budget, stream=stream)
     best_ms = (time.perf_counter() - t0) / reps * 1e3
@@ -238,27 +358,63 @@ def main() -> int:
         if i:
             eval_ms += plan.last_timing()[1] / 5
     plan.set_timing(0)
+    del tt, cc, mm, kk
 
-    # availability stream: 64 snapshots of the 4-zone x 3-type cluster, a full re-plan
-    # (6 791 040 candidates) at each: latency of set_avail + best_plan
+    # the same query where discarding invalid plans cannot help: resources never bind, nearly
+    # every candidate is a valid plan
+    dense_prob = workloads.config4_dense()
+    pd = Plan(dense_prob)
+    pd.set_incremental(False)
+    budget_d = 1.2 * pd.best_plan(objective=MIN_COST, stream=stream).cost_per_iter
+    pd.set_timing(1)
+    for _ in range(3):
+        pd.topk_raw(K, MAX_THROUGHPUT, budget_d, buf, stream)
+    dense_ms, dense_scan_ms, dense_found = timed_steps(
+        pd, lambda: pd.topk_raw(K, MAX_THROUGHPUT, budget_d, buf, stream), 16, torch.cuda.synchronize)
+    dense_counts = pd.last_counts()
+    dense_units = pd.last_scan()[1]
+    pd.destroy()
+
+    if args.copy_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    if args.only_kernels:
+        print(json.dumps({"only_kernels": True, "candidates": n, "ms_per_step": ms_per_step,
+                          "scan_kernel_ms": scan_ms, "eval_batch_ms": eval_ms,
+                          "dense_time_to_top64_ms": dense_ms, "dense_scan_kernel_ms": dense_scan_ms,
+                          "units_cfg4": plan.last_scan()[1], "units_dense": dense_units,
+                          "source_sha256": source_hash()}))
+        plan.destroy()
+        return 0
+
+    # availability streams on the 4-zone x 3-type cluster (6 791 040 candidates): latency of
+    # set_avail + best_plan per snapshot, with the per-unit minima kept between snapshots and
+    # with a full evaluation at each
     prob5 = workloads.config3()
-    plan5 = Plan(prob5)
-    lat = []
-    for snap in workloads.config5_snapshots(prob5):
-        t0 = time.perf_counter()
-        plan5.set_avail(snap)
-        plan5.best_plan(objective=MAX_THROUGHPUT, stream=stream)
-        lat.append((time.perf_counter() - t0) * 1e3)
-    n5 = plan5.num_candidates()
-    plan5.destroy()
-    replan = {"snapshots": len(lat), "candidates": n5, "p50_ms": float(np.percentile(lat, 50)),
-              "p99_ms": float(np.percentile(lat, 99))}
+    walk, events = workloads.config5_snapshots(prob5), workloads.node_events(prob5)
+    replan = {"snapshots": len(walk),
+              "random_walk_full": replan_stream(np, Plan, prob5, walk, stream, False),
+              "random_walk_incremental": replan_stream(np, Plan, prob5, walk, stream, True),
+              "node_events_full": replan_stream(np, Plan, prob5, events, stream, False),
+              "node_events_incremental": replan_stream(np, Plan, prob5, events, stream, True)}
+    # the same kind of stream on the large workload, where the scan is half of a re-plan
+    events4 = workloads.node_events(prob)
+    replan["cfg4_node_events_full"] = replan_stream(np, Plan, prob, events4, stream, False)
+    replan["cfg4_node_events_incremental"] = replan_stream(np, Plan, prob, events4, stream, True)
+    for v in replan.values():
+        if isinstance(v, dict) and not args.copy_probe:
+            per = v.pop("units_evaluated_per_snapshot")
+            v["units_evaluated_min_max"] = [int(min(per)), int(max(per))]
 
     # the same query on the widened spaces: a TP digit per segment (915 206 400 candidates),
     # replicas of a stage split over two GPU types (5 zones x 10 extended types)
     def widened(problem, reps):
         p = Plan(problem)
-        t0 = time.perf_counter()
+        p.set_incremental(False)
         b = 1.2 * p.best_plan(objective=MIN_COST, stream=stream).cost_per_iter
         p.set_timing(1)
         for _ in range(2):
@@ -273,24 +429,35 @@ def main() -> int:
     segtp = widened(prob.with_per_segment_tp(), 16)
     mixed = widened(prob.with_mixed_types(), 16)
 
-    if args.copy_probe:
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").fill_(1.0)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+    # measured ceilings: scalar-per-lane FMA chain, streaming 16-byte stores
+    fma_tflops, _ = microbench.fma(stream=stream)
+    write_gbps, _ = microbench.write(stream=stream)
 
     pbar = mean_pipeline_depth(prob)
     flops_per_cand = FLOPS_PER_STAGE * pbar + FLOPS_EPILOGUE
-    achieved = flops_per_cand * n / (scan_ms * 1e-3) / 1e12
-    valu = None
-    if SCAN_VALU_WAVE_INSTS is not None:
-        issue_ms = SCAN_VALU_WAVE_INSTS * CYCLES_PER_WAVE_INST / SIMDS / CLOCK_HZ * 1e3
-        valu = {"wave_insts_per_launch": SCAN_VALU_WAVE_INSTS, "issue_ms": issue_ms,
-                "frac_of_kernel_time": issue_ms / scan_ms}
+    counters, counters_note = load_counters()
+    roof = alu_roofline(counters.get("scan_cfg4"), scan_ms, flops_per_cand * n)
+    roof.update({"kernel": "k_units<SCAN>", "counters": counters_note,
+                 "peak_note": "256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one vector instruction per "
+                              "lane and cycle; an FMA is one such instruction (78.6 TFLOP/s), "
+                              "157.3 TFLOP/s needs packed FP32, switched off in this build",
+                 "measured_fma_chain_tflops": fma_tflops,
+                 "measured_clock_ghz": fma_tflops * 1e12 / (2 * CUS * SIMDS_PER_CU * LANES_PER_SIMD) / 1e9,
+                 "flops_per_candidate_nominal": flops_per_cand})
+    roof_dense = alu_roofline(counters.get("scan_cfg4_dense"), dense_scan_ms, flops_per_cand * n)
+    roof_dense.update({"kernel": "k_units<SCAN>", "workload": "cfg4_dense"})
+    eval_entry = counters.get("eval_rows_cfg4")
+    roof_eval = {"bound": "hbm", "kernel": "k_eval_rows", "unit": "GB/s",
+                 "achieved": 20.0 * n / (eval_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBPS,
+                 "frac": 20.0 * n / (eval_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+                 "traffic": eval_entry.get("hbm_bytes") if eval_entry else None,
+                 "kernel_ms": eval_ms, "measured_stream_write_GBps": write_gbps,
+                 "frac_of_measured_write": 20.0 * n / (eval_ms * 1e-3) / 1e9 / write_gbps,
+                 "valu_insts_per_candidate": (eval_entry["counters"]["SQ_INSTS_VALU"] * 64 / n
+                                              if eval_entry else None)}
     out = {
-        "metric": "candidate plans evaluated/sec (full hot path incl. top-64 selection)",
+        "metric": "candidate plans evaluated/sec (whole space decided per step, top-64 selection "
+                  "included) and time-to-best-plan",
         "value": n / (ms_per_step * 1e-3), "unit": "candidates/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -299,22 +466,27 @@ def main() -> int:
                                "8 layer splits per pp, <=3 segments",
                    "candidates": n, "objective": "max throughput s.t. cost <= 1.2 x cheapest",
                    "top_k": K, "mean_pipeline_depth": pbar},
-        "roofline": {"bound": "alu", "kernel": "k_units<SCAN>", "achieved": achieved,
-                     "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_FP32_VECTOR_TFLOPS, "traffic": SCAN_TRAFFIC_BYTES,
-                     "flops_per_candidate": flops_per_cand, "kernel_ms": scan_ms,
-                     "valu_issue": valu},
+        "roofline": roof,
+        "roofline_dense": roof_dense,
+        "roofline_eval_batch": roof_eval,
         "extra": {"time_to_top64_ms": ms_per_step, "time_to_best_plan_ms": best_ms,
                   "scan_kernel_ms": scan_ms,
-                  "eval_batch_ms": eval_ms,
-                  "eval_batch_candidates_per_s": n / (eval_ms * 1e-3),
-                  "eval_batch_output_GBps": 20.0 * n / (eval_ms * 1e-3) / 1e9,
-                  "plan_create_ms": create_ms, "replan_stream": replan,
-                  "per_segment_tp": segtp, "mixed_types": mixed, "event_schedule_top64": event_sched, "survivors_refined_valid": list(counts), "best_index": best.index,
+                  "every_candidate_evaluated": {
+                      "eval_batch_ms": eval_ms,
+                      "eval_batch_candidates_per_s": n / (eval_ms * 1e-3),
+                      "dense_time_to_top64_ms": dense_ms, "dense_scan_kernel_ms": dense_scan_ms,
+                      "dense_candidates_per_s": n / (dense_ms * 1e-3),
+                      "dense_found": dense_found,
+                      "dense_survivors_refined_valid": list(dense_counts)},
+                  "plan_create_ms": create_ms, "plan_create_warm_ms": create_warm_ms,
+                  "replan_stream": replan,
+                  "per_segment_tp": segtp, "mixed_types": mixed,
+                  "event_schedule_top64": event_sched,
+                  "survivors_refined_valid": list(counts), "best_index": best.index,
                   "top1_index": top1_index},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(prob, args.cpu_sample)
+        out["cpu_baseline"] = cpu_baseline(prob, prob5, budget, K, args.cpu_sample, args.cpu_snapshots)
     plan.destroy()
     print(json.dumps(out))
     return 0

@@ -202,18 +202,20 @@ sailor_status sailor_plan_set_avail(sailor_plan *plan, const int32_t *avail);
  * H2, Sec. 4.2.1: what does not depend on the availability is reused).  The library keeps, for
  * every piece of the space (one layer split and cut, one TP degree per segment, a range of
  * pools), the best key of its last full evaluation.  While the query (objective and bound) stays
- * the same, sailor_best_plan / sailor_topk evaluate again only the pieces whose quota checks
- * can have changed: those that read a row of the quota table (GPUs one replica takes from a
- * pool -> data-parallel degrees that fit) in which some pool's entry differs from the table of
- * their last evaluation -- an integer-only comparison made while the new table is built.  The
- * other pieces contribute their kept minima.  Results are identical to a full evaluation.
+ * the same, sailor_best_plan / sailor_topk evaluate again only the pieces in which some plan's
+ * validity can have changed: a piece gathers, as always, the bits that say for which
+ * data-parallel degrees each of its segments fits each pool (memory, quota, node size, batch),
+ * compares them with those of its last evaluation -- integers only -- and is evaluated again
+ * only if one differs.  The other pieces contribute their kept minima.  Results are identical
+ * to a full evaluation.  (sailor_plan_last_scan copies a small per-piece table from the device
+ * and waits for it.)
  * on = 1 (default) / 0: off, every call evaluates the whole space. */
 sailor_status sailor_plan_set_incremental(sailor_plan *plan, int32_t on);
 
 /* Pieces of the space the last successful sailor_best_plan / sailor_topk evaluated, and how
  * many there are.  Host pointers, either may be NULL.  SAILOR_EINVAL before the first
  * successful selection. */
-sailor_status sailor_plan_last_scan(const sailor_plan *plan, uint32_t *units_evaluated,
+sailor_status sailor_plan_last_scan(sailor_plan *plan, uint32_t *units_evaluated,
                                     uint32_t *units_total);
 
 /* Number of candidates N. */

@@ -10,6 +10,10 @@ HEADERS = [os.path.join(_HERE, "csrc", "sailor_kernels.hip.h"),
            os.path.join(_HERE, "csrc", "sailor_dev.h"),
            os.path.join(os.path.dirname(_HERE), "include", "sailor.h")]
 LIB = os.path.join(_HERE, "libsailor.so")
+# the calibration kernels of the benchmark (include/sailor_microbench.h), a library of their own
+BENCH_SOURCES = [os.path.join(_HERE, "csrc", "microbench.hip")]
+BENCH_HEADERS = [os.path.join(os.path.dirname(_HERE), "include", "sailor_microbench.h")]
+BENCH_LIB = os.path.join(_HERE, "libsailor_microbench.so")
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
@@ -22,18 +26,23 @@ HIPCC_FLAGS = [
 ]
 
 
-def is_stale() -> bool:
-    if not os.path.exists(LIB):
+def _stale(lib, deps) -> bool:
+    if not os.path.exists(lib):
         return True
-    t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
+    t = os.path.getmtime(lib)
+    return any(os.path.getmtime(f) > t for f in deps)
+
+
+def is_stale() -> bool:
+    return _stale(LIB, SOURCES + HEADERS) or _stale(BENCH_LIB, BENCH_SOURCES + BENCH_HEADERS)
 
 
 def build(force: bool = True, extra_flags=()) -> str:
-    if force or is_stale():
-        hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-        cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-o", LIB, *SOURCES]
-        subprocess.check_call(cmd)
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if force or _stale(LIB, SOURCES + HEADERS):
+        subprocess.check_call([hipcc, *HIPCC_FLAGS, *extra_flags, "-o", LIB, *SOURCES])
+    if force or _stale(BENCH_LIB, BENCH_SOURCES + BENCH_HEADERS):
+        subprocess.check_call([hipcc, *HIPCC_FLAGS, *extra_flags, "-o", BENCH_LIB, *BENCH_SOURCES])
     return LIB
 
 

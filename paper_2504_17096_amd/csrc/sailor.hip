@@ -139,7 +139,9 @@ struct sailor_plan {
   RefRec *staged = nullptr;    // device-side copy of the top-k records before they go to the host
   // re-planning: per-unit minima of the last scan are kept while the query stays the same
   uint32_t *unit_gen = nullptr;   // device, per unit: availability generation of its minima
+  uint32_t *unit_seq = nullptr;   // device, per unit: the call that evaluated it last
   uint32_t *ubits = nullptr;      // device, per unit: validity words as last staged
+  uint32_t last_scan_seq = 0;     // call_seq of the last successful selection's scan
   uint32_t ubits_stride = 0;
   uint32_t avail_gen = 1;         // bumped whenever a new availability table reaches the device
   bool incremental = true;        // sailor_plan_set_incremental
@@ -565,6 +567,8 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
   // the unit reads has changed since (the kernels compare generations per unit)
   sa.unit_gen = pl->unit_gen;
   sa.cur_gen = pl->avail_gen;
+  sa.unit_seq = pl->unit_seq;
+  sa.call_seq = pl->seq + 1;  // the sequence number this call's final kernel will publish
   sa.ubits = pl->incremental ? pl->ubits : nullptr;
   sa.ubits_stride = pl->ubits_stride;
   sa.incremental = (pl->incremental && pl->cache_ok && pl->cache_obj == (int)obj &&
@@ -708,6 +712,7 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
   }
   pl->cache_ok = true;  // the scan completed: every unit's minima and stamp are in place
   pl->last_incremental = was_incremental;
+  pl->last_scan_seq = sa.call_seq;
   if (hdr_out->surv_count > pl->surv_cap || hdr_out->ref_count > pl->ref_cap) return SAILOR_ENOMEM;
   return SAILOR_OK;
 }
@@ -831,8 +836,8 @@ static sailor_status create_impl(const sailor_problem *p, sailor_plan **out, sai
   d.W_max = d.P_max * p->tp_values[TP - 1];
   CREATE_TRY(ar.alloc(&d.qw, (size_t)(d.W_max + 1) * ZG));
   if (d.mixed) CREATE_TRY(ar.alloc(&d.qh, (size_t)(2 * d.W_max + 1) * ZGr));
-  CREATE_TRY(ar.alloc(&d.row_gen, (size_t)d.W_max + 2));
-  CREATE_TRY(hipMemset(d.row_gen, 0, ((size_t)d.W_max + 2) * sizeof(uint32_t)));
+  CREATE_TRY(ar.alloc(&d.row_gen, 1));
+  CREATE_TRY(hipMemset(d.row_gen, 0, sizeof(uint32_t)));
   CREATE_TRY(ar.alloc(&d.h1m, ZG));
   CREATE_TRY(ar.alloc(&d.isect, ZG));
   {
@@ -913,6 +918,8 @@ static sailor_status create_impl(const sailor_problem *p, sailor_plan **out, sai
   CREATE_TRY(ar.alloc(&pl->ulist, unit_cap));
   CREATE_TRY(ar.alloc(&pl->unit_gen, unit_cap));
   CREATE_TRY(hipMemset(pl->unit_gen, 0, unit_cap * sizeof(uint32_t)));
+  CREATE_TRY(ar.alloc(&pl->unit_seq, unit_cap));
+  CREATE_TRY(hipMemset(pl->unit_seq, 0, unit_cap * sizeof(uint32_t)));
   pl->ubits_stride = (uint32_t)(unit_lds_records(ZG, MB) + (size_t)ZG);
   CREATE_TRY(ar.alloc(&pl->ubits, unit_cap * (size_t)pl->ubits_stride));
   CREATE_TRY(ar.alloc(&pl->surv, (size_t)pl->surv_cap));
@@ -1314,11 +1321,26 @@ sailor_status sailor_plan_set_incremental(sailor_plan *pl, int32_t on) {
   return SAILOR_OK;
 }
 
-sailor_status sailor_plan_last_scan(const sailor_plan *pl, uint32_t *units_evaluated,
+sailor_status sailor_plan_last_scan(sailor_plan *pl, uint32_t *units_evaluated,
                                     uint32_t *units_total) {
   if (!pl || !pl->have_hdr) return SAILOR_EINVAL;
   const uint32_t total = (uint32_t)pl->units.size();
-  if (units_evaluated) *units_evaluated = pl->last_incremental ? pl->last_hdr.rescanned : total;
+  if (units_evaluated) {
+    *units_evaluated = total;
+    if (pl->last_incremental) {
+      // every unit carries the number of the call that evaluated it last; they are counted
+      // here, off the selection's own path
+      HIP_TRY(hipSetDevice(pl->device));
+      uint32_t *seq = new (std::nothrow) uint32_t[total];
+      if (!seq) return SAILOR_ENOMEM;
+      const hipError_t e = hipMemcpy(seq, pl->unit_seq, total * sizeof(uint32_t), hipMemcpyDeviceToHost);
+      uint32_t n = 0;
+      for (uint32_t i = 0; i < total; ++i) n += seq[i] == pl->last_scan_seq ? 1u : 0u;
+      delete[] seq;
+      HIP_TRY(e);
+      *units_evaluated = n;
+    }
+  }
   if (units_total) *units_total = total;
   return SAILOR_OK;
 }

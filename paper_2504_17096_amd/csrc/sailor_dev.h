@@ -77,8 +77,7 @@ struct ResultHeader {   // written by the final kernel into host-mapped memory
   uint32_t n_found, surv_count, ref_count, feasible_count;
   uint32_t gmin_bits;  // smallest strict fp32 key of the scan
   uint32_t seq;        // the call's sequence number, written last: the results are complete
-  uint32_t rescanned;  // units an incremental scan evaluated again
-  uint32_t pad;
+  uint32_t pad[2];
 };
 
 struct DevPlan {
@@ -112,8 +111,7 @@ struct DevPlan {
   uint32_t *qw;                // [W_max + 1][ZG] bit d: dpv[d] replicas of w GPUs fit the pool
                                // (a pair: half of them on each type, dpv[d] even)
   uint32_t *qh;                // [2 W_max + 1][ZGr] bit d: dpv[d] * x half-GPUs fit the real pool
-  uint32_t *row_gen;           // [W_max + 2] availability generation at which row w of qw last
-                               // changed; the last entry: any entry of qh
+  uint32_t *row_gen;           // [1] availability generation at which an entry of qh last changed
   uint32_t *h1m;               // [ZG] bit k: tpv[k] exceeds the node size of the pool's type(s) (H1)
   const uint16_t *xt;          // [GX] the two real types of an extended type: a | b << 8
   uint64_t *isect;             // [ZG] bit q: pools p and q draw on a common real pool

@@ -358,10 +358,9 @@ __device__ __forceinline__ void acc_finish(const Acc &p, const LaneC &lc, float 
 // A pool that is a pair of types gives half of the replicas from each (an even number of
 // them); qh serves plans whose segments draw on one real pool together: x half-GPUs per
 // replica of the plan fit the real pool for the degrees whose bit is set.
-// gen: the availability generation (0 while the plan is built).  A row of qw (GPUs per
-// replica) that changes in any pool is stamped with gen in row_gen, so that a scan can tell
-// which units' validity bits are still those of their last evaluation; row_gen[W_max + 1]
-// stands for the whole of qh.
+// gen: the availability generation (0 while the plan is built); when an entry of qh changes,
+// row_gen[0] receives it, so that a scan can tell whether the shared-pool checks of a unit's
+// last evaluation still hold.
 __global__ void k_quota_table(DevPlan pl, const int32_t *avail, int32_t *avail_copy, uint32_t gen) {
   // avail: the table to build from -- pl.avail, or a newer one in host-mapped memory, which
   // is then also copied to avail_copy (= pl.avail) for the kernels that read it later; that
@@ -380,12 +379,7 @@ __global__ void k_quota_table(DevPlan pl, const int32_t *avail, int32_t *avail_c
                    : (D % 2 == 0 && (int64_t)w * D <= 2 * avail_a && (int64_t)w * D <= 2 * avail_b))
         bits |= 1u << d;
     }
-    if (gen == 0u) {
-      pl.qw[i] = bits;
-    } else if (pl.qw[i] != bits) {
-      pl.qw[i] = bits;
-      atomicMax(&pl.row_gen[w], gen);
-    }
+    pl.qw[i] = bits;
   }
   if (!pl.mixed) return;
   const int nh = (2 * pl.W_max + 1) * pl.ZGr;
@@ -399,7 +393,7 @@ __global__ void k_quota_table(DevPlan pl, const int32_t *avail, int32_t *avail_c
       pl.qh[i] = bits;
     } else if (pl.qh[i] != bits) {
       pl.qh[i] = bits;
-      atomicMax(&pl.row_gen[pl.W_max + 1], gen);
+      atomicMax(&pl.row_gen[0], gen);
     }
   }
 }
@@ -454,9 +448,10 @@ struct ScanArgs {
                             // how many; the grid then strides over the list
   uint32_t *unit_gen;       // SCAN, optional: per unit, the availability generation its minima
   uint32_t cur_gen;         // were computed at; a scan stamps what it computes with cur_gen
-  int incremental;          // SCAN: units whose quota rows have not changed since their stamp,
-                            // or whose validity bits come out as they were, keep their minima
-                            // and are not evaluated again
+  uint32_t *unit_seq;       // SCAN, with unit_gen: per unit, the call that evaluated it last
+  uint32_t call_seq;
+  int incremental;          // SCAN: units whose validity bits come out as they were at their
+                            // last evaluation keep their minima and are not evaluated again
   uint32_t *ubits;          // SCAN, with unit_gen: per unit, the validity bits of its records
   uint32_t ubits_stride;    // (and the shared-pool quota words) as last staged; words per unit
   uint32_t *near_list;      // SCAN, optional (best plan): units whose loose minimum lies within
@@ -469,7 +464,6 @@ enum Counter { CNT_SURV = 0, CNT_REF = 1, CNT_FEAS = 2, CNT_GMIN = 3, CNT_TAU0 =
                CNT_NLOOSE = 6, CNT_NSTRICT = 7,  // count-only collect passes
                CNT_NLIST = 8,                    // length of the collect pass's unit list
                CNT_DONE = 9,                     // workgroups of the final kernel that have finished
-               CNT_RESCAN = 10,                  // units an incremental scan evaluated again
                CNT_COUNT = 16 };
 
 __device__ __forceinline__ uint32_t counter_reset_value(int i) {
@@ -483,7 +477,7 @@ __global__ void k_zero_counters(uint32_t *c, uint32_t mask) {
 }
 
 __global__ void k_init_counters(uint32_t *c, int n) {
-  if ((int)threadIdx.x < n) c[threadIdx.x] = counter_reset_value(threadIdx.x);
+  for (int i = threadIdx.x; i < n; i += blockDim.x) c[i] = counter_reset_value(i);
 }
 
 // One candidate of the scan: update the running minima, or append it to the survivors.
@@ -733,25 +727,12 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
   const int k0 = u.tp[0], k1 = u.tp[1], k2 = u.tp[2];            // tp index of each segment
   const int tv0 = pl.tpv[k0], tv1 = pl.tpv[k1], tv2 = pl.tpv[k2];
   const int w0 = n0 * tv0, w1 = n1 * tv1, w2 = n2 * tv2;        // GPUs of one replica
-  bool joint_changed = false;  // (MIXED) the shared-pool table changed: no cheaper test exists
-  if (MODE == MODE_SCAN && a.incremental) {
-    // Re-planning after an availability change: the unit's minima of the last scan still hold
-    // if no quota row it reads (GPUs per replica of its segments; segments 1 and 3 on one pool)
-    // has changed since.  Uniform over the workgroup.  A unit that fails this test is staged
-    // and its validity bits are compared with those of its last evaluation.
-    const uint32_t stamp = a.unit_gen[uidx];
-    uint32_t changed = pl.row_gen[w0];
-    if (S >= 2) changed = max(changed, pl.row_gen[w1]);
-    if (S == 3) changed = max(changed, max(pl.row_gen[w2], pl.row_gen[w0 + w2]));
-    if (MIXED && S >= 2) {
-      joint_changed = pl.row_gen[pl.W_max + 1] > stamp;
-      changed = max(changed, pl.row_gen[pl.W_max + 1]);
-    }
-    if (changed <= stamp) {
-      if (t == 0) unit_publish(a, uidx, a.umin_s[uidx], a.umin_l[uidx]);
-      return;
-    }
-  }
+  // Re-planning after an availability change: the unit is staged as always, and if every
+  // validity word comes out as at its last evaluation its minima still hold.  With pairs of
+  // types the shared-pool table is read during the evaluation, not the staging: a unit of two
+  // or three segments is evaluated again whenever that table has changed since.
+  const bool joint_changed = MIXED && MODE == MODE_SCAN && a.incremental && S >= 2 &&
+                             pl.row_gen[0] > a.unit_gen[uidx];
   const bool keep_bits = MODE == MODE_SCAN && a.ubits != nullptr;
   uint32_t *const ub = keep_bits ? a.ubits + (size_t)uidx * a.ubits_stride : nullptr;
   uint32_t any_here = 0;
@@ -807,10 +788,7 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
   for (int w = 0; w < (int)(blockDim.x >> 6); ++w) any_all |= s_any[w];
   if (MODE == MODE_SCAN && a.incremental && !(any_all & 8u) && !joint_changed) {
     // every validity bit is what it was: the minima still hold (uniform over the workgroup)
-    if (t == 0) {
-      a.unit_gen[uidx] = a.cur_gen;
-      unit_publish(a, uidx, a.umin_s[uidx], a.umin_l[uidx]);
-    }
+    if (t == 0) unit_publish(a, uidx, a.umin_s[uidx], a.umin_l[uidx]);
     return;
   }
   any_all &= 7u;
@@ -820,7 +798,7 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
       a.umin_l[uidx] = kPosInf;
       if (a.unit_gen) {
         a.unit_gen[uidx] = a.cur_gen;
-        if (a.incremental) atomicAdd(&a.counters[CNT_RESCAN], 1u);
+        a.unit_seq[uidx] = a.call_seq;  // evaluated by this call
       }
       if (a.ucost) a.ucost[uidx] = (float)(wall_clock64() - t_begin);
     }
@@ -852,7 +830,7 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
       a.umin_l[uidx] = ml;
       if (a.unit_gen) {
         a.unit_gen[uidx] = a.cur_gen;
-        if (a.incremental) atomicAdd(&a.counters[CNT_RESCAN], 1u);
+        a.unit_seq[uidx] = a.call_seq;  // evaluated by this call
       }
       unit_publish(a, uidx, ms, ml);
       if (a.ucost) a.ucost[uidx] = (float)(wall_clock64() - t_begin);
@@ -1355,7 +1333,6 @@ __global__ __launch_bounds__(1024) void k_pick_best(const RefRec *ref, uint32_t 
     hdr->ref_count = n_ref;
     hdr->feasible_count = n_feas;
     hdr->gmin_bits = gmin;
-    hdr->rescanned = counters[CNT_RESCAN];
     publish(hdr, seq);
   }
 }
@@ -1398,7 +1375,6 @@ __global__ __launch_bounds__(kRankLds) void k_rank_topk(const RefRec *ref, uint3
     hdr->ref_count = n_ref;
     hdr->feasible_count = f;
     hdr->gmin_bits = counters[CNT_GMIN];
-    hdr->rescanned = counters[CNT_RESCAN];
   }
   if (overflow) {  // the host turns ref_count > ref_cap into SAILOR_ENOMEM
     if (gridDim.x == 1) {

@@ -314,6 +314,15 @@ def config4(seed: int = 4, seg3_max_pp: int = 4) -> Problem:
         notes={"objective": "min cost s.t. throughput floor; max throughput s.t. budget; top-64"})
 
 
+def config4_dense(seed: int = 4) -> Problem:
+    """The fourth workload with resources that never bind: 100 000 GPUs in every pool and GPU
+    memory no plan can exhaust, so that nearly every candidate is a valid plan (only batch
+    divisibility rules some out) and an evaluator cannot gain from discarding invalid ones."""
+    p = config4(seed)
+    return replace(p, name="cfg4_dense", avail=np.full_like(p.avail, 100_000),
+                   mem_capacity=np.full_like(p.mem_capacity, 10 ** 15))
+
+
 def config5_snapshots(base: Problem, n_snapshots: int = 64, seed: int = 5) -> List[np.ndarray]:
     """Availability stream for a cluster: every (zone, type) count follows a +-25 %
     multiplicative random walk clamped to [0, 128]; each zone is, independently per
