@@ -19,6 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # the mutation tests point this at a copy of the sources with a planted mistake
 _DIR = os.environ.get("SAILOR_ORACLE_DIR", _HERE)
 _SRC = os.path.join(_DIR, "sailor_oracle.c")
+_SRC_SEARCH = os.path.join(_DIR, "sailor_search_oracle.c")
 _LIB = os.path.join(_DIR, "libsailor_oracle.so")
 
 MAX_THROUGHPUT, MIN_COST = 0, 1
@@ -27,12 +28,11 @@ BIT_OOM, BIT_QUOTA, BIT_BATCH, BIT_TP_NODE, BIT_CONSTRAINT = 1, 2, 4, 8, 32
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, no intrinsics)."""
-    stale = (not os.path.exists(_LIB)
-             or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
-             or os.path.getmtime(_LIB) < os.path.getmtime(os.path.join(_DIR, "sailor_oracle.h")))
+    deps = [_SRC, _SRC_SEARCH, os.path.join(_DIR, "sailor_oracle.h")]
+    stale = not os.path.exists(_LIB) or any(os.path.getmtime(_LIB) < os.path.getmtime(d) for d in deps)
     if force or stale:
         subprocess.check_call(["gcc", "-O2", "-std=c99", "-Wall", "-shared", "-fPIC", "-o", _LIB,
-                               _SRC, "-lpthread", "-lm"])
+                               _SRC, _SRC_SEARCH, "-lpthread", "-lm"])
     return _LIB
 
 
@@ -89,6 +89,35 @@ class Config:
     seg_tp_idx: tuple = (-1, -1, -1)
 
 
+class _SearchResult(C.Structure):
+    _fields_ = [("found", C.c_int32), ("truncated", C.c_int32), ("pp_idx", C.c_int32),
+                ("partition", C.c_int32), ("tp_idx", C.c_int32), ("dp_idx", C.c_int32),
+                ("mb_idx", C.c_int32), ("pp", C.c_int32), ("expanded", C.c_uint64),
+                ("key", C.c_double), ("iter_time", C.c_double), ("cost", C.c_double),
+                ("pools", C.c_int32 * 256)]
+
+
+class _SearchOpts(C.Structure):
+    _fields_ = [("beam_width", C.c_int32), ("max_runs", C.c_int32), ("has_incumbent", C.c_int32),
+                ("incumbent", C.c_double)]
+
+
+@dataclass
+class StagePlan:
+    """A plan whose stages choose their pools freely."""
+    pp_idx: int
+    partition: int
+    tp_idx: int
+    dp_idx: int
+    mb_idx: int
+    pools: tuple
+    key: float
+    iter_time: float
+    cost: float
+    truncated: bool = False
+    expanded: int = 0
+
+
 @dataclass
 class Eval:
     index: int
@@ -125,8 +154,24 @@ def _load():
                                 C.c_int, C.POINTER(_Eval)]
         lib.so_topk.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_int, C.c_int, C.c_double,
                                 C.c_int, C.c_int, C.POINTER(_Eval)]
+        lib.so_eval_assignment.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                           C.c_void_p, C.c_int, C.c_int, C.c_double, C.POINTER(_Eval)]
+        lib.so_search_exhaustive.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, C.c_int,
+                                             C.POINTER(_SearchResult)]
+        lib.so_search_beam.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, C.POINTER(_SearchOpts),
+                                       C.POINTER(_SearchResult)]
+        lib.so_search_prefix_bound.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                               C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_double),
+                                               C.POINTER(C.c_double)]
         _lib = lib
     return _lib
+
+
+def _stage_plan(r: _SearchResult) -> Optional[StagePlan]:
+    if not r.found:
+        return None
+    return StagePlan(r.pp_idx, r.partition, r.tp_idx, r.dp_idx, r.mb_idx, tuple(r.pools[:r.pp]),
+                     r.key, r.iter_time, r.cost, bool(r.truncated), int(r.expanded))
 
 
 def _cfg(c: _Config) -> Config:
@@ -273,6 +318,49 @@ class Oracle:
         if rc != 0:
             raise IndexError((first, count))
         return t, c, m, k
+
+    def eval_assignment(self, pp_idx: int, partition: int, dp_idx: int, mb_idx: int, tp_idx: int,
+                        pools, objective: int = MAX_THROUGHPUT, bound: Optional[float] = None) -> Eval:
+        a = np.ascontiguousarray(pools, dtype=np.int32)
+        e = _Eval()
+        rc = self._lib.so_eval_assignment(self._ctx, pp_idx, partition, dp_idx, mb_idx, tp_idx,
+                                          a.ctypes.data, objective, bound is not None,
+                                          0.0 if bound is None else bound, C.byref(e))
+        if rc != 0:
+            raise ValueError("assignment out of range")
+        return _ev(e)
+
+    def search_exhaustive(self, objective: int = MAX_THROUGHPUT, bound: Optional[float] = None,
+                          max_runs: int = 0) -> Optional[StagePlan]:
+        r = _SearchResult()
+        rc = self._lib.so_search_exhaustive(self._ctx, objective, bound is not None,
+                                            0.0 if bound is None else bound, max_runs, C.byref(r))
+        if rc != 0:
+            raise ValueError("the search does not cover this problem")
+        return _stage_plan(r)
+
+    def search_beam(self, beam_width: int, objective: int = MAX_THROUGHPUT,
+                    bound: Optional[float] = None, max_runs: int = 0,
+                    incumbent: Optional[float] = None) -> Optional[StagePlan]:
+        r = _SearchResult()
+        o = _SearchOpts(beam_width, max_runs, incumbent is not None,
+                        0.0 if incumbent is None else incumbent)
+        rc = self._lib.so_search_beam(self._ctx, objective, bound is not None,
+                                      0.0 if bound is None else bound, C.byref(o), C.byref(r))
+        if rc != 0:
+            raise ValueError("the search does not cover this problem")
+        self.last_search = (bool(r.truncated), int(r.expanded))
+        return _stage_plan(r)
+
+    def prefix_bound(self, pp_idx: int, partition: int, dp_idx: int, mb_idx: int, tp_idx: int,
+                     pools, n_placed: int, objective: int = MAX_THROUGHPUT):
+        """(lower bound on T_iter, on C_iter) of the completions of the first n_placed stages'
+        placement, or None when the prefix itself is not admissible."""
+        a = np.ascontiguousarray(pools, dtype=np.int32)
+        t, c = C.c_double(), C.c_double()
+        rc = self._lib.so_search_prefix_bound(self._ctx, pp_idx, partition, dp_idx, mb_idx, tp_idx,
+                                              a.ctypes.data, n_placed, objective, C.byref(t), C.byref(c))
+        return None if rc != 0 else (t.value, c.value)
 
     def best(self, objective: int = MAX_THROUGHPUT, bound: Optional[float] = None,
              first: int = 0, count: Optional[int] = None, n_threads: int = 1) -> Optional[Eval]:

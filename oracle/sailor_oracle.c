@@ -287,12 +287,14 @@ static double link_bandwidth(const so_problem *p, int a, int b, double bytes) {
   return v;
 }
 
-static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int objective,
-                        int has_bound, double bound, so_eval *out) {
+/* The simulator proper.  A plan is given stage by stage: pool_of[i] (zone * G' + extended
+ * type) and the TP degree of stage i (tp_of[i], its list index tpi_of[i]); nl = layers per
+ * stage; D, mb (list index mb_idx) as in the plan tuple. */
+static void eval_stages(const so_ctx *c, int P, const int32_t *nl, const int *pool_of,
+                        const int *tp_of, const int *tpi_of, int64_t D, int64_t mb, int mb_idx,
+                        uint64_t index, int objective, int has_bound, double bound, so_eval *out) {
   const so_problem *p = &c->p;
-  const int P = g->pp, G = p->n_types, Z = p->n_zones;
-  const int64_t D = g->dp, mb = g->mb;
-  const int32_t *nl = partition_row(c, g);
+  const int G = p->n_types, Z = p->n_zones;
   out->index = index;
   out->mask = 0;
   out->peak_mem = 0;
@@ -308,20 +310,16 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
 
   /* the stage's replicas are of type type_of[i], or half of them of type type_b[i] */
   int type_of[SO_MAX_STAGES], type_b[SO_MAX_STAGES], zone_of[SO_MAX_STAGES], first_layer[SO_MAX_STAGES];
-  int tp_of[SO_MAX_STAGES], tpi_of[SO_MAX_STAGES]; /* TP degree of the stage and its list index */
   /* GPUs that one replica of the plan takes from every real (zone, type) pool, counted in
    * halves: a stage whose replicas are split over two types takes half a replica from each */
   int64_t half_gpus_on_pool[SO_MAX_POOLS];
   memset(half_gpus_on_pool, 0, sizeof half_gpus_on_pool);
   int layer = 0;
   for (int i = 0; i < P; ++i) {
-    int seg = (i < g->cut[0]) ? 0 : (i < g->cut[1]) ? 1 : 2;
-    int pool = g->pool[seg];
+    int pool = pool_of[i];
     type_of[i] = c->xa[pool % c->GX];
     type_b[i] = c->xb[pool % c->GX];
     zone_of[i] = pool / c->GX;
-    tp_of[i] = g->seg_tp[seg];
-    tpi_of[i] = g->seg_tp_idx[seg];
     if (type_b[i] == type_of[i]) {
       half_gpus_on_pool[zone_of[i] * G + type_of[i]] += 2 * tp_of[i];
     } else {
@@ -355,7 +353,7 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
     uint64_t m_model = shard * (uint64_t)p->bytes_per_param;
     int64_t inflight = (P - i) < Nb ? (P - i) : Nb; /* 1F1B: microbatches kept alive */
     uint64_t m_act = (uint64_t)inflight * (uint64_t)nl[i] *
-                     p->act_store_bytes[(size_t)g->mb_idx * p->n_tp + tpi_of[i]];
+                     p->act_store_bytes[(size_t)mb_idx * p->n_tp + tpi_of[i]];
     uint64_t m = m_model + m_act + p->mem_reserved[type_of[i]];
     if (m > p->mem_capacity[type_of[i]]) out->mask |= SO_BIT_OOM;
     if (m > peak) peak = m;
@@ -368,15 +366,15 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
   out->peak_mem = peak;
 
   /* stage times: compute plus activation / gradient transfers to the neighbours */
-  const double p2p = (double)p->p2p_bytes[g->mb_idx];
+  const double p2p = (double)p->p2p_bytes[mb_idx];
   double sum_t = 0.0, max_t = 0.0, t_sync = 0.0, t_upd = 0.0;
   for (int i = 0; i < P; ++i) {
     int gt = type_of[i], z = zone_of[i];
-    double f = layer_time_sum(p, p->t_fwd, gt, g->mb_idx, tpi_of[i], first_layer[i], nl[i]);
-    double b = layer_time_sum(p, p->t_bwd, gt, g->mb_idx, tpi_of[i], first_layer[i], nl[i]);
+    double f = layer_time_sum(p, p->t_fwd, gt, mb_idx, tpi_of[i], first_layer[i], nl[i]);
+    double b = layer_time_sum(p, p->t_bwd, gt, mb_idx, tpi_of[i], first_layer[i], nl[i]);
     if (type_b[i] != gt) { /* the slower replica type sets the stage's pace (straggler, Sec. 4.3) */
-      double f2 = layer_time_sum(p, p->t_fwd, type_b[i], g->mb_idx, tpi_of[i], first_layer[i], nl[i]);
-      double b2 = layer_time_sum(p, p->t_bwd, type_b[i], g->mb_idx, tpi_of[i], first_layer[i], nl[i]);
+      double f2 = layer_time_sum(p, p->t_fwd, type_b[i], mb_idx, tpi_of[i], first_layer[i], nl[i]);
+      double b2 = layer_time_sum(p, p->t_bwd, type_b[i], mb_idx, tpi_of[i], first_layer[i], nl[i]);
       if (f2 + b2 > f + b) { f = f2; b = b2; }
     }
     double x = 0.0;
@@ -429,6 +427,52 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
     }
   }
 }
+
+/* A plan of the flat space: every stage takes the pool and the TP degree of its segment. */
+static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int objective,
+                        int has_bound, double bound, so_eval *out) {
+  int pool_of[SO_MAX_STAGES];
+  int tp_of[SO_MAX_STAGES], tpi_of[SO_MAX_STAGES]; /* TP degree of the stage and its list index */
+  for (int i = 0; i < g->pp; ++i) {
+    int seg = (i < g->cut[0]) ? 0 : (i < g->cut[1]) ? 1 : 2;
+    pool_of[i] = g->pool[seg];
+    tp_of[i] = g->seg_tp[seg];
+    tpi_of[i] = g->seg_tp_idx[seg];
+  }
+  eval_stages(c, g->pp, partition_row(c, g), pool_of, tp_of, tpi_of, g->dp, g->mb, g->mb_idx, index,
+              objective, has_bound, bound, out);
+}
+
+/* A plan whose stages choose their pools freely (the plan tuple of Sec. 4.2 without the
+ * contiguous-segment restriction of the flat space): pools[i] = zone * G' + extended type of
+ * stage i, one TP degree for all stages.  Returns 0, -1 for a value out of range. */
+int so_eval_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx, int tp_idx,
+                       const int32_t *pools, int objective, int has_bound, double bound,
+                       so_eval *out) {
+  const so_problem *p = &c->p;
+  if (pp_idx < 0 || pp_idx >= p->n_pp || dp_idx < 0 || dp_idx >= p->n_dp || mb_idx < 0 ||
+      mb_idx >= p->n_mb || tp_idx < 0 || tp_idx >= p->n_tp || partition < 0 ||
+      partition >= p->n_partitions[pp_idx])
+    return -1;
+  const int P = p->pp_values[pp_idx];
+  int pool_of[SO_MAX_STAGES], tp_of[SO_MAX_STAGES], tpi_of[SO_MAX_STAGES];
+  for (int i = 0; i < P; ++i) {
+    if (pools[i] < 0 || pools[i] >= c->ZG) return -1;
+    pool_of[i] = pools[i];
+    tp_of[i] = p->tp_values[tp_idx];
+    tpi_of[i] = tp_idx;
+  }
+  so_config g;
+  memset(&g, 0, sizeof g);
+  g.pp_idx = pp_idx;
+  g.pp = P;
+  g.partition = partition;
+  eval_stages(c, P, partition_row(c, &g), pool_of, tp_of, tpi_of, p->dp_values[dp_idx],
+              p->mb_values[mb_idx], mb_idx, 0, objective, has_bound, bound, out);
+  return 0;
+}
+
+const so_problem *so_problem_of(const so_ctx *c) { return &c->p; }
 
 int so_eval_one(const so_ctx *c, uint64_t index, int objective, int has_bound, double bound,
                 so_eval *out) {

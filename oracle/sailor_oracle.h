@@ -139,6 +139,44 @@ int so_best(const so_ctx *c, uint64_t first, uint64_t count, int objective, int 
 int so_topk(const so_ctx *c, uint64_t first, uint64_t count, int objective, int has_bound,
             double bound, int k, int n_threads, so_eval *out);
 
+/* ---- plans whose stages choose their pools freely (Sec. 4.2: a (GPU, TP, zone) choice per
+ * stage; Sec. 4.2.2: resources are assigned stage by stage) -------------------------------- */
+
+/* One such plan through the simulator: pools[i] = zone * G' + extended type of stage i, one TP
+ * degree for all stages.  0 ok, -1 value out of range. */
+int so_eval_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx, int tp_idx,
+                       const int32_t *pools, int objective, int has_bound, double bound,
+                       so_eval *out);
+const so_problem *so_problem_of(const so_ctx *c);
+
+#define SO_SEARCH_MAX_STAGES 256
+typedef struct {
+  int32_t found;                 /* 1: a valid plan exists (within the incumbent, if one was given) */
+  int32_t truncated;             /* beam: some frontier was cut to the beam width */
+  int32_t pp_idx, partition, tp_idx, dp_idx, mb_idx, pp;
+  uint64_t expanded;             /* placements generated */
+  double key, iter_time, cost;
+  int32_t pools[SO_SEARCH_MAX_STAGES];
+} so_search_result;
+
+typedef struct {
+  int32_t beam_width;            /* longest frontier kept per sub-problem */
+  int32_t max_runs;              /* 0: any placement; n: at most n runs of equal pools */
+  int32_t has_incumbent;         /* 1: placements whose bound exceeds `incumbent` are dropped */
+  double incumbent;
+} so_search_opts;
+
+/* (sailor_search_oracle.c) sub-problems in the order pp, layer split, TP, D, microbatch size;
+ * equal keys: the first sub-problem, inside it the first placement found.  0 ok, -1 when the
+ * problem uses an option the search does not cover. */
+int so_search_exhaustive(const so_ctx *c, int objective, int has_bound, double bound, int max_runs,
+                         so_search_result *out);
+int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
+                   const so_search_opts *opt, so_search_result *out);
+int so_search_prefix_bound(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                           int tp_idx, const int32_t *pools, int n_placed, int objective,
+                           double *lb_time, double *lb_cost);
+
 #ifdef __cplusplus
 }
 #endif

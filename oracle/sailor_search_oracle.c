@@ -1,0 +1,388 @@
+/*
+ * CPU oracle of the search over per-stage placements -- TEST INFRASTRUCTURE ONLY.
+ *
+ * The planner assigns resources stage by stage (Sec. 4.2.2, Eq. (1): give stage i resources
+ * r, leave R - r to the stages behind it, compose the times with T_total).  Here every stage
+ * of a pipeline chooses its pool (zone, GPU type) freely, all D replicas of a stage on that
+ * pool (H5), one TP degree per plan; (P, layer split, TP, D, microbatch size) is a
+ * "sub-problem", as in the planner's outer loops (Sec. 4.2).
+ *
+ *   so_search_exhaustive   the definition: every placement of every sub-problem is evaluated
+ *                          by the plain simulator (so_eval_assignment) and the smallest key
+ *                          over valid plans wins.  Exponential; for tiny problems.
+ *   so_search_beam         the algorithm, step by step: stages are placed in order, a frontier
+ *                          of partial placements per sub-problem, each with a lower bound on
+ *                          the key of every completion; partial placements whose bound exceeds
+ *                          an incumbent (or violates the constraint) are dropped, and a
+ *                          frontier longer than the beam width keeps the placements with the
+ *                          smallest bounds.  While no frontier is cut the result is the
+ *                          optimum (every dropped placement is provably no better than the
+ *                          incumbent); otherwise it is what these steps produce.
+ *
+ * Bound of a partial placement (stages 0..i placed): every term of T_iter and C_iter
+ * (Sec. 4.3) is monotone in the per-stage quantities, so the placed stages contribute what
+ * they are known to cost and every later stage its cheapest admissible choice (memory and
+ * node size respected, quotas ignored), the open stage's forward transfer counted as zero.
+ * At i = P - 1 the bound is the plan's T_iter / C_iter itself, added up in stage order like
+ * the simulator does.
+ *
+ * Pins (tests/test_oracle_search.py): beam with an unbounded width equals the exhaustive
+ * search on tiny problems; restricted to three contiguous runs it equals the flat space's
+ * optimum (so_best); the returned placement re-evaluates to the reported values; a wider beam
+ * is never worse; bounds never exceed the value of any completion.
+ */
+#include "sailor_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define SS_MAX_STAGES 255
+#define SS_MAX_POOLS 64
+
+typedef struct {
+  double sum;      /* stage times of the closed stages 0 .. i-1 */
+  double maxt;     /* slowest closed stage */
+  double c_open;   /* compute time of stage i (its forward transfer is not known yet) */
+  double xb_open;  /* its backward transfer to stage i-1 */
+  double msync, mupd, dol, comm;
+  double lb_key, lb_T, lb_C;
+  uint8_t cnt[SS_MAX_POOLS]; /* stages placed on each pool */
+  uint8_t pool, runs;
+  uint8_t path[SS_MAX_STAGES];
+} ss_state;
+
+typedef struct {
+  /* the sub-problem */
+  int P, G, Z, ZG, tp, tp_idx, mb_idx, dp_idx, pp_idx, partition;
+  int64_t D, Nb;
+  double p2p;
+  /* per stage and type / zone / pool */
+  double c[SS_MAX_STAGES][16], upd[SS_MAX_STAGES][16], dol[SS_MAX_STAGES][16];
+  double sync[SS_MAX_STAGES][16];
+  uint8_t ok[SS_MAX_STAGES][SS_MAX_POOLS];
+  int cap_cnt[SS_MAX_POOLS];      /* stages a pool can host: avail / (tp * D) */
+  double xfer[16][16], comm[16][16];
+  /* cheapest admissible choice of the stages behind stage i */
+  double Ssum[SS_MAX_STAGES], Smax[SS_MAX_STAGES], Ssync[SS_MAX_STAGES], Supd[SS_MAX_STAGES],
+      Sdol[SS_MAX_STAGES];
+} ss_sub;
+
+static double time_sum(const so_problem *p, const double *tab, int g, int im, int it, int first, int n) {
+  if (p->uniform_layers) return (double)n * tab[(((size_t)g * p->n_mb + im) * p->n_tp + it)];
+  const double *row = tab + (((size_t)g * p->n_mb + im) * p->n_tp + it) * p->n_layers;
+  double s = 0.0;
+  for (int l = first; l < first + n; ++l) s += row[l];
+  return s;
+}
+
+static double upd_sum(const so_problem *p, int g, int it, int first, int n) {
+  if (p->uniform_layers) return (double)n * p->t_upd[(size_t)g * p->n_tp + it];
+  const double *row = p->t_upd + ((size_t)g * p->n_tp + it) * p->n_layers;
+  double s = 0.0;
+  for (int l = first; l < first + n; ++l) s += row[l];
+  return s;
+}
+
+static const int32_t *layers_of(const so_problem *p, int pp_idx, int partition) {
+  size_t row = 0;
+  for (int ip = 0; ip < pp_idx; ++ip) row += (size_t)p->n_partitions[ip] * p->pp_values[ip];
+  return p->partition_layers + row + (size_t)partition * p->pp_values[pp_idx];
+}
+
+/* Tables of one sub-problem.  Returns 0 when it cannot hold a valid plan at all (the batch
+ * does not divide, or some stage fits no pool). */
+static int sub_setup(const so_problem *p, ss_sub *s, int pp_idx, int partition, int tp_idx, int dp_idx,
+                     int mb_idx) {
+  s->P = p->pp_values[pp_idx];
+  s->G = p->n_types;
+  s->Z = p->n_zones;
+  s->ZG = s->G * s->Z;
+  s->pp_idx = pp_idx; s->partition = partition; s->tp_idx = tp_idx; s->dp_idx = dp_idx; s->mb_idx = mb_idx;
+  s->tp = p->tp_values[tp_idx];
+  s->D = p->dp_values[dp_idx];
+  const int64_t mb = p->mb_values[mb_idx];
+  if (p->global_batch % (s->D * mb) != 0) return 0;
+  s->Nb = p->global_batch / (s->D * mb);
+  s->p2p = (double)p->p2p_bytes[mb_idx];
+  const int P = s->P, G = s->G, Z = s->Z;
+  const int32_t *nl = layers_of(p, pp_idx, partition);
+  for (int a = 0; a < s->ZG; ++a) s->cap_cnt[a] = (int)((int64_t)p->avail[a] / ((int64_t)s->tp * s->D));
+  for (int z = 0; z < Z; ++z)
+    for (int y = 0; y < Z; ++y) {
+      s->xfer[z][y] = s->p2p / p->bandwidth[(size_t)z * Z + y];
+      s->comm[z][y] = 0.0;
+      if (p->egress_per_byte && z != y)
+        s->comm[z][y] = (double)s->Nb * (double)s->D * s->p2p *
+                        (p->egress_per_byte[(size_t)z * Z + y] + p->egress_per_byte[(size_t)y * Z + z]);
+    }
+  int first = 0;
+  for (int i = 0; i < P; ++i) {
+    uint64_t params = 0;
+    for (int l = first; l < first + nl[i]; ++l) params += p->layer_params[l];
+    if (i == 0) params += p->embed_params;
+    if (i == P - 1) params += p->head_params;
+    const uint64_t shard = (params + (uint64_t)s->tp - 1) / (uint64_t)s->tp;
+    const int64_t alive = (P - i) < s->Nb ? (P - i) : s->Nb;
+    const uint64_t bytes = shard * (uint64_t)p->bytes_per_param +
+                           (uint64_t)alive * (uint64_t)nl[i] *
+                               p->act_store_bytes[(size_t)mb_idx * p->n_tp + tp_idx];
+    for (int g = 0; g < G; ++g) {
+      const double f = time_sum(p, p->t_fwd, g, mb_idx, tp_idx, first, nl[i]);
+      const double b = time_sum(p, p->t_bwd, g, mb_idx, tp_idx, first, nl[i]);
+      s->c[i][g] = f + b;
+      s->upd[i][g] = upd_sum(p, g, tp_idx, first, nl[i]);
+      s->dol[i][g] = (double)(s->D * s->tp) * p->price_per_hour[g];
+      const int fits = bytes + p->mem_reserved[g] <= p->mem_capacity[g] && s->tp <= p->gpus_per_node[g];
+      for (int z = 0; z < Z; ++z) s->ok[i][z * G + g] = (uint8_t)fits;
+    }
+    for (int z = 0; z < Z; ++z) {
+      double sync = 0.0;
+      if (s->D > 1) {
+        const double grad = (double)shard * (double)p->grad_bytes_per_param;
+        sync = 2.0 * (double)(s->D - 1) / (double)s->D * grad / p->bandwidth[(size_t)z * Z + z];
+      }
+      s->sync[i][z] = sync;
+    }
+    first += nl[i];
+  }
+  /* the cheapest admissible choice of every stage, then what lies behind stage i */
+  double cmin[SS_MAX_STAGES], smin[SS_MAX_STAGES], umin[SS_MAX_STAGES], dmin[SS_MAX_STAGES];
+  for (int i = 0; i < P; ++i) {
+    int any = 0;
+    cmin[i] = smin[i] = umin[i] = dmin[i] = INFINITY;
+    for (int a = 0; a < s->ZG; ++a) {
+      if (!s->ok[i][a]) continue;
+      any = 1;
+      const int g = a % G, z = a / G;
+      if (s->c[i][g] < cmin[i]) cmin[i] = s->c[i][g];
+      if (s->sync[i][z] < smin[i]) smin[i] = s->sync[i][z];
+      if (s->upd[i][g] < umin[i]) umin[i] = s->upd[i][g];
+      if (s->dol[i][g] < dmin[i]) dmin[i] = s->dol[i][g];
+    }
+    if (!any) return 0;
+  }
+  s->Ssum[P - 1] = s->Smax[P - 1] = s->Ssync[P - 1] = s->Supd[P - 1] = s->Sdol[P - 1] = 0.0;
+  for (int i = P - 2; i >= 0; --i) {
+    s->Ssum[i] = s->Ssum[i + 1] + cmin[i + 1];
+    s->Smax[i] = fmax(s->Smax[i + 1], cmin[i + 1]);
+    s->Ssync[i] = fmax(s->Ssync[i + 1], smin[i + 1]);
+    s->Supd[i] = fmax(s->Supd[i + 1], umin[i + 1]);
+    s->Sdol[i] = s->Sdol[i + 1] + dmin[i + 1];
+  }
+  return 1;
+}
+
+/* Lower bounds of the state's completions; the plan's own values when stage P - 1 is placed. */
+static void bounds(const ss_sub *s, int i, ss_state *st, int objective) {
+  const double t_open = st->c_open + st->xb_open;
+  const double tsum = (st->sum + t_open) + s->Ssum[i];
+  const double tmax = fmax(fmax(st->maxt, t_open), s->Smax[i]);
+  st->lb_T = ((tsum + (double)(s->Nb - 1) * tmax) + fmax(st->msync, s->Ssync[i])) + fmax(st->mupd, s->Supd[i]);
+  st->lb_C = (st->dol + s->Sdol[i]) / 3600.0 * st->lb_T + st->comm;
+  st->lb_key = objective == SO_MAX_THROUGHPUT ? st->lb_T : st->lb_C;
+}
+
+/* stage 0 on pool a */
+static int first_state(const ss_sub *s, int a, int objective, ss_state *st) {
+  if (!s->ok[0][a] || s->cap_cnt[a] < 1) return 0;
+  const int g = a % s->G, z = a / s->G;
+  memset(st, 0, sizeof *st);
+  st->c_open = s->c[0][g];
+  st->msync = s->sync[0][z];
+  st->mupd = s->upd[0][g];
+  st->dol = s->dol[0][g];
+  st->cnt[a] = 1;
+  st->pool = (uint8_t)a;
+  st->runs = 1;
+  st->path[0] = (uint8_t)a;
+  bounds(s, 0, st, objective);
+  return 1;
+}
+
+/* stage i + 1 on pool a behind the state par (stages 0 .. i placed) */
+static int extend(const ss_sub *s, int i, const ss_state *par, int a, int max_runs, int objective,
+                  ss_state *st) {
+  if (!s->ok[i + 1][a] || par->cnt[a] + 1 > s->cap_cnt[a]) return 0;
+  const int runs = par->runs + (a != par->pool ? 1 : 0);
+  if (max_runs > 0 && runs > max_runs) return 0;
+  const int g = a % s->G, z = a / s->G, zp = par->pool / s->G;
+  *st = *par;
+  const double t_closed = par->c_open + (s->xfer[zp][z] + par->xb_open); /* forward, then backward */
+  st->sum = par->sum + t_closed;
+  st->maxt = fmax(par->maxt, t_closed);
+  st->c_open = s->c[i + 1][g];
+  st->xb_open = s->xfer[z][zp];
+  st->msync = fmax(par->msync, s->sync[i + 1][z]);
+  st->mupd = fmax(par->mupd, s->upd[i + 1][g]);
+  st->dol = par->dol + s->dol[i + 1][g];
+  if (zp != z) st->comm = par->comm + s->comm[zp][z];
+  st->cnt[a] = (uint8_t)(par->cnt[a] + 1);
+  st->pool = (uint8_t)a;
+  st->runs = (uint8_t)runs;
+  st->path[i + 1] = (uint8_t)a;
+  bounds(s, i + 1, st, objective);
+  return 1;
+}
+
+/* dropped: the bound already violates the constraint, or cannot beat the incumbent */
+static int pruned(const ss_state *st, int objective, int has_bound, double bound, int has_inc, double inc) {
+  if (has_bound) {
+    if (objective == SO_MAX_THROUGHPUT) { if (st->lb_C > bound) return 1; }
+    else if (1.0 / st->lb_T < bound) return 1;
+  }
+  return has_inc && st->lb_key > inc;
+}
+
+typedef struct { double key; uint32_t id; uint32_t pos; } ss_order; /* id: generation order; pos: where it is stored */
+
+static int by_key_then_id(const void *x, const void *y) {
+  const ss_order *a = (const ss_order *)x, *b = (const ss_order *)y;
+  if (a->key < b->key) return -1;
+  if (a->key > b->key) return 1;
+  return a->id < b->id ? -1 : (a->id > b->id ? 1 : 0);
+}
+
+static void take(so_search_result *out, const ss_sub *s, const ss_state *st) {
+  out->found = 1;
+  out->pp_idx = s->pp_idx; out->partition = s->partition; out->tp_idx = s->tp_idx;
+  out->dp_idx = s->dp_idx; out->mb_idx = s->mb_idx; out->pp = s->P;
+  out->key = st->lb_key; out->iter_time = st->lb_T; out->cost = st->lb_C;
+  for (int i = 0; i < s->P; ++i) out->pools[i] = st->path[i];
+}
+
+int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
+                   const so_search_opts *opt, so_search_result *out) {
+  const so_problem *p = so_problem_of(c);
+  memset(out, 0, sizeof *out);
+  if (p->mixed_types || p->per_segment_tp || p->n_bw_coef > 0 || !opt || opt->beam_width < 1) return -1;
+  if (p->n_types > 16 || p->n_zones > 16 || p->n_types * p->n_zones > SS_MAX_POOLS) return -1;
+  const int W = opt->beam_width, ZG = p->n_types * p->n_zones;
+  ss_sub *s = (ss_sub *)malloc(sizeof(ss_sub));
+  ss_state *cur = (ss_state *)malloc(sizeof(ss_state) * (size_t)W);
+  ss_state *all = (ss_state *)malloc(sizeof(ss_state) * (size_t)W * (size_t)ZG);
+  ss_order *ord = (ss_order *)malloc(sizeof(ss_order) * (size_t)W * (size_t)ZG);
+  if (!s || !cur || !all || !ord) { free(s); free(cur); free(all); free(ord); return -1; }
+  for (int ip = 0; ip < p->n_pp; ++ip) {
+    if (p->pp_values[ip] > SS_MAX_STAGES) continue;
+    for (int q = 0; q < p->n_partitions[ip]; ++q)
+      for (int it = 0; it < p->n_tp; ++it)
+        for (int id = 0; id < p->n_dp; ++id)
+          for (int im = 0; im < p->n_mb; ++im) {
+            if (!sub_setup(p, s, ip, q, it, id, im)) continue;
+            /* level 0, then one level per further stage */
+            int n = 0, n_all = 0;
+            for (int a = 0; a < ZG; ++a)
+              if (first_state(s, a, objective, &all[n_all])) {
+                out->expanded += 1;
+                if (!pruned(&all[n_all], objective, has_bound, bound, opt->has_incumbent, opt->incumbent)) {
+                  ord[n_all].key = all[n_all].lb_key;
+                  ord[n_all].id = (uint32_t)a;
+                  ord[n_all].pos = (uint32_t)n_all;
+                  n_all += 1;
+                }
+              }
+            for (int i = 0;; ++i) { /* `all` holds the surviving placements of stages 0 .. i */
+              if (i == s->P - 1) {  /* complete plans: the smallest (key, id) */
+                int bi = -1;
+                for (int k = 0; k < n_all; ++k)
+                  if (bi < 0 || by_key_then_id(&ord[k], &ord[bi]) < 0) bi = k;
+                if (bi >= 0 && (!out->found || all[bi].lb_key < out->key)) take(out, s, &all[bi]);
+                break;
+              }
+              if (n_all > W) { /* keep the W smallest bounds, in that order */
+                qsort(ord, (size_t)n_all, sizeof(ss_order), by_key_then_id);
+                out->truncated = 1;
+                for (int k = 0; k < W; ++k) cur[k] = all[ord[k].pos];
+                n = W;
+              } else { /* all of them, in the order they were generated */
+                for (int k = 0; k < n_all; ++k) cur[k] = all[k];
+                n = n_all;
+              }
+              /* expand: candidate id = rank of the parent * ZG + pool */
+              n_all = 0;
+              for (int r = 0; r < n; ++r)
+                for (int a = 0; a < ZG; ++a) {
+                  ss_state *st = &all[n_all];
+                  if (!extend(s, i, &cur[r], a, opt->max_runs, objective, st)) continue;
+                  out->expanded += 1;
+                  if (pruned(st, objective, has_bound, bound, opt->has_incumbent, opt->incumbent)) continue;
+                  ord[n_all].key = st->lb_key;
+                  ord[n_all].id = (uint32_t)(r * ZG + a);
+                  ord[n_all].pos = (uint32_t)n_all;
+                  n_all += 1;
+                }
+              if (n_all == 0) break;
+            }
+          }
+  }
+  free(s); free(cur); free(all); free(ord);
+  return 0;
+}
+
+/* ---- the definition: every placement of every sub-problem through the plain simulator ---- */
+
+static void place(const so_ctx *c, const so_problem *p, int ip, int q, int it, int id, int im,
+                  int i, int runs, int max_runs, int32_t *pools, int objective, int has_bound,
+                  double bound, so_search_result *out) {
+  const int P = p->pp_values[ip], ZG = p->n_types * p->n_zones;
+  if (i == P) {
+    so_eval e;
+    out->expanded += 1;
+    if (so_eval_assignment(c, ip, q, id, im, it, pools, objective, has_bound, bound, &e) != 0) return;
+    if (e.mask != 0) return;
+    const double key = objective == SO_MAX_THROUGHPUT ? e.iter_time : e.cost;
+    if (out->found && !(key < out->key)) return; /* the first of equal keys stays */
+    out->found = 1;
+    out->pp_idx = ip; out->partition = q; out->tp_idx = it; out->dp_idx = id; out->mb_idx = im;
+    out->pp = P; out->key = key; out->iter_time = e.iter_time; out->cost = e.cost;
+    for (int k = 0; k < P; ++k) out->pools[k] = pools[k];
+    return;
+  }
+  for (int a = 0; a < ZG; ++a) {
+    const int r = (i == 0) ? 1 : runs + (a != pools[i - 1] ? 1 : 0);
+    if (max_runs > 0 && r > max_runs) continue;
+    pools[i] = a;
+    place(c, p, ip, q, it, id, im, i + 1, r, max_runs, pools, objective, has_bound, bound, out);
+  }
+}
+
+int so_search_exhaustive(const so_ctx *c, int objective, int has_bound, double bound, int max_runs,
+                         so_search_result *out) {
+  const so_problem *p = so_problem_of(c);
+  memset(out, 0, sizeof *out);
+  if (p->mixed_types || p->per_segment_tp) return -1;
+  int32_t pools[SO_SEARCH_MAX_STAGES];
+  for (int ip = 0; ip < p->n_pp; ++ip) {
+    if (p->pp_values[ip] > SS_MAX_STAGES) continue;
+    for (int q = 0; q < p->n_partitions[ip]; ++q)
+      for (int it = 0; it < p->n_tp; ++it)
+        for (int id = 0; id < p->n_dp; ++id)
+          for (int im = 0; im < p->n_mb; ++im)
+            place(c, p, ip, q, it, id, im, 0, 0, max_runs, pools, objective, has_bound, bound, out);
+  }
+  return 0;
+}
+
+/* The bound of the first i + 1 stages of a placement (for the tests: it must not exceed the
+ * value of the whole placement).  Returns 0, -1 when the prefix itself is not admissible. */
+int so_search_prefix_bound(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                           int tp_idx, const int32_t *pools, int n_placed, int objective,
+                           double *lb_time, double *lb_cost) {
+  const so_problem *p = so_problem_of(c);
+  if (p->mixed_types || p->per_segment_tp || p->n_bw_coef > 0) return -1;
+  ss_sub *s = (ss_sub *)malloc(sizeof(ss_sub));
+  ss_state a, b;
+  int rc = -1;
+  if (s && sub_setup(p, s, pp_idx, partition, tp_idx, dp_idx, mb_idx) && n_placed >= 1 &&
+      n_placed <= s->P && first_state(s, pools[0], objective, &a)) {
+    rc = 0;
+    for (int i = 0; i + 1 < n_placed && rc == 0; ++i) {
+      if (!extend(s, i, &a, pools[i + 1], 0, objective, &b)) rc = -1;
+      a = b;
+    }
+    if (rc == 0) { *lb_time = a.lb_T; *lb_cost = a.lb_C; }
+  }
+  free(s);
+  return rc;
+}

@@ -10,6 +10,8 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
+SOURCES = ("sailor_oracle.c", "sailor_search_oracle.c", "sailor_oracle.h")
+
 MUTANTS = [
     # (pin file, text in oracle/sailor_oracle.c, replacement)
     ("test_oracle_simulator.py", "(double)(Nb - 1) * max_t", "(double)(Nb) * max_t"),
@@ -30,16 +32,27 @@ MUTANTS = [
     ("test_oracle_mixed_types.py", "half_gpus_on_pool[zone_of[i] * G + type_b[i]] += tp_of[i];", ""),
     ("test_oracle_mixed_types.py", "if (f2 + b2 > f + b) { f = f2; b = b2; }\n    }\n    double x = 0.0;",
      "if (f2 + b2 < f + b) { f = f2; b = b2; }\n    }\n    double x = 0.0;"),
+    # the search: a bound that is not one, a forgotten transfer, a quota that is never full,
+    # the beam's order
+    ("test_oracle_search.py", "const double tsum = (st->sum + t_open) + s->Ssum[i];",
+     "const double tsum = (st->sum + t_open) + 1.5 * s->Ssum[i];"),
+    ("test_oracle_search.py", "st->xb_open = s->xfer[z][zp];", "st->xb_open = 0.0;"),
+    ("test_oracle_search.py", "par->cnt[a] + 1 > s->cap_cnt[a]", "par->cnt[a] > s->cap_cnt[a]"),
+    ("test_oracle_search.py", "if (a->key < b->key) return -1;\n  if (a->key > b->key) return 1;",
+     "if (a->key < b->key) return 1;\n  if (a->key > b->key) return -1;"),
+    ("test_oracle_search.py", "s->Smax[i] = fmax(s->Smax[i + 1], cmin[i + 1]);",
+     "s->Smax[i] = fmax(s->Smax[i + 1], cmin[i]);"),
 ]
 
 
 @pytest.mark.parametrize("pins,old,new", MUTANTS, ids=[f"{m[0][12:-3]}-{i}" for i, m in enumerate(MUTANTS)])
 def test_a_planted_mistake_fails_its_pins(tmp_path, pins, old, new):
-    for f in ("sailor_oracle.c", "sailor_oracle.h"):
+    for f in SOURCES:
         shutil.copy(os.path.join(ROOT, "oracle", f), tmp_path / f)
-    src = (tmp_path / "sailor_oracle.c").read_text()
+    target = "sailor_search_oracle.c" if pins == "test_oracle_search.py" else "sailor_oracle.c"
+    src = (tmp_path / target).read_text()
     assert src.count(old) == 1, "the mutation no longer matches the oracle's source"
-    (tmp_path / "sailor_oracle.c").write_text(src.replace(old, new))
+    (tmp_path / target).write_text(src.replace(old, new))
     env = dict(os.environ, SAILOR_ORACLE_DIR=str(tmp_path))
     run = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", pins), "-x", "-q",
                           "-p", "no:cacheprovider"], cwd=ROOT, env=env, capture_output=True, text=True)
@@ -49,7 +62,7 @@ def test_a_planted_mistake_fails_its_pins(tmp_path, pins, old, new):
 
 def test_the_unmodified_copy_passes(tmp_path):
     # the harness itself: the same route with nothing planted is green
-    for f in ("sailor_oracle.c", "sailor_oracle.h"):
+    for f in SOURCES:
         shutil.copy(os.path.join(ROOT, "oracle", f), tmp_path / f)
     env = dict(os.environ, SAILOR_ORACLE_DIR=str(tmp_path))
     run = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_bandwidth.py"),

@@ -1,0 +1,196 @@
+"""Pins of the oracle's search over per-stage placements (Sec. 4.2.2): the evaluation of a free
+placement against the already pinned flat-space evaluation, the exhaustive search against a
+Python enumeration and against the flat space's optimum, the beam algorithm against the
+exhaustive search, and its bounds against the values of complete placements."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle.oracle import MAX_THROUGHPUT, MIN_COST, Oracle
+from paper_2504_17096_amd import workloads as W
+from tests.helpers import make_problem
+
+OBJECTIVES = [MAX_THROUGHPUT, MIN_COST]
+
+
+def _key(e, objective):
+    return e.iter_time if objective == MAX_THROUGHPUT else e.cost
+
+
+def _stage_pools(cfg):
+    return [cfg.pool[0 if i < cfg.cut[0] else (1 if i < cfg.cut[1] else 2)] for i in range(cfg.pp)]
+
+
+def _tiny(seed, **kw):
+    # three runs allowed for every depth, so that "at most three runs" is the flat space
+    kw.setdefault("seg3_max_pp", 64)
+    return W.tiny_problem(seed, **kw)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_a_placement_made_of_segments_evaluates_like_the_flat_plan(seed):
+    prob = _tiny(seed, n_types=2 + seed % 2, n_zones=2)
+    orc = Oracle(prob)
+    rng = np.random.default_rng(seed)
+    for c in rng.integers(0, orc.num_candidates, 400):
+        cfg, want = orc.decode(int(c)), orc.eval_one(int(c))
+        got = orc.eval_assignment(cfg.pp_idx, cfg.partition, cfg.dp_idx, cfg.mb_idx, cfg.tp_idx,
+                                  _stage_pools(cfg))
+        assert (got.mask, got.peak_mem) == (want.mask, want.peak_mem)
+        assert got.iter_time == want.iter_time and got.cost == want.cost  # the same arithmetic
+
+
+def test_a_free_placement_by_hand():
+    # 3 stages, 2 zones, one GPU type, D = 1, 4 microbatches of size 1: stage times 3 ms each,
+    # transfers 1 ms inside a zone, 10 ms across; placement z = (0, 1, 0) is not a flat plan of
+    # two segments' kind only in that its first and last stage share a pool
+    bw = np.array([[1e9, 1e8], [1e8, 1e9]])
+    p = make_problem(n_layers=3, n_types=1, n_zones=2, mb_list=(1,), tp_list=(1,), dp_list=(1,),
+                     pp_list=[3], global_batch=4, t_fwd=1e-3, t_bwd=2e-3, p2p=1_000_000, bw=bw,
+                     price=3600.0, egress=np.array([[0, 1e-9], [2e-9, 0]]), layer_params=0, avail=2)
+    orc = Oracle(p)
+    e = orc.eval_assignment(0, 0, 0, 0, 0, [0, 1, 0])
+    t = [3e-3 + 10e-3, 3e-3 + 10e-3 + 10e-3, 3e-3 + 10e-3]
+    T = sum(t) + 3 * max(t)
+    assert e.mask == 0 and e.iter_time == pytest.approx(T, rel=1e-14)
+    # three GPUs at 1 $/s, plus 4 microbatches x 1 MB over two boundaries at 3e-9 $/B both ways
+    assert e.cost == pytest.approx(3 * T + 2 * 4 * 1e6 * 3e-9, rel=1e-14)
+    # two stages on zone 0 need two GPUs there: one fewer and the plan is over quota
+    assert Oracle(p.with_avail(np.array([[1], [2]]))).eval_assignment(0, 0, 0, 0, 0, [0, 1, 0]).mask == 2
+    # the search finds the one-zone plan (no slow transfers), which the quota allows only on
+    # ... no zone holds three stages: the best has one boundary crossed
+    best = orc.search_exhaustive()
+    assert sorted(set(best.pools)) == [0, 1] and sum(a != b for a, b in zip(best.pools, best.pools[1:])) == 1
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+def test_the_exhaustive_search_is_a_plain_enumeration(objective):
+    prob = _tiny(5, n_layers=4, n_types=1, n_zones=3)
+    orc = Oracle(prob)
+    best_key, best = None, None
+    order = itertools.product(range(len(prob.pp_values)), range(3), range(len(prob.tp_values)),
+                              range(len(prob.dp_values)), range(len(prob.mb_values)))
+    for ip, q, it, idp, im in order:
+        if q >= prob.n_partitions[ip]:
+            continue
+        for pools in itertools.product(range(3), repeat=int(prob.pp_values[ip])):
+            e = orc.eval_assignment(ip, q, idp, im, it, pools, objective)
+            if e.mask == 0 and (best_key is None or _key(e, objective) < best_key):
+                best_key, best = _key(e, objective), (ip, q, it, idp, im, pools)
+    got = orc.search_exhaustive(objective)
+    assert got.key == best_key
+    assert (got.pp_idx, got.partition, got.tp_idx, got.dp_idx, got.mb_idx, got.pools) == best
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_three_runs_is_the_flat_space(seed, objective):
+    prob = _tiny(seed, n_types=2, n_zones=2)
+    orc = Oracle(prob)
+    flat = orc.best(objective)
+    runs3 = orc.search_exhaustive(objective, max_runs=3)
+    assert (flat is None) == (runs3 is None)
+    if flat is not None:
+        assert runs3.key == _key(flat, objective)          # the same plan, the same arithmetic
+        cfg = orc.decode(flat.index)
+        free = orc.search_exhaustive(objective)
+        assert free.key <= runs3.key                        # more placements: no worse
+        # a bound taken from the data: the constrained optimum agrees as well
+        other = flat.cost if objective == MAX_THROUGHPUT else 1.0 / flat.iter_time
+        bound = other * (0.9 if objective == MAX_THROUGHPUT else 1.1) * (1 + 1e-7)
+        fb, rb = orc.best(objective, bound), orc.search_exhaustive(objective, bound, max_runs=3)
+        assert (fb is None) == (rb is None) and (fb is None or rb.key == _key(fb, objective))
+        assert cfg.pp == prob.pp_values[cfg.pp_idx]
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+@pytest.mark.parametrize("seed", [21, 22, 23, 24])
+def test_the_beam_without_a_cut_is_exhaustive(seed, objective):
+    prob = _tiny(seed, n_layers=6 if seed % 2 else 4, n_types=1 + seed % 2, n_zones=2 + seed % 2)
+    orc = Oracle(prob)
+    want = orc.search_exhaustive(objective)
+    got = orc.search_beam(1 << 20, objective)
+    assert (want is None) == (got is None)
+    if want is None:
+        return
+    assert not got.truncated
+    assert got.key == want.key
+    # the placement it reports is a valid plan with exactly the reported values
+    e = orc.eval_assignment(got.pp_idx, got.partition, got.dp_idx, got.mb_idx, got.tp_idx, got.pools, objective)
+    assert e.mask == 0 and e.iter_time == got.iter_time and e.cost == got.cost
+    # an incumbent (the flat space's optimum) only removes work
+    flat = orc.best(objective)
+    if flat is not None:
+        inc = orc.search_beam(1 << 20, objective, incumbent=_key(flat, objective) * (1 + 1e-9))
+        assert inc.key == want.key and inc.pools == got.pools and inc.expanded <= got.expanded
+    # with a bound
+    other = want.cost if objective == MAX_THROUGHPUT else 1.0 / want.iter_time
+    bound = other * (0.8 if objective == MAX_THROUGHPUT else 1.25) * (1 + 1e-7)
+    wb, gb = orc.search_exhaustive(objective, bound), orc.search_beam(1 << 20, objective, bound)
+    assert (wb is None) == (gb is None) and (wb is None or wb.key == gb.key)
+    # restricted to runs
+    for runs in (1, 2):
+        wr, gr = orc.search_exhaustive(objective, max_runs=runs), orc.search_beam(1 << 20, objective, max_runs=runs)
+        assert (wr is None) == (gr is None) and (wr is None or wr.key == gr.key)
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+def test_a_narrow_beam_returns_valid_plans_and_a_wider_one_is_no_worse(objective):
+    prob = _tiny(31, n_layers=6, n_types=2, n_zones=3)
+    orc = Oracle(prob)
+    exact = orc.search_beam(1 << 20, objective)
+    prev = None
+    for width in (1, 2, 8, 64, 4096):
+        got = orc.search_beam(width, objective)
+        assert got is not None and got.key >= exact.key
+        e = orc.eval_assignment(got.pp_idx, got.partition, got.dp_idx, got.mb_idx, got.tp_idx, got.pools, objective)
+        assert e.mask == 0 and _key(e, objective) == got.key
+        if width <= 2:
+            assert got.truncated
+        if prev is not None:
+            assert got.key <= prev * (1 + 1e-12)
+        prev = got.key
+    assert prev == exact.key
+
+
+@pytest.mark.parametrize("seed", [41, 42])
+def test_bounds_never_exceed_the_value_of_a_completion(seed):
+    prob = _tiny(seed, n_layers=6, n_types=2, n_zones=2)
+    orc = Oracle(prob)
+    rng = np.random.default_rng(seed)
+    checked = 0
+    for _ in range(9000):
+        ip = int(rng.integers(0, len(prob.pp_values)))
+        P = int(prob.pp_values[ip])
+        q, it = int(rng.integers(0, prob.n_partitions[ip])), int(rng.integers(0, len(prob.tp_values)))
+        idp, im = int(rng.integers(0, len(prob.dp_values))), int(rng.integers(0, len(prob.mb_values)))
+        pools = rng.integers(0, 4, P)
+        e = orc.eval_assignment(ip, q, idp, im, it, pools)
+        if e.mask != 0:
+            continue
+        last = (0.0, 0.0)
+        for n in range(1, P + 1):
+            lb = orc.prefix_bound(ip, q, idp, im, it, pools, n)
+            assert lb is not None
+            assert lb[0] <= e.iter_time * (1 + 1e-13) and lb[1] <= e.cost * (1 + 1e-13)
+            assert lb[0] >= last[0] * (1 - 1e-13)  # knowing more never loosens the bound
+            last = lb
+        assert last == (e.iter_time, e.cost)       # all stages placed: the plan's own values
+        checked += 1
+    assert checked > 100
+
+
+def test_with_a_single_choice_per_stage_the_first_bound_is_the_value():
+    # one pool, no transfers: behind the first stage nothing is left to choose, so the bound of
+    # the one-stage prefix is T_iter and C_iter themselves -- with the straggler at the end,
+    # in the middle or in front
+    for split in ([1, 1, 4], [1, 4, 1], [4, 1, 1]):
+        p = make_problem(n_layers=6, n_types=1, n_zones=1, mb_list=(2,), tp_list=(1,), dp_list=(2,),
+                         pp_list=[3], partitions={3: [split]}, global_batch=32, p2p=0, t_upd=1e-4,
+                         layer_params=1000, price=2.5)
+        orc = Oracle(p)
+        e = orc.eval_assignment(0, 0, 0, 0, 0, [0, 0, 0])
+        lb = orc.prefix_bound(0, 0, 0, 0, 0, [0, 0, 0], 1)
+        assert e.mask == 0
+        assert lb[0] == pytest.approx(e.iter_time, rel=1e-14) and lb[1] == pytest.approx(e.cost, rel=1e-14)
