@@ -319,6 +319,70 @@ sailor_status sailor_simulate_1f1b_static(sailor_plan *plan, uint64_t count,
                                           const uint64_t *d_indices, double *d_event,
                                           double *d_closed, void *hip_stream);
 
+/* ---- plans whose stages choose their pools freely ---------------------------------------- */
+
+/* Options of sailor_search. */
+typedef struct {
+  int32_t beam_width;     /* 1 .. 256: longest frontier kept per sub-problem */
+  int32_t max_runs;       /* 0: any placement; n: at most n runs of consecutive stages on one pool
+                             (3 = the candidate space of sailor_best_plan when that space allows
+                             three segments at every depth) */
+  int32_t use_incumbent;  /* 0: none; 1: `incumbent` below; 2: sailor_best_plan runs first and its
+                             key, times 1 + 1e-9, is the incumbent */
+  double incumbent;       /* placements whose bound exceeds it are dropped, complete plans too */
+} sailor_search_options;
+
+/* A plan with one pool per stage (plan tuple of Sec. 4.2). */
+typedef struct {
+  int32_t found;          /* 1: a valid plan (no worse than the incumbent, if any) exists */
+  int32_t exact;          /* 1: no frontier was cut, the plan is the optimum over all placements */
+  int32_t pp, tp, dp, mb;
+  int32_t pp_index, tp_index, dp_index, mb_index, partition;
+  uint32_t mask;            /* of the winner's re-evaluation (0) */
+  uint64_t peak_mem_bytes;  /* of the winner's re-evaluation */
+  double iter_time_s, cost_per_iter; /* as the search accumulated them (stage order, fp64) */
+  double eval_time_s, eval_cost;     /* the same plan through sailor_eval_placements */
+  uint64_t expanded;        /* placements (partial and complete) generated */
+  int32_t incumbent_used;
+  double incumbent;
+  int32_t pool[SAILOR_MAX_STAGES]; /* zone * n_types + type of every stage; unused entries -1 */
+} sailor_stage_plan;
+
+/* Search on top of the evaluator for spaces too large to enumerate (Sec. 4.2.2: resources are
+ * assigned stage by stage, Eq. (1); Sec. 4.2.1, H3 / H4: stop where nothing better can follow;
+ * Sec. 4.2.3: the budget prunes partial assignments).  Every stage chooses its pool freely,
+ * all D replicas of a stage on it (H5), one TP degree per plan.  For every sub-problem
+ * (pipeline depth, layer split, TP, D, microbatch size) the stages are placed in order; a
+ * partial placement carries a lower bound on T_iter and C_iter (Sec. 4.3) of all its
+ * completions -- placed stages at their cost, later stages at their cheapest admissible choice
+ * (memory, node size), the open stage's forward transfer as zero -- and is dropped when the
+ * bound breaks the constraint or exceeds the incumbent; a frontier longer than beam_width keeps
+ * the smallest bounds (ties: the order of generation).  While no frontier is cut (*out.exact)
+ * the result is the optimum over all placements; otherwise it is the best plan these steps
+ * reach.  Equal keys: the first sub-problem in the order pp, layer split, TP, D, microbatch
+ * size.  All arithmetic is fp64 in stage order, so the reported values are those of the plan.
+ * Not for problems with per_segment_tp, mixed_types or bw_poly, more than 64 pools or 255
+ * stages (SAILOR_EINVAL).  Waits for the device.  SAILOR_ENOFEASIBLE (out->found = 0, exact and
+ * expanded still set) when no valid plan is found. */
+sailor_status sailor_search(sailor_plan *plan, sailor_objective objective,
+                            const sailor_constraint *constraint,
+                            const sailor_search_options *options, sailor_stage_plan *out,
+                            void *hip_stream);
+
+/* The simulator (Sec. 4.3) for listed plans of that kind, fp64, exact bytes:
+ *   d_desc   device, [count][5]: pp index, partition, TP index, D index, microbatch index
+ *   d_pools  device, [count][pool_stride]: pool of every stage (pool_stride >= pp)
+ *   outputs  device, [count], any may be NULL
+ * A descriptor or pool out of range yields mask = 0xFFFFFFFF, time = cost = +inf, mem = 0; a
+ * batch that does not divide mask = BATCH_INDIVISIBLE with +inf and 0.  Asynchronous on
+ * hip_stream.  SAILOR_EINVAL for per_segment_tp / mixed_types problems or more than 64 pools. */
+sailor_status sailor_eval_placements(sailor_plan *plan, uint64_t count, const int32_t *d_desc,
+                                     const int32_t *d_pools, uint32_t pool_stride,
+                                     sailor_objective objective,
+                                     const sailor_constraint *constraint, double *d_time,
+                                     double *d_cost, uint64_t *d_mem, uint32_t *d_mask,
+                                     void *hip_stream);
+
 /* Sizes of the intermediate lists of the last successful sailor_best_plan / sailor_topk
  * (the selection of Sec. 4.2 runs as fp32 scan -> survivors -> fp64 re-evaluation):
  * candidates kept by the fp32 threshold, candidates re-evaluated in fp64, and how many of

@@ -28,7 +28,8 @@ EXPORTS = ["sailor_plan_create", "sailor_plan_destroy", "sailor_plan_set_avail",
            "sailor_plan_num_candidates", "sailor_plan_decode", "sailor_eval_batch",
            "sailor_best_plan", "sailor_topk", "sailor_plan_set_scratch", "sailor_plan_set_timing",
            "sailor_plan_last_timing", "sailor_plan_last_counts", "sailor_simulate_1f1b",
-           "sailor_simulate_1f1b_static", "sailor_plan_set_incremental", "sailor_plan_last_scan"]
+           "sailor_simulate_1f1b_static", "sailor_plan_set_incremental", "sailor_plan_last_scan",
+           "sailor_search", "sailor_eval_placements"]
 
 
 class SailorError(RuntimeError):
@@ -75,6 +76,51 @@ class sailor_result(C.Structure):
         ("seg_tp", C.c_int32 * 3), ("seg_tp_index", C.c_int32 * 3),
         ("zone", C.c_int32 * 3), ("type_a", C.c_int32 * 3), ("type_b", C.c_int32 * 3),
     ]
+
+
+MAX_STAGES = 256
+
+
+class sailor_search_options(C.Structure):
+    _fields_ = [("beam_width", C.c_int32), ("max_runs", C.c_int32), ("use_incumbent", C.c_int32),
+                ("incumbent", C.c_double)]
+
+
+class sailor_stage_plan(C.Structure):
+    _fields_ = [("found", C.c_int32), ("exact", C.c_int32),
+                ("pp", C.c_int32), ("tp", C.c_int32), ("dp", C.c_int32), ("mb", C.c_int32),
+                ("pp_index", C.c_int32), ("tp_index", C.c_int32), ("dp_index", C.c_int32),
+                ("mb_index", C.c_int32), ("partition", C.c_int32), ("mask", C.c_uint32),
+                ("peak_mem_bytes", C.c_uint64),
+                ("iter_time_s", C.c_double), ("cost_per_iter", C.c_double),
+                ("eval_time_s", C.c_double), ("eval_cost", C.c_double),
+                ("expanded", C.c_uint64), ("incumbent_used", C.c_int32), ("incumbent", C.c_double),
+                ("pool", C.c_int32 * MAX_STAGES)]
+
+
+@dataclass
+class StagePlan:
+    """Result of sailor_search: one pool per stage."""
+    found: bool
+    exact: bool
+    pp: int
+    tp: int
+    dp: int
+    mb: int
+    pp_index: int
+    tp_index: int
+    dp_index: int
+    mb_index: int
+    partition: int
+    mask: int
+    peak_mem_bytes: int
+    iter_time_s: float
+    cost_per_iter: float
+    eval_time_s: float
+    eval_cost: float
+    expanded: int
+    incumbent: Optional[float]
+    pools: Tuple[int, ...]
 
 
 @dataclass
@@ -141,6 +187,10 @@ def load_library() -> C.CDLL:
     lib.sailor_simulate_1f1b_static.argtypes = [P, C.c_uint64, P, P, P, P]
     lib.sailor_plan_set_incremental.argtypes = [P, C.c_int32]
     lib.sailor_plan_last_scan.argtypes = [P, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+    lib.sailor_search.argtypes = [P, C.c_int, C.POINTER(sailor_constraint),
+                                  C.POINTER(sailor_search_options), C.POINTER(sailor_stage_plan), P]
+    lib.sailor_eval_placements.argtypes = [P, C.c_uint64, P, P, C.c_uint32, C.c_int,
+                                           C.POINTER(sailor_constraint), P, P, P, P, P]
     lib.sailor_plan_last_counts.argtypes = [P, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                             C.POINTER(C.c_uint32)]
     for name in EXPORTS:
@@ -322,6 +372,36 @@ class Plan:
         if rc != SAILOR_OK:
             raise SailorError(rc, "sailor_plan_last_counts")
         return a.value, b.value, c.value
+
+    def search(self, beam_width: int, objective: int = MAX_THROUGHPUT, bound: Optional[float] = None,
+               max_runs: int = 0, incumbent=None, stream: int = 0) -> StagePlan:
+        """sailor_search.  incumbent: None, a float, or "flat" (the library takes the best plan
+        of the flat space).  The returned plan has found = False when nothing valid exists."""
+        o = sailor_search_options(beam_width, max_runs, 0, 0.0)
+        if incumbent == "flat":
+            o.use_incumbent = 2
+        elif incumbent is not None:
+            o.use_incumbent, o.incumbent = 1, float(incumbent)
+        r = sailor_stage_plan()
+        rc = self._lib.sailor_search(self._h, objective, _constraint(bound), C.byref(o), C.byref(r),
+                                     stream or None)
+        if rc not in (SAILOR_OK, SAILOR_ENOFEASIBLE):
+            raise SailorError(rc, "sailor_search")
+        return StagePlan(bool(r.found), bool(r.exact), r.pp, r.tp, r.dp, r.mb, r.pp_index, r.tp_index,
+                         r.dp_index, r.mb_index, r.partition, r.mask, r.peak_mem_bytes, r.iter_time_s,
+                         r.cost_per_iter, r.eval_time_s, r.eval_cost, r.expanded,
+                         r.incumbent if r.incumbent_used else None, tuple(r.pool[:r.pp]))
+
+    def eval_placements(self, count: int, d_desc, d_pools, pool_stride: int,
+                        objective: int = MAX_THROUGHPUT, bound: Optional[float] = None, d_time=None,
+                        d_cost=None, d_mem=None, d_mask=None, stream: int = 0) -> None:
+        """sailor_eval_placements; device tensors: int32 [count][5], int32 [count][pool_stride],
+        float64 / float64 / int64 / int32 outputs."""
+        rc = self._lib.sailor_eval_placements(self._h, count, _ptr(d_desc), _ptr(d_pools), pool_stride,
+                                              objective, _constraint(bound), _ptr(d_time), _ptr(d_cost),
+                                              _ptr(d_mem), _ptr(d_mask), stream or None)
+        if rc != SAILOR_OK:
+            raise SailorError(rc, "sailor_eval_placements")
 
     def set_incremental(self, on: bool) -> None:
         rc = self._lib.sailor_plan_set_incremental(self._h, 1 if on else 0)

@@ -7,6 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 SOURCES = [os.path.join(_HERE, "csrc", "sailor.hip")]
 HEADERS = [os.path.join(_HERE, "csrc", "sailor_kernels.hip.h"),
+           os.path.join(_HERE, "csrc", "sailor_search.hip.h"),
            os.path.join(_HERE, "csrc", "sailor_dev.h"),
            os.path.join(os.path.dirname(_HERE), "include", "sailor.h")]
 LIB = os.path.join(_HERE, "libsailor.so")

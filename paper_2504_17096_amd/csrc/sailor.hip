@@ -14,6 +14,7 @@
 
 #include "../../include/sailor.h"
 #include "sailor_kernels.hip.h"
+#include "sailor_search.hip.h"
 
 using namespace sailor;
 
@@ -149,6 +150,14 @@ struct sailor_plan {
   int cache_obj = 0, cache_hasb = 0;
   float cache_lim_s = 0.f, cache_lim_l = 0.f;
   bool last_incremental = false;  // the last successful selection reused minima
+  // search over per-stage placements: tables and scratch, created by the first call
+  std::vector<SearchPP> search_pps;
+  const SearchPP *d_search_pps = nullptr;
+  uint32_t n_sub = 0;
+  uint8_t *search_states = nullptr;
+  uint32_t search_wgs = 0, search_state_stride = 0;
+  SubResult *search_results = nullptr, *search_final = nullptr;
+  double *search_eval = nullptr;  // T, C, then (as 64-bit words) mem and mask of the winner
   uint32_t cnt_phase = 0;      // which of the two counter sets the next call uses
   bool counters_dirty = false; // a failed call may have left either set in any state
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};  // start, scan end, end, scan start
@@ -1311,6 +1320,175 @@ sailor_status sailor_simulate_1f1b_static(sailor_plan *pl, uint64_t count, const
     k_sim_1f1b<<<(unsigned)a.count, threads, 0, st>>>(pl->dev, a);
     HIP_TRY(hipGetLastError());
   }
+  return SAILOR_OK;
+}
+
+// tables of the search and of the placement evaluation (once per plan)
+static sailor_status search_setup(sailor_plan *pl, bool with_scratch) {
+  if (!pl->d_search_pps) {
+    pl->search_pps.clear();
+    uint32_t sub = 0;
+    for (size_t ip = 0; ip < pl->ppv.size(); ++ip) {
+      SearchPP e{};
+      e.P = pl->ppv[ip];
+      e.n_part = 0;
+      e.rs0 = 0;
+      bool seen = false;
+      for (const ShapeRec &sh : pl->shapes)
+        if (sh.pp_idx == ip) {
+          if (!seen || sh.row_stage < e.rs0) e.rs0 = sh.row_stage;
+          seen = true;
+          e.n_part = std::max(e.n_part, (int32_t)sh.q + 1);
+        }
+      if (!seen) return SAILOR_EINVAL;  // (every depth has a one-segment block)
+      e.sub_off = sub;
+      sub += (uint32_t)e.n_part * (uint32_t)(pl->dev.TP * pl->dev.DP * pl->dev.MB);
+      pl->search_pps.push_back(e);
+    }
+    pl->n_sub = sub;
+    if (pl->arena.upload(&pl->d_search_pps, pl->search_pps.data(), pl->search_pps.size()) != hipSuccess)
+      return SAILOR_ENOMEM;
+  }
+  if (with_scratch && !pl->search_states) {
+    pl->search_wgs = std::min<uint32_t>(pl->n_sub, 2048u);
+    pl->search_state_stride = (kStateBytes + (uint32_t)pl->dev.P_max + 7u) & ~7u;
+    const size_t bytes = (size_t)pl->search_wgs * 2 * kSearchMaxBeam * pl->search_state_stride;
+    if (pl->arena.alloc(&pl->search_states, bytes) != hipSuccess ||
+        pl->arena.alloc(&pl->search_results, (size_t)pl->n_sub) != hipSuccess ||
+        pl->arena.alloc(&pl->search_final, 1) != hipSuccess ||
+        pl->arena.alloc(&pl->search_eval, 4) != hipSuccess)
+      return SAILOR_ENOMEM;
+  }
+  return SAILOR_OK;
+}
+
+sailor_status sailor_eval_placements(sailor_plan *pl, uint64_t count, const int32_t *d_desc,
+                                     const int32_t *d_pools, uint32_t pool_stride,
+                                     sailor_objective objective, const sailor_constraint *constraint,
+                                     double *d_time, double *d_cost, uint64_t *d_mem, uint32_t *d_mask,
+                                     void *hip_stream) {
+  if (!pl || (objective != SAILOR_MAX_THROUGHPUT && objective != SAILOR_MIN_COST)) return SAILOR_EINVAL;
+  if (count == 0) return SAILOR_OK;
+  if (!d_desc || !d_pools || pool_stride < 1) return SAILOR_EINVAL;
+  if (pl->dev.mixed || pl->dev.pst || pl->dev.ZGr > kSearchMaxPools) return SAILOR_EINVAL;
+  if (count > (uint64_t)0x7fffffff) return SAILOR_ERANGE;
+  if (constraint && constraint->has_bound && std::isnan(constraint->bound)) return SAILOR_EINVAL;
+  HIP_TRY(hipSetDevice(pl->device));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  sailor_status rc;
+  try { rc = search_setup(pl, false); } catch (...) { rc = SAILOR_ENOMEM; }
+  if (rc != SAILOR_OK) return rc;
+  rc = refresh_avail(pl, st);
+  if (rc != SAILOR_OK) return rc;
+  PlaceArgs a{};
+  a.count = count; a.desc = d_desc; a.pools = d_pools; a.pool_stride = pool_stride;
+  a.pps = pl->d_search_pps; a.n_pp = (int)pl->search_pps.size();
+  a.objective = (int)objective;
+  a.has_bound = (constraint && constraint->has_bound) ? 1 : 0;
+  a.bound = a.has_bound ? constraint->bound : 0.0;
+  a.T = d_time; a.C = d_cost; a.mem = d_mem; a.mask = d_mask;
+  k_eval_placements<<<(unsigned)((count + kPlaceWaves - 1) / kPlaceWaves), kPlaceWaves * 64, 0, st>>>(pl->dev, a);
+  HIP_TRY(hipGetLastError());
+  return SAILOR_OK;
+}
+
+sailor_status sailor_search(sailor_plan *pl, sailor_objective objective,
+                            const sailor_constraint *constraint, const sailor_search_options *opt,
+                            sailor_stage_plan *out, void *hip_stream) {
+  if (!pl || !opt || !out || (objective != SAILOR_MAX_THROUGHPUT && objective != SAILOR_MIN_COST))
+    return SAILOR_EINVAL;
+  if (opt->beam_width < 1 || opt->beam_width > kSearchMaxBeam || opt->max_runs < 0 ||
+      opt->use_incumbent < 0 || opt->use_incumbent > 2)
+    return SAILOR_EINVAL;
+  if (opt->use_incumbent == 1 && std::isnan(opt->incumbent)) return SAILOR_EINVAL;
+  // one TP degree and one pool per stage, constant link bandwidths, stages counted in a byte
+  if (pl->dev.mixed || pl->dev.pst || pl->dev.n_bw_coef > 0 || pl->dev.ZGr > kSearchMaxPools ||
+      pl->dev.P_max > kSearchMaxStages)
+    return SAILOR_EINVAL;
+  int has_bound;
+  double bound;
+  float lim_s, lim_l;
+  sailor_status rc = constraint_limits(objective, constraint, &has_bound, &bound, &lim_s, &lim_l);
+  if (rc != SAILOR_OK) return rc;
+  HIP_TRY(hipSetDevice(pl->device));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  try { rc = search_setup(pl, true); } catch (...) { rc = SAILOR_ENOMEM; }
+  if (rc != SAILOR_OK) return rc;
+  SearchArgs a{};
+  a.objective = (int)objective;
+  a.has_bound = has_bound;
+  a.bound = bound;
+  a.W = opt->beam_width;
+  a.max_runs = opt->max_runs;
+  if (opt->use_incumbent == 1) {
+    a.has_inc = 1;
+    a.inc = opt->incumbent;
+  } else if (opt->use_incumbent == 2) {
+    // the best plan of the flat space (at most three contiguous runs) through the evaluator:
+    // every placement whose bound exceeds its key can be dropped
+    ResultHeader hdr;
+    rc = run_selection(pl, objective, constraint, 0, st, &hdr);
+    if (rc != SAILOR_OK) return rc;
+    if (hdr.n_found) {
+      const RefRec *rec = reinterpret_cast<const RefRec *>(static_cast<char *>(pl->h_result) + sizeof(ResultHeader));
+      a.has_inc = 1;
+      a.inc = (objective == SAILOR_MAX_THROUGHPUT ? rec[0].T : rec[0].C) * (1.0 + 1e-9);
+    }
+  }
+  rc = refresh_avail(pl, st);
+  if (rc != SAILOR_OK) return rc;
+  a.pps = pl->d_search_pps;
+  a.n_pp = (int)pl->search_pps.size();
+  a.n_sub = pl->n_sub;
+  a.states = pl->search_states;
+  a.state_stride = pl->search_state_stride;
+  a.results = pl->search_results;
+  k_search_beam<<<pl->search_wgs, kSearchThreads, 0, st>>>(pl->dev, a);
+  k_search_pick<<<1, 256, 0, st>>>(pl->search_results, pl->n_sub, pl->search_final);
+  // the winner once more through the simulator, for its memory footprint and its mask
+  PlaceArgs pa{};
+  pa.count = 1;
+  pa.one = pl->search_final;
+  pa.pps = pl->d_search_pps;
+  pa.n_pp = a.n_pp;
+  pa.objective = (int)objective;
+  pa.has_bound = has_bound;
+  pa.bound = bound;
+  pa.T = pl->search_eval;
+  pa.C = pl->search_eval + 1;
+  pa.mem = reinterpret_cast<uint64_t *>(pl->search_eval + 2);
+  pa.mask = reinterpret_cast<uint32_t *>(pl->search_eval + 3);
+  k_eval_placements<<<1, kPlaceWaves * 64, 0, st>>>(pl->dev, pa);
+  HIP_TRY(hipGetLastError());
+  SubResult fin;
+  double ev[4];
+  HIP_TRY(hipMemcpyAsync(&fin, pl->search_final, sizeof fin, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipMemcpyAsync(ev, pl->search_eval, sizeof ev, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  std::memset(out, 0, sizeof *out);
+  for (int i = 0; i < SAILOR_MAX_STAGES; ++i) out->pool[i] = -1;
+  out->exact = fin.truncated ? 0 : 1;
+  out->expanded = fin.expanded;
+  out->incumbent_used = a.has_inc;
+  out->incumbent = a.has_inc ? a.inc : 0.0;
+  if (!fin.found) return SAILOR_ENOFEASIBLE;
+  out->found = 1;
+  out->pp_index = fin.desc[0];
+  out->partition = fin.desc[1];
+  out->tp_index = fin.desc[2];
+  out->dp_index = fin.desc[3];
+  out->mb_index = fin.desc[4];
+  out->pp = pl->ppv[fin.desc[0]];
+  out->tp = pl->tpv[fin.desc[2]];
+  out->dp = pl->dpv[fin.desc[3]];
+  out->mb = pl->mbv[fin.desc[4]];
+  out->iter_time_s = fin.T;
+  out->cost_per_iter = fin.C;
+  out->eval_time_s = ev[0];
+  out->eval_cost = ev[1];
+  std::memcpy(&out->peak_mem_bytes, &ev[2], sizeof(uint64_t));
+  std::memcpy(&out->mask, &ev[3], sizeof(uint32_t));
+  for (int i = 0; i < out->pp; ++i) out->pool[i] = fin.pools[i];
   return SAILOR_OK;
 }
 

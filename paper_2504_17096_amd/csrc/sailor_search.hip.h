@@ -1,0 +1,587 @@
+// Search over per-stage placements (gfx950, wave64), on top of the tables of the evaluator.
+//
+// The planner assigns resources stage by stage (Sailor, Sec. 4.2.2, Eq. (1): stage i gets r,
+// the stages behind it R - r, times composed by T_total); the heuristics H3 / H4 (Sec. 4.2.1)
+// stop early when nothing better can follow.  Here every stage of a pipeline chooses its pool
+// (zone, GPU type) freely -- all D replicas of a stage on that pool (H5), one TP degree per
+// plan -- and one workgroup works through one sub-problem (pipeline depth, layer split, TP,
+// D, microbatch size) level by level: the frontier of placements of stages 0 .. j-1 is
+// extended by every pool for stage j, each extension gets a lower bound on T_iter and C_iter
+// (Sec. 4.3) of all its completions, extensions whose bound breaks the constraint or exceeds
+// an incumbent are dropped, and a frontier longer than the beam width keeps the smallest
+// bounds.  At the last level the bound is the plan's own T_iter / C_iter.
+//
+//   k_search_beam        the level-by-level expansion, one workgroup per sub-problem
+//   k_search_pick        smallest (key, sub-problem) over the sub-problems' winners
+//   k_eval_placements    the simulator of Sec. 4.3 for listed placements, one wave each, fp64
+//
+// All arithmetic is fp64 in a fixed order (sums in stage order), so that which extension is
+// dropped or kept does not depend on how the work is spread over lanes.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "sailor_kernels.hip.h"
+
+namespace sailor {
+
+constexpr int kSearchThreads = 256;
+constexpr int kSearchMaxBeam = 256;    // longest frontier a sub-problem keeps
+constexpr int kSearchBuf = 2048;       // extensions buffered between two sorts
+constexpr int kSearchMaxStages = 255;  // placements count stages per pool in a byte
+constexpr int kSearchMaxPools = 64;
+
+struct SearchPP {      // one pipeline depth
+  int32_t P;
+  uint32_t rs0;        // first entry of its first partition row in the stage tables
+  uint32_t sub_off;    // first sub-problem of this depth
+  int32_t n_part;
+};
+
+struct SState {        // placement of stages 0 .. j; kStateBytes, followed by the path (a byte per stage)
+  double sum;          // times of the closed stages 0 .. j-1
+  double maxt;         // slowest closed stage
+  double c_open;       // compute time of stage j (its forward transfer is not known yet)
+  double xb_open;      // its backward transfer to stage j-1
+  double msync, mupd, dol, comm;
+  uint8_t cnt[kSearchMaxPools];  // stages placed on each pool
+  uint8_t pool, runs, pad[6];
+};
+constexpr uint32_t kStateBytes = sizeof(SState);
+static_assert(kStateBytes == 136, "eight doubles, the pool counts, pool and runs");
+
+struct SubResult {     // winner of one sub-problem (or of the whole search)
+  double key, T, C;
+  uint32_t found, truncated;
+  unsigned long long expanded;
+  uint32_t sid, P;
+  int32_t desc[6];     // pp index, partition, tp index, dp index, mb index, unused
+  uint8_t pools[256];
+};
+
+struct SearchArgs {
+  int objective, has_bound, has_inc, W, max_runs;
+  double bound, inc;
+  const SearchPP *pps;
+  int n_pp;
+  uint32_t n_sub;
+  uint8_t *states;        // [workgroups][2][W] states of state_stride bytes
+  uint32_t state_stride;  // kStateBytes + the path, rounded up to 8
+  SubResult *results;     // [n_sub]
+};
+
+struct SBound { double T, C; };
+
+// Lower bounds of T_iter and C_iter over the completions of a placement whose stage j is open;
+// the plan's own values when j = P - 1 (then every S term is zero).
+__device__ __forceinline__ SBound search_bounds(double sum, double maxt, double c_open, double xb_open,
+                                                double msync, double mupd, double dol, double comm,
+                                                double Ssum, double Smax, double Ssync, double Supd,
+                                                double Sdol, double nbm1) {
+  const double t_open = c_open + xb_open;
+  const double tsum = (sum + t_open) + Ssum;
+  const double tmax = fmax(fmax(maxt, t_open), Smax);
+  SBound b;
+  b.T = ((tsum + nbm1 * tmax) + fmax(msync, Ssync)) + fmax(mupd, Supd);
+  b.C = (dol + Sdol) / 3600.0 * b.T + comm;
+  return b;
+}
+
+__device__ __forceinline__ bool key_id_less(unsigned long long ka, uint32_t ia, unsigned long long kb,
+                                            uint32_t ib) {
+  return ka < kb || (ka == kb && ia < ib);
+}
+
+// Ascending bitonic sort of (key, id) pairs in LDS; m = the power of two >= n, entries
+// n .. m-1 are filled with the largest pair first.
+__device__ __forceinline__ void search_sort(unsigned long long *key, uint32_t *id, int n) {
+  int m = 1;
+  while (m < n) m <<= 1;
+  for (int i = n + (int)threadIdx.x; i < m; i += blockDim.x) { key[i] = ~0ull; id[i] = ~0u; }
+  __syncthreads();
+  for (int k = 2; k <= m; k <<= 1)
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int i = threadIdx.x; i < m; i += blockDim.x) {
+        const int x = i ^ j;
+        if (x > i) {
+          const bool up = (i & k) == 0;
+          const unsigned long long ki = key[i], kx = key[x];
+          const uint32_t ii = id[i], ix = id[x];
+          const bool swap = up ? key_id_less(kx, ix, ki, ii) : key_id_less(ki, ii, kx, ix);
+          if (swap) { key[i] = kx; key[x] = ki; id[i] = ix; id[x] = ii; }
+        }
+      }
+      __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, SearchArgs a) {
+  __shared__ double s_S[5][kSearchMaxStages + 1];        // what lies behind stage i: sum, max, sync, upd, $
+  __shared__ double s_xfer[kMaxZones][kMaxZones], s_comm[kMaxZones][kMaxZones];
+  __shared__ double l_c[kMaxTypes], l_upd[kMaxTypes], l_dol[kMaxTypes], l_sync[kMaxZones];
+  __shared__ double s_min[4][kSearchMaxStages + 1];      // cheapest admissible choice of every stage
+  __shared__ int s_cap[kSearchMaxPools];                 // stages a pool can host
+  __shared__ unsigned long long b_key[kSearchBuf];
+  __shared__ uint32_t b_id[kSearchBuf];
+  __shared__ uint32_t l_fit;                             // bit g: the level's stage fits type g
+  __shared__ uint32_t s_wave[kSearchThreads / 64];
+  __shared__ int s_nbuf, s_bad;
+  __shared__ unsigned long long s_bk[kSearchThreads / 64];
+  __shared__ uint32_t s_bi[kSearchThreads / 64];
+  __shared__ unsigned long long s_expanded;
+  const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+  const int G = pl.G, Z = pl.Z, ZG = pl.ZGr, MB = pl.MB, TP = pl.TP, DP = pl.DP;
+  uint8_t *const buf0 = a.states + (size_t)blockIdx.x * 2 * a.W * a.state_stride;
+  uint8_t *const buf1 = buf0 + (size_t)a.W * a.state_stride;
+
+  for (uint32_t sid = blockIdx.x; sid < a.n_sub; sid += gridDim.x) {  // uniform
+    __syncthreads();  // the shared tables are reused
+    int ip = 0;
+    for (int i = 1; i < a.n_pp; ++i)
+      if (sid >= a.pps[i].sub_off) ip = i;
+    const SearchPP pp = a.pps[ip];
+    uint32_t rem = sid - pp.sub_off;
+    const int im = (int)(rem % (uint32_t)MB); rem /= (uint32_t)MB;
+    const int id = (int)(rem % (uint32_t)DP); rem /= (uint32_t)DP;
+    const int it = (int)(rem % (uint32_t)TP);
+    const int q = (int)(rem / (uint32_t)TP);
+    const int P = pp.P;
+    const uint32_t rs = pp.rs0 + (uint32_t)q * (uint32_t)P;
+    SubResult *res = a.results + sid;
+    const int64_t nb = pl.nb[im * DP + id];
+    const int64_t D = pl.dpv[id];
+    const int tp = pl.tpv[it];
+    if (t == 0) {
+      res->found = 0; res->truncated = 0; res->expanded = 0; res->sid = sid; res->P = (uint32_t)P;
+      res->desc[0] = ip; res->desc[1] = q; res->desc[2] = it; res->desc[3] = id; res->desc[4] = im;
+      res->desc[5] = 0;
+      s_bad = 0;
+      s_expanded = 0;
+    }
+    __syncthreads();
+    if (nb == 0) continue;  // the batch does not divide (uniform)
+    const double p2p = (double)pl.p2p[im];
+    const double nbm1 = (double)(nb - 1);
+    // tables of the sub-problem
+    for (int i = t; i < Z * Z; i += blockDim.x) {
+      const int z = i / Z, y = i - z * Z;
+      s_xfer[z][y] = p2p / pl.bw[z * Z + y];
+      double cm = 0.0;
+      if (pl.egress && z != y)
+        cm = (double)nb * (double)D * p2p * (pl.egress[z * Z + y] + pl.egress[y * Z + z]);
+      s_comm[z][y] = cm;
+    }
+    for (int p = t; p < ZG; p += blockDim.x) s_cap[p] = (int)((int64_t)pl.avail[p] / ((int64_t)tp * D));
+    for (int i = t; i < P; i += blockDim.x) {  // the cheapest admissible choice of stage i
+      const uint64_t params = pl.st_params[rs + i];
+      const uint64_t bytes = stage_bytes_of(params, pl.st_n[rs + i], pl.bpp, i, P, tp, nb, pl.act[im * TP + it]);
+      const uint64_t shard = (params + (uint64_t)tp - 1) / (uint64_t)tp;
+      double cmin = __builtin_huge_val(), umin = cmin, dmin = cmin, smin = cmin;
+      bool any = false;
+      for (int g = 0; g < G; ++g) {
+        if (!(bytes + pl.res[g] <= pl.cap[g] && tp <= pl.node[g])) continue;
+        any = true;
+        cmin = fmin(cmin, pl.st_c[(((size_t)(rs + i) * G + g) * MB + im) * TP + it]);
+        umin = fmin(umin, pl.st_u[((size_t)(rs + i) * G + g) * TP + it]);
+        dmin = fmin(dmin, (double)(D * tp) * pl.price[g]);
+      }
+      for (int z = 0; z < Z; ++z) {
+        double sync = 0.0;
+        if (D > 1) {
+          const double grad = (double)shard * (double)pl.gb;
+          sync = 2.0 * (double)(D - 1) / (double)D * grad / pl.bw[z * Z + z];
+        }
+        smin = fmin(smin, sync);
+      }
+      s_min[0][i] = cmin; s_min[1][i] = smin; s_min[2][i] = umin; s_min[3][i] = dmin;
+      if (!any) s_bad = 1;  // (benign race: every writer stores 1)
+    }
+    __syncthreads();
+    if (s_bad) continue;  // some stage fits no pool (uniform)
+    if (t == 0) {  // what lies behind stage i, accumulated from the last stage backwards
+      s_S[0][P - 1] = s_S[1][P - 1] = s_S[2][P - 1] = s_S[3][P - 1] = s_S[4][P - 1] = 0.0;
+      for (int i = P - 2; i >= 0; --i) {
+        s_S[0][i] = s_S[0][i + 1] + s_min[0][i + 1];
+        s_S[1][i] = fmax(s_S[1][i + 1], s_min[0][i + 1]);
+        s_S[2][i] = fmax(s_S[2][i + 1], s_min[1][i + 1]);
+        s_S[3][i] = fmax(s_S[3][i + 1], s_min[2][i + 1]);
+        s_S[4][i] = s_S[4][i + 1] + s_min[3][i + 1];
+      }
+    }
+    int n_cur = 1;  // frontier length; level 0 extends one empty placement
+    bool truncated = false;
+    for (int j = 0; j < P; ++j) {  // place stage j (uniform loop)
+      uint8_t *const cur = (j & 1) ? buf1 : buf0, *const nxt = (j & 1) ? buf0 : buf1;
+      __syncthreads();
+      // the level's tables: stage j on every type / zone
+      if (t < G) {
+        const uint64_t params = pl.st_params[rs + j];
+        const uint64_t bytes = stage_bytes_of(params, pl.st_n[rs + j], pl.bpp, j, P, tp, nb, pl.act[im * TP + it]);
+        l_c[t] = pl.st_c[(((size_t)(rs + j) * G + t) * MB + im) * TP + it];
+        l_upd[t] = pl.st_u[((size_t)(rs + j) * G + t) * TP + it];
+        l_dol[t] = (double)(D * tp) * pl.price[t];
+        const bool fits = bytes + pl.res[t] <= pl.cap[t] && tp <= pl.node[t];
+        const unsigned long long m = __builtin_amdgcn_ballot_w64(fits);
+        if (t == 0) l_fit = (uint32_t)m;
+      } else if (t >= 64 && t < 64 + Z) {
+        const int z = t - 64;
+        const uint64_t params = pl.st_params[rs + j];
+        const uint64_t shard = (params + (uint64_t)tp - 1) / (uint64_t)tp;
+        double sync = 0.0;
+        if (D > 1) {
+          const double grad = (double)shard * (double)pl.gb;
+          sync = 2.0 * (double)(D - 1) / (double)D * grad / pl.bw[z * Z + z];
+        }
+        l_sync[z] = sync;
+      }
+      if (t == 0) s_nbuf = 0;
+      __syncthreads();
+      const double Ssum = s_S[0][j], Smax = s_S[1][j], Ssync = s_S[2][j], Supd = s_S[3][j], Sdol = s_S[4][j];
+      const bool last = j == P - 1;
+      const int n_total = n_cur * ZG;
+      unsigned long long best_k = ~0ull;  // last level: this thread's smallest (key, id)
+      uint32_t best_i = ~0u;
+      uint32_t my_expanded = 0;
+      for (int row = 0; row * kSearchThreads < n_total; ++row) {  // uniform
+        const int cand = row * kSearchThreads + t;
+        bool keep = false;
+        unsigned long long kbits = 0;
+        if (cand < n_total) {
+          const int r = cand / ZG, p = cand - r * ZG, g = p % G, z = p / G;
+          bool ok = ((l_fit >> g) & 1u) != 0;
+          double sum = 0.0, maxt = 0.0, c_open = l_c[g], xb_open = 0.0, msync = l_sync[z], mupd = l_upd[g],
+                 dol = l_dol[g], comm = 0.0;
+          if (j == 0) {
+            ok = ok && s_cap[p] >= 1;
+          } else {
+            const SState *par = reinterpret_cast<const SState *>(cur + (size_t)r * a.state_stride);
+            const int pz = par->pool / G;
+            const int runs = par->runs + (p != par->pool ? 1 : 0);
+            ok = ok && (int)par->cnt[p] + 1 <= s_cap[p] && (a.max_runs == 0 || runs <= a.max_runs);
+            const double t_closed = par->c_open + (s_xfer[pz][z] + par->xb_open);  // forward, then backward
+            sum = par->sum + t_closed;
+            maxt = fmax(par->maxt, t_closed);
+            xb_open = s_xfer[z][pz];
+            msync = fmax(par->msync, l_sync[z]);
+            mupd = fmax(par->mupd, l_upd[g]);
+            dol = par->dol + l_dol[g];
+            comm = pz != z ? par->comm + s_comm[pz][z] : par->comm;
+          }
+          if (ok) {
+            my_expanded += 1;
+            const SBound b = search_bounds(sum, maxt, c_open, xb_open, msync, mupd, dol, comm, Ssum, Smax,
+                                           Ssync, Supd, Sdol, nbm1);
+            const double key = a.objective == 0 ? b.T : b.C;
+            bool drop = false;
+            if (a.has_bound) drop = a.objective == 0 ? b.C > a.bound : 1.0 / b.T < a.bound;
+            if (a.has_inc && key > a.inc) drop = true;
+            keep = !drop;
+            kbits = (unsigned long long)__double_as_longlong(key);  // non-negative: orders like the value
+          }
+        }
+        if (last) {
+          if (keep && key_id_less(kbits, (uint32_t)cand, best_k, best_i)) { best_k = kbits; best_i = (uint32_t)cand; }
+          continue;
+        }
+        // append the row's survivors in candidate order
+        const unsigned long long m = __builtin_amdgcn_ballot_w64(keep);
+        if (lane == 0) s_wave[wv] = (uint32_t)__popcll(m);
+        __syncthreads();
+        uint32_t before = 0, row_total = 0;
+        for (int w = 0; w < kSearchThreads / 64; ++w) {
+          if (w < wv) before += s_wave[w];
+          row_total += s_wave[w];
+        }
+        int nbuf = s_nbuf;
+        if (nbuf + (int)row_total > kSearchBuf) {  // uniform: make room, only the W smallest can matter
+          __syncthreads();
+          search_sort(b_key, b_id, nbuf);
+          nbuf = min(nbuf, a.W);
+          truncated = true;
+        }
+        if (keep) {
+          const int at = nbuf + (int)before + __popcll(m & ((1ull << lane) - 1ull));
+          b_key[at] = kbits;
+          b_id[at] = (uint32_t)cand;
+        }
+        __syncthreads();
+        if (t == 0) s_nbuf = nbuf + (int)row_total;
+        __syncthreads();
+      }
+      atomicAdd(&s_expanded, (unsigned long long)my_expanded);
+      if (last) {
+        // the smallest (key, id) of the workgroup
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+          const unsigned long long ok2 = __shfl_xor(best_k, off);
+          const uint32_t oi = __shfl_xor(best_i, off);
+          if (key_id_less(ok2, oi, best_k, best_i)) { best_k = ok2; best_i = oi; }
+        }
+        if (lane == 0) { s_bk[wv] = best_k; s_bi[wv] = best_i; }
+        __syncthreads();
+        best_k = s_bk[0]; best_i = s_bi[0];
+        for (int w = 1; w < kSearchThreads / 64; ++w)
+          if (key_id_less(s_bk[w], s_bi[w], best_k, best_i)) { best_k = s_bk[w]; best_i = s_bi[w]; }
+        if (best_i != ~0u) {  // uniform
+          const int r = (int)best_i / ZG, p = (int)best_i - r * ZG, g = p % G, z = p / G;
+          const uint8_t *par_path = cur + (size_t)r * a.state_stride + kStateBytes;
+          for (int i = t; i < P - 1; i += blockDim.x) res->pools[i] = par_path[i];
+          if (t == 0) {
+            double sum = 0.0, maxt = 0.0, xb_open = 0.0, msync = l_sync[z], mupd = l_upd[g], dol = l_dol[g],
+                   comm = 0.0;
+            if (j > 0) {
+              const SState *par = reinterpret_cast<const SState *>(cur + (size_t)r * a.state_stride);
+              const int pz = par->pool / G;
+              const double t_closed = par->c_open + (s_xfer[pz][z] + par->xb_open);
+              sum = par->sum + t_closed;
+              maxt = fmax(par->maxt, t_closed);
+              xb_open = s_xfer[z][pz];
+              msync = fmax(par->msync, l_sync[z]);
+              mupd = fmax(par->mupd, l_upd[g]);
+              dol = par->dol + l_dol[g];
+              comm = pz != z ? par->comm + s_comm[pz][z] : par->comm;
+            }
+            const SBound b = search_bounds(sum, maxt, l_c[g], xb_open, msync, mupd, dol, comm, 0.0, 0.0, 0.0,
+                                           0.0, 0.0, nbm1);
+            res->pools[P - 1] = (uint8_t)p;
+            res->T = b.T;
+            res->C = b.C;
+            res->key = a.objective == 0 ? b.T : b.C;
+            res->found = 1;
+          }
+        }
+        break;
+      }
+      __syncthreads();
+      int n_next = s_nbuf;
+      if (n_next > a.W) {  // uniform: keep the W smallest bounds, in that order
+        search_sort(b_key, b_id, n_next);
+        n_next = a.W;
+        truncated = true;
+      }
+      if (n_next == 0) break;  // uniform
+      // write the next frontier
+      for (int k = t; k < n_next; k += blockDim.x) {
+        const int cand = (int)b_id[k];
+        const int r = cand / ZG, p = cand - r * ZG, g = p % G, z = p / G;
+        uint8_t *const out = nxt + (size_t)k * a.state_stride;
+        SState st;
+        if (j == 0) {
+          st.sum = 0.0; st.maxt = 0.0; st.xb_open = 0.0; st.msync = l_sync[z]; st.mupd = l_upd[g];
+          st.dol = l_dol[g]; st.comm = 0.0;
+          for (int c = 0; c < kSearchMaxPools; ++c) st.cnt[c] = 0;
+          st.runs = 1;
+        } else {
+          const SState *par = reinterpret_cast<const SState *>(cur + (size_t)r * a.state_stride);
+          st = *par;
+          const int pz = par->pool / G;
+          const double t_closed = par->c_open + (s_xfer[pz][z] + par->xb_open);
+          st.sum = par->sum + t_closed;
+          st.maxt = fmax(par->maxt, t_closed);
+          st.xb_open = s_xfer[z][pz];
+          st.msync = fmax(par->msync, l_sync[z]);
+          st.mupd = fmax(par->mupd, l_upd[g]);
+          st.dol = par->dol + l_dol[g];
+          st.comm = pz != z ? par->comm + s_comm[pz][z] : par->comm;
+          st.runs = (uint8_t)(par->runs + (p != par->pool ? 1 : 0));
+          const uint8_t *par_path = cur + (size_t)r * a.state_stride + kStateBytes;
+          for (int i = 0; i < j; ++i) out[kStateBytes + i] = par_path[i];
+        }
+        st.c_open = l_c[g];
+        st.cnt[p] = (uint8_t)(st.cnt[p] + 1);
+        st.pool = (uint8_t)p;
+        for (int c = 0; c < 6; ++c) st.pad[c] = 0;
+        *reinterpret_cast<SState *>(out) = st;
+        out[kStateBytes + j] = (uint8_t)p;
+      }
+      n_cur = n_next;
+    }
+    __syncthreads();
+    if (t == 0) {
+      res->truncated = truncated ? 1u : 0u;
+      res->expanded = s_expanded;
+    }
+  }
+}
+
+// Smallest (key, sub-problem) over the sub-problems' winners; also the totals.
+__global__ __launch_bounds__(256) void k_search_pick(const SubResult *results, uint32_t n_sub, SubResult *out) {
+  __shared__ unsigned long long s_k[4], s_e[4];
+  __shared__ uint32_t s_i[4], s_t[4];
+  const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+  unsigned long long bk = ~0ull, expanded = 0;
+  uint32_t bi = ~0u, trunc = 0;
+  for (uint32_t i = t; i < n_sub; i += blockDim.x) {
+    const SubResult &r = results[i];
+    expanded += r.expanded;
+    trunc |= r.truncated;
+    if (r.found) {
+      const unsigned long long k = (unsigned long long)__double_as_longlong(r.key);
+      if (key_id_less(k, i, bk, bi)) { bk = k; bi = i; }
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const unsigned long long ok = __shfl_xor(bk, off);
+    const uint32_t oi = __shfl_xor(bi, off);
+    if (key_id_less(ok, oi, bk, bi)) { bk = ok; bi = oi; }
+    expanded += __shfl_xor(expanded, off);
+    trunc |= __shfl_xor(trunc, off);
+  }
+  if (lane == 0) { s_k[wv] = bk; s_i[wv] = bi; s_e[wv] = expanded; s_t[wv] = trunc; }
+  __syncthreads();
+  if (t == 0) {
+    for (int w = 1; w < 4; ++w) {
+      if (key_id_less(s_k[w], s_i[w], bk, bi)) { bk = s_k[w]; bi = s_i[w]; }
+      expanded += s_e[w];
+      trunc |= s_t[w];
+    }
+    s_i[0] = bi; s_e[0] = expanded; s_t[0] = trunc;
+  }
+  __syncthreads();
+  bi = s_i[0];
+  if (bi == ~0u) {
+    if (t == 0) { out->found = 0; out->truncated = s_t[0]; out->expanded = s_e[0]; out->P = 0; }
+    return;
+  }
+  const unsigned long long *src = reinterpret_cast<const unsigned long long *>(results + bi);
+  unsigned long long *dst = reinterpret_cast<unsigned long long *>(out);
+  for (uint32_t w = t; w < sizeof(SubResult) / 8; w += blockDim.x) dst[w] = src[w];
+  __syncthreads();
+  if (t == 0) { out->truncated = s_t[0]; out->expanded = s_e[0]; }
+}
+
+// ------------------------------------------------------------------ listed placements
+
+struct PlaceArgs {
+  uint64_t count;
+  const int32_t *desc;    // [count][5] pp index, partition, tp index, dp index, mb index
+  const int32_t *pools;   // [count][pool_stride] pool of every stage
+  uint32_t pool_stride;
+  const SubResult *one;   // alternative to desc / pools: the placement held by this record
+  const SearchPP *pps;
+  int n_pp;
+  int objective, has_bound;
+  double bound;
+  double *T, *C;
+  uint64_t *mem;
+  uint32_t *mask;
+};
+
+constexpr int kPlaceWaves = 4;
+
+// The simulator (Sec. 4.3) for plans whose stages choose their pools freely: one wave per
+// plan, lane i takes stages i, i + 64, ...; sums in stage order.  A descriptor or pool out of
+// range yields mask = 0xFFFFFFFF, T = C = +inf, mem = 0.
+__global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl, PlaceArgs a) {
+  __shared__ RefineLds lds[kPlaceWaves];
+  __shared__ int s_cnt[kPlaceWaves][kSearchMaxPools];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const uint64_t ci = (uint64_t)blockIdx.x * kPlaceWaves + wv;
+  if (ci >= a.count) return;  // whole waves leave; no barrier below
+  const int G = pl.G, Z = pl.Z, ZG = pl.ZGr, MB = pl.MB, TP = pl.TP, DP = pl.DP;
+  int ip, q, it, id, im;
+  if (a.one) { ip = a.one->desc[0]; q = a.one->desc[1]; it = a.one->desc[2]; id = a.one->desc[3]; im = a.one->desc[4]; }
+  else { const int32_t *d = a.desc + ci * 5; ip = d[0]; q = d[1]; it = d[2]; id = d[3]; im = d[4]; }
+  double T = __builtin_huge_val(), C = T;
+  uint64_t peak = 0;
+  uint32_t mask = 0xFFFFFFFFu;
+  bool valid = ip >= 0 && ip < a.n_pp && it >= 0 && it < TP && id >= 0 && id < DP && im >= 0 && im < MB && q >= 0;
+  if (valid) valid = q < a.pps[ip].n_part;
+  const int P = valid ? a.pps[ip].P : 0;
+  if (valid && !a.one && (uint32_t)P > a.pool_stride) valid = false;
+  RefineLds &L = lds[wv];
+  int *cnt = s_cnt[wv];
+  if (valid) {
+    for (int p = lane; p < kSearchMaxPools; p += 64) cnt[p] = 0;
+    bool bad = false;
+    for (int i = lane; i < P; i += 64) {
+      const int p = a.one ? (int)a.one->pools[i] : a.pools[ci * a.pool_stride + i];
+      if (p < 0 || p >= ZG) bad = true;
+    }
+    if (__builtin_amdgcn_ballot_w64(bad) != 0) valid = false;
+  }
+  if (valid) {
+    mask = 0;
+    const uint32_t rs = a.pps[ip].rs0 + (uint32_t)q * (uint32_t)P;
+    const int64_t nb = pl.nb[im * DP + id], D = pl.dpv[id];
+    const int64_t tp = pl.tpv[it];
+    if (nb == 0) {
+      mask = 4u;
+    } else {
+      const double p2p = (double)pl.p2p[im];
+      __builtin_amdgcn_wave_barrier();
+      double max_t = 0.0, t_sync = 0.0, t_upd = 0.0;
+      uint32_t oom = 0, h1 = 0;
+      for (int i = lane; i < P; i += 64) {
+        const int p = a.one ? (int)a.one->pools[i] : a.pools[ci * a.pool_stride + i];
+        const int pn = i < P - 1 ? (a.one ? (int)a.one->pools[i + 1] : a.pools[ci * a.pool_stride + i + 1]) : p;
+        const int pv = i > 0 ? (a.one ? (int)a.one->pools[i - 1] : a.pools[ci * a.pool_stride + i - 1]) : p;
+        const int g = p % G, z = p / G, zn = pn / G, zp = pv / G;
+        atomicAdd(&cnt[p], 1);
+        const size_t si = (size_t)rs + i;
+        const uint64_t params = pl.st_params[si];
+        const uint64_t bytes = stage_bytes_of(params, pl.st_n[si], pl.bpp, i, P, (int)tp, nb, pl.act[im * TP + it]);
+        const uint64_t m = bytes + pl.res[g];
+        if (m > pl.cap[g]) oom = 1u;
+        if (tp > pl.node[g]) h1 = 1u;
+        peak = m > peak ? m : peak;
+        double x = 0.0, comm = 0.0;
+        if (i < P - 1) {
+          x += p2p / link_bw(pl, z, zn, p2p);
+          if (pl.egress && zn != z)
+            comm = (double)nb * (double)D * p2p * (pl.egress[z * Z + zn] + pl.egress[zn * Z + z]);
+        }
+        if (i > 0) x += p2p / link_bw(pl, z, zp, p2p);
+        const double ts = pl.st_c[((si * G + g) * MB + im) * TP + it] + x;
+        max_t = fmax(max_t, ts);
+        if (D > 1) {
+          const uint64_t shard = (params + (uint64_t)tp - 1) / (uint64_t)tp;
+          const double gbytes = (double)shard * (double)pl.gb;
+          t_sync = fmax(t_sync, 2.0 * (double)(D - 1) / (double)D * gbytes / link_bw(pl, z, z, gbytes));
+        }
+        t_upd = fmax(t_upd, pl.st_u[(si * G + g) * TP + it]);
+        L.t[i] = ts;
+        L.dol[i] = (double)(D * tp) * pl.price[g];
+        L.comm[i] = comm;
+      }
+      if (__builtin_amdgcn_ballot_w64(oom != 0) != 0) mask |= 1u;
+      if (__builtin_amdgcn_ballot_w64(h1 != 0) != 0) mask |= 8u;
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        const uint64_t o = __shfl_xor((unsigned long long)peak, off);
+        peak = o > peak ? o : peak;
+      }
+      max_t = wave_max_f64(max_t);
+      t_sync = wave_max_f64(t_sync);
+      t_upd = wave_max_f64(t_upd);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      bool over = false;  // quota: D replicas of every stage on the pool, tp GPUs each
+      for (int p = lane; p < ZG; p += 64)
+        if ((int64_t)cnt[p] * tp * D > (int64_t)pl.avail[p]) over = true;
+      if (__builtin_amdgcn_ballot_w64(over) != 0) mask |= 2u;
+      double sum_t = 0.0, dollars = 0.0, comm = 0.0;
+      for (int i = 0; i < P; ++i) {
+        sum_t += L.t[i];
+        dollars += L.dol[i];
+        comm += L.comm[i];
+      }
+      T = (sum_t + (double)(nb - 1) * max_t) + t_sync + t_upd;
+      C = dollars / 3600.0 * T + comm;
+      if (a.has_bound) {
+        if (a.objective == 0) { if (C > a.bound) mask |= 32u; }
+        else if (1.0 / T < a.bound) mask |= 32u;
+      }
+    }
+  }
+  if (lane == 0) {
+    if (a.T) a.T[ci] = T;
+    if (a.C) a.C[ci] = C;
+    if (a.mem) a.mem[ci] = mask == 0xFFFFFFFFu ? 0 : peak;
+    if (a.mask) a.mask[ci] = mask;
+  }
+}
+
+}  // namespace sailor

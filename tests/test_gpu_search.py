@@ -1,0 +1,220 @@
+"""The search over per-stage placements on the device (sailor_search) and the simulator for
+listed placements (sailor_eval_placements) against the oracle: fp64 on both sides, the same
+order of additions, so values are compared bit for bit and the chosen plans must be equal."""
+import numpy as np
+import pytest
+
+from oracle.oracle import MAX_THROUGHPUT, MIN_COST, Oracle
+from paper_2504_17096_amd import workloads as W
+from tests.helpers import make_problem
+
+pytestmark = pytest.mark.gpu
+OBJECTIVES = [MAX_THROUGHPUT, MIN_COST]
+
+
+def _plan(prob):
+    from paper_2504_17096_amd.binding import Plan
+    return Plan(prob)
+
+
+def _key(x, objective):
+    return x.iter_time if objective == MAX_THROUGHPUT else x.cost
+
+
+def _tiny(seed, **kw):
+    kw.setdefault("seg3_max_pp", 64)
+    return W.tiny_problem(seed, **kw)
+
+
+def check_same(got, want, objective):
+    """got: binding.StagePlan, want: oracle.StagePlan or None."""
+    assert got.found == (want is not None)
+    if want is None:
+        return
+    assert (got.pp_index, got.partition, got.tp_index, got.dp_index, got.mb_index) == \
+           (want.pp_idx, want.partition, want.tp_idx, want.dp_idx, want.mb_idx)
+    assert got.pools == want.pools
+    assert got.iter_time_s == want.iter_time and got.cost_per_iter == want.cost
+    assert got.exact == (not want.truncated)
+    assert got.expanded == want.expanded
+    # the same plan through the device's simulator for placements
+    assert got.mask == 0
+    assert got.eval_time_s == pytest.approx(got.iter_time_s, rel=1e-12)
+    assert got.eval_cost == pytest.approx(got.cost_per_iter, rel=1e-12)
+
+
+def gpu_eval_placements(torch, plan, desc, pools, objective=MAX_THROUGHPUT, bound=None):
+    n, stride = pools.shape
+    d_desc = torch.from_numpy(np.ascontiguousarray(desc, dtype=np.int32)).to("cuda:0")
+    d_pools = torch.from_numpy(np.ascontiguousarray(pools, dtype=np.int32)).to("cuda:0")
+    t = torch.empty(n, dtype=torch.float64, device="cuda:0")
+    c = torch.empty(n, dtype=torch.float64, device="cuda:0")
+    m = torch.empty(n, dtype=torch.int64, device="cuda:0")
+    k = torch.empty(n, dtype=torch.int32, device="cuda:0")
+    plan.eval_placements(n, d_desc, d_pools, stride, objective, bound, t, c, m, k,
+                         stream=torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    return (t.cpu().numpy(), c.cpu().numpy(), m.cpu().numpy().view(np.uint64),
+            k.cpu().numpy().view(np.uint32))
+
+
+def random_placements(prob, rng, n, stride):
+    desc = np.zeros((n, 5), np.int32)
+    pools = np.zeros((n, stride), np.int32)
+    zg = prob.n_zones * prob.n_types
+    for i in range(n):
+        ip = int(rng.integers(0, len(prob.pp_values)))
+        desc[i] = (ip, rng.integers(0, prob.n_partitions[ip]), rng.integers(0, len(prob.tp_values)),
+                   rng.integers(0, len(prob.dp_values)), rng.integers(0, len(prob.mb_values)))
+        P = int(prob.pp_values[ip])
+        # a few runs rather than white noise, so that valid plans are not rare
+        cuts = np.sort(rng.integers(0, P + 1, int(rng.integers(0, 4))))
+        run_pool = rng.integers(0, zg, len(cuts) + 1)
+        pools[i, :P] = run_pool[np.searchsorted(cuts, np.arange(P), side="right")]
+    return desc, pools
+
+
+@pytest.mark.parametrize("make", [
+    lambda: _tiny(1), lambda: _tiny(2, n_types=3, n_zones=3), lambda: W.config2(),
+    lambda: W.config3(), lambda: (lambda p: p.with_bw_poly(W.bandwidth_poly(p)))(_tiny(4, n_zones=3)),
+])
+def test_listed_placements_match_the_oracle(torch_cuda, make):
+    prob = make()
+    plan, orc = _plan(prob), Oracle(prob)
+    rng = np.random.default_rng(7)
+    try:
+        stride = int(max(prob.pp_values)) + 3
+        desc, pools = random_placements(prob, rng, 1500, stride)
+        for objective, bound in ((MAX_THROUGHPUT, None), (MIN_COST, 0.7)):
+            t, c, m, k = gpu_eval_placements(torch_cuda, plan, desc, pools, objective, bound)
+            valid = 0
+            for i in range(len(desc)):
+                P = int(prob.pp_values[desc[i, 0]])
+                e = orc.eval_assignment(desc[i, 0], desc[i, 1], desc[i, 3], desc[i, 4], desc[i, 2],
+                                        pools[i, :P], objective, bound)
+                assert k[i] == e.mask and m[i] == e.peak_mem, (i, desc[i], pools[i, :P])
+                if np.isinf(e.iter_time):
+                    assert np.isinf(t[i]) and np.isinf(c[i])
+                else:
+                    assert t[i] == pytest.approx(e.iter_time, rel=1e-12)
+                    assert c[i] == pytest.approx(e.cost, rel=1e-12)
+                valid += e.mask == 0
+            if bound is None and prob.n_layers <= 8:
+                assert valid > 10  # (on the large workloads random placements are rarely valid)
+        # out of range: a pool, a descriptor
+        bad_desc, bad_pools = desc[:4].copy(), pools[:4].copy()
+        bad_pools[0, 0] = prob.n_zones * prob.n_types
+        bad_desc[1, 0] = len(prob.pp_values)
+        bad_desc[2, 1] = 99
+        t, c, m, k = gpu_eval_placements(torch_cuda, plan, bad_desc, bad_pools)
+        assert list(k[:3]) == [0xFFFFFFFF] * 3 and np.all(np.isinf(t[:3])) and np.all(m[:3] == 0)
+        assert k[3] != 0xFFFFFFFF
+    finally:
+        plan.destroy()
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+@pytest.mark.parametrize("seed", [21, 22, 23, 24])
+def test_tiny_problems_exhaustively(torch_cuda, seed, objective):
+    prob = _tiny(seed, n_layers=6 if seed % 2 else 4, n_types=1 + seed % 2, n_zones=2 + seed % 2)
+    plan, orc = _plan(prob), Oracle(prob)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        want = orc.search_exhaustive(objective)
+        got = plan.search(256, objective, stream=stream)
+        assert got.found == (want is not None)
+        if want is None:
+            return
+        n_exact = 0
+        if got.exact:  # (6 pools x 6 stages outgrow the widest beam without an incumbent)
+            assert got.iter_time_s == want.iter_time and got.cost_per_iter == want.cost
+            n_exact += 1
+        # the beam algorithm step by step, at several widths, with and without an incumbent,
+        # restricted to runs, under a bound
+        flat = orc.best(objective)
+        other = want.cost if objective == MAX_THROUGHPUT else 1.0 / want.iter_time
+        bound = other * (0.8 if objective == MAX_THROUGHPUT else 1.25) * (1 + 1e-7)
+        for width in (1, 3, 16, 256):
+            check_same(plan.search(width, objective, stream=stream), orc.search_beam(width, objective), objective)
+            check_same(plan.search(width, objective, bound=bound, stream=stream),
+                       orc.search_beam(width, objective, bound), objective)
+            for runs in (1, 2, 3):
+                check_same(plan.search(width, objective, max_runs=runs, stream=stream),
+                           orc.search_beam(width, objective, max_runs=runs), objective)
+            if flat is not None:
+                inc = _key(flat, objective) * (1 + 1e-9)
+                check_same(plan.search(width, objective, incumbent=inc, stream=stream),
+                           orc.search_beam(width, objective, incumbent=inc), objective)
+        # three runs, uncut: the flat space's optimum, which is also what the library takes as
+        # its own incumbent
+        if flat is not None:
+            r3 = plan.search(256, objective, max_runs=3, stream=stream)
+            if r3.exact:
+                assert _key_of(r3, objective) == _key(flat, objective)
+                n_exact += 1
+            own = plan.search(256, objective, incumbent="flat", stream=stream)
+            assert own.incumbent == pytest.approx(_key(flat, objective), rel=1e-8)
+            check_same(own, orc.search_beam(256, objective, incumbent=own.incumbent), objective)
+            if own.exact:
+                assert _key_of(own, objective) == _key(want, objective)
+                n_exact += 1
+            assert own.expanded <= got.expanded
+        assert n_exact >= 1
+    finally:
+        plan.destroy()
+
+
+def _key_of(sp, objective):
+    return sp.iter_time_s if objective == MAX_THROUGHPUT else sp.cost_per_iter
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+def test_third_workload_sized_search(torch_cuda, objective):
+    # 4 zones x 3 types, up to 32 stages: 12^32 placements per sub-problem, 960 sub-problems;
+    # the device and the oracle walk the same frontiers
+    prob = W.config3()
+    plan, orc = _plan(prob), Oracle(prob)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        flat = orc.best(objective, n_threads=8)
+        inc = _key(flat, objective) * (1 + 1e-9)
+        for width in (8, 48):
+            got = plan.search(width, objective, incumbent=inc, stream=stream)
+            want = orc.search_beam(width, objective, incumbent=inc)
+            check_same(got, want, objective)
+            assert _key_of(got, objective) <= _key(flat, objective)
+            e = orc.eval_assignment(got.pp_index, got.partition, got.dp_index, got.mb_index, got.tp_index,
+                                    got.pools, objective)
+            assert e.mask == 0 and e.peak_mem == got.peak_mem_bytes and _key(e, objective) == _key_of(got, objective)
+        own = plan.search(48, objective, incumbent="flat", stream=stream)
+        assert own.pools == got.pools
+        # under a budget / a throughput floor taken off the data
+        other = flat.cost if objective == MAX_THROUGHPUT else 1.0 / flat.iter_time
+        bound = other * (0.9 if objective == MAX_THROUGHPUT else 1.1) * (1 + 1e-7)
+        check_same(plan.search(16, objective, bound=bound, stream=stream),
+                   orc.search_beam(16, objective, bound), objective)
+    finally:
+        plan.destroy()
+
+
+def test_search_rejects_what_it_does_not_cover(torch_cuda):
+    from paper_2504_17096_amd.binding import SAILOR_EINVAL, SailorError
+    for prob in (_tiny(1).with_per_segment_tp(), _tiny(1).with_mixed_types(),
+                 (lambda p: p.with_bw_poly(W.bandwidth_poly(p)))(_tiny(1))):
+        plan = _plan(prob)
+        try:
+            with pytest.raises(SailorError) as err:
+                plan.search(8)
+            assert err.value.status == SAILOR_EINVAL
+        finally:
+            plan.destroy()
+    plan = _plan(_tiny(1))
+    try:
+        for width in (0, 257):
+            with pytest.raises(SailorError):
+                plan.search(width)
+        # nothing valid: no GPUs at all
+        plan.set_avail(np.zeros_like(_tiny(1).avail))
+        assert not plan.search(8).found
+    finally:
+        plan.destroy()
