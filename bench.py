@@ -429,6 +429,24 @@ def main() -> int:
     segtp = widened(prob.with_per_segment_tp(), 16)
     mixed = widened(prob.with_mixed_types(), 16)
 
+    # search over per-stage placements (spaces that cannot be enumerated: 12^32 and 20^48
+    # placements per sub-problem), incumbent = the flat space's best plan through the evaluator
+    def searched(problem, width):
+        p = Plan(problem)
+        p.set_incremental(False)
+        flat = p.best_plan(objective=MAX_THROUGHPUT, stream=stream)
+        p.search(width, MAX_THROUGHPUT, incumbent="flat", stream=stream)  # (allocates its scratch)
+        t0 = time.perf_counter()
+        r = p.search(width, MAX_THROUGHPUT, incumbent="flat", stream=stream)
+        ms = (time.perf_counter() - t0) * 1e3
+        out = {"beam_width": width, "ms_incl_flat_best_plan": ms, "placements_generated": r.expanded,
+               "exact": r.exact, "flat_iter_time_s": flat.iter_time_s, "search_iter_time_s": r.iter_time_s,
+               "runs_of_pools": 1 + sum(a != b for a, b in zip(r.pools, r.pools[1:])), "pp": r.pp}
+        p.destroy()
+        return out
+
+    search = {"cfg3": searched(prob5, 64), "cfg4": searched(prob, 64)}
+
     # measured ceilings: scalar-per-lane FMA chain, streaming 16-byte stores
     fma_tflops, _ = microbench.fma(stream=stream)
     write_gbps, _ = microbench.write(stream=stream)
@@ -480,7 +498,7 @@ def main() -> int:
                       "dense_survivors_refined_valid": list(dense_counts)},
                   "plan_create_ms": create_ms, "plan_create_warm_ms": create_warm_ms,
                   "replan_stream": replan,
-                  "per_segment_tp": segtp, "mixed_types": mixed,
+                  "per_segment_tp": segtp, "mixed_types": mixed, "placement_search": search,
                   "event_schedule_top64": event_sched,
                   "survivors_refined_valid": list(counts), "best_index": best.index,
                   "top1_index": top1_index},

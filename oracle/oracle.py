@@ -156,6 +156,9 @@ def _load():
                                 C.c_int, C.c_int, C.POINTER(_Eval)]
         lib.so_eval_assignment.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                            C.c_void_p, C.c_int, C.c_int, C.c_double, C.POINTER(_Eval)]
+        lib.so_eval_split_assignment.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                                 C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_double,
+                                                 C.POINTER(_Eval)]
         lib.so_search_exhaustive.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, C.c_int,
                                              C.POINTER(_SearchResult)]
         lib.so_search_beam.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, C.POINTER(_SearchOpts),
@@ -326,6 +329,20 @@ class Oracle:
         rc = self._lib.so_eval_assignment(self._ctx, pp_idx, partition, dp_idx, mb_idx, tp_idx,
                                           a.ctypes.data, objective, bound is not None,
                                           0.0 if bound is None else bound, C.byref(e))
+        if rc != 0:
+            raise ValueError("assignment out of range")
+        return _ev(e)
+
+    def eval_split_assignment(self, pp_idx: int, partition: int, dp_idx: int, mb_idx: int, tp_idx: int,
+                              pools_a, pools_b, objective: int = MAX_THROUGHPUT,
+                              bound: Optional[float] = None) -> Eval:
+        a = np.ascontiguousarray(pools_a, dtype=np.int32)
+        b = np.ascontiguousarray(pools_b, dtype=np.int32)
+        e = _Eval()
+        rc = self._lib.so_eval_split_assignment(self._ctx, pp_idx, partition, dp_idx, mb_idx, tp_idx,
+                                                a.ctypes.data, b.ctypes.data, objective,
+                                                bound is not None, 0.0 if bound is None else bound,
+                                                C.byref(e))
         if rc != 0:
             raise ValueError("assignment out of range")
         return _ev(e)

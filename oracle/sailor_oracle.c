@@ -472,6 +472,145 @@ int so_eval_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, i
   return 0;
 }
 
+/* A plan whose stages may split their D replicas over two pools, half on each -- pools of
+ * different zones too (the D tuples (GPU, TP, zone) of a stage, Sec. 4.2).  Replicas 0 .. D/2-1
+ * form the pipelines through the first pools, the others the pipelines through the second
+ * pools; the two kinds of pipeline differ in stage times and transfers, and the iteration
+ * waits for the slower kind: T_iter = max(T_pp) + T_sync + T_update (Sec. 4.3).  The gradient
+ * all-reduce of a split stage is a ring through both pools and runs at the pace of its slowest
+ * link (intra-zone links of both zones, the two links between them).  Cross-zone traffic is
+ * paid for: the pipelines' transfers (each kind of pipeline carries half of the replicas) and
+ * the two ring links between the zones of a split stage.
+ * pools_a[i] / pools_b[i]: zone * n_types + type (plain pools only); equal = not split.
+ * Returns 0, -1 for a value out of range or a problem with extended types. */
+int so_eval_split_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                             int tp_idx, const int32_t *pools_a, const int32_t *pools_b,
+                             int objective, int has_bound, double bound, so_eval *out) {
+  const so_problem *p = &c->p;
+  if (p->mixed_types || pp_idx < 0 || pp_idx >= p->n_pp || dp_idx < 0 || dp_idx >= p->n_dp ||
+      mb_idx < 0 || mb_idx >= p->n_mb || tp_idx < 0 || tp_idx >= p->n_tp || partition < 0 ||
+      partition >= p->n_partitions[pp_idx])
+    return -1;
+  const int P = p->pp_values[pp_idx], G = p->n_types, Z = p->n_zones;
+  for (int i = 0; i < P; ++i)
+    if (pools_a[i] < 0 || pools_a[i] >= Z * G || pools_b[i] < 0 || pools_b[i] >= Z * G) return -1;
+  const int64_t replicas = p->dp_values[dp_idx], micro = p->mb_values[mb_idx];
+  const int64_t tp = p->tp_values[tp_idx];
+  so_config g;
+  memset(&g, 0, sizeof g);
+  g.pp_idx = pp_idx; g.pp = P; g.partition = partition;
+  const int32_t *nl = partition_row(c, &g);
+  out->index = 0; out->mask = 0; out->peak_mem = 0;
+  if (p->global_batch % (replicas * micro) != 0) {
+    out->mask = SO_BIT_BATCH;
+    out->iter_time = INFINITY;
+    out->cost = INFINITY;
+    return 0;
+  }
+  const int64_t n_micro = p->global_batch / (replicas * micro);
+  const int32_t *side[2] = {pools_a, pools_b};
+
+  /* quota, counted in half replicas; node size; an odd D cannot be halved */
+  int64_t halves[SO_MAX_POOLS];
+  memset(halves, 0, sizeof halves);
+  for (int i = 0; i < P; ++i) {
+    halves[pools_a[i]] += tp;
+    halves[pools_b[i]] += tp;
+    if (pools_a[i] != pools_b[i] && replicas % 2 != 0) out->mask |= SO_BIT_QUOTA;
+    for (int h = 0; h < 2; ++h)
+      if (tp > p->gpus_per_node[side[h][i] % G]) out->mask |= SO_BIT_TP_NODE;
+  }
+  for (int a = 0; a < Z * G; ++a)
+    if (halves[a] * replicas > 2 * (int64_t)p->avail[a]) out->mask |= SO_BIT_QUOTA;
+
+  /* memory of a worker of either half */
+  uint64_t shard_of[SO_MAX_STAGES];
+  int first_of[SO_MAX_STAGES];
+  int layer = 0;
+  uint64_t peak = 0;
+  for (int i = 0; i < P; ++i) {
+    uint64_t params = 0;
+    first_of[i] = layer;
+    for (int l = layer; l < layer + nl[i]; ++l) params += p->layer_params[l];
+    layer += nl[i];
+    if (i == 0) params += p->embed_params;
+    if (i + 1 == P) params += p->head_params;
+    shard_of[i] = (params + (uint64_t)tp - 1) / (uint64_t)tp;
+    const int64_t alive = (P - i) < n_micro ? (P - i) : n_micro;
+    const uint64_t bytes = shard_of[i] * (uint64_t)p->bytes_per_param +
+                           (uint64_t)alive * (uint64_t)nl[i] *
+                               p->act_store_bytes[(size_t)mb_idx * p->n_tp + tp_idx];
+    for (int h = 0; h < 2; ++h) {
+      const int gt = side[h][i] % G;
+      const uint64_t m = bytes + p->mem_reserved[gt];
+      if (m > p->mem_capacity[gt]) out->mask |= SO_BIT_OOM;
+      if (m > peak) peak = m;
+    }
+  }
+  out->peak_mem = peak;
+
+  /* the two kinds of pipeline */
+  const double msg = (double)p->p2p_bytes[mb_idx];
+  const double *price_of_byte = p->egress_per_byte; /* $/byte between zones, or NULL */
+  double t_pipe = 0.0, t_update = 0.0, traffic_cost = 0.0;
+  for (int h = 0; h < 2; ++h) {
+    double total = 0.0, slowest = 0.0;
+    for (int i = 0; i < P; ++i) {
+      const int gt = side[h][i] % G, z = side[h][i] / G;
+      double t = layer_time_sum(p, p->t_fwd, gt, mb_idx, tp_idx, first_of[i], nl[i]) +
+                 layer_time_sum(p, p->t_bwd, gt, mb_idx, tp_idx, first_of[i], nl[i]);
+      double moves = 0.0;
+      if (i < P - 1) {
+        const int zn = side[h][i + 1] / G;
+        moves += msg / link_bandwidth(p, z, zn, msg);
+        if (price_of_byte && zn != z) /* this kind of pipeline carries half of the replicas */
+          traffic_cost += (double)n_micro * (0.5 * (double)replicas) * msg *
+                          (price_of_byte[(size_t)z * Z + zn] + price_of_byte[(size_t)zn * Z + z]);
+      }
+      if (i > 0) moves += msg / link_bandwidth(p, z, side[h][i - 1] / G, msg);
+      t += moves;
+      total += t;
+      if (t > slowest) slowest = t;
+      const double u = upd_time_sum(p, gt, tp_idx, first_of[i], nl[i]);
+      if (u > t_update) t_update = u;
+    }
+    const double t_kind = total + (double)(n_micro - 1) * slowest;
+    if (t_kind > t_pipe) t_pipe = t_kind;
+  }
+
+  /* gradient all-reduce per stage: a ring through both pools, as fast as its slowest link */
+  double t_allreduce = 0.0;
+  if (replicas > 1)
+    for (int i = 0; i < P; ++i) {
+      const int za = pools_a[i] / G, zb = pools_b[i] / G;
+      const double buffer = (double)shard_of[i] * (double)p->grad_bytes_per_param;
+      double link = link_bandwidth(p, za, za, buffer);
+      if (zb != za) {
+        const double others[3] = {link_bandwidth(p, zb, zb, buffer), link_bandwidth(p, za, zb, buffer),
+                                  link_bandwidth(p, zb, za, buffer)};
+        for (int k = 0; k < 3; ++k)
+          if (others[k] < link) link = others[k];
+      }
+      const double ring_bytes = 2.0 * (double)(replicas - 1) / (double)replicas * buffer;
+      const double t = ring_bytes / link;
+      if (t > t_allreduce) t_allreduce = t;
+      if (price_of_byte && zb != za) /* the ring crosses between the zones once each way */
+        traffic_cost += ring_bytes * (price_of_byte[(size_t)za * Z + zb] + price_of_byte[(size_t)zb * Z + za]);
+    }
+  out->iter_time = t_pipe + t_allreduce + t_update;
+
+  double rent = 0.0; /* $/h of all replicas: half of a stage's at each pool's price */
+  for (int i = 0; i < P; ++i)
+    rent += (double)(replicas * tp) *
+            (0.5 * (p->price_per_hour[pools_a[i] % G] + p->price_per_hour[pools_b[i] % G]));
+  out->cost = rent / 3600.0 * out->iter_time + traffic_cost;
+  if (has_bound) {
+    if (objective == SO_MAX_THROUGHPUT ? out->cost > bound : 1.0 / out->iter_time < bound)
+      out->mask |= SO_BIT_CONSTRAINT;
+  }
+  return 0;
+}
+
 const so_problem *so_problem_of(const so_ctx *c) { return &c->p; }
 
 int so_eval_one(const so_ctx *c, uint64_t index, int objective, int has_bound, double bound,

@@ -149,6 +149,14 @@ int so_eval_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, i
                        so_eval *out);
 const so_problem *so_problem_of(const so_ctx *c);
 
+/* The same with stages that may split their replicas over two pools, also of different zones:
+ * pools_a[i] / pools_b[i] (equal = not split), half of the D replicas on each.  T_iter takes
+ * the slower of the two kinds of pipeline (Sec. 4.3: max over pipelines), a split stage's
+ * all-reduce its slowest link, the cost includes the ring's traffic between the zones. */
+int so_eval_split_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                             int tp_idx, const int32_t *pools_a, const int32_t *pools_b,
+                             int objective, int has_bound, double bound, so_eval *out);
+
 #define SO_SEARCH_MAX_STAGES 256
 typedef struct {
   int32_t found;                 /* 1: a valid plan exists (within the incumbent, if one was given) */

@@ -139,6 +139,46 @@ def test_fourth_workload_sampled_outputs(cfg4, torch_cuda):
     assert float(t[fin].min()) > 0.0 and float(c[fin].min()) > 0.0
 
 
+@pytest.mark.parametrize("objective", [MAX_THROUGHPUT, MIN_COST])
+def test_fourth_workload_whole_space_outputs(cfg4, torch_cuda, objective):
+    # all 104 256 000 candidates, every output, with the constraint bit of each objective; the
+    # oracle's outputs are produced and compared in slices of 2^24 candidates
+    prob, plan, orc = cfg4
+    torch = torch_cuda
+    n = orc.num_candidates
+    ref = orc.best(objective=MIN_COST if objective == MAX_THROUGHPUT else MAX_THROUGHPUT, n_threads=THREADS)
+    bound = off_data(1.2 * ref.cost if objective == MAX_THROUGHPUT else 0.5 / ref.iter_time)
+    t = torch.empty(n, dtype=torch.float32, device="cuda:0")
+    c = torch.empty(n, dtype=torch.float32, device="cuda:0")
+    m = torch.empty(n, dtype=torch.int64, device="cuda:0")
+    k = torch.empty(n, dtype=torch.int32, device="cuda:0")
+    plan.eval_batch(0, n, objective=objective, bound=bound, d_time=t, d_cost=c, d_mem=m, d_mask=k,
+                    stream=torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    step = 1 << 24
+    for lo in range(0, n, step):
+        hi = min(n, lo + step)
+        want = orc.eval_batch(lo, hi - lo, objective=objective, bound=bound, n_threads=THREADS)
+        got = (t[lo:hi].cpu().numpy(), c[lo:hi].cpu().numpy(), m[lo:hi].cpu().numpy().view(np.uint64),
+               k[lo:hi].cpu().numpy().view(np.uint32))
+        assert_eval_parity(got, want, objective, bound)
+
+
+@pytest.mark.parametrize("objective", [MAX_THROUGHPUT, MIN_COST])
+def test_fourth_workload_with_mixed_replica_types_full_space_selection(torch_cuda, objective):
+    # 1 094 400 000 candidates: the oracle ranks the whole space (16 threads, half a minute)
+    prob = W.config4().with_mixed_types()
+    plan, orc = _plan(prob), Oracle(prob)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        want = orc.topk(64, objective=objective, n_threads=THREADS)
+        check_topk(plan.topk(64, objective=objective, stream=stream), want, objective, orc)
+        best = orc.best(objective=objective, n_threads=THREADS)
+        check_result(plan.best_plan(objective=objective, stream=stream), best, orc)
+    finally:
+        plan.destroy()
+
+
 _cfg4_cache = {}
 
 

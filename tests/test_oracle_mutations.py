@@ -32,6 +32,12 @@ MUTANTS = [
     ("test_oracle_mixed_types.py", "half_gpus_on_pool[zone_of[i] * G + type_b[i]] += tp_of[i];", ""),
     ("test_oracle_mixed_types.py", "if (f2 + b2 > f + b) { f = f2; b = b2; }\n    }\n    double x = 0.0;",
      "if (f2 + b2 < f + b) { f = f2; b = b2; }\n    }\n    double x = 0.0;"),
+    # replicas of a stage over two pools: the fastest link instead of the slowest, all replicas
+    # charged on one kind of pipeline, the last kind of pipeline instead of the slower
+    ("test_oracle_split_replicas.py", "if (others[k] < link) link = others[k];",
+     "if (others[k] > link) link = others[k];"),
+    ("test_oracle_split_replicas.py", "(0.5 * (double)replicas) * msg", "((double)replicas) * msg"),
+    ("test_oracle_split_replicas.py", "if (t_kind > t_pipe) t_pipe = t_kind;", "t_pipe = t_kind;"),
     # the search: a bound that is not one, a forgotten transfer, a quota that is never full,
     # the beam's order
     ("test_oracle_search.py", "const double tsum = (st->sum + t_open) + s->Ssum[i];",
