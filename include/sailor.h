@@ -370,14 +370,25 @@ sailor_status sailor_search(sailor_plan *plan, sailor_objective objective,
                             void *hip_stream);
 
 /* The simulator (Sec. 4.3) for listed plans of that kind, fp64, exact bytes:
- *   d_desc   device, [count][5]: pp index, partition, TP index, D index, microbatch index
- *   d_pools  device, [count][pool_stride]: pool of every stage (pool_stride >= pp)
- *   outputs  device, [count], any may be NULL
+ *   d_desc    device, [count][5]: pp index, partition, TP index, D index, microbatch index
+ *   d_pools   device, [count][pool_stride]: pool of every stage (pool_stride >= pp)
+ *   d_pools_b device, same shape, or NULL.  Given, a stage's D replicas are split, half on
+ *             d_pools' pool and half on d_pools_b's -- any two pools, also of different zones
+ *             (the D tuples (GPU, TP, zone) of a stage, Sec. 4.2); equal entries = not split.
+ *             The replicas on the first pools and those on the second pools form two kinds of
+ *             pipeline and T_iter = max over them + T_sync + T_update (Sec. 4.3); the all-reduce
+ *             of a split stage is a ring through both pools at the pace of its slowest link
+ *             (both zones' own links and the two between them); traffic between zones is paid
+ *             for: the pipelines' (each kind carries D / 2 replicas) and the ring's two
+ *             crossings of 2 (D - 1) / D x gradient bytes; memory and node size hold for both
+ *             halves, quotas count halves, an odd D with a split stage is OVER_QUOTA
+ *   outputs   device, [count], any may be NULL
  * A descriptor or pool out of range yields mask = 0xFFFFFFFF, time = cost = +inf, mem = 0; a
  * batch that does not divide mask = BATCH_INDIVISIBLE with +inf and 0.  Asynchronous on
  * hip_stream.  SAILOR_EINVAL for per_segment_tp / mixed_types problems or more than 64 pools. */
 sailor_status sailor_eval_placements(sailor_plan *plan, uint64_t count, const int32_t *d_desc,
-                                     const int32_t *d_pools, uint32_t pool_stride,
+                                     const int32_t *d_pools, const int32_t *d_pools_b,
+                                     uint32_t pool_stride,
                                      sailor_objective objective,
                                      const sailor_constraint *constraint, double *d_time,
                                      double *d_cost, uint64_t *d_mem, uint32_t *d_mask,

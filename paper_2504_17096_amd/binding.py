@@ -189,7 +189,7 @@ def load_library() -> C.CDLL:
     lib.sailor_plan_last_scan.argtypes = [P, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
     lib.sailor_search.argtypes = [P, C.c_int, C.POINTER(sailor_constraint),
                                   C.POINTER(sailor_search_options), C.POINTER(sailor_stage_plan), P]
-    lib.sailor_eval_placements.argtypes = [P, C.c_uint64, P, P, C.c_uint32, C.c_int,
+    lib.sailor_eval_placements.argtypes = [P, C.c_uint64, P, P, P, C.c_uint32, C.c_int,
                                            C.POINTER(sailor_constraint), P, P, P, P, P]
     lib.sailor_plan_last_counts.argtypes = [P, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                             C.POINTER(C.c_uint32)]
@@ -394,10 +394,12 @@ class Plan:
 
     def eval_placements(self, count: int, d_desc, d_pools, pool_stride: int,
                         objective: int = MAX_THROUGHPUT, bound: Optional[float] = None, d_time=None,
-                        d_cost=None, d_mem=None, d_mask=None, stream: int = 0) -> None:
-        """sailor_eval_placements; device tensors: int32 [count][5], int32 [count][pool_stride],
+                        d_cost=None, d_mem=None, d_mask=None, stream: int = 0, d_pools_b=None) -> None:
+        """sailor_eval_placements; device tensors: int32 [count][5], int32 [count][pool_stride]
+        (and optionally the pools of the other half of every stage's replicas),
         float64 / float64 / int64 / int32 outputs."""
-        rc = self._lib.sailor_eval_placements(self._h, count, _ptr(d_desc), _ptr(d_pools), pool_stride,
+        rc = self._lib.sailor_eval_placements(self._h, count, _ptr(d_desc), _ptr(d_pools),
+                                              _ptr(d_pools_b), pool_stride,
                                               objective, _constraint(bound), _ptr(d_time), _ptr(d_cost),
                                               _ptr(d_mem), _ptr(d_mask), stream or None)
         if rc != SAILOR_OK:

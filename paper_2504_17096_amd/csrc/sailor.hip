@@ -1363,7 +1363,8 @@ static sailor_status search_setup(sailor_plan *pl, bool with_scratch) {
 }
 
 sailor_status sailor_eval_placements(sailor_plan *pl, uint64_t count, const int32_t *d_desc,
-                                     const int32_t *d_pools, uint32_t pool_stride,
+                                     const int32_t *d_pools, const int32_t *d_pools_b,
+                                     uint32_t pool_stride,
                                      sailor_objective objective, const sailor_constraint *constraint,
                                      double *d_time, double *d_cost, uint64_t *d_mem, uint32_t *d_mask,
                                      void *hip_stream) {
@@ -1381,7 +1382,7 @@ sailor_status sailor_eval_placements(sailor_plan *pl, uint64_t count, const int3
   rc = refresh_avail(pl, st);
   if (rc != SAILOR_OK) return rc;
   PlaceArgs a{};
-  a.count = count; a.desc = d_desc; a.pools = d_pools; a.pool_stride = pool_stride;
+  a.count = count; a.desc = d_desc; a.pools = d_pools; a.pools_b = d_pools_b; a.pool_stride = pool_stride;
   a.pps = pl->d_search_pps; a.n_pp = (int)pl->search_pps.size();
   a.objective = (int)objective;
   a.has_bound = (constraint && constraint->has_bound) ? 1 : 0;

@@ -457,6 +457,7 @@ struct PlaceArgs {
   uint64_t count;
   const int32_t *desc;    // [count][5] pp index, partition, tp index, dp index, mb index
   const int32_t *pools;   // [count][pool_stride] pool of every stage
+  const int32_t *pools_b; // optional, same shape: pool of the other half of every stage's replicas
   uint32_t pool_stride;
   const SubResult *one;   // alternative to desc / pools: the placement held by this record
   const SearchPP *pps;
@@ -470,11 +471,107 @@ struct PlaceArgs {
 
 constexpr int kPlaceWaves = 4;
 
+// Stages that split their D replicas over two pools, half on each, also across zones (the D
+// tuples of a stage, Sec. 4.2): the replicas on the first pools and those on the second pools
+// form two kinds of pipeline; T_iter takes the slower kind (Sec. 4.3: max over pipelines), a
+// split stage's all-reduce runs over the slowest link of a ring through both pools, and the
+// traffic between zones -- of the pipelines, each kind carrying half of the replicas, and of
+// the ring -- is paid for.  One wave; valid descriptor and pools; nb > 0.
+__device__ __forceinline__ void eval_split_wave(const DevPlan &pl, const int32_t *pa, const int32_t *pb,
+                                                int P, uint32_t rs, int it, int im, int64_t nb, int64_t D,
+                                                int64_t tp, RefineLds &L, double *t_second, int *cnt,
+                                                double &T, double &C, uint64_t &peak, uint32_t &mask) {
+  const int G = pl.G, Z = pl.Z, ZG = pl.ZGr, MB = pl.MB, TP = pl.TP;
+  const int lane = threadIdx.x & 63;
+  const double p2p = (double)pl.p2p[im];
+  double max_a = 0.0, max_b = 0.0, t_sync = 0.0, t_upd = 0.0;
+  uint32_t oom = 0, h1 = 0, odd = 0;
+  for (int i = lane; i < P; i += 64) {
+    const int a = pa[i], b = pb[i];
+    const int ga = a % G, za = a / G, gb = b % G, zb = b / G;
+    atomicAdd(&cnt[a], 1);  // halves of a replica
+    atomicAdd(&cnt[b], 1);
+    if (a != b && (D & 1)) odd = 1u;
+    const size_t si = (size_t)rs + i;
+    const uint64_t params = pl.st_params[si];
+    const uint64_t bytes = stage_bytes_of(params, pl.st_n[si], pl.bpp, i, P, (int)tp, nb, pl.act[im * TP + it]);
+    const uint64_t m1 = bytes + pl.res[ga], m2 = bytes + pl.res[gb];
+    if (m1 > pl.cap[ga] || m2 > pl.cap[gb]) oom = 1u;
+    if (tp > pl.node[ga] || tp > pl.node[gb]) h1 = 1u;
+    peak = m1 > peak ? m1 : peak;
+    peak = m2 > peak ? m2 : peak;
+    double xa = 0.0, xb = 0.0, traffic = 0.0;
+    if (i < P - 1) {
+      const int zna = pa[i + 1] / G, znb = pb[i + 1] / G;
+      xa += p2p / link_bw(pl, za, zna, p2p);
+      xb += p2p / link_bw(pl, zb, znb, p2p);
+      if (pl.egress) {  // each kind of pipeline carries half of the replicas
+        if (zna != za) traffic += (double)nb * (0.5 * (double)D) * p2p * (pl.egress[za * Z + zna] + pl.egress[zna * Z + za]);
+        if (znb != zb) traffic += (double)nb * (0.5 * (double)D) * p2p * (pl.egress[zb * Z + znb] + pl.egress[znb * Z + zb]);
+      }
+    }
+    if (i > 0) {
+      xa += p2p / link_bw(pl, za, pa[i - 1] / G, p2p);
+      xb += p2p / link_bw(pl, zb, pb[i - 1] / G, p2p);
+    }
+    const double ta = pl.st_c[((si * G + ga) * MB + im) * TP + it] + xa;
+    const double tb = pl.st_c[((si * G + gb) * MB + im) * TP + it] + xb;
+    max_a = fmax(max_a, ta);
+    max_b = fmax(max_b, tb);
+    if (D > 1) {
+      const uint64_t shard = (params + (uint64_t)tp - 1) / (uint64_t)tp;
+      const double buffer = (double)shard * (double)pl.gb;
+      double link = link_bw(pl, za, za, buffer);
+      if (zb != za)
+        link = fmin(fmin(link, link_bw(pl, zb, zb, buffer)),
+                    fmin(link_bw(pl, za, zb, buffer), link_bw(pl, zb, za, buffer)));
+      const double ring_bytes = 2.0 * (double)(D - 1) / (double)D * buffer;
+      t_sync = fmax(t_sync, ring_bytes / link);
+      if (pl.egress && zb != za) traffic += ring_bytes * (pl.egress[za * Z + zb] + pl.egress[zb * Z + za]);
+    }
+    t_upd = fmax(t_upd, fmax(pl.st_u[(si * G + ga) * TP + it], pl.st_u[(si * G + gb) * TP + it]));
+    L.t[i] = ta;
+    t_second[i] = tb;
+    L.dol[i] = (double)(D * tp) * (0.5 * (pl.price[ga] + pl.price[gb]));
+    L.comm[i] = traffic;
+  }
+  if (__builtin_amdgcn_ballot_w64(oom != 0) != 0) mask |= 1u;
+  if (__builtin_amdgcn_ballot_w64(h1 != 0) != 0) mask |= 8u;
+  if (__builtin_amdgcn_ballot_w64(odd != 0) != 0) mask |= 2u;  // D replicas cannot be halved
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const uint64_t o = __shfl_xor((unsigned long long)peak, off);
+    peak = o > peak ? o : peak;
+  }
+  max_a = wave_max_f64(max_a);
+  max_b = wave_max_f64(max_b);
+  t_sync = wave_max_f64(t_sync);
+  t_upd = wave_max_f64(t_upd);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  bool over = false;  // every pool holds the halves placed on it
+  for (int p = lane; p < ZG; p += 64)
+    if ((int64_t)cnt[p] * tp * D > 2 * (int64_t)pl.avail[p]) over = true;
+  if (__builtin_amdgcn_ballot_w64(over) != 0) mask |= 2u;
+  double sum_a = 0.0, sum_b = 0.0, dollars = 0.0, traffic = 0.0;
+  for (int i = 0; i < P; ++i) {
+    sum_a += L.t[i];
+    sum_b += t_second[i];
+    dollars += L.dol[i];
+    traffic += L.comm[i];
+  }
+  const double t_pp = fmax(sum_a + (double)(nb - 1) * max_a, sum_b + (double)(nb - 1) * max_b);
+  T = (t_pp + t_sync) + t_upd;
+  C = dollars / 3600.0 * T + traffic;
+}
+
 // The simulator (Sec. 4.3) for plans whose stages choose their pools freely: one wave per
 // plan, lane i takes stages i, i + 64, ...; sums in stage order.  A descriptor or pool out of
 // range yields mask = 0xFFFFFFFF, T = C = +inf, mem = 0.
 __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl, PlaceArgs a) {
   __shared__ RefineLds lds[kPlaceWaves];
+  __shared__ double s_second[kPlaceWaves][kMaxStages];  // stage times of the second kind of pipeline
   __shared__ int s_cnt[kPlaceWaves][kSearchMaxPools];
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const uint64_t ci = (uint64_t)blockIdx.x * kPlaceWaves + wv;
@@ -498,6 +595,10 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl
     for (int i = lane; i < P; i += 64) {
       const int p = a.one ? (int)a.one->pools[i] : a.pools[ci * a.pool_stride + i];
       if (p < 0 || p >= ZG) bad = true;
+      if (a.pools_b && !a.one) {
+        const int p2 = a.pools_b[ci * a.pool_stride + i];
+        if (p2 < 0 || p2 >= ZG) bad = true;
+      }
     }
     if (__builtin_amdgcn_ballot_w64(bad) != 0) valid = false;
   }
@@ -508,6 +609,14 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl
     const int64_t tp = pl.tpv[it];
     if (nb == 0) {
       mask = 4u;
+    } else if (a.pools_b && !a.one) {
+      __builtin_amdgcn_wave_barrier();
+      eval_split_wave(pl, a.pools + ci * a.pool_stride, a.pools_b + ci * a.pool_stride, P, rs, it, im, nb, D,
+                      tp, L, s_second[wv], cnt, T, C, peak, mask);
+      if (a.has_bound) {
+        if (a.objective == 0) { if (C > a.bound) mask |= 32u; }
+        else if (1.0 / T < a.bound) mask |= 32u;
+      }
     } else {
       const double p2p = (double)pl.p2p[im];
       __builtin_amdgcn_wave_barrier();

@@ -218,3 +218,94 @@ def test_search_rejects_what_it_does_not_cover(torch_cuda):
         assert not plan.search(8).found
     finally:
         plan.destroy()
+
+
+# ---- stages that split their replicas over two pools (also across zones) -------------------
+
+def gpu_eval_split(torch, plan, desc, pools_a, pools_b, objective=MAX_THROUGHPUT, bound=None):
+    n, stride = pools_a.shape
+    dev = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to("cuda:0")
+    t = torch.empty(n, dtype=torch.float64, device="cuda:0")
+    c = torch.empty(n, dtype=torch.float64, device="cuda:0")
+    m = torch.empty(n, dtype=torch.int64, device="cuda:0")
+    k = torch.empty(n, dtype=torch.int32, device="cuda:0")
+    plan.eval_placements(n, dev(desc), dev(pools_a), stride, objective, bound, t, c, m, k,
+                         stream=torch.cuda.current_stream().cuda_stream, d_pools_b=dev(pools_b))
+    torch.cuda.synchronize()
+    return (t.cpu().numpy(), c.cpu().numpy(), m.cpu().numpy().view(np.uint64),
+            k.cpu().numpy().view(np.uint32))
+
+
+@pytest.mark.parametrize("make", [
+    lambda: _tiny(1), lambda: _tiny(2, n_types=3, n_zones=3), lambda: W.config2(), lambda: W.config3(),
+    lambda: (lambda p: p.with_bw_poly(W.bandwidth_poly(p)))(_tiny(4, n_zones=3)),
+])
+def test_split_placements_match_the_oracle(torch_cuda, make):
+    prob = make()
+    plan, orc = _plan(prob), Oracle(prob)
+    rng = np.random.default_rng(9)
+    try:
+        stride = int(max(prob.pp_values))
+        desc, pa = random_placements(prob, rng, 1200, stride)
+        _, pb = random_placements(prob, rng, 1200, stride)
+        keep = rng.random(pa.shape) < 0.6          # most stages unsplit, some split anywhere
+        pb = np.where(keep, pa, pb)
+        for objective, bound in ((MAX_THROUGHPUT, None), (MAX_THROUGHPUT, 0.02), (MIN_COST, 0.7)):
+            t, c, m, k = gpu_eval_split(torch_cuda, plan, desc, pa, pb, objective, bound)
+            valid = 0
+            for i in range(len(desc)):
+                P = int(prob.pp_values[desc[i, 0]])
+                e = orc.eval_split_assignment(desc[i, 0], desc[i, 1], desc[i, 3], desc[i, 4], desc[i, 2],
+                                              pa[i, :P], pb[i, :P], objective, bound)
+                tight = bound is not None and np.isfinite(e.iter_time) and abs(
+                    (e.cost if objective == MAX_THROUGHPUT else 1.0 / e.iter_time) / bound - 1.0) < 1e-9
+                if not tight:
+                    assert k[i] == e.mask, (i, desc[i], pa[i, :P], pb[i, :P])
+                assert m[i] == e.peak_mem
+                if np.isinf(e.iter_time):
+                    assert np.isinf(t[i]) and np.isinf(c[i])
+                else:
+                    assert t[i] == pytest.approx(e.iter_time, rel=1e-12)
+                    assert c[i] == pytest.approx(e.cost, rel=1e-12)
+                valid += e.mask == 0
+            if bound is None and prob.n_layers <= 8:
+                assert valid > 10
+        # equal pools everywhere: the unsplit evaluation
+        t0, c0, m0, k0 = gpu_eval_placements(torch_cuda, plan, desc, pa)
+        t1, c1, m1, k1 = gpu_eval_split(torch_cuda, plan, desc, pa, pa)
+        assert np.array_equal(k0, k1) and np.array_equal(m0, m1)
+        fin = np.isfinite(t0)
+        assert np.allclose(t0[fin], t1[fin], rtol=1e-13, atol=0) and np.allclose(c0[fin], c1[fin], rtol=1e-13, atol=0)
+    finally:
+        plan.destroy()
+
+
+def test_best_split_plan_of_an_enumerated_space(torch_cuda):
+    # every way to place and split two stages over 2 zones x 2 types, every (TP, D, microbatch
+    # size): the device evaluates the list, the smallest key is the oracle's
+    prob = _tiny(6, n_layers=4, n_types=2, n_zones=2)
+    plan, orc = _plan(prob), Oracle(prob)
+    try:
+        ip = list(prob.pp_values).index(2)
+        rows = [(ip, q, it, idp, im, a0, a1, b0, b1)
+                for q in range(int(prob.n_partitions[ip])) for it in range(len(prob.tp_values))
+                for idp in range(len(prob.dp_values)) for im in range(len(prob.mb_values))
+                for a0 in range(4) for a1 in range(4) for b0 in range(4) for b1 in range(4)]
+        rows = np.array(rows, np.int32)
+        desc, pa, pb = rows[:, :5], rows[:, 5:7], rows[:, 7:9]
+        for objective in OBJECTIVES:
+            t, c, m, k = gpu_eval_split(torch_cuda, plan, desc, pa, pb, objective)
+            key = np.where(k == 0, t if objective == MAX_THROUGHPUT else c, np.inf)
+            best_key, best_i = None, None
+            for i, r in enumerate(rows):
+                e = orc.eval_split_assignment(r[0], r[1], r[3], r[4], r[2], pa[i], pb[i], objective)
+                if e.mask == 0 and (best_key is None or _key(e, objective) < best_key):
+                    best_key, best_i = _key(e, objective), i
+            assert best_i is not None
+            assert key.min() == pytest.approx(best_key, rel=1e-12)
+            assert key[best_i] == key.min()
+            # splitting helps here or not: either way no unsplit plan beats the winner
+            unsplit = np.all(pa == pb, axis=1)
+            assert key[unsplit].min() >= key.min()
+    finally:
+        plan.destroy()
