@@ -88,7 +88,10 @@ enum {
 
 /* Limits checked by sailor_plan_create. */
 enum {
-  SAILOR_MAX_POOLS = 64,  /* n_zones * n_types */
+  SAILOR_MAX_POOLS = 128, /* n_zones * n_types, and n_zones * G' with mixed_types; the records of
+                             3 * pools * n_mb (segment, pool, microbatch size) triples, 36 bytes
+                             each, and n_mb * n_zones^2 transfer entries of 16 bytes must also fit
+                             the 160 KiB of local memory of a compute unit */
   SAILOR_MAX_TYPES = 16,
   SAILOR_MAX_ZONES = 16,
   SAILOR_MAX_MB = 8,
@@ -182,10 +185,15 @@ typedef struct {
  * per-stage and per-segment tables there, and run three to four passes over the space that
  * decide how later scans are launched (which pieces of the space can never hold a valid plan,
  * how long the others take); results do not depend on that.  *out receives the plan.
- * Test hook: with SAILOR_UNIT_PARTS=n (2..255) in the environment every piece is cut into n
- * parts, which measured times otherwise decide.
+ * (sailor_set_scan_unit_parts overrides how the pieces are cut.)
  * Errors: SAILOR_EINVAL (see limits and field comments), SAILOR_ENOMEM, SAILOR_EDEVICE. */
 sailor_status sailor_plan_create(const sailor_problem *problem, sailor_plan **out);
+
+/* Tuning and testing, process-wide, for plans created afterwards: n = 0 (default) lets the
+ * times measured at plan creation decide which pieces of the space are cut into parts for the
+ * scan; n = 1..255 cuts every piece into n parts instead.  Results never depend on it.
+ * SAILOR_EINVAL outside 0..255. */
+sailor_status sailor_set_scan_unit_parts(int32_t n);
 
 /* Free everything the plan owns (host and device).  NULL is accepted. */
 sailor_status sailor_plan_destroy(sailor_plan *plan);

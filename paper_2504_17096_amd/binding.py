@@ -29,7 +29,7 @@ EXPORTS = ["sailor_plan_create", "sailor_plan_destroy", "sailor_plan_set_avail",
            "sailor_best_plan", "sailor_topk", "sailor_plan_set_scratch", "sailor_plan_set_timing",
            "sailor_plan_last_timing", "sailor_plan_last_counts", "sailor_simulate_1f1b",
            "sailor_simulate_1f1b_static", "sailor_plan_set_incremental", "sailor_plan_last_scan",
-           "sailor_search", "sailor_eval_placements"]
+           "sailor_search", "sailor_eval_placements", "sailor_set_scan_unit_parts"]
 
 
 class SailorError(RuntimeError):
@@ -187,6 +187,7 @@ def load_library() -> C.CDLL:
     lib.sailor_simulate_1f1b_static.argtypes = [P, C.c_uint64, P, P, P, P]
     lib.sailor_plan_set_incremental.argtypes = [P, C.c_int32]
     lib.sailor_plan_last_scan.argtypes = [P, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+    lib.sailor_set_scan_unit_parts.argtypes = [C.c_int32]
     lib.sailor_search.argtypes = [P, C.c_int, C.POINTER(sailor_constraint),
                                   C.POINTER(sailor_search_options), C.POINTER(sailor_stage_plan), P]
     lib.sailor_eval_placements.argtypes = [P, C.c_uint64, P, P, P, C.c_uint32, C.c_int,
@@ -258,6 +259,13 @@ def _constraint(bound: Optional[float]):
     if bound is None:
         return None
     return C.byref(sailor_constraint(float(bound), 1))
+
+
+def set_scan_unit_parts(n: int) -> None:
+    """sailor_set_scan_unit_parts: 0 = cut scan pieces by measured time, n = into n parts each."""
+    rc = load_library().sailor_set_scan_unit_parts(n)
+    if rc != SAILOR_OK:
+        raise SailorError(rc, "sailor_set_scan_unit_parts")
 
 
 class Plan:

@@ -40,6 +40,7 @@ constexpr uint32_t kRankOneWorkgroup = 128;  // largest k whose final ranking ru
 constexpr uint32_t kEvalUnitTarget = 16384;  // candidates per workgroup of the range evaluation
 constexpr unsigned kEvalRowsThreads = 512;
 constexpr size_t kEvalRowsMaxLds = 64 * 1024;  // above this the range form evaluates lane by lane
+constexpr size_t kScanMaxLds = 160 * 1024;     // a scan workgroup stages its records within the LDS of a compute unit
 constexpr size_t kSimMaxLds = 56 * 1024;       // rings of the event-by-event schedule beyond this
 constexpr uint64_t kSimBatch = 64;             // live in device memory, for so many candidates at once
 
@@ -55,6 +56,7 @@ constexpr int kMaxDevices = 64;                // devices whose static scratch a
   } while (0)
 
 std::atomic<void *> g_scratch_ptr[kMaxDevices];  // per device, looked up once
+std::atomic<int> g_forced_unit_parts{0};         // sailor_set_scan_unit_parts
 
 // The current device's copy of `scratch` (the device must be current).
 sailor_status static_scratch(int device, double **out) {
@@ -805,11 +807,16 @@ static sailor_status create_impl(const sailor_problem *p, sailor_plan **out, sai
                        (size_t)d.MB * d.Z * d.Z * sizeof(float4) +
                        (size_t)3 * d.TP * d.MB * d.DP * sizeof(uint64_t) +
                        (size_t)3 * d.TP * d.ZG * sizeof(uint32_t) +
-                       (size_t)d.ZG * (sizeof(PoolInfo) + sizeof(uint64_t)) +
+                       (size_t)d.ZG * (sizeof(PoolInfo) + 2 * sizeof(uint64_t)) +
                        (size_t)(kEvalUnitMaxOuter + d.DP + d.TP) * sizeof(uint32_t);
   pl->lds_bytes = unit_lds_records(d.ZG, d.MB) * (2 * sizeof(float4) + sizeof(uint32_t)) +
                   (size_t)d.MB * d.Z * d.Z * sizeof(float4) +
-                  (size_t)d.ZG * (sizeof(uint64_t) + sizeof(uint32_t));
+                  (size_t)d.ZG * (2 * sizeof(uint64_t) + sizeof(uint32_t));
+  if (pl->lds_bytes > kScanMaxLds) {  // pools x microbatch sizes beyond what a workgroup can stage
+    delete pl;
+    *track = nullptr;
+    return SAILOR_EINVAL;
+  }
 
 #define CREATE_TRY(expr)                                                           \
   do {                                                                             \
@@ -848,7 +855,7 @@ static sailor_status create_impl(const sailor_problem *p, sailor_plan **out, sai
   CREATE_TRY(ar.alloc(&d.row_gen, 1));
   CREATE_TRY(hipMemset(d.row_gen, 0, sizeof(uint32_t)));
   CREATE_TRY(ar.alloc(&d.h1m, ZG));
-  CREATE_TRY(ar.alloc(&d.isect, ZG));
+  CREATE_TRY(ar.alloc(&d.isect, (size_t)2 * ZG));
   {
     std::vector<uint16_t> xt;
     for (int a = 0; a < G; ++a) xt.push_back((uint16_t)(a | (a << 8)));
@@ -883,10 +890,9 @@ static sailor_status create_impl(const sailor_problem *p, sailor_plan **out, sai
   CREATE_TRY(ar.upload(&d.shapes, pl->shapes.data(), NS));
   CREATE_TRY(ar.upload(&d.blocks, pl->blocks.data(), pl->blocks.size()));
   // per-unit tables: one entry per unit as laid out (units dropped later leave room for the
-  // parts of units that are cut); the test hook SAILOR_UNIT_PARTS=n cuts every unit into n
-  // parts whatever the timing says and needs n times the room
-  const char *parts_env = std::getenv("SAILOR_UNIT_PARTS");
-  const long forced_parts = parts_env ? std::min(255L, std::strtol(parts_env, nullptr, 10)) : 0;
+  // parts of units that are cut); sailor_set_scan_unit_parts(n) cuts every unit into n parts
+  // whatever the timing says and needs n times the room
+  const long forced_parts = g_forced_unit_parts.load(std::memory_order_relaxed);
   const size_t unit_cap = pl->units.size() * (size_t)std::max(1L, forced_parts);
   {
     UnitRec *d_units_new = nullptr;
@@ -1490,6 +1496,12 @@ sailor_status sailor_search(sailor_plan *pl, sailor_objective objective,
   std::memcpy(&out->peak_mem_bytes, &ev[2], sizeof(uint64_t));
   std::memcpy(&out->mask, &ev[3], sizeof(uint32_t));
   for (int i = 0; i < out->pp; ++i) out->pool[i] = fin.pools[i];
+  return SAILOR_OK;
+}
+
+sailor_status sailor_set_scan_unit_parts(int32_t n) {
+  if (n < 0 || n > 255) return SAILOR_EINVAL;
+  g_forced_unit_parts.store(n, std::memory_order_relaxed);
   return SAILOR_OK;
 }
 

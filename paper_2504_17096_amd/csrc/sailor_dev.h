@@ -12,7 +12,7 @@
 
 namespace sailor {
 
-constexpr int kMaxMB = 8, kMaxTP = 8, kMaxDP = 24, kMaxPools = 64, kMaxZones = 16,
+constexpr int kMaxMB = 8, kMaxTP = 8, kMaxDP = 24, kMaxPools = 128, kMaxZones = 16,
               kMaxTypes = 16, kMaxStages = 256;
 constexpr int kEvalUnitMaxOuter = 1024;  // most outer-digit values one range-evaluation unit spans
 constexpr int kMaxUnitThreads = 512;  // scan workgroups use 2..8 waves, chosen per plan
@@ -114,7 +114,7 @@ struct DevPlan {
   uint32_t *row_gen;           // [1] availability generation at which an entry of qh last changed
   uint32_t *h1m;               // [ZG] bit k: tpv[k] exceeds the node size of the pool's type(s) (H1)
   const uint16_t *xt;          // [GX] the two real types of an extended type: a | b << 8
-  uint64_t *isect;             // [ZG] bit q: pools p and q draw on a common real pool
+  uint64_t *isect;             // [ZG][2] bit q: pools p and q draw on a common real pool
   int n_bw_coef;               // 0: constant link bandwidth
   const double *bw_poly;       // [Z][Z][n_bw_coef] bandwidth over log2(message bytes)
   double *bwp;                 // [MB][Z][Z] bandwidth seen by one activation transfer

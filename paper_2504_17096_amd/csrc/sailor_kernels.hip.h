@@ -51,6 +51,11 @@ __device__ __forceinline__ double link_bw(const DevPlan &pl, int a, int b, doubl
   return v;
 }
 
+// Bit q of the two-word mask of pool p (pool x pool relations for up to 128 pools).
+__device__ __forceinline__ bool pool_bit(const uint64_t *mask, int p, int q) {
+  return (mask[2 * p + (q >> 6)] >> (q & 63)) & 1ull;
+}
+
 // ------------------------------------------------------------------ set-up kernels
 
 // Reciprocal bandwidths, two-way egress, and the per-(mb, dp, tp) scalars of a plan.
@@ -78,12 +83,13 @@ __global__ void k_small_tables(DevPlan pl) {
     for (int k = 0; k < pl.TP; ++k)
       if (pl.tpv[k] > pl.node[ga] || pl.tpv[k] > pl.node[gb]) m |= 1u << k;
     pl.h1m[p] = m;
-    uint64_t im = 0;  // pools of the same zone with a real type in common (itself included)
+    uint64_t im[2] = {0, 0};  // pools of the same zone with a real type in common (itself included)
     for (int q = 0; q < pl.ZG; ++q) {
       const int y = pl.xt[q % pl.GX], qa = y & 255, qb = y >> 8;
-      if (q / pl.GX == z && (qa == ga || qa == gb || qb == ga || qb == gb)) im |= 1ull << q;
+      if (q / pl.GX == z && (qa == ga || qa == gb || qb == ga || qb == gb)) im[q >> 6] |= 1ull << (q & 63);
     }
-    pl.isect[p] = im;
+    pl.isect[2 * p] = im[0];
+    pl.isect[2 * p + 1] = im[1];
   }
   for (int m = t; m < pl.MB; m += nt) {
     // N_b * D = B / mb whenever the batch divides; the product is exact in fp64 for
@@ -606,7 +612,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
       for (int a2 = u.o_lo; a2 < u.o_lo + u.o_cnt; ++a2) {
         const int i1 = (ZG + a2) * MB + it.mb;
         uint32_t b1 = (a1 != a2) ? (b0 & rbits[i1]) : 0u;
-        if (MIXED && b1 != 0 && ((isect[a2] >> a1) & 1ull))
+        if (MIXED && b1 != 0 && pool_bit(isect, a2, a1))
           b1 &= joint_quota_bits(pl, 2, a1, a2, 0, w0, w1, 0);
         if (wave_any(b1 != 0)) {
           const Rec r1 = rec_load(rec_lo, rec_hi, i1);
@@ -626,7 +632,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
     const int nin = MB * DP * (ZG - 1);
     int z2 = u.o_lo / G, g2 = u.o_lo % G;
     for (int a2 = u.o_lo; a2 < u.o_lo + u.o_cnt; ++a2) {
-      const uint64_t is2 = MIXED ? isect[a2] : 0ull;
+
       for (int e0 = wave * 64; e0 < nin; e0 += nwave * 64) {
         const LaneItem it = lane_item(pl, e0 + lane, nin, ZG - 1, pl.mg_mbzg1);
         const int a1 = it.a1 + (it.a1 >= a2 ? 1 : 0);  // skip the pool of segment 2
@@ -650,7 +656,7 @@ __device__ __forceinline__ void unit_body(const DevPlan &pl, const ScanArgs &a, 
             const int i2 = (2 * ZG + a3) * MB + it.mb;
             uint32_t b2 = b1 & rbits[i2];
             if (MIXED) {
-              if (b2 != 0 && (((is2 >> a1) | (is2 >> a3) | (isect[a3] >> a1)) & 1ull))
+              if (b2 != 0 && (pool_bit(isect, a2, a1) || pool_bit(isect, a2, a3) || pool_bit(isect, a3, a1)))
                 b2 &= joint_quota_bits(pl, 3, a1, a2, a3, w0, w1, w2);
             } else if (a3 == a1) {
               b2 &= q13a;  // segments 1 and 3 share one pool's quota
@@ -717,8 +723,8 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
   float4 *rec_hi = rec_lo + n_rec;                                    // second halves
   uint32_t *rbits = reinterpret_cast<uint32_t *>(rec_hi + n_rec);     // validity bits alone
   float4 *pair = reinterpret_cast<float4 *>(rbits + n_rec);           // [MB][Z][Z]
-  uint64_t *isect = reinterpret_cast<uint64_t *>(pair + MB * Z * Z);  // [ZG]
-  uint32_t *q13 = reinterpret_cast<uint32_t *>(isect + ZG);           // [ZG]
+  uint64_t *isect = reinterpret_cast<uint64_t *>(pair + MB * Z * Z);  // [ZG][2]
+  uint32_t *q13 = reinterpret_cast<uint32_t *>(isect + 2 * ZG);       // [ZG]
   __shared__ float red[2][kMaxUnitThreads / 64];
   __shared__ uint32_t s_any[kMaxUnitThreads / 64];  // per wave, bit j: a pool can host segment j
   const int t = threadIdx.x;
@@ -771,7 +777,7 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
       }
     }
   if (MIXED)  // under ignore_quota no pool counts as shared
-    for (int p = t; p < ZG; p += blockDim.x) isect[p] = a.ignore_quota ? 0ull : pl.isect[p];
+    for (int p = t; p < 2 * ZG; p += blockDim.x) isect[p] = a.ignore_quota ? 0ull : pl.isect[p];
   for (int i = t; i < MB * Z * Z; i += blockDim.x) {  // per mb: transfer a -> b, b -> a, egress
     const int m = i / (Z * Z), ab = i - m * Z * Z, za = ab / Z, zb = ab % Z;
     pair[i] = make_float4(pl.tsec_f[i], pl.tsec_f[(m * Z + zb) * Z + za], pl.egs_f[ab], 0.f);
@@ -1799,8 +1805,8 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
         Acc acc = A0;
         bool quota_ok = q0;
         if (S >= 2) {
-          const uint32_t r2 = od & 63u;
-          const uint32_t t1 = PST ? ((od >> 6) & 7u) : tp;
+          const uint32_t r2 = od & 127u;
+          const uint32_t t1 = PST ? ((od >> 7) & 7u) : tp;
           uint32_t p1 = p0 + 1 + r2;
           if (p1 >= ZG) p1 -= ZG;
           // uniform offsets when the segment has its own tp digit, this lane's otherwise
@@ -1816,14 +1822,14 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
           peak = mem1 > peak ? mem1 : peak;
           const bool q1 = (qm[o_qm + p1] >> dp) & 1u;
           quota_ok = quota_ok && q1;
-          if (S == 2 && MIXED && quota_ok && ((isect[p0] >> p1) & 1ull))
+          if (S == 2 && MIXED && quota_ok && pool_bit(isect, (int)p0, (int)p1))
             quota_ok = (joint_quota_bits(pl, 2, (int)p0, (int)p1, 0, (int)gpus0,
                                          sh.n[1] * vals[DP + t1], 0) >> dp) & 1u;
           const float4 pr = pairm[mul24(z0, Z) + z1];
           acc = acc_cross(acc, r1, pr.x, pr.y, pr.z, single0, true);
           if (S == 3) {
-            const uint32_t r3 = (od >> 9) & 63u;
-            const uint32_t t2 = PST ? (od >> 15) : tp;
+            const uint32_t r3 = (od >> 10) & 127u;
+            const uint32_t t2 = PST ? (od >> 17) : tp;
             uint32_t p2 = p1 + 1 + r3;
             if (p2 >= ZG) p2 -= ZG;
             const uint32_t o_rec2 = 2 * seg_rec + (PST ? mul24(t2, tp_rec) : tpo_rec);
@@ -1837,7 +1843,8 @@ __device__ __forceinline__ void eval_rows_body(const DevPlan &pl, const EvalArgs
             peak = mem2 > peak ? mem2 : peak;
             if (MIXED) {  // pools that draw on one real pool together get the joint check
               quota_ok = quota_ok && ((qm[o_qm2 + p2] >> dp) & 1u);
-              if (quota_ok && (((isect[p0] >> p1) | (isect[p1] >> p2) | (isect[p0] >> p2)) & 1ull))
+              if (quota_ok && (pool_bit(isect, (int)p0, (int)p1) || pool_bit(isect, (int)p1, (int)p2) ||
+                               pool_bit(isect, (int)p0, (int)p2)))
                 quota_ok = (joint_quota_bits(pl, 3, (int)p0, (int)p1, (int)p2, (int)gpus0,
                                              sh.n[1] * vals[DP + t1], sh.n[2] * vals[DP + t2]) >> dp) & 1u;
             } else if (p2 == p0) {  // segments 1 and 3 share one pool's quota
@@ -1879,11 +1886,11 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
   float4 *pair = rec_hi + 3 * TP * (ZG * MB + 1);         // [MB][Z][Z]
   PoolInfo *pinfo = reinterpret_cast<PoolInfo *>(pair + MB * Z * Z);     // [ZG]
   uint64_t *need = reinterpret_cast<uint64_t *>(pinfo + ZG);             // [3][TP][MB][DP]
-  uint64_t *isect = need + 3 * TP * MB * DP;                             // [ZG]
-  uint32_t *qm = reinterpret_cast<uint32_t *>(isect + ZG);               // [3][TP][ZG]
+  uint64_t *isect = need + 3 * TP * MB * DP;                             // [ZG][2]
+  uint32_t *qm = reinterpret_cast<uint32_t *>(isect + 2 * ZG);           // [3][TP][ZG]
   uint32_t *odec = qm + 3 * TP * ZG;  // [o_cnt] the outer digits of the unit, unpacked:
   int32_t *vals = reinterpret_cast<int32_t *>(odec + kEvalUnitMaxOuter);  // [DP] dp, [TP] tp
-  const int t = threadIdx.x;          // r2 | tp2 << 6 | r3 << 9 | tp3 << 15
+  const int t = threadIdx.x;          // r2 | tp2 << 7 | r3 << 10 | tp3 << 17
   if (t < DP) vals[t] = pl.dpv[t];
   else if (t < DP + TP) vals[t] = pl.tpv[t - DP];
   __syncthreads();
@@ -1892,11 +1899,11 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
       uint32_t oa = u.o_lo + o;
       uint32_t d = oa % (uint32_t)(ZG - 1);
       oa /= (uint32_t)(ZG - 1);
-      if (pl.pst) { d |= (oa % (uint32_t)TP) << 6; oa /= (uint32_t)TP; }
+      if (pl.pst) { d |= (oa % (uint32_t)TP) << 7; oa /= (uint32_t)TP; }
       if (S == 3) {
-        d |= (oa % (uint32_t)(ZG - 1)) << 9;
+        d |= (oa % (uint32_t)(ZG - 1)) << 10;
         oa /= (uint32_t)(ZG - 1);
-        if (pl.pst) d |= oa << 15;
+        if (pl.pst) d |= oa << 17;
       }
       odec[o] = d;
     }
@@ -1915,7 +1922,8 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
     pi.avail = pl.mixed ? 0 : pl.avail[p];
     pi.meta = (uint32_t)(p / G) | (pl.h1m[p] << 8);
     pinfo[p] = pi;
-    isect[p] = pl.isect[p];
+    isect[2 * p] = pl.isect[2 * p];
+    isect[2 * p + 1] = pl.isect[2 * p + 1];
   }
   for (int i = t; i < MB * Z * Z; i += blockDim.x) {  // per mb: transfer a -> b, b -> a, egress
     const int m = i / (Z * Z), ab = i - m * Z * Z, za = ab / Z, zb = ab % Z;

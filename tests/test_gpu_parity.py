@@ -469,6 +469,42 @@ def test_widest_lists_with_a_tp_digit_per_segment(torch_cuda):
         plan.destroy()
 
 
+def test_seventy_five_pools_five_zones_five_types_with_pairs(torch_cuda):
+    # 5 zones x (5 types + 10 pairs) = 75 pools: beyond one 64-bit word of pool relations
+    prob = W.tiny_problem(8, n_layers=4, n_types=5, n_zones=5, max_segments=2, partitions_per_pp=2).with_mixed_types()
+    plan, orc = _plan(prob), Oracle(prob)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        n = orc.num_candidates
+        assert plan.num_candidates() == n and n > 1_000_000
+        first, count = n - 1_500_003, 1_500_003           # two-segment blocks, a ragged range
+        assert_eval_parity(gpu_eval(torch_cuda, plan, first, count), orc.eval_batch(first, count, n_threads=THREADS))
+        idx = np.random.default_rng(75).integers(0, n, 300_000).astype(np.uint64)
+        assert_eval_parity(gpu_eval(torch_cuda, plan, 0, len(idx), indices=idx),
+                           orc.eval_batch(indices=idx, n_threads=THREADS))
+        for objective in (MAX_THROUGHPUT, MIN_COST):
+            check_topk(plan.topk(64, objective=objective, stream=stream),
+                       orc.topk(64, objective=objective, n_threads=THREADS), objective, orc)
+            check_result(plan.best_plan(objective=objective, stream=stream),
+                         orc.best(objective=objective, n_threads=THREADS), orc)
+        # three segments on 75 pools as well, on a smaller model
+        p3 = W.tiny_problem(9, n_layers=3, n_types=5, n_zones=5, max_segments=3, seg3_max_pp=3,
+                            partitions_per_pp=1).with_mixed_types()
+        plan3, orc3 = _plan(p3), Oracle(p3)
+        try:
+            n3 = orc3.num_candidates
+            idx = np.random.default_rng(76).integers(0, n3, 400_000).astype(np.uint64)
+            assert_eval_parity(gpu_eval(torch_cuda, plan3, 0, len(idx), indices=idx),
+                               orc3.eval_batch(indices=idx, n_threads=THREADS))
+            assert_eval_parity(gpu_eval(torch_cuda, plan3, n3 - 700_001, 700_001),
+                               orc3.eval_batch(n3 - 700_001, 700_001, n_threads=THREADS))
+            check_topk(plan3.topk(32, stream=stream), orc3.topk(32, n_threads=THREADS), MAX_THROUGHPUT, orc3)
+        finally:
+            plan3.destroy()
+    finally:
+        plan.destroy()
+
+
 def test_eval_batch_replays_from_a_captured_graph(torch_cuda):
     # sailor_eval_batch only enqueues kernels on the caller's stream (no host synchronisation,
     # no memset), so it can be captured; every replay must reproduce the eager outputs
@@ -584,14 +620,17 @@ def test_timing_modes_report_the_scan_and_the_whole_call(torch_cuda):
 
 @pytest.mark.parametrize("parts", [2, 5])
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg2_mixed", "tiny4_segtp", "wide"])
-def test_selection_with_every_scan_unit_cut_into_parts(torch_cuda, monkeypatch, name, parts):
+def test_selection_with_every_scan_unit_cut_into_parts(torch_cuda, name, parts):
     # units that run long are cut by measured time at plan creation, which small problems
-    # never trigger: the library's test hook cuts every unit, and the selections (scan,
+    # never trigger: sailor_set_scan_unit_parts cuts every unit, and the selections (scan,
     # unit list, collect pass over the listed parts) must not change
-    monkeypatch.setenv("SAILOR_UNIT_PARTS", str(parts))
+    from paper_2504_17096_amd.binding import set_scan_unit_parts
     prob = PROBLEMS[name]()
-    plan, orc = _plan(prob), Oracle(prob)
-    monkeypatch.delenv("SAILOR_UNIT_PARTS")
+    set_scan_unit_parts(parts)
+    try:
+        plan, orc = _plan(prob), Oracle(prob)
+    finally:
+        set_scan_unit_parts(0)
     stream = torch_cuda.cuda.current_stream().cuda_stream
     try:
         cheapest = orc.best(objective=MIN_COST, n_threads=THREADS)

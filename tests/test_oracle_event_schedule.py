@@ -119,3 +119,35 @@ def test_bounds_and_limits_on_a_workload():
         assert closed <= e.iter_time * (1 + 1e-12)
         seen += 1
     assert seen > 300 and worst > 1e-3  # and the two do differ on heterogeneous plans
+
+
+def test_the_straggler_counts_n_b_times_not_n_b_plus_one():
+    # Sec. 4.2.2 and 4.2.3 print sum_i t_i + N_b t_straggler; the evaluator uses
+    # sum_i t_i + (N_b - 1) t_straggler.  Against the op-by-op schedule of the same stage times
+    # the second is exact for uniform pipelines and closer for uneven ones, most visibly with
+    # few microbatches, where one extra straggler period is a large share of the makespan.
+    rng = np.random.default_rng(7)
+    err_used, err_printed = [], []
+    for trial in range(60):
+        P = int(rng.integers(1, 7))
+        nb = int(rng.integers(1, 5))
+        uniform = trial % 3 == 0
+        f = np.full(P, 1e-3) if uniform else rng.uniform(0.5e-3, 3e-3, P)
+        b = 2 * f if uniform else rng.uniform(1e-3, 6e-3, P)
+        event = one_f_one_b_makespan(list(f), list(b), nb)
+        t = f + b
+        used = t.sum() + (nb - 1) * t.max()
+        printed = t.sum() + nb * t.max()
+        if uniform:
+            assert used == pytest.approx(event, rel=1e-12)
+        assert printed > used
+        err_used.append(abs(used - event) / event)
+        err_printed.append(abs(printed - event) / event)
+    assert np.mean(err_used) < 0.25 * np.mean(err_printed)
+    assert np.max(err_used) < np.max(err_printed)
+    # the oracle's own closed form is the first one (two stages, one microbatch: the sum)
+    p = make_problem(n_layers=2, pp_list=[2], mb_list=(4,), tp_list=(1,), dp_list=(1,), global_batch=4,
+                     t_fwd=1e-3, t_bwd=2e-3, layer_params=0)
+    o = Oracle(p)
+    ev, closed = o.simulate_1f1b(0)
+    assert closed == pytest.approx(2 * 3e-3, rel=1e-12) and ev == pytest.approx(closed, rel=1e-12)
