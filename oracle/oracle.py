@@ -94,12 +94,12 @@ class _SearchResult(C.Structure):
                 ("partition", C.c_int32), ("tp_idx", C.c_int32), ("dp_idx", C.c_int32),
                 ("mb_idx", C.c_int32), ("pp", C.c_int32), ("expanded", C.c_uint64),
                 ("key", C.c_double), ("iter_time", C.c_double), ("cost", C.c_double),
-                ("pools", C.c_int32 * 256)]
+                ("pools", C.c_int32 * 256), ("pools_b", C.c_int32 * 256)]
 
 
 class _SearchOpts(C.Structure):
     _fields_ = [("beam_width", C.c_int32), ("max_runs", C.c_int32), ("has_incumbent", C.c_int32),
-                ("incumbent", C.c_double)]
+                ("incumbent", C.c_double), ("allow_split", C.c_int32)]
 
 
 @dataclass
@@ -116,6 +116,7 @@ class StagePlan:
     cost: float
     truncated: bool = False
     expanded: int = 0
+    pools_b: tuple = ()
 
 
 @dataclass
@@ -159,7 +160,7 @@ def _load():
         lib.so_eval_split_assignment.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                                  C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_double,
                                                  C.POINTER(_Eval)]
-        lib.so_search_exhaustive.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, C.c_int,
+        lib.so_search_exhaustive.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, C.c_int, C.c_int,
                                              C.POINTER(_SearchResult)]
         lib.so_search_beam.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, C.POINTER(_SearchOpts),
                                        C.POINTER(_SearchResult)]
@@ -174,7 +175,8 @@ def _stage_plan(r: _SearchResult) -> Optional[StagePlan]:
     if not r.found:
         return None
     return StagePlan(r.pp_idx, r.partition, r.tp_idx, r.dp_idx, r.mb_idx, tuple(r.pools[:r.pp]),
-                     r.key, r.iter_time, r.cost, bool(r.truncated), int(r.expanded))
+                     r.key, r.iter_time, r.cost, bool(r.truncated), int(r.expanded),
+                     tuple(r.pools_b[:r.pp]))
 
 
 def _cfg(c: _Config) -> Config:
@@ -348,20 +350,21 @@ class Oracle:
         return _ev(e)
 
     def search_exhaustive(self, objective: int = MAX_THROUGHPUT, bound: Optional[float] = None,
-                          max_runs: int = 0) -> Optional[StagePlan]:
+                          max_runs: int = 0, allow_split: bool = False) -> Optional[StagePlan]:
         r = _SearchResult()
         rc = self._lib.so_search_exhaustive(self._ctx, objective, bound is not None,
-                                            0.0 if bound is None else bound, max_runs, C.byref(r))
+                                            0.0 if bound is None else bound, max_runs,
+                                            1 if allow_split else 0, C.byref(r))
         if rc != 0:
             raise ValueError("the search does not cover this problem")
         return _stage_plan(r)
 
     def search_beam(self, beam_width: int, objective: int = MAX_THROUGHPUT,
                     bound: Optional[float] = None, max_runs: int = 0,
-                    incumbent: Optional[float] = None) -> Optional[StagePlan]:
+                    incumbent: Optional[float] = None, allow_split: bool = False) -> Optional[StagePlan]:
         r = _SearchResult()
         o = _SearchOpts(beam_width, max_runs, incumbent is not None,
-                        0.0 if incumbent is None else incumbent)
+                        0.0 if incumbent is None else incumbent, 1 if allow_split else 0)
         rc = self._lib.so_search_beam(self._ctx, objective, bound is not None,
                                       0.0 if bound is None else bound, C.byref(o), C.byref(r))
         if rc != 0:

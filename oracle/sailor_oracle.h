@@ -165,6 +165,8 @@ typedef struct {
   uint64_t expanded;             /* placements generated */
   double key, iter_time, cost;
   int32_t pools[SO_SEARCH_MAX_STAGES];
+  int32_t pools_b[SO_SEARCH_MAX_STAGES]; /* pool of the other half of a stage's replicas (= pools[i]
+                                            when the stage is not split) */
 } so_search_result;
 
 typedef struct {
@@ -172,13 +174,16 @@ typedef struct {
   int32_t max_runs;              /* 0: any placement; n: at most n runs of equal pools */
   int32_t has_incumbent;         /* 1: placements whose bound exceeds `incumbent` are dropped */
   double incumbent;
+  int32_t allow_split;           /* 1: a stage may put half of its replicas on a second pool, also
+                                    of another zone (so_eval_split_assignment); a stage then has
+                                    (pools)^2 choices (a, b), numbered a * pools + b */
 } so_search_opts;
 
 /* (sailor_search_oracle.c) sub-problems in the order pp, layer split, TP, D, microbatch size;
  * equal keys: the first sub-problem, inside it the first placement found.  0 ok, -1 when the
  * problem uses an option the search does not cover. */
 int so_search_exhaustive(const so_ctx *c, int objective, int has_bound, double bound, int max_runs,
-                         so_search_result *out);
+                         int allow_split, so_search_result *out);
 int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
                    const so_search_opts *opt, so_search_result *out);
 int so_search_prefix_bound(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,

@@ -47,9 +47,13 @@ typedef struct {
   double xb_open;  /* its backward transfer to stage i-1 */
   double msync, mupd, dol, comm;
   double lb_key, lb_T, lb_C;
-  uint8_t cnt[SS_MAX_POOLS]; /* stages placed on each pool */
+  /* with split stages: the same four for the pipelines through the second pools */
+  double sum_b, maxt_b, c_open_b, xb_open_b;
+  uint8_t cnt[SS_MAX_POOLS]; /* stages placed on each pool (with split stages: halves of stages) */
   uint8_t pool, runs;
+  uint8_t pool_b;
   uint8_t path[SS_MAX_STAGES];
+  uint8_t path_b[SS_MAX_STAGES];
 } ss_state;
 
 typedef struct {
@@ -62,7 +66,11 @@ typedef struct {
   double sync[SS_MAX_STAGES][16];
   uint8_t ok[SS_MAX_STAGES][SS_MAX_POOLS];
   int cap_cnt[SS_MAX_POOLS];      /* stages a pool can host: avail / (tp * D) */
+  int cap_half[SS_MAX_POOLS];     /* halves of stages: 2 avail / (tp * D) */
   double xfer[16][16], comm[16][16];
+  double comm_half[16][16];       /* traffic cost of one kind of pipeline (half of the replicas) */
+  double ring_bytes[SS_MAX_STAGES]; /* bytes a ring all-reduce of the stage moves over every link */
+  double bw[16][16], ring_price[16][16], price[16];
   /* cheapest admissible choice of the stages behind stage i */
   double Ssum[SS_MAX_STAGES], Smax[SS_MAX_STAGES], Ssync[SS_MAX_STAGES], Supd[SS_MAX_STAGES],
       Sdol[SS_MAX_STAGES];
@@ -107,14 +115,24 @@ static int sub_setup(const so_problem *p, ss_sub *s, int pp_idx, int partition, 
   s->p2p = (double)p->p2p_bytes[mb_idx];
   const int P = s->P, G = s->G, Z = s->Z;
   const int32_t *nl = layers_of(p, pp_idx, partition);
-  for (int a = 0; a < s->ZG; ++a) s->cap_cnt[a] = (int)((int64_t)p->avail[a] / ((int64_t)s->tp * s->D));
+  for (int g = 0; g < s->G; ++g) s->price[g] = p->price_per_hour[g];
+  for (int a = 0; a < s->ZG; ++a) {
+    s->cap_cnt[a] = (int)((int64_t)p->avail[a] / ((int64_t)s->tp * s->D));
+    s->cap_half[a] = (int)(2 * (int64_t)p->avail[a] / ((int64_t)s->tp * s->D));
+  }
   for (int z = 0; z < Z; ++z)
     for (int y = 0; y < Z; ++y) {
       s->xfer[z][y] = s->p2p / p->bandwidth[(size_t)z * Z + y];
       s->comm[z][y] = 0.0;
-      if (p->egress_per_byte && z != y)
-        s->comm[z][y] = (double)s->Nb * (double)s->D * s->p2p *
-                        (p->egress_per_byte[(size_t)z * Z + y] + p->egress_per_byte[(size_t)y * Z + z]);
+      s->comm_half[z][y] = 0.0;
+      s->ring_price[z][y] = 0.0;
+      s->bw[z][y] = p->bandwidth[(size_t)z * Z + y];
+      if (p->egress_per_byte && z != y) {
+        const double both = p->egress_per_byte[(size_t)z * Z + y] + p->egress_per_byte[(size_t)y * Z + z];
+        s->comm[z][y] = (double)s->Nb * (double)s->D * s->p2p * both;
+        s->comm_half[z][y] = (double)s->Nb * (0.5 * (double)s->D) * s->p2p * both;
+        s->ring_price[z][y] = both;
+      }
     }
   int first = 0;
   for (int i = 0; i < P; ++i) {
@@ -136,6 +154,9 @@ static int sub_setup(const so_problem *p, ss_sub *s, int pp_idx, int partition, 
       const int fits = bytes + p->mem_reserved[g] <= p->mem_capacity[g] && s->tp <= p->gpus_per_node[g];
       for (int z = 0; z < Z; ++z) s->ok[i][z * G + g] = (uint8_t)fits;
     }
+    s->ring_bytes[i] = 0.0;
+    if (s->D > 1)
+      s->ring_bytes[i] = 2.0 * (double)(s->D - 1) / (double)s->D * ((double)shard * (double)p->grad_bytes_per_param);
     for (int z = 0; z < Z; ++z) {
       double sync = 0.0;
       if (s->D > 1) {
@@ -234,6 +255,88 @@ static int pruned(const ss_state *st, int objective, int has_bound, double bound
   return has_inc && st->lb_key > inc;
 }
 
+/* ---- stages that may split their replicas over two pools (a, b), half on each ------------ */
+
+/* bounds with two kinds of pipeline: the slower one counts (Sec. 4.3) */
+static void bounds2(const ss_sub *s, int i, ss_state *st, int objective) {
+  const double ta = st->c_open + st->xb_open, tb = st->c_open_b + st->xb_open_b;
+  const double pa = ((st->sum + ta) + s->Ssum[i]) + (double)(s->Nb - 1) * fmax(fmax(st->maxt, ta), s->Smax[i]);
+  const double pb = ((st->sum_b + tb) + s->Ssum[i]) + (double)(s->Nb - 1) * fmax(fmax(st->maxt_b, tb), s->Smax[i]);
+  st->lb_T = (fmax(pa, pb) + fmax(st->msync, s->Ssync[i])) + fmax(st->mupd, s->Supd[i]);
+  st->lb_C = (st->dol + s->Sdol[i]) / 3600.0 * st->lb_T + st->comm;
+  st->lb_key = objective == SO_MAX_THROUGHPUT ? st->lb_T : st->lb_C;
+}
+
+/* what stage j costs on the pools (a, b) by itself: all-reduce over the slowest link of the
+ * ring, the slower update, the mean rent, the ring's traffic between the zones */
+static void stage_terms2(const ss_sub *s, int j, int a, int b, double *sync, double *upd, double *dol,
+                         double *ring_cost) {
+  const int ga = a % s->G, za = a / s->G, gb = b % s->G, zb = b / s->G;
+  double link = s->bw[za][za];
+  if (zb != za) link = fmin(fmin(link, s->bw[zb][zb]), fmin(s->bw[za][zb], s->bw[zb][za]));
+  *sync = s->ring_bytes[j] / link;
+  *upd = fmax(s->upd[j][ga], s->upd[j][gb]);
+  *dol = (double)(s->D * s->tp) * (0.5 * (s->price[ga] + s->price[gb]));
+  *ring_cost = zb != za ? s->ring_bytes[j] * s->ring_price[za][zb] : 0.0;
+}
+
+static int admissible2(const ss_sub *s, int j, const uint8_t *cnt, int a, int b) {
+  if (!s->ok[j][a] || !s->ok[j][b]) return 0;
+  if (a == b) return cnt[a] + 2 <= s->cap_half[a];
+  if (s->D % 2 != 0) return 0; /* D replicas cannot be halved */
+  return cnt[a] + 1 <= s->cap_half[a] && cnt[b] + 1 <= s->cap_half[b];
+}
+
+static int first_state2(const ss_sub *s, int a, int b, int objective, ss_state *st) {
+  memset(st, 0, sizeof *st);
+  if (!admissible2(s, 0, st->cnt, a, b)) return 0;
+  double sync, upd, dol, ring;
+  stage_terms2(s, 0, a, b, &sync, &upd, &dol, &ring);
+  st->c_open = s->c[0][a % s->G];
+  st->c_open_b = s->c[0][b % s->G];
+  st->msync = sync; st->mupd = upd; st->dol = dol; st->comm = ring;
+  st->cnt[a] += 1; st->cnt[b] += 1;
+  st->pool = (uint8_t)a; st->pool_b = (uint8_t)b;
+  st->runs = 1;
+  st->path[0] = (uint8_t)a; st->path_b[0] = (uint8_t)b;
+  bounds2(s, 0, st, objective);
+  return 1;
+}
+
+static int extend2(const ss_sub *s, int i, const ss_state *par, int a, int b, int max_runs, int objective,
+                   ss_state *st) {
+  if (!admissible2(s, i + 1, par->cnt, a, b)) return 0;
+  const int runs = par->runs + ((a != par->pool || b != par->pool_b) ? 1 : 0);
+  if (max_runs > 0 && runs > max_runs) return 0;
+  const int za = a / s->G, zb = b / s->G, pza = par->pool / s->G, pzb = par->pool_b / s->G;
+  *st = *par;
+  const double ta = par->c_open + (s->xfer[pza][za] + par->xb_open);
+  const double tb = par->c_open_b + (s->xfer[pzb][zb] + par->xb_open_b);
+  st->sum = par->sum + ta;
+  st->maxt = fmax(par->maxt, ta);
+  st->sum_b = par->sum_b + tb;
+  st->maxt_b = fmax(par->maxt_b, tb);
+  st->c_open = s->c[i + 1][a % s->G];
+  st->c_open_b = s->c[i + 1][b % s->G];
+  st->xb_open = s->xfer[za][pza];
+  st->xb_open_b = s->xfer[zb][pzb];
+  double sync, upd, dol, ring;
+  stage_terms2(s, i + 1, a, b, &sync, &upd, &dol, &ring);
+  st->msync = fmax(par->msync, sync);
+  st->mupd = fmax(par->mupd, upd);
+  st->dol = par->dol + dol;
+  double comm = par->comm;
+  if (pza != za) comm += s->comm_half[pza][za];
+  if (pzb != zb) comm += s->comm_half[pzb][zb];
+  st->comm = comm + ring;
+  st->cnt[a] += 1; st->cnt[b] += 1;
+  st->pool = (uint8_t)a; st->pool_b = (uint8_t)b;
+  st->runs = (uint8_t)runs;
+  st->path[i + 1] = (uint8_t)a; st->path_b[i + 1] = (uint8_t)b;
+  bounds2(s, i + 1, st, objective);
+  return 1;
+}
+
 typedef struct { double key; uint32_t id; uint32_t pos; } ss_order; /* id: generation order; pos: where it is stored */
 
 static int by_key_then_id(const void *x, const void *y) {
@@ -248,7 +351,12 @@ static void take(so_search_result *out, const ss_sub *s, const ss_state *st) {
   out->pp_idx = s->pp_idx; out->partition = s->partition; out->tp_idx = s->tp_idx;
   out->dp_idx = s->dp_idx; out->mb_idx = s->mb_idx; out->pp = s->P;
   out->key = st->lb_key; out->iter_time = st->lb_T; out->cost = st->lb_C;
-  for (int i = 0; i < s->P; ++i) out->pools[i] = st->path[i];
+  for (int i = 0; i < s->P; ++i) { out->pools[i] = st->path[i]; out->pools_b[i] = st->path[i]; }
+}
+
+static void take2(so_search_result *out, const ss_sub *s, const ss_state *st) {
+  take(out, s, st);
+  for (int i = 0; i < s->P; ++i) out->pools_b[i] = st->path_b[i];
 }
 
 int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
@@ -258,13 +366,15 @@ int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
   if (p->mixed_types || p->per_segment_tp || p->n_bw_coef > 0 || !opt || opt->beam_width < 1) return -1;
   if (p->n_types > 16 || p->n_zones > 16 || p->n_types * p->n_zones > SS_MAX_POOLS) return -1;
   const int W = opt->beam_width, ZG = p->n_types * p->n_zones;
+  const int split = opt->allow_split ? 1 : 0;
+  const int NCH = split ? ZG * ZG : ZG; /* choices per stage: a pool, or a pair (a, b) = a * ZG + b */
   ss_sub *s = (ss_sub *)malloc(sizeof(ss_sub));
   ss_state *cur = (ss_state *)malloc(sizeof(ss_state) * (size_t)W);
-  ss_state *all = (ss_state *)malloc(sizeof(ss_state) * (size_t)W * (size_t)ZG);
-  ss_order *ord = (ss_order *)malloc(sizeof(ss_order) * (size_t)W * (size_t)ZG);
+  ss_state *all = (ss_state *)malloc(sizeof(ss_state) * (size_t)W * (size_t)NCH);
+  ss_order *ord = (ss_order *)malloc(sizeof(ss_order) * (size_t)W * (size_t)NCH);
   if (!s || !cur || !all || !ord) { free(s); free(cur); free(all); free(ord); return -1; }
   for (int ip = 0; ip < p->n_pp; ++ip) {
-    if (p->pp_values[ip] > SS_MAX_STAGES) continue;
+    if (p->pp_values[ip] > (split ? 127 : SS_MAX_STAGES)) continue; /* halves are counted in a byte */
     for (int q = 0; q < p->n_partitions[ip]; ++q)
       for (int it = 0; it < p->n_tp; ++it)
         for (int id = 0; id < p->n_dp; ++id)
@@ -272,8 +382,9 @@ int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
             if (!sub_setup(p, s, ip, q, it, id, im)) continue;
             /* level 0, then one level per further stage */
             int n = 0, n_all = 0;
-            for (int a = 0; a < ZG; ++a)
-              if (first_state(s, a, objective, &all[n_all])) {
+            for (int a = 0; a < NCH; ++a)
+              if (split ? first_state2(s, a / ZG, a % ZG, objective, &all[n_all])
+                        : first_state(s, a, objective, &all[n_all])) {
                 out->expanded += 1;
                 if (!pruned(&all[n_all], objective, has_bound, bound, opt->has_incumbent, opt->incumbent)) {
                   ord[n_all].key = all[n_all].lb_key;
@@ -287,7 +398,9 @@ int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
                 int bi = -1;
                 for (int k = 0; k < n_all; ++k)
                   if (bi < 0 || by_key_then_id(&ord[k], &ord[bi]) < 0) bi = k;
-                if (bi >= 0 && (!out->found || all[bi].lb_key < out->key)) take(out, s, &all[bi]);
+                if (bi >= 0 && (!out->found || all[bi].lb_key < out->key)) {
+                  if (split) take2(out, s, &all[bi]); else take(out, s, &all[bi]);
+                }
                 break;
               }
               if (n_all > W) { /* keep the W smallest bounds, in that order */
@@ -302,13 +415,15 @@ int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
               /* expand: candidate id = rank of the parent * ZG + pool */
               n_all = 0;
               for (int r = 0; r < n; ++r)
-                for (int a = 0; a < ZG; ++a) {
+                for (int a = 0; a < NCH; ++a) {
                   ss_state *st = &all[n_all];
-                  if (!extend(s, i, &cur[r], a, opt->max_runs, objective, st)) continue;
+                  if (!(split ? extend2(s, i, &cur[r], a / ZG, a % ZG, opt->max_runs, objective, st)
+                              : extend(s, i, &cur[r], a, opt->max_runs, objective, st)))
+                    continue;
                   out->expanded += 1;
                   if (pruned(st, objective, has_bound, bound, opt->has_incumbent, opt->incumbent)) continue;
                   ord[n_all].key = st->lb_key;
-                  ord[n_all].id = (uint32_t)(r * ZG + a);
+                  ord[n_all].id = (uint32_t)(r * NCH + a);
                   ord[n_all].pos = (uint32_t)n_all;
                   n_all += 1;
                 }
@@ -323,43 +438,48 @@ int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
 /* ---- the definition: every placement of every sub-problem through the plain simulator ---- */
 
 static void place(const so_ctx *c, const so_problem *p, int ip, int q, int it, int id, int im,
-                  int i, int runs, int max_runs, int32_t *pools, int objective, int has_bound,
-                  double bound, so_search_result *out) {
+                  int i, int runs, int max_runs, int32_t *pools, int32_t *pools_b, int split,
+                  int objective, int has_bound, double bound, so_search_result *out) {
   const int P = p->pp_values[ip], ZG = p->n_types * p->n_zones;
   if (i == P) {
     so_eval e;
     out->expanded += 1;
-    if (so_eval_assignment(c, ip, q, id, im, it, pools, objective, has_bound, bound, &e) != 0) return;
+    if ((split ? so_eval_split_assignment(c, ip, q, id, im, it, pools, pools_b, objective, has_bound, bound, &e)
+               : so_eval_assignment(c, ip, q, id, im, it, pools, objective, has_bound, bound, &e)) != 0)
+      return;
     if (e.mask != 0) return;
     const double key = objective == SO_MAX_THROUGHPUT ? e.iter_time : e.cost;
     if (out->found && !(key < out->key)) return; /* the first of equal keys stays */
     out->found = 1;
     out->pp_idx = ip; out->partition = q; out->tp_idx = it; out->dp_idx = id; out->mb_idx = im;
     out->pp = P; out->key = key; out->iter_time = e.iter_time; out->cost = e.cost;
-    for (int k = 0; k < P; ++k) out->pools[k] = pools[k];
+    for (int k = 0; k < P; ++k) { out->pools[k] = pools[k]; out->pools_b[k] = pools_b[k]; }
     return;
   }
-  for (int a = 0; a < ZG; ++a) {
-    const int r = (i == 0) ? 1 : runs + (a != pools[i - 1] ? 1 : 0);
-    if (max_runs > 0 && r > max_runs) continue;
-    pools[i] = a;
-    place(c, p, ip, q, it, id, im, i + 1, r, max_runs, pools, objective, has_bound, bound, out);
-  }
+  for (int a = 0; a < ZG; ++a)
+    for (int b = (split ? 0 : a); b < (split ? ZG : a + 1); ++b) {
+      const int r = (i == 0) ? 1 : runs + ((a != pools[i - 1] || b != pools_b[i - 1]) ? 1 : 0);
+      if (max_runs > 0 && r > max_runs) continue;
+      pools[i] = a;
+      pools_b[i] = b;
+      place(c, p, ip, q, it, id, im, i + 1, r, max_runs, pools, pools_b, split, objective, has_bound, bound, out);
+    }
 }
 
 int so_search_exhaustive(const so_ctx *c, int objective, int has_bound, double bound, int max_runs,
-                         so_search_result *out) {
+                         int allow_split, so_search_result *out) {
   const so_problem *p = so_problem_of(c);
   memset(out, 0, sizeof *out);
   if (p->mixed_types || p->per_segment_tp) return -1;
-  int32_t pools[SO_SEARCH_MAX_STAGES];
+  int32_t pools[SO_SEARCH_MAX_STAGES], pools_b[SO_SEARCH_MAX_STAGES];
   for (int ip = 0; ip < p->n_pp; ++ip) {
     if (p->pp_values[ip] > SS_MAX_STAGES) continue;
     for (int q = 0; q < p->n_partitions[ip]; ++q)
       for (int it = 0; it < p->n_tp; ++it)
         for (int id = 0; id < p->n_dp; ++id)
           for (int im = 0; im < p->n_mb; ++im)
-            place(c, p, ip, q, it, id, im, 0, 0, max_runs, pools, objective, has_bound, bound, out);
+            place(c, p, ip, q, it, id, im, 0, 0, max_runs, pools, pools_b, allow_split ? 1 : 0, objective,
+                  has_bound, bound, out);
   }
   return 0;
 }

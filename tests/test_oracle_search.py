@@ -194,3 +194,70 @@ def test_with_a_single_choice_per_stage_the_first_bound_is_the_value():
         lb = orc.prefix_bound(0, 0, 0, 0, 0, [0, 0, 0], 1)
         assert e.mask == 0
         assert lb[0] == pytest.approx(e.iter_time, rel=1e-14) and lb[1] == pytest.approx(e.cost, rel=1e-14)
+
+
+# ---- stages that may split their replicas over two pools --------------------------------------
+
+def _eval_split(orc, sp, objective):
+    return orc.eval_split_assignment(sp.pp_idx, sp.partition, sp.dp_idx, sp.mb_idx, sp.tp_idx,
+                                     sp.pools, sp.pools_b, objective)
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+@pytest.mark.parametrize("seed", [51, 52, 53])
+def test_the_beam_with_split_stages_without_a_cut_is_exhaustive(seed, objective):
+    # (pools)^2 choices per stage: 16^P placements per sub-problem on 2 zones x 2 types
+    prob = _tiny(seed, n_layers=3 if seed % 2 else 4, n_types=2, n_zones=2, partitions_per_pp=1)
+    orc = Oracle(prob)
+    want = orc.search_exhaustive(objective, allow_split=True)
+    got = orc.search_beam(1 << 22, objective, allow_split=True)
+    assert (want is None) == (got is None)
+    if want is None:
+        return
+    assert not got.truncated
+    assert got.key == pytest.approx(want.key, rel=1e-12)
+    e = _eval_split(orc, got, objective)
+    assert e.mask == 0
+    assert e.iter_time == pytest.approx(got.iter_time, rel=1e-12) and e.cost == pytest.approx(got.cost, rel=1e-12)
+    # splitting can only help: the unsplit optimum is one of the placements
+    plain = orc.search_beam(1 << 22, objective)
+    assert got.key <= plain.key * (1 + 1e-12)
+    # and never helps a search restricted to unsplit stages by accident: with one pool it is the same
+    inc = orc.search_beam(1 << 22, objective, allow_split=True, incumbent=plain.key * (1 + 1e-9))
+    assert inc.key == got.key and inc.expanded <= got.expanded
+    wb = want.cost if objective == MAX_THROUGHPUT else 1.0 / want.iter_time
+    bound = wb * (0.85 if objective == MAX_THROUGHPUT else 1.2) * (1 + 1e-7)
+    a, b = orc.search_exhaustive(objective, bound, allow_split=True), orc.search_beam(1 << 22, objective, bound, allow_split=True)
+    assert (a is None) == (b is None) and (a is None or b.key == pytest.approx(a.key, rel=1e-12))
+
+
+def test_split_stages_win_where_one_zone_is_too_small():
+    # two zones of 3 GPUs each, one stage of TP 1, D = 4: no zone holds four replicas, two in
+    # each does; the slower link between the zones sets the all-reduce
+    bw = np.array([[1e10, 5e9], [6e9, 1e10]])
+    p = make_problem(n_layers=2, n_types=1, n_zones=2, mb_list=(1,), tp_list=(1,), dp_list=(2, 4), pp_list=[1],
+                     global_batch=8, layer_params=1_000_000, bw=bw, avail=3)
+    orc = Oracle(p)
+    plain = orc.search_beam(64)
+    split = orc.search_beam(64, allow_split=True)
+    assert plain.dp_idx == 0                       # D = 2 inside one zone
+    assert split.dp_idx == 1 and sorted((split.pools[0], split.pools_b[0])) == [0, 1]
+    e = _eval_split(orc, split, MAX_THROUGHPUT)
+    assert e.mask == 0 and e.iter_time == pytest.approx(split.iter_time, rel=1e-13)
+    # two microbatches of 2 layers x 3 ms, the ring 2 * 3/4 * 4 MB over 5 GB/s
+    assert split.iter_time == pytest.approx(2 * 6e-3 + 1.5 * 4e6 / 5e9, rel=1e-12)
+    assert split.iter_time < plain.iter_time
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+def test_a_narrow_beam_with_split_stages_returns_valid_plans(objective):
+    prob = _tiny(61, n_layers=6, n_types=2, n_zones=2)
+    orc = Oracle(prob)
+    prev = None
+    for width in (1, 4, 32, 512):
+        got = orc.search_beam(width, objective, allow_split=True)
+        e = _eval_split(orc, got, objective)
+        assert e.mask == 0 and _key(e, objective) == pytest.approx(got.key, rel=1e-12)
+        if prev is not None:
+            assert got.key <= prev * (1 + 1e-12)
+        prev = got.key
