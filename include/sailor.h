@@ -338,6 +338,9 @@ typedef struct {
   int32_t use_incumbent;  /* 0: none; 1: `incumbent` below; 2: sailor_best_plan runs first and its
                              key, times 1 + 1e-9, is the incumbent */
   double incumbent;       /* placements whose bound exceeds it are dropped, complete plans too */
+  int32_t allow_split;    /* 1: a stage may put half of its D replicas on a second pool, also of
+                             another zone (see sailor_eval_placements); a stage then has
+                             (pools)^2 choices (a, b).  Pipelines of at most 127 stages */
 } sailor_search_options;
 
 /* A plan with one pool per stage (plan tuple of Sec. 4.2). */
@@ -354,6 +357,8 @@ typedef struct {
   int32_t incumbent_used;
   double incumbent;
   int32_t pool[SAILOR_MAX_STAGES]; /* zone * n_types + type of every stage; unused entries -1 */
+  int32_t pool_b[SAILOR_MAX_STAGES]; /* pool of the other half of the stage's replicas (= pool[i]
+                                        unless the stage is split) */
 } sailor_stage_plan;
 
 /* Search on top of the evaluator for spaces too large to enumerate (Sec. 4.2.2: resources are
@@ -369,6 +374,9 @@ typedef struct {
  * the result is the optimum over all placements; otherwise it is the best plan these steps
  * reach.  Equal keys: the first sub-problem in the order pp, layer split, TP, D, microbatch
  * size.  All arithmetic is fp64 in stage order, so the reported values are those of the plan.
+ * With allow_split the two halves of the replicas form two kinds of pipeline, kept apart in the
+ * bounds (the slower counts, Sec. 4.3), and the D tuples of a stage (Sec. 4.2) may lie in two
+ * zones; unsplit stages cost what they cost without the option.
  * Not for problems with per_segment_tp, mixed_types or bw_poly, more than 64 pools or 255
  * stages (SAILOR_EINVAL).  Waits for the device.  SAILOR_ENOFEASIBLE (out->found = 0, exact and
  * expanded still set) when no valid plan is found. */

@@ -83,7 +83,7 @@ MAX_STAGES = 256
 
 class sailor_search_options(C.Structure):
     _fields_ = [("beam_width", C.c_int32), ("max_runs", C.c_int32), ("use_incumbent", C.c_int32),
-                ("incumbent", C.c_double)]
+                ("incumbent", C.c_double), ("allow_split", C.c_int32)]
 
 
 class sailor_stage_plan(C.Structure):
@@ -95,7 +95,7 @@ class sailor_stage_plan(C.Structure):
                 ("iter_time_s", C.c_double), ("cost_per_iter", C.c_double),
                 ("eval_time_s", C.c_double), ("eval_cost", C.c_double),
                 ("expanded", C.c_uint64), ("incumbent_used", C.c_int32), ("incumbent", C.c_double),
-                ("pool", C.c_int32 * MAX_STAGES)]
+                ("pool", C.c_int32 * MAX_STAGES), ("pool_b", C.c_int32 * MAX_STAGES)]
 
 
 @dataclass
@@ -121,6 +121,7 @@ class StagePlan:
     expanded: int
     incumbent: Optional[float]
     pools: Tuple[int, ...]
+    pools_b: Tuple[int, ...] = ()
 
 
 @dataclass
@@ -382,10 +383,10 @@ class Plan:
         return a.value, b.value, c.value
 
     def search(self, beam_width: int, objective: int = MAX_THROUGHPUT, bound: Optional[float] = None,
-               max_runs: int = 0, incumbent=None, stream: int = 0) -> StagePlan:
+               max_runs: int = 0, incumbent=None, stream: int = 0, allow_split: bool = False) -> StagePlan:
         """sailor_search.  incumbent: None, a float, or "flat" (the library takes the best plan
         of the flat space).  The returned plan has found = False when nothing valid exists."""
-        o = sailor_search_options(beam_width, max_runs, 0, 0.0)
+        o = sailor_search_options(beam_width, max_runs, 0, 0.0, 1 if allow_split else 0)
         if incumbent == "flat":
             o.use_incumbent = 2
         elif incumbent is not None:
@@ -398,7 +399,8 @@ class Plan:
         return StagePlan(bool(r.found), bool(r.exact), r.pp, r.tp, r.dp, r.mb, r.pp_index, r.tp_index,
                          r.dp_index, r.mb_index, r.partition, r.mask, r.peak_mem_bytes, r.iter_time_s,
                          r.cost_per_iter, r.eval_time_s, r.eval_cost, r.expanded,
-                         r.incumbent if r.incumbent_used else None, tuple(r.pool[:r.pp]))
+                         r.incumbent if r.incumbent_used else None, tuple(r.pool[:r.pp]),
+                         tuple(r.pool_b[:r.pp]))
 
     def eval_placements(self, count: int, d_desc, d_pools, pool_stride: int,
                         objective: int = MAX_THROUGHPUT, bound: Optional[float] = None, d_time=None,

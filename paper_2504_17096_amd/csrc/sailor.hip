@@ -157,7 +157,7 @@ struct sailor_plan {
   const SearchPP *d_search_pps = nullptr;
   uint32_t n_sub = 0;
   uint8_t *search_states = nullptr;
-  uint32_t search_wgs = 0, search_state_stride = 0;
+  uint32_t search_wgs = 0, search_state_stride = 0, search_path_stride = 0;
   SubResult *search_results = nullptr, *search_final = nullptr;
   double *search_eval = nullptr;  // T, C, then (as 64-bit words) mem and mask of the winner
   uint32_t cnt_phase = 0;      // which of the two counter sets the next call uses
@@ -1357,7 +1357,8 @@ static sailor_status search_setup(sailor_plan *pl, bool with_scratch) {
   }
   if (with_scratch && !pl->search_states) {
     pl->search_wgs = std::min<uint32_t>(pl->n_sub, 2048u);
-    pl->search_state_stride = (kStateBytes + (uint32_t)pl->dev.P_max + 7u) & ~7u;
+    pl->search_path_stride = ((uint32_t)pl->dev.P_max + 7u) & ~7u;
+    pl->search_state_stride = kStateBytes + 2 * pl->search_path_stride;
     const size_t bytes = (size_t)pl->search_wgs * 2 * kSearchMaxBeam * pl->search_state_stride;
     if (pl->arena.alloc(&pl->search_states, bytes) != hipSuccess ||
         pl->arena.alloc(&pl->search_results, (size_t)pl->n_sub) != hipSuccess ||
@@ -1408,6 +1409,8 @@ sailor_status sailor_search(sailor_plan *pl, sailor_objective objective,
       opt->use_incumbent < 0 || opt->use_incumbent > 2)
     return SAILOR_EINVAL;
   if (opt->use_incumbent == 1 && std::isnan(opt->incumbent)) return SAILOR_EINVAL;
+  if (opt->allow_split != 0 && opt->allow_split != 1) return SAILOR_EINVAL;
+  if (opt->allow_split && pl->dev.P_max > 127) return SAILOR_EINVAL;  // halves of stages counted in a byte
   // one TP degree and one pool per stage, constant link bandwidths, stages counted in a byte
   if (pl->dev.mixed || pl->dev.pst || pl->dev.n_bw_coef > 0 || pl->dev.ZGr > kSearchMaxPools ||
       pl->dev.P_max > kSearchMaxStages)
@@ -1449,8 +1452,10 @@ sailor_status sailor_search(sailor_plan *pl, sailor_objective objective,
   a.n_sub = pl->n_sub;
   a.states = pl->search_states;
   a.state_stride = pl->search_state_stride;
+  a.path_stride = pl->search_path_stride;
   a.results = pl->search_results;
-  k_search_beam<<<pl->search_wgs, kSearchThreads, 0, st>>>(pl->dev, a);
+  if (opt->allow_split) k_search_beam<true><<<pl->search_wgs, kSearchThreads, 0, st>>>(pl->dev, a);
+  else k_search_beam<false><<<pl->search_wgs, kSearchThreads, 0, st>>>(pl->dev, a);
   k_search_pick<<<1, 256, 0, st>>>(pl->search_results, pl->n_sub, pl->search_final);
   // the winner once more through the simulator, for its memory footprint and its mask
   PlaceArgs pa{};
@@ -1473,7 +1478,7 @@ sailor_status sailor_search(sailor_plan *pl, sailor_objective objective,
   HIP_TRY(hipMemcpyAsync(ev, pl->search_eval, sizeof ev, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
   std::memset(out, 0, sizeof *out);
-  for (int i = 0; i < SAILOR_MAX_STAGES; ++i) out->pool[i] = -1;
+  for (int i = 0; i < SAILOR_MAX_STAGES; ++i) out->pool[i] = out->pool_b[i] = -1;
   out->exact = fin.truncated ? 0 : 1;
   out->expanded = fin.expanded;
   out->incumbent_used = a.has_inc;
@@ -1495,7 +1500,10 @@ sailor_status sailor_search(sailor_plan *pl, sailor_objective objective,
   out->eval_cost = ev[1];
   std::memcpy(&out->peak_mem_bytes, &ev[2], sizeof(uint64_t));
   std::memcpy(&out->mask, &ev[3], sizeof(uint32_t));
-  for (int i = 0; i < out->pp; ++i) out->pool[i] = fin.pools[i];
+  for (int i = 0; i < out->pp; ++i) {
+    out->pool[i] = fin.pools[i];
+    out->pool_b[i] = fin.pools_b[i];
+  }
   return SAILOR_OK;
 }
 

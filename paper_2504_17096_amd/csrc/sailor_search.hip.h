@@ -38,25 +38,27 @@ struct SearchPP {      // one pipeline depth
   int32_t n_part;
 };
 
-struct SState {        // placement of stages 0 .. j; kStateBytes, followed by the path (a byte per stage)
+struct SState {        // placement of stages 0 .. j; kStateBytes, followed by the paths (a byte per stage)
   double sum;          // times of the closed stages 0 .. j-1
   double maxt;         // slowest closed stage
   double c_open;       // compute time of stage j (its forward transfer is not known yet)
   double xb_open;      // its backward transfer to stage j-1
+  double sum_b, maxt_b, c_open_b, xb_open_b;  // with split stages: the pipelines through the second pools
   double msync, mupd, dol, comm;
-  uint8_t cnt[kSearchMaxPools];  // stages placed on each pool
-  uint8_t pool, runs, pad[6];
+  uint8_t cnt[kSearchMaxPools];  // stages placed on each pool (with split stages: halves of stages)
+  uint8_t pool, pool_b, runs, pad[5];
 };
 constexpr uint32_t kStateBytes = sizeof(SState);
-static_assert(kStateBytes == 136, "eight doubles, the pool counts, pool and runs");
+static_assert(kStateBytes == 168, "twelve doubles, the pool counts, pools and runs");
 
 struct SubResult {     // winner of one sub-problem (or of the whole search)
   double key, T, C;
   uint32_t found, truncated;
   unsigned long long expanded;
   uint32_t sid, P;
-  int32_t desc[6];     // pp index, partition, tp index, dp index, mb index, unused
-  uint8_t pools[256];
+  int32_t desc[6];     // pp index, partition, tp index, dp index, mb index, 1 when stages may be split
+  int32_t pools[256];  // pool of every stage
+  int32_t pools_b[256];  // pool of the other half of its replicas (= pools[i] when not split)
 };
 
 struct SearchArgs {
@@ -66,7 +68,8 @@ struct SearchArgs {
   int n_pp;
   uint32_t n_sub;
   uint8_t *states;        // [workgroups][2][W] states of state_stride bytes
-  uint32_t state_stride;  // kStateBytes + the path, rounded up to 8
+  uint32_t state_stride;  // kStateBytes + two paths of path_stride bytes
+  uint32_t path_stride;   // the deepest pipeline, rounded up to 8
   SubResult *results;     // [n_sub]
 };
 
@@ -115,15 +118,115 @@ __device__ __forceinline__ void search_sort(unsigned long long *key, uint32_t *i
     }
 }
 
+struct SearchTables {  // LDS of a search workgroup: the sub-problem's and the level's tables
+  double S[5][kSearchMaxStages + 1];   // what lies behind stage i: sum, max, sync, upd, $
+  double xfer[kMaxZones][kMaxZones], comm[kMaxZones][kMaxZones];
+  double comm_half[kMaxZones][kMaxZones];  // traffic of one kind of pipeline (half of the replicas)
+  double bw[kMaxZones][kMaxZones], ring_price[kMaxZones][kMaxZones];
+  double l_c[kMaxTypes], l_upd[kMaxTypes], l_dol[kMaxTypes], l_price[kMaxTypes], l_sync[kMaxZones];
+  double l_ring;                       // bytes the level's stage's ring all-reduce moves over every link
+  double smin[4][kSearchMaxStages + 1];  // cheapest admissible choice of every stage
+  int cap[kSearchMaxPools];            // stages a pool can host
+  int cap_half[kSearchMaxPools];       // halves of stages
+  uint32_t l_fit;                      // bit g: the level's stage fits type g
+  int dp_even;
+  double dtp;                          // D * tp
+};
+
+struct SAcc {          // what a placement carries besides its pool counts
+  double sum, maxt, c_open, xb_open, sum_b, maxt_b, c_open_b, xb_open_b, msync, mupd, dol, comm;
+};
+
+// Stage j on pool a (SPLIT: half of its replicas on pool b) behind the placement par (none for
+// j = 0): may it be placed, and what the placement then carries.  The order of the operations
+// is part of the definition: sums in stage order, a closed stage's transfers forward then
+// backward.
+template <bool SPLIT>
+__device__ __forceinline__ bool search_step(const SearchTables &T, const SState *par, int j, int a, int b,
+                                            int G, int max_runs, SAcc &o, int &runs) {
+  const int ga = a % G, za = a / G, gb = b % G, zb = b / G;
+  bool ok = ((T.l_fit >> ga) & 1u) != 0 && ((T.l_fit >> gb) & 1u) != 0;
+  const int ca = par ? (int)par->cnt[a] : 0, cb = par ? (int)par->cnt[b] : 0;
+  if (!SPLIT) ok = ok && ca + 1 <= T.cap[a];
+  else if (a == b) ok = ok && ca + 2 <= T.cap_half[a];
+  else ok = ok && T.dp_even && ca + 1 <= T.cap_half[a] && cb + 1 <= T.cap_half[b];
+  runs = par ? par->runs + ((a != par->pool || (SPLIT && b != par->pool_b)) ? 1 : 0) : 1;
+  if (max_runs != 0 && runs > max_runs) ok = false;
+  if (!ok) return false;
+  if (!SPLIT) {
+    o.c_open = T.l_c[ga];
+    if (!par) {
+      o.sum = 0.0; o.maxt = 0.0; o.xb_open = 0.0; o.msync = T.l_sync[za]; o.mupd = T.l_upd[ga];
+      o.dol = T.l_dol[ga]; o.comm = 0.0;
+    } else {
+      const int pz = par->pool / G;
+      const double t_closed = par->c_open + (T.xfer[pz][za] + par->xb_open);  // forward, then backward
+      o.sum = par->sum + t_closed;
+      o.maxt = fmax(par->maxt, t_closed);
+      o.xb_open = T.xfer[za][pz];
+      o.msync = fmax(par->msync, T.l_sync[za]);
+      o.mupd = fmax(par->mupd, T.l_upd[ga]);
+      o.dol = par->dol + T.l_dol[ga];
+      o.comm = pz != za ? par->comm + T.comm[pz][za] : par->comm;
+    }
+    o.sum_b = o.maxt_b = o.c_open_b = o.xb_open_b = 0.0;
+    return true;
+  }
+  // the stage by itself: all-reduce over the slowest link of a ring through both pools, the
+  // slower update, the mean rent, the ring's traffic between the zones
+  double link = T.bw[za][za];
+  if (zb != za) link = fmin(fmin(link, T.bw[zb][zb]), fmin(T.bw[za][zb], T.bw[zb][za]));
+  const double sync = T.l_ring / link;
+  const double upd = fmax(T.l_upd[ga], T.l_upd[gb]);
+  const double dol = T.dtp * (0.5 * (T.l_price[ga] + T.l_price[gb]));
+  const double ring = zb != za ? T.l_ring * T.ring_price[za][zb] : 0.0;
+  o.c_open = T.l_c[ga];
+  o.c_open_b = T.l_c[gb];
+  if (!par) {
+    o.sum = o.maxt = o.xb_open = o.sum_b = o.maxt_b = o.xb_open_b = 0.0;
+    o.msync = sync; o.mupd = upd; o.dol = dol; o.comm = ring;
+  } else {
+    const int pza = par->pool / G, pzb = par->pool_b / G;
+    const double ta = par->c_open + (T.xfer[pza][za] + par->xb_open);
+    const double tb = par->c_open_b + (T.xfer[pzb][zb] + par->xb_open_b);
+    o.sum = par->sum + ta;
+    o.maxt = fmax(par->maxt, ta);
+    o.sum_b = par->sum_b + tb;
+    o.maxt_b = fmax(par->maxt_b, tb);
+    o.xb_open = T.xfer[za][pza];
+    o.xb_open_b = T.xfer[zb][pzb];
+    o.msync = fmax(par->msync, sync);
+    o.mupd = fmax(par->mupd, upd);
+    o.dol = par->dol + dol;
+    double comm = par->comm;
+    if (pza != za) comm += T.comm_half[pza][za];
+    if (pzb != zb) comm += T.comm_half[pzb][zb];
+    o.comm = comm + ring;
+  }
+  return true;
+}
+
+// Bounds of a placement whose stage j is open; with split stages the slower of the two kinds
+// of pipeline counts (Sec. 4.3).
+template <bool SPLIT>
+__device__ __forceinline__ SBound search_bound_of(const SearchTables &T, const SAcc &o, int j, double nbm1) {
+  if (!SPLIT)
+    return search_bounds(o.sum, o.maxt, o.c_open, o.xb_open, o.msync, o.mupd, o.dol, o.comm, T.S[0][j],
+                         T.S[1][j], T.S[2][j], T.S[3][j], T.S[4][j], nbm1);
+  const double ta = o.c_open + o.xb_open, tb = o.c_open_b + o.xb_open_b;
+  const double pa = ((o.sum + ta) + T.S[0][j]) + nbm1 * fmax(fmax(o.maxt, ta), T.S[1][j]);
+  const double pb = ((o.sum_b + tb) + T.S[0][j]) + nbm1 * fmax(fmax(o.maxt_b, tb), T.S[1][j]);
+  SBound b;
+  b.T = (fmax(pa, pb) + fmax(o.msync, T.S[2][j])) + fmax(o.mupd, T.S[3][j]);
+  b.C = (o.dol + T.S[4][j]) / 3600.0 * b.T + o.comm;
+  return b;
+}
+
+template <bool SPLIT>
 __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, SearchArgs a) {
-  __shared__ double s_S[5][kSearchMaxStages + 1];        // what lies behind stage i: sum, max, sync, upd, $
-  __shared__ double s_xfer[kMaxZones][kMaxZones], s_comm[kMaxZones][kMaxZones];
-  __shared__ double l_c[kMaxTypes], l_upd[kMaxTypes], l_dol[kMaxTypes], l_sync[kMaxZones];
-  __shared__ double s_min[4][kSearchMaxStages + 1];      // cheapest admissible choice of every stage
-  __shared__ int s_cap[kSearchMaxPools];                 // stages a pool can host
+  __shared__ SearchTables T;
   __shared__ unsigned long long b_key[kSearchBuf];
   __shared__ uint32_t b_id[kSearchBuf];
-  __shared__ uint32_t l_fit;                             // bit g: the level's stage fits type g
   __shared__ uint32_t s_wave[kSearchThreads / 64];
   __shared__ int s_nbuf, s_bad;
   __shared__ unsigned long long s_bk[kSearchThreads / 64];
@@ -131,6 +234,7 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
   __shared__ unsigned long long s_expanded;
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
   const int G = pl.G, Z = pl.Z, ZG = pl.ZGr, MB = pl.MB, TP = pl.TP, DP = pl.DP;
+  const int NCH = SPLIT ? ZG * ZG : ZG;  // choices per stage: a pool, or a pair (a, b) = a * ZG + b
   uint8_t *const buf0 = a.states + (size_t)blockIdx.x * 2 * a.W * a.state_stride;
   uint8_t *const buf1 = buf0 + (size_t)a.W * a.state_stride;
 
@@ -154,24 +258,37 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
     if (t == 0) {
       res->found = 0; res->truncated = 0; res->expanded = 0; res->sid = sid; res->P = (uint32_t)P;
       res->desc[0] = ip; res->desc[1] = q; res->desc[2] = it; res->desc[3] = id; res->desc[4] = im;
-      res->desc[5] = 0;
+      res->desc[5] = SPLIT ? 1 : 0;
       s_bad = 0;
       s_expanded = 0;
+      T.dp_even = (D % 2 == 0) ? 1 : 0;
+      T.dtp = (double)(D * tp);
     }
     __syncthreads();
-    if (nb == 0) continue;  // the batch does not divide (uniform)
+    if (nb == 0) continue;              // the batch does not divide (uniform)
+    if (SPLIT && P > 127) continue;     // halves of stages are counted in a byte (uniform)
     const double p2p = (double)pl.p2p[im];
     const double nbm1 = (double)(nb - 1);
     // tables of the sub-problem
     for (int i = t; i < Z * Z; i += blockDim.x) {
       const int z = i / Z, y = i - z * Z;
-      s_xfer[z][y] = p2p / pl.bw[z * Z + y];
-      double cm = 0.0;
-      if (pl.egress && z != y)
-        cm = (double)nb * (double)D * p2p * (pl.egress[z * Z + y] + pl.egress[y * Z + z]);
-      s_comm[z][y] = cm;
+      T.xfer[z][y] = p2p / pl.bw[z * Z + y];
+      T.bw[z][y] = pl.bw[z * Z + y];
+      double cm = 0.0, ch = 0.0, rp = 0.0;
+      if (pl.egress && z != y) {
+        const double both = pl.egress[z * Z + y] + pl.egress[y * Z + z];
+        cm = (double)nb * (double)D * p2p * both;
+        ch = (double)nb * (0.5 * (double)D) * p2p * both;
+        rp = both;
+      }
+      T.comm[z][y] = cm;
+      T.comm_half[z][y] = ch;
+      T.ring_price[z][y] = rp;
     }
-    for (int p = t; p < ZG; p += blockDim.x) s_cap[p] = (int)((int64_t)pl.avail[p] / ((int64_t)tp * D));
+    for (int p = t; p < ZG; p += blockDim.x) {
+      T.cap[p] = (int)((int64_t)pl.avail[p] / ((int64_t)tp * D));
+      T.cap_half[p] = (int)(2 * (int64_t)pl.avail[p] / ((int64_t)tp * D));
+    }
     for (int i = t; i < P; i += blockDim.x) {  // the cheapest admissible choice of stage i
       const uint64_t params = pl.st_params[rs + i];
       const uint64_t bytes = stage_bytes_of(params, pl.st_n[rs + i], pl.bpp, i, P, tp, nb, pl.act[im * TP + it]);
@@ -193,19 +310,19 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
         }
         smin = fmin(smin, sync);
       }
-      s_min[0][i] = cmin; s_min[1][i] = smin; s_min[2][i] = umin; s_min[3][i] = dmin;
+      T.smin[0][i] = cmin; T.smin[1][i] = smin; T.smin[2][i] = umin; T.smin[3][i] = dmin;
       if (!any) s_bad = 1;  // (benign race: every writer stores 1)
     }
     __syncthreads();
     if (s_bad) continue;  // some stage fits no pool (uniform)
     if (t == 0) {  // what lies behind stage i, accumulated from the last stage backwards
-      s_S[0][P - 1] = s_S[1][P - 1] = s_S[2][P - 1] = s_S[3][P - 1] = s_S[4][P - 1] = 0.0;
+      T.S[0][P - 1] = T.S[1][P - 1] = T.S[2][P - 1] = T.S[3][P - 1] = T.S[4][P - 1] = 0.0;
       for (int i = P - 2; i >= 0; --i) {
-        s_S[0][i] = s_S[0][i + 1] + s_min[0][i + 1];
-        s_S[1][i] = fmax(s_S[1][i + 1], s_min[0][i + 1]);
-        s_S[2][i] = fmax(s_S[2][i + 1], s_min[1][i + 1]);
-        s_S[3][i] = fmax(s_S[3][i + 1], s_min[2][i + 1]);
-        s_S[4][i] = s_S[4][i + 1] + s_min[3][i + 1];
+        T.S[0][i] = T.S[0][i + 1] + T.smin[0][i + 1];
+        T.S[1][i] = fmax(T.S[1][i + 1], T.smin[0][i + 1]);
+        T.S[2][i] = fmax(T.S[2][i + 1], T.smin[1][i + 1]);
+        T.S[3][i] = fmax(T.S[3][i + 1], T.smin[2][i + 1]);
+        T.S[4][i] = T.S[4][i + 1] + T.smin[3][i + 1];
       }
     }
     int n_cur = 1;  // frontier length; level 0 extends one empty placement
@@ -217,28 +334,30 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
       if (t < G) {
         const uint64_t params = pl.st_params[rs + j];
         const uint64_t bytes = stage_bytes_of(params, pl.st_n[rs + j], pl.bpp, j, P, tp, nb, pl.act[im * TP + it]);
-        l_c[t] = pl.st_c[(((size_t)(rs + j) * G + t) * MB + im) * TP + it];
-        l_upd[t] = pl.st_u[((size_t)(rs + j) * G + t) * TP + it];
-        l_dol[t] = (double)(D * tp) * pl.price[t];
+        T.l_c[t] = pl.st_c[(((size_t)(rs + j) * G + t) * MB + im) * TP + it];
+        T.l_upd[t] = pl.st_u[((size_t)(rs + j) * G + t) * TP + it];
+        T.l_dol[t] = (double)(D * tp) * pl.price[t];
+        T.l_price[t] = pl.price[t];
         const bool fits = bytes + pl.res[t] <= pl.cap[t] && tp <= pl.node[t];
         const unsigned long long m = __builtin_amdgcn_ballot_w64(fits);
-        if (t == 0) l_fit = (uint32_t)m;
+        if (t == 0) T.l_fit = (uint32_t)m;
       } else if (t >= 64 && t < 64 + Z) {
         const int z = t - 64;
         const uint64_t params = pl.st_params[rs + j];
         const uint64_t shard = (params + (uint64_t)tp - 1) / (uint64_t)tp;
-        double sync = 0.0;
+        double sync = 0.0, ring = 0.0;
         if (D > 1) {
           const double grad = (double)shard * (double)pl.gb;
           sync = 2.0 * (double)(D - 1) / (double)D * grad / pl.bw[z * Z + z];
+          ring = 2.0 * (double)(D - 1) / (double)D * grad;
         }
-        l_sync[z] = sync;
+        T.l_sync[z] = sync;
+        if (z == 0) T.l_ring = ring;
       }
       if (t == 0) s_nbuf = 0;
       __syncthreads();
-      const double Ssum = s_S[0][j], Smax = s_S[1][j], Ssync = s_S[2][j], Supd = s_S[3][j], Sdol = s_S[4][j];
       const bool last = j == P - 1;
-      const int n_total = n_cur * ZG;
+      const int n_total = n_cur * NCH;
       unsigned long long best_k = ~0ull;  // last level: this thread's smallest (key, id)
       uint32_t best_i = ~0u;
       uint32_t my_expanded = 0;
@@ -247,30 +366,14 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
         bool keep = false;
         unsigned long long kbits = 0;
         if (cand < n_total) {
-          const int r = cand / ZG, p = cand - r * ZG, g = p % G, z = p / G;
-          bool ok = ((l_fit >> g) & 1u) != 0;
-          double sum = 0.0, maxt = 0.0, c_open = l_c[g], xb_open = 0.0, msync = l_sync[z], mupd = l_upd[g],
-                 dol = l_dol[g], comm = 0.0;
-          if (j == 0) {
-            ok = ok && s_cap[p] >= 1;
-          } else {
-            const SState *par = reinterpret_cast<const SState *>(cur + (size_t)r * a.state_stride);
-            const int pz = par->pool / G;
-            const int runs = par->runs + (p != par->pool ? 1 : 0);
-            ok = ok && (int)par->cnt[p] + 1 <= s_cap[p] && (a.max_runs == 0 || runs <= a.max_runs);
-            const double t_closed = par->c_open + (s_xfer[pz][z] + par->xb_open);  // forward, then backward
-            sum = par->sum + t_closed;
-            maxt = fmax(par->maxt, t_closed);
-            xb_open = s_xfer[z][pz];
-            msync = fmax(par->msync, l_sync[z]);
-            mupd = fmax(par->mupd, l_upd[g]);
-            dol = par->dol + l_dol[g];
-            comm = pz != z ? par->comm + s_comm[pz][z] : par->comm;
-          }
-          if (ok) {
+          const int r = cand / NCH, c = cand - r * NCH;
+          const int pa = SPLIT ? c / ZG : c, pb = SPLIT ? c - pa * ZG : c;
+          const SState *par = j == 0 ? nullptr : reinterpret_cast<const SState *>(cur + (size_t)r * a.state_stride);
+          SAcc o;
+          int runs;
+          if (search_step<SPLIT>(T, par, j, pa, pb, G, a.max_runs, o, runs)) {
             my_expanded += 1;
-            const SBound b = search_bounds(sum, maxt, c_open, xb_open, msync, mupd, dol, comm, Ssum, Smax,
-                                           Ssync, Supd, Sdol, nbm1);
+            const SBound b = search_bound_of<SPLIT>(T, o, j, nbm1);
             const double key = a.objective == 0 ? b.T : b.C;
             bool drop = false;
             if (a.has_bound) drop = a.objective == 0 ? b.C > a.bound : 1.0 / b.T < a.bound;
@@ -323,27 +426,21 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
         for (int w = 1; w < kSearchThreads / 64; ++w)
           if (key_id_less(s_bk[w], s_bi[w], best_k, best_i)) { best_k = s_bk[w]; best_i = s_bi[w]; }
         if (best_i != ~0u) {  // uniform
-          const int r = (int)best_i / ZG, p = (int)best_i - r * ZG, g = p % G, z = p / G;
+          const int r = (int)best_i / NCH, c = (int)best_i - r * NCH;
+          const int pa = SPLIT ? c / ZG : c, pb = SPLIT ? c - pa * ZG : c;
           const uint8_t *par_path = cur + (size_t)r * a.state_stride + kStateBytes;
-          for (int i = t; i < P - 1; i += blockDim.x) res->pools[i] = par_path[i];
+          for (int i = t; i < P - 1; i += blockDim.x) {
+            res->pools[i] = par_path[i];
+            res->pools_b[i] = SPLIT ? par_path[a.path_stride + i] : par_path[i];
+          }
           if (t == 0) {
-            double sum = 0.0, maxt = 0.0, xb_open = 0.0, msync = l_sync[z], mupd = l_upd[g], dol = l_dol[g],
-                   comm = 0.0;
-            if (j > 0) {
-              const SState *par = reinterpret_cast<const SState *>(cur + (size_t)r * a.state_stride);
-              const int pz = par->pool / G;
-              const double t_closed = par->c_open + (s_xfer[pz][z] + par->xb_open);
-              sum = par->sum + t_closed;
-              maxt = fmax(par->maxt, t_closed);
-              xb_open = s_xfer[z][pz];
-              msync = fmax(par->msync, l_sync[z]);
-              mupd = fmax(par->mupd, l_upd[g]);
-              dol = par->dol + l_dol[g];
-              comm = pz != z ? par->comm + s_comm[pz][z] : par->comm;
-            }
-            const SBound b = search_bounds(sum, maxt, l_c[g], xb_open, msync, mupd, dol, comm, 0.0, 0.0, 0.0,
-                                           0.0, 0.0, nbm1);
-            res->pools[P - 1] = (uint8_t)p;
+            const SState *par = j == 0 ? nullptr : reinterpret_cast<const SState *>(cur + (size_t)r * a.state_stride);
+            SAcc o;
+            int runs;
+            search_step<SPLIT>(T, par, j, pa, pb, G, a.max_runs, o, runs);
+            const SBound b = search_bound_of<SPLIT>(T, o, j, nbm1);
+            res->pools[P - 1] = pa;
+            res->pools_b[P - 1] = pb;
             res->T = b.T;
             res->C = b.C;
             res->key = a.objective == 0 ? b.T : b.C;
@@ -363,36 +460,40 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
       // write the next frontier
       for (int k = t; k < n_next; k += blockDim.x) {
         const int cand = (int)b_id[k];
-        const int r = cand / ZG, p = cand - r * ZG, g = p % G, z = p / G;
+        const int r = cand / NCH, c = cand - r * NCH;
+        const int pa = SPLIT ? c / ZG : c, pb = SPLIT ? c - pa * ZG : c;
         uint8_t *const out = nxt + (size_t)k * a.state_stride;
+        const SState *par = j == 0 ? nullptr : reinterpret_cast<const SState *>(cur + (size_t)r * a.state_stride);
+        SAcc o;
+        int runs;
+        search_step<SPLIT>(T, par, j, pa, pb, G, a.max_runs, o, runs);
         SState st;
-        if (j == 0) {
-          st.sum = 0.0; st.maxt = 0.0; st.xb_open = 0.0; st.msync = l_sync[z]; st.mupd = l_upd[g];
-          st.dol = l_dol[g]; st.comm = 0.0;
-          for (int c = 0; c < kSearchMaxPools; ++c) st.cnt[c] = 0;
-          st.runs = 1;
-        } else {
-          const SState *par = reinterpret_cast<const SState *>(cur + (size_t)r * a.state_stride);
+        if (par) {
           st = *par;
-          const int pz = par->pool / G;
-          const double t_closed = par->c_open + (s_xfer[pz][z] + par->xb_open);
-          st.sum = par->sum + t_closed;
-          st.maxt = fmax(par->maxt, t_closed);
-          st.xb_open = s_xfer[z][pz];
-          st.msync = fmax(par->msync, l_sync[z]);
-          st.mupd = fmax(par->mupd, l_upd[g]);
-          st.dol = par->dol + l_dol[g];
-          st.comm = pz != z ? par->comm + s_comm[pz][z] : par->comm;
-          st.runs = (uint8_t)(par->runs + (p != par->pool ? 1 : 0));
           const uint8_t *par_path = cur + (size_t)r * a.state_stride + kStateBytes;
-          for (int i = 0; i < j; ++i) out[kStateBytes + i] = par_path[i];
+          for (int i = 0; i < j; ++i) {
+            out[kStateBytes + i] = par_path[i];
+            if (SPLIT) out[kStateBytes + a.path_stride + i] = par_path[a.path_stride + i];
+          }
+        } else {
+          for (int x = 0; x < kSearchMaxPools; ++x) st.cnt[x] = 0;
         }
-        st.c_open = l_c[g];
-        st.cnt[p] = (uint8_t)(st.cnt[p] + 1);
-        st.pool = (uint8_t)p;
-        for (int c = 0; c < 6; ++c) st.pad[c] = 0;
+        st.sum = o.sum; st.maxt = o.maxt; st.c_open = o.c_open; st.xb_open = o.xb_open;
+        st.sum_b = o.sum_b; st.maxt_b = o.maxt_b; st.c_open_b = o.c_open_b; st.xb_open_b = o.xb_open_b;
+        st.msync = o.msync; st.mupd = o.mupd; st.dol = o.dol; st.comm = o.comm;
+        if (!SPLIT) {
+          st.cnt[pa] = (uint8_t)(st.cnt[pa] + 1);
+        } else {
+          st.cnt[pa] = (uint8_t)(st.cnt[pa] + 1);
+          st.cnt[pb] = (uint8_t)(st.cnt[pb] + 1);
+        }
+        st.pool = (uint8_t)pa;
+        st.pool_b = (uint8_t)pb;
+        st.runs = (uint8_t)runs;
+        for (int x = 0; x < 5; ++x) st.pad[x] = 0;
         *reinterpret_cast<SState *>(out) = st;
-        out[kStateBytes + j] = (uint8_t)p;
+        out[kStateBytes + j] = (uint8_t)pa;
+        if (SPLIT) out[kStateBytes + a.path_stride + j] = (uint8_t)pb;
       }
       n_cur = n_next;
     }
@@ -589,14 +690,15 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl
   if (valid && !a.one && (uint32_t)P > a.pool_stride) valid = false;
   RefineLds &L = lds[wv];
   int *cnt = s_cnt[wv];
+  const bool split = a.one ? a.one->desc[5] != 0 : a.pools_b != nullptr;  // stages may split their replicas
   if (valid) {
     for (int p = lane; p < kSearchMaxPools; p += 64) cnt[p] = 0;
     bool bad = false;
     for (int i = lane; i < P; i += 64) {
-      const int p = a.one ? (int)a.one->pools[i] : a.pools[ci * a.pool_stride + i];
+      const int p = a.one ? a.one->pools[i] : a.pools[ci * a.pool_stride + i];
       if (p < 0 || p >= ZG) bad = true;
-      if (a.pools_b && !a.one) {
-        const int p2 = a.pools_b[ci * a.pool_stride + i];
+      if (split) {
+        const int p2 = a.one ? a.one->pools_b[i] : a.pools_b[ci * a.pool_stride + i];
         if (p2 < 0 || p2 >= ZG) bad = true;
       }
     }
@@ -609,9 +711,10 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl
     const int64_t tp = pl.tpv[it];
     if (nb == 0) {
       mask = 4u;
-    } else if (a.pools_b && !a.one) {
+    } else if (split) {
       __builtin_amdgcn_wave_barrier();
-      eval_split_wave(pl, a.pools + ci * a.pool_stride, a.pools_b + ci * a.pool_stride, P, rs, it, im, nb, D,
+      eval_split_wave(pl, a.one ? a.one->pools : a.pools + ci * a.pool_stride,
+                      a.one ? a.one->pools_b : a.pools_b + ci * a.pool_stride, P, rs, it, im, nb, D,
                       tp, L, s_second[wv], cnt, T, C, peak, mask);
       if (a.has_bound) {
         if (a.objective == 0) { if (C > a.bound) mask |= 32u; }
@@ -623,9 +726,9 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl
       double max_t = 0.0, t_sync = 0.0, t_upd = 0.0;
       uint32_t oom = 0, h1 = 0;
       for (int i = lane; i < P; i += 64) {
-        const int p = a.one ? (int)a.one->pools[i] : a.pools[ci * a.pool_stride + i];
-        const int pn = i < P - 1 ? (a.one ? (int)a.one->pools[i + 1] : a.pools[ci * a.pool_stride + i + 1]) : p;
-        const int pv = i > 0 ? (a.one ? (int)a.one->pools[i - 1] : a.pools[ci * a.pool_stride + i - 1]) : p;
+        const int p = a.one ? a.one->pools[i] : a.pools[ci * a.pool_stride + i];
+        const int pn = i < P - 1 ? (a.one ? a.one->pools[i + 1] : a.pools[ci * a.pool_stride + i + 1]) : p;
+        const int pv = i > 0 ? (a.one ? a.one->pools[i - 1] : a.pools[ci * a.pool_stride + i - 1]) : p;
         const int g = p % G, z = p / G, zn = pn / G, zp = pv / G;
         atomicAdd(&cnt[p], 1);
         const size_t si = (size_t)rs + i;

@@ -309,3 +309,84 @@ def test_best_split_plan_of_an_enumerated_space(torch_cuda):
             assert key[unsplit].min() >= key.min()
     finally:
         plan.destroy()
+
+
+# ---- the search with stages that may split their replicas ---------------------------------------
+
+def check_same_split(got, want, objective, orc):
+    assert got.found == (want is not None)
+    if want is None:
+        return
+    assert (got.pp_index, got.partition, got.tp_index, got.dp_index, got.mb_index) == \
+           (want.pp_idx, want.partition, want.tp_idx, want.dp_idx, want.mb_idx)
+    assert got.pools == want.pools and got.pools_b == want.pools_b
+    assert got.iter_time_s == want.iter_time and got.cost_per_iter == want.cost
+    assert got.exact == (not want.truncated) and got.expanded == want.expanded
+    assert got.mask == 0
+    assert got.eval_time_s == pytest.approx(got.iter_time_s, rel=1e-12)
+    assert got.eval_cost == pytest.approx(got.cost_per_iter, rel=1e-12)
+    e = orc.eval_split_assignment(got.pp_index, got.partition, got.dp_index, got.mb_index, got.tp_index,
+                                  got.pools, got.pools_b, objective)
+    assert e.mask == 0 and e.peak_mem == got.peak_mem_bytes
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+@pytest.mark.parametrize("seed", [51, 52, 53, 54])
+def test_split_search_on_tiny_problems(torch_cuda, seed, objective):
+    prob = _tiny(seed, n_layers=3 if seed % 2 else 4, n_types=2, n_zones=2 + (seed == 54), partitions_per_pp=1)
+    plan, orc = _plan(prob), Oracle(prob)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        exhaustive = orc.search_exhaustive(objective, allow_split=True) if seed != 54 else None
+        plain = orc.search_beam(1 << 20, objective)
+        for width in (1, 4, 64, 256):
+            got = plan.search(width, objective, allow_split=True, stream=stream)
+            check_same_split(got, orc.search_beam(width, objective, allow_split=True), objective, orc)
+            if got.exact and exhaustive is not None:
+                assert _key_of(got, objective) == pytest.approx(exhaustive.key, rel=1e-12)
+            if plain is not None:
+                inc = plain.key * (1 + 1e-9)
+                check_same_split(plan.search(width, objective, allow_split=True, incumbent=inc, stream=stream),
+                                 orc.search_beam(width, objective, allow_split=True, incumbent=inc), objective, orc)
+            check_same_split(plan.search(width, objective, allow_split=True, max_runs=2, stream=stream),
+                             orc.search_beam(width, objective, allow_split=True, max_runs=2), objective, orc)
+        if plain is not None:
+            wb = plain.cost if objective == MAX_THROUGHPUT else 1.0 / plain.iter_time
+            bound = wb * (0.9 if objective == MAX_THROUGHPUT else 1.1) * (1 + 1e-7)
+            check_same_split(plan.search(32, objective, bound=bound, allow_split=True, stream=stream),
+                             orc.search_beam(32, objective, bound, allow_split=True), objective, orc)
+    finally:
+        plan.destroy()
+
+
+def test_split_search_where_one_zone_is_too_small(torch_cuda):
+    bw = np.array([[1e10, 5e9], [6e9, 1e10]])
+    p = make_problem(n_layers=2, n_types=1, n_zones=2, mb_list=(1,), tp_list=(1,), dp_list=(2, 4), pp_list=[1],
+                     global_batch=8, layer_params=1_000_000, bw=bw, avail=3)
+    plan, orc = _plan(p), Oracle(p)
+    try:
+        got = plan.search(64, allow_split=True)
+        check_same_split(got, orc.search_beam(64, allow_split=True), MAX_THROUGHPUT, orc)
+        assert got.dp == 4 and sorted((got.pools[0], got.pools_b[0])) == [0, 1]
+        assert got.iter_time_s < plan.search(64).iter_time_s
+    finally:
+        plan.destroy()
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+def test_third_workload_sized_split_search(torch_cuda, objective):
+    # 144 choices per stage, up to 32 stages: the device and the oracle walk the same frontiers
+    prob = W.config3()
+    plan, orc = _plan(prob), Oracle(prob)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        flat = plan.best_plan(objective=objective, stream=stream)
+        inc = (flat.iter_time_s if objective == MAX_THROUGHPUT else flat.cost_per_iter) * (1 + 1e-9)
+        got = plan.search(12, objective, incumbent=inc, allow_split=True, stream=stream)
+        want = orc.search_beam(12, objective, incumbent=inc, allow_split=True)
+        check_same_split(got, want, objective, orc)
+        unsplit = plan.search(12, objective, incumbent=inc, stream=stream)
+        assert _key_of(got, objective) <= inc
+        assert unsplit.found and _key_of(unsplit, objective) <= inc
+    finally:
+        plan.destroy()
