@@ -217,7 +217,12 @@ sailor_status sailor_plan_set_avail(sailor_plan *plan, const int32_t *avail);
  * only if one differs.  The other pieces contribute their kept minima.  Results are identical
  * to a full evaluation.  (sailor_plan_last_scan copies a small per-piece table from the device
  * and waits for it.)
- * on = 1 (default) / 0: off, every call evaluates the whole space. */
+ * on = 0 (default): every call evaluates the whole space; on = 1: minima are kept and reused.
+ * What it buys depends on the stream: the pieces whose validity changes are mostly the ones
+ * that hold many valid plans, and those set the duration of a pass over the space, while a
+ * pass that reuses minima needs one more small kernel to list the pieces near the minimum;
+ * on the synthetic streams measured here it shortens the pass by a third and the call not at
+ * all. */
 sailor_status sailor_plan_set_incremental(sailor_plan *plan, int32_t on);
 
 /* Pieces of the space the last successful sailor_best_plan / sailor_topk evaluated, and how

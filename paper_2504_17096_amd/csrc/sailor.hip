@@ -147,7 +147,7 @@ struct sailor_plan {
   uint32_t last_scan_seq = 0;     // call_seq of the last successful selection's scan
   uint32_t ubits_stride = 0;
   uint32_t avail_gen = 1;         // bumped whenever a new availability table reaches the device
-  bool incremental = true;        // sailor_plan_set_incremental
+  bool incremental = false;       // sailor_plan_set_incremental
   bool cache_ok = false;          // the minima on the device belong to the query below
   int cache_obj = 0, cache_hasb = 0;
   float cache_lim_s = 0.f, cache_lim_l = 0.f;
@@ -649,14 +649,27 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
     // minimum (a superset: see ScanArgs), so the collect pass visits a handful of units
     // instead of asking every unit's workgroups
     sa.band = (float)(1.0 + kTieTol) + 3.0f * kEvalEps;
-    sa.near_list = pl->ulist;
-    sa.near_band = sa.band;
+    // (not when minima are reused: units that are not evaluated again report at once, before
+    // any running minimum exists, and nearly all of them would be listed)
+    if (!sa.incremental) {
+      sa.near_list = pl->ulist;
+      sa.near_band = sa.band;
+    }
   }
   launch_units<MODE_SCAN>(pl, obj, has_bound, sa, st, t_scan ? pl->ev[3] : nullptr,
                           t_scan ? pl->ev[1] : nullptr);
+  const bool listed_by_scan = sa.near_list != nullptr;
   sa.near_list = nullptr;
-  if (best) {
+  if (best && listed_by_scan) {
     sa.tau_src = cnt + CNT_GMIN;
+    sa.ulist = pl->ulist;
+    sa.n_sub = kListSub;
+  } else if (best) {
+    // the smallest strict unit minimum is the scan's minimum; the same kernel lists the units
+    // whose loose minimum lies within the tie band of it
+    k_select_kth<1024><<<1, 1024, 0, st>>>(pl->umin_s, 1, nullptr, n_units, 1u, cnt + CNT_TAU0,
+                                     pl->umin_l, n_units, sa.band, pl->ulist, cnt + CNT_NLIST);
+    sa.tau_src = cnt + CNT_TAU0;
     sa.ulist = pl->ulist;
     sa.n_sub = kListSub;
   } else {
