@@ -450,9 +450,11 @@ def main() -> int:
     search = {"cfg3": searched(prob5, 64, False), "cfg4": searched(prob, 64, False),
               "cfg3_split": searched(prob5, 32, True), "cfg4_split": searched(prob, 16, True)}
 
-    # measured ceilings: scalar-per-lane FMA chain, streaming 16-byte stores
+    # measured ceilings: scalar-per-lane FMA chain, streaming 16-byte stores, and the four
+    # output arrays of the per-candidate evaluation written by a kernel that does nothing else
     fma_tflops, _ = microbench.fma(stream=stream)
     write_gbps, _ = microbench.write(stream=stream)
+    records_gbps, _ = microbench.write_records(n, stream=stream)
 
     pbar = mean_pipeline_depth(prob)
     flops_per_cand = FLOPS_PER_STAGE * pbar + FLOPS_EPILOGUE
@@ -474,6 +476,8 @@ def main() -> int:
                  "traffic": eval_entry.get("hbm_bytes") if eval_entry else None,
                  "kernel_ms": eval_ms, "measured_stream_write_GBps": write_gbps,
                  "frac_of_measured_write": 20.0 * n / (eval_ms * 1e-3) / 1e9 / write_gbps,
+                 "measured_output_write_GBps": records_gbps,
+                 "frac_of_measured_output_write": 20.0 * n / (eval_ms * 1e-3) / 1e9 / records_gbps,
                  "valu_insts_per_candidate": (eval_entry["counters"]["SQ_INSTS_VALU"] * 64 / n
                                               if eval_entry else None)}
     out = {

@@ -1716,7 +1716,9 @@ struct PoolInfo {   // per pool, staged in LDS (a pair of types: the tighter of 
   int64_t room;     // capacity - reserved (the smaller; negative when nothing fits)
   int32_t avail;    // GPUs available (plain types only)
   uint32_t meta;    // zone | (bit 8 + k: tp k exceeds the node size) (H1)
+  uint64_t pad;     // (32 bytes: the index is a shift)
 };
+static_assert(sizeof(PoolInfo) == 32, "one pool per 32 bytes of LDS");
 
 // 24-bit multiply (full rate, unlike the 32-bit one): every product below is a table offset
 __device__ __forceinline__ uint32_t mul24(uint32_t a, uint32_t b) { return __umul24(a, b); }
@@ -1921,6 +1923,7 @@ __global__ __launch_bounds__(512) void k_eval_rows(DevPlan pl, EvalArgs a, const
     pi.room = min((int64_t)pl.cap[ga] - (int64_t)pl.res[ga], (int64_t)pl.cap[gb] - (int64_t)pl.res[gb]);
     pi.avail = pl.mixed ? 0 : pl.avail[p];
     pi.meta = (uint32_t)(p / G) | (pl.h1m[p] << 8);
+    pi.pad = 0;
     pinfo[p] = pi;
     isect[2 * p] = pl.isect[2 * p];
     isect[2 * p + 1] = pl.isect[2 * p + 1];

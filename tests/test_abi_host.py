@@ -30,6 +30,16 @@ def test_exports_every_declared_entry_point(lib):
         assert getattr(lib, name) is not None
 
 
+def test_microbenchmark_library_exports_what_its_header_declares(lib):
+    from paper_2504_17096_amd import microbench
+    header = open(os.path.join(ROOT, "include", "sailor_microbench.h")).read()
+    declared = set(re.findall(r"int\s+(sailor_microbench_\w+)\s*\(", header))
+    assert declared == set(microbench.EXPORTS) and len(declared) == 3
+    mlib = microbench.load_library()
+    for name in declared:
+        assert getattr(mlib, name) is not None
+
+
 def test_struct_layouts_match_the_header(tmp_path):
     """sizeof / offsetof as a C compiler sees the header against the ctypes mirrors."""
     fields = {"sailor_problem": ["n_layers", "per_segment_tp", "n_bw_coef", "mixed_types", "global_batch", "mb_values",

@@ -225,6 +225,34 @@ def test_eval_batch_whole_space(case, torch_cuda, objective):
         assert_eval_parity(got_b, want_b, objective, bound)
 
 
+def test_eval_batch_in_pieces_returns_the_same_bits(case, torch_cuda):
+    # a range is cut into units at fixed places of the index space and clipped where it begins
+    # and ends inside one: however a range is cut into pieces, the pieces hold the bits of the whole
+    prob, plan, orc = case
+    n = orc.num_candidates
+    rng = np.random.default_rng(11)
+    ok = orc.eval_batch()[3] == 0
+    bound = None
+    if ok.any():
+        bound = off_data(float(np.median(orc.eval_batch()[1][ok])))
+    whole = gpu_eval(torch_cuda, plan, 0, n, bound=bound)
+    inner = (prob.n_zones * (prob.n_types if not prob.mixed_types else
+                             prob.n_types + prob.n_types * (prob.n_types - 1) // 2)
+             * len(prob.mb_values) * len(prob.tp_values) * len(prob.dp_values))
+    for piece in (inner - 1, max(inner // 3, 1), int(rng.integers(2 * inner, 9 * inner))):
+        piece = max(piece, n // 300)  # (keeps the number of calls of the larger spaces bounded)
+        parts = [gpu_eval(torch_cuda, plan, lo, min(piece, n - lo), bound=bound) for lo in range(0, n, piece)]
+        for w, *ps in zip(whole, *parts):
+            assert np.array_equal(w, np.concatenate(ps)), piece
+    # ragged ends around whole shapes
+    for _ in range(8):
+        lo = int(rng.integers(0, n - 1))
+        cnt = int(rng.integers(1, n - lo + 1))
+        part = gpu_eval(torch_cuda, plan, lo, cnt, bound=bound)
+        for w, q in zip(whole, part):
+            assert np.array_equal(w[lo:lo + cnt], q), (lo, cnt)
+
+
 def test_eval_batch_ragged_ranges_and_index_lists(case, torch_cuda):
     prob, plan, orc = case
     n = orc.num_candidates
