@@ -94,12 +94,12 @@ class _SearchResult(C.Structure):
                 ("partition", C.c_int32), ("tp_idx", C.c_int32), ("dp_idx", C.c_int32),
                 ("mb_idx", C.c_int32), ("pp", C.c_int32), ("expanded", C.c_uint64),
                 ("key", C.c_double), ("iter_time", C.c_double), ("cost", C.c_double),
-                ("pools", C.c_int32 * 256), ("pools_b", C.c_int32 * 256)]
+                ("pools", C.c_int32 * 256), ("pools_b", C.c_int32 * 256), ("tps", C.c_int32 * 256)]
 
 
 class _SearchOpts(C.Structure):
     _fields_ = [("beam_width", C.c_int32), ("max_runs", C.c_int32), ("has_incumbent", C.c_int32),
-                ("incumbent", C.c_double), ("allow_split", C.c_int32)]
+                ("incumbent", C.c_double), ("allow_split", C.c_int32), ("stage_tp", C.c_int32)]
 
 
 @dataclass
@@ -117,6 +117,7 @@ class StagePlan:
     truncated: bool = False
     expanded: int = 0
     pools_b: tuple = ()
+    tps: tuple = ()      # index of every stage's TP degree
 
 
 @dataclass
@@ -160,8 +161,13 @@ def _load():
         lib.so_eval_split_assignment.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                                  C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_double,
                                                  C.POINTER(_Eval)]
+        lib.so_eval_assignment_tp.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                              C.c_void_p, C.c_int, C.c_int, C.c_double, C.POINTER(_Eval)]
         lib.so_search_exhaustive.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, C.c_int, C.c_int,
-                                             C.POINTER(_SearchResult)]
+                                             C.c_int, C.POINTER(_SearchResult)]
+        lib.so_search_prefix_bound_tp.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                                  C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_double),
+                                                  C.POINTER(C.c_double)]
         lib.so_search_beam.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, C.POINTER(_SearchOpts),
                                        C.POINTER(_SearchResult)]
         lib.so_search_prefix_bound.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
@@ -176,7 +182,7 @@ def _stage_plan(r: _SearchResult) -> Optional[StagePlan]:
         return None
     return StagePlan(r.pp_idx, r.partition, r.tp_idx, r.dp_idx, r.mb_idx, tuple(r.pools[:r.pp]),
                      r.key, r.iter_time, r.cost, bool(r.truncated), int(r.expanded),
-                     tuple(r.pools_b[:r.pp]))
+                     tuple(r.pools_b[:r.pp]), tuple(r.tps[:r.pp]))
 
 
 def _cfg(c: _Config) -> Config:
@@ -335,6 +341,20 @@ class Oracle:
             raise ValueError("assignment out of range")
         return _ev(e)
 
+    def eval_assignment_tp(self, pp_idx: int, partition: int, dp_idx: int, mb_idx: int, tps, pools,
+                           objective: int = MAX_THROUGHPUT, bound: Optional[float] = None) -> Eval:
+        """A plan with a pool and a TP index per stage."""
+        a = np.ascontiguousarray(pools, dtype=np.int32)
+        t = np.ascontiguousarray(tps, dtype=np.int32)
+        assert len(a) == len(t)
+        e = _Eval()
+        rc = self._lib.so_eval_assignment_tp(self._ctx, pp_idx, partition, dp_idx, mb_idx, t.ctypes.data,
+                                             a.ctypes.data, objective, bound is not None,
+                                             0.0 if bound is None else bound, C.byref(e))
+        if rc != 0:
+            raise ValueError("assignment out of range")
+        return _ev(e)
+
     def eval_split_assignment(self, pp_idx: int, partition: int, dp_idx: int, mb_idx: int, tp_idx: int,
                               pools_a, pools_b, objective: int = MAX_THROUGHPUT,
                               bound: Optional[float] = None) -> Eval:
@@ -350,21 +370,24 @@ class Oracle:
         return _ev(e)
 
     def search_exhaustive(self, objective: int = MAX_THROUGHPUT, bound: Optional[float] = None,
-                          max_runs: int = 0, allow_split: bool = False) -> Optional[StagePlan]:
+                          max_runs: int = 0, allow_split: bool = False,
+                          stage_tp: bool = False) -> Optional[StagePlan]:
         r = _SearchResult()
         rc = self._lib.so_search_exhaustive(self._ctx, objective, bound is not None,
                                             0.0 if bound is None else bound, max_runs,
-                                            1 if allow_split else 0, C.byref(r))
+                                            1 if allow_split else 0, 1 if stage_tp else 0, C.byref(r))
         if rc != 0:
             raise ValueError("the search does not cover this problem")
         return _stage_plan(r)
 
     def search_beam(self, beam_width: int, objective: int = MAX_THROUGHPUT,
                     bound: Optional[float] = None, max_runs: int = 0,
-                    incumbent: Optional[float] = None, allow_split: bool = False) -> Optional[StagePlan]:
+                    incumbent: Optional[float] = None, allow_split: bool = False,
+                    stage_tp: bool = False) -> Optional[StagePlan]:
         r = _SearchResult()
         o = _SearchOpts(beam_width, max_runs, incumbent is not None,
-                        0.0 if incumbent is None else incumbent, 1 if allow_split else 0)
+                        0.0 if incumbent is None else incumbent, 1 if allow_split else 0,
+                        1 if stage_tp else 0)
         rc = self._lib.so_search_beam(self._ctx, objective, bound is not None,
                                       0.0 if bound is None else bound, C.byref(o), C.byref(r))
         if rc != 0:
@@ -380,6 +403,16 @@ class Oracle:
         t, c = C.c_double(), C.c_double()
         rc = self._lib.so_search_prefix_bound(self._ctx, pp_idx, partition, dp_idx, mb_idx, tp_idx,
                                               a.ctypes.data, n_placed, objective, C.byref(t), C.byref(c))
+        return None if rc != 0 else (t.value, c.value)
+
+    def prefix_bound_tp(self, pp_idx: int, partition: int, dp_idx: int, mb_idx: int, tps, pools,
+                        n_placed: int, objective: int = MAX_THROUGHPUT):
+        """prefix_bound for a placement with a TP index per stage."""
+        a = np.ascontiguousarray(pools, dtype=np.int32)
+        tt = np.ascontiguousarray(tps, dtype=np.int32)
+        t, c = C.c_double(), C.c_double()
+        rc = self._lib.so_search_prefix_bound_tp(self._ctx, pp_idx, partition, dp_idx, mb_idx, tt.ctypes.data,
+                                                 a.ctypes.data, n_placed, objective, C.byref(t), C.byref(c))
         return None if rc != 0 else (t.value, c.value)
 
     def best(self, objective: int = MAX_THROUGHPUT, bound: Optional[float] = None,

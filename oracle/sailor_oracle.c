@@ -446,21 +446,20 @@ static void eval_config(const so_ctx *c, const so_config *g, uint64_t index, int
 /* A plan whose stages choose their pools freely (the plan tuple of Sec. 4.2 without the
  * contiguous-segment restriction of the flat space): pools[i] = zone * G' + extended type of
  * stage i, one TP degree for all stages.  Returns 0, -1 for a value out of range. */
-int so_eval_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx, int tp_idx,
-                       const int32_t *pools, int objective, int has_bound, double bound,
-                       so_eval *out) {
+int so_eval_assignment_tp(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                          const int32_t *tp_idx, const int32_t *pools, int objective, int has_bound,
+                          double bound, so_eval *out) {
   const so_problem *p = &c->p;
   if (pp_idx < 0 || pp_idx >= p->n_pp || dp_idx < 0 || dp_idx >= p->n_dp || mb_idx < 0 ||
-      mb_idx >= p->n_mb || tp_idx < 0 || tp_idx >= p->n_tp || partition < 0 ||
-      partition >= p->n_partitions[pp_idx])
+      mb_idx >= p->n_mb || partition < 0 || partition >= p->n_partitions[pp_idx])
     return -1;
   const int P = p->pp_values[pp_idx];
   int pool_of[SO_MAX_STAGES], tp_of[SO_MAX_STAGES], tpi_of[SO_MAX_STAGES];
   for (int i = 0; i < P; ++i) {
-    if (pools[i] < 0 || pools[i] >= c->ZG) return -1;
+    if (pools[i] < 0 || pools[i] >= c->ZG || tp_idx[i] < 0 || tp_idx[i] >= p->n_tp) return -1;
     pool_of[i] = pools[i];
-    tp_of[i] = p->tp_values[tp_idx];
-    tpi_of[i] = tp_idx;
+    tp_of[i] = p->tp_values[tp_idx[i]];
+    tpi_of[i] = tp_idx[i];
   }
   so_config g;
   memset(&g, 0, sizeof g);
@@ -470,6 +469,15 @@ int so_eval_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, i
   eval_stages(c, P, partition_row(c, &g), pool_of, tp_of, tpi_of, p->dp_values[dp_idx],
               p->mb_values[mb_idx], mb_idx, 0, objective, has_bound, bound, out);
   return 0;
+}
+
+int so_eval_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx, int tp_idx,
+                       const int32_t *pools, int objective, int has_bound, double bound,
+                       so_eval *out) {
+  int32_t tps[SO_MAX_STAGES];
+  for (int i = 0; i < SO_MAX_STAGES; ++i) tps[i] = tp_idx;
+  return so_eval_assignment_tp(c, pp_idx, partition, dp_idx, mb_idx, tps, pools, objective, has_bound,
+                               bound, out);
 }
 
 /* A plan whose stages may split their D replicas over two pools, half on each -- pools of

@@ -149,6 +149,13 @@ int so_eval_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, i
                        so_eval *out);
 const so_problem *so_problem_of(const so_ctx *c);
 
+/* The same with a TP degree per stage (tp_ij of Sec. 4.2.2 taken per stage): tp_idx[i] = index
+ * of stage i's degree in tp_values.  A stage's memory shard, activation bytes, profiled times,
+ * node-size check, gradient shard, GPUs against its pool's quota and rent use its own degree. */
+int so_eval_assignment_tp(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                          const int32_t *tp_idx, const int32_t *pools, int objective, int has_bound,
+                          double bound, so_eval *out);
+
 /* The same with stages that may split their replicas over two pools, also of different zones:
  * pools_a[i] / pools_b[i] (equal = not split), half of the D replicas on each.  T_iter takes
  * the slower of the two kinds of pipeline (Sec. 4.3: max over pipelines), a split stage's
@@ -167,6 +174,8 @@ typedef struct {
   int32_t pools[SO_SEARCH_MAX_STAGES];
   int32_t pools_b[SO_SEARCH_MAX_STAGES]; /* pool of the other half of a stage's replicas (= pools[i]
                                             when the stage is not split) */
+  int32_t tps[SO_SEARCH_MAX_STAGES];     /* index of every stage's TP degree (= tp_idx unless the
+                                            stages choose their own) */
 } so_search_result;
 
 typedef struct {
@@ -177,18 +186,24 @@ typedef struct {
   int32_t allow_split;           /* 1: a stage may put half of its replicas on a second pool, also
                                     of another zone (so_eval_split_assignment); a stage then has
                                     (pools)^2 choices (a, b), numbered a * pools + b */
+  int32_t stage_tp;              /* 1: every stage chooses its TP degree too (so_eval_assignment_tp);
+                                    a stage has pools x n_tp choices (a, t), numbered a * n_tp + t,
+                                    and TP leaves the sub-problem.  Not together with allow_split */
 } so_search_opts;
 
 /* (sailor_search_oracle.c) sub-problems in the order pp, layer split, TP, D, microbatch size;
  * equal keys: the first sub-problem, inside it the first placement found.  0 ok, -1 when the
  * problem uses an option the search does not cover. */
 int so_search_exhaustive(const so_ctx *c, int objective, int has_bound, double bound, int max_runs,
-                         int allow_split, so_search_result *out);
+                         int allow_split, int stage_tp, so_search_result *out);
 int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
                    const so_search_opts *opt, so_search_result *out);
 int so_search_prefix_bound(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
                            int tp_idx, const int32_t *pools, int n_placed, int objective,
                            double *lb_time, double *lb_cost);
+int so_search_prefix_bound_tp(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                              const int32_t *tp_idx, const int32_t *pools, int n_placed, int objective,
+                              double *lb_time, double *lb_cost);
 
 #ifdef __cplusplus
 }

@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SOURCES = ("sailor_oracle.c", "sailor_search_oracle.c", "sailor_oracle.h")
 
 MUTANTS = [
-    # (pin file, text in oracle/sailor_oracle.c, replacement)
+    # (pin file, text in the oracle's source, replacement[, source file if not the default])
     ("test_oracle_simulator.py", "(double)(Nb - 1) * max_t", "(double)(Nb) * max_t"),
     ("test_oracle_simulator.py", "2.0 * (double)(D - 1) / (double)D * grad_bytes",
      "2.0 * (double)(D) / (double)D * grad_bytes"),
@@ -48,14 +48,23 @@ MUTANTS = [
      "if (a->key < b->key) return 1;\n  if (a->key > b->key) return -1;"),
     ("test_oracle_search.py", "s->Smax[i] = fmax(s->Smax[i + 1], cmin[i + 1]);",
      "s->Smax[i] = fmax(s->Smax[i + 1], cmin[i]);"),
+    # a TP degree per stage: the quota counted in stages instead of GPUs, the rent of the first
+    # degree, runs that ignore the degree, every stage evaluated at the first stage's degree
+    ("test_oracle_search.py", "par->cnt[a] + s->tpv[t] > s->cap_gpus[a]", "par->cnt[a] + 1 > s->cap_gpus[a]"),
+    ("test_oracle_search.py", "st->dol = par->dol + s->dol3[g][t];", "st->dol = par->dol + s->dol3[g][0];"),
+    ("test_oracle_search.py", "(a != par->pool || t != par->tpi) ? 1 : 0", "(a != par->pool) ? 1 : 0"),
+    ("test_oracle_search.py", "tp_of[i] = p->tp_values[tp_idx[i]];", "tp_of[i] = p->tp_values[tp_idx[0]];",
+     "sailor_oracle.c"),
 ]
 
 
-@pytest.mark.parametrize("pins,old,new", MUTANTS, ids=[f"{m[0][12:-3]}-{i}" for i, m in enumerate(MUTANTS)])
-def test_a_planted_mistake_fails_its_pins(tmp_path, pins, old, new):
+@pytest.mark.parametrize("mutant", MUTANTS, ids=[f"{m[0][12:-3]}-{i}" for i, m in enumerate(MUTANTS)])
+def test_a_planted_mistake_fails_its_pins(tmp_path, mutant):
+    pins, old, new = mutant[:3]
     for f in SOURCES:
         shutil.copy(os.path.join(ROOT, "oracle", f), tmp_path / f)
-    target = "sailor_search_oracle.c" if pins == "test_oracle_search.py" else "sailor_oracle.c"
+    target = mutant[3] if len(mutant) > 3 else (
+        "sailor_search_oracle.c" if pins == "test_oracle_search.py" else "sailor_oracle.c")
     src = (tmp_path / target).read_text()
     assert src.count(old) == 1, "the mutation no longer matches the oracle's source"
     (tmp_path / target).write_text(src.replace(old, new))
