@@ -431,15 +431,18 @@ def main() -> int:
 
     # search over per-stage placements (spaces that cannot be enumerated: 12^32 and 20^48
     # placements per sub-problem), incumbent = the flat space's best plan through the evaluator
-    def searched(problem, width, split):
+    def searched(problem, width, split, stage_tp=False):
         p = Plan(problem)
         p.set_incremental(False)
         flat = p.best_plan(objective=MAX_THROUGHPUT, stream=stream)
-        p.search(width, MAX_THROUGHPUT, incumbent="flat", allow_split=split, stream=stream)  # (allocates its scratch)
+        kw = dict(incumbent="flat", allow_split=split, stage_tp=stage_tp, stream=stream)
+        p.search(width, MAX_THROUGHPUT, **kw)  # (allocates its scratch)
         t0 = time.perf_counter()
-        r = p.search(width, MAX_THROUGHPUT, incumbent="flat", allow_split=split, stream=stream)
+        r = p.search(width, MAX_THROUGHPUT, **kw)
         ms = (time.perf_counter() - t0) * 1e3
-        out = {"beam_width": width, "split_stages": split, "ms_incl_flat_best_plan": ms,
+        out = {"beam_width": width, "split_stages": split, "tp_per_stage": stage_tp,
+               "tp_degrees_used": sorted({int(problem.tp_values[t]) for t in r.tps}),
+               "ms_incl_flat_best_plan": ms,
                "placements_generated": r.expanded, "exact": r.exact, "flat_iter_time_s": flat.iter_time_s,
                "search_iter_time_s": r.iter_time_s, "pp": r.pp,
                "runs_of_pools": 1 + sum(a != b for a, b in zip(zip(r.pools, r.pools_b), zip(r.pools[1:], r.pools_b[1:]))),
@@ -448,7 +451,8 @@ def main() -> int:
         return out
 
     search = {"cfg3": searched(prob5, 64, False), "cfg4": searched(prob, 64, False),
-              "cfg3_split": searched(prob5, 32, True), "cfg4_split": searched(prob, 16, True)}
+              "cfg3_split": searched(prob5, 32, True), "cfg4_split": searched(prob, 16, True),
+              "cfg3_stage_tp": searched(prob5, 64, False, True), "cfg4_stage_tp": searched(prob, 32, False, True)}
 
     # measured ceilings: scalar-per-lane FMA chain, streaming 16-byte stores, and the four
     # output arrays of the per-candidate evaluation written by a kernel that does nothing else

@@ -345,7 +345,11 @@ typedef struct {
   double incumbent;       /* placements whose bound exceeds it are dropped, complete plans too */
   int32_t allow_split;    /* 1: a stage may put half of its D replicas on a second pool, also of
                              another zone (see sailor_eval_placements); a stage then has
-                             (pools)^2 choices (a, b).  Pipelines of at most 127 stages */
+                             (pools)^2 choices (a, b) */
+  int32_t stage_tp;       /* 1: every stage chooses its TP degree too (tp_ij of Sec. 4.2.2, taken
+                             per stage): a stage has pools x n_tp choices, TP is no longer part
+                             of the sub-problem, a pool's quota counts the GPUs of one replica.
+                             Not together with allow_split */
 } sailor_search_options;
 
 /* A plan with one pool per stage (plan tuple of Sec. 4.2). */
@@ -364,6 +368,9 @@ typedef struct {
   int32_t pool[SAILOR_MAX_STAGES]; /* zone * n_types + type of every stage; unused entries -1 */
   int32_t pool_b[SAILOR_MAX_STAGES]; /* pool of the other half of the stage's replicas (= pool[i]
                                         unless the stage is split) */
+  int32_t stage_tp_index[SAILOR_MAX_STAGES]; /* index of every stage's TP degree (= tp_index unless
+                                        the stages choose their own; then tp / tp_index are
+                                        stage 0's) */
 } sailor_stage_plan;
 
 /* Search on top of the evaluator for spaces too large to enumerate (Sec. 4.2.2: resources are
@@ -381,7 +388,9 @@ typedef struct {
  * size.  All arithmetic is fp64 in stage order, so the reported values are those of the plan.
  * With allow_split the two halves of the replicas form two kinds of pipeline, kept apart in the
  * bounds (the slower counts, Sec. 4.3), and the D tuples of a stage (Sec. 4.2) may lie in two
- * zones; unsplit stages cost what they cost without the option.
+ * zones; unsplit stages cost what they cost without the option.  With stage_tp a run of the run
+ * limit ends where the pool or the degree changes, and "cheapest admissible choice" runs over the
+ * (type, TP) pairs that fit.
  * Not for problems with per_segment_tp, mixed_types or bw_poly, more than 64 pools or 255
  * stages (SAILOR_EINVAL).  Waits for the device.  SAILOR_ENOFEASIBLE (out->found = 0, exact and
  * expanded still set) when no valid plan is found. */
@@ -403,13 +412,17 @@ sailor_status sailor_search(sailor_plan *plan, sailor_objective objective,
  *             for: the pipelines' (each kind carries D / 2 replicas) and the ring's two
  *             crossings of 2 (D - 1) / D x gradient bytes; memory and node size hold for both
  *             halves, quotas count halves, an odd D with a split stage is OVER_QUOTA
+ *   d_tps     device, same shape, or NULL.  Given, stage i runs at TP degree tp_values[d_tps[..][i]]
+ *             instead of the descriptor's: its memory shard, activation bytes, profiled times,
+ *             node-size check, gradient shard, GPUs against its pool's quota and rent use it
+ *             (tp_ij of Sec. 4.2.2).  Not together with d_pools_b (SAILOR_EINVAL)
  *   outputs   device, [count], any may be NULL
- * A descriptor or pool out of range yields mask = 0xFFFFFFFF, time = cost = +inf, mem = 0; a
+ * A descriptor, pool or TP index out of range yields mask = 0xFFFFFFFF, time = cost = +inf, mem = 0; a
  * batch that does not divide mask = BATCH_INDIVISIBLE with +inf and 0.  Asynchronous on
  * hip_stream.  SAILOR_EINVAL for per_segment_tp / mixed_types problems or more than 64 pools. */
 sailor_status sailor_eval_placements(sailor_plan *plan, uint64_t count, const int32_t *d_desc,
                                      const int32_t *d_pools, const int32_t *d_pools_b,
-                                     uint32_t pool_stride,
+                                     const int32_t *d_tps, uint32_t pool_stride,
                                      sailor_objective objective,
                                      const sailor_constraint *constraint, double *d_time,
                                      double *d_cost, uint64_t *d_mem, uint32_t *d_mask,

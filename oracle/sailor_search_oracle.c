@@ -533,7 +533,7 @@ int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
   ss_order *ord = (ss_order *)malloc(sizeof(ss_order) * cap * (size_t)NCH);
   if (!s || !cur || !all || !ord) { free(s); free(cur); free(all); free(ord); return -1; }
   for (int ip = 0; ip < p->n_pp; ++ip) {
-    if (p->pp_values[ip] > (split ? 127 : SS_MAX_STAGES)) continue; /* halves are counted in a byte */
+    if (p->pp_values[ip] > SS_MAX_STAGES) continue;
     for (int q = 0; q < p->n_partitions[ip]; ++q)
       for (int it = 0; it < (stp ? 1 : p->n_tp); ++it)
         for (int id = 0; id < p->n_dp; ++id)

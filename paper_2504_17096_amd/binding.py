@@ -83,7 +83,7 @@ MAX_STAGES = 256
 
 class sailor_search_options(C.Structure):
     _fields_ = [("beam_width", C.c_int32), ("max_runs", C.c_int32), ("use_incumbent", C.c_int32),
-                ("incumbent", C.c_double), ("allow_split", C.c_int32)]
+                ("incumbent", C.c_double), ("allow_split", C.c_int32), ("stage_tp", C.c_int32)]
 
 
 class sailor_stage_plan(C.Structure):
@@ -95,7 +95,8 @@ class sailor_stage_plan(C.Structure):
                 ("iter_time_s", C.c_double), ("cost_per_iter", C.c_double),
                 ("eval_time_s", C.c_double), ("eval_cost", C.c_double),
                 ("expanded", C.c_uint64), ("incumbent_used", C.c_int32), ("incumbent", C.c_double),
-                ("pool", C.c_int32 * MAX_STAGES), ("pool_b", C.c_int32 * MAX_STAGES)]
+                ("pool", C.c_int32 * MAX_STAGES), ("pool_b", C.c_int32 * MAX_STAGES),
+                ("stage_tp_index", C.c_int32 * MAX_STAGES)]
 
 
 @dataclass
@@ -122,6 +123,7 @@ class StagePlan:
     incumbent: Optional[float]
     pools: Tuple[int, ...]
     pools_b: Tuple[int, ...] = ()
+    tps: Tuple[int, ...] = ()      # index of every stage's TP degree
 
 
 @dataclass
@@ -191,7 +193,7 @@ def load_library() -> C.CDLL:
     lib.sailor_set_scan_unit_parts.argtypes = [C.c_int32]
     lib.sailor_search.argtypes = [P, C.c_int, C.POINTER(sailor_constraint),
                                   C.POINTER(sailor_search_options), C.POINTER(sailor_stage_plan), P]
-    lib.sailor_eval_placements.argtypes = [P, C.c_uint64, P, P, P, C.c_uint32, C.c_int,
+    lib.sailor_eval_placements.argtypes = [P, C.c_uint64, P, P, P, P, C.c_uint32, C.c_int,
                                            C.POINTER(sailor_constraint), P, P, P, P, P]
     lib.sailor_plan_last_counts.argtypes = [P, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                             C.POINTER(C.c_uint32)]
@@ -383,10 +385,12 @@ class Plan:
         return a.value, b.value, c.value
 
     def search(self, beam_width: int, objective: int = MAX_THROUGHPUT, bound: Optional[float] = None,
-               max_runs: int = 0, incumbent=None, stream: int = 0, allow_split: bool = False) -> StagePlan:
+               max_runs: int = 0, incumbent=None, stream: int = 0, allow_split: bool = False,
+               stage_tp: bool = False) -> StagePlan:
         """sailor_search.  incumbent: None, a float, or "flat" (the library takes the best plan
         of the flat space).  The returned plan has found = False when nothing valid exists."""
-        o = sailor_search_options(beam_width, max_runs, 0, 0.0, 1 if allow_split else 0)
+        o = sailor_search_options(beam_width, max_runs, 0, 0.0, 1 if allow_split else 0,
+                                  1 if stage_tp else 0)
         if incumbent == "flat":
             o.use_incumbent = 2
         elif incumbent is not None:
@@ -400,16 +404,17 @@ class Plan:
                          r.dp_index, r.mb_index, r.partition, r.mask, r.peak_mem_bytes, r.iter_time_s,
                          r.cost_per_iter, r.eval_time_s, r.eval_cost, r.expanded,
                          r.incumbent if r.incumbent_used else None, tuple(r.pool[:r.pp]),
-                         tuple(r.pool_b[:r.pp]))
+                         tuple(r.pool_b[:r.pp]), tuple(r.stage_tp_index[:r.pp]))
 
     def eval_placements(self, count: int, d_desc, d_pools, pool_stride: int,
                         objective: int = MAX_THROUGHPUT, bound: Optional[float] = None, d_time=None,
-                        d_cost=None, d_mem=None, d_mask=None, stream: int = 0, d_pools_b=None) -> None:
+                        d_cost=None, d_mem=None, d_mask=None, stream: int = 0, d_pools_b=None,
+                        d_tps=None) -> None:
         """sailor_eval_placements; device tensors: int32 [count][5], int32 [count][pool_stride]
-        (and optionally the pools of the other half of every stage's replicas),
-        float64 / float64 / int64 / int32 outputs."""
+        (and optionally the pools of the other half of every stage's replicas, or the TP index
+        of every stage), float64 / float64 / int64 / int32 outputs."""
         rc = self._lib.sailor_eval_placements(self._h, count, _ptr(d_desc), _ptr(d_pools),
-                                              _ptr(d_pools_b), pool_stride,
+                                              _ptr(d_pools_b), _ptr(d_tps), pool_stride,
                                               objective, _constraint(bound), _ptr(d_time), _ptr(d_cost),
                                               _ptr(d_mem), _ptr(d_mask), stream or None)
         if rc != SAILOR_OK:

@@ -155,7 +155,7 @@ struct sailor_plan {
   // search over per-stage placements: tables and scratch, created by the first call
   std::vector<SearchPP> search_pps;
   const SearchPP *d_search_pps = nullptr;
-  uint32_t n_sub = 0;
+  uint32_t n_sub = 0, n_sub_t = 0;  // sub-problems with TP in them / with a TP degree per stage
   uint8_t *search_states = nullptr;
   uint32_t search_wgs = 0, search_state_stride = 0, search_path_stride = 0;
   SubResult *search_results = nullptr, *search_final = nullptr;
@@ -1346,7 +1346,7 @@ sailor_status sailor_simulate_1f1b_static(sailor_plan *pl, uint64_t count, const
 static sailor_status search_setup(sailor_plan *pl, bool with_scratch) {
   if (!pl->d_search_pps) {
     pl->search_pps.clear();
-    uint32_t sub = 0;
+    uint32_t sub = 0, sub_t = 0;
     for (size_t ip = 0; ip < pl->ppv.size(); ++ip) {
       SearchPP e{};
       e.P = pl->ppv[ip];
@@ -1361,10 +1361,13 @@ static sailor_status search_setup(sailor_plan *pl, bool with_scratch) {
         }
       if (!seen) return SAILOR_EINVAL;  // (every depth has a one-segment block)
       e.sub_off = sub;
+      e.sub_off_t = sub_t;
       sub += (uint32_t)e.n_part * (uint32_t)(pl->dev.TP * pl->dev.DP * pl->dev.MB);
+      sub_t += (uint32_t)e.n_part * (uint32_t)(pl->dev.DP * pl->dev.MB);
       pl->search_pps.push_back(e);
     }
     pl->n_sub = sub;
+    pl->n_sub_t = sub_t;
     if (pl->arena.upload(&pl->d_search_pps, pl->search_pps.data(), pl->search_pps.size()) != hipSuccess)
       return SAILOR_ENOMEM;
   }
@@ -1384,13 +1387,13 @@ static sailor_status search_setup(sailor_plan *pl, bool with_scratch) {
 
 sailor_status sailor_eval_placements(sailor_plan *pl, uint64_t count, const int32_t *d_desc,
                                      const int32_t *d_pools, const int32_t *d_pools_b,
-                                     uint32_t pool_stride,
+                                     const int32_t *d_tps, uint32_t pool_stride,
                                      sailor_objective objective, const sailor_constraint *constraint,
                                      double *d_time, double *d_cost, uint64_t *d_mem, uint32_t *d_mask,
                                      void *hip_stream) {
   if (!pl || (objective != SAILOR_MAX_THROUGHPUT && objective != SAILOR_MIN_COST)) return SAILOR_EINVAL;
   if (count == 0) return SAILOR_OK;
-  if (!d_desc || !d_pools || pool_stride < 1) return SAILOR_EINVAL;
+  if (!d_desc || !d_pools || pool_stride < 1 || (d_pools_b && d_tps)) return SAILOR_EINVAL;
   if (pl->dev.mixed || pl->dev.pst || pl->dev.ZGr > kSearchMaxPools) return SAILOR_EINVAL;
   if (count > (uint64_t)0x7fffffff) return SAILOR_ERANGE;
   if (constraint && constraint->has_bound && std::isnan(constraint->bound)) return SAILOR_EINVAL;
@@ -1402,7 +1405,8 @@ sailor_status sailor_eval_placements(sailor_plan *pl, uint64_t count, const int3
   rc = refresh_avail(pl, st);
   if (rc != SAILOR_OK) return rc;
   PlaceArgs a{};
-  a.count = count; a.desc = d_desc; a.pools = d_pools; a.pools_b = d_pools_b; a.pool_stride = pool_stride;
+  a.count = count; a.desc = d_desc; a.pools = d_pools; a.pools_b = d_pools_b; a.tps = d_tps;
+  a.pool_stride = pool_stride;
   a.pps = pl->d_search_pps; a.n_pp = (int)pl->search_pps.size();
   a.objective = (int)objective;
   a.has_bound = (constraint && constraint->has_bound) ? 1 : 0;
@@ -1423,8 +1427,9 @@ sailor_status sailor_search(sailor_plan *pl, sailor_objective objective,
     return SAILOR_EINVAL;
   if (opt->use_incumbent == 1 && std::isnan(opt->incumbent)) return SAILOR_EINVAL;
   if (opt->allow_split != 0 && opt->allow_split != 1) return SAILOR_EINVAL;
-  if (opt->allow_split && pl->dev.P_max > 127) return SAILOR_EINVAL;  // halves of stages counted in a byte
-  // one TP degree and one pool per stage, constant link bandwidths, stages counted in a byte
+  if (opt->stage_tp != 0 && opt->stage_tp != 1) return SAILOR_EINVAL;
+  if (opt->allow_split && opt->stage_tp) return SAILOR_EINVAL;
+  // plain pools, constant link bandwidths, a pipeline's stages numbered in a byte
   if (pl->dev.mixed || pl->dev.pst || pl->dev.n_bw_coef > 0 || pl->dev.ZGr > kSearchMaxPools ||
       pl->dev.P_max > kSearchMaxStages)
     return SAILOR_EINVAL;
@@ -1462,14 +1467,16 @@ sailor_status sailor_search(sailor_plan *pl, sailor_objective objective,
   if (rc != SAILOR_OK) return rc;
   a.pps = pl->d_search_pps;
   a.n_pp = (int)pl->search_pps.size();
-  a.n_sub = pl->n_sub;
+  a.n_sub = opt->stage_tp ? pl->n_sub_t : pl->n_sub;
   a.states = pl->search_states;
   a.state_stride = pl->search_state_stride;
   a.path_stride = pl->search_path_stride;
   a.results = pl->search_results;
-  if (opt->allow_split) k_search_beam<true><<<pl->search_wgs, kSearchThreads, 0, st>>>(pl->dev, a);
-  else k_search_beam<false><<<pl->search_wgs, kSearchThreads, 0, st>>>(pl->dev, a);
-  k_search_pick<<<1, 256, 0, st>>>(pl->search_results, pl->n_sub, pl->search_final);
+  const unsigned wgs = std::min<uint32_t>(pl->search_wgs, a.n_sub);
+  if (opt->allow_split) k_search_beam<SEARCH_SPLIT><<<wgs, kSearchThreads, 0, st>>>(pl->dev, a);
+  else if (opt->stage_tp) k_search_beam<SEARCH_STAGE_TP><<<wgs, kSearchThreads, 0, st>>>(pl->dev, a);
+  else k_search_beam<SEARCH_PLAIN><<<wgs, kSearchThreads, 0, st>>>(pl->dev, a);
+  k_search_pick<<<1, 256, 0, st>>>(pl->search_results, a.n_sub, pl->search_final);
   // the winner once more through the simulator, for its memory footprint and its mask
   PlaceArgs pa{};
   pa.count = 1;
@@ -1491,7 +1498,7 @@ sailor_status sailor_search(sailor_plan *pl, sailor_objective objective,
   HIP_TRY(hipMemcpyAsync(ev, pl->search_eval, sizeof ev, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
   std::memset(out, 0, sizeof *out);
-  for (int i = 0; i < SAILOR_MAX_STAGES; ++i) out->pool[i] = out->pool_b[i] = -1;
+  for (int i = 0; i < SAILOR_MAX_STAGES; ++i) out->pool[i] = out->pool_b[i] = out->stage_tp_index[i] = -1;
   out->exact = fin.truncated ? 0 : 1;
   out->expanded = fin.expanded;
   out->incumbent_used = a.has_inc;
@@ -1516,6 +1523,7 @@ sailor_status sailor_search(sailor_plan *pl, sailor_objective objective,
   for (int i = 0; i < out->pp; ++i) {
     out->pool[i] = fin.pools[i];
     out->pool_b[i] = fin.pools_b[i];
+    out->stage_tp_index[i] = fin.tps[i];
   }
   return SAILOR_OK;
 }

@@ -11,6 +11,10 @@
 // an incumbent are dropped, and a frontier longer than the beam width keeps the smallest
 // bounds.  At the last level the bound is the plan's own T_iter / C_iter.
 //
+// Two wider forms of a stage's choice: half of its replicas on a second pool (a, b), or its own
+// TP degree (a, t) -- tp_ij of Sec. 4.2.2 taken per stage; TP then leaves the sub-problem and a
+// pool's quota is counted in GPUs of one replica.
+//
 //   k_search_beam        the level-by-level expansion, one workgroup per sub-problem
 //   k_search_pick        smallest (key, sub-problem) over the sub-problems' winners
 //   k_eval_placements    the simulator of Sec. 4.3 for listed placements, one wave each, fp64
@@ -36,7 +40,11 @@ struct SearchPP {      // one pipeline depth
   uint32_t rs0;        // first entry of its first partition row in the stage tables
   uint32_t sub_off;    // first sub-problem of this depth
   int32_t n_part;
+  uint32_t sub_off_t;  // the same when TP is not part of the sub-problem
+  uint32_t pad[3];
 };
+
+enum : int { SEARCH_PLAIN = 0, SEARCH_SPLIT = 1, SEARCH_STAGE_TP = 2 };
 
 struct SState {        // placement of stages 0 .. j; kStateBytes, followed by the paths (a byte per stage)
   double sum;          // times of the closed stages 0 .. j-1
@@ -45,20 +53,22 @@ struct SState {        // placement of stages 0 .. j; kStateBytes, followed by t
   double xb_open;      // its backward transfer to stage j-1
   double sum_b, maxt_b, c_open_b, xb_open_b;  // with split stages: the pipelines through the second pools
   double msync, mupd, dol, comm;
-  uint8_t cnt[kSearchMaxPools];  // stages placed on each pool (with split stages: halves of stages)
-  uint8_t pool, pool_b, runs, pad[5];
+  uint16_t cnt[kSearchMaxPools];  // stages placed on each pool (split stages: halves of stages; a
+                                  // TP degree per stage: GPUs of one replica)
+  uint8_t pool, pool_b, runs, tpi, pad[4];  // tpi: the open stage's TP index (TP per stage)
 };
 constexpr uint32_t kStateBytes = sizeof(SState);
-static_assert(kStateBytes == 168, "twelve doubles, the pool counts, pools and runs");
+static_assert(kStateBytes == 232, "twelve doubles, the pool counts, pools, runs and TP index");
 
 struct SubResult {     // winner of one sub-problem (or of the whole search)
   double key, T, C;
   uint32_t found, truncated;
   unsigned long long expanded;
   uint32_t sid, P;
-  int32_t desc[6];     // pp index, partition, tp index, dp index, mb index, 1 when stages may be split
+  int32_t desc[6];     // pp index, partition, tp index, dp index, mb index, the search's mode
   int32_t pools[256];  // pool of every stage
   int32_t pools_b[256];  // pool of the other half of its replicas (= pools[i] when not split)
+  int32_t tps[256];      // TP index of every stage (= desc[2] unless the stages choose their own)
 };
 
 struct SearchArgs {
@@ -131,19 +141,52 @@ struct SearchTables {  // LDS of a search workgroup: the sub-problem's and the l
   uint32_t l_fit;                      // bit g: the level's stage fits type g
   int dp_even;
   double dtp;                          // D * tp
+  // a TP degree per stage: the level's stage on every type / zone at every degree
+  double l_c3[kMaxTypes][kMaxTP], l_upd3[kMaxTypes][kMaxTP], l_dol3[kMaxTypes][kMaxTP];
+  double l_sync3[kMaxZones][kMaxTP];
+  uint32_t l_fit3[kMaxTP];             // bit g: the level's stage fits type g at this degree
+  int tpv[kMaxTP];
+  int cap_gpus[kSearchMaxPools];       // GPUs one replica can take from a pool
 };
 
 struct SAcc {          // what a placement carries besides its pool counts
   double sum, maxt, c_open, xb_open, sum_b, maxt_b, c_open_b, xb_open_b, msync, mupd, dol, comm;
 };
 
-// Stage j on pool a (SPLIT: half of its replicas on pool b) behind the placement par (none for
-// j = 0): may it be placed, and what the placement then carries.  The order of the operations
-// is part of the definition: sums in stage order, a closed stage's transfers forward then
-// backward.
-template <bool SPLIT>
+// Stage j on pool a (split stages: half of its replicas on pool b; a TP degree per stage: b is
+// its TP index) behind the placement par (none for j = 0): may it be placed, and what the
+// placement then carries.  The order of the operations is part of the definition: sums in
+// stage order, a closed stage's transfers forward then backward.
+template <int MODE>
 __device__ __forceinline__ bool search_step(const SearchTables &T, const SState *par, int j, int a, int b,
                                             int G, int max_runs, SAcc &o, int &runs) {
+  constexpr bool SPLIT = MODE == SEARCH_SPLIT;
+  if (MODE == SEARCH_STAGE_TP) {
+    const int g = a % G, z = a / G, t = b;
+    bool ok = ((T.l_fit3[t] >> g) & 1u) != 0;
+    const int used = par ? (int)par->cnt[a] : 0;
+    ok = ok && used + T.tpv[t] <= T.cap_gpus[a];
+    runs = par ? par->runs + ((a != par->pool || t != par->tpi) ? 1 : 0) : 1;
+    if (max_runs != 0 && runs > max_runs) ok = false;
+    if (!ok) return false;
+    o.c_open = T.l_c3[g][t];
+    if (!par) {
+      o.sum = 0.0; o.maxt = 0.0; o.xb_open = 0.0; o.msync = T.l_sync3[z][t]; o.mupd = T.l_upd3[g][t];
+      o.dol = T.l_dol3[g][t]; o.comm = 0.0;
+    } else {
+      const int pz = par->pool / G;
+      const double t_closed = par->c_open + (T.xfer[pz][z] + par->xb_open);  // forward, then backward
+      o.sum = par->sum + t_closed;
+      o.maxt = fmax(par->maxt, t_closed);
+      o.xb_open = T.xfer[z][pz];
+      o.msync = fmax(par->msync, T.l_sync3[z][t]);
+      o.mupd = fmax(par->mupd, T.l_upd3[g][t]);
+      o.dol = par->dol + T.l_dol3[g][t];
+      o.comm = pz != z ? par->comm + T.comm[pz][z] : par->comm;
+    }
+    o.sum_b = o.maxt_b = o.c_open_b = o.xb_open_b = 0.0;
+    return true;
+  }
   const int ga = a % G, za = a / G, gb = b % G, zb = b / G;
   bool ok = ((T.l_fit >> ga) & 1u) != 0 && ((T.l_fit >> gb) & 1u) != 0;
   const int ca = par ? (int)par->cnt[a] : 0, cb = par ? (int)par->cnt[b] : 0;
@@ -208,9 +251,9 @@ __device__ __forceinline__ bool search_step(const SearchTables &T, const SState 
 
 // Bounds of a placement whose stage j is open; with split stages the slower of the two kinds
 // of pipeline counts (Sec. 4.3).
-template <bool SPLIT>
+template <int MODE>
 __device__ __forceinline__ SBound search_bound_of(const SearchTables &T, const SAcc &o, int j, double nbm1) {
-  if (!SPLIT)
+  if (MODE != SEARCH_SPLIT)
     return search_bounds(o.sum, o.maxt, o.c_open, o.xb_open, o.msync, o.mupd, o.dol, o.comm, T.S[0][j],
                          T.S[1][j], T.S[2][j], T.S[3][j], T.S[4][j], nbm1);
   const double ta = o.c_open + o.xb_open, tb = o.c_open_b + o.xb_open_b;
@@ -222,8 +265,9 @@ __device__ __forceinline__ SBound search_bound_of(const SearchTables &T, const S
   return b;
 }
 
-template <bool SPLIT>
+template <int MODE>
 __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, SearchArgs a) {
+  constexpr bool SPLIT = MODE == SEARCH_SPLIT, STP = MODE == SEARCH_STAGE_TP;
   __shared__ SearchTables T;
   __shared__ unsigned long long b_key[kSearchBuf];
   __shared__ uint32_t b_id[kSearchBuf];
@@ -232,9 +276,12 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
   __shared__ unsigned long long s_bk[kSearchThreads / 64];
   __shared__ uint32_t s_bi[kSearchThreads / 64];
   __shared__ unsigned long long s_expanded;
+  __shared__ unsigned char s_fit3[kMaxTypes][kMaxTP];
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
   const int G = pl.G, Z = pl.Z, ZG = pl.ZGr, MB = pl.MB, TP = pl.TP, DP = pl.DP;
-  const int NCH = SPLIT ? ZG * ZG : ZG;  // choices per stage: a pool, or a pair (a, b) = a * ZG + b
+  // choices per stage: a pool; a pair (a, b) = a * ZG + b; a pool and a TP index (a, t) = a * TP + t
+  const int NCH = SPLIT ? ZG * ZG : (STP ? ZG * TP : ZG);
+  const int CH2 = STP ? TP : ZG;  // a choice c of two parts is (c / CH2, c % CH2)
   uint8_t *const buf0 = a.states + (size_t)blockIdx.x * 2 * a.W * a.state_stride;
   uint8_t *const buf1 = buf0 + (size_t)a.W * a.state_stride;
 
@@ -242,13 +289,13 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
     __syncthreads();  // the shared tables are reused
     int ip = 0;
     for (int i = 1; i < a.n_pp; ++i)
-      if (sid >= a.pps[i].sub_off) ip = i;
+      if (sid >= (STP ? a.pps[i].sub_off_t : a.pps[i].sub_off)) ip = i;
     const SearchPP pp = a.pps[ip];
-    uint32_t rem = sid - pp.sub_off;
+    uint32_t rem = sid - (STP ? pp.sub_off_t : pp.sub_off);
     const int im = (int)(rem % (uint32_t)MB); rem /= (uint32_t)MB;
     const int id = (int)(rem % (uint32_t)DP); rem /= (uint32_t)DP;
-    const int it = (int)(rem % (uint32_t)TP);
-    const int q = (int)(rem / (uint32_t)TP);
+    const int it = STP ? 0 : (int)(rem % (uint32_t)TP);  // (TP per stage: not part of the sub-problem)
+    const int q = STP ? (int)rem : (int)(rem / (uint32_t)TP);
     const int P = pp.P;
     const uint32_t rs = pp.rs0 + (uint32_t)q * (uint32_t)P;
     SubResult *res = a.results + sid;
@@ -258,7 +305,7 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
     if (t == 0) {
       res->found = 0; res->truncated = 0; res->expanded = 0; res->sid = sid; res->P = (uint32_t)P;
       res->desc[0] = ip; res->desc[1] = q; res->desc[2] = it; res->desc[3] = id; res->desc[4] = im;
-      res->desc[5] = SPLIT ? 1 : 0;
+      res->desc[5] = MODE;
       s_bad = 0;
       s_expanded = 0;
       T.dp_even = (D % 2 == 0) ? 1 : 0;
@@ -266,7 +313,6 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
     }
     __syncthreads();
     if (nb == 0) continue;              // the batch does not divide (uniform)
-    if (SPLIT && P > 127) continue;     // halves of stages are counted in a byte (uniform)
     const double p2p = (double)pl.p2p[im];
     const double nbm1 = (double)(nb - 1);
     // tables of the sub-problem
@@ -288,7 +334,41 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
     for (int p = t; p < ZG; p += blockDim.x) {
       T.cap[p] = (int)((int64_t)pl.avail[p] / ((int64_t)tp * D));
       T.cap_half[p] = (int)(2 * (int64_t)pl.avail[p] / ((int64_t)tp * D));
+      T.cap_gpus[p] = (int)((int64_t)pl.avail[p] / D);
     }
+    if (t < TP) T.tpv[t] = pl.tpv[t];
+    if (STP) {
+      for (int i = t; i < P; i += blockDim.x) {  // the cheapest admissible (type, TP) of stage i
+        const uint64_t params = pl.st_params[rs + i];
+        double cmin = __builtin_huge_val(), umin = cmin, dmin = cmin, smin = cmin;
+        bool any = false;
+        for (int k = 0; k < TP; ++k) {
+          const int tpk = pl.tpv[k];
+          const uint64_t bytes = stage_bytes_of(params, pl.st_n[rs + i], pl.bpp, i, P, tpk, nb, pl.act[im * TP + k]);
+          const uint64_t shard = (params + (uint64_t)tpk - 1) / (uint64_t)tpk;
+          bool fits_some = false;
+          for (int g = 0; g < G; ++g) {
+            if (!(bytes + pl.res[g] <= pl.cap[g] && tpk <= pl.node[g])) continue;
+            fits_some = true;
+            cmin = fmin(cmin, pl.st_c[(((size_t)(rs + i) * G + g) * MB + im) * TP + k]);
+            umin = fmin(umin, pl.st_u[((size_t)(rs + i) * G + g) * TP + k]);
+            dmin = fmin(dmin, (double)(D * tpk) * pl.price[g]);
+          }
+          if (!fits_some) continue;
+          any = true;
+          for (int z = 0; z < Z; ++z) {
+            double sync = 0.0;
+            if (D > 1) {
+              const double grad = (double)shard * (double)pl.gb;
+              sync = 2.0 * (double)(D - 1) / (double)D * grad / pl.bw[z * Z + z];
+            }
+            smin = fmin(smin, sync);
+          }
+        }
+        T.smin[0][i] = cmin; T.smin[1][i] = smin; T.smin[2][i] = umin; T.smin[3][i] = dmin;
+        if (!any) s_bad = 1;  // (benign race: every writer stores 1)
+      }
+    } else
     for (int i = t; i < P; i += blockDim.x) {  // the cheapest admissible choice of stage i
       const uint64_t params = pl.st_params[rs + i];
       const uint64_t bytes = stage_bytes_of(params, pl.st_n[rs + i], pl.bpp, i, P, tp, nb, pl.act[im * TP + it]);
@@ -331,7 +411,33 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
       uint8_t *const cur = (j & 1) ? buf1 : buf0, *const nxt = (j & 1) ? buf0 : buf1;
       __syncthreads();
       // the level's tables: stage j on every type / zone
-      if (t < G) {
+      if (STP) {
+        if (t < G * TP) {  // (type g, TP index k)
+          const int g = t / TP, k = t - g * TP, tpk = pl.tpv[k];
+          const uint64_t params = pl.st_params[rs + j];
+          const uint64_t bytes = stage_bytes_of(params, pl.st_n[rs + j], pl.bpp, j, P, tpk, nb, pl.act[im * TP + k]);
+          T.l_c3[g][k] = pl.st_c[(((size_t)(rs + j) * G + g) * MB + im) * TP + k];
+          T.l_upd3[g][k] = pl.st_u[((size_t)(rs + j) * G + g) * TP + k];
+          T.l_dol3[g][k] = (double)(D * tpk) * pl.price[g];
+          s_fit3[g][k] = (bytes + pl.res[g] <= pl.cap[g] && tpk <= pl.node[g]) ? 1 : 0;
+        } else if (t >= 128 && t < 128 + Z * TP) {  // (zone z, TP index k)
+          const int z = (t - 128) / TP, k = (t - 128) - z * TP, tpk = pl.tpv[k];
+          const uint64_t params = pl.st_params[rs + j];
+          const uint64_t shard = (params + (uint64_t)tpk - 1) / (uint64_t)tpk;
+          double sync = 0.0;
+          if (D > 1) {
+            const double grad = (double)shard * (double)pl.gb;
+            sync = 2.0 * (double)(D - 1) / (double)D * grad / pl.bw[z * Z + z];
+          }
+          T.l_sync3[z][k] = sync;
+        }
+        __syncthreads();
+        if (t < TP) {
+          uint32_t m = 0;
+          for (int g = 0; g < G; ++g) m |= (uint32_t)s_fit3[g][t] << g;
+          T.l_fit3[t] = m;
+        }
+      } else if (t < G) {
         const uint64_t params = pl.st_params[rs + j];
         const uint64_t bytes = stage_bytes_of(params, pl.st_n[rs + j], pl.bpp, j, P, tp, nb, pl.act[im * TP + it]);
         T.l_c[t] = pl.st_c[(((size_t)(rs + j) * G + t) * MB + im) * TP + it];
@@ -367,13 +473,13 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
         unsigned long long kbits = 0;
         if (cand < n_total) {
           const int r = cand / NCH, c = cand - r * NCH;
-          const int pa = SPLIT ? c / ZG : c, pb = SPLIT ? c - pa * ZG : c;
+          const int pa = (SPLIT || STP) ? c / CH2 : c, pb = (SPLIT || STP) ? c - pa * CH2 : c;
           const SState *par = j == 0 ? nullptr : reinterpret_cast<const SState *>(cur + (size_t)r * a.state_stride);
           SAcc o;
           int runs;
-          if (search_step<SPLIT>(T, par, j, pa, pb, G, a.max_runs, o, runs)) {
+          if (search_step<MODE>(T, par, j, pa, pb, G, a.max_runs, o, runs)) {
             my_expanded += 1;
-            const SBound b = search_bound_of<SPLIT>(T, o, j, nbm1);
+            const SBound b = search_bound_of<MODE>(T, o, j, nbm1);
             const double key = a.objective == 0 ? b.T : b.C;
             bool drop = false;
             if (a.has_bound) drop = a.objective == 0 ? b.C > a.bound : 1.0 / b.T < a.bound;
@@ -427,20 +533,23 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
           if (key_id_less(s_bk[w], s_bi[w], best_k, best_i)) { best_k = s_bk[w]; best_i = s_bi[w]; }
         if (best_i != ~0u) {  // uniform
           const int r = (int)best_i / NCH, c = (int)best_i - r * NCH;
-          const int pa = SPLIT ? c / ZG : c, pb = SPLIT ? c - pa * ZG : c;
+          const int pa = (SPLIT || STP) ? c / CH2 : c, pb = (SPLIT || STP) ? c - pa * CH2 : c;
           const uint8_t *par_path = cur + (size_t)r * a.state_stride + kStateBytes;
           for (int i = t; i < P - 1; i += blockDim.x) {
             res->pools[i] = par_path[i];
             res->pools_b[i] = SPLIT ? par_path[a.path_stride + i] : par_path[i];
+            res->tps[i] = STP ? par_path[a.path_stride + i] : it;
           }
           if (t == 0) {
             const SState *par = j == 0 ? nullptr : reinterpret_cast<const SState *>(cur + (size_t)r * a.state_stride);
             SAcc o;
             int runs;
-            search_step<SPLIT>(T, par, j, pa, pb, G, a.max_runs, o, runs);
-            const SBound b = search_bound_of<SPLIT>(T, o, j, nbm1);
+            search_step<MODE>(T, par, j, pa, pb, G, a.max_runs, o, runs);
+            const SBound b = search_bound_of<MODE>(T, o, j, nbm1);
             res->pools[P - 1] = pa;
-            res->pools_b[P - 1] = pb;
+            res->pools_b[P - 1] = SPLIT ? pb : pa;
+            res->tps[P - 1] = STP ? pb : it;
+            if (STP) res->desc[2] = P > 1 ? (int)par_path[a.path_stride] : pb;  // stage 0's
             res->T = b.T;
             res->C = b.C;
             res->key = a.objective == 0 ? b.T : b.C;
@@ -461,19 +570,19 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
       for (int k = t; k < n_next; k += blockDim.x) {
         const int cand = (int)b_id[k];
         const int r = cand / NCH, c = cand - r * NCH;
-        const int pa = SPLIT ? c / ZG : c, pb = SPLIT ? c - pa * ZG : c;
+        const int pa = (SPLIT || STP) ? c / CH2 : c, pb = (SPLIT || STP) ? c - pa * CH2 : c;
         uint8_t *const out = nxt + (size_t)k * a.state_stride;
         const SState *par = j == 0 ? nullptr : reinterpret_cast<const SState *>(cur + (size_t)r * a.state_stride);
         SAcc o;
         int runs;
-        search_step<SPLIT>(T, par, j, pa, pb, G, a.max_runs, o, runs);
+        search_step<MODE>(T, par, j, pa, pb, G, a.max_runs, o, runs);
         SState st;
         if (par) {
           st = *par;
           const uint8_t *par_path = cur + (size_t)r * a.state_stride + kStateBytes;
           for (int i = 0; i < j; ++i) {
             out[kStateBytes + i] = par_path[i];
-            if (SPLIT) out[kStateBytes + a.path_stride + i] = par_path[a.path_stride + i];
+            if (SPLIT || STP) out[kStateBytes + a.path_stride + i] = par_path[a.path_stride + i];
           }
         } else {
           for (int x = 0; x < kSearchMaxPools; ++x) st.cnt[x] = 0;
@@ -481,19 +590,22 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
         st.sum = o.sum; st.maxt = o.maxt; st.c_open = o.c_open; st.xb_open = o.xb_open;
         st.sum_b = o.sum_b; st.maxt_b = o.maxt_b; st.c_open_b = o.c_open_b; st.xb_open_b = o.xb_open_b;
         st.msync = o.msync; st.mupd = o.mupd; st.dol = o.dol; st.comm = o.comm;
-        if (!SPLIT) {
-          st.cnt[pa] = (uint8_t)(st.cnt[pa] + 1);
+        if (STP) {
+          st.cnt[pa] = (uint16_t)(st.cnt[pa] + T.tpv[pb]);
+        } else if (!SPLIT) {
+          st.cnt[pa] = (uint16_t)(st.cnt[pa] + 1);
         } else {
-          st.cnt[pa] = (uint8_t)(st.cnt[pa] + 1);
-          st.cnt[pb] = (uint8_t)(st.cnt[pb] + 1);
+          st.cnt[pa] = (uint16_t)(st.cnt[pa] + 1);
+          st.cnt[pb] = (uint16_t)(st.cnt[pb] + 1);
         }
         st.pool = (uint8_t)pa;
-        st.pool_b = (uint8_t)pb;
+        st.pool_b = SPLIT ? (uint8_t)pb : (uint8_t)pa;
+        st.tpi = STP ? (uint8_t)pb : (uint8_t)it;
         st.runs = (uint8_t)runs;
-        for (int x = 0; x < 5; ++x) st.pad[x] = 0;
+        for (int x = 0; x < 4; ++x) st.pad[x] = 0;
         *reinterpret_cast<SState *>(out) = st;
         out[kStateBytes + j] = (uint8_t)pa;
-        if (SPLIT) out[kStateBytes + a.path_stride + j] = (uint8_t)pb;
+        if (SPLIT || STP) out[kStateBytes + a.path_stride + j] = (uint8_t)pb;
       }
       n_cur = n_next;
     }
@@ -559,6 +671,7 @@ struct PlaceArgs {
   const int32_t *desc;    // [count][5] pp index, partition, tp index, dp index, mb index
   const int32_t *pools;   // [count][pool_stride] pool of every stage
   const int32_t *pools_b; // optional, same shape: pool of the other half of every stage's replicas
+  const int32_t *tps;     // optional, same shape: TP index of every stage (else the descriptor's)
   uint32_t pool_stride;
   const SubResult *one;   // alternative to desc / pools: the placement held by this record
   const SearchPP *pps;
@@ -668,8 +781,10 @@ __device__ __forceinline__ void eval_split_wave(const DevPlan &pl, const int32_t
 }
 
 // The simulator (Sec. 4.3) for plans whose stages choose their pools freely: one wave per
-// plan, lane i takes stages i, i + 64, ...; sums in stage order.  A descriptor or pool out of
-// range yields mask = 0xFFFFFFFF, T = C = +inf, mem = 0.
+// plan, lane i takes stages i, i + 64, ...; sums in stage order.  With a TP index per stage
+// every per-stage quantity (memory shard, activation bytes, profiled times, node size, gradient
+// shard, GPUs against the quota, rent) uses the stage's own degree.  A descriptor, pool or TP
+// index out of range yields mask = 0xFFFFFFFF, T = C = +inf, mem = 0.
 __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl, PlaceArgs a) {
   __shared__ RefineLds lds[kPlaceWaves];
   __shared__ double s_second[kPlaceWaves][kMaxStages];  // stage times of the second kind of pipeline
@@ -690,7 +805,8 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl
   if (valid && !a.one && (uint32_t)P > a.pool_stride) valid = false;
   RefineLds &L = lds[wv];
   int *cnt = s_cnt[wv];
-  const bool split = a.one ? a.one->desc[5] != 0 : a.pools_b != nullptr;  // stages may split their replicas
+  const bool split = a.one ? a.one->desc[5] == SEARCH_SPLIT : a.pools_b != nullptr;  // stages may split their replicas
+  const int32_t *const tps = a.one ? a.one->tps : (a.tps ? a.tps + ci * a.pool_stride : nullptr);
   if (valid) {
     for (int p = lane; p < kSearchMaxPools; p += 64) cnt[p] = 0;
     bool bad = false;
@@ -701,6 +817,7 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl
         const int p2 = a.one ? a.one->pools_b[i] : a.pools_b[ci * a.pool_stride + i];
         if (p2 < 0 || p2 >= ZG) bad = true;
       }
+      if (tps && (tps[i] < 0 || tps[i] >= TP)) bad = true;
     }
     if (__builtin_amdgcn_ballot_w64(bad) != 0) valid = false;
   }
@@ -730,13 +847,15 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl
         const int pn = i < P - 1 ? (a.one ? a.one->pools[i + 1] : a.pools[ci * a.pool_stride + i + 1]) : p;
         const int pv = i > 0 ? (a.one ? a.one->pools[i - 1] : a.pools[ci * a.pool_stride + i - 1]) : p;
         const int g = p % G, z = p / G, zn = pn / G, zp = pv / G;
-        atomicAdd(&cnt[p], 1);
+        const int ti = tps ? tps[i] : it;      // this stage's TP index and degree
+        const int64_t tpi = pl.tpv[ti];
+        atomicAdd(&cnt[p], (int)tpi);          // GPUs of one replica
         const size_t si = (size_t)rs + i;
         const uint64_t params = pl.st_params[si];
-        const uint64_t bytes = stage_bytes_of(params, pl.st_n[si], pl.bpp, i, P, (int)tp, nb, pl.act[im * TP + it]);
+        const uint64_t bytes = stage_bytes_of(params, pl.st_n[si], pl.bpp, i, P, (int)tpi, nb, pl.act[im * TP + ti]);
         const uint64_t m = bytes + pl.res[g];
         if (m > pl.cap[g]) oom = 1u;
-        if (tp > pl.node[g]) h1 = 1u;
+        if (tpi > pl.node[g]) h1 = 1u;
         peak = m > peak ? m : peak;
         double x = 0.0, comm = 0.0;
         if (i < P - 1) {
@@ -745,16 +864,16 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl
             comm = (double)nb * (double)D * p2p * (pl.egress[z * Z + zn] + pl.egress[zn * Z + z]);
         }
         if (i > 0) x += p2p / link_bw(pl, z, zp, p2p);
-        const double ts = pl.st_c[((si * G + g) * MB + im) * TP + it] + x;
+        const double ts = pl.st_c[((si * G + g) * MB + im) * TP + ti] + x;
         max_t = fmax(max_t, ts);
         if (D > 1) {
-          const uint64_t shard = (params + (uint64_t)tp - 1) / (uint64_t)tp;
+          const uint64_t shard = (params + (uint64_t)tpi - 1) / (uint64_t)tpi;
           const double gbytes = (double)shard * (double)pl.gb;
           t_sync = fmax(t_sync, 2.0 * (double)(D - 1) / (double)D * gbytes / link_bw(pl, z, z, gbytes));
         }
-        t_upd = fmax(t_upd, pl.st_u[(si * G + g) * TP + it]);
+        t_upd = fmax(t_upd, pl.st_u[(si * G + g) * TP + ti]);
         L.t[i] = ts;
-        L.dol[i] = (double)(D * tp) * pl.price[g];
+        L.dol[i] = (double)(D * tpi) * pl.price[g];
         L.comm[i] = comm;
       }
       if (__builtin_amdgcn_ballot_w64(oom != 0) != 0) mask |= 1u;
@@ -770,9 +889,9 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      bool over = false;  // quota: D replicas of every stage on the pool, tp GPUs each
+      bool over = false;  // quota: D replicas of every stage on the pool, its tp GPUs each
       for (int p = lane; p < ZG; p += 64)
-        if ((int64_t)cnt[p] * tp * D > (int64_t)pl.avail[p]) over = true;
+        if ((int64_t)cnt[p] * D > (int64_t)pl.avail[p]) over = true;
       if (__builtin_amdgcn_ballot_w64(over) != 0) mask |= 2u;
       double sum_t = 0.0, dollars = 0.0, comm = 0.0;
       for (int i = 0; i < P; ++i) {

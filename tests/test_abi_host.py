@@ -48,10 +48,11 @@ def test_struct_layouts_match_the_header(tmp_path):
               "sailor_result": ["index", "iter_time_s", "mask", "pp", "mb_index", "cut", "pool",
                                 "seg_tp", "seg_tp_index", "zone", "type_a", "type_b"],
               "sailor_constraint": ["bound", "has_bound"],
-              "sailor_search_options": ["beam_width", "max_runs", "use_incumbent", "incumbent", "allow_split"],
+              "sailor_search_options": ["beam_width", "max_runs", "use_incumbent", "incumbent", "allow_split",
+                                        "stage_tp"],
               "sailor_stage_plan": ["found", "exact", "pp", "partition", "mask", "peak_mem_bytes",
                                     "iter_time_s", "eval_cost", "expanded", "incumbent_used",
-                                    "incumbent", "pool", "pool_b"]}
+                                    "incumbent", "pool", "pool_b", "stage_tp_index"]}
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "sailor.h"', 'int main(void) {']
     for st, fl in fields.items():
         lines.append(f'printf("{st} %zu\\n", sizeof({st}));')

@@ -390,3 +390,144 @@ def test_third_workload_sized_split_search(torch_cuda, objective):
         assert unsplit.found and _key_of(unsplit, objective) <= inc
     finally:
         plan.destroy()
+
+
+# ---- stages that choose their TP degree too (tp_ij of Sec. 4.2.2, per stage) -----------------
+
+def gpu_eval_tp(torch, plan, desc, pools, tps, objective=MAX_THROUGHPUT, bound=None):
+    n, stride = pools.shape
+    dev = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to("cuda:0")
+    t = torch.empty(n, dtype=torch.float64, device="cuda:0")
+    c = torch.empty(n, dtype=torch.float64, device="cuda:0")
+    m = torch.empty(n, dtype=torch.int64, device="cuda:0")
+    k = torch.empty(n, dtype=torch.int32, device="cuda:0")
+    plan.eval_placements(n, dev(desc), dev(pools), stride, objective, bound, t, c, m, k,
+                         stream=torch.cuda.current_stream().cuda_stream, d_tps=dev(tps))
+    torch.cuda.synchronize()
+    return (t.cpu().numpy(), c.cpu().numpy(), m.cpu().numpy().view(np.uint64),
+            k.cpu().numpy().view(np.uint32))
+
+
+@pytest.mark.parametrize("make", [
+    lambda: _tiny(1), lambda: _tiny(2, n_types=3, n_zones=3), lambda: W.config2(), lambda: W.config3(),
+    lambda: (lambda p: p.with_bw_poly(W.bandwidth_poly(p)))(_tiny(4, n_zones=3)),
+])
+def test_placements_with_a_tp_per_stage_match_the_oracle(torch_cuda, make):
+    prob = make()
+    plan, orc = _plan(prob), Oracle(prob)
+    rng = np.random.default_rng(13)
+    try:
+        stride = int(max(prob.pp_values)) + 1
+        desc, pools = random_placements(prob, rng, 1500, stride)
+        # degrees in runs as well, a third of the plans with one degree throughout
+        tps = np.zeros_like(pools)
+        for i in range(len(desc)):
+            P = int(prob.pp_values[desc[i, 0]])
+            cuts = np.sort(rng.integers(0, P + 1, int(rng.integers(0, 3))))
+            run_tp = rng.integers(0, len(prob.tp_values), len(cuts) + 1)
+            tps[i, :P] = run_tp[np.searchsorted(cuts, np.arange(P), side="right")]
+        for objective, bound in ((MAX_THROUGHPUT, None), (MIN_COST, 0.7)):
+            t, c, m, k = gpu_eval_tp(torch_cuda, plan, desc, pools, tps, objective, bound)
+            valid = mixed = 0
+            for i in range(len(desc)):
+                P = int(prob.pp_values[desc[i, 0]])
+                e = orc.eval_assignment_tp(desc[i, 0], desc[i, 1], desc[i, 3], desc[i, 4], tps[i, :P],
+                                           pools[i, :P], objective, bound)
+                assert k[i] == e.mask and m[i] == e.peak_mem, (i, desc[i], pools[i, :P], tps[i, :P])
+                if np.isinf(e.iter_time):
+                    assert np.isinf(t[i]) and np.isinf(c[i])
+                else:
+                    assert t[i] == pytest.approx(e.iter_time, rel=1e-12)
+                    assert c[i] == pytest.approx(e.cost, rel=1e-12)
+                valid += e.mask == 0
+                mixed += e.mask == 0 and len(set(tps[i, :P])) > 1
+            if bound is None and prob.n_layers <= 8:
+                assert valid > 10 and mixed > 3
+        # the descriptor's degree everywhere: the evaluation without the array
+        same = np.repeat(desc[:, 2:3], stride, axis=1)
+        t0, c0, m0, k0 = gpu_eval_placements(torch_cuda, plan, desc, pools)
+        t1, c1, m1, k1 = gpu_eval_tp(torch_cuda, plan, desc, pools, same)
+        assert np.array_equal(k0, k1) and np.array_equal(m0, m1)
+        assert np.array_equal(t0, t1) and np.array_equal(c0, c1)
+        # a degree out of range; both optional arrays at once
+        bad = tps[:3].copy()
+        bad[1, 0] = len(prob.tp_values)
+        t, c, m, k = gpu_eval_tp(torch_cuda, plan, desc[:3], pools[:3], bad)
+        assert k[1] == 0xFFFFFFFF and np.isinf(t[1]) and m[1] == 0 and k[0] != 0xFFFFFFFF
+        from paper_2504_17096_amd.binding import SAILOR_EINVAL, SailorError
+        d = torch_cuda.zeros((1, stride), dtype=torch_cuda.int32, device="cuda:0")
+        with pytest.raises(SailorError) as err:
+            plan.eval_placements(1, torch_cuda.zeros((1, 5), dtype=torch_cuda.int32, device="cuda:0"), d, stride,
+                                 d_pools_b=d, d_tps=d)
+        assert err.value.status == SAILOR_EINVAL
+    finally:
+        plan.destroy()
+
+
+def check_same_tp(got, want, objective, orc):
+    assert got.found == (want is not None)
+    if want is None:
+        return
+    assert (got.pp_index, got.partition, got.dp_index, got.mb_index) == \
+           (want.pp_idx, want.partition, want.dp_idx, want.mb_idx)
+    assert got.pools == want.pools and got.tps == want.tps and got.tp_index == want.tps[0]
+    assert got.iter_time_s == want.iter_time and got.cost_per_iter == want.cost
+    assert got.exact == (not want.truncated) and got.expanded == want.expanded
+    assert got.mask == 0
+    assert got.eval_time_s == pytest.approx(got.iter_time_s, rel=1e-12)
+    assert got.eval_cost == pytest.approx(got.cost_per_iter, rel=1e-12)
+    e = orc.eval_assignment_tp(got.pp_index, got.partition, got.dp_index, got.mb_index, got.tps, got.pools, objective)
+    assert e.mask == 0 and e.peak_mem == got.peak_mem_bytes
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+@pytest.mark.parametrize("seed", [71, 72, 73, 74])
+def test_search_with_a_tp_per_stage_on_tiny_problems(torch_cuda, seed, objective):
+    prob = _tiny(seed, n_layers=3 if seed % 2 else 4, n_types=1 + seed % 2, n_zones=2 + (seed == 74),
+                 partitions_per_pp=1 + (seed == 72))
+    plan, orc = _plan(prob), Oracle(prob)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        exhaustive = orc.search_exhaustive(objective, stage_tp=True) if seed != 74 else None
+        plain = orc.search_beam(1 << 20, objective)
+        for width in (1, 4, 64, 256):
+            got = plan.search(width, objective, stage_tp=True, stream=stream)
+            check_same_tp(got, orc.search_beam(width, objective, stage_tp=True), objective, orc)
+            if got.exact and exhaustive is not None:
+                assert _key_of(got, objective) == exhaustive.key
+            if plain is not None:
+                inc = plain.key * (1 + 1e-9)
+                check_same_tp(plan.search(width, objective, stage_tp=True, incumbent=inc, stream=stream),
+                              orc.search_beam(width, objective, stage_tp=True, incumbent=inc), objective, orc)
+            for runs in (1, 2, 3):
+                check_same_tp(plan.search(width, objective, stage_tp=True, max_runs=runs, stream=stream),
+                              orc.search_beam(width, objective, stage_tp=True, max_runs=runs), objective, orc)
+        if plain is not None:
+            wb = plain.cost if objective == MAX_THROUGHPUT else 1.0 / plain.iter_time
+            bound = wb * (0.9 if objective == MAX_THROUGHPUT else 1.1) * (1 + 1e-7)
+            check_same_tp(plan.search(32, objective, bound=bound, stage_tp=True, stream=stream),
+                          orc.search_beam(32, objective, bound, stage_tp=True), objective, orc)
+        # the two wider forms of a choice exclude each other
+        from paper_2504_17096_amd.binding import SAILOR_EINVAL, SailorError
+        with pytest.raises(SailorError) as err:
+            plan.search(8, objective, stage_tp=True, allow_split=True, stream=stream)
+        assert err.value.status == SAILOR_EINVAL
+    finally:
+        plan.destroy()
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+def test_third_workload_sized_search_with_a_tp_per_stage(torch_cuda, objective):
+    # 48 choices per stage (12 pools x 4 degrees), up to 32 stages, 240 sub-problems
+    prob = W.config3()
+    plan, orc = _plan(prob), Oracle(prob)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        flat = plan.best_plan(objective=objective, stream=stream)
+        inc = (flat.iter_time_s if objective == MAX_THROUGHPUT else flat.cost_per_iter) * (1 + 1e-9)
+        for width in (8, 40):
+            got = plan.search(width, objective, incumbent=inc, stage_tp=True, stream=stream)
+            check_same_tp(got, orc.search_beam(width, objective, incumbent=inc, stage_tp=True), objective, orc)
+            assert _key_of(got, objective) <= inc
+    finally:
+        plan.destroy()
