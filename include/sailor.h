@@ -391,7 +391,8 @@ typedef struct {
  * zones; unsplit stages cost what they cost without the option.  With stage_tp a run of the run
  * limit ends where the pool or the degree changes, and "cheapest admissible choice" runs over the
  * (type, TP) pairs that fit.
- * Not for problems with per_segment_tp, mixed_types or bw_poly, more than 64 pools or 255
+ * per_segment_tp only shapes the enumerated space (and the incumbent taken from it); the search
+ * does not look at it.  Not for problems with mixed_types or bw_poly, more than 64 pools or 255
  * stages (SAILOR_EINVAL).  Waits for the device.  SAILOR_ENOFEASIBLE (out->found = 0, exact and
  * expanded still set) when no valid plan is found. */
 sailor_status sailor_search(sailor_plan *plan, sailor_objective objective,
@@ -419,7 +420,7 @@ sailor_status sailor_search(sailor_plan *plan, sailor_objective objective,
  *   outputs   device, [count], any may be NULL
  * A descriptor, pool or TP index out of range yields mask = 0xFFFFFFFF, time = cost = +inf, mem = 0; a
  * batch that does not divide mask = BATCH_INDIVISIBLE with +inf and 0.  Asynchronous on
- * hip_stream.  SAILOR_EINVAL for per_segment_tp / mixed_types problems or more than 64 pools. */
+ * hip_stream.  SAILOR_EINVAL for mixed_types problems or more than 64 pools. */
 sailor_status sailor_eval_placements(sailor_plan *plan, uint64_t count, const int32_t *d_desc,
                                      const int32_t *d_pools, const int32_t *d_pools_b,
                                      const int32_t *d_tps, uint32_t pool_stride,

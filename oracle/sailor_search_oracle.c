@@ -517,7 +517,7 @@ int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
                    const so_search_opts *opt, so_search_result *out) {
   const so_problem *p = so_problem_of(c);
   memset(out, 0, sizeof *out);
-  if (p->mixed_types || p->per_segment_tp || p->n_bw_coef > 0 || !opt || opt->beam_width < 1) return -1;
+  if (p->mixed_types || p->n_bw_coef > 0 || !opt || opt->beam_width < 1) return -1;
   if (p->n_types > 16 || p->n_zones > 16 || p->n_types * p->n_zones > SS_MAX_POOLS) return -1;
   const int W = opt->beam_width, ZG = p->n_types * p->n_zones;
   const int split = opt->allow_split ? 1 : 0, stp = opt->stage_tp ? 1 : 0, NT = p->n_tp;
@@ -675,7 +675,7 @@ int so_search_exhaustive(const so_ctx *c, int objective, int has_bound, double b
                          int allow_split, int stage_tp, so_search_result *out) {
   const so_problem *p = so_problem_of(c);
   memset(out, 0, sizeof *out);
-  if (p->mixed_types || p->per_segment_tp || (allow_split && stage_tp)) return -1;
+  if (p->mixed_types || (allow_split && stage_tp)) return -1;
   int32_t pools[SO_SEARCH_MAX_STAGES], pools_b[SO_SEARCH_MAX_STAGES];
   if (stage_tp) {
     for (int ip = 0; ip < p->n_pp; ++ip) {
@@ -705,7 +705,7 @@ int so_search_prefix_bound(const so_ctx *c, int pp_idx, int partition, int dp_id
                            int tp_idx, const int32_t *pools, int n_placed, int objective,
                            double *lb_time, double *lb_cost) {
   const so_problem *p = so_problem_of(c);
-  if (p->mixed_types || p->per_segment_tp || p->n_bw_coef > 0) return -1;
+  if (p->mixed_types || p->n_bw_coef > 0) return -1;
   ss_sub *s = (ss_sub *)malloc(sizeof(ss_sub));
   ss_state a, b;
   int rc = -1;
@@ -726,7 +726,7 @@ int so_search_prefix_bound_tp(const so_ctx *c, int pp_idx, int partition, int dp
                               const int32_t *tp_idx, const int32_t *pools, int n_placed, int objective,
                               double *lb_time, double *lb_cost) {
   const so_problem *p = so_problem_of(c);
-  if (p->mixed_types || p->per_segment_tp || p->n_bw_coef > 0) return -1;
+  if (p->mixed_types || p->n_bw_coef > 0) return -1;
   ss_sub *s = (ss_sub *)malloc(sizeof(ss_sub));
   ss_state a, b;
   int rc = -1;

@@ -1394,7 +1394,7 @@ sailor_status sailor_eval_placements(sailor_plan *pl, uint64_t count, const int3
   if (!pl || (objective != SAILOR_MAX_THROUGHPUT && objective != SAILOR_MIN_COST)) return SAILOR_EINVAL;
   if (count == 0) return SAILOR_OK;
   if (!d_desc || !d_pools || pool_stride < 1 || (d_pools_b && d_tps)) return SAILOR_EINVAL;
-  if (pl->dev.mixed || pl->dev.pst || pl->dev.ZGr > kSearchMaxPools) return SAILOR_EINVAL;
+  if (pl->dev.mixed || pl->dev.ZGr > kSearchMaxPools) return SAILOR_EINVAL;
   if (count > (uint64_t)0x7fffffff) return SAILOR_ERANGE;
   if (constraint && constraint->has_bound && std::isnan(constraint->bound)) return SAILOR_EINVAL;
   HIP_TRY(hipSetDevice(pl->device));
@@ -1430,7 +1430,7 @@ sailor_status sailor_search(sailor_plan *pl, sailor_objective objective,
   if (opt->stage_tp != 0 && opt->stage_tp != 1) return SAILOR_EINVAL;
   if (opt->allow_split && opt->stage_tp) return SAILOR_EINVAL;
   // plain pools, constant link bandwidths, a pipeline's stages numbered in a byte
-  if (pl->dev.mixed || pl->dev.pst || pl->dev.n_bw_coef > 0 || pl->dev.ZGr > kSearchMaxPools ||
+  if (pl->dev.mixed || pl->dev.n_bw_coef > 0 || pl->dev.ZGr > kSearchMaxPools ||
       pl->dev.P_max > kSearchMaxStages)
     return SAILOR_EINVAL;
   int has_bound;

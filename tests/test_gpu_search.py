@@ -199,8 +199,7 @@ def test_third_workload_sized_search(torch_cuda, objective):
 
 def test_search_rejects_what_it_does_not_cover(torch_cuda):
     from paper_2504_17096_amd.binding import SAILOR_EINVAL, SailorError
-    for prob in (_tiny(1).with_per_segment_tp(), _tiny(1).with_mixed_types(),
-                 (lambda p: p.with_bw_poly(W.bandwidth_poly(p)))(_tiny(1))):
+    for prob in (_tiny(1).with_mixed_types(), (lambda p: p.with_bw_poly(W.bandwidth_poly(p)))(_tiny(1))):
         plan = _plan(prob)
         try:
             with pytest.raises(SailorError) as err:
@@ -529,5 +528,26 @@ def test_third_workload_sized_search_with_a_tp_per_stage(torch_cuda, objective):
             got = plan.search(width, objective, incumbent=inc, stage_tp=True, stream=stream)
             check_same_tp(got, orc.search_beam(width, objective, incumbent=inc, stage_tp=True), objective, orc)
             assert _key_of(got, objective) <= inc
+    finally:
+        plan.destroy()
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+def test_a_problem_with_a_tp_per_segment_is_searched_like_the_plain_one(torch_cuda, objective):
+    # per_segment_tp shapes the enumerated space only; its optimum is what "flat" takes as the
+    # incumbent, and a search with a TP degree per stage and three runs covers that space
+    prob = _tiny(5, n_layers=4, n_types=2, n_zones=2)
+    seg = prob.with_per_segment_tp()
+    plan, orc, flat_orc = _plan(seg), Oracle(prob), Oracle(seg)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    try:
+        for width in (4, 256):
+            check_same(plan.search(width, objective, stream=stream), orc.search_beam(width, objective), objective)
+            check_same_tp(plan.search(width, objective, stage_tp=True, stream=stream),
+                          Oracle(seg).search_beam(width, objective, stage_tp=True), objective, orc)
+        flat = flat_orc.best(objective)
+        own = plan.search(256, objective, stage_tp=True, max_runs=3, incumbent="flat", stream=stream)
+        assert own.incumbent == pytest.approx(_key(flat, objective), rel=1e-8)
+        assert own.found and _key_of(own, objective) <= _key(flat, objective) * (1 + 1e-9)
     finally:
         plan.destroy()

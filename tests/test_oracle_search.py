@@ -426,3 +426,12 @@ def test_a_narrow_beam_with_a_tp_per_stage_returns_valid_plans(objective):
         if prev is not None:
             assert got.key <= prev * (1 + 1e-12)
         prev = got.key
+
+
+def test_a_tp_per_segment_in_the_flat_space_does_not_change_the_search():
+    prob = _tiny(33, n_layers=4, n_types=2, n_zones=2)
+    a, b = Oracle(prob), Oracle(prob.with_per_segment_tp())
+    for objective in OBJECTIVES:
+        for kw in ({}, {"stage_tp": True}, {"allow_split": True}):
+            x, y = a.search_beam(16, objective, **kw), b.search_beam(16, objective, **kw)
+            assert (x.pools, x.pools_b, x.tps, x.key, x.expanded) == (y.pools, y.pools_b, y.tps, y.key, y.expanded)
