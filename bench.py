@@ -405,6 +405,11 @@ def main() -> int:
     events4 = workloads.node_events(prob)
     replan["cfg4_node_events_full"] = replan_stream(np, Plan, prob, events4, stream, False)
     replan["cfg4_node_events_incremental"] = replan_stream(np, Plan, prob, events4, stream, True)
+    # ... and on its space with a TP degree per segment (915 206 400 candidates), where a pass
+    # over the space is most of a re-plan and kept minima shorten it
+    prob4s = prob.with_per_segment_tp()
+    replan["cfg4_segment_tp_node_events_full"] = replan_stream(np, Plan, prob4s, events4, stream, False)
+    replan["cfg4_segment_tp_node_events_incremental"] = replan_stream(np, Plan, prob4s, events4, stream, True)
     for v in replan.values():
         if isinstance(v, dict) and not args.copy_probe:
             per = v.pop("units_evaluated_per_snapshot")
