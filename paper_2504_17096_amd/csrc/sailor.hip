@@ -158,6 +158,7 @@ struct sailor_plan {
   uint32_t n_sub = 0, n_sub_t = 0;  // sub-problems with TP in them / with a TP degree per stage
   uint8_t *search_states = nullptr;
   uint32_t search_wgs = 0, search_state_stride = 0, search_path_stride = 0;
+  int search_beam_cap = 0;  // beam width the frontier buffers hold
   SubResult *search_results = nullptr, *search_final = nullptr;
   double *search_eval = nullptr;  // T, C, then (as 64-bit words) mem and mask of the winner
   uint32_t cnt_phase = 0;      // which of the two counter sets the next call uses
@@ -1343,7 +1344,9 @@ sailor_status sailor_simulate_1f1b_static(sailor_plan *pl, uint64_t count, const
 }
 
 // tables of the search and of the placement evaluation (once per plan)
-static sailor_status search_setup(sailor_plan *pl, bool with_scratch) {
+// (beam = 0: the tables only; beam > 0: also the search's buffers, its frontiers sized for the
+// widest beam asked for so far)
+static sailor_status search_setup(sailor_plan *pl, int beam) {
   if (!pl->d_search_pps) {
     pl->search_pps.clear();
     uint32_t sub = 0, sub_t = 0;
@@ -1371,16 +1374,40 @@ static sailor_status search_setup(sailor_plan *pl, bool with_scratch) {
     if (pl->arena.upload(&pl->d_search_pps, pl->search_pps.data(), pl->search_pps.size()) != hipSuccess)
       return SAILOR_ENOMEM;
   }
-  if (with_scratch && !pl->search_states) {
+  if (beam > 0 && !pl->search_results) {
+    SubResult *res = nullptr, *fin = nullptr;
+    double *ev = nullptr;
+    if (pl->arena.alloc(&res, (size_t)pl->n_sub) != hipSuccess || pl->arena.alloc(&fin, 1) != hipSuccess ||
+        pl->arena.alloc(&ev, 4) != hipSuccess) {
+      pl->arena.free_one(res);
+      pl->arena.free_one(fin);
+      pl->arena.free_one(ev);
+      return SAILOR_ENOMEM;
+    }
+    if (hipMemset(fin, 0, sizeof(SubResult)) != hipSuccess) {  // (read by the winner's re-evaluation
+      pl->arena.free_one(res);                                 // also when nothing was found)
+      pl->arena.free_one(fin);
+      pl->arena.free_one(ev);
+      return SAILOR_EDEVICE;
+    }
+    pl->search_results = res;
+    pl->search_final = fin;
+    pl->search_eval = ev;
+  }
+  if (beam > pl->search_beam_cap) {
+    // (no search is in flight on these buffers: every call waits for its own kernels)
+    pl->arena.free_one(pl->search_states);
+    pl->search_states = nullptr;
+    pl->search_beam_cap = 0;
     pl->search_wgs = std::min<uint32_t>(pl->n_sub, 2048u);
     pl->search_path_stride = ((uint32_t)pl->dev.P_max + 7u) & ~7u;
     pl->search_state_stride = kStateBytes + 2 * pl->search_path_stride;
-    const size_t bytes = (size_t)pl->search_wgs * 2 * kSearchMaxBeam * pl->search_state_stride;
-    if (pl->arena.alloc(&pl->search_states, bytes) != hipSuccess ||
-        pl->arena.alloc(&pl->search_results, (size_t)pl->n_sub) != hipSuccess ||
-        pl->arena.alloc(&pl->search_final, 1) != hipSuccess ||
-        pl->arena.alloc(&pl->search_eval, 4) != hipSuccess)
+    const size_t bytes = (size_t)pl->search_wgs * 2 * (size_t)beam * pl->search_state_stride;
+    if (pl->arena.alloc(&pl->search_states, bytes) != hipSuccess) {
+      pl->search_states = nullptr;
       return SAILOR_ENOMEM;
+    }
+    pl->search_beam_cap = beam;
   }
   return SAILOR_OK;
 }
@@ -1400,7 +1427,7 @@ sailor_status sailor_eval_placements(sailor_plan *pl, uint64_t count, const int3
   HIP_TRY(hipSetDevice(pl->device));
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   sailor_status rc;
-  try { rc = search_setup(pl, false); } catch (...) { rc = SAILOR_ENOMEM; }
+  try { rc = search_setup(pl, 0); } catch (...) { rc = SAILOR_ENOMEM; }
   if (rc != SAILOR_OK) return rc;
   rc = refresh_avail(pl, st);
   if (rc != SAILOR_OK) return rc;
@@ -1440,7 +1467,7 @@ sailor_status sailor_search(sailor_plan *pl, sailor_objective objective,
   if (rc != SAILOR_OK) return rc;
   HIP_TRY(hipSetDevice(pl->device));
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  try { rc = search_setup(pl, true); } catch (...) { rc = SAILOR_ENOMEM; }
+  try { rc = search_setup(pl, opt->beam_width); } catch (...) { rc = SAILOR_ENOMEM; }
   if (rc != SAILOR_OK) return rc;
   SearchArgs a{};
   a.objective = (int)objective;
