@@ -435,3 +435,38 @@ def test_a_tp_per_segment_in_the_flat_space_does_not_change_the_search():
         for kw in ({}, {"stage_tp": True}, {"allow_split": True}):
             x, y = a.search_beam(16, objective, **kw), b.search_beam(16, objective, **kw)
             assert (x.pools, x.pools_b, x.tps, x.key, x.expanded) == (y.pools, y.pools_b, y.tps, y.key, y.expanded)
+
+
+def test_replicas_that_cannot_be_halved_leave_the_split_search_where_the_plain_one_is():
+    # odd data-parallel degrees only: no stage can be split, so the search with pairs of pools
+    # generates exactly the placements (a, a) -- as many as the search with one pool per stage
+    base = _tiny(34, n_layers=4, n_types=2, n_zones=2)
+    from dataclasses import replace
+    odd = replace(base, dp_values=np.asarray([1, 3], np.int32), global_batch=12)
+    orc = Oracle(odd)
+    for objective in OBJECTIVES:
+        a, b = orc.search_beam(1 << 20, objective), orc.search_beam(1 << 20, objective, allow_split=True)
+        assert a is not None
+        assert (b.pools, b.pools_b, b.key, b.expanded) == (a.pools, a.pools, a.key, a.expanded)
+
+
+def test_the_second_pipelines_crossing_is_paid_for():
+    # D = 2, two zones of one type: zone 0 has three GPUs, zone 1 one.  Two stages need four: one
+    # stage whole in zone 0, the other with a replica in each zone, so one kind of pipeline stays
+    # in zone 0 and the other crosses -- whichever stage is split, and whichever half is named first
+    bw = np.array([[1e9, 2e8], [2e8, 1e9]])
+    p = make_problem(n_layers=2, n_types=1, n_zones=2, mb_list=(1,), tp_list=(1,), dp_list=(2,), pp_list=[2],
+                     global_batch=8, t_fwd=1e-3, t_bwd=2e-3, p2p=1_000_000, bw=bw, layer_params=1_000_000,
+                     price=3600.0, avail=np.array([[3], [1]]), egress=np.array([[0.0, 1e-9], [3e-9, 0.0]]))
+    orc = Oracle(p)
+    for objective in OBJECTIVES:
+        got = orc.search_beam(1 << 16, objective, allow_split=True)
+        want = orc.search_exhaustive(objective, allow_split=True)
+        assert got.key == pytest.approx(want.key, rel=1e-13)
+        split = [a != b for a, b in zip(got.pools, got.pools_b)]
+        assert sum(split) == 1
+        e = _eval_split(orc, got, objective)
+        assert e.mask == 0 and e.cost == pytest.approx(got.cost, rel=1e-13)
+        # 4 microbatches x 1 MB x one replica over the boundary, both directions' prices, plus the
+        # split stage's ring (2 MB over the boundary, both directions' prices), plus the rent
+        assert got.cost == pytest.approx(4 * got.iter_time + 4 * 1e6 * 4e-9 + 2e6 * 4e-9, rel=1e-13)

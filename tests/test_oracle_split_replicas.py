@@ -132,3 +132,22 @@ def test_quota_memory_and_node_size_of_both_halves():
     e = oq.eval_split_assignment(0, 0, 0, 0, 0, [0], [1])
     assert e.mask == BIT_OOM and e.peak_mem == 200_000_000 * 16
     assert oq.eval_split_assignment(0, 0, 0, 0, 1, [0], [1]).mask == BIT_TP_NODE
+
+
+def test_a_stage_on_two_types_pays_both_prices_and_waits_for_the_slower_update():
+    # one stage, D = 2, one replica on each of two types of one zone: type 1 is twice as slow in
+    # compute and in its optimizer step and costs a third; 2 microbatches per pipeline
+    tf = np.zeros((2, 1, 1, 1)); tf[:, 0, 0, 0] = (1e-3, 2e-3)
+    tu = np.zeros((2, 1, 1)); tu[:, 0, 0] = (3e-4, 6e-4)
+    p = make_problem(n_layers=1, n_types=2, n_zones=1, mb_list=(1,), tp_list=(1,), dp_list=(2,), pp_list=[1],
+                     global_batch=4, t_fwd=tf, t_bwd=0.0, t_upd=tu, layer_params=0, p2p=0,
+                     price=np.array([3600.0, 1200.0]))
+    orc = Oracle(p)
+    for a, b in (([0], [1]), ([1], [0])):
+        e = orc.eval_split_assignment(0, 0, 0, 0, 0, a, b)
+        T = 2 * 2e-3 + 6e-4                  # the slower kind of pipeline, then the slower update
+        assert e.mask == 0 and e.iter_time == pytest.approx(T, rel=1e-13)
+        assert e.cost == pytest.approx((1.0 + 1.0 / 3.0) * T, rel=1e-13)   # one GPU at each price
+    fast = orc.eval_split_assignment(0, 0, 0, 0, 0, [0], [0])
+    assert fast.iter_time == pytest.approx(2 * 1e-3 + 3e-4, rel=1e-13)
+    assert fast.cost == pytest.approx(2.0 * fast.iter_time, rel=1e-13)
