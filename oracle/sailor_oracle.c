@@ -907,3 +907,113 @@ int so_topk(const so_ctx *c, uint64_t first, uint64_t count, int objective, int 
   for (int t = 0; t < n_threads; ++t) free(jobs[t].top);
   return n;
 }
+
+int so_eval_replica_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                               int tp_idx, const int32_t *pools, int objective, int has_bound,
+                               double bound, so_eval *out) {
+  const so_problem *p = &c->p;
+  if (p->mixed_types || pp_idx < 0 || pp_idx >= p->n_pp || dp_idx < 0 || dp_idx >= p->n_dp ||
+      mb_idx < 0 || mb_idx >= p->n_mb || tp_idx < 0 || tp_idx >= p->n_tp || partition < 0 ||
+      partition >= p->n_partitions[pp_idx])
+    return -1;
+  const int P = p->pp_values[pp_idx], G = p->n_types, Z = p->n_zones;
+  const int64_t D = p->dp_values[dp_idx], micro = p->mb_values[mb_idx], tp = p->tp_values[tp_idx];
+  for (int64_t k = 0; k < (int64_t)P * D; ++k)
+    if (pools[k] < 0 || pools[k] >= Z * G) return -1;
+  so_config g;
+  memset(&g, 0, sizeof g);
+  g.pp_idx = pp_idx; g.pp = P; g.partition = partition;
+  const int32_t *nl = partition_row(c, &g);
+  out->index = 0; out->mask = 0; out->peak_mem = 0;
+  if (p->global_batch % (D * micro) != 0) {
+    out->mask = SO_BIT_BATCH;
+    out->iter_time = INFINITY;
+    out->cost = INFINITY;
+    return 0;
+  }
+  const int64_t n_micro = p->global_batch / (D * micro);
+
+  /* what every pool gives, node size, memory of every replica's worker */
+  int64_t gpus[SO_MAX_POOLS];
+  memset(gpus, 0, sizeof gpus);
+  uint64_t shard_of[SO_MAX_STAGES], peak = 0;
+  int first_of[SO_MAX_STAGES];
+  int layer = 0;
+  for (int i = 0; i < P; ++i) {
+    uint64_t params = 0;
+    first_of[i] = layer;
+    for (int l = layer; l < layer + nl[i]; ++l) params += p->layer_params[l];
+    layer += nl[i];
+    if (i == 0) params += p->embed_params;
+    if (i + 1 == P) params += p->head_params;
+    shard_of[i] = (params + (uint64_t)tp - 1) / (uint64_t)tp;
+    const int64_t in_flight = (P - i) < n_micro ? (P - i) : n_micro;
+    const uint64_t bytes = shard_of[i] * (uint64_t)p->bytes_per_param +
+                           (uint64_t)in_flight * (uint64_t)nl[i] *
+                               p->act_store_bytes[(size_t)mb_idx * p->n_tp + tp_idx];
+    for (int64_t r = 0; r < D; ++r) {
+      const int a = pools[(int64_t)i * D + r], gt = a % G;
+      gpus[a] += tp;
+      if (tp > p->gpus_per_node[gt]) out->mask |= SO_BIT_TP_NODE;
+      const uint64_t m = bytes + p->mem_reserved[gt];
+      if (m > p->mem_capacity[gt]) out->mask |= SO_BIT_OOM;
+      if (m > peak) peak = m;
+    }
+  }
+  for (int a = 0; a < Z * G; ++a)
+    if (gpus[a] > (int64_t)p->avail[a]) out->mask |= SO_BIT_QUOTA;
+  out->peak_mem = peak;
+
+  /* the D pipelines, each with its own stage times and transfers */
+  const double msg = (double)p->p2p_bytes[mb_idx];
+  double t_pipe = 0.0, t_update = 0.0, traffic_cost = 0.0, rent = 0.0;
+  for (int64_t r = 0; r < D; ++r) {
+    double total = 0.0, slowest = 0.0;
+    for (int i = 0; i < P; ++i) {
+      const int a = pools[(int64_t)i * D + r], gt = a % G, z = a / G;
+      double t = layer_time_sum(p, p->t_fwd, gt, mb_idx, tp_idx, first_of[i], nl[i]) +
+                 layer_time_sum(p, p->t_bwd, gt, mb_idx, tp_idx, first_of[i], nl[i]);
+      double moves = 0.0;
+      if (i < P - 1) {
+        const int zn = pools[(int64_t)(i + 1) * D + r] / G;
+        moves += msg / link_bandwidth(p, z, zn, msg);
+        if (p->egress_per_byte && zn != z) /* one replica's microbatches, both directions */
+          traffic_cost += (double)n_micro * msg *
+                          (p->egress_per_byte[(size_t)z * Z + zn] + p->egress_per_byte[(size_t)zn * Z + z]);
+      }
+      if (i > 0) moves += msg / link_bandwidth(p, z, pools[(int64_t)(i - 1) * D + r] / G, msg);
+      t += moves;
+      total += t;
+      if (t > slowest) slowest = t;
+      const double u = upd_time_sum(p, gt, tp_idx, first_of[i], nl[i]);
+      if (u > t_update) t_update = u;
+      rent += (double)tp * p->price_per_hour[gt];
+    }
+    const double t_this = total + (double)(n_micro - 1) * slowest;
+    if (t_this > t_pipe) t_pipe = t_this;
+  }
+
+  /* gradient all-reduce per stage: a ring through the replicas in their order */
+  double t_allreduce = 0.0;
+  if (D > 1)
+    for (int i = 0; i < P; ++i) {
+      const double buffer = (double)shard_of[i] * (double)p->grad_bytes_per_param;
+      const double ring_bytes = 2.0 * (double)(D - 1) / (double)D * buffer;
+      double link = INFINITY;
+      for (int64_t r = 0; r < D; ++r) {
+        const int zr = pools[(int64_t)i * D + r] / G, zs = pools[(int64_t)i * D + (r + 1) % D] / G;
+        const double w = link_bandwidth(p, zr, zs, buffer);
+        if (w < link) link = w;
+        if (p->egress_per_byte && zr != zs) traffic_cost += ring_bytes * p->egress_per_byte[(size_t)zr * Z + zs];
+      }
+      const double t = ring_bytes / link;
+      if (t > t_allreduce) t_allreduce = t;
+    }
+  out->iter_time = t_pipe + t_allreduce + t_update;
+  out->cost = rent / 3600.0 * out->iter_time + traffic_cost;
+  if (has_bound) {
+    if (objective == SO_MAX_THROUGHPUT ? out->cost > bound : 1.0 / out->iter_time < bound)
+      out->mask |= SO_BIT_CONSTRAINT;
+  }
+  return 0;
+}

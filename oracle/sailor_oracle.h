@@ -164,6 +164,19 @@ int so_eval_split_assignment(const so_ctx *c, int pp_idx, int partition, int dp_
                              int tp_idx, const int32_t *pools_a, const int32_t *pools_b,
                              int objective, int has_bound, double bound, so_eval *out);
 
+/* The plan tuple in full (Sec. 4.2: D tuples per stage): every replica of every stage names its
+ * pool, pools[i * D + r] for stage i and replica r.  Replica r of all stages forms pipeline r;
+ * T_iter = max over the D pipelines + T_sync + T_update (Sec. 4.3).  A stage's gradient all-reduce
+ * is a ring through its replicas in their order (r -> r + 1 -> ... -> 0) at the pace of its
+ * slowest link; traffic between zones is paid for where a pipeline or a ring crosses.  Quotas
+ * count the GPUs every pool gives, memory and node size hold for every replica's type, one TP
+ * degree per plan.  With all replicas of a stage on one pool this is so_eval_assignment, with
+ * the first half on one pool and the second half on another so_eval_split_assignment (D >= 4).
+ * Returns 0, -1 for a value out of range or a problem with extended types. */
+int so_eval_replica_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                               int tp_idx, const int32_t *pools, int objective, int has_bound,
+                               double bound, so_eval *out);
+
 #define SO_SEARCH_MAX_STAGES 256
 typedef struct {
   int32_t found;                 /* 1: a valid plan exists (within the incumbent, if one was given) */

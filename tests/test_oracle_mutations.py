@@ -55,6 +55,14 @@ MUTANTS = [
     ("test_oracle_search.py", "(a != par->pool || t != par->tpi) ? 1 : 0", "(a != par->pool) ? 1 : 0"),
     ("test_oracle_search.py", "tp_of[i] = p->tp_values[tp_idx[i]];", "tp_of[i] = p->tp_values[tp_idx[0]];",
      "sailor_oracle.c"),
+    # a pool per replica: a ring that is not closed, its fastest link, the last pipeline instead of
+    # the slowest, replicas counted instead of GPUs, the ring's traffic priced in the wrong direction
+    ("test_oracle_replica_placements.py", "(r + 1) % D] / G;", "(r + 1 < D ? r + 1 : r)] / G;"),
+    ("test_oracle_replica_placements.py", "if (w < link) link = w;", "if (w > link || link == INFINITY) link = w;"),
+    ("test_oracle_replica_placements.py", "if (t_this > t_pipe) t_pipe = t_this;", "t_pipe = t_this;"),
+    ("test_oracle_replica_placements.py", "gpus[a] += tp;", "gpus[a] += 1;"),
+    ("test_oracle_replica_placements.py", "traffic_cost += ring_bytes * p->egress_per_byte[(size_t)zr * Z + zs];",
+     "traffic_cost += ring_bytes * p->egress_per_byte[(size_t)zs * Z + zr];"),
 ]
 
 
