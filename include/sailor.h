@@ -429,6 +429,29 @@ sailor_status sailor_eval_placements(sailor_plan *plan, uint64_t count, const in
                                      double *d_cost, uint64_t *d_mem, uint32_t *d_mask,
                                      void *hip_stream);
 
+/* The plan tuple in full (Sec. 4.2: a stage has D tuples (GPU, TP, zone), one per replica): every
+ * replica of every stage names its pool -- uneven splits of a stage's replicas, any number of
+ * pools per stage.
+ *   d_desc    device, [count][5]: pp index, partition, TP index, D index, microbatch index
+ *   d_pools   device, [count][stride] with stride >= P x D: the pool of replica r of stage i at
+ *             i * D + r
+ * Replica r of all stages forms pipeline r, with its own stage times and transfers, and
+ * T_iter = max over the D pipelines + T_sync + T_update (Sec. 4.3).  The gradient all-reduce of
+ * a stage is a ring through its replicas in their order (0 -> 1 -> ... -> D - 1 -> 0) at the
+ * pace of its slowest link, 2 (D - 1) / D x gradient bytes over it.  Traffic between zones is
+ * paid for where a pipeline crosses (both directions' prices per microbatch, as everywhere) and
+ * where a ring link crosses (that direction's price).  Memory and node size hold for every
+ * replica's GPU type, a pool's quota counts the GPUs it gives, one TP degree per plan.  With all
+ * replicas of a stage on one pool the values are those of sailor_eval_placements.
+ * Outputs and errors as for sailor_eval_placements (an invalid row also when stride < P x D).
+ * Asynchronous on hip_stream.  SAILOR_EINVAL for mixed_types problems or more than 64 pools. */
+sailor_status sailor_eval_replica_placements(sailor_plan *plan, uint64_t count, const int32_t *d_desc,
+                                             const int32_t *d_pools, uint64_t stride,
+                                             sailor_objective objective,
+                                             const sailor_constraint *constraint, double *d_time,
+                                             double *d_cost, uint64_t *d_mem, uint32_t *d_mask,
+                                             void *hip_stream);
+
 /* Sizes of the intermediate lists of the last successful sailor_best_plan / sailor_topk
  * (the selection of Sec. 4.2 runs as fp32 scan -> survivors -> fp64 re-evaluation):
  * candidates kept by the fp32 threshold, candidates re-evaluated in fp64, and how many of

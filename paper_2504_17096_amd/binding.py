@@ -29,7 +29,8 @@ EXPORTS = ["sailor_plan_create", "sailor_plan_destroy", "sailor_plan_set_avail",
            "sailor_best_plan", "sailor_topk", "sailor_plan_set_scratch", "sailor_plan_set_timing",
            "sailor_plan_last_timing", "sailor_plan_last_counts", "sailor_simulate_1f1b",
            "sailor_simulate_1f1b_static", "sailor_plan_set_incremental", "sailor_plan_last_scan",
-           "sailor_search", "sailor_eval_placements", "sailor_set_scan_unit_parts"]
+           "sailor_search", "sailor_eval_placements", "sailor_eval_replica_placements",
+           "sailor_set_scan_unit_parts"]
 
 
 class SailorError(RuntimeError):
@@ -195,6 +196,8 @@ def load_library() -> C.CDLL:
                                   C.POINTER(sailor_search_options), C.POINTER(sailor_stage_plan), P]
     lib.sailor_eval_placements.argtypes = [P, C.c_uint64, P, P, P, P, C.c_uint32, C.c_int,
                                            C.POINTER(sailor_constraint), P, P, P, P, P]
+    lib.sailor_eval_replica_placements.argtypes = [P, C.c_uint64, P, P, C.c_uint64, C.c_int,
+                                                   C.POINTER(sailor_constraint), P, P, P, P, P]
     lib.sailor_plan_last_counts.argtypes = [P, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                             C.POINTER(C.c_uint32)]
     for name in EXPORTS:
@@ -419,6 +422,17 @@ class Plan:
                                               _ptr(d_mem), _ptr(d_mask), stream or None)
         if rc != SAILOR_OK:
             raise SailorError(rc, "sailor_eval_placements")
+
+    def eval_replica_placements(self, count: int, d_desc, d_pools, stride: int,
+                                objective: int = MAX_THROUGHPUT, bound: Optional[float] = None, d_time=None,
+                                d_cost=None, d_mem=None, d_mask=None, stream: int = 0) -> None:
+        """sailor_eval_replica_placements; device tensors: int32 [count][5], int32 [count][stride] with
+        the pool of replica r of stage i at i * D + r, float64 / float64 / int64 / int32 outputs."""
+        rc = self._lib.sailor_eval_replica_placements(self._h, count, _ptr(d_desc), _ptr(d_pools), stride,
+                                                      objective, _constraint(bound), _ptr(d_time),
+                                                      _ptr(d_cost), _ptr(d_mem), _ptr(d_mask), stream or None)
+        if rc != SAILOR_OK:
+            raise SailorError(rc, "sailor_eval_replica_placements")
 
     def set_incremental(self, on: bool) -> None:
         rc = self._lib.sailor_plan_set_incremental(self._h, 1 if on else 0)

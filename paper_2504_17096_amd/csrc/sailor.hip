@@ -1444,6 +1444,37 @@ sailor_status sailor_eval_placements(sailor_plan *pl, uint64_t count, const int3
   return SAILOR_OK;
 }
 
+sailor_status sailor_eval_replica_placements(sailor_plan *pl, uint64_t count, const int32_t *d_desc,
+                                             const int32_t *d_pools, uint64_t stride,
+                                             sailor_objective objective,
+                                             const sailor_constraint *constraint, double *d_time,
+                                             double *d_cost, uint64_t *d_mem, uint32_t *d_mask,
+                                             void *hip_stream) {
+  if (!pl || (objective != SAILOR_MAX_THROUGHPUT && objective != SAILOR_MIN_COST)) return SAILOR_EINVAL;
+  if (count == 0) return SAILOR_OK;
+  if (!d_desc || !d_pools || stride < 1) return SAILOR_EINVAL;
+  if (pl->dev.mixed || pl->dev.ZGr > kSearchMaxPools) return SAILOR_EINVAL;
+  if (count > (uint64_t)0x7fffffff) return SAILOR_ERANGE;
+  if (constraint && constraint->has_bound && std::isnan(constraint->bound)) return SAILOR_EINVAL;
+  HIP_TRY(hipSetDevice(pl->device));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  sailor_status rc;
+  try { rc = search_setup(pl, 0); } catch (...) { rc = SAILOR_ENOMEM; }
+  if (rc != SAILOR_OK) return rc;
+  rc = refresh_avail(pl, st);
+  if (rc != SAILOR_OK) return rc;
+  ReplicaArgs a{};
+  a.count = count; a.desc = d_desc; a.pools = d_pools; a.stride = stride;
+  a.pps = pl->d_search_pps; a.n_pp = (int)pl->search_pps.size();
+  a.objective = (int)objective;
+  a.has_bound = (constraint && constraint->has_bound) ? 1 : 0;
+  a.bound = a.has_bound ? constraint->bound : 0.0;
+  a.T = d_time; a.C = d_cost; a.mem = d_mem; a.mask = d_mask;
+  k_eval_replicas<<<(unsigned)((count + kPlaceWaves - 1) / kPlaceWaves), kPlaceWaves * 64, 0, st>>>(pl->dev, a);
+  HIP_TRY(hipGetLastError());
+  return SAILOR_OK;
+}
+
 sailor_status sailor_search(sailor_plan *pl, sailor_objective objective,
                             const sailor_constraint *constraint, const sailor_search_options *opt,
                             sailor_stage_plan *out, void *hip_stream) {

@@ -18,6 +18,7 @@
 //   k_search_beam        the level-by-level expansion, one workgroup per sub-problem
 //   k_search_pick        smallest (key, sub-problem) over the sub-problems' winners
 //   k_eval_placements    the simulator of Sec. 4.3 for listed placements, one wave each, fp64
+//   k_eval_replicas      the same for plans in which every replica of every stage names its pool
 //
 // All arithmetic is fp64 in a fixed order (sums in stage order), so that which extension is
 // dropped or kept does not depend on how the work is spread over lanes.
@@ -901,6 +902,155 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl
       }
       T = (sum_t + (double)(nb - 1) * max_t) + t_sync + t_upd;
       C = dollars / 3600.0 * T + comm;
+      if (a.has_bound) {
+        if (a.objective == 0) { if (C > a.bound) mask |= 32u; }
+        else if (1.0 / T < a.bound) mask |= 32u;
+      }
+    }
+  }
+  if (lane == 0) {
+    if (a.T) a.T[ci] = T;
+    if (a.C) a.C[ci] = C;
+    if (a.mem) a.mem[ci] = mask == 0xFFFFFFFFu ? 0 : peak;
+    if (a.mask) a.mask[ci] = mask;
+  }
+}
+
+// ------------------------------------------------------------------ a pool per replica
+
+struct ReplicaArgs {
+  uint64_t count;
+  const int32_t *desc;    // [count][5] pp index, partition, tp index, dp index, mb index
+  const int32_t *pools;   // [count][stride]: the pool of replica r of stage i at i * D + r
+  uint64_t stride;
+  const SearchPP *pps;
+  int n_pp;
+  int objective, has_bound;
+  double bound;
+  double *T, *C;
+  uint64_t *mem;
+  uint32_t *mask;
+};
+
+__device__ __forceinline__ double wave_min_f64(double v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v = fmin(v, __shfl_xor(v, off));
+  return v;
+}
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+// The plan tuple in full (Sec. 4.2: D tuples per stage): replica r of all stages is pipeline r,
+// T_iter = max over the D pipelines + T_sync + T_update (Sec. 4.3); the all-reduce of a stage is
+// a ring through its replicas in their order at the pace of its slowest link; traffic between
+// zones is paid for where a pipeline or a ring crosses; a pool's quota counts the GPUs it gives.
+// One wave per plan: lane l takes the pipelines l, l + 64, ... and walks their stages in order,
+// so a pipeline's sum is taken in stage order.  A descriptor or pool out of range, or fewer
+// than P x D entries per plan, yields mask = 0xFFFFFFFF, T = C = +inf, mem = 0.
+__global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_replicas(DevPlan pl, ReplicaArgs a) {
+  __shared__ int s_cnt[kPlaceWaves][kSearchMaxPools];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const uint64_t ci = (uint64_t)blockIdx.x * kPlaceWaves + wv;
+  if (ci >= a.count) return;  // whole waves leave; no barrier below
+  const int G = pl.G, Z = pl.Z, ZG = pl.ZGr, MB = pl.MB, TP = pl.TP, DP = pl.DP;
+  const int32_t *d = a.desc + ci * 5;
+  const int ip = d[0], q = d[1], it = d[2], id = d[3], im = d[4];
+  double T = __builtin_huge_val(), C = T;
+  uint64_t peak = 0;
+  uint32_t mask = 0xFFFFFFFFu;
+  bool valid = ip >= 0 && ip < a.n_pp && it >= 0 && it < TP && id >= 0 && id < DP && im >= 0 && im < MB && q >= 0;
+  if (valid) valid = q < a.pps[ip].n_part;
+  const int P = valid ? a.pps[ip].P : 0;
+  const int64_t D = valid ? (int64_t)pl.dpv[id] : 0;
+  if (valid && (uint64_t)P * (uint64_t)D > a.stride) valid = false;
+  const int32_t *pools = a.pools + ci * a.stride;
+  int *cnt = s_cnt[wv];
+  if (valid) {
+    for (int p = lane; p < kSearchMaxPools; p += 64) cnt[p] = 0;
+    bool bad = false;
+    for (int64_t k = lane; k < (int64_t)P * D; k += 64)
+      if (pools[k] < 0 || pools[k] >= ZG) bad = true;
+    if (__builtin_amdgcn_ballot_w64(bad) != 0) valid = false;
+  }
+  if (valid) {
+    mask = 0;
+    const uint32_t rs = a.pps[ip].rs0 + (uint32_t)q * (uint32_t)P;
+    const int64_t nb = pl.nb[im * DP + id];
+    const int64_t tp = pl.tpv[it];
+    if (nb == 0) {
+      mask = 4u;
+    } else {
+      const double p2p = (double)pl.p2p[im];
+      __builtin_amdgcn_wave_barrier();
+      double t_pipe = 0.0, t_upd = 0.0, t_sync = 0.0, rent = 0.0, traffic = 0.0;
+      uint32_t oom = 0, h1 = 0;
+      // the pipelines
+      for (int64_t r = lane; r < D; r += 64) {
+        double total = 0.0, slowest = 0.0;
+        for (int i = 0; i < P; ++i) {
+          const int p = pools[(int64_t)i * D + r], g = p % G, z = p / G;
+          atomicAdd(&cnt[p], (int)tp);  // GPUs the pool gives
+          const size_t si = (size_t)rs + i;
+          const uint64_t bytes = stage_bytes_of(pl.st_params[si], pl.st_n[si], pl.bpp, i, P, (int)tp, nb, pl.act[im * TP + it]);
+          const uint64_t m = bytes + pl.res[g];
+          if (m > pl.cap[g]) oom = 1u;
+          if (tp > pl.node[g]) h1 = 1u;
+          peak = m > peak ? m : peak;
+          double x = 0.0;
+          if (i < P - 1) {
+            const int zn = pools[(int64_t)(i + 1) * D + r] / G;
+            x += p2p / link_bw(pl, z, zn, p2p);
+            if (pl.egress && zn != z)  // one replica's microbatches, both directions
+              traffic += (double)nb * p2p * (pl.egress[z * Z + zn] + pl.egress[zn * Z + z]);
+          }
+          if (i > 0) x += p2p / link_bw(pl, z, pools[(int64_t)(i - 1) * D + r] / G, p2p);
+          const double ts = pl.st_c[((si * G + g) * MB + im) * TP + it] + x;
+          total += ts;
+          slowest = fmax(slowest, ts);
+          t_upd = fmax(t_upd, pl.st_u[(si * G + g) * TP + it]);
+          rent += (double)tp * pl.price[g];
+        }
+        t_pipe = fmax(t_pipe, total + (double)(nb - 1) * slowest);
+      }
+      // the rings
+      if (D > 1)
+        for (int i = 0; i < P; ++i) {  // uniform
+          const uint64_t params = pl.st_params[rs + i];
+          const uint64_t shard = (params + (uint64_t)tp - 1) / (uint64_t)tp;
+          const double buffer = (double)shard * (double)pl.gb;
+          const double ring_bytes = 2.0 * (double)(D - 1) / (double)D * buffer;
+          double link = __builtin_huge_val();
+          for (int64_t r = lane; r < D; r += 64) {
+            const int zr = pools[(int64_t)i * D + r] / G, zs = pools[(int64_t)i * D + (r + 1 == D ? 0 : r + 1)] / G;
+            link = fmin(link, link_bw(pl, zr, zs, buffer));
+            if (pl.egress && zr != zs) traffic += ring_bytes * pl.egress[zr * Z + zs];
+          }
+          t_sync = fmax(t_sync, ring_bytes / wave_min_f64(link));
+        }
+      if (__builtin_amdgcn_ballot_w64(oom != 0) != 0) mask |= 1u;
+      if (__builtin_amdgcn_ballot_w64(h1 != 0) != 0) mask |= 8u;
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        const uint64_t o = __shfl_xor((unsigned long long)peak, off);
+        peak = o > peak ? o : peak;
+      }
+      t_pipe = wave_max_f64(t_pipe);
+      t_upd = wave_max_f64(t_upd);
+      rent = wave_sum_f64(rent);
+      traffic = wave_sum_f64(traffic);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      bool over = false;
+      for (int p = lane; p < ZG; p += 64)
+        if ((int64_t)cnt[p] > (int64_t)pl.avail[p]) over = true;
+      if (__builtin_amdgcn_ballot_w64(over) != 0) mask |= 2u;
+      T = (t_pipe + t_sync) + t_upd;
+      C = rent / 3600.0 * T + traffic;
       if (a.has_bound) {
         if (a.objective == 0) { if (C > a.bound) mask |= 32u; }
         else if (1.0 / T < a.bound) mask |= 32u;

@@ -551,3 +551,107 @@ def test_a_problem_with_a_tp_per_segment_is_searched_like_the_plain_one(torch_cu
         assert own.found and _key_of(own, objective) <= _key(flat, objective) * (1 + 1e-9)
     finally:
         plan.destroy()
+
+
+# ---- every replica of every stage names its pool (uneven splits, any number of pools) --------
+
+def random_replica_placements(prob, rng, n):
+    zg = prob.n_zones * prob.n_types
+    stride = int(max(prob.pp_values)) * int(max(prob.dp_values))
+    desc = np.zeros((n, 5), np.int32)
+    pools = np.zeros((n, stride), np.int32)
+    for k in range(n):
+        ip = int(rng.integers(0, len(prob.pp_values)))
+        desc[k] = (ip, rng.integers(0, prob.n_partitions[ip]), rng.integers(0, len(prob.tp_values)),
+                   rng.integers(0, len(prob.dp_values)), rng.integers(0, len(prob.mb_values)))
+        P, D = int(prob.pp_values[ip]), int(prob.dp_values[desc[k, 3]])
+        # stages in a few runs of pools; inside a stage the replicas in one to three uneven blocks
+        cuts = np.sort(rng.integers(0, P + 1, int(rng.integers(0, 3))))
+        base = rng.integers(0, zg, len(cuts) + 1)[np.searchsorted(cuts, np.arange(P), side="right")]
+        grid = np.repeat(base[:, None], D, axis=1)
+        for i in range(P):
+            if D > 1 and rng.random() < 0.4:
+                for _ in range(int(rng.integers(1, 3))):
+                    lo = int(rng.integers(0, D))
+                    grid[i, lo:int(rng.integers(lo, D + 1))] = rng.integers(0, zg)
+        pools[k, :P * D] = grid.reshape(-1)
+    return desc, pools, stride
+
+
+@pytest.mark.parametrize("make", [
+    lambda: _tiny(1), lambda: _tiny(2, n_types=3, n_zones=3), lambda: W.config2(), lambda: W.config3(),
+    lambda: (lambda p: p.with_bw_poly(W.bandwidth_poly(p)))(_tiny(4, n_zones=3)),
+])
+def test_placements_with_a_pool_per_replica_match_the_oracle(torch_cuda, make):
+    prob = make()
+    plan, orc = _plan(prob), Oracle(prob)
+    rng = np.random.default_rng(17)
+    torch = torch_cuda
+    try:
+        n = 1200 if prob.n_layers <= 24 else 500
+        desc, pools, stride = random_replica_placements(prob, rng, n)
+        dev = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to("cuda:0")
+        d_desc, d_pools = dev(desc), dev(pools)
+        for objective, bound in ((MAX_THROUGHPUT, None), (MIN_COST, 0.7), (MAX_THROUGHPUT, 0.05)):
+            t = torch.empty(n, dtype=torch.float64, device="cuda:0")
+            c = torch.empty(n, dtype=torch.float64, device="cuda:0")
+            m = torch.empty(n, dtype=torch.int64, device="cuda:0")
+            k = torch.empty(n, dtype=torch.int32, device="cuda:0")
+            plan.eval_replica_placements(n, d_desc, d_pools, stride, objective, bound, t, c, m, k,
+                                         stream=torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            t, c = t.cpu().numpy(), c.cpu().numpy()
+            m, k = m.cpu().numpy().view(np.uint64), k.cpu().numpy().view(np.uint32)
+            valid = uneven = 0
+            for i in range(n):
+                P, D = int(prob.pp_values[desc[i, 0]]), int(prob.dp_values[desc[i, 3]])
+                grid = pools[i, :P * D].reshape(P, D)
+                e = orc.eval_replica_assignment(desc[i, 0], desc[i, 1], desc[i, 3], desc[i, 4], desc[i, 2],
+                                                grid, objective, bound)
+                tight = bound is not None and np.isfinite(e.iter_time) and abs(
+                    (e.cost if objective == MAX_THROUGHPUT else 1.0 / e.iter_time) / bound - 1.0) < 1e-9
+                if not tight:
+                    assert k[i] == e.mask, (i, desc[i], grid)
+                assert m[i] == e.peak_mem
+                if np.isinf(e.iter_time):
+                    assert np.isinf(t[i]) and np.isinf(c[i])
+                else:
+                    assert t[i] == pytest.approx(e.iter_time, rel=1e-12)
+                    assert c[i] == pytest.approx(e.cost, rel=1e-12)
+                valid += e.mask == 0
+                uneven += e.mask == 0 and any(len(set(row)) > 1 for row in grid)
+            if bound is None and prob.n_layers <= 8:
+                assert valid > 10 and uneven > 3
+        # agreeing replicas: the evaluator with one pool per stage
+        P_max, D_max = int(max(prob.pp_values)), int(max(prob.dp_values))
+        d2, p2 = random_placements(prob, rng, 300, P_max)
+        rep = np.zeros((300, stride), np.int32)
+        for i in range(300):
+            P, D = int(prob.pp_values[d2[i, 0]]), int(prob.dp_values[d2[i, 3]])
+            rep[i, :P * D] = np.repeat(p2[i, :P, None], D, axis=1).reshape(-1)
+        t0, c0, m0, k0 = gpu_eval_placements(torch, plan, d2, p2)
+        t1 = torch.empty(300, dtype=torch.float64, device="cuda:0"); c1 = torch.empty_like(t1)
+        m1 = torch.empty(300, dtype=torch.int64, device="cuda:0"); k1 = torch.empty(300, dtype=torch.int32, device="cuda:0")
+        plan.eval_replica_placements(300, dev(d2), dev(rep), stride, MAX_THROUGHPUT, None, t1, c1, m1, k1,
+                                     stream=torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert np.array_equal(k0, k1.cpu().numpy().view(np.uint32)) and np.array_equal(m0, m1.cpu().numpy().view(np.uint64))
+        fin = np.isfinite(t0)
+        assert np.array_equal(t0[fin], t1.cpu().numpy()[fin])  # the same sums in the same order
+        assert np.allclose(c0[fin], c1.cpu().numpy()[fin], rtol=1e-13, atol=0)
+        # too few entries per plan, a pool out of range
+        bad = rep[:2].copy()
+        bad[1, 0] = prob.n_zones * prob.n_types
+        small = int(prob.pp_values[d2[0, 0]]) * int(prob.dp_values[d2[0, 3]]) - 1
+        kb = torch.empty(2, dtype=torch.int32, device="cuda:0")
+        plan.eval_replica_placements(2, dev(d2[:2]), dev(bad), stride, d_mask=kb,
+                                     stream=torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert kb.cpu().numpy().view(np.uint32)[1] == 0xFFFFFFFF
+        if small >= 1:
+            plan.eval_replica_placements(1, dev(d2[:1]), dev(rep[:1, :small]), small, d_mask=kb,
+                                         stream=torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            assert kb.cpu().numpy().view(np.uint32)[0] == 0xFFFFFFFF
+    finally:
+        plan.destroy()
