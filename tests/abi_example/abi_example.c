@@ -143,6 +143,55 @@ int main(void) {
     CHECK(h_cl[i] / h_ev[i] > 0.5 && h_cl[i] / h_ev[i] < 1.5);
   }
 
+  /* a pool per stage: the search, with the enumerated space's best plan as the incumbent, finds a
+   * plan that is no worse; the simulator for listed plans gives the same plan the same values,
+   * also when every replica names its pool */
+  sailor_search_options so;
+  memset(&so, 0, sizeof so);
+  so.beam_width = 32;
+  so.use_incumbent = 2;
+  static sailor_stage_plan sp;
+  CHECK(sailor_search(plan, SAILOR_MAX_THROUGHPUT, NULL, &so, &sp, NULL) == SAILOR_OK);
+  CHECK(sp.found == 1 && sp.mask == 0 && sp.incumbent_used == 1);
+  CHECK(sp.iter_time_s <= best.iter_time_s * (1.0 + 2e-9) && sp.eval_time_s == sp.iter_time_s);
+  {
+    int32_t h_desc[5] = {sp.pp_index, sp.partition, sp.tp_index, sp.dp_index, sp.mb_index};
+    int32_t *h_rep = (int32_t *)malloc(sizeof(int32_t) * (size_t)sp.pp * (size_t)sp.dp);
+    CHECK(h_rep != NULL);
+    for (int i = 0; i < sp.pp; ++i)
+      for (int r = 0; r < sp.dp; ++r) h_rep[i * sp.dp + r] = sp.pool[i];
+    int32_t *d_desc = NULL, *d_pool = NULL, *d_rep = NULL;
+    double *d_two = NULL, h_two[2];
+    CHECK(hipMalloc((void **)&d_desc, sizeof h_desc) == hipSuccess);
+    CHECK(hipMalloc((void **)&d_pool, sizeof(int32_t) * (size_t)sp.pp) == hipSuccess);
+    CHECK(hipMalloc((void **)&d_rep, sizeof(int32_t) * (size_t)sp.pp * (size_t)sp.dp) == hipSuccess);
+    CHECK(hipMalloc((void **)&d_two, sizeof h_two) == hipSuccess);
+    CHECK(hipMemcpy(d_desc, h_desc, sizeof h_desc, hipMemcpyHostToDevice) == hipSuccess);
+    CHECK(hipMemcpy(d_pool, sp.pool, sizeof(int32_t) * (size_t)sp.pp, hipMemcpyHostToDevice) == hipSuccess);
+    CHECK(hipMemcpy(d_rep, h_rep, sizeof(int32_t) * (size_t)sp.pp * (size_t)sp.dp, hipMemcpyHostToDevice) == hipSuccess);
+    CHECK(sailor_eval_placements(plan, 1, d_desc, d_pool, NULL, NULL, (uint32_t)sp.pp, SAILOR_MAX_THROUGHPUT, NULL,
+                                 d_two, NULL, NULL, NULL, NULL) == SAILOR_OK);
+    CHECK(sailor_eval_replica_placements(plan, 1, d_desc, d_rep, (uint64_t)sp.pp * (uint64_t)sp.dp,
+                                         SAILOR_MAX_THROUGHPUT, NULL, d_two + 1, NULL, NULL, NULL, NULL) == SAILOR_OK);
+    CHECK(hipDeviceSynchronize() == hipSuccess);
+    CHECK(hipMemcpy(h_two, d_two, sizeof h_two, hipMemcpyDeviceToHost) == hipSuccess);
+    CHECK(h_two[0] == sp.iter_time_s && h_two[1] == sp.iter_time_s);
+    hipFree(d_desc); hipFree(d_pool); hipFree(d_rep); hipFree(d_two);
+    free(h_rep);
+  }
+
+  /* a re-plan with the minima of the last pass kept: the same answer as before for the same table */
+  {
+    sailor_result again;
+    uint32_t evaluated = 0, units = 0;
+    CHECK(sailor_plan_set_incremental(plan, 1) == SAILOR_OK);
+    CHECK(sailor_best_plan(plan, SAILOR_MAX_THROUGHPUT, NULL, &again, NULL) == SAILOR_OK);
+    CHECK(sailor_best_plan(plan, SAILOR_MAX_THROUGHPUT, NULL, &again, NULL) == SAILOR_OK);
+    CHECK(again.index == best.index && again.iter_time_s == best.iter_time_s);
+    CHECK(sailor_plan_last_scan(plan, &evaluated, &units) == SAILOR_OK && evaluated == 0 && units > 0);
+    CHECK(sailor_plan_set_incremental(plan, 0) == SAILOR_OK);
+  }
+
   /* no GPUs, no plan; errors are statuses, not crashes */
   memset(avail, 0, sizeof avail);
   CHECK(sailor_plan_set_avail(plan, avail) == SAILOR_OK);
