@@ -966,6 +966,7 @@ int so_eval_replica_assignment(const so_ctx *c, int pp_idx, int partition, int d
 
   /* the D pipelines, each with its own stage times and transfers */
   const double msg = (double)p->p2p_bytes[mb_idx];
+  const double *fee = p->egress_per_byte; /* $/byte between zones, or NULL */
   double t_pipe = 0.0, t_update = 0.0, traffic_cost = 0.0, rent = 0.0;
   for (int64_t r = 0; r < D; ++r) {
     double total = 0.0, slowest = 0.0;
@@ -977,9 +978,8 @@ int so_eval_replica_assignment(const so_ctx *c, int pp_idx, int partition, int d
       if (i < P - 1) {
         const int zn = pools[(int64_t)(i + 1) * D + r] / G;
         moves += msg / link_bandwidth(p, z, zn, msg);
-        if (p->egress_per_byte && zn != z) /* one replica's microbatches, both directions */
-          traffic_cost += (double)n_micro * msg *
-                          (p->egress_per_byte[(size_t)z * Z + zn] + p->egress_per_byte[(size_t)zn * Z + z]);
+        if (fee && zn != z) /* one replica's microbatches, both directions */
+          traffic_cost += (double)n_micro * msg * (fee[(size_t)z * Z + zn] + fee[(size_t)zn * Z + z]);
       }
       if (i > 0) moves += msg / link_bandwidth(p, z, pools[(int64_t)(i - 1) * D + r] / G, msg);
       t += moves;
@@ -1004,7 +1004,7 @@ int so_eval_replica_assignment(const so_ctx *c, int pp_idx, int partition, int d
         const int zr = pools[(int64_t)i * D + r] / G, zs = pools[(int64_t)i * D + (r + 1) % D] / G;
         const double w = link_bandwidth(p, zr, zs, buffer);
         if (w < link) link = w;
-        if (p->egress_per_byte && zr != zs) traffic_cost += ring_bytes * p->egress_per_byte[(size_t)zr * Z + zs];
+        if (fee && zr != zs) traffic_cost += ring_bytes * fee[(size_t)zr * Z + zs];
       }
       const double t = ring_bytes / link;
       if (t > t_allreduce) t_allreduce = t;

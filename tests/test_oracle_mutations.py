@@ -61,8 +61,8 @@ MUTANTS = [
     ("test_oracle_replica_placements.py", "if (w < link) link = w;", "if (w > link || link == INFINITY) link = w;"),
     ("test_oracle_replica_placements.py", "if (t_this > t_pipe) t_pipe = t_this;", "t_pipe = t_this;"),
     ("test_oracle_replica_placements.py", "gpus[a] += tp;", "gpus[a] += 1;"),
-    ("test_oracle_replica_placements.py", "traffic_cost += ring_bytes * p->egress_per_byte[(size_t)zr * Z + zs];",
-     "traffic_cost += ring_bytes * p->egress_per_byte[(size_t)zs * Z + zr];"),
+    ("test_oracle_replica_placements.py", "traffic_cost += ring_bytes * fee[(size_t)zr * Z + zs];",
+     "traffic_cost += ring_bytes * fee[(size_t)zs * Z + zr];"),
 ]
 
 
