@@ -655,3 +655,58 @@ def test_placements_with_a_pool_per_replica_match_the_oracle(torch_cuda, make):
             assert kb.cpu().numpy().view(np.uint32)[0] == 0xFFFFFFFF
     finally:
         plan.destroy()
+
+
+# ---- the limits of the search: 64 pools, 255 stages, nothing to evaluate ----------------------
+
+def test_search_at_its_limits(torch_cuda):
+    from paper_2504_17096_amd.binding import SAILOR_EINVAL, SailorError
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    # 8 zones x 8 types = 64 pools: 64 choices per stage, 4 096 with split stages, 192 with degrees
+    wide = _tiny(9, n_layers=3, n_types=8, n_zones=8, partitions_per_pp=1)
+    plan, orc = _plan(wide), Oracle(wide)
+    try:
+        for objective in OBJECTIVES:
+            check_same(plan.search(8, objective, stream=stream), orc.search_beam(8, objective), objective)
+            check_same_split(plan.search(3, objective, allow_split=True, stream=stream),
+                             orc.search_beam(3, objective, allow_split=True), objective, orc)
+            check_same_tp(plan.search(5, objective, stage_tp=True, stream=stream),
+                          orc.search_beam(5, objective, stage_tp=True), objective, orc)
+        # nothing to evaluate is not an error
+        plan.eval_placements(0, None, None, 1)
+        plan.eval_replica_placements(0, None, None, 1)
+    finally:
+        plan.destroy()
+    # 255 stages of one or two layers: the deepest pipeline the search takes, all three forms
+    rng = np.random.default_rng(255)
+    L = 256
+    deep = make_problem(n_layers=L, n_types=2, n_zones=2, mb_list=(1, 2), tp_list=(1, 2), dp_list=(1, 2, 4),
+                        pp_list=[64, 255], global_batch=64, uniform_layers=False,
+                        partitions={255: [[2] + [1] * 254]},
+                        t_fwd=rng.uniform(0.5e-3, 2e-3, (2, 2, 2, L)), t_bwd=rng.uniform(1e-3, 4e-3, (2, 2, 2, L)),
+                        t_upd=rng.uniform(1e-5, 3e-5, (2, 2, L)),
+                        layer_params=rng.integers(1_000_000, 3_000_000, L).astype(np.uint64),
+                        act=rng.integers(1_000_000, 9_000_000, (2, 2)).astype(np.uint64), p2p=2_000_000,
+                        cap=np.array([2, 1], np.uint64) * np.uint64(1 << 30), avail=np.array([[600, 300], [400, 500]]),
+                        bw=np.array([[1e10, 1e9], [2e9, 1e10]]), egress=np.array([[0, 2e-11], [3e-11, 0]]),
+                        price=np.array([3.0, 1.5]))
+    plan, orc = _plan(deep), Oracle(deep)
+    try:
+        check_same(plan.search(6, MAX_THROUGHPUT, stream=stream), orc.search_beam(6, MAX_THROUGHPUT), MAX_THROUGHPUT)
+        check_same_split(plan.search(2, MIN_COST, allow_split=True, stream=stream),
+                         orc.search_beam(2, MIN_COST, allow_split=True), MIN_COST, orc)
+        check_same_tp(plan.search(4, MAX_THROUGHPUT, stage_tp=True, stream=stream),
+                      orc.search_beam(4, MAX_THROUGHPUT, stage_tp=True), MAX_THROUGHPUT, orc)
+    finally:
+        plan.destroy()
+    # one stage more and the search declines
+    from dataclasses import replace
+    too_deep = replace(deep, pp_values=np.asarray([64, 256], np.int32), n_partitions=np.asarray([1, 1], np.int32),
+                       partition_layers=np.asarray([4] * 64 + [1] * 256, np.int32))
+    plan = _plan(too_deep)
+    try:
+        with pytest.raises(SailorError) as err:
+            plan.search(4, stream=stream)
+        assert err.value.status == SAILOR_EINVAL
+    finally:
+        plan.destroy()
