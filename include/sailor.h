@@ -48,6 +48,12 @@
  * segments of the plan together take from it, else OVER_QUOTA; the rent is the mean of the
  * two prices.
  *
+ * Beyond the enumerated space (further down): sailor_search places the stages of a pipeline one
+ * by one -- a pool per stage, optionally a second pool for half of its replicas or a TP degree of
+ * its own -- with lower bounds and a beam (Sec. 4.2.1, 4.2.2); sailor_eval_placements and
+ * sailor_eval_replica_placements run the simulator of Sec. 4.3 on listed plans of that kind, down
+ * to a pool per replica of every stage; sailor_simulate_1f1b replays a plan's 1F1B schedule op by op.
+ *
  * Mask bits of an evaluated candidate (0 = valid plan)
  *   bit 0 OOM               some stage's worker exceeds its GPU's memory (Sec. 4.3)
  *   bit 1 OVER_QUOTA        a pool needs more GPUs than are available (Sec. 4)
