@@ -449,7 +449,8 @@ sailor_status sailor_eval_placements(sailor_plan *plan, uint64_t count, const in
  * where a ring link crosses (that direction's price).  Memory and node size hold for every
  * replica's GPU type, a pool's quota counts the GPUs it gives, one TP degree per plan.  With all
  * replicas of a stage on one pool the values are those of sailor_eval_placements.
- * Outputs and errors as for sailor_eval_placements (an invalid row also when stride < P x D).
+ * Outputs and errors as for sailor_eval_placements (an invalid row also when stride < P x D or
+ * D > 65 536).
  * Asynchronous on hip_stream.  SAILOR_EINVAL for mixed_types problems or more than 64 pools. */
 sailor_status sailor_eval_replica_placements(sailor_plan *plan, uint64_t count, const int32_t *d_desc,
                                              const int32_t *d_pools, uint64_t stride,

@@ -918,6 +918,8 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl
 
 // ------------------------------------------------------------------ a pool per replica
 
+constexpr int64_t kReplicaMaxDegree = 65536;  // replicas per stage a listed plan may name one by one
+
 struct ReplicaArgs {
   uint64_t count;
   const int32_t *desc;    // [count][5] pp index, partition, tp index, dp index, mb index
@@ -949,8 +951,8 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
 // a ring through its replicas in their order at the pace of its slowest link; traffic between
 // zones is paid for where a pipeline or a ring crosses; a pool's quota counts the GPUs it gives.
 // One wave per plan: lane l takes the pipelines l, l + 64, ... and walks their stages in order,
-// so a pipeline's sum is taken in stage order.  A descriptor or pool out of range, or fewer
-// than P x D entries per plan, yields mask = 0xFFFFFFFF, T = C = +inf, mem = 0.
+// so a pipeline's sum is taken in stage order.  A descriptor or pool out of range, fewer than
+// P x D entries per plan or more than 65 536 replicas yield mask = 0xFFFFFFFF, T = C = +inf, mem = 0.
 __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_replicas(DevPlan pl, ReplicaArgs a) {
   __shared__ int s_cnt[kPlaceWaves][kSearchMaxPools];
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -966,7 +968,7 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_replicas(DevPlan pl, 
   if (valid) valid = q < a.pps[ip].n_part;
   const int P = valid ? a.pps[ip].P : 0;
   const int64_t D = valid ? (int64_t)pl.dpv[id] : 0;
-  if (valid && (uint64_t)P * (uint64_t)D > a.stride) valid = false;
+  if (valid && (D > kReplicaMaxDegree || (uint64_t)P * (uint64_t)D > a.stride)) valid = false;
   const int32_t *pools = a.pools + ci * a.stride;
   int *cnt = s_cnt[wv];
   if (valid) {
