@@ -342,7 +342,7 @@ sailor_status sailor_simulate_1f1b_static(sailor_plan *plan, uint64_t count,
 
 /* Options of sailor_search. */
 typedef struct {
-  int32_t beam_width;     /* 1 .. 256: longest frontier kept per sub-problem */
+  int32_t beam_width;     /* 1 .. 1024: longest frontier kept per sub-problem */
   int32_t max_runs;       /* 0: any placement; n: at most n runs of consecutive stages on one pool
                              (3 = the candidate space of sailor_best_plan when that space allows
                              three segments at every depth) */

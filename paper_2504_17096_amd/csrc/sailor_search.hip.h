@@ -31,7 +31,7 @@
 namespace sailor {
 
 constexpr int kSearchThreads = 256;
-constexpr int kSearchMaxBeam = 256;    // longest frontier a sub-problem keeps
+constexpr int kSearchMaxBeam = 1024;   // longest frontier a sub-problem keeps (half of kSearchBuf at most)
 constexpr int kSearchBuf = 2048;       // extensions buffered between two sorts
 constexpr int kSearchMaxStages = 255;  // placements count stages per pool in a byte
 constexpr int kSearchMaxPools = 64;

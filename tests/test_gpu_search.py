@@ -209,7 +209,7 @@ def test_search_rejects_what_it_does_not_cover(torch_cuda):
             plan.destroy()
     plan = _plan(_tiny(1))
     try:
-        for width in (0, 257):
+        for width in (0, 1025):
             with pytest.raises(SailorError):
                 plan.search(width)
         # nothing valid: no GPUs at all
@@ -708,5 +708,23 @@ def test_search_at_its_limits(torch_cuda):
         with pytest.raises(SailorError) as err:
             plan.search(4, stream=stream)
         assert err.value.status == SAILOR_EINVAL
+    finally:
+        plan.destroy()
+
+
+def test_a_beam_wider_than_one_pass_of_the_workgroup(torch_cuda):
+    # 300 and 1 024 states per frontier: four states per thread when the next frontier is written,
+    # and sorts in the middle of a level (the buffer between two sorts holds 2 048 extensions)
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    prob = _tiny(12, n_layers=8, n_types=3, n_zones=3, partitions_per_pp=1)
+    plan, orc = _plan(prob), Oracle(prob)
+    try:
+        for width in (300, 1024):
+            check_same(plan.search(width, MAX_THROUGHPUT, stream=stream), orc.search_beam(width, MAX_THROUGHPUT),
+                       MAX_THROUGHPUT)
+            check_same_tp(plan.search(width, MIN_COST, stage_tp=True, stream=stream),
+                          orc.search_beam(width, MIN_COST, stage_tp=True), MIN_COST, orc)
+        check_same_split(plan.search(300, MAX_THROUGHPUT, allow_split=True, max_runs=3, stream=stream),
+                         orc.search_beam(300, MAX_THROUGHPUT, allow_split=True, max_runs=3), MAX_THROUGHPUT, orc)
     finally:
         plan.destroy()
