@@ -455,6 +455,40 @@ def main() -> int:
         p.destroy()
         return out
 
+    # independent queries in flight: one plan, one stream and one host thread each (a serving
+    # loop); the small kernels behind one query's scan then overlap the other queries' scans
+    def in_flight(k, n=200):
+        import threading
+        plans = [Plan(prob) for _ in range(k)]
+        streams = [torch.cuda.Stream() for _ in range(k)]
+        for p in plans:
+            p.set_incremental(False)
+        took = [0.0] * k
+        gate = threading.Barrier(k)
+
+        def run(i):
+            out = (sailor_result * K)()
+            for _ in range(10):
+                plans[i].topk_raw(K, MAX_THROUGHPUT, budget, out, streams[i].cuda_stream)
+            gate.wait()
+            t0 = time.perf_counter()
+            for _ in range(n):
+                plans[i].topk_raw(K, MAX_THROUGHPUT, budget, out, streams[i].cuda_stream)
+            took[i] = time.perf_counter() - t0
+
+        threads = [threading.Thread(target=run, args=(i,)) for i in range(k)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+        for p in plans:
+            p.destroy()
+        return {"queries_in_flight": k, "ms_per_query_per_thread": max(took) / n * 1e3,
+                "candidates_per_s_in_all": k * n * prob_n / max(took)}
+
+    prob_n = n
+    serving = [in_flight(2), in_flight(4)]
+
     search = {"cfg3": searched(prob5, 64, False), "cfg4": searched(prob, 64, False),
               "cfg3_split": searched(prob5, 32, True), "cfg4_split": searched(prob, 16, True),
               "cfg3_stage_tp": searched(prob5, 64, False, True), "cfg4_stage_tp": searched(prob, 32, False, True)}
@@ -515,6 +549,7 @@ def main() -> int:
                   "plan_create_ms": create_ms, "plan_create_warm_ms": create_warm_ms,
                   "replan_stream": replan,
                   "per_segment_tp": segtp, "mixed_types": mixed, "placement_search": search,
+                  "independent_queries_in_flight": serving,
                   "event_schedule_top64": event_sched,
                   "survivors_refined_valid": list(counts), "best_index": best.index,
                   "top1_index": top1_index},
