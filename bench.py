@@ -318,6 +318,7 @@ def main() -> int:
     assert n_found == K, n_found
     top1_index = int(buf[0].index)
     counts = plan.last_counts()
+    units_evaluated, units_total = plan.last_scan()  # the rest fell to their cost bounds
 
     # the selected plans' 1F1B schedules event by event, against the closed form the
     # evaluator uses for T_pp (outside the timed region)
@@ -344,6 +345,18 @@ def main() -> int:
         best = plan.best_plan(objective=MAX_THROUGHPUT, bound=budget, stream=stream)
     best_ms = (time.perf_counter() - t0) / reps * 1e3
 
+    # the timed query once more with a budget that no plan exceeds: nothing falls to a cost
+    # bound, only invalid plans are discarded (outside the timed region)
+    unbound = None
+    if not args.only_kernels:
+        for _ in range(3):
+            plan.topk_raw(K, MAX_THROUGHPUT, 1e30, buf, stream)
+        u_ms, u_scan_ms, u_found = timed_steps(
+            plan, lambda: plan.topk_raw(K, MAX_THROUGHPUT, 1e30, buf, stream), 16, torch.cuda.synchronize)
+        unbound = {"time_to_top64_ms": u_ms, "scan_kernel_ms": u_scan_ms, "found": u_found,
+                   "units_evaluated": plan.last_scan()[0]}
+        step()  # (the last query of the plan is the timed one again)
+
     # per-candidate outputs for the whole space (20 B per candidate)
     tt = torch.empty(n, dtype=torch.float32, device="cuda:0")
     cc = torch.empty(n, dtype=torch.float32, device="cuda:0")
@@ -360,19 +373,31 @@ def main() -> int:
     plan.set_timing(0)
     del tt, cc, mm, kk
 
-    # the same query where discarding invalid plans cannot help: resources never bind, nearly
-    # every candidate is a valid plan
+    # the same kind of query where nothing can be discarded: resources never bind, nearly every
+    # candidate is a valid plan, and the budget is one that no plan exceeds (so no piece of the
+    # space is ruled out by its cost bound either): every candidate's arithmetic is done
     dense_prob = workloads.config4_dense()
     pd = Plan(dense_prob)
     pd.set_incremental(False)
-    budget_d = 1.2 * pd.best_plan(objective=MIN_COST, stream=stream).cost_per_iter
+    budget_never = 1e30
     pd.set_timing(1)
     for _ in range(3):
-        pd.topk_raw(K, MAX_THROUGHPUT, budget_d, buf, stream)
+        pd.topk_raw(K, MAX_THROUGHPUT, budget_never, buf, stream)
     dense_ms, dense_scan_ms, dense_found = timed_steps(
-        pd, lambda: pd.topk_raw(K, MAX_THROUGHPUT, budget_d, buf, stream), 16, torch.cuda.synchronize)
+        pd, lambda: pd.topk_raw(K, MAX_THROUGHPUT, budget_never, buf, stream), 16, torch.cuda.synchronize)
     dense_counts = pd.last_counts()
-    dense_units = pd.last_scan()[1]
+    dense_evaluated, dense_units = pd.last_scan()
+    assert dense_evaluated == dense_units, (dense_evaluated, dense_units)
+    dense_budget = None
+    if not args.only_kernels:
+        # ... and under the timed query's kind of budget, where whole pieces fall to their bound
+        budget_d = 1.2 * pd.best_plan(objective=MIN_COST, stream=stream).cost_per_iter
+        for _ in range(3):
+            pd.topk_raw(K, MAX_THROUGHPUT, budget_d, buf, stream)
+        b_ms, b_scan_ms, b_found = timed_steps(
+            pd, lambda: pd.topk_raw(K, MAX_THROUGHPUT, budget_d, buf, stream), 16, torch.cuda.synchronize)
+        dense_budget = {"time_to_top64_ms": b_ms, "scan_kernel_ms": b_scan_ms, "found": b_found,
+                        "units_evaluated": pd.last_scan()[0], "units": dense_units}
     pd.destroy()
 
     if args.copy_probe:
@@ -539,12 +564,15 @@ def main() -> int:
         "roofline_eval_batch": roof_eval,
         "extra": {"time_to_top64_ms": ms_per_step, "time_to_best_plan_ms": best_ms,
                   "scan_kernel_ms": scan_ms,
+                  "pieces_of_the_space": {"evaluated": units_evaluated, "total": units_total},
+                  "same_query_with_a_budget_that_never_binds": unbound,
                   "every_candidate_evaluated": {
                       "eval_batch_ms": eval_ms,
                       "eval_batch_candidates_per_s": n / (eval_ms * 1e-3),
                       "dense_time_to_top64_ms": dense_ms, "dense_scan_kernel_ms": dense_scan_ms,
                       "dense_candidates_per_s": n / (dense_ms * 1e-3),
                       "dense_found": dense_found,
+                      "dense_under_budget_of_1p2x_cheapest": dense_budget,
                       "dense_survivors_refined_valid": list(dense_counts)},
                   "plan_create_ms": create_ms, "plan_create_warm_ms": create_warm_ms,
                   "replan_stream": replan,

@@ -232,7 +232,13 @@ sailor_status sailor_plan_set_avail(sailor_plan *plan, const int32_t *avail);
 sailor_status sailor_plan_set_incremental(sailor_plan *plan, int32_t on);
 
 /* Pieces of the space the last successful sailor_best_plan / sailor_topk evaluated, and how
- * many there are.  Host pointers, either may be NULL.  SAILOR_EINVAL before the first
+ * many there are.  Not counted as evaluated: pieces whose minima were reused, and pieces passed
+ * over because a bound computed at sailor_plan_create proves that they hold nothing for the
+ * query (the smallest cost, or time, of any plan of the piece whatever the availability
+ * already violates the constraint; for the best plan also: its smallest objective value
+ * cannot come within the tie band of a plan already seen) -- Sec. 4.2.1, H3, applied to a
+ * piece instead of a partial plan.  Copies a small per-piece table from the device and waits
+ * for it.  Host pointers, either may be NULL.  SAILOR_EINVAL before the first
  * successful selection. */
 sailor_status sailor_plan_last_scan(sailor_plan *plan, uint32_t *units_evaluated,
                                     uint32_t *units_total);

@@ -130,6 +130,7 @@ struct sailor_plan {
   hipEvent_t ev_upload = nullptr;
   // scratch of the selection pipeline
   float *umin_s = nullptr, *umin_l = nullptr;
+  float *lb_time = nullptr, *lb_cost = nullptr;  // per unit: smallest time / cost with availability ignored
   uint32_t *counters = nullptr;
   uint32_t *ulist = nullptr;   // units the collect pass has to visit
   SurvRec *surv = nullptr;
@@ -587,6 +588,8 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
                     pl->cache_hasb == has_bound && pl->cache_lim_s == sa.lim_s &&
                     pl->cache_lim_l == sa.lim_l) ? 1 : 0;
   const bool was_incremental = sa.incremental != 0;
+  // (the constrained quantity is the cost when throughput is the objective, and the time otherwise)
+  if (has_bound) sa.ulb_con = obj == SAILOR_MAX_THROUGHPUT ? pl->lb_cost : pl->lb_time;
   pl->cache_ok = false;  // until this call has succeeded
   pl->cache_obj = (int)obj;
   pl->cache_hasb = has_bound;
@@ -655,12 +658,15 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
     if (!sa.incremental) {
       sa.near_list = pl->ulist;
       sa.near_band = sa.band;
+      // (minima kept for later calls must not depend on this call's running minimum)
+      if (!pl->incremental) sa.ulb_key = obj == SAILOR_MAX_THROUGHPUT ? pl->lb_time : pl->lb_cost;
     }
   }
   launch_units<MODE_SCAN>(pl, obj, has_bound, sa, st, t_scan ? pl->ev[3] : nullptr,
                           t_scan ? pl->ev[1] : nullptr);
   const bool listed_by_scan = sa.near_list != nullptr;
   sa.near_list = nullptr;
+  sa.ulb_key = nullptr;
   if (best && listed_by_scan) {
     sa.tau_src = cnt + CNT_GMIN;
     sa.ulist = pl->ulist;
@@ -943,6 +949,8 @@ static sailor_status create_impl(const sailor_problem *p, sailor_plan **out, sai
   // selection scratch
   CREATE_TRY(ar.alloc(&pl->umin_s, unit_cap));
   CREATE_TRY(ar.alloc(&pl->umin_l, unit_cap));
+  CREATE_TRY(ar.alloc(&pl->lb_time, unit_cap));
+  CREATE_TRY(ar.alloc(&pl->lb_cost, unit_cap));
   CREATE_TRY(ar.alloc(&pl->counters, (size_t)2 * CNT_COUNT));
   CREATE_TRY(ar.alloc(&pl->ulist, unit_cap));
   CREATE_TRY(ar.alloc(&pl->unit_gen, unit_cap));
@@ -1064,6 +1072,15 @@ static sailor_status create_impl(const sailor_problem *p, sailor_plan **out, sai
     for (size_t i = 0; i < NU; ++i) sorted[i] = pl->units[order[i]];
     pl->units.swap(sorted);
     CREATE_TRY(hipMemcpy(d_units, pl->units.data(), NU * sizeof(UnitRec), hipMemcpyHostToDevice));
+    // Per unit (in its final order), the smallest iteration time and the smallest cost over the
+    // plans that do not depend on the availability: bounds that let a query pass over a unit.
+    ca.ignore_quota = 1;
+    ca.ucost = nullptr;
+    launch_units<MODE_SCAN>(pl, SAILOR_MAX_THROUGHPUT, 0, ca, nullptr, nullptr, nullptr);
+    CREATE_TRY(hipMemcpy(pl->lb_time, pl->umin_s, NU * sizeof(float), hipMemcpyDeviceToDevice));
+    launch_units<MODE_SCAN>(pl, SAILOR_MIN_COST, 0, ca, nullptr, nullptr, nullptr);
+    CREATE_TRY(hipMemcpy(pl->lb_cost, pl->umin_s, NU * sizeof(float), hipMemcpyDeviceToDevice));
+    CREATE_TRY(hipGetLastError());
     k_init_counters<<<1, 64>>>(pl->counters, 2 * CNT_COUNT);
     CREATE_TRY(hipDeviceSynchronize());
     ar.free_one(d_cost);
@@ -1604,8 +1621,7 @@ sailor_status sailor_plan_last_scan(sailor_plan *pl, uint32_t *units_evaluated,
   if (!pl || !pl->have_hdr) return SAILOR_EINVAL;
   const uint32_t total = (uint32_t)pl->units.size();
   if (units_evaluated) {
-    *units_evaluated = total;
-    if (pl->last_incremental) {
+    {
       // every unit carries the number of the call that evaluated it last; they are counted
       // here, off the selection's own path
       HIP_TRY(hipSetDevice(pl->device));

@@ -464,6 +464,14 @@ struct ScanArgs {
   float near_band;          // near_band of the smallest strict key seen so far are appended
                             // here (count in counters[CNT_NLIST]); the running minimum only
                             // falls, so the list holds every unit within the band of the final one
+  const float *ulb_con;     // SCAN, optional, with a constraint: per unit, the smallest value the
+                            // constrained quantity takes on any plan of the unit that memory, node
+                            // size and batch allow (availability ignored; the same fp32 arithmetic,
+                            // so an exact bound): a unit whose bound fails the loose limit holds
+                            // nothing and is not staged at all (Sec. 4.2.1, H3, applied to a unit)
+  const float *ulb_key;     // SCAN, optional, with near_list: the same bound for the objective;
+                            // a unit that cannot come within near_band of the running minimum
+                            // is passed over
 };
 
 enum Counter { CNT_SURV = 0, CNT_REF = 1, CNT_FEAS = 2, CNT_GMIN = 3, CNT_TAU0 = 4, CNT_TAU1 = 5,
@@ -712,6 +720,27 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
   const unsigned long long t_begin = (MODE == MODE_SCAN && a.ucost) ? wall_clock64() : 0ull;
   const UnitRec u = pl.units[uidx];
   float tau = kPosInf;
+  if (MODE == MODE_SCAN && (a.ulb_con || a.ulb_key)) {
+    bool dead = false;  // must come out the same in every wave of the workgroup
+    if (HASB && a.ulb_con) dead = !(a.ulb_con[uidx] <= a.lim_l);
+    if (a.ulb_key && a.near_list) {
+      // the running minimum changes while the workgroup reads it: one thread reads, all follow
+      __shared__ uint32_t s_seen;
+      if (threadIdx.x == 0)
+        s_seen = __hip_atomic_load(&a.counters[CNT_GMIN], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __syncthreads();
+      dead = dead || a.ulb_key[uidx] > __uint_as_float(s_seen) * a.near_band;
+    }
+    if (dead) {
+      if (threadIdx.x == 0) {
+        a.umin_s[uidx] = kPosInf;
+        a.umin_l[uidx] = kPosInf;
+        if (a.unit_gen) a.unit_gen[uidx] = a.cur_gen;  // (not counted as evaluated: unit_seq stays)
+        if (a.ucost) a.ucost[uidx] = 0.f;
+      }
+      return;
+    }
+  }
   if (MODE == MODE_COLLECT) {
     tau = a.use_tau_host ? a.tau_host : __uint_as_float(*a.tau_src) * a.band;
     const float um = a.umin_l[uidx];

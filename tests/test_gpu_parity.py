@@ -318,6 +318,60 @@ def test_no_feasible_plan_and_availability_update(torch_cuda):
         plan.destroy()
 
 
+def test_pieces_ruled_out_by_their_bounds_are_passed_over_and_nothing_is_lost(torch_cuda):
+    # The bounds are taken at plan creation with the availability ignored (Sec. 4.2.1, H3, applied
+    # to a piece of the space): a plan created while GPUs are scarce must still find what becomes
+    # valid when many arrive, for every bound, and must pass over pieces only when a bound binds.
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    prob = W.config2()
+    scarce = np.minimum(prob.avail, 2)
+    plan = _plan(prob.with_avail(scarce))
+    try:
+        ruled_out = 0
+        for avail in (scarce, prob.avail, prob.avail * 4, prob.avail // 3):
+            plan.set_avail(avail)
+            orc = Oracle(prob.with_avail(avail))
+            t, c, _, mask = orc.eval_batch(n_threads=THREADS)
+            ok = mask == 0
+            if not ok.any():
+                assert plan.best_plan(stream=stream) is None
+                continue
+            for objective in (MAX_THROUGHPUT, MIN_COST):
+                val = c if objective == MAX_THROUGHPUT else 1.0 / t
+                lo, hi = float(val[ok].min()), float(val[ok].max())
+                seen = []
+                for q in (0.0, 0.02, 0.2, 0.6, 1.0):
+                    # (for MIN_COST the bound is a floor on iterations/s: tight means large)
+                    bound = off_data(lo + q * (hi - lo)) if objective == MAX_THROUGHPUT else \
+                        off_data(hi - q * (hi - lo)) * (1.0 - 2e-7)
+                    got = plan.topk(40, objective=objective, bound=bound, stream=stream)
+                    seen.append(plan.last_scan())
+                    check_topk(got, orc.topk(40, objective=objective, bound=bound, n_threads=THREADS),
+                               objective, orc, bound)
+                    want = orc.best(objective=objective, bound=bound, n_threads=THREADS)
+                    best = plan.best_plan(objective=objective, bound=bound, stream=stream)
+                    assert (best is None) == (want is None)
+                    if want is not None:
+                        check_result(best, want, orc)
+                total = seen[0][1]
+                evaluated = [e for e, _ in seen]
+                assert evaluated == sorted(evaluated), evaluated  # a looser bound never rules out more
+                ruled_out += evaluated[0] < total
+        # (the bounds ignore the availability: where GPUs are scarce even the tightest bound that
+        # leaves a plan may rule nothing out, with many GPUs it does)
+        assert ruled_out >= 2, ruled_out
+        # a budget below every plan's cost: nothing is evaluated, nothing is found
+        assert plan.topk(40, objective=MAX_THROUGHPUT, bound=1e-30, stream=stream) == []
+        assert plan.last_scan()[0] == 0
+        # a bound that cannot bind, and no bound at all: every piece is evaluated
+        plan.topk(40, objective=MAX_THROUGHPUT, bound=1e30, stream=stream)
+        assert plan.last_scan()[0] == plan.last_scan()[1]
+        plan.topk(40, objective=MAX_THROUGHPUT, stream=stream)
+        assert plan.last_scan()[0] == plan.last_scan()[1]
+    finally:
+        plan.destroy()
+
+
 def test_near_ties_follow_the_lowest_index_rule(torch_cuda):
     stream = torch_cuda.cuda.current_stream().cuda_stream
     for rel, first_wins in ((4e-6, True), (4e-5, False), (9.9e-6, True), (1.01e-5, False)):

@@ -41,7 +41,9 @@ def test_node_events_on_the_third_workload(torch_cuda):
         assert inc.last_scan() == (total, total)  # nothing kept yet: everything evaluated
         _same(inc.best_plan(stream=stream), full.best_plan(stream=stream))
         assert inc.last_scan()[0] == 0            # same query, same availability: all kept
-        assert full.last_scan() == (total, total)
+        # (without kept minima the best-plan pass also passes over pieces that cannot come near
+        # the minimum seen so far)
+        assert 0 < full.last_scan()[0] <= total and full.last_scan()[1] == total
         evaluated = []
         for i, snap in enumerate(W.node_events(prob)):
             inc.set_avail(snap)
@@ -87,7 +89,12 @@ def test_a_different_query_evaluates_everything_again(torch_cuda):
             want = orc.best(objective=objective, bound=bound)
             assert (a is None) == (want is None) and (a is None or a.index == want.index)
             n_eval, total = inc.last_scan()
-            assert n_eval == (0 if kept else total), (objective, bound, n_eval, total)
+            if kept:
+                assert n_eval == 0, (objective, bound, n_eval, total)
+            elif bound is None:
+                assert n_eval == total, (objective, bound, n_eval, total)
+            else:  # pieces that cannot meet the bound whatever the availability are passed over
+                assert 0 < n_eval <= total, (objective, bound, n_eval, total)
     finally:
         inc.destroy()
         full.destroy()

@@ -217,6 +217,44 @@ def test_fourth_workload_max_throughput_under_a_budget(cfg4, torch_cuda):
                MAX_THROUGHPUT)
 
 
+def test_fourth_workload_best_plan_repeats_exactly(cfg4, torch_cuda):
+    # The best-plan pass lets a piece of the space leave early when its bound cannot come near
+    # the smallest key seen so far -- a value that other workgroups lower meanwhile.  Every
+    # repeat, on the shared plan and on fresh ones (whose first calls run against cold caches),
+    # must return the plan that a pass without that shortcut returns (kept minima switch it
+    # off; that pass is checked against the oracle by the tests above).
+    prob, plan, orc = cfg4
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    ref = _plan(prob)
+    ref.set_incremental(True)
+    try:
+        fastest = ref.best_plan(objective=MAX_THROUGHPUT, stream=stream)
+        cheapest = ref.best_plan(objective=MIN_COST, stream=stream)
+        queries = [(MAX_THROUGHPUT, None), (MIN_COST, None), (MIN_COST, 0.5 / fastest.iter_time_s),
+                   (MIN_COST, 0.9 / fastest.iter_time_s), (MAX_THROUGHPUT, 1.2 * cheapest.cost_per_iter),
+                   (MAX_THROUGHPUT, 3.0 * cheapest.cost_per_iter)]
+        want = [ref.best_plan(objective=o, bound=b, stream=stream) for o, b in queries]
+        assert all(w is not None for w in want)
+        passed_over = 0
+        for fresh in range(3):
+            p = plan if fresh == 0 else _plan(prob)
+            try:
+                for rep in range(8 if fresh == 0 else 2):
+                    for (o, b), w in zip(queries, want):
+                        got = p.best_plan(objective=o, bound=b, stream=stream)
+                        assert got is not None, (fresh, rep, o, b)
+                        assert (got.index, got.iter_time_s, got.cost_per_iter) == \
+                               (w.index, w.iter_time_s, w.cost_per_iter), (fresh, rep, o, b)
+                        evaluated, total = p.last_scan()
+                        passed_over += evaluated < total
+            finally:
+                if p is not plan:
+                    p.destroy()
+        assert passed_over > 0  # the shortcut was at work
+    finally:
+        ref.destroy()
+
+
 # ------------------------------------------------------------------ a TP digit per segment
 
 @pytest.mark.parametrize("objective", [MAX_THROUGHPUT, MIN_COST])
