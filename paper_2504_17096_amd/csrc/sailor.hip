@@ -33,6 +33,13 @@ constexpr uint64_t kUnitTargetMin = 4096, kUnitTargetMax = 65536, kUnitsWanted =
 constexpr uint32_t kCollectSub = 4;      // workgroups that share one unit in the collect pass
 constexpr uint32_t kListSub = 8;         // the same when the pass walks a list of units,
 constexpr uint32_t kListUnits = 256;     // and the units it visits per round
+// A top-k query whose constraint leaves at most this many units alive skips the scan: one pass
+// keeps every valid candidate of those units (see run_selection_impl)
+constexpr uint32_t kDirectUnits = 128;
+constexpr uint32_t kDirectSub = 16;             // workgroups that share one of them
+constexpr uint32_t kDirectManySurvivors = 8192;  // more than the select kernel holds in registers
+                                                // (or than half the survivor buffer): the query
+                                                // goes back to the scan from then on
 // a scan unit that takes more than kSplitAbove x the average load of a workgroup slot (and
 // kSplitAboveMean x the mean unit) is cut into parts of about kSplitTo x that load
 constexpr double kSplitAbove = 0.9, kSplitAboveMean = 1.5, kSplitTo = 0.7, kSplitToMean = 1.1;
@@ -131,6 +138,15 @@ struct sailor_plan {
   // scratch of the selection pipeline
   float *umin_s = nullptr, *umin_l = nullptr;
   float *lb_time = nullptr, *lb_cost = nullptr;  // per unit: smallest time / cost with availability ignored
+  // the units in ascending order of either bound (device), and the sorted bounds (host)
+  uint32_t *order_time = nullptr, *order_cost = nullptr;
+  std::vector<float> lb_time_sorted, lb_cost_sorted;
+  // the last query whose direct pass kept too many candidates (it is not tried again)
+  bool direct_declined = false;
+  int declined_obj = 0;
+  float declined_lim = 0.f;
+  bool last_direct = false;       // the last successful selection took the direct pass
+  uint32_t last_direct_units = 0; // over this many units
   uint32_t *counters = nullptr;
   uint32_t *ulist = nullptr;   // units the collect pass has to visit
   SurvRec *surv = nullptr;
@@ -542,6 +558,7 @@ void launch_units(sailor_plan *pl, sailor_objective obj, int has_bound, const Sc
                   hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
   const unsigned n_units = (unsigned)pl->units.size();
   const dim3 grid(MODE == MODE_SCAN ? n_units
+                  : a.direct        ? a.n_list_host * a.n_sub
                   : a.ulist         ? std::min(n_units, kListUnits) * a.n_sub
                                     : n_units * a.n_sub),
       block(pl->unit_threads);
@@ -553,7 +570,7 @@ void launch_units(sailor_plan *pl, sailor_objective obj, int has_bound, const Sc
 // Shared by best_plan (k = 0: tolerance rule) and topk.
 sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
                                  const sailor_constraint *con, uint32_t k, hipStream_t st,
-                                 ResultHeader *hdr_out) {
+                                 ResultHeader *hdr_out, bool allow_direct, bool *again) {
   int has_bound;
   double bound;
   ScanArgs sa{};
@@ -601,7 +618,9 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
 
   // collect -> [k-th smallest survivor key] -> fp64 refine -> final selection -> sync
   auto run_tail = [&](ResultHeader *hdr) -> sailor_status {
-    launch_units<MODE_COLLECT>(pl, obj, has_bound, sa, st, nullptr, nullptr);
+    // (a direct pass is the call's pass over the space: the scan's timing events ride on it)
+    launch_units<MODE_COLLECT>(pl, obj, has_bound, sa, st, sa.direct && t_scan ? pl->ev[3] : nullptr,
+                               sa.direct && t_scan ? pl->ev[1] : nullptr);
     RefineArgs ra{};
     ra.surv = pl->surv;
     ra.surv_cap = pl->surv_cap;
@@ -648,6 +667,44 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
   };
 
   if (t_all) HIP_TRY(hipEventRecord(pl->ev[0], st));
+  // A top-k query whose constraint leaves only a few units alive (their bounds are sorted on
+  // the host) needs no scan and no threshold: one pass over those units keeps every valid
+  // candidate within the loose limit, and the usual tail -- the k-th smallest key among them,
+  // fp64 re-evaluation, ranking -- follows.  Not when minima are kept for later calls (this
+  // pass produces none), and not for a query that kept too many candidates the last time.
+  pl->last_direct = false;
+  if (allow_direct && !best && has_bound && !pl->incremental &&
+      !(pl->direct_declined && pl->declined_obj == (int)obj && pl->declined_lim == sa.lim_l)) {
+    const bool on_cost = obj == SAILOR_MAX_THROUGHPUT;
+    const std::vector<float> &sorted_lb = on_cost ? pl->lb_cost_sorted : pl->lb_time_sorted;
+    const size_t n_live = (size_t)(std::upper_bound(sorted_lb.begin(), sorted_lb.end(), sa.lim_l) -
+                                   sorted_lb.begin());
+    if (n_live > 0 && n_live <= kDirectUnits) {
+      sa.direct = 1;
+      sa.n_list_host = (uint32_t)n_live;
+      sa.ulist = on_cost ? pl->order_cost : pl->order_time;
+      sa.n_sub = kDirectSub;
+      sa.use_tau_host = 1;
+      sa.tau_host = kPosInf;
+      rc = run_tail(hdr_out);
+      if (rc != SAILOR_OK) return rc;
+      pl->total_timed = t_all;
+      pl->scan_timed = t_scan;
+      if (hdr_out->surv_count > std::min(kDirectManySurvivors, pl->surv_cap / 2)) {
+        pl->direct_declined = true;
+        pl->declined_obj = (int)obj;
+        pl->declined_lim = sa.lim_l;
+      }
+      if (hdr_out->surv_count > pl->surv_cap || hdr_out->ref_count > pl->ref_cap) {
+        *again = true;  // more candidates than the buffers hold: the scan and its threshold decide
+        return SAILOR_OK;
+      }
+      pl->last_direct = true;
+      pl->last_direct_units = (uint32_t)n_live;
+      pl->last_incremental = false;
+      return SAILOR_OK;
+    }
+  }
   if (best) {
     // the scan itself lists the units that can hold a plan within the tie band of the
     // minimum (a superset: see ScanArgs), so the collect pass visits a handful of units
@@ -750,7 +807,9 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
 
 sailor_status run_selection(sailor_plan *pl, sailor_objective obj, const sailor_constraint *con,
                             uint32_t k, hipStream_t st, ResultHeader *hdr_out) {
-  const sailor_status rc = run_selection_impl(pl, obj, con, k, st, hdr_out);
+  bool again = false;
+  sailor_status rc = run_selection_impl(pl, obj, con, k, st, hdr_out, true, &again);
+  if (rc == SAILOR_OK && again) rc = run_selection_impl(pl, obj, con, k, st, hdr_out, false, &again);
   if (rc == SAILOR_EDEVICE) pl->counters_dirty = true;
   if (rc == SAILOR_OK) { pl->last_hdr = *hdr_out; pl->have_hdr = true; }
   return rc;
@@ -951,6 +1010,8 @@ static sailor_status create_impl(const sailor_problem *p, sailor_plan **out, sai
   CREATE_TRY(ar.alloc(&pl->umin_l, unit_cap));
   CREATE_TRY(ar.alloc(&pl->lb_time, unit_cap));
   CREATE_TRY(ar.alloc(&pl->lb_cost, unit_cap));
+  CREATE_TRY(ar.alloc(&pl->order_time, unit_cap));
+  CREATE_TRY(ar.alloc(&pl->order_cost, unit_cap));
   CREATE_TRY(ar.alloc(&pl->counters, (size_t)2 * CNT_COUNT));
   CREATE_TRY(ar.alloc(&pl->ulist, unit_cap));
   CREATE_TRY(ar.alloc(&pl->unit_gen, unit_cap));
@@ -1081,6 +1142,17 @@ static sailor_status create_impl(const sailor_problem *p, sailor_plan **out, sai
     launch_units<MODE_SCAN>(pl, SAILOR_MIN_COST, 0, ca, nullptr, nullptr, nullptr);
     CREATE_TRY(hipMemcpy(pl->lb_cost, pl->umin_s, NU * sizeof(float), hipMemcpyDeviceToDevice));
     CREATE_TRY(hipGetLastError());
+    // ... and the units sorted by either bound: the host then knows how many units a limit
+    // leaves alive, and the device which
+    for (int which = 0; which < 2; ++which) {
+      CREATE_TRY(hipMemcpy(val.data(), which ? pl->lb_cost : pl->lb_time, NU * sizeof(float), hipMemcpyDeviceToHost));
+      std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) { return val[x] < val[y]; });
+      std::vector<float> &sorted_lb = which ? pl->lb_cost_sorted : pl->lb_time_sorted;
+      sorted_lb.resize(NU);
+      for (size_t i = 0; i < NU; ++i) sorted_lb[i] = val[order[i]];
+      CREATE_TRY(hipMemcpy(which ? pl->order_cost : pl->order_time, order.data(), NU * sizeof(uint32_t),
+                           hipMemcpyHostToDevice));
+    }
     k_init_counters<<<1, 64>>>(pl->counters, 2 * CNT_COUNT);
     CREATE_TRY(hipDeviceSynchronize());
     ar.free_one(d_cost);
@@ -1621,7 +1693,9 @@ sailor_status sailor_plan_last_scan(sailor_plan *pl, uint32_t *units_evaluated,
   if (!pl || !pl->have_hdr) return SAILOR_EINVAL;
   const uint32_t total = (uint32_t)pl->units.size();
   if (units_evaluated) {
-    {
+    if (pl->last_direct) {
+      *units_evaluated = pl->last_direct_units;
+    } else {
       // every unit carries the number of the call that evaluated it last; they are counted
       // here, off the selection's own path
       HIP_TRY(hipSetDevice(pl->device));

@@ -469,6 +469,9 @@ struct ScanArgs {
                             // size and batch allow (availability ignored; the same fp32 arithmetic,
                             // so an exact bound): a unit whose bound fails the loose limit holds
                             // nothing and is not staged at all (Sec. 4.2.1, H3, applied to a unit)
+  int direct;               // COLLECT without a scan before it: ulist names the only units whose
+  uint32_t n_list_host;     // bound meets the limit (n_list_host of them); every candidate of
+                            // theirs that is valid and within the loose limit is kept
   const float *ulb_key;     // SCAN, optional, with near_list: the same bound for the objective;
                             // a unit that cannot come within near_band of the running minimum
                             // is passed over
@@ -518,9 +521,18 @@ __device__ __forceinline__ void visit(const ScanArgs &a, float T, float C, bool 
         atomicAdd(&a.counters[CNT_NLOOSE], (uint32_t)__popcll(m_loose));
         if (m_strict != 0) atomicAdd(&a.counters[CNT_NSTRICT], (uint32_t)__popcll(m_strict));
       }
-    } else if (loose && key <= tau) {
+    } else {
+      // one atomic per wave: the first lane that keeps its candidate reserves the slots of all
+      const bool take = loose && key <= tau;
+      const uint64_t m_take = __builtin_amdgcn_ballot_w64(take);
+      if (m_take == 0) return;
+      const int lane = (int)(threadIdx.x & 63u), leader = __builtin_ctzll(m_take);
+      uint32_t base = 0;
+      if (lane == leader) base = atomicAdd(&a.counters[CNT_SURV], (uint32_t)__popcll(m_take));
+      base = (uint32_t)__shfl((int)base, leader);
+      if (!take) return;
       const bool strict = !HASB || con <= a.lim_s;
-      const uint32_t slot = atomicAdd(&a.counters[CNT_SURV], 1u);
+      const uint32_t slot = base + (uint32_t)__popcll(m_take & ((1ull << lane) - 1ull));
       if (slot < a.surv_cap) {
         SurvRec sv;
         sv.idx = idx;
@@ -743,8 +755,10 @@ __device__ __forceinline__ void unit_work(const DevPlan &pl, const ScanArgs &a, 
   }
   if (MODE == MODE_COLLECT) {
     tau = a.use_tau_host ? a.tau_host : __uint_as_float(*a.tau_src) * a.band;
-    const float um = a.umin_l[uidx];
-    if (!(um < kPosInf && um <= tau)) return;  // uniform over the workgroup
+    if (!a.direct) {  // (without a scan before this pass there are no minima to consult)
+      const float um = a.umin_l[uidx];
+      if (!(um < kPosInf && um <= tau)) return;  // uniform over the workgroup
+    }
   }
   const int ZG = pl.ZG, G = pl.GX, MB = pl.MB, Z = pl.Z, S = u.s;
   const size_t n_rec = unit_lds_records(ZG, MB);
@@ -884,7 +898,8 @@ __global__ __launch_bounds__(kMaxUnitThreads) void k_units(DevPlan pl, ScanArgs 
     unit_work<MODE, OBJ, HASB, MIXED>(pl, a, blockIdx.x / a.n_sub, (int)(blockIdx.x % a.n_sub), a.n_sub,
                                lds_raw);
   } else {
-    const uint32_t n_list = a.counters[CNT_NLIST], per_round = gridDim.x / a.n_sub;
+    const uint32_t n_list = a.direct ? a.n_list_host : a.counters[CNT_NLIST];
+    const uint32_t per_round = gridDim.x / a.n_sub;
     const int sub = (int)(blockIdx.x % a.n_sub);
     for (uint32_t e = blockIdx.x / a.n_sub; e < n_list; e += per_round) {  // uniform
       unit_work<MODE, OBJ, HASB, MIXED>(pl, a, a.ulist[e], sub, a.n_sub, lds_raw);

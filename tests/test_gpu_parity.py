@@ -300,6 +300,14 @@ def test_best_plan_and_topk(case, torch_cuda, objective):
             check_topk(got_k, want_k, objective, orc, bound)
             if want_k:
                 check_result(got_k[0], want_k[0], orc) if got_k[0].index == want_k[0].index else None
+            if bound is not None:
+                # With few pieces of the space alive under the bound the call above kept every
+                # valid candidate of theirs in one pass; a plan that keeps minima for later calls
+                # never does, so this one goes through the scan and its thresholds.
+                plan.set_incremental(True)
+                check_topk(plan.topk(k, objective=objective, bound=bound, stream=stream), want_k,
+                           objective, orc, bound)
+                plan.set_incremental(False)
 
 
 def test_no_feasible_plan_and_availability_update(torch_cuda):
@@ -446,6 +454,49 @@ def test_small_scratch_makes_topk_search_for_a_tighter_threshold(torch_cuda):
         assert ei.value.status == SAILOR_ENOMEM
         plan.set_scratch(1 << 16, 1 << 12)
         check_topk(plan.topk(64, stream=stream), orc.topk(64), MAX_THROUGHPUT, orc)
+    finally:
+        plan.destroy()
+
+
+def test_one_pass_over_the_pieces_left_alive_falls_back_when_it_keeps_too_much(torch_cuda):
+    # A bounded top-k query that leaves few pieces alive keeps all their valid candidates in one
+    # pass.  More of them than the survivor buffer holds: the call goes through the scan and its
+    # threshold instead.  More than half the buffer: this call stands, and the same query takes
+    # the scan from the next call on.  The plans are the oracle's every time.
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    prob = W.config2()
+    orc = Oracle(prob)
+    plan = _plan(prob)
+    try:
+        budget = 2.0 * orc.best(objective=MIN_COST).cost
+        want = orc.topk(64, objective=MAX_THROUGHPUT, bound=budget, n_threads=THREADS)
+        check_topk(plan.topk(64, objective=MAX_THROUGHPUT, bound=budget, stream=stream), want,
+                   MAX_THROUGHPUT, orc, budget)
+        live, total = plan.last_scan()
+        kept = plan.last_counts()[0]
+        t, c, _, mask = orc.eval_batch(n_threads=THREADS)
+        n_within = int(np.count_nonzero((mask == 0) & (c <= budget)))
+        # every plan within the budget was kept (the fp32 pass lets a hair more through)
+        assert live <= 128 and live < total and n_within <= kept <= n_within * 1.01 + 10, (live, kept, n_within)
+        assert kept > 1000  # (what the two cases below rely on)
+        # half the buffer exceeded: the answer stands, the next call scans
+        plan.set_scratch(kept + kept // 2, 4096)
+        for rep in range(3):
+            check_topk(plan.topk(64, objective=MAX_THROUGHPUT, bound=budget, stream=stream), want,
+                       MAX_THROUGHPUT, orc, budget)
+            assert (plan.last_counts()[0] == kept) == (rep == 0), (rep, plan.last_counts())
+        # ... another query is tried in one pass again
+        other = 1.9 * orc.best(objective=MIN_COST).cost
+        check_topk(plan.topk(64, objective=MAX_THROUGHPUT, bound=other, stream=stream),
+                   orc.topk(64, objective=MAX_THROUGHPUT, bound=other, n_threads=THREADS),
+                   MAX_THROUGHPUT, orc, other)
+        # the buffer exceeded: the scan's threshold decides within the same call
+        plan.set_scratch(kept // 2, 4096)
+        for q, w in ((budget, want), (other, None)):
+            w = w or orc.topk(64, objective=MAX_THROUGHPUT, bound=q, n_threads=THREADS)
+            check_topk(plan.topk(64, objective=MAX_THROUGHPUT, bound=q, stream=stream), w,
+                       MAX_THROUGHPUT, orc, q)
+            assert plan.last_counts()[0] <= kept // 2
     finally:
         plan.destroy()
 
