@@ -78,6 +78,41 @@ def test_third_workload_selection(cfg3, torch_cuda, objective):
     check_topk(plan.topk(64, objective=objective, stream=stream), top, objective)
 
 
+@pytest.mark.parametrize("objective", [MAX_THROUGHPUT, MIN_COST])
+def test_third_workload_bounds_from_tight_to_loose(cfg3, torch_cuda, objective):
+    # From a bound that leaves two pieces of the space alive to one that rules nothing out: the
+    # one pass over the live pieces, the scan that passes over the others, and the plain scan
+    # all return the oracle's plans; so does the same plan after GPUs have gone away.
+    prob, plan, orc = cfg3
+    stream = torch_cuda.cuda.current_stream().cuda_stream
+    total = None
+    seen = []
+    try:
+        for avail in (prob.avail, prob.avail // 2):
+            plan.set_avail(avail)
+            o = Oracle(prob.with_avail(avail))
+            if objective == MAX_THROUGHPUT:
+                base = o.best(objective=MIN_COST, n_threads=THREADS).cost
+                bounds = [f * base for f in (1.02, 1.2, 1.35, 1.5, 2.0, 4.0)]
+            else:
+                base = 1.0 / o.best(objective=MAX_THROUGHPUT, n_threads=THREADS).iter_time
+                bounds = [f * base for f in (0.98, 0.8, 0.5, 0.2)]
+            for bound in bounds:
+                best, top = oracle_best_and_topk(o, 64, objective, bound)
+                check_topk(plan.topk(64, objective=objective, bound=bound, stream=stream), top,
+                           objective, o, bound)
+                evaluated, total = plan.last_scan()
+                seen.append(evaluated)
+                got = plan.best_plan(objective=objective, bound=bound, stream=stream)
+                assert (got is None) == (best is None)
+                if best is not None:
+                    check_result(got, best, o)
+        if objective == MAX_THROUGHPUT:  # (a throughput floor rules no piece out here)
+            assert min(seen) <= 16 and max(seen) > 128 and max(seen) <= total, (seen, total)
+    finally:
+        plan.set_avail(prob.avail)
+
+
 def test_availability_stream_replans_match_the_oracle(cfg3, torch_cuda):
     # 64 availability snapshots of the third workload's cluster, a full re-plan at each
     prob, plan, orc0 = cfg3
