@@ -256,8 +256,10 @@ def replan_stream(np, Plan, prob, snapshots, stream, incremental):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    # (a step takes about 0.04 ms; the first fifty-odd calls of a process run a quarter slower
+    # while the HIP runtime grows its pools, hence the long default warm-up)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--cpu-sample", type=int, default=16_000_000)
     ap.add_argument("--cpu-snapshots", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -237,7 +237,7 @@ sailor_status sailor_plan_set_incremental(sailor_plan *plan, int32_t on);
  * query (the smallest cost, or time, of any plan of the piece whatever the availability
  * already violates the constraint; for the best plan also: its smallest objective value
  * cannot come within the tie band of a plan already seen) -- Sec. 4.2.1, H3, applied to a
- * piece instead of a partial plan.  When a sailor_topk query's constraint leaves at most 128
+ * piece instead of a partial plan.  When a query's constraint leaves at most 128
  * pieces alive the library visits exactly those in one pass and keeps every valid plan of
  * theirs (no pass over the other pieces, no threshold); units_evaluated is then their number.
  * Copies a small per-piece table from the device and waits for it.  Host pointers, either may

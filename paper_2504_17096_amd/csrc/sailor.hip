@@ -33,7 +33,7 @@ constexpr uint64_t kUnitTargetMin = 4096, kUnitTargetMax = 65536, kUnitsWanted =
 constexpr uint32_t kCollectSub = 4;      // workgroups that share one unit in the collect pass
 constexpr uint32_t kListSub = 8;         // the same when the pass walks a list of units,
 constexpr uint32_t kListUnits = 256;     // and the units it visits per round
-// A top-k query whose constraint leaves at most this many units alive skips the scan: one pass
+// A query whose constraint leaves at most this many units alive skips the scan: one pass
 // keeps every valid candidate of those units (see run_selection_impl)
 constexpr uint32_t kDirectUnits = 128;
 constexpr uint32_t kDirectSub = 16;             // workgroups that share one of them
@@ -631,12 +631,15 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
     ra.has_bound = has_bound;
     ra.bound = bound;
     ra.band = 1.0f + 3.0f * kEvalEps;
-    if (!best) {
+    if (!best || sa.direct) {
       // the exact k-th smallest fp32 key among the survivors, then only its neighbourhood
+      // (best plan after a direct pass: the smallest key and its tie band -- what the collect
+      // pass behind a scan gathers in the first place)
       k_select_kth<256><<<1, 256, 0, st>>>(&pl->surv[0].key, (int)(sizeof(SurvRec) / 4),
-                                       cnt + CNT_SURV, pl->surv_cap, k, cnt + CNT_TAU1, nullptr,
-                                       0u, 0.f, nullptr, nullptr);
+                                       cnt + CNT_SURV, pl->surv_cap, best ? 1u : k, cnt + CNT_TAU1,
+                                       nullptr, 0u, 0.f, nullptr, nullptr);
       ra.tau_src = cnt + CNT_TAU1;
+      if (best) ra.band = (float)(1.0 + kTieTol) + 3.0f * kEvalEps;
     }
     k_refine<<<256, kRefineWaves * 64, 0, st>>>(pl->dev, ra);
     if (best) {
@@ -667,13 +670,13 @@ sailor_status run_selection_impl(sailor_plan *pl, sailor_objective obj,
   };
 
   if (t_all) HIP_TRY(hipEventRecord(pl->ev[0], st));
-  // A top-k query whose constraint leaves only a few units alive (their bounds are sorted on
-  // the host) needs no scan and no threshold: one pass over those units keeps every valid
-  // candidate within the loose limit, and the usual tail -- the k-th smallest key among them,
-  // fp64 re-evaluation, ranking -- follows.  Not when minima are kept for later calls (this
+  // A query whose constraint leaves only a few units alive (their bounds are sorted on the
+  // host) needs no scan and no threshold: one pass over those units keeps every valid
+  // candidate within the loose limit, and the usual tail -- the k-th smallest key among them
+  // (the smallest, for the best plan), fp64 re-evaluation, ranking -- follows.  Not when minima are kept for later calls (this
   // pass produces none), and not for a query that kept too many candidates the last time.
   pl->last_direct = false;
-  if (allow_direct && !best && has_bound && !pl->incremental &&
+  if (allow_direct && has_bound && !pl->incremental &&
       !(pl->direct_declined && pl->declined_obj == (int)obj && pl->declined_lim == sa.lim_l)) {
     const bool on_cost = obj == SAILOR_MAX_THROUGHPUT;
     const std::vector<float> &sorted_lb = on_cost ? pl->lb_cost_sorted : pl->lb_time_sorted;
