@@ -579,7 +579,8 @@ def main() -> int:
                                "8 layer splits per pp, <=3 segments",
                    "candidates": n, "objective": "max throughput s.t. cost <= 1.2 x cheapest",
                    "top_k": K, "mean_pipeline_depth": pbar},
-        "roofline": roof,
+        "roofline": dict(roof, frac_scan_no_binding_budget=roof_unbound["frac"],
+                         frac_scan_dense=roof_dense["frac"]),
         "roofline_scan_no_binding_budget": roof_unbound,
         "roofline_dense": roof_dense,
         "roofline_eval_batch": roof_eval,
