@@ -33,7 +33,7 @@ if ROOT not in sys.path:
 FLOPS_PER_STAGE, FLOPS_EPILOGUE = 12.0, 15.0
 # vector ALU of the part: 256 compute units x 4 SIMDs x 16 lanes at 2.4 GHz issue 39.3 T
 # lane-operations/s; an FMA counts two flops (78.6 TFLOP/s), the published 157.3 TFLOP/s
-# needs packed FP32 instructions, which this build switches off
+# needs packed FP32 instructions, which the library is compiled without
 CUS, SIMDS_PER_CU, LANES_PER_SIMD, CLOCK_HZ = 256, 4, 16, 2.4e9
 PEAK_LANE_OPS = CUS * SIMDS_PER_CU * LANES_PER_SIMD * CLOCK_HZ / 1e12   # T lane-ops/s
 PEAK_FP32_FMA_TFLOPS, PEAK_FP32_PACKED_TFLOPS = 78.6, 157.3
@@ -276,7 +276,7 @@ def main() -> int:
         print("bench.py: --steps must be at least 1 and --warmup at least 0", file=sys.stderr)
         return 2
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no sharding across GPUs); "
+        print("bench.py: the library runs on one GPU only (no sharding across GPUs); "
               "use --gpus 1", file=sys.stderr)
         return 2
 
@@ -548,7 +548,7 @@ def main() -> int:
                  "counters": counters_note,
                  "peak_note": "256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one vector instruction per "
                               "lane and cycle; an FMA is one such instruction (78.6 TFLOP/s), "
-                              "157.3 TFLOP/s needs packed FP32, switched off in this build",
+                              "157.3 TFLOP/s needs packed FP32, which the library is compiled without",
                  "measured_fma_chain_tflops": fma_tflops,
                  "measured_clock_ghz": fma_tflops * 1e12 / (2 * CUS * SIMDS_PER_CU * LANES_PER_SIMD) / 1e9,
                  "flops_per_candidate_nominal": flops_per_cand})
