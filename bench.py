@@ -5,14 +5,16 @@ OPT-30B-like cluster with 104 256 000 candidate plans): index decode, table gath
 per-stage memory check, 1F1B makespan with transfers and gradient all-reduce, cost,
 validity mask, and the selection of the 64 best plans for "max throughput under a
 budget of 1.2 x the cheapest plan".  Inputs are resident on the device before timing;
-every step evaluates the whole space (nothing is kept from one step to the next).
+every step decides the whole space (nothing is kept from one step to the next): pieces of
+the space whose cost bound, computed once per plan, already exceeds the budget are ruled out
+by one comparison each, the others are evaluated candidate by candidate.
 
-Prints one JSON line: candidates/s over the timed steps; the roofline of the dominant
-kernel (the full-space scan: its duration from HIP events on its own dispatch, its
-instruction counts from the committed rocprofv3 counter summary, which is used only while
-the kernel sources still hash to what the counters were taken on); the same for a variant of
-the workload in which nearly every candidate is valid; measured FMA and write ceilings; and
-the CPU oracle timed on this host for the same calls.
+Prints one JSON line: candidates/s over the timed steps; the roofline of the step's pass over
+the space (its duration from HIP events on its own dispatch, its instruction counts from the
+committed rocprofv3 counter summary, which is used only while the kernel sources still hash
+to what the counters were taken on); the same for the scan of every piece under a budget that
+never binds, and for a variant of the workload in which nearly every candidate is valid;
+measured FMA and write ceilings; and the CPU oracle timed on this host for the same calls.
 """
 from __future__ import annotations
 
