@@ -161,6 +161,9 @@ def _load():
         lib.so_eval_split_assignment.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                                  C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_double,
                                                  C.POINTER(_Eval)]
+        lib.so_eval_split_assignment_tp.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                                    C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_double,
+                                                    C.POINTER(_Eval)]
         lib.so_eval_assignment_tp.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                               C.c_void_p, C.c_int, C.c_int, C.c_double, C.POINTER(_Eval)]
         lib.so_eval_replica_assignment.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
@@ -367,6 +370,22 @@ class Oracle:
                                                 a.ctypes.data, b.ctypes.data, objective,
                                                 bound is not None, 0.0 if bound is None else bound,
                                                 C.byref(e))
+        if rc != 0:
+            raise ValueError("assignment out of range")
+        return _ev(e)
+
+    def eval_split_assignment_tp(self, pp_idx: int, partition: int, dp_idx: int, mb_idx: int, tp_idx,
+                                 pools_a, pools_b, objective: int = MAX_THROUGHPUT,
+                                 bound: Optional[float] = None) -> Eval:
+        """Two pools and a TP index per stage (tp_idx: one index per stage)."""
+        t = np.ascontiguousarray(tp_idx, dtype=np.int32)
+        a = np.ascontiguousarray(pools_a, dtype=np.int32)
+        b = np.ascontiguousarray(pools_b, dtype=np.int32)
+        e = _Eval()
+        rc = self._lib.so_eval_split_assignment_tp(self._ctx, pp_idx, partition, dp_idx, mb_idx,
+                                                   t.ctypes.data, a.ctypes.data, b.ctypes.data, objective,
+                                                   bound is not None, 0.0 if bound is None else bound,
+                                                   C.byref(e))
         if rc != 0:
             raise ValueError("assignment out of range")
         return _ev(e)

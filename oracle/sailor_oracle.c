@@ -490,20 +490,22 @@ int so_eval_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, i
  * paid for: the pipelines' transfers (each kind of pipeline carries half of the replicas) and
  * the two ring links between the zones of a split stage.
  * pools_a[i] / pools_b[i]: zone * n_types + type (plain pools only); equal = not split.
+ * tp_idx[i]: index of stage i's TP degree (both halves of a stage use the same degree); the
+ * stage's shard, activation bytes, profiled times, node-size check, quota and rent follow it.
  * Returns 0, -1 for a value out of range or a problem with extended types. */
-int so_eval_split_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
-                             int tp_idx, const int32_t *pools_a, const int32_t *pools_b,
-                             int objective, int has_bound, double bound, so_eval *out) {
+int so_eval_split_assignment_tp(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                                const int32_t *tp_idx, const int32_t *pools_a, const int32_t *pools_b,
+                                int objective, int has_bound, double bound, so_eval *out) {
   const so_problem *p = &c->p;
   if (p->mixed_types || pp_idx < 0 || pp_idx >= p->n_pp || dp_idx < 0 || dp_idx >= p->n_dp ||
-      mb_idx < 0 || mb_idx >= p->n_mb || tp_idx < 0 || tp_idx >= p->n_tp || partition < 0 ||
-      partition >= p->n_partitions[pp_idx])
+      mb_idx < 0 || mb_idx >= p->n_mb || partition < 0 || partition >= p->n_partitions[pp_idx])
     return -1;
   const int P = p->pp_values[pp_idx], G = p->n_types, Z = p->n_zones;
   for (int i = 0; i < P; ++i)
-    if (pools_a[i] < 0 || pools_a[i] >= Z * G || pools_b[i] < 0 || pools_b[i] >= Z * G) return -1;
+    if (pools_a[i] < 0 || pools_a[i] >= Z * G || pools_b[i] < 0 || pools_b[i] >= Z * G ||
+        tp_idx[i] < 0 || tp_idx[i] >= p->n_tp)
+      return -1;
   const int64_t replicas = p->dp_values[dp_idx], micro = p->mb_values[mb_idx];
-  const int64_t tp = p->tp_values[tp_idx];
   so_config g;
   memset(&g, 0, sizeof g);
   g.pp_idx = pp_idx; g.pp = P; g.partition = partition;
@@ -522,11 +524,12 @@ int so_eval_split_assignment(const so_ctx *c, int pp_idx, int partition, int dp_
   int64_t halves[SO_MAX_POOLS];
   memset(halves, 0, sizeof halves);
   for (int i = 0; i < P; ++i) {
-    halves[pools_a[i]] += tp;
-    halves[pools_b[i]] += tp;
+    const int64_t width = p->tp_values[tp_idx[i]]; /* GPUs of one replica of this stage */
+    halves[pools_a[i]] += width;
+    halves[pools_b[i]] += width;
     if (pools_a[i] != pools_b[i] && replicas % 2 != 0) out->mask |= SO_BIT_QUOTA;
     for (int h = 0; h < 2; ++h)
-      if (tp > p->gpus_per_node[side[h][i] % G]) out->mask |= SO_BIT_TP_NODE;
+      if (width > p->gpus_per_node[side[h][i] % G]) out->mask |= SO_BIT_TP_NODE;
   }
   for (int a = 0; a < Z * G; ++a)
     if (halves[a] * replicas > 2 * (int64_t)p->avail[a]) out->mask |= SO_BIT_QUOTA;
@@ -543,11 +546,12 @@ int so_eval_split_assignment(const so_ctx *c, int pp_idx, int partition, int dp_
     layer += nl[i];
     if (i == 0) params += p->embed_params;
     if (i + 1 == P) params += p->head_params;
-    shard_of[i] = (params + (uint64_t)tp - 1) / (uint64_t)tp;
+    const uint64_t width = (uint64_t)p->tp_values[tp_idx[i]];
+    shard_of[i] = (params + width - 1) / width;
     const int64_t alive = (P - i) < n_micro ? (P - i) : n_micro;
     const uint64_t bytes = shard_of[i] * (uint64_t)p->bytes_per_param +
                            (uint64_t)alive * (uint64_t)nl[i] *
-                               p->act_store_bytes[(size_t)mb_idx * p->n_tp + tp_idx];
+                               p->act_store_bytes[(size_t)mb_idx * p->n_tp + tp_idx[i]];
     for (int h = 0; h < 2; ++h) {
       const int gt = side[h][i] % G;
       const uint64_t m = bytes + p->mem_reserved[gt];
@@ -565,8 +569,8 @@ int so_eval_split_assignment(const so_ctx *c, int pp_idx, int partition, int dp_
     double total = 0.0, slowest = 0.0;
     for (int i = 0; i < P; ++i) {
       const int gt = side[h][i] % G, z = side[h][i] / G;
-      double t = layer_time_sum(p, p->t_fwd, gt, mb_idx, tp_idx, first_of[i], nl[i]) +
-                 layer_time_sum(p, p->t_bwd, gt, mb_idx, tp_idx, first_of[i], nl[i]);
+      double t = layer_time_sum(p, p->t_fwd, gt, mb_idx, tp_idx[i], first_of[i], nl[i]) +
+                 layer_time_sum(p, p->t_bwd, gt, mb_idx, tp_idx[i], first_of[i], nl[i]);
       double moves = 0.0;
       if (i < P - 1) {
         const int zn = side[h][i + 1] / G;
@@ -579,7 +583,7 @@ int so_eval_split_assignment(const so_ctx *c, int pp_idx, int partition, int dp_
       t += moves;
       total += t;
       if (t > slowest) slowest = t;
-      const double u = upd_time_sum(p, gt, tp_idx, first_of[i], nl[i]);
+      const double u = upd_time_sum(p, gt, tp_idx[i], first_of[i], nl[i]);
       if (u > t_update) t_update = u;
     }
     const double t_kind = total + (double)(n_micro - 1) * slowest;
@@ -609,7 +613,7 @@ int so_eval_split_assignment(const so_ctx *c, int pp_idx, int partition, int dp_
 
   double rent = 0.0; /* $/h of all replicas: half of a stage's at each pool's price */
   for (int i = 0; i < P; ++i)
-    rent += (double)(replicas * tp) *
+    rent += (double)(replicas * (int64_t)p->tp_values[tp_idx[i]]) *
             (0.5 * (p->price_per_hour[pools_a[i] % G] + p->price_per_hour[pools_b[i] % G]));
   out->cost = rent / 3600.0 * out->iter_time + traffic_cost;
   if (has_bound) {
@@ -617,6 +621,16 @@ int so_eval_split_assignment(const so_ctx *c, int pp_idx, int partition, int dp_
       out->mask |= SO_BIT_CONSTRAINT;
   }
   return 0;
+}
+
+/* The same with one TP degree for all stages. */
+int so_eval_split_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                             int tp_idx, const int32_t *pools_a, const int32_t *pools_b,
+                             int objective, int has_bound, double bound, so_eval *out) {
+  int32_t every_stage[SO_MAX_STAGES];
+  for (int i = 0; i < SO_MAX_STAGES; ++i) every_stage[i] = tp_idx;
+  return so_eval_split_assignment_tp(c, pp_idx, partition, dp_idx, mb_idx, every_stage, pools_a, pools_b,
+                                     objective, has_bound, bound, out);
 }
 
 const so_problem *so_problem_of(const so_ctx *c) { return &c->p; }

@@ -164,6 +164,12 @@ int so_eval_split_assignment(const so_ctx *c, int pp_idx, int partition, int dp_
                              int tp_idx, const int32_t *pools_a, const int32_t *pools_b,
                              int objective, int has_bound, double bound, so_eval *out);
 
+/* Both at once: two pools and a TP degree per stage (tp_idx[i], the same for both halves of the
+ * stage) -- the free per-stage (GPU type, zone, TP) choice of Sec. 4.2 with two tuples per stage. */
+int so_eval_split_assignment_tp(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                                const int32_t *tp_idx, const int32_t *pools_a, const int32_t *pools_b,
+                                int objective, int has_bound, double bound, so_eval *out);
+
 /* The plan tuple in full (Sec. 4.2: D tuples per stage): every replica of every stage names its
  * pool, pools[i * D + r] for stage i and replica r.  Replica r of all stages forms pipeline r;
  * T_iter = max over the D pipelines + T_sync + T_update (Sec. 4.3).  A stage's gradient all-reduce

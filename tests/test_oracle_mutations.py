@@ -38,6 +38,15 @@ MUTANTS = [
      "if (others[k] > link) link = others[k];"),
     ("test_oracle_split_replicas.py", "(0.5 * (double)replicas) * msg", "((double)replicas) * msg"),
     ("test_oracle_split_replicas.py", "if (t_kind > t_pipe) t_pipe = t_kind;", "t_pipe = t_kind;"),
+    # ... with a TP degree per stage: the second half's GPUs counted as one per replica, the
+    # first stage's degree for every stage's activations, update time and rent
+    ("test_oracle_split_replicas.py", "halves[pools_b[i]] += width;", "halves[pools_b[i]] += 1;"),
+    ("test_oracle_split_replicas.py", "p->act_store_bytes[(size_t)mb_idx * p->n_tp + tp_idx[i]];",
+     "p->act_store_bytes[(size_t)mb_idx * p->n_tp + tp_idx[0]];"),
+    ("test_oracle_split_replicas.py", "const double u = upd_time_sum(p, gt, tp_idx[i], first_of[i], nl[i]);",
+     "const double u = upd_time_sum(p, gt, tp_idx[0], first_of[i], nl[i]);"),
+    ("test_oracle_split_replicas.py", "rent += (double)(replicas * (int64_t)p->tp_values[tp_idx[i]]) *",
+     "rent += (double)(replicas * (int64_t)p->tp_values[tp_idx[0]]) *"),
     # the search: a bound that is not one, a forgotten transfer, a quota that is never full,
     # the beam's order
     ("test_oracle_search.py", "const double tsum = (st->sum + t_open) + s->Ssum[i];",

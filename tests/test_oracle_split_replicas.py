@@ -151,3 +151,71 @@ def test_a_stage_on_two_types_pays_both_prices_and_waits_for_the_slower_update()
     fast = orc.eval_split_assignment(0, 0, 0, 0, 0, [0], [0])
     assert fast.iter_time == pytest.approx(2 * 1e-3 + 3e-4, rel=1e-13)
     assert fast.cost == pytest.approx(2.0 * fast.iter_time, rel=1e-13)
+
+
+# ------------------------------------------------------------------ two pools and a TP degree per stage
+
+@pytest.mark.parametrize("seed", [4, 5, 6])
+def test_with_a_degree_per_stage_the_two_special_cases_come_back(seed):
+    # equal halves: the evaluation with a TP degree per stage; one degree for all stages: the
+    # split evaluation above -- both pinned on their own
+    prob = _tiny(seed, n_types=2, n_zones=2 + seed % 2)
+    orc = Oracle(prob)
+    rng = np.random.default_rng(seed)
+    zg = prob.n_zones * prob.n_types
+    for _ in range(600):
+        ip = int(rng.integers(0, len(prob.pp_values)))
+        P = int(prob.pp_values[ip])
+        args = (ip, int(rng.integers(0, prob.n_partitions[ip])), int(rng.integers(0, len(prob.dp_values))),
+                int(rng.integers(0, len(prob.mb_values))))
+        pools, other = rng.integers(0, zg, P), rng.integers(0, zg, P)
+        tps = rng.integers(0, len(prob.tp_values), P)
+        one = int(rng.integers(0, len(prob.tp_values)))
+        for objective, bound in ((MAX_THROUGHPUT, None), (MIN_COST, 3.0)):
+            a = orc.eval_assignment_tp(*args, tps, pools, objective, bound)
+            b = orc.eval_split_assignment_tp(*args, tps, pools, pools, objective, bound)
+            assert (a.mask, a.peak_mem) == (b.mask, b.peak_mem)
+            if np.isfinite(a.iter_time):
+                assert b.iter_time == pytest.approx(a.iter_time, rel=1e-13)
+                assert b.cost == pytest.approx(a.cost, rel=1e-13)
+            c = orc.eval_split_assignment(*args, one, pools, other, objective, bound)
+            d = orc.eval_split_assignment_tp(*args, np.full(P, one), pools, other, objective, bound)
+            assert (c.mask, c.peak_mem, c.iter_time, c.cost) == (d.mask, d.peak_mem, d.iter_time, d.cost) or \
+                (np.isnan(c.cost) and np.isnan(d.cost))
+
+
+def test_two_zones_and_two_degrees_by_hand():
+    # the two-zone problem above with TP degrees 1 and 2: at degree 2 a layer takes half the
+    # time and a worker holds half of the parameters.  Stage 0 (degree 2) split over the zones,
+    # stage 1 (degree 1) in zone 0.
+    tf = np.zeros((1, 1, 2, 1)); tf[0, 0, :, 0] = (1e-3, 0.5e-3)
+    tb = 2 * tf
+    tu = np.zeros((1, 2, 1)); tu[0, :, 0] = (5e-4, 2.5e-4)
+    # GPUs: zone 0 gives one replica of stage 0 (2) and both of stage 1 (1 + 1), zone 1 the other
+    # replica of stage 0 (2)
+    orc = Oracle(_two_zone(tp_list=(1, 2), t_fwd=tf, t_bwd=tb, t_upd=tu, avail=np.array([[4], [2]])))
+    e = orc.eval_split_assignment_tp(0, 0, 0, 0, [1, 0], [0, 0], [1, 0])
+    assert e.mask == 0
+    ms = 1e-3
+    a = [1.5 * ms + 1 * ms, 3 * ms + 1 * ms]             # both stages in zone 0
+    b = [1.5 * ms + 5 * ms, 3 * ms + 10 * ms]            # zone 1 -> zone 0 (5 ms forward, 10 ms back)
+    t_pp = max(sum(a) + 3 * max(a), sum(b) + 3 * max(b))
+    # stage 0's ring carries half of the parameters (1 MB of gradients) over the slowest link, stage 1's 2 MB in zone 0
+    t_sync = max(1e6 / 1e8, 2e6 / 1e9)
+    T = t_pp + t_sync + 5e-4                              # stage 1's update at degree 1 is the slower one
+    assert e.iter_time == pytest.approx(T, rel=1e-13)
+    # rent: stage 0 two replicas of 2 GPUs, stage 1 two of 1, at 1 $/s; traffic as before, the ring half as much
+    assert e.cost == pytest.approx(6 * T + 4 * 1e6 * 4e-9 + 1e6 * 4e-9, rel=1e-13)
+    # memory: stage 0 holds half of its parameters and two microbatches in flight (10 MB), stage 1
+    # all of its parameters and one microbatch (17 MB)
+    assert e.peak_mem == 1_000_000 * 16 + 1_000_000
+    # one GPU fewer in either zone: stage 0's wider replicas no longer fit
+    for avail in ([[3], [2]], [[4], [1]]):
+        short = Oracle(_two_zone(tp_list=(1, 2), t_fwd=tf, t_bwd=tb, t_upd=tu, avail=np.array(avail)))
+        assert short.eval_split_assignment_tp(0, 0, 0, 0, [1, 0], [0, 0], [1, 0]).mask == BIT_QUOTA
+        # ... while degree 1 everywhere still does (zone 0: 1 + 2, zone 1: 1)
+        assert short.eval_split_assignment_tp(0, 0, 0, 0, [0, 0], [0, 0], [1, 0]).mask == 0
+    # a node of one GPU cannot host degree 2, whichever half sits on it
+    small = Oracle(_two_zone(tp_list=(1, 2), t_fwd=tf, t_bwd=tb, t_upd=tu, node=1))
+    assert small.eval_split_assignment_tp(0, 0, 0, 0, [1, 0], [0, 0], [1, 0]).mask & BIT_TP_NODE
+    assert small.eval_split_assignment_tp(0, 0, 0, 0, [0, 0], [0, 0], [1, 0]).mask & BIT_TP_NODE == 0
