@@ -431,7 +431,8 @@ sailor_status sailor_search(sailor_plan *plan, sailor_objective objective,
  *   d_tps     device, same shape, or NULL.  Given, stage i runs at TP degree tp_values[d_tps[..][i]]
  *             instead of the descriptor's: its memory shard, activation bytes, profiled times,
  *             node-size check, gradient shard, GPUs against its pool's quota and rent use it
- *             (tp_ij of Sec. 4.2.2).  Not together with d_pools_b (SAILOR_EINVAL)
+ *             (tp_ij of Sec. 4.2.2).  Together with d_pools_b both halves of a stage run at
+ *             the stage's degree: two (GPU type, zone) tuples and a TP degree per stage
  *   outputs   device, [count], any may be NULL
  * A descriptor, pool or TP index out of range yields mask = 0xFFFFFFFF, time = cost = +inf, mem = 0; a
  * batch that does not divide mask = BATCH_INDIVISIBLE with +inf and 0.  Asynchronous on

@@ -414,8 +414,8 @@ class Plan:
                         d_cost=None, d_mem=None, d_mask=None, stream: int = 0, d_pools_b=None,
                         d_tps=None) -> None:
         """sailor_eval_placements; device tensors: int32 [count][5], int32 [count][pool_stride]
-        (and optionally the pools of the other half of every stage's replicas, or the TP index
-        of every stage), float64 / float64 / int64 / int32 outputs."""
+        (and optionally the pools of the other half of every stage's replicas, the TP index
+        of every stage, or both), float64 / float64 / int64 / int32 outputs."""
         rc = self._lib.sailor_eval_placements(self._h, count, _ptr(d_desc), _ptr(d_pools),
                                               _ptr(d_pools_b), _ptr(d_tps), pool_stride,
                                               objective, _constraint(bound), _ptr(d_time), _ptr(d_cost),

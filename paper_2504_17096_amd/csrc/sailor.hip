@@ -1512,7 +1512,7 @@ sailor_status sailor_eval_placements(sailor_plan *pl, uint64_t count, const int3
                                      void *hip_stream) {
   if (!pl || (objective != SAILOR_MAX_THROUGHPUT && objective != SAILOR_MIN_COST)) return SAILOR_EINVAL;
   if (count == 0) return SAILOR_OK;
-  if (!d_desc || !d_pools || pool_stride < 1 || (d_pools_b && d_tps)) return SAILOR_EINVAL;
+  if (!d_desc || !d_pools || pool_stride < 1) return SAILOR_EINVAL;
   if (pl->dev.mixed || pl->dev.ZGr > kSearchMaxPools) return SAILOR_EINVAL;
   if (count > (uint64_t)0x7fffffff) return SAILOR_ERANGE;
   if (constraint && constraint->has_bound && std::isnan(constraint->bound)) return SAILOR_EINVAL;

@@ -691,11 +691,13 @@ constexpr int kPlaceWaves = 4;
 // form two kinds of pipeline; T_iter takes the slower kind (Sec. 4.3: max over pipelines), a
 // split stage's all-reduce runs over the slowest link of a ring through both pools, and the
 // traffic between zones -- of the pipelines, each kind carrying half of the replicas, and of
-// the ring -- is paid for.  One wave; valid descriptor and pools; nb > 0.
+// the ring -- is paid for.  With a TP index per stage (tps; else it for all) both halves of a
+// stage use the stage's degree.  One wave; valid descriptor, pools and TP indices; nb > 0.
 __device__ __forceinline__ void eval_split_wave(const DevPlan &pl, const int32_t *pa, const int32_t *pb,
-                                                int P, uint32_t rs, int it, int im, int64_t nb, int64_t D,
-                                                int64_t tp, RefineLds &L, double *t_second, int *cnt,
-                                                double &T, double &C, uint64_t &peak, uint32_t &mask) {
+                                                const int32_t *tps, int P, uint32_t rs, int it, int im,
+                                                int64_t nb, int64_t D, RefineLds &L, double *t_second,
+                                                int *cnt, double &T, double &C, uint64_t &peak,
+                                                uint32_t &mask) {
   const int G = pl.G, Z = pl.Z, ZG = pl.ZGr, MB = pl.MB, TP = pl.TP;
   const int lane = threadIdx.x & 63;
   const double p2p = (double)pl.p2p[im];
@@ -704,12 +706,14 @@ __device__ __forceinline__ void eval_split_wave(const DevPlan &pl, const int32_t
   for (int i = lane; i < P; i += 64) {
     const int a = pa[i], b = pb[i];
     const int ga = a % G, za = a / G, gb = b % G, zb = b / G;
-    atomicAdd(&cnt[a], 1);  // halves of a replica
-    atomicAdd(&cnt[b], 1);
+    const int ti = tps ? tps[i] : it;  // this stage's TP index and degree
+    const int64_t tp = pl.tpv[ti];
+    atomicAdd(&cnt[a], (int)tp);  // GPUs of one replica, counted once per half
+    atomicAdd(&cnt[b], (int)tp);
     if (a != b && (D & 1)) odd = 1u;
     const size_t si = (size_t)rs + i;
     const uint64_t params = pl.st_params[si];
-    const uint64_t bytes = stage_bytes_of(params, pl.st_n[si], pl.bpp, i, P, (int)tp, nb, pl.act[im * TP + it]);
+    const uint64_t bytes = stage_bytes_of(params, pl.st_n[si], pl.bpp, i, P, (int)tp, nb, pl.act[im * TP + ti]);
     const uint64_t m1 = bytes + pl.res[ga], m2 = bytes + pl.res[gb];
     if (m1 > pl.cap[ga] || m2 > pl.cap[gb]) oom = 1u;
     if (tp > pl.node[ga] || tp > pl.node[gb]) h1 = 1u;
@@ -729,8 +733,8 @@ __device__ __forceinline__ void eval_split_wave(const DevPlan &pl, const int32_t
       xa += p2p / link_bw(pl, za, pa[i - 1] / G, p2p);
       xb += p2p / link_bw(pl, zb, pb[i - 1] / G, p2p);
     }
-    const double ta = pl.st_c[((si * G + ga) * MB + im) * TP + it] + xa;
-    const double tb = pl.st_c[((si * G + gb) * MB + im) * TP + it] + xb;
+    const double ta = pl.st_c[((si * G + ga) * MB + im) * TP + ti] + xa;
+    const double tb = pl.st_c[((si * G + gb) * MB + im) * TP + ti] + xb;
     max_a = fmax(max_a, ta);
     max_b = fmax(max_b, tb);
     if (D > 1) {
@@ -744,7 +748,7 @@ __device__ __forceinline__ void eval_split_wave(const DevPlan &pl, const int32_t
       t_sync = fmax(t_sync, ring_bytes / link);
       if (pl.egress && zb != za) traffic += ring_bytes * (pl.egress[za * Z + zb] + pl.egress[zb * Z + za]);
     }
-    t_upd = fmax(t_upd, fmax(pl.st_u[(si * G + ga) * TP + it], pl.st_u[(si * G + gb) * TP + it]));
+    t_upd = fmax(t_upd, fmax(pl.st_u[(si * G + ga) * TP + ti], pl.st_u[(si * G + gb) * TP + ti]));
     L.t[i] = ta;
     t_second[i] = tb;
     L.dol[i] = (double)(D * tp) * (0.5 * (pl.price[ga] + pl.price[gb]));
@@ -767,7 +771,7 @@ __device__ __forceinline__ void eval_split_wave(const DevPlan &pl, const int32_t
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   bool over = false;  // every pool holds the halves placed on it
   for (int p = lane; p < ZG; p += 64)
-    if ((int64_t)cnt[p] * tp * D > 2 * (int64_t)pl.avail[p]) over = true;
+    if ((int64_t)cnt[p] * D > 2 * (int64_t)pl.avail[p]) over = true;
   if (__builtin_amdgcn_ballot_w64(over) != 0) mask |= 2u;
   double sum_a = 0.0, sum_b = 0.0, dollars = 0.0, traffic = 0.0;
   for (int i = 0; i < P; ++i) {
@@ -826,14 +830,13 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl
     mask = 0;
     const uint32_t rs = a.pps[ip].rs0 + (uint32_t)q * (uint32_t)P;
     const int64_t nb = pl.nb[im * DP + id], D = pl.dpv[id];
-    const int64_t tp = pl.tpv[it];
     if (nb == 0) {
       mask = 4u;
     } else if (split) {
       __builtin_amdgcn_wave_barrier();
       eval_split_wave(pl, a.one ? a.one->pools : a.pools + ci * a.pool_stride,
-                      a.one ? a.one->pools_b : a.pools_b + ci * a.pool_stride, P, rs, it, im, nb, D,
-                      tp, L, s_second[wv], cnt, T, C, peak, mask);
+                      a.one ? a.one->pools_b : a.pools_b + ci * a.pool_stride,
+                      a.one ? nullptr : tps, P, rs, it, im, nb, D, L, s_second[wv], cnt, T, C, peak, mask);
       if (a.has_bound) {
         if (a.objective == 0) { if (C > a.bound) mask |= 32u; }
         else if (1.0 / T < a.bound) mask |= 32u;

@@ -448,17 +448,87 @@ def test_placements_with_a_tp_per_stage_match_the_oracle(torch_cuda, make):
         t1, c1, m1, k1 = gpu_eval_tp(torch_cuda, plan, desc, pools, same)
         assert np.array_equal(k0, k1) and np.array_equal(m0, m1)
         assert np.array_equal(t0, t1) and np.array_equal(c0, c1)
-        # a degree out of range; both optional arrays at once
+        # a degree out of range
         bad = tps[:3].copy()
         bad[1, 0] = len(prob.tp_values)
         t, c, m, k = gpu_eval_tp(torch_cuda, plan, desc[:3], pools[:3], bad)
         assert k[1] == 0xFFFFFFFF and np.isinf(t[1]) and m[1] == 0 and k[0] != 0xFFFFFFFF
-        from paper_2504_17096_amd.binding import SAILOR_EINVAL, SailorError
-        d = torch_cuda.zeros((1, stride), dtype=torch_cuda.int32, device="cuda:0")
-        with pytest.raises(SailorError) as err:
-            plan.eval_placements(1, torch_cuda.zeros((1, 5), dtype=torch_cuda.int32, device="cuda:0"), d, stride,
-                                 d_pools_b=d, d_tps=d)
-        assert err.value.status == SAILOR_EINVAL
+    finally:
+        plan.destroy()
+
+
+def gpu_eval_split_tp(torch, plan, desc, pools_a, pools_b, tps, objective=MAX_THROUGHPUT, bound=None):
+    n, stride = pools_a.shape
+    dev = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to("cuda:0")
+    t = torch.empty(n, dtype=torch.float64, device="cuda:0")
+    c = torch.empty(n, dtype=torch.float64, device="cuda:0")
+    m = torch.empty(n, dtype=torch.int64, device="cuda:0")
+    k = torch.empty(n, dtype=torch.int32, device="cuda:0")
+    plan.eval_placements(n, dev(desc), dev(pools_a), stride, objective, bound, t, c, m, k,
+                         stream=torch.cuda.current_stream().cuda_stream, d_pools_b=dev(pools_b),
+                         d_tps=dev(tps))
+    torch.cuda.synchronize()
+    return (t.cpu().numpy(), c.cpu().numpy(), m.cpu().numpy().view(np.uint64),
+            k.cpu().numpy().view(np.uint32))
+
+
+@pytest.mark.parametrize("make", [
+    lambda: _tiny(1), lambda: _tiny(2, n_types=3, n_zones=3), lambda: W.config2(), lambda: W.config3(),
+    lambda: (lambda p: p.with_bw_poly(W.bandwidth_poly(p)))(_tiny(4, n_zones=3)),
+])
+def test_placements_with_two_pools_and_a_tp_per_stage_match_the_oracle(torch_cuda, make):
+    # two (GPU type, zone) tuples and a TP degree per stage (Sec. 4.2): both optional arrays at once
+    prob = make()
+    plan, orc = _plan(prob), Oracle(prob)
+    rng = np.random.default_rng(17)
+    try:
+        stride = int(max(prob.pp_values)) + 2
+        desc, pa = random_placements(prob, rng, 1500, stride)
+        _, pb = random_placements(prob, rng, 1500, stride)
+        pb = np.where(rng.random(pa.shape) < 0.6, pa, pb)
+        tps = np.zeros_like(pa)
+        for i in range(len(desc)):
+            P = int(prob.pp_values[desc[i, 0]])
+            cuts = np.sort(rng.integers(0, P + 1, int(rng.integers(0, 3))))
+            run_tp = rng.integers(0, len(prob.tp_values), len(cuts) + 1)
+            tps[i, :P] = run_tp[np.searchsorted(cuts, np.arange(P), side="right")]
+        for objective, bound in ((MAX_THROUGHPUT, None), (MAX_THROUGHPUT, 0.02), (MIN_COST, 0.7)):
+            t, c, m, k = gpu_eval_split_tp(torch_cuda, plan, desc, pa, pb, tps, objective, bound)
+            valid = both = 0
+            for i in range(len(desc)):
+                P = int(prob.pp_values[desc[i, 0]])
+                e = orc.eval_split_assignment_tp(desc[i, 0], desc[i, 1], desc[i, 3], desc[i, 4], tps[i, :P],
+                                                 pa[i, :P], pb[i, :P], objective, bound)
+                tight = bound is not None and np.isfinite(e.iter_time) and abs(
+                    (e.cost if objective == MAX_THROUGHPUT else 1.0 / e.iter_time) / bound - 1.0) < 1e-9
+                if not tight:
+                    assert k[i] == e.mask, (i, desc[i], pa[i, :P], pb[i, :P], tps[i, :P])
+                assert m[i] == e.peak_mem
+                if np.isinf(e.iter_time):
+                    assert np.isinf(t[i]) and np.isinf(c[i])
+                else:
+                    assert t[i] == pytest.approx(e.iter_time, rel=1e-12)
+                    assert c[i] == pytest.approx(e.cost, rel=1e-12)
+                valid += e.mask == 0
+                # (times and costs are compared whether or not the plan is valid)
+                both += np.isfinite(e.iter_time) and len(set(tps[i, :P])) > 1 and \
+                    not np.array_equal(pa[i, :P], pb[i, :P])
+            if bound is None and prob.n_layers <= 8:
+                assert valid > 10 and both > 50
+        # each array alone, through the call that takes both
+        same = np.repeat(desc[:, 2:3], stride, axis=1)
+        assert all(np.array_equal(x, y) for x, y in zip(gpu_eval_split(torch_cuda, plan, desc, pa, pb),
+                                                        gpu_eval_split_tp(torch_cuda, plan, desc, pa, pb, same)))
+        fin = lambda r: [np.where(np.isfinite(x), x, 0) if x.dtype.kind == "f" else x for x in r]
+        r0, r1 = gpu_eval_tp(torch_cuda, plan, desc, pa, tps), gpu_eval_split_tp(torch_cuda, plan, desc, pa, pa, tps)
+        assert np.array_equal(r0[2], r1[2]) and np.array_equal(r0[3], r1[3])
+        ok = np.isfinite(r0[0])
+        assert np.allclose(r0[0][ok], r1[0][ok], rtol=1e-13, atol=0) and np.allclose(r0[1][ok], r1[1][ok], rtol=1e-13, atol=0)
+        # a degree out of range in a split plan
+        bad = tps[:3].copy()
+        bad[2, 0] = -1
+        t, c, m, k = gpu_eval_split_tp(torch_cuda, plan, desc[:3], pa[:3], pb[:3], bad)
+        assert k[2] == 0xFFFFFFFF and np.isinf(t[2]) and m[2] == 0 and k[0] != 0xFFFFFFFF
     finally:
         plan.destroy()
 
