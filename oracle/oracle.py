@@ -168,6 +168,8 @@ def _load():
                                               C.c_void_p, C.c_int, C.c_int, C.c_double, C.POINTER(_Eval)]
         lib.so_eval_replica_assignment.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                                    C.c_void_p, C.c_int, C.c_int, C.c_double, C.POINTER(_Eval)]
+        lib.so_eval_replica_assignment_tp.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                                      C.c_void_p, C.c_int, C.c_int, C.c_double, C.POINTER(_Eval)]
         lib.so_search_exhaustive.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, C.c_int, C.c_int,
                                              C.c_int, C.POINTER(_SearchResult)]
         lib.so_search_prefix_bound_tp.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
@@ -403,6 +405,23 @@ class Oracle:
             raise ValueError("assignment out of range")
         return _ev(e)
 
+
+    def eval_replica_assignment_tp(self, pp_idx: int, partition: int, dp_idx: int, mb_idx: int, tp_idx,
+                                   pools, objective: int = MAX_THROUGHPUT,
+                                   bound: Optional[float] = None) -> Eval:
+        """pools: [P][D], the pool of every replica of every stage; tp_idx: [P], a TP index per stage."""
+        a = np.ascontiguousarray(pools, dtype=np.int32)
+        t = np.ascontiguousarray(tp_idx, dtype=np.int32)
+        assert a.shape == (int(self._prob.pp_values[pp_idx]), int(self._prob.dp_values[dp_idx]))
+        assert t.shape == (a.shape[0],)
+        e = _Eval()
+        rc = self._lib.so_eval_replica_assignment_tp(self._ctx, pp_idx, partition, dp_idx, mb_idx,
+                                                     t.ctypes.data, a.ctypes.data, objective,
+                                                     bound is not None, 0.0 if bound is None else bound,
+                                                     C.byref(e))
+        if rc != 0:
+            raise ValueError("assignment out of range")
+        return _ev(e)
     def search_exhaustive(self, objective: int = MAX_THROUGHPUT, bound: Optional[float] = None,
                           max_runs: int = 0, allow_split: bool = False,
                           stage_tp: bool = False) -> Optional[StagePlan]:

@@ -922,18 +922,19 @@ int so_topk(const so_ctx *c, uint64_t first, uint64_t count, int objective, int 
   return n;
 }
 
-int so_eval_replica_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
-                               int tp_idx, const int32_t *pools, int objective, int has_bound,
-                               double bound, so_eval *out) {
+int so_eval_replica_assignment_tp(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                                  const int32_t *tp_idx, const int32_t *pools, int objective,
+                                  int has_bound, double bound, so_eval *out) {
   const so_problem *p = &c->p;
   if (p->mixed_types || pp_idx < 0 || pp_idx >= p->n_pp || dp_idx < 0 || dp_idx >= p->n_dp ||
-      mb_idx < 0 || mb_idx >= p->n_mb || tp_idx < 0 || tp_idx >= p->n_tp || partition < 0 ||
-      partition >= p->n_partitions[pp_idx])
+      mb_idx < 0 || mb_idx >= p->n_mb || partition < 0 || partition >= p->n_partitions[pp_idx])
     return -1;
   const int P = p->pp_values[pp_idx], G = p->n_types, Z = p->n_zones;
-  const int64_t D = p->dp_values[dp_idx], micro = p->mb_values[mb_idx], tp = p->tp_values[tp_idx];
+  const int64_t D = p->dp_values[dp_idx], micro = p->mb_values[mb_idx];
   for (int64_t k = 0; k < (int64_t)P * D; ++k)
     if (pools[k] < 0 || pools[k] >= Z * G) return -1;
+  for (int i = 0; i < P; ++i)
+    if (tp_idx[i] < 0 || tp_idx[i] >= p->n_tp) return -1;
   so_config g;
   memset(&g, 0, sizeof g);
   g.pp_idx = pp_idx; g.pp = P; g.partition = partition;
@@ -960,15 +961,16 @@ int so_eval_replica_assignment(const so_ctx *c, int pp_idx, int partition, int d
     layer += nl[i];
     if (i == 0) params += p->embed_params;
     if (i + 1 == P) params += p->head_params;
-    shard_of[i] = (params + (uint64_t)tp - 1) / (uint64_t)tp;
+    const int64_t degree = p->tp_values[tp_idx[i]]; /* every replica of the stage runs at it */
+    shard_of[i] = (params + (uint64_t)degree - 1) / (uint64_t)degree;
     const int64_t in_flight = (P - i) < n_micro ? (P - i) : n_micro;
     const uint64_t bytes = shard_of[i] * (uint64_t)p->bytes_per_param +
                            (uint64_t)in_flight * (uint64_t)nl[i] *
-                               p->act_store_bytes[(size_t)mb_idx * p->n_tp + tp_idx];
+                               p->act_store_bytes[(size_t)mb_idx * p->n_tp + (size_t)tp_idx[i]]; /* at the stage's degree */
     for (int64_t r = 0; r < D; ++r) {
       const int a = pools[(int64_t)i * D + r], gt = a % G;
-      gpus[a] += tp;
-      if (tp > p->gpus_per_node[gt]) out->mask |= SO_BIT_TP_NODE;
+      gpus[a] += degree;
+      if (degree > p->gpus_per_node[gt]) out->mask |= SO_BIT_TP_NODE;
       const uint64_t m = bytes + p->mem_reserved[gt];
       if (m > p->mem_capacity[gt]) out->mask |= SO_BIT_OOM;
       if (m > peak) peak = m;
@@ -986,8 +988,8 @@ int so_eval_replica_assignment(const so_ctx *c, int pp_idx, int partition, int d
     double total = 0.0, slowest = 0.0;
     for (int i = 0; i < P; ++i) {
       const int a = pools[(int64_t)i * D + r], gt = a % G, z = a / G;
-      double t = layer_time_sum(p, p->t_fwd, gt, mb_idx, tp_idx, first_of[i], nl[i]) +
-                 layer_time_sum(p, p->t_bwd, gt, mb_idx, tp_idx, first_of[i], nl[i]);
+      double t = layer_time_sum(p, p->t_fwd, gt, mb_idx, tp_idx[i], first_of[i], nl[i]) +
+                 layer_time_sum(p, p->t_bwd, gt, mb_idx, tp_idx[i], first_of[i], nl[i]);
       double moves = 0.0;
       if (i < P - 1) {
         const int zn = pools[(int64_t)(i + 1) * D + r] / G;
@@ -999,9 +1001,9 @@ int so_eval_replica_assignment(const so_ctx *c, int pp_idx, int partition, int d
       t += moves;
       total += t;
       if (t > slowest) slowest = t;
-      const double u = upd_time_sum(p, gt, tp_idx, first_of[i], nl[i]);
-      if (u > t_update) t_update = u;
-      rent += (double)tp * p->price_per_hour[gt];
+      const double step = upd_time_sum(p, gt, tp_idx[i], first_of[i], nl[i]); /* optimizer step */
+      if (step > t_update) t_update = step;
+      rent += (double)p->tp_values[tp_idx[i]] * p->price_per_hour[gt];
     }
     const double t_this = total + (double)(n_micro - 1) * slowest;
     if (t_this > t_pipe) t_pipe = t_this;
@@ -1030,4 +1032,14 @@ int so_eval_replica_assignment(const so_ctx *c, int pp_idx, int partition, int d
       out->mask |= SO_BIT_CONSTRAINT;
   }
   return 0;
+}
+
+/* The same with one TP degree for all stages. */
+int so_eval_replica_assignment(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                               int tp_idx, const int32_t *pools, int objective, int has_bound,
+                               double bound, so_eval *out) {
+  int32_t all_stages[SO_MAX_STAGES];
+  for (int i = 0; i < SO_MAX_STAGES; ++i) all_stages[i] = tp_idx;
+  return so_eval_replica_assignment_tp(c, pp_idx, partition, dp_idx, mb_idx, all_stages, pools, objective,
+                                       has_bound, bound, out);
 }

@@ -183,6 +183,12 @@ int so_eval_replica_assignment(const so_ctx *c, int pp_idx, int partition, int d
                                int tp_idx, const int32_t *pools, int objective, int has_bound,
                                double bound, so_eval *out);
 
+/* The same with a TP degree per stage (tp_idx[i]; all replicas of a stage run at it): the
+ * D tuples (GPU type, TP, zone) of every stage with TP taken per stage. */
+int so_eval_replica_assignment_tp(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                                  const int32_t *tp_idx, const int32_t *pools, int objective,
+                                  int has_bound, double bound, so_eval *out);
+
 #define SO_SEARCH_MAX_STAGES 256
 typedef struct {
   int32_t found;                 /* 1: a valid plan exists (within the incumbent, if one was given) */

@@ -47,6 +47,13 @@ MUTANTS = [
      "const double u = upd_time_sum(p, gt, tp_idx[0], first_of[i], nl[i]);"),
     ("test_oracle_split_replicas.py", "rent += (double)(replicas * (int64_t)p->tp_values[tp_idx[i]]) *",
      "rent += (double)(replicas * (int64_t)p->tp_values[tp_idx[0]]) *"),
+    # a pool per replica with a TP degree per stage: one GPU per replica against the quota, the
+    # first stage's degree for every stage's rent, the descriptor-less times of stage 0 everywhere
+    ("test_oracle_replica_placements.py", "gpus[a] += degree;", "gpus[a] += 1;"),
+    ("test_oracle_replica_placements.py", "rent += (double)p->tp_values[tp_idx[i]] * p->price_per_hour[gt];",
+     "rent += (double)p->tp_values[tp_idx[0]] * p->price_per_hour[gt];"),
+    ("test_oracle_replica_placements.py", "const int64_t degree = p->tp_values[tp_idx[i]];",
+     "const int64_t degree = p->tp_values[tp_idx[0]];"),
     # the search: a bound that is not one, a forgotten transfer, a quota that is never full,
     # the beam's order
     ("test_oracle_search.py", "const double tsum = (st->sum + t_open) + s->Ssum[i];",
@@ -69,7 +76,6 @@ MUTANTS = [
     ("test_oracle_replica_placements.py", "(r + 1) % D] / G;", "(r + 1 < D ? r + 1 : r)] / G;"),
     ("test_oracle_replica_placements.py", "if (w < link) link = w;", "if (w > link || link == INFINITY) link = w;"),
     ("test_oracle_replica_placements.py", "if (t_this > t_pipe) t_pipe = t_this;", "t_pipe = t_this;"),
-    ("test_oracle_replica_placements.py", "gpus[a] += tp;", "gpus[a] += 1;"),
     ("test_oracle_replica_placements.py", "traffic_cost += ring_bytes * fee[(size_t)zr * Z + zs];",
      "traffic_cost += ring_bytes * fee[(size_t)zs * Z + zr];"),
 ]

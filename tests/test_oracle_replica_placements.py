@@ -136,3 +136,77 @@ def test_pipelines_pay_for_their_own_crossings():
     T = max(sum(a) + 3 * max(a), sum(b) + 3 * max(b))
     assert e.mask == 0 and e.iter_time == pytest.approx(T, rel=1e-14)
     assert e.cost == pytest.approx(4 * T + 4 * 1e6 * 4e-9, rel=1e-14)  # no gradients: no ring traffic
+
+
+# ------------------------------------------------------------------ a TP degree per stage as well
+
+@pytest.mark.parametrize("seed", [4, 5, 6])
+def test_with_a_degree_per_stage_agreeing_replicas_reduce_to_the_pinned_evaluators(seed):
+    # all replicas of a stage on one pool: the evaluation with a pool and a TP degree per stage;
+    # the halves on two pools: the one with two pools and a degree per stage; one degree for all
+    # stages: the evaluation above -- each pinned on its own
+    prob = W.tiny_problem(seed, n_types=2 + seed % 2, n_zones=2 + seed % 2, seg3_max_pp=64)
+    orc = Oracle(prob)
+    rng = np.random.default_rng(seed)
+    zg = prob.n_zones * prob.n_types
+    checked = mixed = 0
+    for _ in range(1200):
+        ip = int(rng.integers(0, len(prob.pp_values)))
+        P = int(prob.pp_values[ip])
+        q = int(rng.integers(0, prob.n_partitions[ip]))
+        idp, im = int(rng.integers(0, len(prob.dp_values))), int(rng.integers(0, len(prob.mb_values)))
+        D = int(prob.dp_values[idp])
+        cuts = np.sort(rng.integers(0, P + 1, int(rng.integers(0, 3))))
+        pa = rng.integers(0, zg, len(cuts) + 1)[np.searchsorted(cuts, np.arange(P), side="right")]
+        pb = np.where(rng.random(P) < 0.5, pa, rng.integers(0, zg, P))
+        tps = rng.integers(0, len(prob.tp_values), len(cuts) + 1)[np.searchsorted(cuts, np.arange(P), side="right")]
+        any_pools = rng.integers(0, zg, (P, D))
+        it = int(rng.integers(0, len(prob.tp_values)))
+        for objective, bound in ((MAX_THROUGHPUT, None), (MIN_COST, 0.5)):
+            one = np.repeat(pa[:, None], D, axis=1)
+            _same(orc.eval_replica_assignment_tp(ip, q, idp, im, tps, one, objective, bound),
+                  orc.eval_assignment_tp(ip, q, idp, im, tps, pa, objective, bound))
+            a = orc.eval_replica_assignment(ip, q, idp, im, it, any_pools, objective, bound)
+            b = orc.eval_replica_assignment_tp(ip, q, idp, im, np.full(P, it), any_pools, objective, bound)
+            assert (a.mask, a.peak_mem) == (b.mask, b.peak_mem)
+            assert (a.iter_time, a.cost) == (b.iter_time, b.cost) or np.isinf(a.iter_time)
+            if D % 2 == 0:
+                two = np.concatenate([np.repeat(pa[:, None], D // 2, axis=1), np.repeat(pb[:, None], D // 2, axis=1)], axis=1)
+                want = orc.eval_split_assignment_tp(ip, q, idp, im, tps, pa, pb, objective, bound)
+                tight = bound is not None and np.isfinite(want.iter_time) and abs(1.0 / want.iter_time / bound - 1) < 1e-9
+                if not tight:
+                    _same(orc.eval_replica_assignment_tp(ip, q, idp, im, tps, two, objective, bound), want)
+                # (times and costs are compared whether or not the plan is valid)
+                checked += np.isfinite(want.iter_time)
+                mixed += np.isfinite(want.iter_time) and len(set(tps)) > 1
+    assert checked > 200 and mixed > 50
+
+
+def test_uneven_split_with_two_degrees_by_hand():
+    # two stages, D = 4: stage 0 at TP 2 (three replicas on pool 0, one on pool 1), stage 1 at TP 1
+    # (two and two).  GPUs: pool 0 gives 3 x 2 + 2 x 1 = 8, pool 1 gives 1 x 2 + 2 x 1 = 4.
+    tf = np.zeros((2, 1, 2, 1)); tf[0, 0, :, 0] = (2e-3, 1e-3); tf[1, 0, :, 0] = (6e-3, 3e-3)
+    p = make_problem(n_layers=2, n_types=2, n_zones=1, mb_list=(1,), tp_list=(1, 2), dp_list=(4,), pp_list=[2],
+                     global_batch=8, t_fwd=tf, t_bwd=0.0, layer_params=10_000_000, p2p=0, act=0,
+                     avail=np.array([[8, 4]]), node=np.array([2, 2], np.int32), price=np.array([3600.0, 1800.0]),
+                     bw=1e9, grad_bytes=2)
+    orc = Oracle(p)
+    pools = [[0, 0, 0, 1], [0, 1, 0, 1]]
+    e = orc.eval_replica_assignment_tp(0, 0, 0, 0, [1, 0], pools)
+    assert e.mask == 0
+    # memory: stage 0 holds half of its parameters (80 MB), stage 1 all of them (160 MB)
+    assert e.peak_mem == 10_000_000 * 16
+    # pipelines (2 microbatches each): r0 (1 + 2) ms, r1 (1 + 6), r2 (1 + 2), r3 (3 + 6); the last is the slowest
+    t_pp = (3e-3 + 6e-3) + 1 * 6e-3
+    # rings inside the one zone at 1 GB/s: stage 0 2 * 3/4 * 10 MB, stage 1 2 * 3/4 * 20 MB
+    t_sync = 1.5 * 20e6 / 1e9
+    assert e.iter_time == pytest.approx(t_pp + t_sync, rel=1e-14)
+    # rent in $/s: stage 0 three replicas of 2 GPUs at 1 and one at 0.5, stage 1 two of 1 GPU at each price
+    assert e.cost == pytest.approx((3 * 2 * 1.0 + 1 * 2 * 0.5 + 2 * 1.0 + 2 * 0.5) * e.iter_time, rel=1e-14)
+    # one GPU fewer in either pool breaks the quota; with degree 1 for stage 0 it still fits
+    for avail in ([[7, 4]], [[8, 3]]):
+        short = Oracle(p.with_avail(np.array(avail)))
+        assert short.eval_replica_assignment_tp(0, 0, 0, 0, [1, 0], pools).mask == BIT_QUOTA
+        assert short.eval_replica_assignment_tp(0, 0, 0, 0, [0, 0], pools).mask == 0
+    # the other way round (stage 1 at TP 2) pool 1 would have to give 1 + 2 x 2 = 5
+    assert orc.eval_replica_assignment_tp(0, 0, 0, 0, [0, 1], pools).mask == BIT_QUOTA
