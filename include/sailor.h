@@ -451,19 +451,25 @@ sailor_status sailor_eval_placements(sailor_plan *plan, uint64_t count, const in
  *   d_desc    device, [count][5]: pp index, partition, TP index, D index, microbatch index
  *   d_pools   device, [count][stride] with stride >= P x D: the pool of replica r of stage i at
  *             i * D + r
+ *   d_tps     device, [count][tps_stride] with tps_stride >= P, or NULL: the TP index of every
+ *             stage, at which all replicas of the stage run, instead of the descriptor's (the
+ *             stage's memory shard, activation bytes, profiled times, node-size check, gradient
+ *             shard, GPUs against the quotas and rent use it)
  * Replica r of all stages forms pipeline r, with its own stage times and transfers, and
  * T_iter = max over the D pipelines + T_sync + T_update (Sec. 4.3).  The gradient all-reduce of
  * a stage is a ring through its replicas in their order (0 -> 1 -> ... -> D - 1 -> 0) at the
  * pace of its slowest link, 2 (D - 1) / D x gradient bytes over it.  Traffic between zones is
  * paid for where a pipeline crosses (both directions' prices per microbatch, as everywhere) and
  * where a ring link crosses (that direction's price).  Memory and node size hold for every
- * replica's GPU type, a pool's quota counts the GPUs it gives, one TP degree per plan.  With all
- * replicas of a stage on one pool the values are those of sailor_eval_placements.
- * Outputs and errors as for sailor_eval_placements (an invalid row also when stride < P x D or
- * D > 65 536).
+ * replica's GPU type, a pool's quota counts the GPUs it gives, one TP degree per plan or per
+ * stage.  With all replicas of a stage on one pool the values are those of
+ * sailor_eval_placements.
+ * Outputs and errors as for sailor_eval_placements (an invalid row also when stride < P x D,
+ * tps_stride < P or D > 65 536).
  * Asynchronous on hip_stream.  SAILOR_EINVAL for mixed_types problems or more than 64 pools. */
 sailor_status sailor_eval_replica_placements(sailor_plan *plan, uint64_t count, const int32_t *d_desc,
                                              const int32_t *d_pools, uint64_t stride,
+                                             const int32_t *d_tps, uint32_t tps_stride,
                                              sailor_objective objective,
                                              const sailor_constraint *constraint, double *d_time,
                                              double *d_cost, uint64_t *d_mem, uint32_t *d_mask,

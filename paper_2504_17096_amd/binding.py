@@ -196,7 +196,7 @@ def load_library() -> C.CDLL:
                                   C.POINTER(sailor_search_options), C.POINTER(sailor_stage_plan), P]
     lib.sailor_eval_placements.argtypes = [P, C.c_uint64, P, P, P, P, C.c_uint32, C.c_int,
                                            C.POINTER(sailor_constraint), P, P, P, P, P]
-    lib.sailor_eval_replica_placements.argtypes = [P, C.c_uint64, P, P, C.c_uint64, C.c_int,
+    lib.sailor_eval_replica_placements.argtypes = [P, C.c_uint64, P, P, C.c_uint64, P, C.c_uint32, C.c_int,
                                                    C.POINTER(sailor_constraint), P, P, P, P, P]
     lib.sailor_plan_last_counts.argtypes = [P, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                             C.POINTER(C.c_uint32)]
@@ -425,10 +425,13 @@ class Plan:
 
     def eval_replica_placements(self, count: int, d_desc, d_pools, stride: int,
                                 objective: int = MAX_THROUGHPUT, bound: Optional[float] = None, d_time=None,
-                                d_cost=None, d_mem=None, d_mask=None, stream: int = 0) -> None:
+                                d_cost=None, d_mem=None, d_mask=None, stream: int = 0, d_tps=None,
+                                tps_stride: int = 0) -> None:
         """sailor_eval_replica_placements; device tensors: int32 [count][5], int32 [count][stride] with
-        the pool of replica r of stage i at i * D + r, float64 / float64 / int64 / int32 outputs."""
+        the pool of replica r of stage i at i * D + r (optionally int32 [count][tps_stride], the TP
+        index of every stage), float64 / float64 / int64 / int32 outputs."""
         rc = self._lib.sailor_eval_replica_placements(self._h, count, _ptr(d_desc), _ptr(d_pools), stride,
+                                                      _ptr(d_tps), tps_stride,
                                                       objective, _constraint(bound), _ptr(d_time),
                                                       _ptr(d_cost), _ptr(d_mem), _ptr(d_mask), stream or None)
         if rc != SAILOR_OK:

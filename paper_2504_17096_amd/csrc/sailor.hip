@@ -1538,13 +1538,14 @@ sailor_status sailor_eval_placements(sailor_plan *pl, uint64_t count, const int3
 
 sailor_status sailor_eval_replica_placements(sailor_plan *pl, uint64_t count, const int32_t *d_desc,
                                              const int32_t *d_pools, uint64_t stride,
+                                             const int32_t *d_tps, uint32_t tps_stride,
                                              sailor_objective objective,
                                              const sailor_constraint *constraint, double *d_time,
                                              double *d_cost, uint64_t *d_mem, uint32_t *d_mask,
                                              void *hip_stream) {
   if (!pl || (objective != SAILOR_MAX_THROUGHPUT && objective != SAILOR_MIN_COST)) return SAILOR_EINVAL;
   if (count == 0) return SAILOR_OK;
-  if (!d_desc || !d_pools || stride < 1) return SAILOR_EINVAL;
+  if (!d_desc || !d_pools || stride < 1 || (d_tps && tps_stride < 1)) return SAILOR_EINVAL;
   if (pl->dev.mixed || pl->dev.ZGr > kSearchMaxPools) return SAILOR_EINVAL;
   if (count > (uint64_t)0x7fffffff) return SAILOR_ERANGE;
   if (constraint && constraint->has_bound && std::isnan(constraint->bound)) return SAILOR_EINVAL;
@@ -1557,6 +1558,7 @@ sailor_status sailor_eval_replica_placements(sailor_plan *pl, uint64_t count, co
   if (rc != SAILOR_OK) return rc;
   ReplicaArgs a{};
   a.count = count; a.desc = d_desc; a.pools = d_pools; a.stride = stride;
+  a.tps = d_tps; a.tps_stride = tps_stride;
   a.pps = pl->d_search_pps; a.n_pp = (int)pl->search_pps.size();
   a.objective = (int)objective;
   a.has_bound = (constraint && constraint->has_bound) ? 1 : 0;

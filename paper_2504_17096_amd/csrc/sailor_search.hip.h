@@ -928,6 +928,8 @@ struct ReplicaArgs {
   const int32_t *desc;    // [count][5] pp index, partition, tp index, dp index, mb index
   const int32_t *pools;   // [count][stride]: the pool of replica r of stage i at i * D + r
   uint64_t stride;
+  const int32_t *tps;     // optional, [count][tps_stride]: TP index of every stage (else the descriptor's)
+  uint32_t tps_stride;
   const SearchPP *pps;
   int n_pp;
   int objective, has_bound;
@@ -972,20 +974,24 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_replicas(DevPlan pl, 
   const int P = valid ? a.pps[ip].P : 0;
   const int64_t D = valid ? (int64_t)pl.dpv[id] : 0;
   if (valid && (D > kReplicaMaxDegree || (uint64_t)P * (uint64_t)D > a.stride)) valid = false;
+  if (valid && a.tps && (uint32_t)P > a.tps_stride) valid = false;
   const int32_t *pools = a.pools + ci * a.stride;
+  const int32_t *const tps = a.tps ? a.tps + ci * a.tps_stride : nullptr;
   int *cnt = s_cnt[wv];
   if (valid) {
     for (int p = lane; p < kSearchMaxPools; p += 64) cnt[p] = 0;
     bool bad = false;
     for (int64_t k = lane; k < (int64_t)P * D; k += 64)
       if (pools[k] < 0 || pools[k] >= ZG) bad = true;
+    if (tps)
+      for (int i = lane; i < P; i += 64)
+        if (tps[i] < 0 || tps[i] >= TP) bad = true;
     if (__builtin_amdgcn_ballot_w64(bad) != 0) valid = false;
   }
   if (valid) {
     mask = 0;
     const uint32_t rs = a.pps[ip].rs0 + (uint32_t)q * (uint32_t)P;
     const int64_t nb = pl.nb[im * DP + id];
-    const int64_t tp = pl.tpv[it];
     if (nb == 0) {
       mask = 4u;
     } else {
@@ -998,9 +1004,11 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_replicas(DevPlan pl, 
         double total = 0.0, slowest = 0.0;
         for (int i = 0; i < P; ++i) {
           const int p = pools[(int64_t)i * D + r], g = p % G, z = p / G;
+          const int ti = tps ? tps[i] : it;  // the stage's TP index and degree
+          const int64_t tp = pl.tpv[ti];
           atomicAdd(&cnt[p], (int)tp);  // GPUs the pool gives
           const size_t si = (size_t)rs + i;
-          const uint64_t bytes = stage_bytes_of(pl.st_params[si], pl.st_n[si], pl.bpp, i, P, (int)tp, nb, pl.act[im * TP + it]);
+          const uint64_t bytes = stage_bytes_of(pl.st_params[si], pl.st_n[si], pl.bpp, i, P, (int)tp, nb, pl.act[im * TP + ti]);
           const uint64_t m = bytes + pl.res[g];
           if (m > pl.cap[g]) oom = 1u;
           if (tp > pl.node[g]) h1 = 1u;
@@ -1013,10 +1021,10 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_replicas(DevPlan pl, 
               traffic += (double)nb * p2p * (pl.egress[z * Z + zn] + pl.egress[zn * Z + z]);
           }
           if (i > 0) x += p2p / link_bw(pl, z, pools[(int64_t)(i - 1) * D + r] / G, p2p);
-          const double ts = pl.st_c[((si * G + g) * MB + im) * TP + it] + x;
+          const double ts = pl.st_c[((si * G + g) * MB + im) * TP + ti] + x;
           total += ts;
           slowest = fmax(slowest, ts);
-          t_upd = fmax(t_upd, pl.st_u[(si * G + g) * TP + it]);
+          t_upd = fmax(t_upd, pl.st_u[(si * G + g) * TP + ti]);
           rent += (double)tp * pl.price[g];
         }
         t_pipe = fmax(t_pipe, total + (double)(nb - 1) * slowest);
@@ -1025,7 +1033,8 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_replicas(DevPlan pl, 
       if (D > 1)
         for (int i = 0; i < P; ++i) {  // uniform
           const uint64_t params = pl.st_params[rs + i];
-          const uint64_t shard = (params + (uint64_t)tp - 1) / (uint64_t)tp;
+          const uint64_t tp = (uint64_t)pl.tpv[tps ? tps[i] : it];
+          const uint64_t shard = (params + tp - 1) / tp;
           const double buffer = (double)shard * (double)pl.gb;
           const double ring_bytes = 2.0 * (double)(D - 1) / (double)D * buffer;
           double link = __builtin_huge_val();

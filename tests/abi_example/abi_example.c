@@ -171,7 +171,7 @@ int main(void) {
     CHECK(hipMemcpy(d_rep, h_rep, sizeof(int32_t) * (size_t)sp.pp * (size_t)sp.dp, hipMemcpyHostToDevice) == hipSuccess);
     CHECK(sailor_eval_placements(plan, 1, d_desc, d_pool, NULL, NULL, (uint32_t)sp.pp, SAILOR_MAX_THROUGHPUT, NULL,
                                  d_two, NULL, NULL, NULL, NULL) == SAILOR_OK);
-    CHECK(sailor_eval_replica_placements(plan, 1, d_desc, d_rep, (uint64_t)sp.pp * (uint64_t)sp.dp,
+    CHECK(sailor_eval_replica_placements(plan, 1, d_desc, d_rep, (uint64_t)sp.pp * (uint64_t)sp.dp, NULL, 0,
                                          SAILOR_MAX_THROUGHPUT, NULL, d_two + 1, NULL, NULL, NULL, NULL) == SAILOR_OK);
     CHECK(hipDeviceSynchronize() == hipSuccess);
     CHECK(hipMemcpy(h_two, d_two, sizeof h_two, hipMemcpyDeviceToHost) == hipSuccess);

@@ -727,6 +727,79 @@ def test_placements_with_a_pool_per_replica_match_the_oracle(torch_cuda, make):
         plan.destroy()
 
 
+@pytest.mark.parametrize("make", [
+    lambda: _tiny(1), lambda: _tiny(2, n_types=3, n_zones=3), lambda: W.config2(),
+    lambda: (lambda p: p.with_bw_poly(W.bandwidth_poly(p)))(_tiny(4, n_zones=3)),
+])
+def test_placements_with_a_pool_per_replica_and_a_tp_per_stage_match_the_oracle(torch_cuda, make):
+    # the plan tuple in full (Sec. 4.2): every replica its (GPU type, zone), every stage its TP degree
+    prob = make()
+    plan, orc = _plan(prob), Oracle(prob)
+    rng = np.random.default_rng(23)
+    torch = torch_cuda
+    try:
+        n = 1200
+        desc, pools, stride = random_replica_placements(prob, rng, n)
+        P_max = int(max(prob.pp_values))
+        tps = np.zeros((n, P_max + 1), np.int32)
+        for i in range(n):
+            P = int(prob.pp_values[desc[i, 0]])
+            cuts = np.sort(rng.integers(0, P + 1, int(rng.integers(0, 3))))
+            tps[i, :P] = rng.integers(0, len(prob.tp_values), len(cuts) + 1)[np.searchsorted(cuts, np.arange(P), side="right")]
+        dev = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to("cuda:0")
+        d_desc, d_pools, d_tps = dev(desc), dev(pools), dev(tps)
+
+        def run(d_t, objective=MAX_THROUGHPUT, bound=None, cnt=n, descs=d_desc, pls=d_pools, t_stride=P_max + 1):
+            t = torch.empty(cnt, dtype=torch.float64, device="cuda:0")
+            c = torch.empty(cnt, dtype=torch.float64, device="cuda:0")
+            m = torch.empty(cnt, dtype=torch.int64, device="cuda:0")
+            k = torch.empty(cnt, dtype=torch.int32, device="cuda:0")
+            plan.eval_replica_placements(cnt, descs, pls, stride, objective, bound, t, c, m, k,
+                                         stream=torch.cuda.current_stream().cuda_stream, d_tps=d_t,
+                                         tps_stride=t_stride if d_t is not None else 0)
+            torch.cuda.synchronize()
+            return (t.cpu().numpy(), c.cpu().numpy(), m.cpu().numpy().view(np.uint64),
+                    k.cpu().numpy().view(np.uint32))
+
+        for objective, bound in ((MAX_THROUGHPUT, None), (MIN_COST, 0.7), (MAX_THROUGHPUT, 0.05)):
+            t, c, m, k = run(d_tps, objective, bound)
+            mixed = 0
+            for i in range(n):
+                P, D = int(prob.pp_values[desc[i, 0]]), int(prob.dp_values[desc[i, 3]])
+                grid = pools[i, :P * D].reshape(P, D)
+                e = orc.eval_replica_assignment_tp(desc[i, 0], desc[i, 1], desc[i, 3], desc[i, 4], tps[i, :P],
+                                                   grid, objective, bound)
+                tight = bound is not None and np.isfinite(e.iter_time) and abs(
+                    (e.cost if objective == MAX_THROUGHPUT else 1.0 / e.iter_time) / bound - 1.0) < 1e-9
+                if not tight:
+                    assert k[i] == e.mask, (i, desc[i], grid, tps[i, :P])
+                assert m[i] == e.peak_mem
+                if np.isinf(e.iter_time):
+                    assert np.isinf(t[i]) and np.isinf(c[i])
+                else:
+                    assert t[i] == pytest.approx(e.iter_time, rel=1e-12)
+                    assert c[i] == pytest.approx(e.cost, rel=1e-12)
+                # (times and costs are compared whether or not the plan is valid)
+                mixed += np.isfinite(e.iter_time) and len(set(tps[i, :P])) > 1 and \
+                    any(len(set(row)) > 1 for row in grid)
+            if bound is None:
+                assert mixed > 30
+        # the descriptor's degree for every stage: the call without the array, bit for bit
+        same = dev(np.repeat(desc[:, 2:3], P_max + 1, axis=1))
+        assert all(np.array_equal(x, y) for x, y in zip(run(None), run(same)))
+        # a degree out of range; fewer degrees than stages
+        bad = tps[:2].copy()
+        bad[1, 0] = len(prob.tp_values)
+        k = run(dev(bad), cnt=2, descs=dev(desc[:2]), pls=dev(pools[:2]))[3]
+        assert k[1] == 0xFFFFFFFF and k[0] != 0xFFFFFFFF
+        P0 = int(prob.pp_values[desc[0, 0]])
+        if P0 > 1:
+            k = run(dev(tps[:1, :P0 - 1]), cnt=1, descs=dev(desc[:1]), pls=dev(pools[:1]), t_stride=P0 - 1)[3]
+            assert k[0] == 0xFFFFFFFF
+    finally:
+        plan.destroy()
+
+
 # ---- the limits of the search: 64 pools, 255 stages, nothing to evaluate ----------------------
 
 def test_search_at_its_limits(torch_cuda):
