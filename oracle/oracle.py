@@ -175,6 +175,9 @@ def _load():
         lib.so_search_prefix_bound_tp.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                                   C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_double),
                                                   C.POINTER(C.c_double)]
+        lib.so_search_prefix_bound_split_tp.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+                                                        C.POINTER(C.c_double), C.POINTER(C.c_double)]
         lib.so_search_beam.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, C.POINTER(_SearchOpts),
                                        C.POINTER(_SearchResult)]
         lib.so_search_prefix_bound.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
@@ -466,6 +469,18 @@ class Oracle:
         t, c = C.c_double(), C.c_double()
         rc = self._lib.so_search_prefix_bound_tp(self._ctx, pp_idx, partition, dp_idx, mb_idx, tt.ctypes.data,
                                                  a.ctypes.data, n_placed, objective, C.byref(t), C.byref(c))
+        return None if rc != 0 else (t.value, c.value)
+
+    def prefix_bound_split_tp(self, pp_idx: int, partition: int, dp_idx: int, mb_idx: int, tps, pools_a,
+                              pools_b, n_placed: int, objective: int = MAX_THROUGHPUT):
+        """prefix_bound for a placement with two pools and a TP index per stage."""
+        a = np.ascontiguousarray(pools_a, dtype=np.int32)
+        b = np.ascontiguousarray(pools_b, dtype=np.int32)
+        tt = np.ascontiguousarray(tps, dtype=np.int32)
+        t, c = C.c_double(), C.c_double()
+        rc = self._lib.so_search_prefix_bound_split_tp(self._ctx, pp_idx, partition, dp_idx, mb_idx,
+                                                       tt.ctypes.data, a.ctypes.data, b.ctypes.data, n_placed,
+                                                       objective, C.byref(t), C.byref(c))
         return None if rc != 0 else (t.value, c.value)
 
     def best(self, objective: int = MAX_THROUGHPUT, bound: Optional[float] = None,

@@ -229,6 +229,9 @@ int so_search_prefix_bound(const so_ctx *c, int pp_idx, int partition, int dp_id
 int so_search_prefix_bound_tp(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
                               const int32_t *tp_idx, const int32_t *pools, int n_placed, int objective,
                               double *lb_time, double *lb_cost);
+int so_search_prefix_bound_split_tp(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                                    const int32_t *tp_idx, const int32_t *pools_a, const int32_t *pools_b,
+                                    int n_placed, int objective, double *lb_time, double *lb_cost);
 
 #ifdef __cplusplus
 }

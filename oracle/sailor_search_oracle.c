@@ -84,6 +84,9 @@ typedef struct {
   double dol3[16][8];
   uint8_t ok3[SS_MAX_STAGES][16][8]; /* the stage fits the type's memory and node at this degree */
   int cap_gpus[SS_MAX_POOLS];        /* GPUs one replica can take from a pool: avail / D */
+  /* ... and two pools per stage as well */
+  double ring3[SS_MAX_STAGES][8];    /* bytes the stage's ring all-reduce moves over every link, per TP index */
+  int cap_half_gpus[SS_MAX_POOLS];   /* GPUs of one replica, counted once per half of a stage: 2 avail / D */
   /* cheapest admissible choice of the stages behind stage i */
   double Ssum[SS_MAX_STAGES], Smax[SS_MAX_STAGES], Ssync[SS_MAX_STAGES], Supd[SS_MAX_STAGES],
       Sdol[SS_MAX_STAGES];
@@ -379,14 +382,21 @@ static int sub_setup_tp(const so_problem *p, ss_sub *s, int pp_idx, int partitio
   s->p2p = (double)p->p2p_bytes[mb_idx];
   const int P = s->P, G = s->G, Z = s->Z;
   const int32_t *nl = layers_of(p, pp_idx, partition);
-  for (int a = 0; a < s->ZG; ++a) s->cap_gpus[a] = (int)((int64_t)p->avail[a] / s->D);
+  for (int a = 0; a < s->ZG; ++a) {
+    s->cap_gpus[a] = (int)((int64_t)p->avail[a] / s->D);
+    s->cap_half_gpus[a] = (int)(2 * (int64_t)p->avail[a] / s->D);
+  }
+  for (int g = 0; g < G; ++g) s->price[g] = p->price_per_hour[g];
   for (int z = 0; z < Z; ++z)
     for (int y = 0; y < Z; ++y) {
       s->xfer[z][y] = s->p2p / p->bandwidth[(size_t)z * Z + y];
-      s->comm[z][y] = 0.0;
+      s->bw[z][y] = p->bandwidth[(size_t)z * Z + y];
+      s->comm[z][y] = s->comm_half[z][y] = s->ring_price[z][y] = 0.0;
       if (p->egress_per_byte && z != y) {
         const double both = p->egress_per_byte[(size_t)z * Z + y] + p->egress_per_byte[(size_t)y * Z + z];
         s->comm[z][y] = (double)s->Nb * (double)s->D * s->p2p * both;
+        s->comm_half[z][y] = (double)s->Nb * (0.5 * (double)s->D) * s->p2p * both;
+        s->ring_price[z][y] = both;
       }
     }
   for (int g = 0; g < G; ++g)
@@ -405,6 +415,9 @@ static int sub_setup_tp(const so_problem *p, ss_sub *s, int pp_idx, int partitio
       const uint64_t shard = (params + (uint64_t)s->tpv[t] - 1) / (uint64_t)s->tpv[t];
       const uint64_t bytes = shard * (uint64_t)p->bytes_per_param +
                              (uint64_t)alive * (uint64_t)nl[i] * p->act_store_bytes[(size_t)mb_idx * p->n_tp + t];
+      s->ring3[i][t] = 0.0;
+      if (s->D > 1)
+        s->ring3[i][t] = 2.0 * (double)(s->D - 1) / (double)s->D * ((double)shard * (double)p->grad_bytes_per_param);
       int fits_some = 0;
       for (int g = 0; g < G; ++g) {
         s->c3[i][g][t] = time_sum(p, p->t_fwd, g, mb_idx, t, first, nl[i]) + time_sum(p, p->t_bwd, g, mb_idx, t, first, nl[i]);
@@ -481,6 +494,82 @@ static int extend_tp(const ss_sub *s, int i, const ss_state *par, int a, int t, 
   return 1;
 }
 
+/* ---- two pools and a TP degree per stage: a choice is (pool a, pool b, TP index t); both halves
+ * of the stage run at the degree, a pool's quota counts the GPUs of one replica once per half ---- */
+
+static int admissible2_tp(const ss_sub *s, int j, const uint16_t *cnt, int a, int b, int t) {
+  if (!s->ok3[j][a % s->G][t] || !s->ok3[j][b % s->G][t]) return 0;
+  const int width = s->tpv[t];
+  if (a == b) return cnt[a] + 2 * width <= s->cap_half_gpus[a];
+  if (s->D % 2 != 0) return 0; /* D replicas cannot be halved */
+  return cnt[a] + width <= s->cap_half_gpus[a] && cnt[b] + width <= s->cap_half_gpus[b];
+}
+
+/* what stage j costs on the pools (a, b) at TP index t by itself */
+static void stage_terms2_tp(const ss_sub *s, int j, int a, int b, int t, double *sync, double *upd,
+                            double *dol, double *ring_cost) {
+  const int ga = a % s->G, za = a / s->G, gb = b % s->G, zb = b / s->G;
+  double link = s->bw[za][za];
+  if (zb != za) link = fmin(fmin(link, s->bw[zb][zb]), fmin(s->bw[za][zb], s->bw[zb][za]));
+  *sync = s->ring3[j][t] / link;
+  *upd = fmax(s->upd3[j][ga][t], s->upd3[j][gb][t]);
+  *dol = (double)(s->D * s->tpv[t]) * (0.5 * (s->price[ga] + s->price[gb]));
+  *ring_cost = zb != za ? s->ring3[j][t] * s->ring_price[za][zb] : 0.0;
+}
+
+static int first_state2_tp(const ss_sub *s, int a, int b, int t, int objective, ss_state *st) {
+  memset(st, 0, sizeof *st);
+  if (!admissible2_tp(s, 0, st->cnt, a, b, t)) return 0;
+  double sync, upd, dol, ring;
+  stage_terms2_tp(s, 0, a, b, t, &sync, &upd, &dol, &ring);
+  st->c_open = s->c3[0][a % s->G][t];
+  st->c_open_b = s->c3[0][b % s->G][t];
+  st->msync = sync; st->mupd = upd; st->dol = dol; st->comm = ring;
+  st->cnt[a] = (uint16_t)(st->cnt[a] + s->tpv[t]);
+  st->cnt[b] = (uint16_t)(st->cnt[b] + s->tpv[t]);
+  st->pool = (uint8_t)a; st->pool_b = (uint8_t)b; st->tpi = (uint8_t)t;
+  st->runs = 1;
+  st->path[0] = (uint8_t)a; st->path_b[0] = (uint8_t)b; st->path_t[0] = (uint8_t)t;
+  bounds2(s, 0, st, objective);
+  return 1;
+}
+
+/* stage i + 1 behind the state par; a run ends where a pool or the degree changes */
+static int extend2_tp(const ss_sub *s, int i, const ss_state *par, int a, int b, int t, int max_runs,
+                      int objective, ss_state *st) {
+  if (!admissible2_tp(s, i + 1, par->cnt, a, b, t)) return 0;
+  const int runs = par->runs + ((a != par->pool || b != par->pool_b || t != par->tpi) ? 1 : 0);
+  if (max_runs > 0 && runs > max_runs) return 0;
+  const int za = a / s->G, zb = b / s->G, pza = par->pool / s->G, pzb = par->pool_b / s->G;
+  *st = *par;
+  const double ta = par->c_open + (s->xfer[pza][za] + par->xb_open);   /* forward, then backward */
+  const double tb = par->c_open_b + (s->xfer[pzb][zb] + par->xb_open_b);
+  st->sum = par->sum + ta;
+  st->maxt = fmax(par->maxt, ta);
+  st->sum_b = par->sum_b + tb;
+  st->maxt_b = fmax(par->maxt_b, tb);
+  st->c_open = s->c3[i + 1][a % s->G][t];
+  st->c_open_b = s->c3[i + 1][b % s->G][t];
+  st->xb_open = s->xfer[za][pza];
+  st->xb_open_b = s->xfer[zb][pzb];
+  double sync, upd, dol, ring;
+  stage_terms2_tp(s, i + 1, a, b, t, &sync, &upd, &dol, &ring);
+  st->msync = fmax(par->msync, sync);
+  st->mupd = fmax(par->mupd, upd);
+  st->dol = par->dol + dol;
+  double comm = par->comm;
+  if (pza != za) comm += s->comm_half[pza][za];
+  if (pzb != zb) comm += s->comm_half[pzb][zb];
+  st->comm = comm + ring;
+  st->cnt[a] = (uint16_t)(st->cnt[a] + s->tpv[t]);
+  st->cnt[b] = (uint16_t)(st->cnt[b] + s->tpv[t]);
+  st->pool = (uint8_t)a; st->pool_b = (uint8_t)b; st->tpi = (uint8_t)t;
+  st->runs = (uint8_t)runs;
+  st->path[i + 1] = (uint8_t)a; st->path_b[i + 1] = (uint8_t)b; st->path_t[i + 1] = (uint8_t)t;
+  bounds2(s, i + 1, st, objective);
+  return 1;
+}
+
 typedef struct { double key; uint32_t id; uint32_t pos; } ss_order; /* id: generation order; pos: where it is stored */
 
 static int by_key_then_id(const void *x, const void *y) {
@@ -513,6 +602,11 @@ static void take_tp(so_search_result *out, const ss_sub *s, const ss_state *st) 
   for (int i = 0; i < s->P; ++i) out->tps[i] = st->path_t[i];
 }
 
+static void take2_tp(so_search_result *out, const ss_sub *s, const ss_state *st) {
+  take_tp(out, s, st);
+  for (int i = 0; i < s->P; ++i) out->pools_b[i] = st->path_b[i];
+}
+
 int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
                    const so_search_opts *opt, so_search_result *out) {
   const so_problem *p = so_problem_of(c);
@@ -521,9 +615,10 @@ int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
   if (p->n_types > 16 || p->n_zones > 16 || p->n_types * p->n_zones > SS_MAX_POOLS) return -1;
   const int W = opt->beam_width, ZG = p->n_types * p->n_zones;
   const int split = opt->allow_split ? 1 : 0, stp = opt->stage_tp ? 1 : 0, NT = p->n_tp;
-  if (split && stp) return -1;
-  /* choices per stage: a pool; a pair (a, b) = a * ZG + b; a pool and a TP index (a, t) = a * NT + t */
-  const int NCH = split ? ZG * ZG : (stp ? ZG * NT : ZG);
+  const int both = split && stp;
+  /* choices per stage: a pool; a pair (a, b) = a * ZG + b; a pool and a TP index (a, t) = a * NT + t;
+   * a pair and a TP index (a, b, t) = (a * ZG + b) * NT + t */
+  const int NCH = both ? ZG * ZG * NT : split ? ZG * ZG : (stp ? ZG * NT : ZG);
   /* room for a frontier of `cap` placements and its cap * NCH extensions; grows with the
    * frontier (a beam width far beyond what a problem can fill costs nothing) */
   size_t cap = (size_t)(W < 1024 ? W : 1024);
@@ -542,7 +637,8 @@ int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
             /* level 0, then one level per further stage */
             int n = 0, n_all = 0;
             for (int a = 0; a < NCH; ++a)
-              if (split ? first_state2(s, a / ZG, a % ZG, objective, &all[n_all])
+              if (both    ? first_state2_tp(s, a / NT / ZG, a / NT % ZG, a % NT, objective, &all[n_all])
+                  : split ? first_state2(s, a / ZG, a % ZG, objective, &all[n_all])
                   : stp ? first_state_tp(s, a / NT, a % NT, objective, &all[n_all])
                         : first_state(s, a, objective, &all[n_all])) {
                 out->expanded += 1;
@@ -559,7 +655,8 @@ int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
                 for (int k = 0; k < n_all; ++k)
                   if (bi < 0 || by_key_then_id(&ord[k], &ord[bi]) < 0) bi = k;
                 if (bi >= 0 && (!out->found || all[bi].lb_key < out->key)) {
-                  if (split) take2(out, s, &all[bi]);
+                  if (both) take2_tp(out, s, &all[bi]);
+                  else if (split) take2(out, s, &all[bi]);
                   else if (stp) take_tp(out, s, &all[bi]);
                   else take(out, s, &all[bi]);
                 }
@@ -593,7 +690,8 @@ int so_search_beam(const so_ctx *c, int objective, int has_bound, double bound,
               for (int r = 0; r < n; ++r)
                 for (int a = 0; a < NCH; ++a) {
                   ss_state *st = &all[n_all];
-                  if (!(split ? extend2(s, i, &cur[r], a / ZG, a % ZG, opt->max_runs, objective, st)
+                  if (!(both    ? extend2_tp(s, i, &cur[r], a / NT / ZG, a / NT % ZG, a % NT, opt->max_runs, objective, st)
+                        : split ? extend2(s, i, &cur[r], a / ZG, a % ZG, opt->max_runs, objective, st)
                         : stp ? extend_tp(s, i, &cur[r], a / NT, a % NT, opt->max_runs, objective, st)
                               : extend(s, i, &cur[r], a, opt->max_runs, objective, st)))
                     continue;
@@ -671,12 +769,55 @@ static void place_tp(const so_ctx *c, const so_problem *p, int ip, int q, int id
     }
 }
 
+/* the same with two pools and a TP index per stage */
+static void place2_tp(const so_ctx *c, const so_problem *p, int ip, int q, int id, int im, int i, int runs,
+                      int max_runs, int32_t *pools, int32_t *pools_b, int32_t *tps, int objective,
+                      int has_bound, double bound, so_search_result *out) {
+  const int P = p->pp_values[ip], ZG = p->n_types * p->n_zones;
+  if (i == P) {
+    so_eval e;
+    out->expanded += 1;
+    if (so_eval_split_assignment_tp(c, ip, q, id, im, tps, pools, pools_b, objective, has_bound, bound, &e) != 0)
+      return;
+    if (e.mask != 0) return;
+    const double key = objective == SO_MAX_THROUGHPUT ? e.iter_time : e.cost;
+    if (out->found && !(key < out->key)) return; /* the first of equal keys stays */
+    out->found = 1;
+    out->pp_idx = ip; out->partition = q; out->tp_idx = tps[0]; out->dp_idx = id; out->mb_idx = im;
+    out->pp = P; out->key = key; out->iter_time = e.iter_time; out->cost = e.cost;
+    for (int k = 0; k < P; ++k) { out->pools[k] = pools[k]; out->pools_b[k] = pools_b[k]; out->tps[k] = tps[k]; }
+    return;
+  }
+  for (int a = 0; a < ZG; ++a)
+    for (int b = 0; b < ZG; ++b)
+      for (int t = 0; t < p->n_tp; ++t) {
+        const int r = (i == 0) ? 1
+                               : runs + ((a != pools[i - 1] || b != pools_b[i - 1] || t != tps[i - 1]) ? 1 : 0);
+        if (max_runs > 0 && r > max_runs) continue;
+        pools[i] = a;
+        pools_b[i] = b;
+        tps[i] = t;
+        place2_tp(c, p, ip, q, id, im, i + 1, r, max_runs, pools, pools_b, tps, objective, has_bound, bound, out);
+      }
+}
+
 int so_search_exhaustive(const so_ctx *c, int objective, int has_bound, double bound, int max_runs,
                          int allow_split, int stage_tp, so_search_result *out) {
   const so_problem *p = so_problem_of(c);
   memset(out, 0, sizeof *out);
-  if (p->mixed_types || (allow_split && stage_tp)) return -1;
+  if (p->mixed_types) return -1;
   int32_t pools[SO_SEARCH_MAX_STAGES], pools_b[SO_SEARCH_MAX_STAGES];
+  if (allow_split && stage_tp) {
+    int32_t tps[SO_SEARCH_MAX_STAGES];
+    for (int ip = 0; ip < p->n_pp; ++ip) {
+      if (p->pp_values[ip] > SS_MAX_STAGES) continue;
+      for (int q = 0; q < p->n_partitions[ip]; ++q)
+        for (int id = 0; id < p->n_dp; ++id)
+          for (int im = 0; im < p->n_mb; ++im)
+            place2_tp(c, p, ip, q, id, im, 0, 0, max_runs, pools, pools_b, tps, objective, has_bound, bound, out);
+    }
+    return 0;
+  }
   if (stage_tp) {
     for (int ip = 0; ip < p->n_pp; ++ip) {
       if (p->pp_values[ip] > SS_MAX_STAGES) continue;
@@ -736,6 +877,30 @@ int so_search_prefix_bound_tp(const so_ctx *c, int pp_idx, int partition, int dp
     for (int i = 0; i + 1 < n_placed && rc == 0; ++i) {
       if (tp_idx[i + 1] < 0 || tp_idx[i + 1] >= s->n_tp ||
           !extend_tp(s, i, &a, pools[i + 1], tp_idx[i + 1], 0, objective, &b))
+        rc = -1;
+      a = b;
+    }
+    if (rc == 0) { *lb_time = a.lb_T; *lb_cost = a.lb_C; }
+  }
+  free(s);
+  return rc;
+}
+
+int so_search_prefix_bound_split_tp(const so_ctx *c, int pp_idx, int partition, int dp_idx, int mb_idx,
+                                    const int32_t *tp_idx, const int32_t *pools_a, const int32_t *pools_b,
+                                    int n_placed, int objective, double *lb_time, double *lb_cost) {
+  const so_problem *p = so_problem_of(c);
+  if (p->mixed_types || p->n_bw_coef > 0) return -1;
+  ss_sub *s = (ss_sub *)malloc(sizeof(ss_sub));
+  ss_state a, b;
+  int rc = -1;
+  if (s && sub_setup_tp(p, s, pp_idx, partition, dp_idx, mb_idx) && n_placed >= 1 && n_placed <= s->P &&
+      tp_idx[0] >= 0 && tp_idx[0] < s->n_tp &&
+      first_state2_tp(s, pools_a[0], pools_b[0], tp_idx[0], objective, &a)) {
+    rc = 0;
+    for (int i = 0; i + 1 < n_placed && rc == 0; ++i) {
+      if (tp_idx[i + 1] < 0 || tp_idx[i + 1] >= s->n_tp ||
+          !extend2_tp(s, i, &a, pools_a[i + 1], pools_b[i + 1], tp_idx[i + 1], 0, objective, &b))
         rc = -1;
       a = b;
     }

@@ -71,6 +71,14 @@ MUTANTS = [
     ("test_oracle_search.py", "(a != par->pool || t != par->tpi) ? 1 : 0", "(a != par->pool) ? 1 : 0"),
     ("test_oracle_search.py", "tp_of[i] = p->tp_values[tp_idx[i]];", "tp_of[i] = p->tp_values[tp_idx[0]];",
      "sailor_oracle.c"),
+    # two pools and a TP degree per stage: a stage on one pool counted once, the first pool's price
+    # for both halves, runs that ignore the degree
+    ("test_oracle_search.py", "if (a == b) return cnt[a] + 2 * width <= s->cap_half_gpus[a];",
+     "if (a == b) return cnt[a] + width <= s->cap_half_gpus[a];"),
+    ("test_oracle_search.py", "*dol = (double)(s->D * s->tpv[t]) * (0.5 * (s->price[ga] + s->price[gb]));",
+     "*dol = (double)(s->D * s->tpv[t]) * s->price[ga];"),
+    ("test_oracle_search.py", "(a != par->pool || b != par->pool_b || t != par->tpi) ? 1 : 0",
+     "(a != par->pool || b != par->pool_b) ? 1 : 0"),
     # a pool per replica: a ring that is not closed, its fastest link, the last pipeline instead of
     # the slowest, replicas counted instead of GPUs, the ring's traffic priced in the wrong direction
     ("test_oracle_replica_placements.py", "(r + 1) % D] / G;", "(r + 1 < D ? r + 1 : r)] / G;"),

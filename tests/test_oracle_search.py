@@ -470,3 +470,132 @@ def test_the_second_pipelines_crossing_is_paid_for():
         # 4 microbatches x 1 MB x one replica over the boundary, both directions' prices, plus the
         # split stage's ring (2 MB over the boundary, both directions' prices), plus the rent
         assert got.cost == pytest.approx(4 * got.iter_time + 4 * 1e6 * 4e-9 + 2e6 * 4e-9, rel=1e-13)
+
+
+# ---- two pools and a TP degree per stage -------------------------------------------------------
+
+def _eval_both(orc, sp, objective):
+    return orc.eval_split_assignment_tp(sp.pp_idx, sp.partition, sp.dp_idx, sp.mb_idx, sp.tps, sp.pools,
+                                        sp.pools_b, objective)
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+def test_the_exhaustive_search_with_two_pools_and_a_tp_per_stage_is_a_plain_enumeration(objective):
+    prob = _tiny(8, n_layers=2, n_types=1, n_zones=2, partitions_per_pp=2)
+    orc = Oracle(prob)
+    n_tp = len(prob.tp_values)
+    best_key, best = None, None
+    order = itertools.product(range(len(prob.pp_values)), range(2), range(len(prob.dp_values)),
+                              range(len(prob.mb_values)))
+    for ip, q, idp, im in order:
+        if q >= prob.n_partitions[ip]:
+            continue
+        P = int(prob.pp_values[ip])
+        for choice in itertools.product(range(2 * 2 * n_tp), repeat=P):   # ((a, b), tp) = divmod(choice, n_tp)
+            pa, pb = [c // n_tp // 2 for c in choice], [c // n_tp % 2 for c in choice]
+            tps = [c % n_tp for c in choice]
+            e = orc.eval_split_assignment_tp(ip, q, idp, im, tps, pa, pb, objective)
+            if e.mask == 0 and (best_key is None or _key(e, objective) < best_key):
+                best_key, best = _key(e, objective), (ip, q, idp, im, tuple(pa), tuple(pb), tuple(tps))
+    got = orc.search_exhaustive(objective, allow_split=True, stage_tp=True)
+    assert got.key == best_key
+    assert (got.pp_idx, got.partition, got.dp_idx, got.mb_idx, got.pools, got.pools_b, got.tps) == best
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+@pytest.mark.parametrize("seed", [101, 102, 103])
+def test_the_beam_with_two_pools_and_a_tp_per_stage_without_a_cut_is_exhaustive(seed, objective):
+    # (pools^2 x degrees) choices per stage
+    prob = _tiny(seed, n_layers=3, n_types=1 + seed % 2, n_zones=2, partitions_per_pp=1)
+    orc = Oracle(prob)
+    want = orc.search_exhaustive(objective, allow_split=True, stage_tp=True)
+    got = orc.search_beam(1 << 22, objective, allow_split=True, stage_tp=True)
+    assert (want is None) == (got is None)
+    if want is None:
+        return
+    assert not got.truncated
+    assert got.key == pytest.approx(want.key, rel=1e-12)
+    e = _eval_both(orc, got, objective)
+    assert e.mask == 0
+    assert e.iter_time == pytest.approx(got.iter_time, rel=1e-12) and e.cost == pytest.approx(got.cost, rel=1e-12)
+    # a superset of either option alone
+    for kw in (dict(allow_split=True), dict(stage_tp=True), dict()):
+        assert got.key <= orc.search_beam(1 << 22, objective, **kw).key * (1 + 1e-12)
+    inc = orc.search_beam(1 << 22, objective, allow_split=True, stage_tp=True,
+                          incumbent=orc.search_beam(1 << 22, objective).key * (1 + 1e-9))
+    assert inc.key == got.key and inc.expanded <= got.expanded
+    other = want.cost if objective == MAX_THROUGHPUT else 1.0 / want.iter_time
+    bound = other * (0.85 if objective == MAX_THROUGHPUT else 1.2) * (1 + 1e-7)
+    a = orc.search_exhaustive(objective, bound, allow_split=True, stage_tp=True)
+    b = orc.search_beam(1 << 22, objective, bound, allow_split=True, stage_tp=True)
+    assert (a is None) == (b is None) and (a is None or b.key == pytest.approx(a.key, rel=1e-12))
+    for runs in (1, 2):
+        a = orc.search_exhaustive(objective, max_runs=runs, allow_split=True, stage_tp=True)
+        b = orc.search_beam(1 << 22, objective, max_runs=runs, allow_split=True, stage_tp=True)
+        assert (a is None) == (b is None) and (a is None or b.key == pytest.approx(a.key, rel=1e-12))
+
+
+def test_with_one_degree_or_one_pool_the_combined_search_is_the_simpler_one():
+    base = _tiny(111, n_layers=4, n_types=2, n_zones=2)
+    from dataclasses import replace
+    one = replace(base, tp_values=base.tp_values[1:2], t_fwd=base.t_fwd[:, :, 1:2], t_bwd=base.t_bwd[:, :, 1:2],
+                  t_upd=base.t_upd[:, 1:2], act_store_bytes=base.act_store_bytes[:, 1:2])
+    orc = Oracle(one)
+    for objective in OBJECTIVES:
+        for width in (2, 16, 1 << 20):
+            a = orc.search_beam(width, objective, allow_split=True)
+            b = orc.search_beam(width, objective, allow_split=True, stage_tp=True)
+            assert (a.pools, a.pools_b, a.key, a.iter_time, a.cost, a.truncated, a.expanded, a.dp_idx, a.mb_idx) == \
+                   (b.pools, b.pools_b, b.key, b.iter_time, b.cost, b.truncated, b.expanded, b.dp_idx, b.mb_idx)
+    # one pool in all: splitting has nothing to choose, the search with a degree per stage remains
+    single = Oracle(_tiny(112, n_layers=4, n_types=1, n_zones=1))
+    for objective in OBJECTIVES:
+        for width in (2, 1 << 20):
+            a = single.search_beam(width, objective, stage_tp=True)
+            b = single.search_beam(width, objective, allow_split=True, stage_tp=True)
+            assert (a.pools, a.tps, a.key, a.iter_time, a.cost, a.truncated, a.dp_idx, a.mb_idx) == \
+                   (b.pools, b.tps, b.key, b.iter_time, b.cost, b.truncated, b.dp_idx, b.mb_idx)
+            assert b.pools_b == b.pools
+
+
+@pytest.mark.parametrize("seed", [121, 122])
+def test_bounds_with_two_pools_and_a_tp_per_stage_never_exceed_the_value_of_a_completion(seed):
+    prob = _tiny(seed, n_layers=6, n_types=2, n_zones=2)
+    orc = Oracle(prob)
+    rng = np.random.default_rng(seed)
+    checked = 0
+    for _ in range(20000):
+        ip = int(rng.integers(0, len(prob.pp_values)))
+        P = int(prob.pp_values[ip])
+        q = int(rng.integers(0, prob.n_partitions[ip]))
+        idp, im = int(rng.integers(0, len(prob.dp_values))), int(rng.integers(0, len(prob.mb_values)))
+        pa = rng.integers(0, 4, P)
+        pb = np.where(rng.random(P) < 0.5, pa, rng.integers(0, 4, P))
+        tps = rng.integers(0, len(prob.tp_values), P)
+        e = orc.eval_split_assignment_tp(ip, q, idp, im, tps, pa, pb)
+        if e.mask != 0:
+            continue
+        last = (0.0, 0.0)
+        for n in range(1, P + 1):
+            lb = orc.prefix_bound_split_tp(ip, q, idp, im, tps, pa, pb, n)
+            assert lb is not None
+            assert lb[0] <= e.iter_time * (1 + 1e-13) and lb[1] <= e.cost * (1 + 1e-13)
+            assert lb[0] >= last[0] * (1 - 1e-13)
+            last = lb
+        assert last[0] == pytest.approx(e.iter_time, rel=1e-13) and last[1] == pytest.approx(e.cost, rel=1e-13)
+        checked += 1
+    assert checked > 100
+
+
+@pytest.mark.parametrize("objective", OBJECTIVES)
+def test_a_narrow_beam_with_two_pools_and_a_tp_per_stage_returns_valid_plans(objective):
+    prob = _tiny(131, n_layers=5, n_types=2, n_zones=2)
+    orc = Oracle(prob)
+    prev = None
+    for width in (1, 4, 32, 512):
+        got = orc.search_beam(width, objective, allow_split=True, stage_tp=True)
+        e = _eval_both(orc, got, objective)
+        assert e.mask == 0 and _key(e, objective) == pytest.approx(got.key, rel=1e-12)
+        if prev is not None:
+            assert got.key <= prev * (1 + 1e-12)
+        prev = got.key
