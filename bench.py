@@ -525,7 +525,10 @@ def main() -> int:
 
     search = {"cfg3": searched(prob5, 64, False), "cfg4": searched(prob, 64, False),
               "cfg3_split": searched(prob5, 32, True), "cfg4_split": searched(prob, 16, True),
-              "cfg3_stage_tp": searched(prob5, 64, False, True), "cfg4_stage_tp": searched(prob, 32, False, True)}
+              "cfg3_stage_tp": searched(prob5, 64, False, True), "cfg4_stage_tp": searched(prob, 32, False, True),
+              # two pools and a TP degree per stage: 12 x 12 x 4 and 20 x 20 x 4 choices per stage
+              "cfg3_split_stage_tp": searched(prob5, 16, True, True),
+              "cfg4_split_stage_tp": searched(prob, 8, True, True)}
 
     # measured ceilings: scalar-per-lane FMA chain, streaming 16-byte stores, and the four
     # output arrays of the per-candidate evaluation written by a kernel that does nothing else

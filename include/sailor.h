@@ -49,8 +49,8 @@
  * two prices.
  *
  * Beyond the enumerated space (further down): sailor_search places the stages of a pipeline one
- * by one -- a pool per stage, optionally a second pool for half of its replicas or a TP degree of
- * its own -- with lower bounds and a beam (Sec. 4.2.1, 4.2.2); sailor_eval_placements and
+ * by one -- a pool per stage, optionally a second pool for half of its replicas, a TP degree of
+ * its own, or both -- with lower bounds and a beam (Sec. 4.2.1, 4.2.2); sailor_eval_placements and
  * sailor_eval_replica_placements run the simulator of Sec. 4.3 on listed plans of that kind, down
  * to a pool per replica of every stage; sailor_simulate_1f1b replays a plan's 1F1B schedule op by op.
  *
@@ -364,7 +364,9 @@ typedef struct {
   int32_t stage_tp;       /* 1: every stage chooses its TP degree too (tp_ij of Sec. 4.2.2, taken
                              per stage): a stage has pools x n_tp choices, TP is no longer part
                              of the sub-problem, a pool's quota counts the GPUs of one replica.
-                             Not together with allow_split */
+                             Together with allow_split a stage chooses (a, b, TP degree): two
+                             (GPU type, zone) tuples and one degree for both halves,
+                             (pools)^2 x n_tp choices */
 } sailor_search_options;
 
 /* A plan with one pool per stage (plan tuple of Sec. 4.2). */
@@ -405,7 +407,8 @@ typedef struct {
  * bounds (the slower counts, Sec. 4.3), and the D tuples of a stage (Sec. 4.2) may lie in two
  * zones; unsplit stages cost what they cost without the option.  With stage_tp a run of the run
  * limit ends where the pool or the degree changes, and "cheapest admissible choice" runs over the
- * (type, TP) pairs that fit.
+ * (type, TP) pairs that fit.  With both, both hold: two kinds of pipeline at the stage's degree,
+ * a pool's quota counting the GPUs of one replica once per half.
  * per_segment_tp only shapes the enumerated space (and the incumbent taken from it); the search
  * does not look at it.  Not for problems with mixed_types or bw_poly, more than 64 pools or 255
  * stages (SAILOR_EINVAL).  Waits for the device.  SAILOR_ENOFEASIBLE (out->found = 0, exact and

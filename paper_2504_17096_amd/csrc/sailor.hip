@@ -1493,7 +1493,7 @@ static sailor_status search_setup(sailor_plan *pl, int beam) {
     pl->search_beam_cap = 0;
     pl->search_wgs = std::min<uint32_t>(pl->n_sub, 2048u);
     pl->search_path_stride = ((uint32_t)pl->dev.P_max + 7u) & ~7u;
-    pl->search_state_stride = kStateBytes + 2 * pl->search_path_stride;
+    pl->search_state_stride = kStateBytes + 3 * pl->search_path_stride;  // pools, second pools, TP indices
     const size_t bytes = (size_t)pl->search_wgs * 2 * (size_t)beam * pl->search_state_stride;
     if (pl->arena.alloc(&pl->search_states, bytes) != hipSuccess) {
       pl->search_states = nullptr;
@@ -1580,7 +1580,6 @@ sailor_status sailor_search(sailor_plan *pl, sailor_objective objective,
   if (opt->use_incumbent == 1 && std::isnan(opt->incumbent)) return SAILOR_EINVAL;
   if (opt->allow_split != 0 && opt->allow_split != 1) return SAILOR_EINVAL;
   if (opt->stage_tp != 0 && opt->stage_tp != 1) return SAILOR_EINVAL;
-  if (opt->allow_split && opt->stage_tp) return SAILOR_EINVAL;
   // plain pools, constant link bandwidths, a pipeline's stages numbered in a byte
   if (pl->dev.mixed || pl->dev.n_bw_coef > 0 || pl->dev.ZGr > kSearchMaxPools ||
       pl->dev.P_max > kSearchMaxStages)
@@ -1625,7 +1624,8 @@ sailor_status sailor_search(sailor_plan *pl, sailor_objective objective,
   a.path_stride = pl->search_path_stride;
   a.results = pl->search_results;
   const unsigned wgs = std::min<uint32_t>(pl->search_wgs, a.n_sub);
-  if (opt->allow_split) k_search_beam<SEARCH_SPLIT><<<wgs, kSearchThreads, 0, st>>>(pl->dev, a);
+  if (opt->allow_split && opt->stage_tp) k_search_beam<SEARCH_SPLIT_TP><<<wgs, kSearchThreads, 0, st>>>(pl->dev, a);
+  else if (opt->allow_split) k_search_beam<SEARCH_SPLIT><<<wgs, kSearchThreads, 0, st>>>(pl->dev, a);
   else if (opt->stage_tp) k_search_beam<SEARCH_STAGE_TP><<<wgs, kSearchThreads, 0, st>>>(pl->dev, a);
   else k_search_beam<SEARCH_PLAIN><<<wgs, kSearchThreads, 0, st>>>(pl->dev, a);
   k_search_pick<<<1, 256, 0, st>>>(pl->search_results, a.n_sub, pl->search_final);

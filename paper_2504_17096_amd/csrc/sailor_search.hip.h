@@ -45,7 +45,7 @@ struct SearchPP {      // one pipeline depth
   uint32_t pad[3];
 };
 
-enum : int { SEARCH_PLAIN = 0, SEARCH_SPLIT = 1, SEARCH_STAGE_TP = 2 };
+enum : int { SEARCH_PLAIN = 0, SEARCH_SPLIT = 1, SEARCH_STAGE_TP = 2, SEARCH_SPLIT_TP = 3 };
 
 struct SState {        // placement of stages 0 .. j; kStateBytes, followed by the paths (a byte per stage)
   double sum;          // times of the closed stages 0 .. j-1
@@ -79,7 +79,7 @@ struct SearchArgs {
   int n_pp;
   uint32_t n_sub;
   uint8_t *states;        // [workgroups][2][W] states of state_stride bytes
-  uint32_t state_stride;  // kStateBytes + two paths of path_stride bytes
+  uint32_t state_stride;  // kStateBytes + three paths of path_stride bytes (pools, second pools, TP indices)
   uint32_t path_stride;   // the deepest pipeline, rounded up to 8
   SubResult *results;     // [n_sub]
 };
@@ -148,22 +148,66 @@ struct SearchTables {  // LDS of a search workgroup: the sub-problem's and the l
   uint32_t l_fit3[kMaxTP];             // bit g: the level's stage fits type g at this degree
   int tpv[kMaxTP];
   int cap_gpus[kSearchMaxPools];       // GPUs one replica can take from a pool
+  // ... and two pools per stage as well
+  double l_ring3[kMaxTP];              // the level's stage's ring bytes at every degree
+  int cap_half_gpus[kSearchMaxPools];  // GPUs of one replica, counted once per half of a stage
+  long long dp;                        // D
 };
 
 struct SAcc {          // what a placement carries besides its pool counts
   double sum, maxt, c_open, xb_open, sum_b, maxt_b, c_open_b, xb_open_b, msync, mupd, dol, comm;
 };
 
-// Stage j on pool a (split stages: half of its replicas on pool b; a TP degree per stage: b is
-// its TP index) behind the placement par (none for j = 0): may it be placed, and what the
-// placement then carries.  The order of the operations is part of the definition: sums in
-// stage order, a closed stage's transfers forward then backward.
+// Stage j on pool a (split stages: half of its replicas on pool b, else b = a) at TP index k (a
+// TP degree per stage; else the sub-problem's) behind the placement par (none for j = 0): may
+// it be placed, and what the placement then carries.  The order of the operations is part of
+// the definition: sums in stage order, a closed stage's transfers forward then backward.
 template <int MODE>
 __device__ __forceinline__ bool search_step(const SearchTables &T, const SState *par, int j, int a, int b,
-                                            int G, int max_runs, SAcc &o, int &runs) {
+                                            int k, int G, int max_runs, SAcc &o, int &runs) {
   constexpr bool SPLIT = MODE == SEARCH_SPLIT;
+  if (MODE == SEARCH_SPLIT_TP) {
+    const int ga = a % G, za = a / G, gb = b % G, zb = b / G, width = T.tpv[k];
+    bool ok = ((T.l_fit3[k] >> ga) & 1u) != 0 && ((T.l_fit3[k] >> gb) & 1u) != 0;
+    const int ca = par ? (int)par->cnt[a] : 0, cb = par ? (int)par->cnt[b] : 0;
+    if (a == b) ok = ok && ca + 2 * width <= T.cap_half_gpus[a];
+    else ok = ok && T.dp_even && ca + width <= T.cap_half_gpus[a] && cb + width <= T.cap_half_gpus[b];
+    runs = par ? par->runs + ((a != par->pool || b != par->pool_b || k != par->tpi) ? 1 : 0) : 1;
+    if (max_runs != 0 && runs > max_runs) ok = false;
+    if (!ok) return false;
+    double link = T.bw[za][za];
+    if (zb != za) link = fmin(fmin(link, T.bw[zb][zb]), fmin(T.bw[za][zb], T.bw[zb][za]));
+    const double sync = T.l_ring3[k] / link;
+    const double upd = fmax(T.l_upd3[ga][k], T.l_upd3[gb][k]);
+    const double dol = (double)(T.dp * (long long)width) * (0.5 * (T.l_price[ga] + T.l_price[gb]));
+    const double ring = zb != za ? T.l_ring3[k] * T.ring_price[za][zb] : 0.0;
+    o.c_open = T.l_c3[ga][k];
+    o.c_open_b = T.l_c3[gb][k];
+    if (!par) {
+      o.sum = o.maxt = o.xb_open = o.sum_b = o.maxt_b = o.xb_open_b = 0.0;
+      o.msync = sync; o.mupd = upd; o.dol = dol; o.comm = ring;
+    } else {
+      const int pza = par->pool / G, pzb = par->pool_b / G;
+      const double ta = par->c_open + (T.xfer[pza][za] + par->xb_open);  // forward, then backward
+      const double tb = par->c_open_b + (T.xfer[pzb][zb] + par->xb_open_b);
+      o.sum = par->sum + ta;
+      o.maxt = fmax(par->maxt, ta);
+      o.sum_b = par->sum_b + tb;
+      o.maxt_b = fmax(par->maxt_b, tb);
+      o.xb_open = T.xfer[za][pza];
+      o.xb_open_b = T.xfer[zb][pzb];
+      o.msync = fmax(par->msync, sync);
+      o.mupd = fmax(par->mupd, upd);
+      o.dol = par->dol + dol;
+      double comm = par->comm;
+      if (pza != za) comm += T.comm_half[pza][za];
+      if (pzb != zb) comm += T.comm_half[pzb][zb];
+      o.comm = comm + ring;
+    }
+    return true;
+  }
   if (MODE == SEARCH_STAGE_TP) {
-    const int g = a % G, z = a / G, t = b;
+    const int g = a % G, z = a / G, t = k;
     bool ok = ((T.l_fit3[t] >> g) & 1u) != 0;
     const int used = par ? (int)par->cnt[a] : 0;
     ok = ok && used + T.tpv[t] <= T.cap_gpus[a];
@@ -254,7 +298,7 @@ __device__ __forceinline__ bool search_step(const SearchTables &T, const SState 
 // of pipeline counts (Sec. 4.3).
 template <int MODE>
 __device__ __forceinline__ SBound search_bound_of(const SearchTables &T, const SAcc &o, int j, double nbm1) {
-  if (MODE != SEARCH_SPLIT)
+  if (MODE != SEARCH_SPLIT && MODE != SEARCH_SPLIT_TP)
     return search_bounds(o.sum, o.maxt, o.c_open, o.xb_open, o.msync, o.mupd, o.dol, o.comm, T.S[0][j],
                          T.S[1][j], T.S[2][j], T.S[3][j], T.S[4][j], nbm1);
   const double ta = o.c_open + o.xb_open, tb = o.c_open_b + o.xb_open_b;
@@ -268,7 +312,9 @@ __device__ __forceinline__ SBound search_bound_of(const SearchTables &T, const S
 
 template <int MODE>
 __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, SearchArgs a) {
-  constexpr bool SPLIT = MODE == SEARCH_SPLIT, STP = MODE == SEARCH_STAGE_TP;
+  constexpr bool BOTH = MODE == SEARCH_SPLIT_TP;
+  constexpr bool SPLIT = MODE == SEARCH_SPLIT || BOTH;     // two pools per stage
+  constexpr bool STP = MODE == SEARCH_STAGE_TP || BOTH;    // a TP degree per stage
   __shared__ SearchTables T;
   __shared__ unsigned long long b_key[kSearchBuf];
   __shared__ uint32_t b_id[kSearchBuf];
@@ -280,9 +326,16 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
   __shared__ unsigned char s_fit3[kMaxTypes][kMaxTP];
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
   const int G = pl.G, Z = pl.Z, ZG = pl.ZGr, MB = pl.MB, TP = pl.TP, DP = pl.DP;
-  // choices per stage: a pool; a pair (a, b) = a * ZG + b; a pool and a TP index (a, t) = a * TP + t
-  const int NCH = SPLIT ? ZG * ZG : (STP ? ZG * TP : ZG);
-  const int CH2 = STP ? TP : ZG;  // a choice c of two parts is (c / CH2, c % CH2)
+  // choices per stage: a pool; a pair (a, b) = a * ZG + b; a pool and a TP index (a, t) = a * TP + t;
+  // a pair and a TP index ((a * ZG + b) * TP + t)
+  const int NCH = BOTH ? ZG * ZG * TP : (SPLIT ? ZG * ZG : (STP ? ZG * TP : ZG));
+  // a choice c -> first pool, second pool (= the first without split stages), TP index
+  auto choice = [&](int c, int it0, int &ca, int &cb, int &ck) {
+    ck = STP ? c % TP : it0;
+    const int pools = STP ? c / TP : c;
+    ca = SPLIT ? pools / ZG : pools;
+    cb = SPLIT ? pools - ca * ZG : ca;
+  };
   uint8_t *const buf0 = a.states + (size_t)blockIdx.x * 2 * a.W * a.state_stride;
   uint8_t *const buf1 = buf0 + (size_t)a.W * a.state_stride;
 
@@ -311,6 +364,7 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
       s_expanded = 0;
       T.dp_even = (D % 2 == 0) ? 1 : 0;
       T.dtp = (double)(D * tp);
+      T.dp = (long long)D;
     }
     __syncthreads();
     if (nb == 0) continue;              // the batch does not divide (uniform)
@@ -336,6 +390,7 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
       T.cap[p] = (int)((int64_t)pl.avail[p] / ((int64_t)tp * D));
       T.cap_half[p] = (int)(2 * (int64_t)pl.avail[p] / ((int64_t)tp * D));
       T.cap_gpus[p] = (int)((int64_t)pl.avail[p] / D);
+      T.cap_half_gpus[p] = (int)(2 * (int64_t)pl.avail[p] / D);
     }
     if (t < TP) T.tpv[t] = pl.tpv[t];
     if (STP) {
@@ -420,17 +475,20 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
           T.l_c3[g][k] = pl.st_c[(((size_t)(rs + j) * G + g) * MB + im) * TP + k];
           T.l_upd3[g][k] = pl.st_u[((size_t)(rs + j) * G + g) * TP + k];
           T.l_dol3[g][k] = (double)(D * tpk) * pl.price[g];
+          if (k == 0) T.l_price[g] = pl.price[g];
           s_fit3[g][k] = (bytes + pl.res[g] <= pl.cap[g] && tpk <= pl.node[g]) ? 1 : 0;
         } else if (t >= 128 && t < 128 + Z * TP) {  // (zone z, TP index k)
           const int z = (t - 128) / TP, k = (t - 128) - z * TP, tpk = pl.tpv[k];
           const uint64_t params = pl.st_params[rs + j];
           const uint64_t shard = (params + (uint64_t)tpk - 1) / (uint64_t)tpk;
-          double sync = 0.0;
+          double sync = 0.0, ring = 0.0;
           if (D > 1) {
             const double grad = (double)shard * (double)pl.gb;
             sync = 2.0 * (double)(D - 1) / (double)D * grad / pl.bw[z * Z + z];
+            ring = 2.0 * (double)(D - 1) / (double)D * grad;
           }
           T.l_sync3[z][k] = sync;
+          if (z == 0) T.l_ring3[k] = ring;
         }
         __syncthreads();
         if (t < TP) {
@@ -474,11 +532,12 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
         unsigned long long kbits = 0;
         if (cand < n_total) {
           const int r = cand / NCH, c = cand - r * NCH;
-          const int pa = (SPLIT || STP) ? c / CH2 : c, pb = (SPLIT || STP) ? c - pa * CH2 : c;
+          int pa, pb, pk;
+          choice(c, it, pa, pb, pk);
           const SState *par = j == 0 ? nullptr : reinterpret_cast<const SState *>(cur + (size_t)r * a.state_stride);
           SAcc o;
           int runs;
-          if (search_step<MODE>(T, par, j, pa, pb, G, a.max_runs, o, runs)) {
+          if (search_step<MODE>(T, par, j, pa, pb, pk, G, a.max_runs, o, runs)) {
             my_expanded += 1;
             const SBound b = search_bound_of<MODE>(T, o, j, nbm1);
             const double key = a.objective == 0 ? b.T : b.C;
@@ -534,23 +593,24 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
           if (key_id_less(s_bk[w], s_bi[w], best_k, best_i)) { best_k = s_bk[w]; best_i = s_bi[w]; }
         if (best_i != ~0u) {  // uniform
           const int r = (int)best_i / NCH, c = (int)best_i - r * NCH;
-          const int pa = (SPLIT || STP) ? c / CH2 : c, pb = (SPLIT || STP) ? c - pa * CH2 : c;
+          int pa, pb, pk;
+          choice(c, it, pa, pb, pk);
           const uint8_t *par_path = cur + (size_t)r * a.state_stride + kStateBytes;
           for (int i = t; i < P - 1; i += blockDim.x) {
             res->pools[i] = par_path[i];
             res->pools_b[i] = SPLIT ? par_path[a.path_stride + i] : par_path[i];
-            res->tps[i] = STP ? par_path[a.path_stride + i] : it;
+            res->tps[i] = STP ? par_path[2 * a.path_stride + i] : it;
           }
           if (t == 0) {
             const SState *par = j == 0 ? nullptr : reinterpret_cast<const SState *>(cur + (size_t)r * a.state_stride);
             SAcc o;
             int runs;
-            search_step<MODE>(T, par, j, pa, pb, G, a.max_runs, o, runs);
+            search_step<MODE>(T, par, j, pa, pb, pk, G, a.max_runs, o, runs);
             const SBound b = search_bound_of<MODE>(T, o, j, nbm1);
             res->pools[P - 1] = pa;
-            res->pools_b[P - 1] = SPLIT ? pb : pa;
-            res->tps[P - 1] = STP ? pb : it;
-            if (STP) res->desc[2] = P > 1 ? (int)par_path[a.path_stride] : pb;  // stage 0's
+            res->pools_b[P - 1] = pb;
+            res->tps[P - 1] = pk;
+            if (STP) res->desc[2] = P > 1 ? (int)par_path[2 * a.path_stride] : pk;  // stage 0's
             res->T = b.T;
             res->C = b.C;
             res->key = a.objective == 0 ? b.T : b.C;
@@ -571,19 +631,21 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
       for (int k = t; k < n_next; k += blockDim.x) {
         const int cand = (int)b_id[k];
         const int r = cand / NCH, c = cand - r * NCH;
-        const int pa = (SPLIT || STP) ? c / CH2 : c, pb = (SPLIT || STP) ? c - pa * CH2 : c;
+        int pa, pb, pk;
+        choice(c, it, pa, pb, pk);
         uint8_t *const out = nxt + (size_t)k * a.state_stride;
         const SState *par = j == 0 ? nullptr : reinterpret_cast<const SState *>(cur + (size_t)r * a.state_stride);
         SAcc o;
         int runs;
-        search_step<MODE>(T, par, j, pa, pb, G, a.max_runs, o, runs);
+        search_step<MODE>(T, par, j, pa, pb, pk, G, a.max_runs, o, runs);
         SState st;
         if (par) {
           st = *par;
           const uint8_t *par_path = cur + (size_t)r * a.state_stride + kStateBytes;
           for (int i = 0; i < j; ++i) {
             out[kStateBytes + i] = par_path[i];
-            if (SPLIT || STP) out[kStateBytes + a.path_stride + i] = par_path[a.path_stride + i];
+            if (SPLIT) out[kStateBytes + a.path_stride + i] = par_path[a.path_stride + i];
+            if (STP) out[kStateBytes + 2 * a.path_stride + i] = par_path[2 * a.path_stride + i];
           }
         } else {
           for (int x = 0; x < kSearchMaxPools; ++x) st.cnt[x] = 0;
@@ -591,8 +653,11 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
         st.sum = o.sum; st.maxt = o.maxt; st.c_open = o.c_open; st.xb_open = o.xb_open;
         st.sum_b = o.sum_b; st.maxt_b = o.maxt_b; st.c_open_b = o.c_open_b; st.xb_open_b = o.xb_open_b;
         st.msync = o.msync; st.mupd = o.mupd; st.dol = o.dol; st.comm = o.comm;
-        if (STP) {
-          st.cnt[pa] = (uint16_t)(st.cnt[pa] + T.tpv[pb]);
+        if (BOTH) {
+          st.cnt[pa] = (uint16_t)(st.cnt[pa] + T.tpv[pk]);
+          st.cnt[pb] = (uint16_t)(st.cnt[pb] + T.tpv[pk]);
+        } else if (STP) {
+          st.cnt[pa] = (uint16_t)(st.cnt[pa] + T.tpv[pk]);
         } else if (!SPLIT) {
           st.cnt[pa] = (uint16_t)(st.cnt[pa] + 1);
         } else {
@@ -600,13 +665,14 @@ __global__ __launch_bounds__(kSearchThreads) void k_search_beam(DevPlan pl, Sear
           st.cnt[pb] = (uint16_t)(st.cnt[pb] + 1);
         }
         st.pool = (uint8_t)pa;
-        st.pool_b = SPLIT ? (uint8_t)pb : (uint8_t)pa;
-        st.tpi = STP ? (uint8_t)pb : (uint8_t)it;
+        st.pool_b = (uint8_t)pb;
+        st.tpi = (uint8_t)pk;
         st.runs = (uint8_t)runs;
         for (int x = 0; x < 4; ++x) st.pad[x] = 0;
         *reinterpret_cast<SState *>(out) = st;
         out[kStateBytes + j] = (uint8_t)pa;
-        if (SPLIT || STP) out[kStateBytes + a.path_stride + j] = (uint8_t)pb;
+        if (SPLIT) out[kStateBytes + a.path_stride + j] = (uint8_t)pb;
+        if (STP) out[kStateBytes + 2 * a.path_stride + j] = (uint8_t)pk;
       }
       n_cur = n_next;
     }
@@ -810,7 +876,8 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl
   if (valid && !a.one && (uint32_t)P > a.pool_stride) valid = false;
   RefineLds &L = lds[wv];
   int *cnt = s_cnt[wv];
-  const bool split = a.one ? a.one->desc[5] == SEARCH_SPLIT : a.pools_b != nullptr;  // stages may split their replicas
+  const bool split = a.one ? (a.one->desc[5] == SEARCH_SPLIT || a.one->desc[5] == SEARCH_SPLIT_TP)
+                           : a.pools_b != nullptr;  // stages may split their replicas
   const int32_t *const tps = a.one ? a.one->tps : (a.tps ? a.tps + ci * a.pool_stride : nullptr);
   if (valid) {
     for (int p = lane; p < kSearchMaxPools; p += 64) cnt[p] = 0;
@@ -836,7 +903,7 @@ __global__ __launch_bounds__(kPlaceWaves * 64) void k_eval_placements(DevPlan pl
       __builtin_amdgcn_wave_barrier();
       eval_split_wave(pl, a.one ? a.one->pools : a.pools + ci * a.pool_stride,
                       a.one ? a.one->pools_b : a.pools_b + ci * a.pool_stride,
-                      a.one ? nullptr : tps, P, rs, it, im, nb, D, L, s_second[wv], cnt, T, C, peak, mask);
+                      tps, P, rs, it, im, nb, D, L, s_second[wv], cnt, T, C, peak, mask);
       if (a.has_bound) {
         if (a.objective == 0) { if (C > a.bound) mask |= 32u; }
         else if (1.0 / T < a.bound) mask |= 32u;
