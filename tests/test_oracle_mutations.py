@@ -12,8 +12,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 SOURCES = ("sailor_oracle.c", "sailor_search_oracle.c", "sailor_oracle.h")
 
+# the pins of the search with a TP degree per stage, and of the one with two pools as well
+TP_PINS = "tp_per_stage or own_tp or two_degrees or one_degree_to_choose"
+BOTH_PINS = "two_pools_and_a_tp or combined_search"
+
 MUTANTS = [
-    # (pin file, text in the oracle's source, replacement[, source file if not the default])
+    # (pin file, text in the oracle's source, replacement[, source file if not the default[, a -k
+    # expression that selects the pins of that part of the file, to keep the run short]])
     ("test_oracle_simulator.py", "(double)(Nb - 1) * max_t", "(double)(Nb) * max_t"),
     ("test_oracle_simulator.py", "2.0 * (double)(D - 1) / (double)D * grad_bytes",
      "2.0 * (double)(D) / (double)D * grad_bytes"),
@@ -63,22 +68,26 @@ MUTANTS = [
     ("test_oracle_search.py", "if (a->key < b->key) return -1;\n  if (a->key > b->key) return 1;",
      "if (a->key < b->key) return 1;\n  if (a->key > b->key) return -1;"),
     ("test_oracle_search.py", "s->Smax[i] = fmax(s->Smax[i + 1], cmin[i + 1]);",
-     "s->Smax[i] = fmax(s->Smax[i + 1], cmin[i]);"),
+     "s->Smax[i] = fmax(s->Smax[i + 1], cmin[i]);", "sailor_search_oracle.c",
+     "bounds_never_exceed or first_bound_is_the_value"),
     # a TP degree per stage: the quota counted in stages instead of GPUs, the rent of the first
     # degree, runs that ignore the degree, every stage evaluated at the first stage's degree
-    ("test_oracle_search.py", "par->cnt[a] + s->tpv[t] > s->cap_gpus[a]", "par->cnt[a] + 1 > s->cap_gpus[a]"),
-    ("test_oracle_search.py", "st->dol = par->dol + s->dol3[g][t];", "st->dol = par->dol + s->dol3[g][0];"),
-    ("test_oracle_search.py", "(a != par->pool || t != par->tpi) ? 1 : 0", "(a != par->pool) ? 1 : 0"),
+    ("test_oracle_search.py", "par->cnt[a] + s->tpv[t] > s->cap_gpus[a]", "par->cnt[a] + 1 > s->cap_gpus[a]",
+     "sailor_search_oracle.c", TP_PINS),
+    ("test_oracle_search.py", "st->dol = par->dol + s->dol3[g][t];", "st->dol = par->dol + s->dol3[g][0];",
+     "sailor_search_oracle.c", TP_PINS),
+    ("test_oracle_search.py", "(a != par->pool || t != par->tpi) ? 1 : 0", "(a != par->pool) ? 1 : 0",
+     "sailor_search_oracle.c", TP_PINS),
     ("test_oracle_search.py", "tp_of[i] = p->tp_values[tp_idx[i]];", "tp_of[i] = p->tp_values[tp_idx[0]];",
-     "sailor_oracle.c"),
+     "sailor_oracle.c", TP_PINS),
     # two pools and a TP degree per stage: a stage on one pool counted once, the first pool's price
     # for both halves, runs that ignore the degree
     ("test_oracle_search.py", "if (a == b) return cnt[a] + 2 * width <= s->cap_half_gpus[a];",
-     "if (a == b) return cnt[a] + width <= s->cap_half_gpus[a];"),
+     "if (a == b) return cnt[a] + width <= s->cap_half_gpus[a];", "sailor_search_oracle.c", BOTH_PINS),
     ("test_oracle_search.py", "*dol = (double)(s->D * s->tpv[t]) * (0.5 * (s->price[ga] + s->price[gb]));",
-     "*dol = (double)(s->D * s->tpv[t]) * s->price[ga];"),
+     "*dol = (double)(s->D * s->tpv[t]) * s->price[ga];", "sailor_search_oracle.c", BOTH_PINS),
     ("test_oracle_search.py", "(a != par->pool || b != par->pool_b || t != par->tpi) ? 1 : 0",
-     "(a != par->pool || b != par->pool_b) ? 1 : 0"),
+     "(a != par->pool || b != par->pool_b) ? 1 : 0", "sailor_search_oracle.c", BOTH_PINS),
     # a pool per replica: a ring that is not closed, its fastest link, the last pipeline instead of
     # the slowest, replicas counted instead of GPUs, the ring's traffic priced in the wrong direction
     ("test_oracle_replica_placements.py", "(r + 1) % D] / G;", "(r + 1 < D ? r + 1 : r)] / G;"),
@@ -100,8 +109,9 @@ def test_a_planted_mistake_fails_its_pins(tmp_path, mutant):
     assert src.count(old) == 1, "the mutation no longer matches the oracle's source"
     (tmp_path / target).write_text(src.replace(old, new))
     env = dict(os.environ, SAILOR_ORACLE_DIR=str(tmp_path))
+    select = ["-k", mutant[4]] if len(mutant) > 4 else []
     run = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", pins), "-x", "-q",
-                          "-p", "no:cacheprovider"], cwd=ROOT, env=env, capture_output=True, text=True)
+                          "-p", "no:cacheprovider"] + select, cwd=ROOT, env=env, capture_output=True, text=True)
     assert run.returncode == 1, "the pins passed on a broken oracle:\n" + run.stdout[-2000:]
     assert " failed" in run.stdout
 
