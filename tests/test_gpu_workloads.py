@@ -386,6 +386,19 @@ def test_third_workload_with_mixed_replica_types(torch_cuda):
             check_topk(plan.topk(64, objective=objective, stream=stream), top, objective)
         base_best = Oracle(base).best(objective=MAX_THROUGHPUT, n_threads=THREADS)
         assert orc.best(objective=MAX_THROUGHPUT, n_threads=THREADS).iter_time <= base_best.iter_time * (1 + 1e-12)
+        # under constraints: pieces ruled out by their bounds (which ignore the availability, and
+        # with it which pairs of types share a real pool), the one pass over the few left alive
+        cheapest = orc.best(objective=MIN_COST, n_threads=THREADS)
+        fastest = orc.best(objective=MAX_THROUGHPUT, n_threads=THREADS)
+        few = []
+        for objective, bound in ((MAX_THROUGHPUT, 1.2 * cheapest.cost), (MAX_THROUGHPUT, 2.5 * cheapest.cost),
+                                 (MIN_COST, 0.6 / fastest.iter_time)):
+            best, top = oracle_best_and_topk(orc, 64, objective, bound)
+            check_topk(plan.topk(64, objective=objective, bound=bound, stream=stream), top, objective, orc, bound)
+            evaluated, total = plan.last_scan()
+            few.append(evaluated <= 128 and evaluated < total)
+            check_result(plan.best_plan(objective=objective, bound=bound, stream=stream), best, orc)
+        assert any(few), few
     finally:
         plan.destroy()
 
