@@ -358,6 +358,13 @@ def test_third_workload_with_link_profiles(torch_cuda):
             check_topk(plan.topk(64, objective=objective, stream=stream), top, objective)
         slower = orc.best(objective=MAX_THROUGHPUT, n_threads=THREADS).iter_time
         assert slower >= Oracle(base).best(objective=MAX_THROUGHPUT, n_threads=THREADS).iter_time
+        # under constraints (the per-piece bounds are taken with the same link profiles)
+        cheapest = orc.best(objective=MIN_COST, n_threads=THREADS).cost
+        for objective, bound in ((MAX_THROUGHPUT, 1.1 * cheapest), (MAX_THROUGHPUT, 1.6 * cheapest),
+                                 (MIN_COST, 0.7 / slower)):
+            best, top = oracle_best_and_topk(orc, 64, objective, bound)
+            check_topk(plan.topk(64, objective=objective, bound=bound, stream=stream), top, objective, orc, bound)
+            check_result(plan.best_plan(objective=objective, bound=bound, stream=stream), best, orc)
     finally:
         plan.destroy()
 
